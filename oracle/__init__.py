@@ -1,0 +1,18 @@
+"""CPU oracle for the SBP hot path.  TEST INFRASTRUCTURE ONLY.
+
+Nothing in the product package may import this.  Only tests, the smoke check
+and the benchmark's cpu_baseline leg call it.  It shares no code with the HIP
+path; it is a plain fp64 write-out of what the paper defines.
+"""
+from .sbp_oracle import (  # noqa: F401
+    GRID_PER_CELL,
+    GRID_SHARED,
+    k_from_ratio,
+    keep_count,
+    sample_indices,
+    inverse_map,
+    forward_cache,
+    backward_linear,
+    backward_dwconv,
+    mix64,
+)

@@ -1,0 +1,189 @@
+"""Plain CPU oracle of the Stochastic-Backpropagation (SBP) hot path.
+
+TEST INFRASTRUCTURE.  Slow, fp64, obviously-correct write-out of what the paper
+defines; it is imported only by tests, the smoke check and the benchmark's
+cpu_baseline leg, never by the product path, and it shares no code with the HIP
+kernels.
+
+What follows the paper and what is this repository's own reading:
+
+* ``backward_linear`` is the definition in the paper's section "Calculation of
+  Linear Layers": the split of the backward pass into kept and dropped index
+  sets (the equation labelled ``eq:backward_fc_sbp``) with every dropped term
+  removed, i.e. dX_drop = 0 and dW = X_keep^T dX_{i+1}^keep.  The paper stores
+  W as [C_in, C_out]; here W is [C_out, C_in] (Y = X W^T + b), so the same
+  quantities read dW = dY_k^T X_k and dX_k = dY_k W.  The paper omits the
+  bias; db = column sum of the kept rows of dY follows from the same split.
+  No 1/r rescaling: the update rule (``eq:sbp_formula``) carries only 1/B,
+  which belongs to the loss.
+* ``backward_dwconv`` is the ordinary convolution backward of the section
+  "Calculation of Convolutional Layers" (``eq:conv_grad_layer_before_sbp``)
+  applied to dY with its dropped positions set to zero, for a depthwise
+  kernel.  dX is dense (the paper's remark (a): dropped inputs still receive
+  gradient from kept neighbours).
+* ``forward_cache`` keeps only the kept rows of the layer input ("only caches a
+  subset of the feature maps").
+* ``sample_indices``: the paper only names "grid-wise mask sampling" and shows a
+  figure.  The reading taken here: tile the H x W map into 2x2 cells and keep
+  k = round(4 r) of the four slots of every cell, drawn from a counter-based
+  integer hash of (seed, stream, sample, cell).  The hash constants and the
+  canonical order of the index list are this repository's own specification:
+  PARITY UNPINNED by the paper for the generator itself (the mixer is pinned to
+  the published SplitMix64 sequence, the structure to the properties the paper
+  states: fixed keep ratio per cell, equal visiting frequency of every
+  position).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+GRID_PER_CELL = 0  # independent draw in every 2x2 cell
+GRID_SHARED = 1    # one slot permutation shared by all cells of a sample
+
+_MASK64 = (1 << 64) - 1
+_GAMMA = 0x9E3779B97F4A7C15
+_C1 = 0xBF58476D1CE4E5B9
+_C2 = 0x94D049BB133111EB
+
+
+def mix64(z: int) -> int:
+    """SplitMix64 output function (Steele, Lea, Flood 2014) on a 64-bit word."""
+    z &= _MASK64
+    z = ((z ^ (z >> 30)) * _C1) & _MASK64
+    z = ((z ^ (z >> 27)) * _C2) & _MASK64
+    return z ^ (z >> 31)
+
+
+def _absorb(h: int, v: int) -> int:
+    return mix64((h + v + _GAMMA) & _MASK64)
+
+
+def k_from_ratio(r: float, cell: int = 2) -> int:
+    """Kept slots per cell for keep ratio r: round-half-up(r * cell^2), at least 1."""
+    if not (0.0 < r <= 1.0):
+        raise ValueError("keep ratio must be in (0, 1]")
+    n = cell * cell
+    k = int(np.floor(r * n + 0.5))
+    return max(1, min(n, k))
+
+
+def _k_partial(k: int, c: int) -> int:
+    """Kept slots of an edge cell with c (1 or 2) valid slots: round-half-up(k*c/4), >= 1."""
+    return max(1, (k * c + 2) // 4)
+
+
+def keep_count(B: int, P: int, H: int, W: int, k: int) -> int:
+    """Closed-form number of kept rows for a draw (keep ratio r = K / (B*(P+H*W)))."""
+    full = (H // 2) * (W // 2)
+    edge2 = (W % 2) * (H // 2) + (H % 2) * (W // 2)
+    corner = (H % 2) * (W % 2)
+    return B * (P + k * full + _k_partial(k, 2) * edge2 + _k_partial(k, 1) * corner)
+
+
+def _slot_ranks(h: int):
+    """Rank (0..3) of each of the four slots in the permutation drawn from hash h.
+
+    p in [0, 24) is taken from the top 32 bits of h by multiply-shift and decoded
+    as a Lehmer code: digit d_t picks the d_t-th of the slots not yet placed.
+    """
+    p = ((h >> 32) * 24) >> 32
+    digits = (p // 6, (p % 6) // 2, p % 2, 0)
+    remaining = [0, 1, 2, 3]
+    rank = [0, 0, 0, 0]
+    for t, d in enumerate(digits):
+        s = remaining.pop(d)
+        rank[s] = t
+    return rank
+
+
+def sample_indices(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sample=True):
+    """Grid-wise keep-set at k kept slots per 2x2 cell.
+
+    Returns int32 flat row ids into the [B*(P+H*W)] row space, in canonical
+    order: sample-major; inside a sample the P prefix rows (always kept), then
+    the cells in row-major cell order, and inside a cell the kept slots in
+    ascending slot number s = 2*(y%2) + (x%2).
+    """
+    if not (1 <= k <= 4):
+        raise ValueError("k must be in 1..4")
+    N = P + H * W
+    ch, cw = (H + 1) // 2, (W + 1) // 2
+    base = _absorb(_absorb(0, seed), stream_id)
+    out = []
+    for b in range(B):
+        hb = _absorb(base, b if per_sample else 0)
+        out.extend(b * N + p for p in range(P))
+        for cy in range(ch):
+            for cx in range(cw):
+                cell = 0 if mode == GRID_SHARED else cy * cw + cx
+                rank = _slot_ranks(_absorb(hb, cell))
+                valid = [s for s in range(4)
+                         if 2 * cy + (s >> 1) < H and 2 * cx + (s & 1) < W]
+                kc = k if len(valid) == 4 else _k_partial(k, len(valid))
+                chosen = sorted(sorted(valid, key=lambda s: rank[s])[:kc])
+                for s in chosen:
+                    y, x = 2 * cy + (s >> 1), 2 * cx + (s & 1)
+                    out.append(b * N + P + y * W + x)
+    return np.asarray(out, dtype=np.int32)
+
+
+def inverse_map(idx, M):
+    """inv[m] = position of row m in idx, or -1 for a dropped row."""
+    inv = np.full(M, -1, dtype=np.int32)
+    inv[np.asarray(idx, dtype=np.int64)] = np.arange(len(idx), dtype=np.int32)
+    return inv
+
+
+def forward_cache(X, idx):
+    """X_k[j, :] = X[idx[j], :] -- the only activation kept for the backward pass."""
+    X = np.asarray(X)
+    return X[np.asarray(idx, dtype=np.int64)].copy()
+
+
+def backward_linear(dY, idx, X_k, W, M):
+    """SBP backward of Y = X W^T + b restricted to the kept rows Z = set(idx).
+
+    dY [M, Cout] (only rows in idx are read), X_k [K, Cin] = X[idx], W [Cout, Cin].
+    Returns (dW [Cout, Cin], db [Cout], dX [M, Cin]) in fp64:
+      dW[o, i] = sum_{m in Z} dY[m, o] X[m, i]
+      db[o]    = sum_{m in Z} dY[m, o]
+      dX[m, :] = dY[m, :] W for m in Z, +0.0 elsewhere.
+    """
+    idx = np.asarray(idx, dtype=np.int64)
+    dY = np.asarray(dY, dtype=np.float64)
+    X_k = np.asarray(X_k, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    dY_k = dY[idx]
+    dW = dY_k.T @ X_k
+    db = dY_k.sum(axis=0)
+    dX = np.zeros((M, W.shape[1]), dtype=np.float64)
+    dX[idx] = dY_k @ W
+    return dW, db, dX
+
+
+def backward_dwconv(dY, idx, X, Wd, pad):
+    """Backward of a depthwise conv (stride 1, zero padding) with dY zeroed off the keep-set.
+
+    Forward: Y[b,y,x,c] = sum_{u,v} X[b, y+u-pad, x+v-pad, c] Wd[u,v,c] (+ bias).
+    dY, X [B,H,W,C] (channels last), Wd [ks,ks,C], idx = kept flat positions in
+    [0, B*H*W).  Returns (dWd [ks,ks,C], db [C], dX [B,H,W,C]) in fp64.
+    """
+    dY = np.asarray(dY, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    Wd = np.asarray(Wd, dtype=np.float64)
+    B, H, Wi, C = dY.shape
+    ks = Wd.shape[0]
+    mask = np.zeros(B * H * Wi, dtype=np.float64)
+    mask[np.asarray(idx, dtype=np.int64)] = 1.0
+    g = dY * mask.reshape(B, H, Wi, 1)
+    Xp = np.zeros((B, H + 2 * pad, Wi + 2 * pad, C), dtype=np.float64)
+    Xp[:, pad:pad + H, pad:pad + Wi, :] = X
+    dXp = np.zeros_like(Xp)
+    dWd = np.zeros((ks, ks, C), dtype=np.float64)
+    for u in range(ks):
+        for v in range(ks):
+            dWd[u, v, :] = (g * Xp[:, u:u + H, v:v + Wi, :]).sum(axis=(0, 1, 2))
+            dXp[:, u:u + H, v:v + Wi, :] += g * Wd[u, v, :]
+    db = g.sum(axis=(0, 1, 2))
+    dX = dXp[:, pad:pad + H, pad:pad + Wi, :].copy()
+    return dWd, db, dX
