@@ -1,0 +1,172 @@
+/*
+ * sbp.h -- C ABI of the Stochastic-Backpropagation (SBP) hot path for AMD MI355X (gfx950).
+ *
+ * SBP (arXiv 2210.00129) runs the full forward pass but back-propagates through a random
+ * subset of spatial positions only: per layer it caches just the kept rows of the input
+ * activation and computes weight / input gradients from the kept rows of the output
+ * gradient (paper, section "Calculation of Linear Layers", equation eq:backward_fc_sbp).
+ *
+ * Conventions shared by every call
+ *   - All tensor pointers are DEVICE pointers (HBM); descriptors are host structs.
+ *   - Tensors are dense, row-major, no strides: a [R, C] matrix has leading dimension C.
+ *     Feature maps are channels-last, i.e. a [B, H, W, C] map is the [B*H*W, C] matrix.
+ *   - The library allocates nothing and frees nothing.  Every buffer, including the
+ *     workspace, is owned by the caller and only borrowed until the work enqueued on
+ *     `stream` has run.  Inputs are never written; outputs are fully overwritten unless a
+ *     flag says otherwise.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work; none of them synchronises.
+ *   - Every argument is validated on the host BEFORE the first HIP call; a failed
+ *     validation enqueues nothing.  Return value: SBP_OK or a negative SBP_ERR_* code;
+ *     sbp_last_error() gives a thread-local description of the last failure.
+ *   - Weight layout is W[Cout, Cin] (Y = X W^T + b).  The paper writes W as [Cin, Cout];
+ *     the quantities are the same with the storage transposed.
+ *   - No gradient is rescaled by 1/r (the paper's update rule eq:sbp_formula carries 1/B only).
+ */
+#ifndef SBP_H_
+#define SBP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define SBP_OK              0
+#define SBP_ERR_NULL       (-1)  /* a required pointer is NULL */
+#define SBP_ERR_SHAPE      (-2)  /* a size is non-positive, inconsistent or overflows int32 row ids */
+#define SBP_ERR_RATIO      (-3)  /* keep ratio / kept-slot count out of range */
+#define SBP_ERR_DTYPE      (-4)  /* unknown element type */
+#define SBP_ERR_CAPACITY   (-5)  /* an output buffer is smaller than what would be written */
+#define SBP_ERR_WORKSPACE  (-6)  /* workspace NULL/too small/misaligned */
+#define SBP_ERR_HIP        (-7)  /* a HIP launch failed (no device, bad stream, ...) */
+#define SBP_ERR_FLAGS      (-8)  /* unknown or unsupported flag / mode */
+
+/* element types of activations and weights */
+#define SBP_F32   0   /* fp32 storage, fp32 accumulate */
+#define SBP_BF16  1   /* bf16 storage, fp32 accumulate (MFMA) */
+
+/* sampler modes */
+#define SBP_GRID_PER_CELL 0  /* independent draw in every 2x2 cell */
+#define SBP_GRID_SHARED   1  /* one slot permutation shared by all cells of a sample (regular lattice) */
+
+/* flags of sbp_backward_linear */
+#define SBP_FLAG_DY_COMPACT     1u  /* dY is already compact: [K, Cout], row j belongs to idx[j] */
+#define SBP_FLAG_DX_COMPACT     2u  /* write dX compact: [K, Cin], no scatter, no zero rows */
+#define SBP_FLAG_ACCUMULATE_DW  4u  /* dW += and db += instead of overwrite */
+
+/*
+ * One draw of a grid-wise keep-set (paper, "How to sample the gradient keep mask?": a
+ * structured sample drawn afresh every step).  The paper gives no algorithm; the reading
+ * implemented here: the H x W map of each sample is tiled into 2x2 cells and k of the 4
+ * slots of every cell are kept (k = round(4 r)); partial cells on an odd edge with c valid
+ * slots keep max(1, round(k c / 4)) of them.  The draw is a pure function of
+ * (seed, stream_id, sample, cell): a SplitMix64-based counter hash, no state.
+ * Rows are numbered b*(P + H*W) + p for the P always-kept prefix rows of sample b (the
+ * ViT class token) and b*(P + H*W) + P + y*W + x for grid position (y, x).
+ */
+typedef struct sbp_sample_desc {
+  int32_t  B;          /* samples in the batch, >= 1 */
+  int32_t  P;          /* always-kept prefix rows per sample, >= 0 */
+  int32_t  H, W;       /* grid, >= 1 each */
+  int32_t  cell;       /* cell edge; must be 2 */
+  int32_t  k;          /* kept slots per full cell, 1..4 */
+  int32_t  mode;       /* SBP_GRID_PER_CELL or SBP_GRID_SHARED */
+  int32_t  per_sample; /* 1: every sample draws its own mask; 0: one mask for the batch */
+  uint64_t seed;       /* run seed */
+  uint64_t stream_id;  /* caller's (step, layer) counter: a new value gives a new mask */
+} sbp_sample_desc;
+
+/* Host only.  Text for a status code; never NULL. */
+const char* sbp_status_string(int32_t status);
+/* Host only.  Thread-local description of the last failed call on this thread ("" if none). */
+const char* sbp_last_error(void);
+
+/* Host only.  Kept slots per cell for keep ratio r: round-half-up(r*cell*cell), clamped to
+ * [1, cell*cell].  Returns SBP_ERR_RATIO if r is not in (0, 1], SBP_ERR_SHAPE if cell != 2. */
+int32_t sbp_k_from_ratio(double r, int32_t cell);
+
+/* Host only.  Number of kept rows K of a draw (closed form), or a negative SBP_ERR_* code.
+ * The keep ratio of the paper is K / (B*(P+H*W)). */
+int64_t sbp_keep_count(const sbp_sample_desc* desc);
+
+/*
+ * Step "sample keep-set".  Writes the kept row ids, int32, into idx[0..K) in canonical
+ * order: sample-major; inside a sample the P prefix rows, then the cells in row-major cell
+ * order, and inside a cell the kept slots in ascending slot number 2*(y%2) + (x%2).
+ *   idx          device, out, capacity idx_capacity elements (>= K else SBP_ERR_CAPACITY)
+ *   inv          device, out, [B*(P+H*W)] or NULL: inv[row] = position of row in idx, -1 if dropped
+ */
+int32_t sbp_sample_indices(const sbp_sample_desc* desc, int32_t* idx, int64_t idx_capacity,
+                           int32_t* inv, void* stream);
+
+/*
+ * Step "forward cache" (paper: SBP "only caches a subset of the feature maps"):
+ * X_k[j, :] = X[idx[j], :] for j in [0, K).
+ *   X      device, in,  [M, C] of `dtype`
+ *   idx    device, in,  [K] row ids in [0, M), unique (caller's contract; any unique list is legal)
+ *   X_k    device, out, [K, C] of `dtype`
+ */
+int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t K, int32_t C,
+                          int32_t dtype, void* X_k, void* stream);
+
+/* Host only.  Bytes of workspace sbp_backward_linear needs for these sizes (0 on invalid sizes). */
+size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t Cout,
+                                     int32_t dtype, uint32_t flags);
+
+/*
+ * Steps "gather dY", "dW", "db", "dX" (paper, eq:backward_fc_sbp with every dropped term
+ * removed):
+ *   dW[o, i] = sum_j dY[idx[j], o] * X_k[j, i]           fp32, [Cout, Cin]
+ *   db[o]    = sum_j dY[idx[j], o]                       fp32, [Cout]
+ *   dX[idx[j], :] = dY[idx[j], :] * W ; every other row of dX is +0.0     `dtype`, [M, Cin]
+ * Sums are accumulated in fp32; bf16 outputs are rounded once (round-to-nearest-even).
+ * The result is deterministic (no floating-point atomics).
+ *   dY     device, in,  [M, Cout] (only rows in idx are read) or [K, Cout] with SBP_FLAG_DY_COMPACT
+ *   idx    device, in,  [K] unique row ids in [0, M)
+ *   X_k    device, in,  [K, Cin] rows cached by sbp_forward_cache (may be NULL if dW is NULL)
+ *   W      device, in,  [Cout, Cin]                       (may be NULL if dX is NULL)
+ *   dW, db, dX   device, out; each may be NULL to skip that output
+ *   workspace    device, 256-byte aligned, at least sbp_backward_linear_workspace(...) bytes;
+ *                contents on entry are irrelevant, contents on exit are unspecified
+ * Channel counts that are multiples of 8 take the MFMA path for SBP_BF16; any other shape
+ * and SBP_F32 take a plain (slower) kernel -- never an error.
+ */
+int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const void* X_k, const void* W,
+                            int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
+                            float* dW, float* db, void* dX,
+                            void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/* Host only.  Bytes of workspace sbp_backward_dwconv needs (0 on invalid sizes). */
+size_t sbp_backward_dwconv_workspace(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks,
+                                     int64_t K, int32_t dtype, uint32_t flags);
+
+/*
+ * Step "depthwise conv backward on kept outputs" (paper, eq:conv_grad_layer_before_sbp with
+ * dY set to zero at dropped positions; exact because the gradient arriving from an SBP
+ * pointwise layer is zero there, eq:conv_grad_layer_before_sbp_chain).  Depthwise, stride 1,
+ * zero padding `pad`, forward Y[b,y,x,c] = sum_{u,v} X[b,y+u-pad,x+v-pad,c] * Wd[u,v,c]:
+ *   dWd[u,v,c] = sum_{(b,y,x) kept} dY[b,y,x,c] * X[b,y+u-pad,x+v-pad,c]      fp32, [ks,ks,C]
+ *   db[c]      = sum_{(b,y,x) kept} dY[b,y,x,c]                               fp32, [C]
+ *   dX[b,y,x,c]= sum_{u,v} [ (b,y-u+pad,x-v+pad) kept ] dY[..] * Wd[u,v,c]    `dtype`, dense
+ *   dY   device, in, [B,H,W,C]; only kept positions are read
+ *   idx  device, in, [K] kept flat positions b*H*W + y*W + x, unique
+ *   inv  device, in, [B*H*W] inverse of idx (-1 = dropped) or NULL (then built in the workspace)
+ *   X    device, in, [B,H,W,C] FULL input of the layer (a k>1 conv needs the neighbours)
+ *   Wd   device, in, [ks,ks,C]
+ *   dWd, db, dX  device, out; each may be NULL
+ * ks must be odd and <= 7, pad = ks/2.
+ */
+int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* inv,
+                            const void* X, const void* Wd,
+                            int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int32_t pad,
+                            int64_t K, int32_t dtype,
+                            float* dWd, float* db, void* dX,
+                            void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SBP_H_ */

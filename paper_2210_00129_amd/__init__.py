@@ -1,0 +1,149 @@
+"""MI355X-native hot path of Stochastic Backpropagation (SBP, arXiv 2210.00129).
+
+Thin Python binding over the C-ABI library libsbp.so (hand-written HIP kernels for gfx950).
+The functions below carry the names of the library's entry points and only marshal
+arguments: torch provides device memory and the current stream, every step of the path
+runs in the library's kernels.  There is no fallback: without the built library, or
+without a GPU for the compute calls, they raise.
+
+    idx, inv = sample_indices(B, P, H, W, k, seed, stream_id)     # draw the keep-set
+    X_k      = forward_cache(X, idx)                              # cache kept rows only
+    dW, db, dX = backward_linear(dY, idx, X_k, W)                 # token-subset backward
+    dWd, db, dX = backward_dwconv(dY, idx, X, Wd)                 # depthwise 7x7, kept outputs
+"""
+from __future__ import annotations
+
+import torch
+
+from . import _lib
+from ._lib import SampleDesc, SbpError  # noqa: F401
+
+F32, BF16 = 0, 1
+GRID_PER_CELL, GRID_SHARED = 0, 1
+FLAG_DY_COMPACT, FLAG_DX_COMPACT, FLAG_ACCUMULATE_DW = 1, 2, 4
+
+_DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    try:
+        return _DTYPES[t.dtype]
+    except KeyError:
+        raise TypeError(f"unsupported dtype {t.dtype}; use float32 or bfloat16") from None
+
+
+def _dev(t, name):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in GPU memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def make_desc(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sample=True) -> SampleDesc:
+    return SampleDesc(int(B), int(P), int(H), int(W), 2, int(k), int(mode), int(bool(per_sample)),
+                      int(seed) & 0xFFFFFFFFFFFFFFFF, int(stream_id) & 0xFFFFFFFFFFFFFFFF)
+
+
+def k_from_ratio(r: float, cell: int = 2) -> int:
+    """Kept slots per 2x2 cell for keep ratio r (host only)."""
+    return _lib.check(_lib.lib().sbp_k_from_ratio(float(r), int(cell)))
+
+
+def keep_count(B, P, H, W, k, mode=GRID_PER_CELL, per_sample=True) -> int:
+    """Number of kept rows K of a draw (host only, closed form)."""
+    d = make_desc(B, P, H, W, k, 0, 0, mode, per_sample)
+    return _lib.check(_lib.lib().sbp_keep_count(d))
+
+
+def sample_indices(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sample=True, want_inv=False,
+                   device="cuda", idx_out=None, inv_out=None):
+    """Draws the grid-wise keep-set on the GPU; returns (idx [K] int32, inv [B*(P+H*W)] int32 or None)."""
+    d = make_desc(B, P, H, W, k, seed, stream_id, mode, per_sample)
+    K = _lib.check(_lib.lib().sbp_keep_count(d))
+    dev = torch.device(device)
+    idx = idx_out if idx_out is not None else torch.empty(K, dtype=torch.int32, device=dev)
+    inv = inv_out
+    if inv is None and want_inv:
+        inv = torch.empty(B * (P + H * W), dtype=torch.int32, device=dev)
+    _lib.check(_lib.lib().sbp_sample_indices(d, _dev(idx, "idx"), idx.numel(), _dev(inv, "inv"),
+                                             _stream(idx.device)))
+    return idx, inv
+
+
+def forward_cache(X: torch.Tensor, idx: torch.Tensor, out=None) -> torch.Tensor:
+    """X_k = X[idx] (rows), the only part of the layer input kept for the backward pass."""
+    if X.dim() != 2:
+        raise ValueError("X must be [M, C]")
+    M, C = X.shape
+    K = idx.numel()
+    Xk = out if out is not None else torch.empty((K, C), dtype=X.dtype, device=X.device)
+    _lib.check(_lib.lib().sbp_forward_cache(_dev(X, "X"), _dev(idx, "idx"), M, K, C, _dtype_code(X),
+                                            _dev(Xk, "X_k"), _stream(X.device)))
+    return Xk
+
+
+def backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags=0) -> int:
+    return int(_lib.lib().sbp_backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags))
+
+
+def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), dW=None, db=None, dX=None,
+                    workspace=None):
+    """SBP backward of Y = X W^T + b on the kept rows.  Returns (dW fp32, db fp32, dX)."""
+    Cout, Cin = W.shape
+    K = idx.numel() if idx is not None else dY.shape[0]
+    if M is None:
+        if flags & FLAG_DY_COMPACT:
+            raise ValueError("M is required when dY is compact")
+        M = dY.shape[0]
+    code = _dtype_code(W)
+    dev = W.device
+    if "dW" in want and dW is None:
+        dW = torch.empty((Cout, Cin), dtype=torch.float32, device=dev)
+    if "db" in want and db is None:
+        db = torch.empty((Cout,), dtype=torch.float32, device=dev)
+    if "dX" in want and dX is None:
+        rows = K if (flags & FLAG_DX_COMPACT) else M
+        dX = torch.empty((rows, Cin), dtype=W.dtype, device=dev)
+    need = backward_linear_workspace(M, K, Cin, Cout, code, flags)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _lib.check(_lib.lib().sbp_backward_linear(
+        _dev(dY, "dY"), _dev(idx, "idx"), _dev(X_k, "X_k"), _dev(W, "W"), M, K, Cin, Cout, code,
+        _dev(dW, "dW"), _dev(db, "db"), _dev(dX, "dX"), _dev(workspace, "workspace"), workspace.numel(),
+        flags, _stream(dev)))
+    return dW, db, dX
+
+
+def backward_dwconv_workspace(B, H, W, C, ks, K, dtype_code, flags=0) -> int:
+    return int(_lib.lib().sbp_backward_dwconv_workspace(B, H, W, C, ks, K, dtype_code, flags))
+
+
+def backward_dwconv(dY, idx, X, Wd, inv=None, want=("dWd", "db", "dX"), dWd=None, db=None, dX=None,
+                    workspace=None):
+    """Depthwise-conv backward on the kept output positions.  dY, X: [B,H,W,C]; Wd: [ks,ks,C]."""
+    B, H, W, C = dY.shape
+    ks = Wd.shape[0]
+    K = idx.numel()
+    code = _dtype_code(dY)
+    dev = dY.device
+    if "dWd" in want and dWd is None:
+        dWd = torch.empty((ks, ks, C), dtype=torch.float32, device=dev)
+    if "db" in want and db is None:
+        db = torch.empty((C,), dtype=torch.float32, device=dev)
+    if "dX" in want and dX is None:
+        dX = torch.empty((B, H, W, C), dtype=dY.dtype, device=dev)
+    need = backward_dwconv_workspace(B, H, W, C, ks, K, code, 0)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _lib.check(_lib.lib().sbp_backward_dwconv(
+        _dev(dY, "dY"), _dev(idx, "idx"), _dev(inv, "inv"), _dev(X, "X"), _dev(Wd, "Wd"), B, H, W, C, ks, ks // 2,
+        K, code, _dev(dWd, "dWd"), _dev(db, "db"), _dev(dX, "dX"), _dev(workspace, "workspace"),
+        workspace.numel(), 0, _stream(dev)))
+    return dWd, db, dX

@@ -1,0 +1,180 @@
+// C ABI of libsbp: host-side validation, then kernel launches.  Every argument check runs
+// before the first HIP call so that error paths need no device.
+#include <cstdarg>
+#include <cstdio>
+#include <cmath>
+
+#include "sbp_internal.h"
+
+namespace sbp {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int32_t check_launch(const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(SBP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return SBP_OK;
+}
+
+static int32_t validate_desc(const sbp_sample_desc* d) {
+  if (!d) return fail(SBP_ERR_NULL, "sample descriptor is NULL");
+  if (d->B < 1 || d->P < 0 || d->H < 1 || d->W < 1)
+    return fail(SBP_ERR_SHAPE, "bad geometry B=%d P=%d H=%d W=%d", d->B, d->P, d->H, d->W);
+  if (d->cell != 2) return fail(SBP_ERR_SHAPE, "cell must be 2, got %d", d->cell);
+  if (d->k < 1 || d->k > 4) return fail(SBP_ERR_RATIO, "k must be in 1..4, got %d", d->k);
+  if (d->mode != SBP_GRID_PER_CELL && d->mode != SBP_GRID_SHARED)
+    return fail(SBP_ERR_FLAGS, "unknown sampler mode %d", d->mode);
+  if (d->per_sample != 0 && d->per_sample != 1)
+    return fail(SBP_ERR_FLAGS, "per_sample must be 0 or 1, got %d", d->per_sample);
+  int64_t rows = (int64_t)d->B * ((int64_t)d->P + (int64_t)d->H * d->W);
+  if (rows > INT32_MAX) return fail(SBP_ERR_SHAPE, "B*(P+H*W)=%lld exceeds int32 row ids", (long long)rows);
+  return SBP_OK;
+}
+
+static int elem_bytes(int32_t dtype) { return dtype == SBP_F32 ? 4 : dtype == SBP_BF16 ? 2 : 0; }
+
+}  // namespace sbp
+
+using namespace sbp;
+
+extern "C" {
+
+const char* sbp_status_string(int32_t st) {
+  switch (st) {
+    case SBP_OK: return "ok";
+    case SBP_ERR_NULL: return "null pointer";
+    case SBP_ERR_SHAPE: return "bad shape";
+    case SBP_ERR_RATIO: return "bad keep ratio";
+    case SBP_ERR_DTYPE: return "bad dtype";
+    case SBP_ERR_CAPACITY: return "output capacity too small";
+    case SBP_ERR_WORKSPACE: return "bad workspace";
+    case SBP_ERR_HIP: return "HIP error";
+    case SBP_ERR_FLAGS: return "bad flags";
+    default: return "unknown status";
+  }
+}
+
+const char* sbp_last_error(void) { return g_err; }
+
+int32_t sbp_k_from_ratio(double r, int32_t cell) {
+  if (cell != 2) return fail(SBP_ERR_SHAPE, "cell must be 2, got %d", cell);
+  if (!(r > 0.0 && r <= 1.0)) return fail(SBP_ERR_RATIO, "keep ratio %g not in (0,1]", r);
+  int32_t n = cell * cell;
+  int32_t k = (int32_t)std::floor(r * n + 0.5);
+  return k < 1 ? 1 : (k > n ? n : k);
+}
+
+int64_t sbp_keep_count(const sbp_sample_desc* d) {
+  int32_t st = validate_desc(d);
+  if (st != SBP_OK) return st;
+  return keep_count_host(*d);
+}
+
+int32_t sbp_sample_indices(const sbp_sample_desc* d, int32_t* idx, int64_t idx_capacity, int32_t* inv,
+                           void* stream) {
+  int32_t st = validate_desc(d);
+  if (st != SBP_OK) return st;
+  if (!idx) return fail(SBP_ERR_NULL, "idx is NULL");
+  int64_t K = keep_count_host(*d);
+  if (idx_capacity < K)
+    return fail(SBP_ERR_CAPACITY, "idx capacity %lld < K=%lld", (long long)idx_capacity, (long long)K);
+  return launch_sample(*d, idx, inv, (hipStream_t)stream);
+}
+
+int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t K, int32_t C, int32_t dtype,
+                          void* Xk, void* stream) {
+  if (!X || !idx || !Xk) return fail(SBP_ERR_NULL, "X, idx and X_k must be non-NULL");
+  int eb = elem_bytes(dtype);
+  if (!eb) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (M < 1 || M > INT32_MAX || C < 1) return fail(SBP_ERR_SHAPE, "bad shape M=%lld C=%d", (long long)M, C);
+  if (K < 0 || K > M) return fail(SBP_ERR_SHAPE, "need 0 <= K <= M, got K=%lld M=%lld", (long long)K, (long long)M);
+  if (K == 0) return SBP_OK;
+  return launch_gather_rows(X, idx, K, C, eb, Xk, (hipStream_t)stream);
+}
+
+static int32_t validate_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags) {
+  if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (flags & ~(SBP_FLAG_DY_COMPACT | SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW))
+    return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);
+  if (M < 1 || M > INT32_MAX || Cin < 1 || Cout < 1)
+    return fail(SBP_ERR_SHAPE, "bad shape M=%lld Cin=%d Cout=%d", (long long)M, Cin, Cout);
+  if (K < 0 || K > M) return fail(SBP_ERR_SHAPE, "need 0 <= K <= M, got K=%lld M=%lld", (long long)K, (long long)M);
+  if ((int64_t)Cin * Cout > INT32_MAX) return fail(SBP_ERR_SHAPE, "Cin*Cout too large");
+  return SBP_OK;
+}
+
+size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
+                                     uint32_t flags) {
+  if (validate_linear(M, K, Cin, Cout, dtype, flags) != SBP_OK) return 0;
+  return plan_linear(M, K, Cin, Cout, dtype, flags).bytes;
+}
+
+int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const void* Xk, const void* W, int64_t M,
+                            int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, float* dW, float* db,
+                            void* dX, void* ws, size_t ws_bytes, uint32_t flags, void* stream) {
+  int32_t st = validate_linear(M, K, Cin, Cout, dtype, flags);
+  if (st != SBP_OK) return st;
+  if (!dY) return fail(SBP_ERR_NULL, "dY is NULL");
+  bool need_idx = !((flags & SBP_FLAG_DY_COMPACT) && ((flags & SBP_FLAG_DX_COMPACT) || !dX));
+  if (need_idx && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL");
+  if (dW && !Xk && K > 0) return fail(SBP_ERR_NULL, "X_k is NULL but dW is requested");
+  if (dX && !W) return fail(SBP_ERR_NULL, "W is NULL but dX is requested");
+  LinearPlan p = plan_linear(M, K, Cin, Cout, dtype, flags);
+  if (p.bytes) {
+    if (!ws) return fail(SBP_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", p.bytes);
+    if (ws_bytes < p.bytes) return fail(SBP_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", ws_bytes, p.bytes);
+    if ((uintptr_t)ws % 256) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  }
+  if (!dW && !db && !dX) return SBP_OK;
+  return launch_backward_linear(p, dY, idx, Xk, W, M, K, Cin, Cout, dtype, dW, db, dX, ws, flags,
+                                (hipStream_t)stream);
+}
+
+static int32_t validate_dw(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int32_t pad, int64_t K,
+                           int32_t dtype, uint32_t flags) {
+  if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (flags) return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);
+  if (B < 1 || H < 1 || W < 1 || C < 1) return fail(SBP_ERR_SHAPE, "bad shape B=%d H=%d W=%d C=%d", B, H, W, C);
+  if (ks < 1 || ks > 7 || (ks & 1) == 0) return fail(SBP_ERR_SHAPE, "kernel size must be odd and <= 7, got %d", ks);
+  if (pad != ks / 2) return fail(SBP_ERR_SHAPE, "pad must be ks/2=%d, got %d", ks / 2, pad);
+  int64_t Mpos = (int64_t)B * H * W;
+  if (Mpos > INT32_MAX) return fail(SBP_ERR_SHAPE, "B*H*W exceeds int32 row ids");
+  if (K < 0 || K > Mpos) return fail(SBP_ERR_SHAPE, "need 0 <= K <= B*H*W, got K=%lld", (long long)K);
+  return SBP_OK;
+}
+
+size_t sbp_backward_dwconv_workspace(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int64_t K,
+                                     int32_t dtype, uint32_t flags) {
+  if (validate_dw(B, H, W, C, ks, ks / 2, K, dtype, flags) != SBP_OK) return 0;
+  return plan_dwconv(B, H, W, C, ks, K, dtype).bytes;
+}
+
+int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* inv, const void* X,
+                            const void* Wd, int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks,
+                            int32_t pad, int64_t K, int32_t dtype, float* dWd, float* db, void* dX, void* ws,
+                            size_t ws_bytes, uint32_t flags, void* stream) {
+  int32_t st = validate_dw(B, H, W, C, ks, pad, K, dtype, flags);
+  if (st != SBP_OK) return st;
+  if (!dY) return fail(SBP_ERR_NULL, "dY is NULL");
+  if ((dWd || db) && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL but dWd / db is requested");
+  if (dX && !idx && !inv && K > 0) return fail(SBP_ERR_NULL, "idx and inv are both NULL");
+  if (dWd && !X) return fail(SBP_ERR_NULL, "X is NULL but dWd is requested");
+  if (dX && !Wd) return fail(SBP_ERR_NULL, "Wd is NULL but dX is requested");
+  DwPlan p = plan_dwconv(B, H, W, C, ks, K, dtype);
+  if (!ws) return fail(SBP_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", p.bytes);
+  if (ws_bytes < p.bytes) return fail(SBP_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", ws_bytes, p.bytes);
+  if ((uintptr_t)ws % 256) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  if (!dWd && !db && !dX) return SBP_OK;
+  return launch_backward_dwconv(p, dY, idx, inv, X, Wd, B, H, W, C, ks, pad, K, dtype, dWd, db, dX, ws,
+                                (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libsbp (not part of the ABI).
+#ifndef SBP_INTERNAL_H_
+#define SBP_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "sbp.h"
+
+namespace sbp {
+
+// Records a formatted message for sbp_last_error() and returns `code`.
+int32_t fail(int32_t code, const char* fmt, ...);
+// Turns the state left by a kernel launch into a status code.
+int32_t check_launch(const char* what);
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- sampler -----------------------------------------------------------------------------
+int64_t keep_count_host(const sbp_sample_desc& d);
+int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipStream_t s);
+
+// ---- row gather --------------------------------------------------------------------------
+int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t C, int32_t elem_bytes,
+                           void* Xk, hipStream_t s);
+
+// ---- linear backward ---------------------------------------------------------------------
+struct LinearPlan {
+  bool   mfma;          // bf16 MFMA path (else plain kernels)
+  int    splits;        // split-K factor of the dW contraction
+  int    rows_per_split;// kept rows per split (multiple of the k-step)
+  size_t off_partial;   // fp32 [splits, Cout, Cin]
+  size_t off_inv;       // int32 [M]
+  size_t bytes;
+};
+LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags);
+int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const void* Xk,
+                               const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
+                               int32_t dtype, float* dW, float* db, void* dX, void* ws, uint32_t flags,
+                               hipStream_t s);
+
+// ---- depthwise backward ------------------------------------------------------------------
+struct DwPlan {
+  int    tiles_y, tiles_x; // spatial tiles of the dWd/db partial reduction
+  int    nparts;           // partial accumulators per (tap, channel)
+  size_t off_inv;          // int32 [B*H*W]
+  size_t off_partial;      // fp32 [nparts, ks*ks+1, C]
+  size_t bytes;
+};
+DwPlan plan_dwconv(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int64_t K, int32_t dtype);
+int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* idx, const int32_t* inv,
+                               const void* X, const void* Wd, int32_t B, int32_t H, int32_t W, int32_t C,
+                               int32_t ks, int32_t pad, int64_t K, int32_t dtype, float* dWd, float* db,
+                               void* dX, void* ws, hipStream_t s);
+
+}  // namespace sbp
+#endif

@@ -1,0 +1,165 @@
+"""Host-side checks of the C-ABI library: it loads, exports every declared symbol, and rejects
+bad arguments before touching the GPU (none of these calls launches a kernel)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2210_00129_amd as sbp
+from paper_2210_00129_amd import _lib
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sbp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sbp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert len(names) == 10
+    handle = ctypes.CDLL(_lib.LIB_PATH)
+    for n in names:
+        assert hasattr(handle, n), n
+    assert sorted(_lib.PROTOTYPES) == names
+
+
+def test_status_strings():
+    L = _lib.lib()
+    assert L.sbp_status_string(0) == b"ok"
+    for code in range(-8, 0):
+        assert L.sbp_status_string(code) not in (b"", b"ok", b"unknown status")
+    assert L.sbp_status_string(-99) == b"unknown status"
+
+
+@pytest.mark.parametrize("r", [0.05, 0.125, 0.25, 0.3, 0.375, 0.5, 0.62, 0.75, 0.875, 0.9, 1.0])
+def test_k_from_ratio_matches_oracle(r):
+    assert sbp.k_from_ratio(r) == oracle.k_from_ratio(r)
+
+
+def test_k_from_ratio_rejects_bad_input():
+    for r in (0.0, -0.5, 1.01, float("nan")):
+        with pytest.raises(sbp.SbpError) as e:
+            sbp.k_from_ratio(r)
+        assert e.value.status == -3
+    with pytest.raises(sbp.SbpError) as e:
+        sbp.k_from_ratio(0.5, cell=3)
+    assert e.value.status == -2
+
+
+@pytest.mark.parametrize("geom", [(2, 0, 14, 14), (64, 1, 14, 14), (2, 0, 200, 336), (2, 0, 5, 7), (1, 2, 3, 3),
+                                  (3, 1, 1, 6), (1, 0, 1, 1), (2, 0, 50, 84), (2, 0, 800, 1333)])
+def test_keep_count_matches_oracle(geom):
+    B, P, H, W = geom
+    for k in (1, 2, 3, 4):
+        assert sbp.keep_count(B, P, H, W, k) == oracle.keep_count(B, P, H, W, k)
+
+
+def _desc(**kw):
+    base = dict(B=2, P=0, H=4, W=4, k=2, seed=0, stream_id=0)
+    base.update(kw)
+    d = sbp.make_desc(base["B"], base["P"], base["H"], base["W"], base["k"], base["seed"], base["stream_id"])
+    for f in ("cell", "mode", "per_sample"):
+        if f in kw:
+            setattr(d, f, kw[f])
+    return d
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(B=0), -2), (dict(P=-1), -2), (dict(H=0), -2), (dict(W=0), -2), (dict(cell=4), -2),
+    (dict(k=0), -3), (dict(k=5), -3), (dict(mode=7), -8), (dict(per_sample=2), -8),
+    (dict(B=70000, H=200, W=200), -2),
+])
+def test_keep_count_rejects_bad_descriptor(kw, status):
+    assert _lib.lib().sbp_keep_count(_desc(**kw)) == status
+    assert _lib.lib().sbp_last_error() != b""
+
+
+def test_sample_indices_argument_errors():
+    L = _lib.lib()
+    d = _desc()
+    assert L.sbp_sample_indices(None, 16, 100, None, None) == -1
+    assert L.sbp_sample_indices(d, None, 100, None, None) == -1
+    assert L.sbp_sample_indices(d, 4096, 15, None, None) == -5      # K = 16
+    assert b"capacity" in L.sbp_last_error()
+
+
+def test_forward_cache_argument_errors():
+    L = _lib.lib()
+    p = 4096  # never dereferenced: validation fails first
+    assert L.sbp_forward_cache(None, p, 10, 5, 8, 1, p, None) == -1
+    assert L.sbp_forward_cache(p, p, 10, 5, 8, 9, p, None) == -4
+    assert L.sbp_forward_cache(p, p, 0, 0, 8, 1, p, None) == -2
+    assert L.sbp_forward_cache(p, p, 10, 11, 8, 1, p, None) == -2
+    assert L.sbp_forward_cache(p, p, 10, 5, 0, 1, p, None) == -2
+    assert L.sbp_forward_cache(p, p, 10, 0, 8, 1, p, None) == 0     # nothing to gather
+
+
+def test_backward_linear_argument_errors():
+    L = _lib.lib()
+    p = 4096
+    ws = L.sbp_backward_linear_workspace(100, 50, 64, 128, 1, 0)
+    assert ws > 0 and ws % 256 == 0
+    args = dict(dY=p, idx=p, Xk=p, W=p, M=100, K=50, Cin=64, Cout=128, dtype=1, dW=p, db=p, dX=p, ws=p * 4,
+                ws_bytes=ws, flags=0)
+
+    def call(**kw):
+        a = dict(args)
+        a.update(kw)
+        return L.sbp_backward_linear(a["dY"], a["idx"], a["Xk"], a["W"], a["M"], a["K"], a["Cin"], a["Cout"],
+                                     a["dtype"], a["dW"], a["db"], a["dX"], a["ws"], a["ws_bytes"], a["flags"], None)
+
+    assert call(dY=None) == -1
+    assert call(idx=None) == -1
+    assert call(Xk=None) == -1
+    assert call(W=None) == -1
+    assert call(dtype=5) == -4
+    assert call(K=101) == -2
+    assert call(M=0) == -2
+    assert call(Cin=0) == -2
+    assert call(flags=64) == -8
+    assert call(ws=None) == -6
+    assert call(ws_bytes=ws - 1) == -6
+    assert call(ws=p * 4 + 8) == -6
+    assert call(dW=None, db=None, dX=None) == 0                     # nothing requested, nothing launched
+    assert L.sbp_backward_linear_workspace(100, 500, 64, 128, 1, 0) == 0
+    # compact dX needs no inverse map: smaller workspace
+    assert L.sbp_backward_linear_workspace(100, 50, 64, 128, 1, 2) < ws
+
+
+def test_backward_dwconv_argument_errors():
+    L = _lib.lib()
+    p = 4096
+    ws = L.sbp_backward_dwconv_workspace(2, 8, 8, 16, 7, 64, 1, 0)
+    assert ws > 0
+
+    def call(dY=p, idx=p, inv=None, X=p, Wd=p, B=2, H=8, W=8, C=16, ks=7, pad=3, K=64, dtype=1, dWd=p, db=p,
+             dX=p, wsp=p * 4, wsb=ws, flags=0):
+        return L.sbp_backward_dwconv(dY, idx, inv, X, Wd, B, H, W, C, ks, pad, K, dtype, dWd, db, dX, wsp, wsb,
+                                     flags, None)
+
+    assert call(dY=None) == -1
+    assert call(idx=None) == -1
+    assert call(X=None) == -1
+    assert call(Wd=None) == -1
+    assert call(ks=4) == -2
+    assert call(ks=9, pad=4) == -2
+    assert call(pad=2) == -2
+    assert call(K=200) == -2
+    assert call(dtype=3) == -4
+    assert call(flags=1) == -8
+    assert call(wsp=None) == -6
+    assert call(wsb=16) == -6
+    assert call(dWd=None, db=None, dX=None) == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    X = torch.zeros(4, 8)
+    idx = torch.zeros(2, dtype=torch.int32)
+    with pytest.raises(ValueError):
+        sbp.forward_cache(X, idx)

@@ -1,0 +1,290 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Index work must be bit-exact; gradients within 1e-5 (fp32 outputs) / 2e-2 (bf16 outputs)
+of max|reference|, with a tighter bound derived from one bf16 rounding also enforced."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2210_00129_amd as sbp
+import synth_inputs as si
+from gpu_util import TOL_BF16, TOL_BF16_TIGHT, TOL_F32, bits, check_linear, f64, nerr
+
+pytestmark = pytest.mark.gpu
+
+
+# ------------------------------------------------------------------ sampler
+@pytest.mark.parametrize("geom", [(2, 0, 4, 4), (2, 0, 14, 14), (64, 1, 14, 14), (3, 1, 5, 7), (1, 2, 3, 3),
+                                  (2, 1, 1, 6), (1, 0, 1, 1), (2, 0, 50, 84), (2, 0, 100, 168)])
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_sampler_bit_exact(geom, k):
+    B, P, H, W = geom
+    for mode in (sbp.GRID_PER_CELL, sbp.GRID_SHARED):
+        for per_sample in (True, False):
+            seed, stream = 12345 + k, 1000 * k + mode
+            idx, inv = sbp.sample_indices(B, P, H, W, k, seed, stream, mode=mode, per_sample=per_sample,
+                                          want_inv=True)
+            want = oracle.sample_indices(B, P, H, W, k, seed, stream, mode=mode, per_sample=per_sample)
+            assert np.array_equal(idx.cpu().numpy(), want)
+            assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(want, B * (P + H * W)))
+
+
+def test_sampler_full_size_detection_map_and_extreme_seeds():
+    B, P, H, W, k = 2, 0, 200, 336, 2
+    for seed, stream in [(0, 0), (2**64 - 1, 2**63 + 11)]:
+        idx, _ = sbp.sample_indices(B, P, H, W, k, seed, stream)
+        want = oracle.sample_indices(B, P, H, W, k, seed, stream)
+        assert idx.numel() == 67200
+        assert np.array_equal(idx.cpu().numpy(), want)
+
+
+def test_sampler_golden_vectors():
+    from test_oracle_sampler import _read_golden
+    for (B, P, H, W, k, mode, ps, seed, stream), want in _read_golden():
+        idx, _ = sbp.sample_indices(B, P, H, W, k, seed, stream, mode=mode, per_sample=bool(ps))
+        assert np.array_equal(idx.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------ forward cache
+@pytest.mark.parametrize("dtype,C", [("f32", 64), ("bf16", 192), ("bf16", 768), ("bf16", 20), ("f32", 7), ("bf16", 3)])
+def test_forward_cache_bit_exact(dtype, C):
+    B, P, H, W = 4, 1, 14, 14
+    M = B * (P + H * W)
+    X = si.normal((M, C), 1.0, 5, dtype)
+    idx_np = oracle.sample_indices(B, P, H, W, 2, 3, 4)
+    idx = torch.from_numpy(idx_np).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idx)
+    want = oracle.forward_cache(bits(X), idx_np)
+    assert np.array_equal(bits(Xk), want)
+
+
+def test_forward_cache_arbitrary_unique_rows_and_empty():
+    M, C = 1000, 128
+    X = si.normal((M, C), 1.0, 6, "bf16")
+    rng = np.random.default_rng(0)
+    idx_np = rng.permutation(M)[:333].astype(np.int32)
+    Xk = sbp.forward_cache(X.cuda(), torch.from_numpy(idx_np).cuda())
+    assert np.array_equal(bits(Xk), bits(X)[idx_np])
+    empty = sbp.forward_cache(X.cuda(), torch.empty(0, dtype=torch.int32, device="cuda"))
+    assert empty.shape == (0, C)
+
+
+# ------------------------------------------------------------------ linear backward
+def _grid_case(B, P, H, W, Cin, Cout, k, dtype, seed):
+    M = B * (P + H * W)
+    X, Wt, dY = si.linear_case(M, Cin, Cout, seed, dtype)
+    idx = oracle.sample_indices(B, P, H, W, k, seed, 1000 + seed)
+    return X, Wt, dY, idx
+
+
+def test_linear_fp32_config():
+    # B=2, 14x14 tokens, 64 -> 256, r = 0.5, seed 0
+    X, W, dY, idx = _grid_case(2, 0, 14, 14, 64, 256, 2, "f32", 0)
+    assert idx.size == 196
+    check_linear(X, W, dY, idx, "f32")
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [(192, 768), (768, 192), (128, 512), (512, 128), (72, 200), (8, 8), (264, 136)])
+def test_linear_bf16_mfma_tiles_and_ragged_tails(shape, k):
+    Cin, Cout = shape
+    # 6 samples of 1 + 14x14 tokens: K spans several 128-row tiles with a ragged tail
+    X, W, dY, idx = _grid_case(6, 1, 14, 14, Cin, Cout, k, "bf16", 10 + k)
+    check_linear(X, W, dY, idx, "bf16")
+
+
+@pytest.mark.parametrize("shape", [(20, 36), (7, 5), (64, 30)])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_linear_plain_path_odd_channels(shape, dtype):
+    Cin, Cout = shape
+    X, W, dY, idx = _grid_case(3, 1, 6, 6, Cin, Cout, 2, dtype, 21)
+    check_linear(X, W, dY, idx, dtype)
+
+
+@pytest.mark.parametrize("flags", [sbp.FLAG_DY_COMPACT, sbp.FLAG_DX_COMPACT, sbp.FLAG_DY_COMPACT | sbp.FLAG_DX_COMPACT])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_linear_compact_flags(flags, dtype):
+    X, W, dY, idx = _grid_case(4, 1, 14, 14, 192, 256, 2, dtype, 31)
+    check_linear(X, W, dY, idx, dtype, flags=flags)
+
+
+def test_linear_vit_tiny_mlp_full_size():
+    # B=64, 197 tokens, 192 -> 768 -> 192, r = 0.5, fresh mask per layer
+    for (Cin, Cout, seed) in [(192, 768, 41), (768, 192, 42)]:
+        X, W, dY, idx = _grid_case(64, 1, 14, 14, Cin, Cout, 2, "bf16", seed)
+        assert idx.size == 6336
+        check_linear(X, W, dY, idx, "bf16")
+
+
+@pytest.mark.parametrize("name,Cin,Cout", [("qkv", 768, 2304), ("proj", 768, 768), ("fc1", 768, 3072), ("fc2", 3072, 768)])
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_linear_vit_base_full_size(name, Cin, Cout, k):
+    X, W, dY, idx = _grid_case(64, 1, 14, 14, Cin, Cout, k, "bf16", 50 + k)
+    assert idx.size == [3200, 6336, 9472, 12608][k - 1]
+    check_linear(X, W, dY, idx, "bf16", check_cache=(k == 2))
+
+
+@pytest.mark.parametrize("geom", [(200, 336, 128, 512), (200, 336, 512, 128), (100, 168, 256, 1024), (100, 168, 1024, 256)])
+def test_linear_convnext_detection_full_size(geom):
+    H, W, Cin, Cout = geom
+    X, Wt, dY, idx = _grid_case(2, 0, H, W, Cin, Cout, 2, "bf16", 61)
+    check_linear(X, Wt, dY, idx, "bf16", check_cache=False)
+
+
+def test_linear_integer_inputs_are_bit_exact():
+    # small integers: every product and partial sum is exact in fp32, so any summation order must
+    # reproduce the oracle bit for bit, and the kept / dropped halves must add up to full backprop
+    B, P, H, W, Cin, Cout = 4, 0, 8, 8, 64, 128
+    M = B * H * W
+    X = si.small_ints((M, Cin), -3, 3, 1, "bf16")
+    Wt = si.small_ints((Cout, Cin), -3, 3, 2, "bf16")
+    dY = si.small_ints((M, Cout), -3, 3, 3, "bf16")
+    idx = oracle.sample_indices(B, P, H, W, 2, 7, 7)
+    comp = np.setdiff1d(np.arange(M), idx).astype(np.int32)
+    outs = []
+    for z in (idx, comp, np.arange(M, dtype=np.int32)):
+        zi = torch.from_numpy(z).cuda()
+        Xk = sbp.forward_cache(X.cuda(), zi)
+        dW, db, dX = sbp.backward_linear(dY.cuda(), zi, Xk, Wt.cuda())
+        rW, rb, rX = oracle.backward_linear(si.to_f64(dY), z, si.to_f64(X)[z], si.to_f64(Wt), M)
+        assert np.array_equal(f64(dW), rW) and np.array_equal(f64(db), rb) and np.array_equal(f64(dX), rX)
+        outs.append((f64(dW), f64(db), f64(dX)))
+    for a, b, full in zip(*outs):
+        assert np.array_equal(a + b, full)
+
+
+def test_linear_dropped_rows_of_dY_are_never_used():
+    X, W, dY, idx = _grid_case(4, 1, 14, 14, 128, 128, 2, "bf16", 71)
+    M = X.shape[0]
+    dropped = np.setdiff1d(np.arange(M), idx)
+    dY2 = dY.clone()
+    dY2[torch.from_numpy(dropped)] = float("nan")
+    idxd = torch.from_numpy(idx).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idxd)
+    a = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda())
+    b = sbp.backward_linear(dY2.cuda(), idxd, Xk, W.cuda())
+    for u, v in zip(a, b):
+        assert np.array_equal(bits(u), bits(v))
+
+
+def test_linear_nothing_kept_and_everything_kept():
+    M, Cin, Cout = 300, 64, 96
+    X, W, dY = si.linear_case(M, Cin, Cout, 81, "bf16")
+    empty = torch.empty(0, dtype=torch.int32, device="cuda")
+    Xk = torch.empty((0, Cin), dtype=torch.bfloat16, device="cuda")
+    dW, db, dX = sbp.backward_linear(dY.cuda(), empty, Xk, W.cuda())
+    assert np.all(bits(dW) == 0) and np.all(bits(db) == 0) and np.all(bits(dX) == 0)
+    check_linear(X, W, dY, np.arange(M, dtype=np.int32), "bf16")
+
+
+def test_linear_accumulate_flag():
+    X, W, dY, idx = _grid_case(2, 1, 14, 14, 64, 128, 2, "bf16", 91)
+    M = X.shape[0]
+    idxd = torch.from_numpy(idx).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idxd)
+    dW0 = torch.full((128, 64), 2.0, dtype=torch.float32, device="cuda")
+    db0 = torch.full((128,), -1.0, dtype=torch.float32, device="cuda")
+    dW, db, _ = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda(), flags=sbp.FLAG_ACCUMULATE_DW, dW=dW0, db=db0)
+    rW, rb, _ = oracle.backward_linear(si.to_f64(dY), idx, si.to_f64(X)[idx], si.to_f64(W), M)
+    assert nerr(f64(dW), rW + 2.0) <= TOL_F32 and nerr(f64(db), rb - 1.0) <= TOL_F32
+
+
+def test_linear_is_deterministic():
+    X, W, dY, idx = _grid_case(8, 1, 14, 14, 256, 256, 2, "bf16", 95)
+    idxd = torch.from_numpy(idx).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idxd)
+    a = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda())
+    b = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda())
+    for u, v in zip(a, b):
+        assert np.array_equal(bits(u), bits(v))
+
+
+def test_two_layer_chain_same_mask_compact():
+    # eq:backward_fc2_sbp_same_drop_loc: one keep-set for both layers of an MLP; the gradient
+    # stays compact between them and is scattered once at the end
+    B, P, H, W, C0, C1, C2 = 4, 1, 14, 14, 64, 256, 64
+    M = B * (P + H * W)
+    X0, W0, _ = si.linear_case(M, C0, C1, 101, "bf16")
+    X1, W1, dY2 = si.linear_case(M, C1, C2, 102, "bf16")
+    idx = oracle.sample_indices(B, P, H, W, 2, 5, 5)
+    idxd = torch.from_numpy(idx).cuda()
+    X0k, X1k = sbp.forward_cache(X0.cuda(), idxd), sbp.forward_cache(X1.cuda(), idxd)
+    dW1, db1, g = sbp.backward_linear(dY2.cuda(), idxd, X1k, W1.cuda(), flags=sbp.FLAG_DX_COMPACT)
+    dW0, db0, dX0 = sbp.backward_linear(g, idxd, X0k, W0.cuda(), M=M, flags=sbp.FLAG_DY_COMPACT)
+    # oracle: same chain through the full-size zero-filled gradient, with the GPU's bf16 rounding of g
+    rW1, rb1, rg = oracle.backward_linear(si.to_f64(dY2), idx, si.to_f64(X1)[idx], si.to_f64(W1), M)
+    assert nerr(f64(g), rg[idx]) <= TOL_BF16_TIGHT
+    g_full = np.zeros((M, C1))
+    g_full[idx] = f64(g)
+    rW0, rb0, rX0 = oracle.backward_linear(g_full, idx, si.to_f64(X0)[idx], si.to_f64(W0), M)
+    assert nerr(f64(dW0), rW0) <= TOL_F32 and nerr(f64(db0), rb0) <= TOL_F32
+    assert nerr(f64(dX0), rX0) <= TOL_BF16_TIGHT
+    dropped = np.setdiff1d(np.arange(M), idx)
+    assert np.all(bits(dX0)[dropped] == 0)
+
+
+# ------------------------------------------------------------------ depthwise backward
+def _check_dw(B, H, W, C, ks, k, dtype, seed, use_inv):
+    X, Wd, dY = si.dwconv_case(B, H, W, C, ks, seed, dtype)
+    idx_np = oracle.sample_indices(B, 0, H, W, k, seed, 77)
+    idx = torch.from_numpy(idx_np).cuda()
+    inv = torch.from_numpy(oracle.inverse_map(idx_np, B * H * W)).cuda() if use_inv else None
+    dWd, db, dX = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+    rWd, rb, rX = oracle.backward_dwconv(si.to_f64(dY), idx_np, si.to_f64(X), si.to_f64(Wd), ks // 2)
+    assert nerr(f64(dWd), rWd) <= TOL_F32
+    assert nerr(f64(db), rb) <= TOL_F32
+    assert nerr(f64(dX), rX) <= (TOL_F32 if dtype == "f32" else TOL_BF16_TIGHT)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("k", [1, 2, 4])
+def test_dwconv_small(dtype, k):
+    _check_dw(2, 10, 12, 64, 7, k, dtype, 111, use_inv=(k == 2))
+
+
+@pytest.mark.parametrize("geom", [(1, 7, 9, 24, 7), (2, 5, 5, 8, 3), (1, 3, 20, 130, 7), (1, 16, 16, 6, 5)])
+def test_dwconv_odd_shapes(geom):
+    B, H, W, C, ks = geom
+    _check_dw(B, H, W, C, ks, 2, "bf16", 121, use_inv=False)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4])
+def test_dwconv_convnext_stage3_full_size(k):
+    _check_dw(2, 50, 84, 512, 7, k, "bf16", 131, use_inv=True)
+
+
+def test_dwconv_single_kept_position_stamps_kernel():
+    B, H, W, C, ks = 1, 9, 11, 64, 7
+    X, Wd, dY = si.dwconv_case(B, H, W, C, ks, 141, "f32")
+    y0, x0 = 4, 5
+    idx = torch.tensor([y0 * W + x0], dtype=torch.int32, device="cuda")
+    dWd, db, dX = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda())
+    g = f64(dY)[0, y0, x0]
+    want = np.zeros((B, H, W, C))
+    want[0, y0 - 3:y0 + 4, x0 - 3:x0 + 4] = f64(Wd) * g
+    assert nerr(f64(dX), want) <= TOL_F32
+    assert nerr(f64(dWd), f64(X)[0, y0 - 3:y0 + 4, x0 - 3:x0 + 4] * g) <= TOL_F32
+    assert nerr(f64(db), g) <= TOL_F32
+
+
+def test_convnext_block_chain():
+    # pw2 backward -> pw1 backward (scattered, zero rows) -> depthwise backward on kept outputs
+    B, H, W, C, E = 2, 12, 16, 64, 256
+    M = B * H * W
+    idx_np = oracle.sample_indices(B, 0, H, W, 2, 9, 9)
+    idx = torch.from_numpy(idx_np).cuda()
+    Xd, Wdw, _ = si.dwconv_case(B, H, W, C, 7, 151, "bf16")
+    X1, W1, _ = si.linear_case(M, C, E, 152, "bf16")
+    X2, W2, dY = si.linear_case(M, E, C, 153, "bf16")
+    X1k, X2k = sbp.forward_cache(X1.cuda(), idx), sbp.forward_cache(X2.cuda(), idx)
+    _, _, g2 = sbp.backward_linear(dY.cuda(), idx, X2k, W2.cuda(), flags=sbp.FLAG_DX_COMPACT)
+    _, _, g1 = sbp.backward_linear(g2, idx, X1k, W1.cuda(), M=M, flags=sbp.FLAG_DY_COMPACT)
+    dWd, db, dX = sbp.backward_dwconv(g1.view(B, H, W, C), idx, Xd.cuda(), Wdw.cuda())
+    # oracle on the GPU's own (rounded) intermediate so that only the depthwise step is compared
+    rWd, rb, rX = oracle.backward_dwconv(f64(g1).reshape(B, H, W, C), idx_np, si.to_f64(Xd), si.to_f64(Wdw), 3)
+    assert nerr(f64(dWd), rWd) <= TOL_F32 and nerr(f64(db), rb) <= TOL_F32
+    assert nerr(f64(dX), rX) <= TOL_BF16_TIGHT
+    # since g1 is zero off the keep-set, a dense depthwise backward of g1 gives the same result
+    full = np.arange(M, dtype=np.int32)
+    fWd, fb, fX = oracle.backward_dwconv(f64(g1).reshape(B, H, W, C), full, si.to_f64(Xd), si.to_f64(Wdw), 3)
+    assert np.array_equal(fWd, rWd) and np.array_equal(fX, rX)
