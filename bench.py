@@ -1,0 +1,327 @@
+#!/usr/bin/env python3
+"""Benchmark of the SBP hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload vit_base] [--ratio 0.5]
+
+One "step" is one pass of the whole path over one synthetic batch of the workload: for every
+block, draw a fresh grid-wise keep-set, cache the kept input rows of every linear layer
+(forward side), then run the token-subset backward (dW, db, dX) of every linear layer; workloads
+with a depthwise conv add its kept-position backward.  Inputs are resident in HBM before the
+timed region.  Prints ONE JSON line.
+
+value = useful contraction work (4 K Cin Cout flop per linear, + 4 ks^2 K C for the depthwise
+conv) of a step divided by the step's wall time, everything included.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "SBP backward TFLOP/s at keep r=0.5 + speedup vs r=1 on one MI355X"
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vit_base")
+    ap.add_argument("--ratio", type=float, default=0.5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the side measurements of the other workloads")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    return ap.parse_args()
+
+
+class LinearLayer:
+    """Device buffers and pre-marshalled library calls of one linear layer of one block."""
+
+    def __init__(self, sbp, torch, L, shape, M, Kmax, dtype, src, ws, stream):
+        self.Cin, self.Cout = shape.Cin, shape.Cout
+        X, W, dY = src
+        self.X, self.W, self.dY = X.clone(), W.clone(), dY.clone()     # own memory per block
+        self.Xk = torch.empty((Kmax, self.Cin), dtype=X.dtype, device="cuda")
+        self.code = sbp.BF16 if dtype == "bf16" else sbp.F32
+        self.M = M
+        self.L = L
+        self.ws = ws
+        self.stream = stream
+
+    def bind_outputs(self, dW, db, dX):
+        self.dW, self.db, self.dX = dW, db, dX
+
+    def cache(self, idx_ptr, K):
+        return self.L.sbp_forward_cache(self.X.data_ptr(), idx_ptr, self.M, K, self.Cin, self.code,
+                                        self.Xk.data_ptr(), self.stream)
+
+    def backward(self, idx_ptr, K):
+        return self.L.sbp_backward_linear(self.dY.data_ptr(), idx_ptr, self.Xk.data_ptr(), self.W.data_ptr(), self.M,
+                                          K, self.Cin, self.Cout, self.code, self.dW.data_ptr(), self.db.data_ptr(),
+                                          self.dX.data_ptr(), self.ws.data_ptr(), self.ws.numel(), 0, self.stream)
+
+
+class Job:
+    """All buffers of a workload and a step() that enqueues one pass of the path."""
+
+    def __init__(self, wl, torch, sbp, si):
+        from paper_2210_00129_amd import _lib
+        self.wl, self.torch, self.sbp = wl, torch, sbp
+        self.L = _lib.lib()
+        self.check = _lib.check
+        self.stream = torch.cuda.current_stream().cuda_stream
+        M = wl.M
+        self.M = M
+        self.code = sbp.BF16 if wl.dtype == "bf16" else sbp.F32
+        ws_bytes = 256
+        for s in wl.linears:
+            for k in (1, 2, 3, 4):
+                K = sbp.keep_count(wl.B, wl.P, wl.H, wl.W, k)
+                ws_bytes = max(ws_bytes, sbp.backward_linear_workspace(M, K, s.Cin, s.Cout, self.code, 0))
+        if wl.dw_channels:
+            ws_bytes = max(ws_bytes, sbp.backward_dwconv_workspace(wl.B, wl.H, wl.W, wl.dw_channels, 7, M, self.code, 0))
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        self.idx = torch.empty(M, dtype=torch.int32, device="cuda")
+        self.inv = torch.empty(M, dtype=torch.int32, device="cuda") if wl.dw_channels else None
+        # one seeded CPU draw per layer shape, copied into separate device buffers for every block so
+        # that successive blocks do not hit each other's data in the 256 MB last-level cache
+        srcs = [tuple(t.cuda() for t in si.linear_case(M, s.Cin, s.Cout, 100 + i, wl.dtype))
+                for i, s in enumerate(wl.linears)]
+        self.blocks = []
+        for _ in range(wl.blocks):
+            self.blocks.append([LinearLayer(sbp, torch, self.L, s, M, M, wl.dtype, srcs[i], self.ws, self.stream)
+                                for i, s in enumerate(wl.linears)])
+        del srcs
+        # outputs are shared by all blocks (a training loop hands them to the optimizer / previous layer)
+        tdt = si.torch_dtype(wl.dtype)
+        outs = [(torch.empty((s.Cout, s.Cin), dtype=torch.float32, device="cuda"),
+                 torch.empty((s.Cout,), dtype=torch.float32, device="cuda"),
+                 torch.empty((M, s.Cin), dtype=tdt, device="cuda")) for s in wl.linears]
+        for blk in self.blocks:
+            for lay, o in zip(blk, outs):
+                lay.bind_outputs(*o)
+        self.outs = outs
+        if wl.dw_channels:
+            C = wl.dw_channels
+            self.dw_in = [tuple(t.cuda() for t in si.dwconv_case(wl.B, wl.H, wl.W, C, 7, 200 + b, wl.dtype))
+                          for b in range(wl.blocks)]
+            self.dw_out = (torch.empty((7, 7, C), dtype=torch.float32, device="cuda"),
+                           torch.empty((C,), dtype=torch.float32, device="cuda"),
+                           torch.empty((wl.B, wl.H, wl.W, C), dtype=tdt, device="cuda"))
+        self.desc = sbp.make_desc(wl.B, wl.P, wl.H, wl.W, 2, 0, 0)
+        self.step_no = 0
+
+    def set_ratio(self, r):
+        self.k = self.sbp.k_from_ratio(r)
+        self.desc.k = self.k
+        self.K = self.sbp.keep_count(self.wl.B, self.wl.P, self.wl.H, self.wl.W, self.k)
+
+    def flops_per_step(self):
+        f = sum(4.0 * self.K * s.Cin * s.Cout for s in self.wl.linears)
+        if self.wl.dw_channels:
+            f += 4.0 * 49 * self.K * self.wl.dw_channels
+        return f * self.wl.blocks
+
+    def step(self):
+        L, check = self.L, self.check
+        idx_ptr, K = self.idx.data_ptr(), self.K
+        inv_ptr = self.inv.data_ptr() if self.inv is not None else None
+        self.step_no += 1
+        for b, blk in enumerate(self.blocks):
+            self.desc.stream_id = self.step_no * 1000 + b          # fresh mask for every block and step
+            check(L.sbp_sample_indices(ctypes.byref(self.desc), idx_ptr, self.M, inv_ptr, self.stream))
+            for lay in blk:                                         # forward side: keep only the kept rows
+                check(lay.cache(idx_ptr, K))
+            for lay in reversed(blk):                               # backward side
+                check(lay.backward(idx_ptr, K))
+            if self.wl.dw_channels:
+                X, Wd, dY = self.dw_in[b]
+                dWd, db, dX = self.dw_out
+                wl = self.wl
+                check(L.sbp_backward_dwconv(dY.data_ptr(), idx_ptr, inv_ptr, X.data_ptr(), Wd.data_ptr(), wl.B, wl.H,
+                                            wl.W, wl.dw_channels, 7, 3, K, self.code, dWd.data_ptr(), db.data_ptr(),
+                                            dX.data_ptr(), self.ws.data_ptr(), self.ws.numel(), 0, self.stream))
+
+    def time_steps(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return max(e0.elapsed_time(e1) / steps, 0.0), wall
+
+    def kernel_breakdown(self, steps):
+        """Second pass with every launch bracketed by HIP events: per-class average durations."""
+        sbp, torch = self.sbp, self.torch
+        torch.cuda.synchronize()
+        sbp.profile_read(reset=True)
+        sbp.profile_enable(True)
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        sbp.profile_enable(False)
+        return sbp.profile_read(reset=True)
+
+    def algorithmic_bytes_per_step(self):
+        """Bytes the method itself must move: kept rows in, gradients out (dX at full size)."""
+        s_ = 2 if self.wl.dtype == "bf16" else 4
+        K, M = self.K, self.M
+        total = 4 * K                                                       # idx written by the sampler
+        for s in self.wl.linears:
+            total += 2 * K * s.Cin * s_ + 4 * K                             # cache gather
+            total += s_ * (K * s.Cout + K * s.Cin + s.Cout * s.Cin + M * s.Cin) + 4 * s.Cout * s.Cin + 4 * s.Cout + 4 * K
+        if self.wl.dw_channels:
+            C = self.wl.dw_channels
+            total += s_ * (K * C + 2 * M * C) + 49 * C * (s_ + 4)
+        return total * self.wl.blocks
+
+
+def cpu_baseline(wl, r, seconds, si):
+    """The fp64 oracle, as it stands, on the host cores: whole blocks of the same workload until the
+    time budget is used (at least one block)."""
+    import numpy as np
+    import oracle
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    k = oracle.k_from_ratio(r)
+    M = wl.M
+    data = [tuple(si.to_f64(t) for t in si.linear_case(M, s.Cin, s.Cout, 100 + i, wl.dtype))
+            for i, s in enumerate(wl.linears)]
+    dwd = None
+    if wl.dw_channels:
+        dwd = tuple(si.to_f64(t) for t in si.dwconv_case(wl.B, wl.H, wl.W, wl.dw_channels, 7, 200, wl.dtype))
+    flops, blocks, t0 = 0.0, 0, time.perf_counter()
+    while blocks < wl.blocks and (blocks == 0 or time.perf_counter() - t0 < seconds):
+        idx = oracle.sample_indices(wl.B, wl.P, wl.H, wl.W, k, 0, 1000 + blocks)
+        K = idx.size
+        for (X, W, dY), s in zip(data, wl.linears):
+            Xk = oracle.forward_cache(X, idx)
+            oracle.backward_linear(dY, idx, Xk, W, M)
+            flops += 4.0 * K * s.Cin * s.Cout
+        if dwd is not None:
+            oracle.backward_dwconv(dwd[2], idx, dwd[0], dwd[1], 3)
+            flops += 4.0 * 49 * K * wl.dw_channels
+        blocks += 1
+    dt = time.perf_counter() - t0
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{blocks} of {wl.blocks} block(s) of {wl.name} at r={r} (fp64 numpy oracle incl. its "
+                      f"python sampler), {dt:.1f} s"}
+
+
+def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3):
+    wl = si.WORKLOADS[name]
+    job = Job(wl, torch, sbp, si)
+    out = {"workload": name}
+    for rr in (r, 1.0):
+        job.set_ratio(rr)
+        ms, _ = job.time_steps(steps, warmup)
+        tag = f"r{rr:g}"
+        out[tag] = {"ms_per_step": round(ms, 4), "tflops": round(job.flops_per_step() / ms / 1e9, 2),
+                    "algorithmic_gbs": round(job.algorithmic_bytes_per_step() / ms / 1e6, 1)}
+    out["speedup_vs_r1"] = round(out["r1"]["ms_per_step"] / out[f"r{r:g}"]["ms_per_step"], 3)
+    del job
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py measures one GPU: this path has no multi-GPU leg (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2210_00129_amd as sbp
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    wl = si.WORKLOADS[args.workload]
+    job = Job(wl, torch, sbp, si)
+
+    job.set_ratio(args.ratio)
+    ms, wall_ms = job.time_steps(args.steps, args.warmup)
+    flops = job.flops_per_step()
+    value = flops / ms / 1e9                       # TFLOP/s
+    bytes_step = job.algorithmic_bytes_per_step()
+    K_r = job.K
+    prof = job.kernel_breakdown(max(2, min(args.steps, 5)))
+
+    # dominant kernel and its roofline
+    gemm_flops = {"dw_gemm": 2.0, "dx_gemm": 2.0}
+    per_launch = {}
+    for cls in ("dw_gemm", "dx_gemm"):
+        tot_ms, n = prof[cls]
+        if n:
+            fl = sum(gemm_flops[cls] * K_r * s.Cin * s.Cout for s in wl.linears) / len(wl.linears)
+            per_launch[cls] = (tot_ms / n, fl)
+    dom = max(per_launch, key=lambda c: prof[c][0]) if per_launch else None
+    roofline = None
+    if dom:
+        avg_ms, fl = per_launch[dom]
+        achieved = fl / avg_ms / 1e9
+        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "avg_launch_us": round(avg_ms * 1e3, 2),
+                    "flops_per_launch": fl}
+    breakdown = {c: {"ms_per_step": round(v[0] / max(2, min(args.steps, 5)), 4), "launches": v[1]}
+                 for c, v in prof.items() if v[1]}
+
+    # same kernels at r = 1
+    job.set_ratio(1.0)
+    ms_full, _ = job.time_steps(max(3, args.steps // 2), 2)
+    job.set_ratio(args.ratio)
+    s_ = 2 if wl.dtype == "bf16" else 4
+    cached = sum(K_r * s.Cin * s_ + 4 * K_r for s in wl.linears)
+    full = sum(wl.M * s.Cin * s_ for s in wl.linears)
+
+    result = {
+        "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B}, {wl.N} tokens, {wl.blocks} blocks x "
+                               f"{[(s.name, s.Cin, s.Cout) for s in wl.linears]}, grid-wise 2x2 keep r={args.ratio}",
+                   "keep_ratio": args.ratio, "K": K_r, "M": wl.M},
+        "speedup_vs_r1": round(ms_full / ms, 3), "ms_per_step_r1": round(ms_full, 4),
+        "ideal_flop_ratio_vs_r1": round(wl.M / K_r, 3),
+        "host_wall_ms_per_step": round(wall_ms, 4),
+        "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "algorithmic_gbs": round(bytes_step / ms / 1e6, 1),
+        "activation_memory_saving": round(1.0 - cached / full, 4),
+        "kernel_breakdown": breakdown,
+        "roofline": roofline,
+    }
+    del job
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        extras = []
+        for name in ("vit_tiny_mlp", "convnext_det_s1", "convnext_det_s2", "convnext_s3_block"):
+            if name != wl.name:
+                extras.append(measure_extra(name, args.ratio, torch, sbp, si))
+        result["other_workloads"] = extras
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, args.ratio, args.cpu_seconds, si)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -166,6 +166,29 @@ int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* i
                             float* dWd, float* db, void* dX,
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
+/*
+ * Measurement aid (not a step of the method; for benchmarks only).  While enabled, every kernel
+ * launch of the library is bracketed by a pair of HIP events on the caller's stream; this is the
+ * one place where the library creates HIP objects (the events, destroyed again by the read call).
+ * sbp_profile_read waits for the recorded events, adds the elapsed times of the kernels of class
+ * `which` to *total_ms and their number to *launches (host pointers), and forgets all records when
+ * which == SBP_PROF_RESET.  Not thread-safe; do not enable under graph capture.
+ */
+#define SBP_PROF_SAMPLE      0
+#define SBP_PROF_GATHER      1
+#define SBP_PROF_DW_GEMM     2   /* dW contraction (MFMA) */
+#define SBP_PROF_DX_GEMM     3   /* dX contraction (MFMA) */
+#define SBP_PROF_REDUCE      4   /* split reduction of dW / db */
+#define SBP_PROF_COLSUM      5   /* db column sums */
+#define SBP_PROF_ZERO_ROWS   6   /* marking kept rows + zero-filling dropped rows of dX */
+#define SBP_PROF_DWCONV_DX   7
+#define SBP_PROF_DWCONV_DW   8
+#define SBP_PROF_OTHER       9
+#define SBP_PROF_NCLASSES   10
+#define SBP_PROF_RESET     (-1)
+int32_t sbp_profile_enable(int32_t on);
+int32_t sbp_profile_read(int32_t which, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -147,3 +147,25 @@ def backward_dwconv(dY, idx, X, Wd, inv=None, want=("dWd", "db", "dX"), dWd=None
         K, code, _dev(dWd, "dWd"), _dev(db, "db"), _dev(dX, "dX"), _dev(workspace, "workspace"),
         workspace.numel(), 0, _stream(dev)))
     return dWd, db, dX
+
+
+PROF_CLASSES = ("sample", "gather", "dw_gemm", "dx_gemm", "reduce", "colsum", "zero_rows", "dwconv_dx",
+                "dwconv_dw", "other")
+
+
+def profile_enable(on: bool) -> None:
+    """Benchmark aid: bracket every kernel launch of the library with HIP events."""
+    _lib.check(_lib.lib().sbp_profile_enable(1 if on else 0))
+
+
+def profile_read(reset: bool = True) -> dict:
+    """Per kernel class: (total milliseconds, launches) recorded since the last reset."""
+    import ctypes
+    out = {}
+    for i, name in enumerate(PROF_CLASSES):
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        _lib.check(_lib.lib().sbp_profile_read(i, ctypes.byref(ms), ctypes.byref(n)))
+        out[name] = (ms.value, n.value)
+    if reset:
+        _lib.check(_lib.lib().sbp_profile_read(-1, None, None))
+    return out

@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cmath>
+#include <vector>
 
 #include "sbp_internal.h"
 
@@ -22,6 +23,25 @@ int32_t check_launch(const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SBP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
   return SBP_OK;
+}
+
+// ---- measurement aid --------------------------------------------------------------------------
+struct ProfRec { int cls; hipEvent_t a, b; };
+static bool g_prof_on = false;
+static std::vector<ProfRec>* g_prof = nullptr;
+
+ProfScope::ProfScope(int cls, hipStream_t s) : cls_(cls), s_(s), rec_(nullptr) {
+  if (!g_prof_on) return;
+  if (!g_prof) g_prof = new std::vector<ProfRec>();
+  ProfRec r{cls, nullptr, nullptr};
+  if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+  (void)hipEventRecord(r.a, s);
+  g_prof->push_back(r);
+  rec_ = reinterpret_cast<void*>(g_prof->size());   // index + 1
+}
+ProfScope::~ProfScope() {
+  if (!rec_) return;
+  (void)hipEventRecord((*g_prof)[reinterpret_cast<size_t>(rec_) - 1].b, s_);
 }
 
 static int32_t validate_desc(const sbp_sample_desc* d) {
@@ -91,12 +111,12 @@ int32_t sbp_sample_indices(const sbp_sample_desc* d, int32_t* idx, int64_t idx_c
 
 int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t K, int32_t C, int32_t dtype,
                           void* Xk, void* stream) {
-  if (!X || !idx || !Xk) return fail(SBP_ERR_NULL, "X, idx and X_k must be non-NULL");
   int eb = elem_bytes(dtype);
   if (!eb) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
   if (M < 1 || M > INT32_MAX || C < 1) return fail(SBP_ERR_SHAPE, "bad shape M=%lld C=%d", (long long)M, C);
   if (K < 0 || K > M) return fail(SBP_ERR_SHAPE, "need 0 <= K <= M, got K=%lld M=%lld", (long long)K, (long long)M);
-  if (K == 0) return SBP_OK;
+  if (K == 0) return SBP_OK;   // nothing to gather (empty tensors may have NULL storage)
+  if (!X || !idx || !Xk) return fail(SBP_ERR_NULL, "X, idx and X_k must be non-NULL");
   return launch_gather_rows(X, idx, K, C, eb, Xk, (hipStream_t)stream);
 }
 
@@ -175,6 +195,36 @@ int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* i
   if (!dWd && !db && !dX) return SBP_OK;
   return launch_backward_dwconv(p, dY, idx, inv, X, Wd, B, H, W, C, ks, pad, K, dtype, dWd, db, dX, ws,
                                 (hipStream_t)stream);
+}
+
+int32_t sbp_profile_enable(int32_t on) {
+  g_prof_on = on != 0;
+  return SBP_OK;
+}
+
+int32_t sbp_profile_read(int32_t which, double* total_ms, int64_t* launches) {
+  if (which != SBP_PROF_RESET && (which < 0 || which >= SBP_PROF_NCLASSES))
+    return fail(SBP_ERR_FLAGS, "unknown kernel class %d", which);
+  if (which != SBP_PROF_RESET && (!total_ms || !launches)) return fail(SBP_ERR_NULL, "output pointer is NULL");
+  if (!g_prof) return SBP_OK;
+  if (which == SBP_PROF_RESET) {
+    for (auto& r : *g_prof) {
+      (void)hipEventSynchronize(r.b);
+      (void)hipEventDestroy(r.a);
+      (void)hipEventDestroy(r.b);
+    }
+    g_prof->clear();
+    return SBP_OK;
+  }
+  for (auto& r : *g_prof) {
+    if (r.cls != which) continue;
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess)
+      return fail(SBP_ERR_HIP, "event timing failed");
+    *total_ms += ms;
+    *launches += 1;
+  }
+  return SBP_OK;
 }
 
 }  // extern "C"

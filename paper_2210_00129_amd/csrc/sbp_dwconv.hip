@@ -125,15 +125,15 @@ static void launch_dw_typed(const DwPlan& p, const T* dY, const int32_t* idx, co
   if (dX) {
     const long long total = (long long)B * H * W * C;
     unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, DW_THREADS), 1 << 20);
-    hipLaunchKernelGGL((dw_dx_kernel<T, KS>), dim3(blocks), dim3(DW_THREADS), 0, s, dY, inv, Wd, B, H, W, C, dX);
+    SBP_LAUNCH(SBP_PROF_DWCONV_DX, s, (dw_dx_kernel<T, KS>), dim3(blocks), dim3(DW_THREADS), 0, s, dY, inv, Wd, B, H, W, C, dX);
   }
   if (dWd || db) {
     const int n = (KS * KS + 1) * C;
     const int per_slice = (int)ceil_div(std::max<int64_t>(K, 1), p.nparts);
     dim3 grid((unsigned)ceil_div(n, DW_THREADS), p.nparts);
-    hipLaunchKernelGGL((dw_dw_kernel<T, KS>), grid, dim3(DW_THREADS), 0, s, dY, idx, X, H, W, C, (int)K, per_slice,
+    SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_dw_kernel<T, KS>), grid, dim3(DW_THREADS), 0, s, dY, idx, X, H, W, C, (int)K, per_slice,
                        part);
-    hipLaunchKernelGGL(dw_reduce_kernel, dim3((unsigned)ceil_div(n, DW_THREADS)), dim3(DW_THREADS), 0, s, part,
+    SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, dw_reduce_kernel, dim3((unsigned)ceil_div(n, DW_THREADS)), dim3(DW_THREADS), 0, s, part,
                        p.nparts, KS * KS, C, dWd, db);
   }
 }
@@ -148,10 +148,10 @@ int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* i
   const long long npos = (long long)B * H * W;
   const int32_t* inv = inv_in;
   if (!inv && dX) {      // build the inverse map from idx
-    hipLaunchKernelGGL(dw_fill_kernel, dim3((unsigned)std::min<long long>(ceil_div(npos, DW_THREADS), 4096)),
+    SBP_LAUNCH(SBP_PROF_OTHER, s, dw_fill_kernel, dim3((unsigned)std::min<long long>(ceil_div(npos, DW_THREADS), 4096)),
                        dim3(DW_THREADS), 0, s, inv_ws, npos, -1);
     if (K > 0)
-      hipLaunchKernelGGL(dw_mark_kernel, dim3((unsigned)ceil_div(K, DW_THREADS)), dim3(DW_THREADS), 0, s, idx, (int)K,
+      SBP_LAUNCH(SBP_PROF_OTHER, s, dw_mark_kernel, dim3((unsigned)ceil_div(K, DW_THREADS)), dim3(DW_THREADS), 0, s, idx, (int)K,
                          inv_ws);
     inv = inv_ws;
   }

@@ -56,17 +56,17 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
     long long blocks = ceil_div(total, 256LL * U);
     if (blocks > 256 * 16) blocks = 256 * 16;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(gather_rows_vec16<U>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)X, idx,
+    SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_vec16<U>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)X, idx,
                        (long long)K, ppr, (uint4*)Xk);
   } else {
     const long long total = K * C;
     long long blocks = ceil_div(total, 256);
     if (blocks > 256 * 32) blocks = 256 * 32;
     if (elem_bytes == 4)
-      hipLaunchKernelGGL(gather_rows_elem<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint32_t*)X,
+      SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_elem<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint32_t*)X,
                          idx, (long long)K, C, (uint32_t*)Xk);
     else
-      hipLaunchKernelGGL(gather_rows_elem<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint16_t*)X,
+      SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_elem<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint16_t*)X,
                          idx, (long long)K, C, (uint16_t*)Xk);
   }
   return check_launch("gather_rows");

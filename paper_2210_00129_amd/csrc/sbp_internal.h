@@ -15,6 +15,21 @@ int32_t fail(int32_t code, const char* fmt, ...);
 // Turns the state left by a kernel launch into a status code.
 int32_t check_launch(const char* what);
 
+// Brackets the launches issued during its lifetime with a pair of events when profiling is on.
+struct ProfScope {
+  ProfScope(int cls, hipStream_t s);
+  ~ProfScope();
+  int cls_;
+  hipStream_t s_;
+  void* rec_;
+};
+
+#define SBP_LAUNCH(cls, stream, ...)             \
+  do {                                            \
+    ::sbp::ProfScope _prof_scope((cls), (stream)); \
+    hipLaunchKernelGGL(__VA_ARGS__);              \
+  } while (0)
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 

@@ -547,18 +547,18 @@ static int32_t launch_plain(const LinearPlan& p, const T* dY, const int32_t* idx
   if (want_dw) {
     long long nW = (long long)Cin * Cout;
     dim3 grid((unsigned)std::min<long long>(ceil_div(nW, NTHREADS), 8192), p.splits);
-    hipLaunchKernelGGL((plain_dw_kernel<T>), grid, dim3(NTHREADS), 0, s, dY, idx_in, Xk, (int)K, Cin, Cout,
+    SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (plain_dw_kernel<T>), grid, dim3(NTHREADS), 0, s, dY, idx_in, Xk, (int)K, Cin, Cout,
                        p.rows_per_split, part);
   }
   if (want_db) {
     dim3 grid((unsigned)ceil_div(Cout, NTHREADS), p.splits);
-    hipLaunchKernelGGL((plain_db_kernel<T>), grid, dim3(NTHREADS), 0, s, dY, idx_in, (int)K, Cout,
+    SBP_LAUNCH(SBP_PROF_COLSUM, s, (plain_db_kernel<T>), grid, dim3(NTHREADS), 0, s, dY, idx_in, (int)K, Cout,
                        p.rows_per_split, dbp);
   }
   if (dX) {
     long long total = (long long)K * Cin;
     unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 65535);
-    hipLaunchKernelGGL((plain_dx_kernel<T>), dim3(blocks), dim3(NTHREADS), 0, s, dY, idx_in, idx_out, W,
+    SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (plain_dx_kernel<T>), dim3(blocks), dim3(NTHREADS), 0, s, dY, idx_in, idx_out, W,
                        (long long)K, Cin, Cout, dX);
   }
   return SBP_OK;
@@ -569,7 +569,7 @@ static void launch_dx_mfma(const uint16_t* dY, const int32_t* idx_in, const int3
                            int K, int Cin, int Cout, uint16_t* dX, hipStream_t s) {
   const int tiles = (int)(ceil_div(K, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  hipLaunchKernelGGL((dx_mfma_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), lds, s, dY, idx_in, idx_out, W, K, Cin,
+  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), lds, s, dY, idx_in, idx_out, W, K, Cin,
                      Cout, dX);
 }
 
@@ -578,7 +578,7 @@ static void launch_dw_mfma(const uint16_t* dY, const int32_t* idx, const uint16_
                            int splits, int rps, float* part, hipStream_t s) {
   const int tiles = (int)(ceil_div(Cout, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  hipLaunchKernelGGL((dw_mfma_kernel<BM, BN>), dim3(tiles, splits), dim3(NTHREADS), lds, s, dY, idx, Xk, K, Cin,
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN>), dim3(tiles, splits), dim3(NTHREADS), lds, s, dY, idx, Xk, K, Cin,
                      Cout, rps, part);
 }
 
@@ -597,18 +597,18 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
 
   if (K == 0) {  // nothing kept: gradients are zero
     if (!accumulate) {
-      if (dW) hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(NTHREADS), 0, s, (uint32_t*)dW, nW);
-      if (db) hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(NTHREADS), 0, s, (uint32_t*)db, (long long)Cout);
+      if (dW) SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(256), dim3(NTHREADS), 0, s, (uint32_t*)dW, nW);
+      if (db) SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(1), dim3(NTHREADS), 0, s, (uint32_t*)db, (long long)Cout);
     }
     if (dX && !dx_compact)
-      hipLaunchKernelGGL(fill_zero_kernel, dim3(1024), dim3(NTHREADS), 0, s, (uint32_t*)dX,
+      SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(1024), dim3(NTHREADS), 0, s, (uint32_t*)dX,
                          (long long)M * Cin * eb / 4);
     return check_launch("backward_linear (K = 0)");
   }
 
   const bool scatter = dX && !dx_compact;
   if (scatter)
-    hipLaunchKernelGGL(mark_rows_kernel, dim3((unsigned)ceil_div(K, NTHREADS)), dim3(NTHREADS), 0, s, idx, (int)K, inv);
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, mark_rows_kernel, dim3((unsigned)ceil_div(K, NTHREADS)), dim3(NTHREADS), 0, s, idx, (int)K, inv);
 
   const bool aligned = ((uintptr_t)dY % 16 == 0) && ((uintptr_t)Xk % 16 == 0) && ((uintptr_t)W % 16 == 0) &&
                        ((uintptr_t)dX % 16 == 0);
@@ -616,7 +616,7 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     const uint16_t* dYh = static_cast<const uint16_t*>(dY);
     if (db) {
       dim3 grid((unsigned)ceil_div(Cout, 256), p.splits);
-      hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(NTHREADS), 0, s, dYh, idx_in, (int)K, Cout, p.rows_per_split,
+      SBP_LAUNCH(SBP_PROF_COLSUM, s, colsum_bf16_kernel, grid, dim3(NTHREADS), 0, s, dYh, idx_in, (int)K, Cout, p.rows_per_split,
                          dbp);
     }
     if (dW)
@@ -637,12 +637,12 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     if (nW % 4 == 0) {
       const long long total = (dW ? nW / 4 : 0) + (db ? Cout : 0);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
-      hipLaunchKernelGGL(reduce_splits_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW, dbp,
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW, dbp,
                          p.splits, Cout, db, accumulate);
     } else {
       const long long total = (dW ? nW : 0) + (db ? Cout : 0);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
-      hipLaunchKernelGGL(reduce_splits_scalar_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW,
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_scalar_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW,
                          dbp, Cout, db, accumulate);
     }
   }
@@ -652,15 +652,15 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     if (row_bytes % 16 == 0 && (uintptr_t)dX % 16 == 0) {
       const int ppr = (int)(row_bytes / 16);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * ppr, NTHREADS), 8192);
-      hipLaunchKernelGGL(zero_dropped_rows_kernel, dim3(blocks), dim3(NTHREADS), 0, s, idx, inv, (int)K,
+      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, zero_dropped_rows_kernel, dim3(blocks), dim3(NTHREADS), 0, s, idx, inv, (int)K,
                          (long long)M, ppr, (uint4*)dX);
     } else if (eb == 4) {
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * Cin, NTHREADS), 8192);
-      hipLaunchKernelGGL((zero_dropped_rows_elem_kernel<uint32_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
+      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (zero_dropped_rows_elem_kernel<uint32_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
                          (int)K, (long long)M, Cin, (uint32_t*)dX);
     } else {
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * Cin, NTHREADS), 8192);
-      hipLaunchKernelGGL((zero_dropped_rows_elem_kernel<uint16_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
+      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (zero_dropped_rows_elem_kernel<uint16_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
                          (int)K, (long long)M, Cin, (uint16_t*)dX);
     }
   }

@@ -131,7 +131,7 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
   long long total = (long long)g.B * (g.P + g.ch * g.cw);
   int blocks = (int)((total + 255) / 256);
   if (blocks > 65535) blocks = 65535;
-  hipLaunchKernelGGL(sample_kernel, dim3(blocks), dim3(256), 0, s, g, idx, inv);
+  SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_kernel, dim3(blocks), dim3(256), 0, s, g, idx, inv);
   return check_launch("sample_kernel");
 }
 

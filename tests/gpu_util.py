@@ -10,7 +10,7 @@ import synth_inputs as si
 # max |gpu - ref| / max |ref| bars
 TOL_F32 = 1e-5          # fp32 outputs (fp32 path, and dW / db of the bf16 path: fp32 accumulators)
 TOL_BF16 = 2e-2         # bf16 outputs, stated bar
-TOL_BF16_TIGHT = 3e-3   # one RNE rounding of an exact-to-fp32 value is <= 2^-9 of its magnitude
+TOL_BF16_TIGHT = 4.1e-3 # one RNE rounding to bf16 (8 significant bits) is <= 2^-8 = 3.9e-3 of the value's magnitude
 
 
 def nerr(got, ref):

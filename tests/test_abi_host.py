@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 10
+    assert len(names) == 12
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -92,6 +92,8 @@ def test_forward_cache_argument_errors():
     L = _lib.lib()
     p = 4096  # never dereferenced: validation fails first
     assert L.sbp_forward_cache(None, p, 10, 5, 8, 1, p, None) == -1
+    assert L.sbp_forward_cache(p, None, 10, 5, 8, 1, p, None) == -1
+    assert L.sbp_forward_cache(p, p, 10, 5, 8, 1, None, None) == -1
     assert L.sbp_forward_cache(p, p, 10, 5, 8, 9, p, None) == -4
     assert L.sbp_forward_cache(p, p, 0, 0, 8, 1, p, None) == -2
     assert L.sbp_forward_cache(p, p, 10, 11, 8, 1, p, None) == -2
