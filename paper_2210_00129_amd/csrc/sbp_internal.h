@@ -44,6 +44,8 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
 // ---- linear backward ---------------------------------------------------------------------
 struct LinearPlan {
   bool   mfma;          // bf16 MFMA path (else plain kernels)
+  int    bm_w, bn_w;    // tile of the dW contraction (output channels x input channels)
+  int    bm_x, bn_x;    // tile of the dX contraction (kept rows x input channels)
   int    splits;        // split-K factor of the dW contraction
   int    rows_per_split;// kept rows per split (multiple of the k-step)
   size_t off_partial;   // fp32 [splits, Cout, Cin]

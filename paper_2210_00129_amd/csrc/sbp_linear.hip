@@ -4,340 +4,42 @@
 //   dX[idx[j],:] = dY[idx[j],:] W              every other row of dX = +0
 // W is stored [Cout, Cin].
 //
-// bf16 path: both contractions run on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32
-// accumulate).  The kept rows of dY are gathered by the tile loaders themselves, so dY_k is never
-// materialised.  Operands whose contraction index is the slow axis in memory (dY and X_k for dW, W for
-// dX) are transposed in registers on their way into LDS, so that every MFMA operand is one 16-byte LDS
-// read.  dW is split along the kept rows into partial sums that a second kernel adds in a fixed order
-// (deterministic, no floating-point atomics).
+// bf16 path: both contractions run on the gfx950 matrix cores (see sbp_mfma_gemm.h).  dW is split
+// along the kept rows into fp32 partial sums that a second kernel adds in a fixed order
+// (deterministic, no floating-point atomics); db rides on the dW tiles.
 // fp32 and odd shapes take plain kernels.
-#include "sbp_internal.h"
+#include <cstdio>
+#include <cstdlib>
+
+#include "sbp_mfma_gemm.h"
 
 namespace sbp {
 
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-static constexpr int BK = 64;          // contraction elements per LDS stage
-static constexpr int NTHREADS = 256;   // 4 wavefronts, arranged 2 x 2 over the block tile
-
-// ------------------------------------------------------------------------------------------------
-// LDS tile layout.  A tile holds ROWS rows of BK bf16 (128 bytes, eight 16-byte chunks).  Row m is
-// stored at physical row prow(m) (bits 0 and 3 exchanged) and its chunk c at slot c ^ (m & 7).  With
-// this, the 16-byte reads of an MFMA operand (32 consecutive rows, one chunk), the writes of the
-// row-major loader (eight chunks of one row per 8 lanes) and the writes of the transposing loader
-// (rows 8 apart across lane groups) all spread over the 64 banks.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ int prow(int m) { return (m & ~9) | ((m & 1) << 3) | ((m >> 3) & 1); }
-__device__ __forceinline__ int lds_off(int m, int c) { return prow(m) * 128 + ((c ^ (m & 7)) << 4); }
-
-__device__ __forceinline__ uint32_t bf16_round(float f) {   // round-to-nearest-even, NaN kept quiet
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-// 16-bit halves `hi ? upper : lower` of two words, first word's half in the low 16 bits
-__device__ __forceinline__ uint32_t pack_halves(uint32_t first, uint32_t second, int hi) {
-  return hi ? ((first >> 16) | (second & 0xffff0000u)) : ((first & 0xffffu) | (second << 16));
-}
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// ------------------------------------------------------------------------------------------------
-// Loader for an operand stored [rows][k] with k contiguous (dY as the left operand of dX).
-// Rows may be gathered through idx.  Each thread owns chunk (t & 7) of physical rows (t>>3) + 32 i.
-// ------------------------------------------------------------------------------------------------
-template <int ROWS>
-struct RowMajorLoader {
-  static constexpr int NI = ROWS / 32;
-  const uint16_t* ptr[NI];
-  uint4 reg[NI];
-  int soff[NI];
-  int c;
-  int kdim;
-
-  __device__ __forceinline__ void init(const uint16_t* src, const int32_t* idx, long long ld, int row0, int nrows,
-                                       int kdim_, int t) {
-    c = t & 7;
-    kdim = kdim_;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int q = (t >> 3) + 32 * i;        // physical row
-      const int m = prow(q);                  // logical row (prow is its own inverse)
-      const int r = row0 + m;
-      soff[i] = q * 128 + ((c ^ (m & 7)) << 4);
-      if (r < nrows) {
-        const long long g = idx ? (long long)idx[r] : (long long)r;
-        ptr[i] = src + g * ld + c * 8;
-      } else {
-        ptr[i] = nullptr;
-      }
-    }
-  }
-  __device__ __forceinline__ void load(int kt) {
-    const int k = kt * BK + c * 8;
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      if (ptr[i] && k < kdim) reg[i] = *reinterpret_cast<const uint4*>(ptr[i] + (long long)kt * BK);
-      else reg[i] = make_uint4(0, 0, 0, 0);
-    }
-  }
-  __device__ __forceinline__ void store(char* buf) const {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) *reinterpret_cast<uint4*>(buf + soff[i]) = reg[i];
-  }
-};
-
-// ------------------------------------------------------------------------------------------------
-// Loader for an operand stored [k][cols] with cols contiguous (contraction index on the slow axis).
-// The k rows may be gathered through idx.  Thread (kg = t & 7, mg = t >> 3) loads the 8(k) x MW(col)
-// block at k rows 8 kg .. 8 kg + 7 and columns MW mg .., transposes it in registers (v_perm) and
-// writes MW rows of eight k each into the tile.
-// ------------------------------------------------------------------------------------------------
-template <int ROWS>
-struct TransposingLoader {
-  static constexpr int MW = ROWS / 32;          // 8 (16-byte loads), 4 (8-byte) or 2 (4-byte)
-  static constexpr int ND = MW / 2;             // dwords per loaded row piece
-  const uint16_t* src;
-  const int32_t* idx;
-  long long ld;
-  int kdim, kg, col;                            // col: first column of this thread's block (absolute)
-  bool col_ok;
-  int soff[MW];
-  uint32_t reg[8][ND];
-
-  __device__ __forceinline__ void init(const uint16_t* src_, const int32_t* idx_, long long ld_, int col0,
-                                       int ncols, int kdim_, int t) {
-    src = src_; idx = idx_; ld = ld_; kdim = kdim_;
-    kg = t & 7;
-    const int mg = t >> 3;
-    col = col0 + MW * mg;
-    col_ok = col < ncols;
-#pragma unroll
-    for (int mm = 0; mm < MW; ++mm) soff[mm] = lds_off(MW * mg + mm, kg);
-  }
-  __device__ __forceinline__ void load(int kbase) {   // kbase: first contraction row of this stage
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int k = kbase + 8 * kg + i;
-      if (col_ok && k < kdim) {
-        const long long g = idx ? (long long)idx[k] : (long long)k;
-        const uint16_t* p = src + g * ld + col;
-        if constexpr (ND == 4) {
-          uint4 v = *reinterpret_cast<const uint4*>(p);
-          reg[i][0] = v.x; reg[i][1] = v.y; reg[i][2] = v.z; reg[i][3] = v.w;
-        } else if constexpr (ND == 2) {
-          uint2 v = *reinterpret_cast<const uint2*>(p);
-          reg[i][0] = v.x; reg[i][1] = v.y;
-        } else {
-          reg[i][0] = *reinterpret_cast<const uint32_t*>(p);
-        }
-      } else {
-#pragma unroll
-        for (int d = 0; d < ND; ++d) reg[i][d] = 0;
-      }
-    }
-  }
-  __device__ __forceinline__ void store(char* buf) const {
-#pragma unroll
-    for (int mm = 0; mm < MW; ++mm) {
-      uint4 v;   // element e of the 16-byte vector = contraction row 8 kg + e (compiles to v_perm_b32)
-      v.x = pack_halves(reg[0][mm >> 1], reg[1][mm >> 1], mm & 1);
-      v.y = pack_halves(reg[2][mm >> 1], reg[3][mm >> 1], mm & 1);
-      v.z = pack_halves(reg[4][mm >> 1], reg[5][mm >> 1], mm & 1);
-      v.w = pack_halves(reg[6][mm >> 1], reg[7][mm >> 1], mm & 1);
-      *reinterpret_cast<uint4*>(buf + soff[mm]) = v;
-    }
-  }
-};
-
-// One LDS stage of MFMAs for a wavefront: FM x FN tiles of 32x32, contraction BK = 4 x 16.
-// Lane l supplies row (l & 31), contraction elements 8 (l >> 5) .. + 7 of each 16-wide step.
-template <int FM, int FN>
-__device__ __forceinline__ void mma_stage(const char* tA, const char* tB, int a_off, int b_off, int lane_s,
-                                          int lane_h, f32x16_t (&acc)[FM][FN]) {
-#pragma unroll
-  for (int ks = 0; ks < BK / 16; ++ks) {
-    const int ch = ((2 * ks + lane_h) ^ lane_s) << 4;
-    bf16x8_t a[FM], b[FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i) a[i] = *reinterpret_cast<const bf16x8_t*>(tA + a_off + i * 4096 + ch);
-#pragma unroll
-    for (int j = 0; j < FN; ++j) b[j] = *reinterpret_cast<const bf16x8_t*>(tB + b_off + j * 4096 + ch);
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-      for (int j = 0; j < FN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// dX tile kernel.  C[j, i] = sum_o dY[row(j), o] W[o, i] for a BM x BN tile of (kept row, input channel).
-// ------------------------------------------------------------------------------------------------
 template <int BM, int BN>
-__global__ void __launch_bounds__(NTHREADS) dx_mfma_kernel(const uint16_t* __restrict__ dY,
-                                                            const int32_t* __restrict__ idx_in,   // rows of dY (NULL: compact)
-                                                            const int32_t* __restrict__ idx_out,  // rows of dX (NULL: compact)
-                                                            const uint16_t* __restrict__ W, int K, int Cin, int Cout,
-                                                            uint16_t* __restrict__ dX) {
-  constexpr int FM = BM / 64, FN = BN / 64;
+__global__ void __launch_bounds__(NTHREADS, (BM + BN) <= 256 ? 2 : 1)
+dx_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,   // rows of dY (NULL: compact)
+               const int32_t* __restrict__ idx_out,                                    // rows of dX (NULL: compact)
+               const uint16_t* __restrict__ W, int K, int Cin, int Cout, uint16_t* __restrict__ dX) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
   const int tiles_n = (Cin + BN - 1) / BN;
   const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-
-  RowMajorLoader<BM> la;
-  TransposingLoader<BN> lb;
-  la.init(dY, idx_in, Cout, m0, K, Cout, t);
-  lb.init(W, nullptr, Cin, n0, Cin, Cout, t);
-
-  f32x16_t acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int a_off = prow(wm + (lane & 31)) * 128, b_off = prow(wn + (lane & 31)) * 128;
-  const int lane_s = lane & 7, lane_h = lane >> 5;
-  const int nk = (Cout + BK - 1) / BK;
-
-  la.load(0); lb.load(0);
-  la.store(smem); lb.store(smem + A_BYTES);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    if (kt + 1 < nk) { la.load(kt + 1); lb.load((kt + 1) * BK); }
-    mma_stage<FM, FN>(cur, cur + A_BYTES, a_off, b_off, lane_s, lane_h, acc);
-    if (kt + 1 < nk) { la.store(nxt); lb.store(nxt + A_BYTES); }
-    __syncthreads();
-  }
-
-  // epilogue: acc register v of lane l is C[row = 8 (v/4) + 4 (l>>5) + (v&3)][col = l & 31] of its 32x32 tile
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int j = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      if (j < K) {
-        const long long orow = idx_out ? (long long)idx_out[j] : (long long)j;
-#pragma unroll
-        for (int jn = 0; jn < FN; ++jn) {
-          const int col = n0 + wn + 32 * jn + (lane & 31);
-          if (col < Cin) dX[orow * Cin + col] = (uint16_t)bf16_round(acc[i][jn][v]);
-        }
-      }
-    }
-  }
+  dx_tile<BM, BN>(smem, dY, idx_in, idx_out, W, K, Cin, Cout, dX, tile_m * BM, tile_n * BN);
 }
 
-// ------------------------------------------------------------------------------------------------
-// dW tile kernel.  partial[s][o, i] = sum over the kept rows j of split s of dY[row(j), o] X_k[j, i].
-// ------------------------------------------------------------------------------------------------
 template <int BM, int BN>
-__global__ void __launch_bounds__(NTHREADS) dw_mfma_kernel(const uint16_t* __restrict__ dY,
-                                                            const int32_t* __restrict__ idx,   // rows of dY (NULL: compact)
-                                                            const uint16_t* __restrict__ Xk, int K, int Cin, int Cout,
-                                                            int rows_per_split, float* __restrict__ partial) {
-  constexpr int FM = BM / 64, FN = BN / 64;
+__global__ void __launch_bounds__(NTHREADS, (BM + BN) <= 256 ? 2 : 1)
+dw_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,      // rows of dY (NULL: compact)
+               const uint16_t* __restrict__ Xk, int K, int Cin, int Cout, int rows_per_split,
+               float* __restrict__ partial, float* __restrict__ dbp) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
   const int tiles_n = (Cin + BN - 1) / BN;
   const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int split = blockIdx.y;
-  const int j0 = split * rows_per_split;
-  const int j1 = min(K, j0 + rows_per_split);
-
-  TransposingLoader<BM> la;
-  TransposingLoader<BN> lb;
-  la.init(dY, idx, Cout, m0, Cout, j1, t);
-  lb.init(Xk, nullptr, Cin, n0, Cin, j1, t);
-
-  f32x16_t acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int a_off = prow(wm + (lane & 31)) * 128, b_off = prow(wn + (lane & 31)) * 128;
-  const int lane_s = lane & 7, lane_h = lane >> 5;
-  const int nk = (j1 - j0 + BK - 1) / BK;
-
-  if (nk > 0) {
-    la.load(j0); lb.load(j0);
-    la.store(smem); lb.store(smem + A_BYTES);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE;
-    char* nxt = smem + ((kt + 1) & 1) * STAGE;
-    if (kt + 1 < nk) { la.load(j0 + (kt + 1) * BK); lb.load(j0 + (kt + 1) * BK); }
-    mma_stage<FM, FN>(cur, cur + A_BYTES, a_off, b_off, lane_s, lane_h, acc);
-    if (kt + 1 < nk) { la.store(nxt); lb.store(nxt + A_BYTES); }
-    __syncthreads();
-  }
-
-  float* out = partial + (long long)split * Cout * Cin;
-#pragma unroll
-  for (int i = 0; i < FM; ++i) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int o = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-      if (o < Cout) {
-#pragma unroll
-        for (int jn = 0; jn < FN; ++jn) {
-          const int col = n0 + wn + 32 * jn + (lane & 31);
-          if (col < Cin) out[(long long)o * Cin + col] = acc[i][jn][v];
-        }
-      }
-    }
-  }
+  const int j0 = split * rows_per_split, j1 = min(K, j0 + rows_per_split);
+  dw_tile<BM, BN>(smem, dY, idx, Xk, Cin, Cout, j0, j1, partial + (long long)split * Cout * Cin,
+                  dbp ? dbp + (long long)split * Cout : nullptr, tile_m * BM, tile_n * BN);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Column sums of the kept rows of dY (bf16), in row splits: dbp[s][o] = sum_{j in split s} dY[row(j), o].
-// Thread (x, y): 8 columns starting at 8 (32 blockIdx.x + x), rows y, y + 8, ... of the split.
-// ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(NTHREADS) colsum_bf16_kernel(const uint16_t* __restrict__ dY,
-                                                                const int32_t* __restrict__ idx, int K, int Cout,
-                                                                int rows_per_split, float* __restrict__ dbp) {
-  __shared__ float red[8][32][9];
-  const int x = threadIdx.x & 31, y = threadIdx.x >> 5;
-  const int col = 8 * (32 * blockIdx.x + x);
-  const int j0 = blockIdx.y * rows_per_split, j1 = min(K, j0 + rows_per_split);
-  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (col < Cout) {
-    for (int j = j0 + y; j < j1; j += 8) {
-      const long long g = idx ? (long long)idx[j] : (long long)j;
-      const uint4 v = *reinterpret_cast<const uint4*>(dY + g * Cout + col);
-      s[0] += bf16_lo(v.x); s[1] += bf16_hi(v.x); s[2] += bf16_lo(v.y); s[3] += bf16_hi(v.y);
-      s[4] += bf16_lo(v.z); s[5] += bf16_hi(v.z); s[6] += bf16_lo(v.w); s[7] += bf16_hi(v.w);
-    }
-  }
-#pragma unroll
-  for (int e = 0; e < 8; ++e) red[y][x][e] = s[e];
-  __syncthreads();
-  if (y == 0 && col < Cout) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float a = 0.f;
-#pragma unroll
-      for (int yy = 0; yy < 8; ++yy) a += red[yy][x][e];
-      dbp[(long long)blockIdx.y * Cout + col + e] = a;
-    }
-  }
-}
 
 // dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.
 __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __restrict__ partial, int nsplit_w,
@@ -511,15 +213,30 @@ __global__ void __launch_bounds__(NTHREADS) plain_db_kernel(const T* __restrict_
 // ------------------------------------------------------------------------------------------------
 static constexpr int kNumCU = 256;
 
+// Debug aid: SBP_TILE_DW / SBP_TILE_DX = "256x256" | "256x128" | "128x128" force a tile shape.
+static bool env_tile(const char* name, int* bm, int* bn) {
+  const char* v = std::getenv(name);
+  if (!v) return false;
+  int a = 0, b = 0;
+  if (std::sscanf(v, "%dx%d", &a, &b) != 2) return false;
+  if (!((a == 256 && b == 256) || (a == 256 && b == 128) || (a == 128 && b == 128))) return false;
+  *bm = a; *bn = b;
+  return true;
+}
+
 LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags) {
   LinearPlan p{};
   p.mfma = dtype == SBP_BF16 && Cin % 8 == 0 && Cout % 8 == 0;
+  p.bm_w = p.bn_w = p.bm_x = p.bn_x = 128;
   int splits = 1;
   if (K > 0) {
     if (p.mfma) {
-      // enough blocks to cover the chip about twice, each split at least 4 stages long
-      const int64_t tiles = ceil_div(Cout, 128) * ceil_div(Cin, 128);
-      int64_t want = ceil_div(2 * kNumCU, tiles);
+      env_tile("SBP_TILE_DW", &p.bm_w, &p.bn_w);
+      env_tile("SBP_TILE_DX", &p.bm_x, &p.bn_x);
+      // enough blocks to fill the chip's block slots once, each split at least 4 stages long
+      const int64_t tiles = ceil_div(Cout, p.bm_w) * ceil_div(Cin, p.bn_w);
+      const int64_t slots = (p.bm_w + p.bn_w <= 256) ? 2 * kNumCU : kNumCU;
+      int64_t want = std::max<int64_t>(1, slots / tiles);
       int64_t max_by_len = std::max<int64_t>(1, K / (4 * BK));
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_len), 64));
     } else {
@@ -564,22 +281,31 @@ static int32_t launch_plain(const LinearPlan& p, const T* dY, const int32_t* idx
   return SBP_OK;
 }
 
+template <typename KernelT>
+static void allow_big_lds(KernelT kernel, size_t lds) {
+  if (lds > 64 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+}
+
 template <int BM, int BN>
 static void launch_dx_mfma(const uint16_t* dY, const int32_t* idx_in, const int32_t* idx_out, const uint16_t* W,
                            int K, int Cin, int Cout, uint16_t* dX, hipStream_t s) {
   const int tiles = (int)(ceil_div(K, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), lds, s, dY, idx_in, idx_out, W, K, Cin,
-                     Cout, dX);
+  allow_big_lds(dx_mfma_kernel<BM, BN>, lds);
+  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), lds, s, dY, idx_in, idx_out,
+             W, K, Cin, Cout, dX);
 }
 
 template <int BM, int BN>
 static void launch_dw_mfma(const uint16_t* dY, const int32_t* idx, const uint16_t* Xk, int K, int Cin, int Cout,
-                           int splits, int rps, float* part, hipStream_t s) {
+                           int splits, int rps, float* part, float* dbp, hipStream_t s) {
   const int tiles = (int)(ceil_div(Cout, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN>), dim3(tiles, splits), dim3(NTHREADS), lds, s, dY, idx, Xk, K, Cin,
-                     Cout, rps, part);
+  allow_big_lds(dw_mfma_kernel<BM, BN>, lds);
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN>), dim3(tiles, splits), dim3(NTHREADS), lds, s, dY, idx, Xk, K,
+             Cin, Cout, rps, part, dbp);
 }
 
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const void* Xk,
@@ -614,17 +340,26 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
                        ((uintptr_t)dX % 16 == 0);
   if (p.mfma && aligned) {
     const uint16_t* dYh = static_cast<const uint16_t*>(dY);
-    if (db) {
-      dim3 grid((unsigned)ceil_div(Cout, 256), p.splits);
-      SBP_LAUNCH(SBP_PROF_COLSUM, s, colsum_bf16_kernel, grid, dim3(NTHREADS), 0, s, dYh, idx_in, (int)K, Cout, p.rows_per_split,
-                         dbp);
+    const uint16_t* Xkh = static_cast<const uint16_t*>(Xk);
+    const uint16_t* Wh = static_cast<const uint16_t*>(W);
+    uint16_t* dXh = static_cast<uint16_t*>(dX);
+    if (dW || db) {   // db rides on the dW tiles
+      float* dbq = db ? dbp : nullptr;
+      if (p.bm_w == 256 && p.bn_w == 256)
+        launch_dw_mfma<256, 256>(dYh, idx_in, Xkh, (int)K, Cin, Cout, p.splits, p.rows_per_split, part, dbq, s);
+      else if (p.bm_w == 256)
+        launch_dw_mfma<256, 128>(dYh, idx_in, Xkh, (int)K, Cin, Cout, p.splits, p.rows_per_split, part, dbq, s);
+      else
+        launch_dw_mfma<128, 128>(dYh, idx_in, Xkh, (int)K, Cin, Cout, p.splits, p.rows_per_split, part, dbq, s);
     }
-    if (dW)
-      launch_dw_mfma<128, 128>(dYh, idx_in, static_cast<const uint16_t*>(Xk), (int)K, Cin, Cout, p.splits,
-                               p.rows_per_split, part, s);
-    if (dX)
-      launch_dx_mfma<128, 128>(dYh, idx_in, idx_out, static_cast<const uint16_t*>(W), (int)K, Cin, Cout,
-                               static_cast<uint16_t*>(dX), s);
+    if (dX) {
+      if (p.bm_x == 256 && p.bn_x == 256)
+        launch_dx_mfma<256, 256>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+      else if (p.bm_x == 256)
+        launch_dx_mfma<256, 128>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+      else
+        launch_dx_mfma<128, 128>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+    }
   } else if (dtype == SBP_F32) {
     launch_plain<float>(p, (const float*)dY, idx_in, idx_out, (const float*)Xk, (const float*)W, K, Cin, Cout, part,
                         dbp, dW != nullptr, db != nullptr, (float*)dX, s);
