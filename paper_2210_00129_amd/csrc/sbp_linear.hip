@@ -15,6 +15,18 @@
 
 namespace sbp {
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by workgroup id.  This
+// maps the id so that every XCD works on one contiguous chunk of the tile list: neighbouring tiles,
+// which share operand panels, then meet in the same L2.  The grid is padded to a multiple of 8;
+// ids that map beyond the list are idle.
+static constexpr int kNumXCD = 8;
+// stages of global loads kept in flight in registers: 2 where the register file allows it
+template <int BM, int BN> static constexpr int kPrefetch = (BM + BN <= 384) ? 2 : 1;
+__device__ __forceinline__ int xcd_chunked_id(int wg, int ntiles) {
+  const int per = (ntiles + kNumXCD - 1) / kNumXCD;
+  return (wg % kNumXCD) * per + wg / kNumXCD;
+}
+
 template <int BM, int BN>
 __global__ void __launch_bounds__(NTHREADS, (BM + BN) <= 256 ? 2 : 1)
 dx_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,   // rows of dY (NULL: compact)
@@ -22,8 +34,11 @@ dx_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_
                const uint16_t* __restrict__ W, int K, int Cin, int Cout, uint16_t* __restrict__ dX) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tiles_n = (Cin + BN - 1) / BN;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
-  dx_tile<BM, BN>(smem, dY, idx_in, idx_out, W, K, Cin, Cout, dX, tile_m * BM, tile_n * BN);
+  const int ntiles = ((K + BM - 1) / BM) * tiles_n;
+  const int L = xcd_chunked_id(blockIdx.x, ntiles);
+  if (L >= ntiles) return;
+  const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
+  dx_tile<BM, BN, kPrefetch<BM, BN>>(smem, dY, idx_in, idx_out, W, K, Cin, Cout, dX, tile_m * BM, tile_n * BN);
 }
 
 template <int BM, int BN>
@@ -32,14 +47,18 @@ dw_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                const uint16_t* __restrict__ Xk, int K, int Cin, int Cout, int rows_per_split,
                float* __restrict__ partial, float* __restrict__ dbp) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tiles_n = (Cin + BN - 1) / BN;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
-  const int split = blockIdx.y;
+  const int tiles_n = (Cin + BN - 1) / BN, tiles_m = (Cout + BM - 1) / BM;
+  const int nsplit = (K + rows_per_split - 1) / rows_per_split;
+  const int ntiles = tiles_m * tiles_n * nsplit;
+  const int L = xcd_chunked_id(blockIdx.x, ntiles);
+  if (L >= ntiles) return;
+  const int split = L / (tiles_m * tiles_n);
+  const int rem = L - split * tiles_m * tiles_n;
+  const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
   const int j0 = split * rows_per_split, j1 = min(K, j0 + rows_per_split);
-  dw_tile<BM, BN>(smem, dY, idx, Xk, Cin, Cout, j0, j1, partial + (long long)split * Cout * Cin,
+  dw_tile<BM, BN, kPrefetch<BM, BN>>(smem, dY, idx, Xk, Cin, Cout, j0, j1, partial + (long long)split * Cout * Cin,
                   dbp ? dbp + (long long)split * Cout : nullptr, tile_m * BM, tile_n * BN);
 }
-
 
 // dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.
 __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __restrict__ partial, int nsplit_w,
@@ -294,7 +313,7 @@ static void launch_dx_mfma(const uint16_t* dY, const int32_t* idx_in, const int3
   const int tiles = (int)(ceil_div(K, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
   allow_big_lds(dx_mfma_kernel<BM, BN>, lds);
-  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN>), dim3(tiles), dim3(NTHREADS), lds, s, dY, idx_in, idx_out,
+  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN>), dim3(8 * (unsigned)ceil_div(tiles, 8)), dim3(NTHREADS), lds, s, dY, idx_in, idx_out,
              W, K, Cin, Cout, dX);
 }
 
@@ -304,7 +323,8 @@ static void launch_dw_mfma(const uint16_t* dY, const int32_t* idx, const uint16_
   const int tiles = (int)(ceil_div(Cout, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
   allow_big_lds(dw_mfma_kernel<BM, BN>, lds);
-  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN>), dim3(tiles, splits), dim3(NTHREADS), lds, s, dY, idx, Xk, K,
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN>), dim3(8 * (unsigned)ceil_div((long long)tiles * splits, 8)),
+             dim3(NTHREADS), lds, s, dY, idx, Xk, K,
              Cin, Cout, rps, part, dbp);
 }
 
