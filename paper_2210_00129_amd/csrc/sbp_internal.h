@@ -48,6 +48,9 @@ struct LinearPlan {
   int    bm_x, bn_x;    // tile of the dX contraction (kept rows x input channels)
   int    splits;        // split-K factor of the dW contraction
   int    rows_per_split;// kept rows per split (multiple of the k-step)
+  int    nw_w, nw_x;    // wavefronts per block of the two contractions (4 or 8)
+  int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
+  int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]
   size_t off_inv;       // int32 [M]
   size_t bytes;

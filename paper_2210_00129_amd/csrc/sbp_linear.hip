@@ -20,15 +20,13 @@ namespace sbp {
 // which share operand panels, then meet in the same L2.  The grid is padded to a multiple of 8;
 // ids that map beyond the list are idle.
 static constexpr int kNumXCD = 8;
-// stages of global loads kept in flight in registers: 2 where the register file allows it
-template <int BM, int BN> static constexpr int kPrefetch = (BM + BN <= 384) ? 2 : 1;
 __device__ __forceinline__ int xcd_chunked_id(int wg, int ntiles) {
   const int per = (ntiles + kNumXCD - 1) / kNumXCD;
   return (wg % kNumXCD) * per + wg / kNumXCD;
 }
 
-template <int BM, int BN>
-__global__ void __launch_bounds__(NTHREADS, (BM + BN) <= 256 ? 2 : 1)
+template <int BM, int BN, int NW>
+__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1)
 dx_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,   // rows of dY (NULL: compact)
                const int32_t* __restrict__ idx_out,                                    // rows of dX (NULL: compact)
                const uint16_t* __restrict__ W, int K, int Cin, int Cout, uint16_t* __restrict__ dX) {
@@ -38,26 +36,38 @@ dx_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_
   const int L = xcd_chunked_id(blockIdx.x, ntiles);
   if (L >= ntiles) return;
   const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-  dx_tile<BM, BN, kPrefetch<BM, BN>>(smem, dY, idx_in, idx_out, W, K, Cin, Cout, dX, tile_m * BM, tile_n * BN);
+  dx_tile<BM, BN, NW>(smem, dY, idx_in, idx_out, W, K, Cin, Cout, dX, tile_m * BM, tile_n * BN);
 }
 
-template <int BM, int BN>
-__global__ void __launch_bounds__(NTHREADS, (BM + BN) <= 256 ? 2 : 1)
+// Grid: when db is wanted, one column-sum block per (slice of kept rows, 256 output channels); then the
+// dW tiles (padded to a multiple of 8, XCD-chunked).
+static constexpr int kDbSliceRows = 128;     // smallest slice
+static constexpr int kMaxDbSlices = 64;      // at most this many partial sums per channel
+template <int BM, int BN, int NW>
+__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1)
 dw_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,      // rows of dY (NULL: compact)
                const uint16_t* __restrict__ Xk, int K, int Cin, int Cout, int rows_per_split,
-               float* __restrict__ partial, float* __restrict__ dbp) {
+               float* __restrict__ partial, float* __restrict__ dbp, int db_blocks, int db_slice_rows) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tiles_n = (Cin + BN - 1) / BN, tiles_m = (Cout + BM - 1) / BM;
   const int nsplit = (K + rows_per_split - 1) / rows_per_split;
+  if ((int)blockIdx.x < db_blocks) {          // column-sum blocks go first: they share the CUs with the tiles
+    const int nslice = (K + db_slice_rows - 1) / db_slice_rows;
+    const int slice = blockIdx.x % nslice, chunk = blockIdx.x / nslice;
+    const int j0 = slice * db_slice_rows, j1 = min(K, j0 + db_slice_rows);
+    colsum_block(smem, dY, idx, Cout, j0, j1, chunk * 256, dbp + (long long)slice * Cout);
+    return;
+  }
+  const int wg = blockIdx.x - db_blocks;
+  const int tiles_n = (Cin + BN - 1) / BN, tiles_m = (Cout + BM - 1) / BM;
   const int ntiles = tiles_m * tiles_n * nsplit;
-  const int L = xcd_chunked_id(blockIdx.x, ntiles);
+  const int L = xcd_chunked_id(wg, ntiles);
   if (L >= ntiles) return;
   const int split = L / (tiles_m * tiles_n);
   const int rem = L - split * tiles_m * tiles_n;
   const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
   const int j0 = split * rows_per_split, j1 = min(K, j0 + rows_per_split);
-  dw_tile<BM, BN, kPrefetch<BM, BN>>(smem, dY, idx, Xk, Cin, Cout, j0, j1, partial + (long long)split * Cout * Cin,
-                  dbp ? dbp + (long long)split * Cout : nullptr, tile_m * BM, tile_n * BN);
+  dw_tile<BM, BN, NW>(smem, dY, idx, Xk, Cin, Cout, j0, j1, partial + (long long)split * Cout * Cin, tile_m * BM,
+                  tile_n * BN);
 }
 
 // dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.
@@ -232,14 +242,17 @@ __global__ void __launch_bounds__(NTHREADS) plain_db_kernel(const T* __restrict_
 // ------------------------------------------------------------------------------------------------
 static constexpr int kNumCU = 256;
 
-// Debug aid: SBP_TILE_DW / SBP_TILE_DX = "256x256" | "256x128" | "128x128" force a tile shape.
-static bool env_tile(const char* name, int* bm, int* bn) {
+// Debug aid: SBP_TILE_DW / SBP_TILE_DX = "256x256x8" | "256x256x4" | "256x128x4" | "128x128x4" force a tile
+// shape (rows x columns x wavefronts).
+static bool env_tile(const char* name, int* bm, int* bn, int* nw) {
   const char* v = std::getenv(name);
   if (!v) return false;
-  int a = 0, b = 0;
-  if (std::sscanf(v, "%dx%d", &a, &b) != 2) return false;
-  if (!((a == 256 && b == 256) || (a == 256 && b == 128) || (a == 128 && b == 128))) return false;
-  *bm = a; *bn = b;
+  int a = 0, b = 0, w = 4;
+  if (std::sscanf(v, "%dx%dx%d", &a, &b, &w) < 2) return false;
+  const bool ok = (a == 256 && b == 256 && (w == 4 || w == 8)) || (a == 256 && b == 128 && w == 4) ||
+                  (a == 128 && b == 128 && w == 4);
+  if (!ok) return false;
+  *bm = a; *bn = b; *nw = w;
   return true;
 }
 
@@ -247,11 +260,12 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   LinearPlan p{};
   p.mfma = dtype == SBP_BF16 && Cin % 8 == 0 && Cout % 8 == 0;
   p.bm_w = p.bn_w = p.bm_x = p.bn_x = 128;
+  p.nw_w = p.nw_x = 4;
   int splits = 1;
   if (K > 0) {
     if (p.mfma) {
-      env_tile("SBP_TILE_DW", &p.bm_w, &p.bn_w);
-      env_tile("SBP_TILE_DX", &p.bm_x, &p.bn_x);
+      env_tile("SBP_TILE_DW", &p.bm_w, &p.bn_w, &p.nw_w);
+      env_tile("SBP_TILE_DX", &p.bm_x, &p.bn_x, &p.nw_x);
       // enough blocks to fill the chip's block slots once, each split at least 4 stages long
       const int64_t tiles = ceil_div(Cout, p.bm_w) * ceil_div(Cin, p.bn_w);
       const int64_t slots = (p.bm_w + p.bn_w <= 256) ? 2 * kNumCU : kNumCU;
@@ -269,7 +283,9 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   p.rows_per_split = (int)rps;
   size_t off = 0;
   p.off_partial = off;
-  off += align_up((size_t)splits * ((size_t)Cout * Cin + (size_t)Cout) * sizeof(float), 256);
+  p.db_slice_rows = (int)std::max<int64_t>(kDbSliceRows, ceil_div(ceil_div(K, kMaxDbSlices), 8) * 8);
+  p.db_slices = p.mfma ? (int)std::max<int64_t>(1, ceil_div(K, p.db_slice_rows)) : splits;
+  off += align_up(((size_t)splits * Cout * Cin + (size_t)std::max(p.db_slices, splits) * Cout) * sizeof(float), 256);
   p.off_inv = off;
   if (!(flags & SBP_FLAG_DX_COMPACT)) off += align_up((size_t)M * sizeof(int32_t), 256);
   p.bytes = off;
@@ -307,25 +323,26 @@ static void allow_big_lds(KernelT kernel, size_t lds) {
                               (int)lds);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NW>
 static void launch_dx_mfma(const uint16_t* dY, const int32_t* idx_in, const int32_t* idx_out, const uint16_t* W,
                            int K, int Cin, int Cout, uint16_t* dX, hipStream_t s) {
   const int tiles = (int)(ceil_div(K, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  allow_big_lds(dx_mfma_kernel<BM, BN>, lds);
-  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN>), dim3(8 * (unsigned)ceil_div(tiles, 8)), dim3(NTHREADS), lds, s, dY, idx_in, idx_out,
+  allow_big_lds(dx_mfma_kernel<BM, BN, NW>, lds);
+  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN, NW>), dim3(8 * (unsigned)ceil_div(tiles, 8)), dim3(64 * NW), lds, s, dY, idx_in, idx_out,
              W, K, Cin, Cout, dX);
 }
 
-template <int BM, int BN>
-static void launch_dw_mfma(const uint16_t* dY, const int32_t* idx, const uint16_t* Xk, int K, int Cin, int Cout,
-                           int splits, int rps, float* part, float* dbp, hipStream_t s) {
+template <int BM, int BN, int NW>
+static void launch_dw_mfma(const LinearPlan& p, const uint16_t* dY, const int32_t* idx, const uint16_t* Xk, int K,
+                           int Cin, int Cout, float* part, float* dbp, hipStream_t s) {
   const int tiles = (int)(ceil_div(Cout, BM) * ceil_div(Cin, BN));
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  allow_big_lds(dw_mfma_kernel<BM, BN>, lds);
-  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN>), dim3(8 * (unsigned)ceil_div((long long)tiles * splits, 8)),
-             dim3(NTHREADS), lds, s, dY, idx, Xk, K,
-             Cin, Cout, rps, part, dbp);
+  allow_big_lds(dw_mfma_kernel<BM, BN, NW>, lds);
+  const unsigned gemm_blocks = 8 * (unsigned)ceil_div((long long)tiles * p.splits, 8);
+  const unsigned db_blocks = dbp ? (unsigned)(ceil_div(Cout, 256) * p.db_slices) : 0u;
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN, NW>), dim3(gemm_blocks + db_blocks), dim3(64 * NW), lds, s, dY,
+             idx, Xk, K, Cin, Cout, p.rows_per_split, part, dbp, (int)db_blocks, p.db_slice_rows);
 }
 
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const void* Xk,
@@ -358,27 +375,32 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
 
   const bool aligned = ((uintptr_t)dY % 16 == 0) && ((uintptr_t)Xk % 16 == 0) && ((uintptr_t)W % 16 == 0) &&
                        ((uintptr_t)dX % 16 == 0);
-  if (p.mfma && aligned) {
+  const bool use_mfma = p.mfma && aligned;
+  if (use_mfma) {
     const uint16_t* dYh = static_cast<const uint16_t*>(dY);
     const uint16_t* Xkh = static_cast<const uint16_t*>(Xk);
     const uint16_t* Wh = static_cast<const uint16_t*>(W);
     uint16_t* dXh = static_cast<uint16_t*>(dX);
     if (dW || db) {   // db rides on the dW tiles
       float* dbq = db ? dbp : nullptr;
-      if (p.bm_w == 256 && p.bn_w == 256)
-        launch_dw_mfma<256, 256>(dYh, idx_in, Xkh, (int)K, Cin, Cout, p.splits, p.rows_per_split, part, dbq, s);
+      if (p.bm_w == 256 && p.bn_w == 256 && p.nw_w == 8)
+        launch_dw_mfma<256, 256, 8>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
+      else if (p.bm_w == 256 && p.bn_w == 256)
+        launch_dw_mfma<256, 256, 4>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
       else if (p.bm_w == 256)
-        launch_dw_mfma<256, 128>(dYh, idx_in, Xkh, (int)K, Cin, Cout, p.splits, p.rows_per_split, part, dbq, s);
+        launch_dw_mfma<256, 128, 4>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
       else
-        launch_dw_mfma<128, 128>(dYh, idx_in, Xkh, (int)K, Cin, Cout, p.splits, p.rows_per_split, part, dbq, s);
+        launch_dw_mfma<128, 128, 4>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
     }
     if (dX) {
-      if (p.bm_x == 256 && p.bn_x == 256)
-        launch_dx_mfma<256, 256>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+      if (p.bm_x == 256 && p.bn_x == 256 && p.nw_x == 8)
+        launch_dx_mfma<256, 256, 8>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+      else if (p.bm_x == 256 && p.bn_x == 256)
+        launch_dx_mfma<256, 256, 4>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
       else if (p.bm_x == 256)
-        launch_dx_mfma<256, 128>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+        launch_dx_mfma<256, 128, 4>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
       else
-        launch_dx_mfma<128, 128>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
+        launch_dx_mfma<128, 128, 4>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
     }
   } else if (dtype == SBP_F32) {
     launch_plain<float>(p, (const float*)dY, idx_in, idx_out, (const float*)Xk, (const float*)W, K, Cin, Cout, part,
@@ -393,12 +415,12 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
       const long long total = (dW ? nW / 4 : 0) + (db ? Cout : 0);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
       SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW, dbp,
-                         p.splits, Cout, db, accumulate);
+                         use_mfma ? p.db_slices : p.splits, Cout, db, accumulate);
     } else {
       const long long total = (dW ? nW : 0) + (db ? Cout : 0);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
       SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_scalar_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW,
-                         dbp, Cout, db, accumulate);
+                         dbp, Cout, db, accumulate);   // plain path only: db partials follow the dW splits
     }
   }
 

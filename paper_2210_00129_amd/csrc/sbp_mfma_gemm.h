@@ -28,9 +28,11 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define SBP_LDS __attribute__((address_space(3)))
+#define SBP_GLB __attribute__((address_space(1)))
 
 static constexpr int BK = 64;          // contraction elements per LDS stage
-static constexpr int NTHREADS = 256;   // 4 wavefronts, arranged 2 x 2 over the block tile
+static constexpr int NTHREADS = 256;   // threads of the small kernels and of the 4-wavefront GEMM blocks
+// A GEMM block has NW = 4 wavefronts (2 x 2 over the tile) or NW = 8 (2 x 4: two wavefronts per SIMD).
 
 __device__ __forceinline__ uint32_t bf16_round(float f) {   // round-to-nearest-even, NaN kept quiet
   uint32_t u = __float_as_uint(f);
@@ -42,48 +44,60 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 // ------------------------------------------------------------------------------------------------
+// Global -> LDS copies bypass the register file: global_load_lds_dwordx4 moves 16 bytes per lane
+// straight into LDS, the 64 lanes of a wavefront filling one contiguous 1 KB block whose base is
+// wave-uniform.  Where a piece lands is therefore fixed by the lane number; the swizzles below are
+// applied by choosing which global piece each lane fetches.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void async_copy16(const void* g, char* lds_block) {
+  __builtin_amdgcn_global_load_lds((SBP_GLB const void*)g, (SBP_LDS void*)lds_block, 16, 0, 0);
+}
+__device__ __forceinline__ void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
+// ------------------------------------------------------------------------------------------------
 // "row" tile: ROWS rows of BK bf16 (128 bytes = eight 16-byte chunks).  Row m sits at physical row
 // prow(m) (bits 0 and 3 exchanged), its chunk c at slot c ^ (m & 7): the 16-byte operand reads of 32
-// consecutive rows and the loader's writes both spread over all 64 banks.
+// consecutive rows spread over all 64 banks.  One 1 KB block = 8 physical rows.
 // Rows past the end are clamped to the last row (their results are never stored); in the tail stage
 // chunks past kdim re-read the last chunk (the other operand is zero there).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ int prow(int m) { return (m & ~9) | ((m & 1) << 3) | ((m >> 3) & 1); }
 
-template <int ROWS, int NPRE>
+template <int ROWS, int NW>
 struct RowTileLoader {
-  static constexpr int NI = ROWS / 32;
-  const uint16_t* ptr[NI];
-  uint4 reg[NPRE][NI];
-  int soff[NI];
-  int c, kdim;
+  static constexpr int NI = ROWS / 8 / NW;      // 1 KB blocks per wavefront and stage (even)
+  const uint16_t* rowp[NI];
+  int koff[2];                                  // element offset of this lane's chunk in even / odd blocks
+  int kdim, blk0;
 
   __device__ __forceinline__ void init(const uint16_t* src, const int32_t* idx, long long ld, int row0, int nrows,
-                                       int kdim_, int t) {
-    c = t & 7;
+                                       int kdim_, int lane, int wave) {
     kdim = kdim_;
+    blk0 = wave * NI;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int q = (t >> 3) + 32 * i;        // physical row
-      const int m = prow(q);                  // logical row (prow is its own inverse)
-      const int r = min(row0 + m, nrows - 1);
-      soff[i] = q * 128 + ((c ^ (m & 7)) << 4);
+    for (int n = 0; n < NI; ++n) {
+      const int q = (blk0 + n) * 8 + (lane >> 3);          // physical row of this lane in block n
+      const int r = min(row0 + prow(q), nrows - 1);        // logical row (prow is its own inverse)
       const long long g = idx ? (long long)idx[r] : (long long)r;
-      ptr[i] = src + g * ld;
+      rowp[n] = src + g * ld;
+    }
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int m7 = ((lane >> 3) & 6) | par;              // low bits of the logical row: bit 0 = block parity
+      koff[par] = ((lane & 7) ^ m7) * 8;
     }
   }
-  template <int S, bool TAIL>
-  __device__ __forceinline__ void load(int kbase) {
-    int k = kbase + c * 8;
-    if (TAIL) k = min(k, kdim - 8);
+  __device__ __forceinline__ void fetch_rows(int) {}
+  template <bool TAIL>
+  __device__ __forceinline__ void issue(int kbase, char* tile) const {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) reg[S][i] = *reinterpret_cast<const uint4*>(ptr[i] + k);
+    for (int n = 0; n < NI; ++n) {
+      int k = kbase + koff[n & 1];
+      if (TAIL) k = min(k, kdim - 8);
+      async_copy16(rowp[n] + k, tile + (blk0 + n) * 1024);
+    }
   }
-  template <int S>
-  __device__ __forceinline__ void store(char* buf) const {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) *reinterpret_cast<uint4*>(buf + soff[i]) = reg[S][i];
-  }
+  __device__ __forceinline__ void zero_tail(char*, int, int) const {}
 };
 
 // per-lane byte offset of the operand fragment rows wbase + 32 f + (lane & 31) in a row tile
@@ -100,52 +114,58 @@ __device__ __forceinline__ void read_row_frags(const char* tile, int lane_off, i
 // "slow" tile: BK contraction rows of COLS bf16, pitch COLS * 2 bytes, stored as in memory except
 // that 16-byte chunk c of row k sits at slot c ^ ((k & 3) << 2).  A transposing read of a 16-lane
 // group touches 4 consecutive rows x 32 bytes; the swizzle puts those on different banks.
+// One 1 KB block = 2 rows (COLS = 256) or 4 rows (COLS = 128).
 // Columns past the end are clamped (never stored); contraction rows past kdim are clamped for the
-// address and zeroed in the tail stage.  Row ids of a gathered operand are fetched one stage early.
+// address and their LDS rows zeroed afterwards (tail stage only).  Row ids of a gathered operand are
+// fetched one stage early.
 // ------------------------------------------------------------------------------------------------
-template <int COLS, int NPRE>
+template <int COLS, int NW>
 struct SlowTileLoader {
-  static constexpr int CPR = COLS / 8;                 // chunks per contraction row
-  static constexpr int RSTEP = NTHREADS / CPR;         // rows between a thread's successive chunks (8 or 16)
-  static constexpr int NI = BK / RSTEP;                // chunks per thread and stage
+  static constexpr int LPR = COLS / 8;                 // lanes (chunks) per contraction row
+  static constexpr int RPI = 64 / LPR;                 // rows per 1 KB block
+  static constexpr int NI = BK / RPI / NW;             // blocks per wavefront and stage (even)
   static constexpr int PITCH = COLS * 2;
   const uint16_t* src;
   const int32_t* idx;
   long long ld;
-  int kdim, krow, soff0;
-  int nrow[NI];                                        // row ids for the next load() of a gathered operand
-  uint4 reg[NPRE][NI];
+  int kdim, blk0, rsub;
+  int coff[2];                                         // column (elements) of this lane's chunk in even / odd blocks
+  int nrow[NI];                                        // row ids for the next issue() of a gathered operand
 
   __device__ __forceinline__ void init(const uint16_t* src_, const int32_t* idx_, long long ld_, int col0, int ncols,
-                                       int kdim_, int t) {
-    idx = idx_; ld = ld_; kdim = kdim_;
-    const int c = t % CPR;
-    krow = t / CPR;
-    src = src_ + min(col0 + 8 * c, ncols - 8);
-    soff0 = krow * PITCH + ((c ^ ((krow & 3) << 2)) << 4);
+                                       int kdim_, int lane, int wave) {
+    src = src_; idx = idx_; ld = ld_; kdim = kdim_;
+    blk0 = wave * NI;
+    rsub = lane / LPR;
+    const int p = lane % LPR;
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int k3 = (RPI * par + rsub) & 3;             // low bits of the row index (blk0 is even)
+      coff[par] = min(col0 + 8 * (p ^ (k3 << 2)), ncols - 8);
+    }
   }
-  // fetch the row ids of the stage starting at kbase (no-op for an operand that is not gathered)
   __device__ __forceinline__ void fetch_rows(int kbase) {
     if (idx) {
 #pragma unroll
-      for (int i = 0; i < NI; ++i) nrow[i] = idx[min(kbase + krow + RSTEP * i, kdim - 1)];
+      for (int n = 0; n < NI; ++n) nrow[n] = idx[min(kbase + RPI * (blk0 + n) + rsub, kdim - 1)];
     }
   }
-  template <int S, bool TAIL>
-  __device__ __forceinline__ void load(int kbase) {
+  template <bool TAIL>
+  __device__ __forceinline__ void issue(int kbase, char* tile) const {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int k = kbase + krow + RSTEP * i;
-      const long long g = idx ? (long long)nrow[i] : (long long)(TAIL ? min(k, kdim - 1) : k);
-      uint4 v = *reinterpret_cast<const uint4*>(src + g * ld);
-      if (TAIL && k >= kdim) v = make_uint4(0, 0, 0, 0);
-      reg[S][i] = v;
+    for (int n = 0; n < NI; ++n) {
+      const int k = kbase + RPI * (blk0 + n) + rsub;
+      const long long g = idx ? (long long)nrow[n] : (long long)(TAIL ? min(k, kdim - 1) : k);
+      async_copy16(src + g * ld + coff[n & 1], tile + (blk0 + n) * 1024);
     }
   }
-  template <int S>
-  __device__ __forceinline__ void store(char* buf) const {
+  // zero the LDS rows kvalid .. BK-1 (contraction rows past the end of the operand)
+  __device__ __forceinline__ void zero_tail(char* tile, int kvalid, int t) const {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) *reinterpret_cast<uint4*>(buf + soff0 + i * RSTEP * PITCH) = reg[S][i];
+    for (int i = 0; i < BK * LPR / (64 * NW); ++i) {
+      const int q = t + 64 * NW * i;
+      if (q / LPR >= kvalid) *reinterpret_cast<uint4*>(tile + q * 16) = make_uint4(0, 0, 0, 0);
+    }
   }
 };
 
@@ -185,84 +205,47 @@ __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[FM][FN]) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Generic stage loop.  LA / LB are loaders, READ_A / READ_B fragment readers, MMA the multiply step.
-// NPRE = 1: the loads of stage kt+1 are issued before the MFMAs of stage kt and stored after them.
-// NPRE = 2: the loads of stage kt+2 are issued before the MFMAs of stage kt, and the registers of
-//           stage kt+1 (loaded one iteration earlier) are stored while they run.
+// Stage loop with two LDS stages: while the MFMAs of stage kt run, the copies of stage kt+1 are in
+// flight into the other buffer.  One barrier per stage: it publishes the landed stage and retires the
+// buffer the next copies will overwrite.
 // ------------------------------------------------------------------------------------------------
-template <int S, bool TAIL, class LA, class LB>
-__device__ __forceinline__ void issue_loads(LA& la, LB& lb, int kbase) {
-  la.template load<S, TAIL>(kbase);
-  lb.template load<S, TAIL>(kbase);
-}
-
-template <int NPRE, int A_BYTES, int STAGE, class LA, class LB, class Compute, class Fetch>
-__device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, int nk, bool tail, Compute&& compute,
-                                           Fetch&& fetch) {
-  // stage s covers contraction rows k0 + s BK ..; `tail` says the last stage is partial
-  auto load_stage = [&](auto sel, int s) {
-    constexpr int S = decltype(sel)::value;
-    if (tail && s == nk - 1) issue_loads<S, true>(la, lb, k0 + s * BK);
-    else issue_loads<S, false>(la, lb, k0 + s * BK);
-    fetch(la, lb, k0 + (s + 1) * BK);
-  };
-  using I0 = std::integral_constant<int, 0>;
-  using I1 = std::integral_constant<int, 1>;
+template <int A_BYTES, int STAGE, class LA, class LB, class Compute>
+__device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, int kend, int nk, Compute&& compute) {
   if (nk <= 0) return;
-  if constexpr (NPRE == 1) {
-    load_stage(I0{}, 0);
-    la.template store<0>(smem); lb.template store<0>(smem + A_BYTES);
+  const int t = threadIdx.x;
+  const bool tail = ((kend - k0) % BK) != 0;
+  auto issue = [&](int s) {
+    char* buf = smem + (s & 1) * STAGE;
+    const int kbase = k0 + s * BK;
+    if (tail && s == nk - 1) {
+      la.template issue<true>(kbase, buf);
+      lb.template issue<true>(kbase, buf + A_BYTES);
+    } else {
+      la.template issue<false>(kbase, buf);
+      lb.template issue<false>(kbase, buf + A_BYTES);
+    }
+    la.fetch_rows(kbase + BK);
+    lb.fetch_rows(kbase + BK);
+  };
+  issue(0);
+  for (int kt = 0; kt < nk; ++kt) {
+    char* cur = smem + (kt & 1) * STAGE;
+    wait_async_copies();
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const char* cur = smem + (kt & 1) * STAGE;
-      char* nxt = smem + ((kt + 1) & 1) * STAGE;
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT == 3
-      if (kt + 1 < nk) load_stage(I0{}, kt + 1);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
-      compute(cur);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
-      if (kt + 1 < nk) { la.template store<0>(nxt); lb.template store<0>(nxt + A_BYTES); }
-#endif
+    if (tail && kt == nk - 1) {
+      const int kvalid = kend - (k0 + kt * BK);
+      la.zero_tail(cur, kvalid, t);
+      lb.zero_tail(cur + A_BYTES, kvalid, t);
       __syncthreads();
     }
-  } else {
-    load_stage(I0{}, 0);
-    if (nk > 1) load_stage(I1{}, 1);
-    la.template store<0>(smem); lb.template store<0>(smem + A_BYTES);
-    __syncthreads();
-    for (int kt = 0; kt < nk; kt += 2) {
-      {  // even stage: registers set 0 is free (stored), set 1 holds stage kt+1
-        const char* cur = smem;
-        char* nxt = smem + STAGE;
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT == 3
-        if (kt + 2 < nk) load_stage(I0{}, kt + 2);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
-        if (kt + 1 < nk) { la.template store<1>(nxt); lb.template store<1>(nxt + A_BYTES); }
+    if (kt + 1 < nk) issue(kt + 1);
 #endif
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
-        compute(cur);
+    compute(cur);
 #endif
-        __syncthreads();
-      }
-      if (kt + 1 < nk) {  // odd stage
-        const char* cur = smem + STAGE;
-        char* nxt = smem;
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT == 3
-        if (kt + 3 < nk) load_stage(I1{}, kt + 3);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
-        if (kt + 2 < nk) { la.template store<0>(nxt); lb.template store<0>(nxt + A_BYTES); }
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
-        compute(cur);
-#endif
-        __syncthreads();
-      }
-    }
   }
+  __syncthreads();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -271,21 +254,20 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
 // tile is C[row l & 31][col 8 (v >> 2) + 4 (l >> 5) + (v & 3)].  The epilogue rounds to bf16, stages
 // 64 rows at a time through LDS and writes whole 16-byte pieces of the (scattered) dX rows.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NPRE>
+template <int BM, int BN, int NW>
 __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,
                                         const int32_t* __restrict__ idx_out, const uint16_t* __restrict__ W, int K,
                                         int Cin, int Cout, uint16_t* __restrict__ dX, int m0, int n0) {
-  constexpr int FM = BM / 64, FN = BN / 64;
+  constexpr int WGN = NW / 2;                     // wavefront grid: 2 rows x WGN columns
+  constexpr int FM = BM / 64, FN = BN / (32 * WGN);
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
+  const int wm = (wave / WGN) * (BM / 2), wn = (wave % WGN) * (BN / WGN);
 
-  using LA = RowTileLoader<BM, NPRE>;
-  using LB = SlowTileLoader<BN, NPRE>;
-  LA la;
-  LB lb;
-  la.init(dY, idx_in, Cout, m0, K, Cout, t);
-  lb.init(W, nullptr, Cin, n0, Cin, Cout, t);
+  RowTileLoader<BM, NW> la;
+  SlowTileLoader<BN, NW> lb;
+  la.init(dY, idx_in, Cout, m0, K, Cout, lane, __builtin_amdgcn_readfirstlane(wave));
+  lb.init(W, nullptr, Cin, n0, Cin, Cout, lane, __builtin_amdgcn_readfirstlane(wave));
 
   f32x16_t acc[FM][FN];
   zero_acc<FM, FN>(acc);
@@ -295,34 +277,30 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
   const int nk = (Cout + BK - 1) / BK;
 
   auto compute = [&](const char* cur) {
-    bf16x8_t a[2][FM], b[2][FN];
-    read_row_frags<FM>(cur, a_off, 0, lane, a[0]);
-    read_slow_frags<BN, FN>(cur + A_BYTES, b_off, 0, b[0]);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) {
-        read_row_frags<FM>(cur, a_off, ks + 1, lane, a[(ks + 1) & 1]);
-        read_slow_frags<BN, FN>(cur + A_BYTES, b_off, ks + 1, b[(ks + 1) & 1]);
-      }
+      bf16x8_t a[FM], b[FN];
+      read_slow_frags<BN, FN>(cur + A_BYTES, b_off, ks, b);
+      read_row_frags<FM>(cur, a_off, ks, lane, a);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   };
-  stage_loop<NPRE, A_BYTES, STAGE>(smem, la, lb, 0, nk, (Cout % BK) != 0, compute, [](LA&, LB&, int) {});
+  stage_loop<A_BYTES, STAGE>(smem, la, lb, 0, Cout, nk, compute);
 
   // epilogue
   constexpr int PITCH = BN * 2 + 16;              // staging row pitch (bytes)
   constexpr int CPR = BN / 8;                     // 16-byte pieces per staged row
-  constexpr int RPP = NTHREADS / CPR;             // rows written per pass of the block
+  constexpr int RPP = 64 * NW / CPR;              // rows written per pass of the block
   const int pc = t % CPR, pr = t / CPR;
   const bool col_ok = n0 + 8 * pc < Cin;
 #pragma unroll
   for (int i = 0; i < FM; ++i) {
     {
-      char* row = smem + ((wave >> 1) * 32 + (lane & 31)) * PITCH + (wn + 4 * (lane >> 5)) * 2;
+      char* row = smem + ((wave / WGN) * 32 + (lane & 31)) * PITCH + (wn + 4 * (lane >> 5)) * 2;
 #pragma unroll
       for (int jn = 0; jn < FN; ++jn)
 #pragma unroll
@@ -351,70 +329,45 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 // ------------------------------------------------------------------------------------------------
 // dW tile: BM output channels x BN input channels over the kept rows [j0, j1) of one split, written
 // as an fp32 partial.  Register v of lane l of a 32x32 tile is
-// C[row 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col l & 31].  Blocks of the first tile column also produce
-// the partial bias gradient db[o] = sum_j dY[row(j), o] by multiplying their dY fragments with ones.
+// C[row 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col l & 31].
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NPRE>
+template <int BM, int BN, int NW>
 __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                                         const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
-                                        float* __restrict__ part, float* __restrict__ dbp, int m0, int n0) {
-  constexpr int FM = BM / 64, FN = BN / 64;
-  constexpr int FD = FM / 2;                       // dY fragments whose row sums this wavefront owns
+                                        float* __restrict__ part, int m0, int n0) {
+  constexpr int WGN = NW / 2;                     // wavefront grid: 2 rows x WGN columns
+  constexpr int FM = BM / 64, FN = BN / (32 * WGN);
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = (wave >> 1) * (BM / 2), wn = (wave & 1) * (BN / 2);
-  const bool do_db = dbp != nullptr && n0 == 0;    // block-uniform
-  const bool upper = (wave & 1) != 0;              // this wavefront owns fragments FD .. 2 FD - 1
+  const int wm = (wave / WGN) * (BM / 2), wn = (wave % WGN) * (BN / WGN);
 
-  using LA = SlowTileLoader<BM, NPRE>;
-  using LB = SlowTileLoader<BN, NPRE>;
-  LA la;
-  LB lb;
-  la.init(dY, idx, Cout, m0, Cout, j1, t);
-  lb.init(Xk, nullptr, Cin, n0, Cin, j1, t);
+  SlowTileLoader<BM, NW> la;
+  SlowTileLoader<BN, NW> lb;
+  la.init(dY, idx, Cout, m0, Cout, j1, lane, __builtin_amdgcn_readfirstlane(wave));
+  lb.init(Xk, nullptr, Cin, n0, Cin, j1, lane, __builtin_amdgcn_readfirstlane(wave));
   la.fetch_rows(j0);
 
   f32x16_t acc[FM][FN];
   zero_acc<FM, FN>(acc);
-  f32x16_t accd[FD];
-#pragma unroll
-  for (int f = 0; f < FD; ++f)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) accd[f][v] = 0.f;
-  bf16x8_t ones;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
-
   int a_off[FM], b_off[FN];
   slow_tile_lane_offs<BM, FM>(wm, lane, a_off);
   slow_tile_lane_offs<BN, FN>(wn, lane, b_off);
   const int nk = (j1 - j0 + BK - 1) / BK;
 
   auto compute = [&](const char* cur) {
-    bf16x8_t a[2][FM], b[2][FN];
-    read_slow_frags<BM, FM>(cur, a_off, 0, a[0]);
-    read_slow_frags<BN, FN>(cur + A_BYTES, b_off, 0, b[0]);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) {
-        read_slow_frags<BM, FM>(cur, a_off, ks + 1, a[(ks + 1) & 1]);
-        read_slow_frags<BN, FN>(cur + A_BYTES, b_off, ks + 1, b[(ks + 1) & 1]);
-      }
+      bf16x8_t a[FM], b[FN];
+      read_slow_frags<BN, FN>(cur + A_BYTES, b_off, ks, b);
+      read_slow_frags<BM, FM>(cur, a_off, ks, a);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks & 1][i], b[ks & 1][j], acc[i][j], 0, 0, 0);
-      if (do_db) {
-#pragma unroll
-        for (int f = 0; f < FD; ++f)
-          accd[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(upper ? a[ks & 1][f + FD] : a[ks & 1][f], ones, accd[f],
-                                                            0, 0, 0);
-      }
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   };
-  stage_loop<NPRE, A_BYTES, STAGE>(smem, la, lb, j0, nk, ((j1 - j0) % BK) != 0, compute,
-                                   [](LA& a, LB&, int kbase) { a.fetch_rows(kbase); });
+  stage_loop<A_BYTES, STAGE>(smem, la, lb, j0, j1, nk, compute);
 
   if (m0 + BM <= Cout && n0 + BN <= Cin) {         // interior tile: no bounds checks
 #pragma unroll
@@ -439,14 +392,43 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
         }
       }
   }
-  if (do_db && (lane & 31) == 0) {      // every column of accd holds the row sums; column 0 writes them
+}
+
+// ------------------------------------------------------------------------------------------------
+// Partial bias gradient of one split: dbp[o] = sum_{j in [j0, j1)} dY[row(j), o] for 256 channels
+// starting at c0.  Thread (x = t & 31, y = t >> 5) owns 8 channels and every 8th row; the eight row
+// lanes are added in a fixed order through LDS.  Pure streaming work for blocks that ride along with
+// the dW tiles (same launch, same rows, so the reads meet the GEMM's in cache).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void colsum_block(char* smem, const uint16_t* __restrict__ dY,
+                                             const int32_t* __restrict__ idx, int Cout, int j0, int j1, int c0,
+                                             float* __restrict__ dbp) {
+  float(*red)[32][9] = reinterpret_cast<float(*)[32][9]>(smem);
+  const int x = threadIdx.x & 31, y = threadIdx.x >> 5;     // wavefronts past the fourth only keep the barrier company
+  const int col = c0 + 8 * x;
+  float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (col < Cout && y < 8) {
+#pragma unroll 4
+    for (int j = j0 + y; j < j1; j += 8) {
+      const long long g = idx ? (long long)idx[j] : (long long)j;
+      const uint4 v = *reinterpret_cast<const uint4*>(dY + g * Cout + col);
+      s[0] += bf16_lo(v.x); s[1] += bf16_hi(v.x); s[2] += bf16_lo(v.y); s[3] += bf16_hi(v.y);
+      s[4] += bf16_lo(v.z); s[5] += bf16_hi(v.z); s[6] += bf16_lo(v.w); s[7] += bf16_hi(v.w);
+    }
+  }
+  if (y < 8) {
 #pragma unroll
-    for (int f = 0; f < FD; ++f)
+    for (int e = 0; e < 8; ++e) red[y][x][e] = s[e];
+  }
+  __syncthreads();
+  if (y == 0 && col < Cout) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int o = m0 + wm + 32 * ((upper ? FD : 0) + f) + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        if (o < Cout) dbp[o] = accd[f][v];
-      }
+    for (int e = 0; e < 8; ++e) {
+      float a = 0.f;
+#pragma unroll
+      for (int yy = 0; yy < 8; ++yy) a += red[yy][x][e];
+      dbp[col + e] = a;
+    }
   }
 }
 
