@@ -63,8 +63,8 @@ class LinearLayer:
         return self.L.sbp_forward_cache(self.X.data_ptr(), idx_ptr, self.M, K, self.Cin, self.code,
                                         self.Xk.data_ptr(), self.stream)
 
-    def backward(self, idx_ptr, K):
-        return self.L.sbp_backward_linear(self.dY.data_ptr(), idx_ptr, self.Xk.data_ptr(), self.W.data_ptr(), self.M,
+    def backward(self, idx_ptr, inv_ptr, K):
+        return self.L.sbp_backward_linear(self.dY.data_ptr(), idx_ptr, inv_ptr, self.Xk.data_ptr(), self.W.data_ptr(), self.M,
                                           K, self.Cin, self.Cout, self.code, self.dW.data_ptr(), self.db.data_ptr(),
                                           self.dX.data_ptr(), self.ws.data_ptr(), self.ws.numel(), 0, self.stream)
 
@@ -90,7 +90,7 @@ class Job:
             ws_bytes = max(ws_bytes, sbp.backward_dwconv_workspace(wl.B, wl.H, wl.W, wl.dw_channels, 7, M, self.code, 0))
         self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
         self.idx = torch.empty(M, dtype=torch.int32, device="cuda")
-        self.inv = torch.empty(M, dtype=torch.int32, device="cuda") if wl.dw_channels else None
+        self.inv = torch.empty(M, dtype=torch.int32, device="cuda")   # the sampler's inverse map rides along
         # one seeded CPU draw per layer shape, copied into separate device buffers for every block so
         # that successive blocks do not hit each other's data in the 256 MB last-level cache
         srcs = [tuple(t.cuda() for t in si.linear_case(M, s.Cin, s.Cout, 100 + i, wl.dtype))
@@ -141,7 +141,7 @@ class Job:
             for lay in blk:                                         # forward side: keep only the kept rows
                 check(lay.cache(idx_ptr, K))
             for lay in reversed(blk):                               # backward side
-                check(lay.backward(idx_ptr, K))
+                check(lay.backward(idx_ptr, inv_ptr, K))
             if self.wl.dw_channels:
                 X, Wd, dY = self.dw_in[b]
                 dWd, db, dX = self.dw_out
@@ -267,7 +267,10 @@ def main():
     prof = job.kernel_breakdown(max(2, min(args.steps, 5)))
 
     # dominant kernel and its roofline
-    gemm_flops = {"dw_gemm": 2.0, "dx_gemm": 2.0}
+    # the bf16 path issues ONE launch per linear layer (dW tiles + dX tiles + db + zero-fill), recorded
+    # under "dw_gemm"; separate dX launches exist only on the plain fp32 path
+    fused = prof["dx_gemm"][1] == 0
+    gemm_flops = {"dw_gemm": 4.0 if fused else 2.0, "dx_gemm": 2.0}
     per_launch = {}
     for cls in ("dw_gemm", "dx_gemm"):
         tot_ms, n = prof[cls]
@@ -279,7 +282,7 @@ def main():
     if dom:
         avg_ms, fl = per_launch[dom]
         achieved = fl / avg_ms / 1e9
-        roofline = {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+        roofline = {"bound": "mfma", "kernel": "linear_bwd_kernel (dW + dX tiles)" if fused else dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
                     "avg_launch_us": round(avg_ms * 1e3, 2),
                     "flops_per_launch": fl}

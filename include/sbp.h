@@ -126,6 +126,9 @@ size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t 
  * The result is deterministic (no floating-point atomics).
  *   dY     device, in,  [M, Cout] (only rows in idx are read) or [K, Cout] with SBP_FLAG_DY_COMPACT
  *   idx    device, in,  [K] unique row ids in [0, M)
+ *   inv    device, in,  [M] inverse of idx as written by sbp_sample_indices (inv[idx[j]] = j; other
+ *                       entries may hold anything that is not a position of that row), or NULL: then it
+ *                       is built in the workspace by one more small kernel.  Only used to zero-fill dX.
  *   X_k    device, in,  [K, Cin] rows cached by sbp_forward_cache (may be NULL if dW is NULL)
  *   W      device, in,  [Cout, Cin]                       (may be NULL if dX is NULL)
  *   dW, db, dX   device, out; each may be NULL to skip that output
@@ -134,7 +137,8 @@ size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t 
  * Channel counts that are multiples of 8 take the MFMA path for SBP_BF16; any other shape
  * and SBP_F32 take a plain (slower) kernel -- never an error.
  */
-int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const void* X_k, const void* W,
+int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* inv, const void* X_k,
+                            const void* W,
                             int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
                             float* dW, float* db, void* dX,
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);

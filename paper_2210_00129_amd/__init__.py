@@ -94,7 +94,7 @@ def backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags=0) -> int:
 
 
 def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), dW=None, db=None, dX=None,
-                    workspace=None):
+                    workspace=None, inv=None):
     """SBP backward of Y = X W^T + b on the kept rows.  Returns (dW fp32, db fp32, dX)."""
     Cout, Cin = W.shape
     K = idx.numel() if idx is not None else dY.shape[0]
@@ -115,7 +115,7 @@ def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), d
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     _lib.check(_lib.lib().sbp_backward_linear(
-        _dev(dY, "dY"), _dev(idx, "idx"), _dev(X_k, "X_k"), _dev(W, "W"), M, K, Cin, Cout, code,
+        _dev(dY, "dY"), _dev(idx, "idx"), _dev(inv, "inv"), _dev(X_k, "X_k"), _dev(W, "W"), M, K, Cin, Cout, code,
         _dev(dW, "dW"), _dev(db, "db"), _dev(dX, "dX"), _dev(workspace, "workspace"), workspace.numel(),
         flags, _stream(dev)))
     return dW, db, dX

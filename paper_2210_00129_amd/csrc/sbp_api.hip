@@ -137,7 +137,8 @@ size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t 
   return plan_linear(M, K, Cin, Cout, dtype, flags).bytes;
 }
 
-int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const void* Xk, const void* W, int64_t M,
+int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* inv, const void* Xk, const void* W,
+                            int64_t M,
                             int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, float* dW, float* db,
                             void* dX, void* ws, size_t ws_bytes, uint32_t flags, void* stream) {
   int32_t st = validate_linear(M, K, Cin, Cout, dtype, flags);
@@ -154,7 +155,7 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const void* Xk, 
     if ((uintptr_t)ws % 256) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   }
   if (!dW && !db && !dX) return SBP_OK;
-  return launch_backward_linear(p, dY, idx, Xk, W, M, K, Cin, Cout, dtype, dW, db, dX, ws, flags,
+  return launch_backward_linear(p, dY, idx, inv, Xk, W, M, K, Cin, Cout, dtype, dW, db, dX, ws, flags,
                                 (hipStream_t)stream);
 }
 

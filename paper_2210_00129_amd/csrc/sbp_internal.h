@@ -44,11 +44,10 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
 // ---- linear backward ---------------------------------------------------------------------
 struct LinearPlan {
   bool   mfma;          // bf16 MFMA path (else plain kernels)
-  int    bm_w, bn_w;    // tile of the dW contraction (output channels x input channels)
-  int    bm_x, bn_x;    // tile of the dX contraction (kept rows x input channels)
+  int    bm_w, bn_w;    // tile of both contractions (rows x columns)
   int    splits;        // split-K factor of the dW contraction
   int    rows_per_split;// kept rows per split (multiple of the k-step)
-  int    nw_w, nw_x;    // wavefronts per block of the two contractions (4 or 8)
+  int    nw_w;          // wavefronts per block (4 or 8)
   int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
   int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]
@@ -56,8 +55,8 @@ struct LinearPlan {
   size_t bytes;
 };
 LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags);
-int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const void* Xk,
-                               const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
+int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv,
+                               const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
                                int32_t dtype, float* dW, float* db, void* dX, void* ws, uint32_t flags,
                                hipStream_t s);
 

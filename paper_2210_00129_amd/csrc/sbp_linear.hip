@@ -25,49 +25,84 @@ __device__ __forceinline__ int xcd_chunked_id(int wg, int ntiles) {
   return (wg % kNumXCD) * per + wg / kNumXCD;
 }
 
-template <int BM, int BN, int NW>
-__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1)
-dx_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,   // rows of dY (NULL: compact)
-               const int32_t* __restrict__ idx_out,                                    // rows of dX (NULL: compact)
-               const uint16_t* __restrict__ W, int K, int Cin, int Cout, uint16_t* __restrict__ dX) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int tiles_n = (Cin + BN - 1) / BN;
-  const int ntiles = ((K + BM - 1) / BM) * tiles_n;
-  const int L = xcd_chunked_id(blockIdx.x, ntiles);
-  if (L >= ntiles) return;
-  const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-  dx_tile<BM, BN, NW>(smem, dY, idx_in, idx_out, W, K, Cin, Cout, dX, tile_m * BM, tile_n * BN);
+static constexpr int kDbSliceRows = 128;     // smallest row slice of a column-sum block
+static constexpr int kMaxDbSlices = 64;      // at most this many partial sums per channel
+
+// Everything one linear layer's backward needs, in one launch.  The grid is four segments of
+// workgroups, each doing one kind of work:
+//   [zero]  write +0 to the rows of dX that are not kept (row m is kept iff idx[inv[m]] == m)
+//   [db]    column sums of the kept rows of dY, one block per (row slice, 256 channels)
+//   [dX]    BM x BN tiles of dX = dY_k W, scattered to the kept rows
+//   [dW]    BM x BN tiles of the per-split partial sums of dW = dY_k^T X_k
+// The helper segments come first (short, they share the CUs with the tiles); zero + db is padded to a
+// multiple of 8 and each tile segment is a multiple of 8, so the XCD chunking of a segment is exact.
+struct LinArgs {
+  const uint16_t* dY;
+  const int32_t* idx_in;    // rows of dY (NULL: dY is compact)
+  const int32_t* idx_out;   // rows of dX (NULL: dX is compact)
+  const int32_t* idx;       // the keep list itself (for the kept-row test)
+  const int32_t* inv;
+  const uint16_t* Xk;
+  const uint16_t* W;
+  uint16_t* dX;
+  float* part;
+  float* dbp;
+  int K, M, Cin, Cout, rows_per_split, db_slice_rows;
+  int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
+};
+
+__device__ __forceinline__ void zero_rows_block(const LinArgs& a, int blk) {
+  const int ppr = a.Cin / 8;                                   // 16-byte pieces per row
+  const long long total = (long long)a.M * ppr;
+  uint4* out = reinterpret_cast<uint4*>(a.dX);
+  for (long long e = (long long)blk * blockDim.x + threadIdx.x; e < total; e += (long long)a.n_zero * blockDim.x) {
+    const int m = (int)(e / ppr);
+    const int j = a.inv[m];
+    const bool kept = (unsigned)j < (unsigned)a.K && a.idx[j] == m;
+    if (!kept) out[e] = make_uint4(0, 0, 0, 0);
+  }
 }
 
-// Grid: when db is wanted, one column-sum block per (slice of kept rows, 256 output channels); then the
-// dW tiles (padded to a multiple of 8, XCD-chunked).
-static constexpr int kDbSliceRows = 128;     // smallest slice
-static constexpr int kMaxDbSlices = 64;      // at most this many partial sums per channel
 template <int BM, int BN, int NW>
-__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1)
-dw_mfma_kernel(const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,      // rows of dY (NULL: compact)
-               const uint16_t* __restrict__ Xk, int K, int Cin, int Cout, int rows_per_split,
-               float* __restrict__ partial, float* __restrict__ dbp, int db_blocks, int db_slice_rows) {
+__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_kernel(const LinArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int nsplit = (K + rows_per_split - 1) / rows_per_split;
-  if ((int)blockIdx.x < db_blocks) {          // column-sum blocks go first: they share the CUs with the tiles
-    const int nslice = (K + db_slice_rows - 1) / db_slice_rows;
-    const int slice = blockIdx.x % nslice, chunk = blockIdx.x / nslice;
-    const int j0 = slice * db_slice_rows, j1 = min(K, j0 + db_slice_rows);
-    colsum_block(smem, dY, idx, Cout, j0, j1, chunk * 256, dbp + (long long)slice * Cout);
+  int wg = blockIdx.x;
+  if (wg < a.n_helper) {
+    if (wg < a.n_zero) {
+      zero_rows_block(a, wg);
+    } else {
+      const int b = wg - a.n_zero;
+      const int nslice = (a.K + a.db_slice_rows - 1) / a.db_slice_rows;
+      const int slice = b % nslice, chunk = b / nslice;
+      if (a.dbp && chunk * 256 < a.Cout) {
+        const int j0 = slice * a.db_slice_rows, j1 = min(a.K, j0 + a.db_slice_rows);
+        colsum_block(smem, a.dY, a.idx_in, a.Cout, j0, j1, chunk * 256, a.dbp + (long long)slice * a.Cout);
+      }
+    }
     return;
   }
-  const int wg = blockIdx.x - db_blocks;
-  const int tiles_n = (Cin + BN - 1) / BN, tiles_m = (Cout + BM - 1) / BM;
+  wg -= a.n_helper;
+  const int tiles_n = (a.Cin + BN - 1) / BN;
+  if (wg < a.n_dx) {
+    const int ntiles = ((a.K + BM - 1) / BM) * tiles_n;
+    const int L = xcd_chunked_id(wg, ntiles);
+    if (L >= ntiles) return;
+    const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
+    dx_tile<BM, BN, NW>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * BM, tile_n * BN);
+    return;
+  }
+  wg -= a.n_dx;
+  const int tiles_m = (a.Cout + BM - 1) / BM;
+  const int nsplit = (a.K + a.rows_per_split - 1) / a.rows_per_split;
   const int ntiles = tiles_m * tiles_n * nsplit;
   const int L = xcd_chunked_id(wg, ntiles);
   if (L >= ntiles) return;
   const int split = L / (tiles_m * tiles_n);
   const int rem = L - split * tiles_m * tiles_n;
   const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
-  const int j0 = split * rows_per_split, j1 = min(K, j0 + rows_per_split);
-  dw_tile<BM, BN, NW>(smem, dY, idx, Xk, Cin, Cout, j0, j1, partial + (long long)split * Cout * Cin, tile_m * BM,
-                  tile_n * BN);
+  const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
+  dw_tile<BM, BN, NW>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, a.part + (long long)split * a.Cout * a.Cin,
+                      tile_m * BM, tile_n * BN);
 }
 
 // dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.
@@ -242,8 +277,8 @@ __global__ void __launch_bounds__(NTHREADS) plain_db_kernel(const T* __restrict_
 // ------------------------------------------------------------------------------------------------
 static constexpr int kNumCU = 256;
 
-// Debug aid: SBP_TILE_DW / SBP_TILE_DX = "256x256x8" | "256x256x4" | "256x128x4" | "128x128x4" force a tile
-// shape (rows x columns x wavefronts).
+// Debug aid: SBP_TILE = "256x256x8" | "256x256x4" | "256x128x4" | "128x128x4" forces a tile shape
+// (rows x columns x wavefronts) for both contractions.
 static bool env_tile(const char* name, int* bm, int* bn, int* nw) {
   const char* v = std::getenv(name);
   if (!v) return false;
@@ -259,13 +294,12 @@ static bool env_tile(const char* name, int* bm, int* bn, int* nw) {
 LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags) {
   LinearPlan p{};
   p.mfma = dtype == SBP_BF16 && Cin % 8 == 0 && Cout % 8 == 0;
-  p.bm_w = p.bn_w = p.bm_x = p.bn_x = 128;
-  p.nw_w = p.nw_x = 4;
+  p.bm_w = p.bn_w = 128;
+  p.nw_w = 4;
   int splits = 1;
   if (K > 0) {
     if (p.mfma) {
-      env_tile("SBP_TILE_DW", &p.bm_w, &p.bn_w, &p.nw_w);
-      env_tile("SBP_TILE_DX", &p.bm_x, &p.bn_x, &p.nw_x);
+      env_tile("SBP_TILE", &p.bm_w, &p.bn_w, &p.nw_w);
       // enough blocks to fill the chip's block slots once, each split at least 4 stages long
       const int64_t tiles = ceil_div(Cout, p.bm_w) * ceil_div(Cin, p.bn_w);
       const int64_t slots = (p.bm_w + p.bn_w <= 256) ? 2 * kNumCU : kNumCU;
@@ -324,30 +358,25 @@ static void allow_big_lds(KernelT kernel, size_t lds) {
 }
 
 template <int BM, int BN, int NW>
-static void launch_dx_mfma(const uint16_t* dY, const int32_t* idx_in, const int32_t* idx_out, const uint16_t* W,
-                           int K, int Cin, int Cout, uint16_t* dX, hipStream_t s) {
-  const int tiles = (int)(ceil_div(K, BM) * ceil_div(Cin, BN));
+static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero,
+                              hipStream_t s) {
   const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  allow_big_lds(dx_mfma_kernel<BM, BN, NW>, lds);
-  SBP_LAUNCH(SBP_PROF_DX_GEMM, s, (dx_mfma_kernel<BM, BN, NW>), dim3(8 * (unsigned)ceil_div(tiles, 8)), dim3(64 * NW), lds, s, dY, idx_in, idx_out,
-             W, K, Cin, Cout, dX);
+  allow_big_lds(linear_bwd_kernel<BM, BN, NW>, lds);
+  const long long tiles_n = ceil_div(a.Cin, BN);
+  a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M * (a.Cin / 8), 64 * NW * 16))) : 0;
+  const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
+  a.n_helper = (int)(8 * ceil_div(a.n_zero + n_db, 8));
+  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, BM) * tiles_n, 8)) : 0;
+  a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, BM) * tiles_n * p.splits, 8)) : 0;
+  const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
+  if (grid == 0) return;
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 
-template <int BM, int BN, int NW>
-static void launch_dw_mfma(const LinearPlan& p, const uint16_t* dY, const int32_t* idx, const uint16_t* Xk, int K,
-                           int Cin, int Cout, float* part, float* dbp, hipStream_t s) {
-  const int tiles = (int)(ceil_div(Cout, BM) * ceil_div(Cin, BN));
-  const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  allow_big_lds(dw_mfma_kernel<BM, BN, NW>, lds);
-  const unsigned gemm_blocks = 8 * (unsigned)ceil_div((long long)tiles * p.splits, 8);
-  const unsigned db_blocks = dbp ? (unsigned)(ceil_div(Cout, 256) * p.db_slices) : 0u;
-  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (dw_mfma_kernel<BM, BN, NW>), dim3(gemm_blocks + db_blocks), dim3(64 * NW), lds, s, dY,
-             idx, Xk, K, Cin, Cout, p.rows_per_split, part, dbp, (int)db_blocks, p.db_slice_rows);
-}
-
-int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const void* Xk,
-                               const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
-                               float* dW, float* db, void* dX, void* ws, uint32_t flags, hipStream_t s) {
+int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv_in,
+                               const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
+                               int32_t dtype, float* dW, float* db, void* dX, void* ws, uint32_t flags,
+                               hipStream_t s) {
   const int eb = dtype == SBP_F32 ? 4 : 2;
   const bool dy_compact = flags & SBP_FLAG_DY_COMPACT, dx_compact = flags & SBP_FLAG_DX_COMPACT;
   const int accumulate = (flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
@@ -355,7 +384,8 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   const int32_t* idx_out = dx_compact ? nullptr : idx;
   float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_partial);
   float* dbp = part + (size_t)p.splits * Cout * Cin;
-  int32_t* inv = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.off_inv);
+  int32_t* inv_ws = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.off_inv);
+  const int32_t* inv = inv_in;
   const long long nW = (long long)Cin * Cout;
 
   if (K == 0) {  // nothing kept: gradients are zero
@@ -370,38 +400,32 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   }
 
   const bool scatter = dX && !dx_compact;
-  if (scatter)
-    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, mark_rows_kernel, dim3((unsigned)ceil_div(K, NTHREADS)), dim3(NTHREADS), 0, s, idx, (int)K, inv);
+  if (scatter && !inv) {   // no inverse map from the caller: build one (needs no clearing, see mark_rows_kernel)
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, mark_rows_kernel, dim3((unsigned)ceil_div(K, NTHREADS)), dim3(NTHREADS), 0, s, idx,
+               (int)K, inv_ws);
+    inv = inv_ws;
+  }
 
   const bool aligned = ((uintptr_t)dY % 16 == 0) && ((uintptr_t)Xk % 16 == 0) && ((uintptr_t)W % 16 == 0) &&
                        ((uintptr_t)dX % 16 == 0);
   const bool use_mfma = p.mfma && aligned;
   if (use_mfma) {
     const uint16_t* dYh = static_cast<const uint16_t*>(dY);
-    const uint16_t* Xkh = static_cast<const uint16_t*>(Xk);
-    const uint16_t* Wh = static_cast<const uint16_t*>(W);
-    uint16_t* dXh = static_cast<uint16_t*>(dX);
-    if (dW || db) {   // db rides on the dW tiles
-      float* dbq = db ? dbp : nullptr;
-      if (p.bm_w == 256 && p.bn_w == 256 && p.nw_w == 8)
-        launch_dw_mfma<256, 256, 8>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
-      else if (p.bm_w == 256 && p.bn_w == 256)
-        launch_dw_mfma<256, 256, 4>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
-      else if (p.bm_w == 256)
-        launch_dw_mfma<256, 128, 4>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
-      else
-        launch_dw_mfma<128, 128, 4>(p, dYh, idx_in, Xkh, (int)K, Cin, Cout, part, dbq, s);
-    }
-    if (dX) {
-      if (p.bm_x == 256 && p.bn_x == 256 && p.nw_x == 8)
-        launch_dx_mfma<256, 256, 8>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
-      else if (p.bm_x == 256 && p.bn_x == 256)
-        launch_dx_mfma<256, 256, 4>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
-      else if (p.bm_x == 256)
-        launch_dx_mfma<256, 128, 4>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
-      else
-        launch_dx_mfma<128, 128, 4>(dYh, idx_in, idx_out, Wh, (int)K, Cin, Cout, dXh, s);
-    }
+    LinArgs a{};
+    a.dY = dYh; a.idx_in = idx_in; a.idx_out = idx_out; a.idx = idx; a.inv = inv;
+    a.Xk = static_cast<const uint16_t*>(Xk); a.W = static_cast<const uint16_t*>(W);
+    a.dX = static_cast<uint16_t*>(dX); a.part = part; a.dbp = db ? dbp : nullptr;
+    a.K = (int)K; a.M = (int)M; a.Cin = Cin; a.Cout = Cout;
+    a.rows_per_split = p.rows_per_split; a.db_slice_rows = p.db_slice_rows;
+    const bool want_dx = dX != nullptr, want_dw = dW != nullptr;
+    if (p.bm_w == 256 && p.nw_w == 8)
+      launch_linear_bwd<256, 256, 8>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.bm_w == 256 && p.bn_w == 256)
+      launch_linear_bwd<256, 256, 4>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.bm_w == 256)
+      launch_linear_bwd<256, 128, 4>(p, a, want_dx, want_dw, scatter, s);
+    else
+      launch_linear_bwd<128, 128, 4>(p, a, want_dx, want_dw, scatter, s);
   } else if (dtype == SBP_F32) {
     launch_plain<float>(p, (const float*)dY, idx_in, idx_out, (const float*)Xk, (const float*)W, K, Cin, Cout, part,
                         dbp, dW != nullptr, db != nullptr, (float*)dX, s);
@@ -424,7 +448,7 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     }
   }
 
-  if (scatter) {
+  if (scatter && !use_mfma) {   // the MFMA launch zero-fills by itself
     const long long row_bytes = (long long)Cin * eb;
     if (row_bytes % 16 == 0 && (uintptr_t)dX % 16 == 0) {
       const int ppr = (int)(row_bytes / 16);

@@ -34,7 +34,7 @@ def bits(t):
     return t.view(torch.int16 if t.dtype == torch.bfloat16 else torch.int32).numpy()
 
 
-def check_linear(X, W, dY, idx_np, dtype, flags=0, check_cache=True):
+def check_linear(X, W, dY, idx_np, dtype, flags=0, check_cache=True, inv_mode=None):
     """Runs cache + backward on the GPU and the oracle; returns the three normalised errors."""
     M = X.shape[0]
     dev = "cuda"
@@ -46,7 +46,17 @@ def check_linear(X, W, dY, idx_np, dtype, flags=0, check_cache=True):
     dY_in = dYd
     if flags & sbp.FLAG_DY_COMPACT:
         dY_in = dYd[idx.long()].contiguous()
-    dW, db, dX = sbp.backward_linear(dY_in, idx, Xk, Wd_, M=M, flags=flags)
+    inv = None
+    if inv_mode is not None:
+        # the inverse map a caller may hand over: exact where rows are kept, -1 ("sampler") or
+        # arbitrary numbers ("garbage") where they are dropped
+        inv_np = oracle.inverse_map(idx_np, M)
+        if inv_mode == "garbage":
+            rng = np.random.default_rng(1)
+            junk = rng.integers(-5, max(len(idx_np), 1) + 5, size=M).astype(np.int32)
+            inv_np = np.where(inv_np >= 0, inv_np, junk).astype(np.int32)
+        inv = torch.from_numpy(inv_np).to(dev)
+    dW, db, dX = sbp.backward_linear(dY_in, idx, Xk, Wd_, M=M, flags=flags, inv=inv)
     torch.cuda.synchronize()
     rW, rb, rX = oracle.backward_linear(si.to_f64(dY), idx_np, si.to_f64(X)[idx_np], si.to_f64(W), M)
     out_tol = TOL_F32 if dtype == "f32" else TOL_BF16_TIGHT

@@ -112,7 +112,7 @@ def test_backward_linear_argument_errors():
     def call(**kw):
         a = dict(args)
         a.update(kw)
-        return L.sbp_backward_linear(a["dY"], a["idx"], a["Xk"], a["W"], a["M"], a["K"], a["Cin"], a["Cout"],
+        return L.sbp_backward_linear(a["dY"], a["idx"], None, a["Xk"], a["W"], a["M"], a["K"], a["Cin"], a["Cout"],
                                      a["dtype"], a["dW"], a["db"], a["dX"], a["ws"], a["ws_bytes"], a["flags"], None)
 
     assert call(dY=None) == -1

@@ -93,6 +93,26 @@ def test_linear_bf16_mfma_tiles_and_ragged_tails(shape, k):
     check_linear(X, W, dY, idx, "bf16")
 
 
+@pytest.mark.parametrize("inv_mode", ["sampler", "garbage"])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_linear_with_caller_supplied_inverse_map(inv_mode, dtype):
+    X, W, dY, idx = _grid_case(5, 1, 14, 14, 192, 320, 2, dtype, 17)
+    check_linear(X, W, dY, idx, dtype, inv_mode=inv_mode)
+
+
+def test_linear_single_outputs():
+    # each output on its own (the launch then carries only that kind of work)
+    X, W, dY, idx = _grid_case(4, 1, 14, 14, 128, 256, 2, "bf16", 19)
+    M = X.shape[0]
+    idxd = torch.from_numpy(idx).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idxd)
+    full = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda())
+    for i, name in enumerate(("dW", "db", "dX")):
+        one = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda(), want=(name,))
+        assert [o is not None for o in one] == [j == i for j in range(3)]
+        assert np.array_equal(bits(one[i]), bits(full[i]))
+
+
 @pytest.mark.parametrize("shape", [(20, 36), (7, 5), (64, 30)])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_linear_plain_path_odd_channels(shape, dtype):
