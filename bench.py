@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements of the other workloads")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--main-only", action="store_true",
+                    help="only the timed region at the chosen ratio (for profiler runs: no r=1 leg, no event pass)")
     return ap.parse_args()
 
 
@@ -264,6 +266,11 @@ def main():
     value = flops / ms / 1e9                       # TFLOP/s
     bytes_step = job.algorithmic_bytes_per_step()
     K_r = job.K
+    if args.main_only:
+        print(json.dumps({"metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "ms_per_step": round(ms, 4),
+                          "steps": args.steps, "warmup": args.warmup, "config": {"workload": wl.name,
+                                                                                 "keep_ratio": args.ratio}}))
+        return
     prof = job.kernel_breakdown(max(2, min(args.steps, 5)))
 
     # dominant kernel and its roofline

@@ -117,15 +117,26 @@ __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __
        e += (long long)gridDim.x * blockDim.x) {
     if (e < nW4) {
       float4 a = accumulate ? reinterpret_cast<const float4*>(dW)[e] : make_float4(0, 0, 0, 0);
-      for (int s = 0; s < nsplit_w; ++s) {
-        const float4 p = reinterpret_cast<const float4*>(partial + (long long)s * nW)[e];
-        a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+      for (int s0 = 0; s0 < nsplit_w; s0 += 4) {   // four loads in flight, added in split order
+        float4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          p[u] = s0 + u < nsplit_w ? reinterpret_cast<const float4*>(partial + (long long)(s0 + u) * nW)[e]
+                                   : make_float4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { a.x += p[u].x; a.y += p[u].y; a.z += p[u].z; a.w += p[u].w; }
       }
       reinterpret_cast<float4*>(dW)[e] = a;
     } else {
       const long long o = e - nW4;
       float a = accumulate ? db[o] : 0.f;
-      for (int s = 0; s < nsplit_b; ++s) a += dbp[(long long)s * Cout + o];
+      for (int s0 = 0; s0 < nsplit_b; s0 += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = s0 + u < nsplit_b ? dbp[(long long)(s0 + u) * Cout + o] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a += p[u];
+      }
       db[o] = a;
     }
   }

@@ -59,8 +59,8 @@ __host__ __device__ static inline void sample_unit(const SampleGeom& g, long lon
                                                    int32_t* __restrict__ inv) {
   const int units = g.P + g.ch * g.cw;              // work items per sample
   {
-    const int b = (int)(t / units);
-    const int u = (int)(t - (long long)b * units);
+    const int b = (int)((unsigned)t / (unsigned)units);       // t < B * units < 2^31 (row ids are int32)
+    const int u = (int)t - b * units;
     const int row0 = b * g.N;
     const int out0 = b * g.per_sample_K;
     if (u < g.P) {                                   // always-kept prefix row
