@@ -193,6 +193,19 @@ class Job:
         return total * self.wl.blocks
 
 
+def measured_traffic(name):
+    """HBM-side bytes per launch of the dominant kernel, as measured with rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE and written down in profiles/ (bench.py cannot run the profiler on itself)."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH"):
+                return int(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(wl, r, seconds, si):
     """The fp64 oracle, as it stands, on the host cores: whole blocks of the same workload until the
     time budget is used (at least one block)."""
@@ -290,7 +303,9 @@ def main():
         avg_ms, fl = per_launch[dom]
         achieved = fl / avg_ms / 1e9
         roofline = {"bound": "mfma", "kernel": "linear_bwd_kernel (dW + dX tiles)" if fused else dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": measured_traffic("linear_bwd_kernel_vit_base_r0.5.md")
+                    if (wl.name == "vit_base" and args.ratio == 0.5) else None,
                     "avg_launch_us": round(avg_ms * 1e3, 2),
                     "flops_per_launch": fl}
     breakdown = {c: {"ms_per_step": round(v[0] / max(2, min(args.steps, 5)), 4), "launches": v[1]}
