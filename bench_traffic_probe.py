@@ -3,9 +3,9 @@
 
 Run it twice under rocprofv3, once per counter (the two do not fit one pass):
 
-    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch -- python3 bench_traffic_probe.py
-    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write -- python3 bench_traffic_probe.py
-    python3 bench_traffic_probe.py --summarize gpurun_out/pmc_fetch gpurun_out/pmc_write
+    rocprofv3 --pmc FETCH_SIZE --output-format csv -d prof_out/pmc_fetch -- python3 bench_traffic_probe.py
+    rocprofv3 --pmc WRITE_SIZE --output-format csv -d prof_out/pmc_write -- python3 bench_traffic_probe.py
+    python3 bench_traffic_probe.py --summarize prof_out/pmc_fetch prof_out/pmc_write
 
 The workload: a plain device-to-device copy of known size (the calibration: what the counter reads
 for a known number of bytes), then one SBP linear backward per ViT-Base layer shape at r = 0.5 and one
