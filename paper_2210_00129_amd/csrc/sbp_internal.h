@@ -48,6 +48,7 @@ struct LinearPlan {
   int    splits;        // split-K factor of the dW contraction
   int    rows_per_split;// kept rows per split (multiple of the k-step)
   int    nw_w;          // wavefronts per block (4 or 8)
+  int    kb;            // contraction elements per LDS stage (64: two stages, 32: four stages)
   int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
   int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]

@@ -27,6 +27,7 @@ __device__ __forceinline__ int xcd_chunked_id(int wg, int ntiles) {
 
 static constexpr int kDbSliceRows = 128;     // smallest row slice of a column-sum block
 static constexpr int kMaxDbSlices = 64;      // at most this many partial sums per channel
+static constexpr int kMaxRowsPerSplit = 2048;   // kept rows per dW split (their ids are staged in LDS)
 
 // Everything one linear layer's backward needs, in one launch.  The grid is four segments of
 // workgroups, each doing one kind of work:
@@ -63,7 +64,7 @@ __device__ __forceinline__ void zero_rows_block(const LinArgs& a, int blk) {
   }
 }
 
-template <int BM, int BN, int NW>
+template <int BM, int BN, int NW, int KB, int NSTAGE>
 __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_kernel(const LinArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int wg = blockIdx.x;
@@ -88,7 +89,7 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
     const int L = xcd_chunked_id(wg, ntiles);
     if (L >= ntiles) return;
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-    dx_tile<BM, BN, NW>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * BM, tile_n * BN);
+    dx_tile<BM, BN, NW, KB, NSTAGE>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * BM, tile_n * BN);
     return;
   }
   wg -= a.n_dx;
@@ -101,7 +102,7 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
   const int rem = L - split * tiles_m * tiles_n;
   const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
   const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
-  dw_tile<BM, BN, NW>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, a.part + (long long)split * a.Cout * a.Cin,
+  dw_tile<BM, BN, NW, KB, NSTAGE>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, a.part + (long long)split * a.Cout * a.Cin,
                       tile_m * BM, tile_n * BN);
 }
 
@@ -288,17 +289,16 @@ __global__ void __launch_bounds__(NTHREADS) plain_db_kernel(const T* __restrict_
 // ------------------------------------------------------------------------------------------------
 static constexpr int kNumCU = 256;
 
-// Debug aid: SBP_TILE = "256x256x8" | "256x256x4" | "256x128x4" | "128x128x4" forces a tile shape
-// (rows x columns x wavefronts) for both contractions.
-static bool env_tile(const char* name, int* bm, int* bn, int* nw) {
+// Debug aid: SBP_TILE = "128x128x4x64" | "128x128x4x32" | "256x256x8x64" | "256x256x8x32" forces a tile
+// shape (rows x columns x wavefronts x stage length; stage length 32 runs a 4-deep ring, 64 a 2-deep one).
+static bool env_tile(const char* name, int* bm, int* bn, int* nw, int* kb) {
   const char* v = std::getenv(name);
   if (!v) return false;
-  int a = 0, b = 0, w = 4;
-  if (std::sscanf(v, "%dx%dx%d", &a, &b, &w) < 2) return false;
-  const bool ok = (a == 256 && b == 256 && (w == 4 || w == 8)) || (a == 256 && b == 128 && w == 4) ||
-                  (a == 128 && b == 128 && w == 4);
+  int a = 0, b = 0, w = 4, k = 64;
+  if (std::sscanf(v, "%dx%dx%dx%d", &a, &b, &w, &k) < 2) return false;
+  const bool ok = ((a == 256 && b == 256 && w == 8) || (a == 128 && b == 128 && w == 4)) && (k == 32 || k == 64);
   if (!ok) return false;
-  *bm = a; *bn = b; *nw = w;
+  *bm = a; *bn = b; *nw = w; *kb = k;
   return true;
 }
 
@@ -307,22 +307,24 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   p.mfma = dtype == SBP_BF16 && Cin % 8 == 0 && Cout % 8 == 0;
   p.bm_w = p.bn_w = 128;
   p.nw_w = 4;
+  p.kb = 64;
   int splits = 1;
   if (K > 0) {
     if (p.mfma) {
-      env_tile("SBP_TILE", &p.bm_w, &p.bn_w, &p.nw_w);
+      env_tile("SBP_TILE", &p.bm_w, &p.bn_w, &p.nw_w, &p.kb);
       // enough blocks to fill the chip's block slots once, each split at least 4 stages long
       const int64_t tiles = ceil_div(Cout, p.bm_w) * ceil_div(Cin, p.bn_w);
       const int64_t slots = (p.bm_w + p.bn_w <= 256) ? 2 * kNumCU : kNumCU;
       int64_t want = std::max<int64_t>(1, slots / tiles);
-      int64_t max_by_len = std::max<int64_t>(1, K / (4 * BK));
+      int64_t max_by_len = std::max<int64_t>(1, K / (4 * 64));
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_len), 64));
+      splits = (int)std::max<int64_t>(splits, ceil_div(K, kMaxRowsPerSplit));   // the split's row ids sit in LDS
     } else {
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(K, 512), 64));
     }
   }
   int64_t rps = K > 0 ? ceil_div(K, splits) : 0;
-  rps = ceil_div(rps, BK) * BK;
+  rps = ceil_div(rps, 64) * 64;
   if (rps > 0) splits = (int)ceil_div(K, rps);
   p.splits = splits;
   p.rows_per_split = (int)rps;
@@ -368,11 +370,12 @@ static void allow_big_lds(KernelT kernel, size_t lds) {
                               (int)lds);
 }
 
-template <int BM, int BN, int NW>
+template <int BM, int BN, int NW, int KB, int NSTAGE>
 static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero,
                               hipStream_t s) {
-  const size_t lds = 2 * (size_t)(BM + BN) * 128;
-  allow_big_lds(linear_bwd_kernel<BM, BN, NW>, lds);
+  // stage ring + the row-id table of a dW split (rows_per_split rounded up to the stage length)
+  const size_t lds = (size_t)NSTAGE * (BM + BN) * KB * 2 + (size_t)(p.rows_per_split + KB) * sizeof(int);
+  allow_big_lds(linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>, lds);
   const long long tiles_n = ceil_div(a.Cin, BN);
   a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M * (a.Cin / 8), 64 * NW * 16))) : 0;
   const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
@@ -381,7 +384,7 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, BM) * tiles_n * p.splits, 8)) : 0;
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
   if (grid == 0) return;
-  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW>), dim3(grid), dim3(64 * NW), lds, s, a);
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv_in,
@@ -429,14 +432,14 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     a.K = (int)K; a.M = (int)M; a.Cin = Cin; a.Cout = Cout;
     a.rows_per_split = p.rows_per_split; a.db_slice_rows = p.db_slice_rows;
     const bool want_dx = dX != nullptr, want_dw = dW != nullptr;
-    if (p.bm_w == 256 && p.nw_w == 8)
-      launch_linear_bwd<256, 256, 8>(p, a, want_dx, want_dw, scatter, s);
-    else if (p.bm_w == 256 && p.bn_w == 256)
-      launch_linear_bwd<256, 256, 4>(p, a, want_dx, want_dw, scatter, s);
-    else if (p.bm_w == 256)
-      launch_linear_bwd<256, 128, 4>(p, a, want_dx, want_dw, scatter, s);
+    if (p.bm_w == 256 && p.nw_w == 8 && p.kb == 32)
+      launch_linear_bwd<256, 256, 8, 32, 4>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.bm_w == 256 && p.nw_w == 8)
+      launch_linear_bwd<256, 256, 8, 64, 2>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.kb == 32)
+      launch_linear_bwd<128, 128, 4, 32, 4>(p, a, want_dx, want_dw, scatter, s);
     else
-      launch_linear_bwd<128, 128, 4>(p, a, want_dx, want_dw, scatter, s);
+      launch_linear_bwd<128, 128, 4, 64, 2>(p, a, want_dx, want_dw, scatter, s);
   } else if (dtype == SBP_F32) {
     launch_plain<float>(p, (const float*)dY, idx_in, idx_out, (const float*)Xk, (const float*)W, K, Cin, Cout, part,
                         dbp, dW != nullptr, db != nullptr, (float*)dX, s);

@@ -4,7 +4,7 @@
 // on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
 // A block of 256 threads (2 x 2 wavefronts) owns a BM x BN tile and walks the contraction in stages
-// of BK = 64.  Global memory is read in 16-byte pieces into registers NPRE stages ahead and stored to
+// of BK = 64 or 32.  Global memory is read in 16-byte pieces into registers NPRE stages ahead and stored to
 // a double-buffered LDS stage; the kept rows of dY are gathered by these loads, so dY_k never exists
 // in memory.  Two LDS tile layouts:
 //   * "row" tile  [rows][BK]   for an operand whose contraction index is contiguous in memory (dY in
@@ -30,7 +30,6 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 #define SBP_LDS __attribute__((address_space(3)))
 #define SBP_GLB __attribute__((address_space(1)))
 
-static constexpr int BK = 64;          // contraction elements per LDS stage
 static constexpr int NTHREADS = 256;   // threads of the small kernels and of the 4-wavefront GEMM blocks
 // A GEMM block has NW = 4 wavefronts (2 x 2 over the tile) or NW = 8 (2 x 4: two wavefronts per SIMD).
 
@@ -52,22 +51,31 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ void async_copy16(const void* g, char* lds_block) {
   __builtin_amdgcn_global_load_lds((SBP_GLB const void*)g, (SBP_LDS void*)lds_block, 16, 0, 0);
 }
-__device__ __forceinline__ void wait_async_copies() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+// wait until at most N of this wavefront's copies are still in flight (they complete in issue order)
+template <int N>
+__device__ __forceinline__ void wait_async_copies() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
 
 // ------------------------------------------------------------------------------------------------
-// "row" tile: ROWS rows of BK bf16 (128 bytes = eight 16-byte chunks).  Row m sits at physical row
-// prow(m) (bits 0 and 3 exchanged), its chunk c at slot c ^ (m & 7): the 16-byte operand reads of 32
-// consecutive rows spread over all 64 banks.  One 1 KB block = 8 physical rows.
+// "row" tile: ROWS rows of KB contraction elements (operand whose contraction index is contiguous in
+// memory), swizzled so that the 16-byte operand reads of 32 consecutive rows spread over all 64 banks.
+//   KB = 64: 128-byte rows; row m at physical row prow(m) (bits 0 and 3 exchanged), chunk c at slot
+//            c ^ (m & 7); a 1 KB block is 8 physical rows.
+//   KB = 32:  64-byte rows; chunk c of row m at slot c ^ ((m >> 2) & 3); a 1 KB block is 16 rows.
 // Rows past the end are clamped to the last row (their results are never stored); in the tail stage
 // chunks past kdim re-read the last chunk (the other operand is zero there).
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ int prow(int m) { return (m & ~9) | ((m & 1) << 3) | ((m >> 3) & 1); }
 
-template <int ROWS, int NW>
+template <int ROWS, int NW, int KB>
 struct RowTileLoader {
-  static constexpr int NI = ROWS / 8 / NW;      // 1 KB blocks per wavefront and stage (even)
+  static constexpr int RPB = KB == 64 ? 8 : 16;         // rows per 1 KB block
+  static constexpr int NI = ROWS / RPB / NW;            // blocks per wavefront and stage
+  static_assert(NI >= 1 && (KB == 32 || NI % 2 == 0), "block parity trick needs an even block count");
   const uint16_t* rowp[NI];
-  int koff[2];                                  // element offset of this lane's chunk in even / odd blocks
+  int koff[2];                                          // element offset of this lane's chunk in even / odd blocks
   int kdim, blk0;
 
   __device__ __forceinline__ void init(const uint16_t* src, const int32_t* idx, long long ld, int row0, int nrows,
@@ -76,18 +84,22 @@ struct RowTileLoader {
     blk0 = wave * NI;
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
-      const int q = (blk0 + n) * 8 + (lane >> 3);          // physical row of this lane in block n
-      const int r = min(row0 + prow(q), nrows - 1);        // logical row (prow is its own inverse)
+      const int q = (blk0 + n) * RPB + (KB == 64 ? (lane >> 3) : (lane >> 2));   // physical row of this lane
+      const int m = KB == 64 ? prow(q) : q;                                       // logical row
+      const int r = min(row0 + m, nrows - 1);
       const long long g = idx ? (long long)idx[r] : (long long)r;
       rowp[n] = src + g * ld;
     }
+    if (KB == 64) {
 #pragma unroll
-    for (int par = 0; par < 2; ++par) {
-      const int m7 = ((lane >> 3) & 6) | par;              // low bits of the logical row: bit 0 = block parity
-      koff[par] = ((lane & 7) ^ m7) * 8;
+      for (int par = 0; par < 2; ++par) {
+        const int m7 = ((lane >> 3) & 6) | par;          // low bits of the logical row: bit 0 = block parity
+        koff[par] = ((lane & 7) ^ m7) * 8;
+      }
+    } else {
+      koff[0] = koff[1] = ((lane & 3) ^ ((lane >> 4) & 3)) * 8;
     }
   }
-  __device__ __forceinline__ void fetch_rows(int) {}
   template <bool TAIL>
   __device__ __forceinline__ void issue(int kbase, char* tile) const {
 #pragma unroll
@@ -101,53 +113,52 @@ struct RowTileLoader {
 };
 
 // per-lane byte offset of the operand fragment rows wbase + 32 f + (lane & 31) in a row tile
-__device__ __forceinline__ int row_tile_lane_off(int wbase, int lane) { return prow(wbase + (lane & 31)) * 128; }
+template <int KB>
+__device__ __forceinline__ int row_tile_lane_off(int wbase, int lane) {
+  return KB == 64 ? prow(wbase + (lane & 31)) * 128 : (wbase + (lane & 31)) * 64;
+}
 
-template <int F>
+template <int F, int KB>
 __device__ __forceinline__ void read_row_frags(const char* tile, int lane_off, int ks, int lane, bf16x8_t (&a)[F]) {
-  const int ch = ((2 * ks + (lane >> 5)) ^ (lane & 7)) << 4;
+  const int sw = KB == 64 ? (lane & 7) : ((lane >> 2) & 3);
+  const int ch = ((2 * ks + (lane >> 5)) ^ sw) << 4;
 #pragma unroll
-  for (int f = 0; f < F; ++f) a[f] = *reinterpret_cast<const bf16x8_t*>(tile + lane_off + f * 4096 + ch);
+  for (int f = 0; f < F; ++f) a[f] = *reinterpret_cast<const bf16x8_t*>(tile + lane_off + f * (32 * KB * 2) + ch);
 }
 
 // ------------------------------------------------------------------------------------------------
-// "slow" tile: BK contraction rows of COLS bf16, pitch COLS * 2 bytes, stored as in memory except
+// "slow" tile: KB contraction rows of COLS bf16, pitch COLS * 2 bytes, stored as in memory except
 // that 16-byte chunk c of row k sits at slot c ^ ((k & 3) << 2).  A transposing read of a 16-lane
 // group touches 4 consecutive rows x 32 bytes; the swizzle puts those on different banks.
 // One 1 KB block = 2 rows (COLS = 256) or 4 rows (COLS = 128).
 // Columns past the end are clamped (never stored); contraction rows past kdim are clamped for the
-// address and their LDS rows zeroed afterwards (tail stage only).  Row ids of a gathered operand are
-// fetched one stage early.
+// address and their LDS rows zeroed afterwards (tail stage only).  The row ids of a gathered operand
+// come from a table in LDS (rows[k - k0], filled by the caller), so no global load sits between the
+// copies.
 // ------------------------------------------------------------------------------------------------
-template <int COLS, int NW>
+template <int COLS, int NW, int KB>
 struct SlowTileLoader {
   static constexpr int LPR = COLS / 8;                 // lanes (chunks) per contraction row
   static constexpr int RPI = 64 / LPR;                 // rows per 1 KB block
-  static constexpr int NI = BK / RPI / NW;             // blocks per wavefront and stage (even)
+  static constexpr int NI = KB / RPI / NW;             // blocks per wavefront and stage
+  static_assert(NI >= 1 && (RPI == 4 || NI % 2 == 0), "block parity trick needs an even block count");
   static constexpr int PITCH = COLS * 2;
   const uint16_t* src;
-  const int32_t* idx;
+  const int* rows;                                     // LDS table of row ids, or nullptr
   long long ld;
-  int kdim, blk0, rsub;
+  int k0, kdim, blk0, rsub;
   int coff[2];                                         // column (elements) of this lane's chunk in even / odd blocks
-  int nrow[NI];                                        // row ids for the next issue() of a gathered operand
 
-  __device__ __forceinline__ void init(const uint16_t* src_, const int32_t* idx_, long long ld_, int col0, int ncols,
-                                       int kdim_, int lane, int wave) {
-    src = src_; idx = idx_; ld = ld_; kdim = kdim_;
+  __device__ __forceinline__ void init(const uint16_t* src_, const int* rows_, long long ld_, int col0, int ncols,
+                                       int k0_, int kdim_, int lane, int wave) {
+    src = src_; rows = rows_; ld = ld_; k0 = k0_; kdim = kdim_;
     blk0 = wave * NI;
     rsub = lane / LPR;
     const int p = lane % LPR;
 #pragma unroll
     for (int par = 0; par < 2; ++par) {
-      const int k3 = (RPI * par + rsub) & 3;             // low bits of the row index (blk0 is even)
+      const int k3 = (RPI * par + rsub) & 3;             // low bits of the row index (blk0 * RPI is a multiple of 4)
       coff[par] = min(col0 + 8 * (p ^ (k3 << 2)), ncols - 8);
-    }
-  }
-  __device__ __forceinline__ void fetch_rows(int kbase) {
-    if (idx) {
-#pragma unroll
-      for (int n = 0; n < NI; ++n) nrow[n] = idx[min(kbase + RPI * (blk0 + n) + rsub, kdim - 1)];
     }
   }
   template <bool TAIL>
@@ -155,14 +166,14 @@ struct SlowTileLoader {
 #pragma unroll
     for (int n = 0; n < NI; ++n) {
       const int k = kbase + RPI * (blk0 + n) + rsub;
-      const long long g = idx ? (long long)nrow[n] : (long long)(TAIL ? min(k, kdim - 1) : k);
+      const long long g = rows ? (long long)rows[k - k0] : (long long)(TAIL ? min(k, kdim - 1) : k);
       async_copy16(src + g * ld + coff[n & 1], tile + (blk0 + n) * 1024);
     }
   }
-  // zero the LDS rows kvalid .. BK-1 (contraction rows past the end of the operand)
+  // zero the LDS rows kvalid .. KB-1 (contraction rows past the end of the operand)
   __device__ __forceinline__ void zero_tail(char* tile, int kvalid, int t) const {
 #pragma unroll
-    for (int i = 0; i < BK * LPR / (64 * NW); ++i) {
+    for (int i = 0; i < KB * LPR / (64 * NW); ++i) {
       const int q = t + 64 * NW * i;
       if (q / LPR >= kvalid) *reinterpret_cast<uint4*>(tile + q * 16) = make_uint4(0, 0, 0, 0);
     }
@@ -205,18 +216,21 @@ __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[FM][FN]) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Stage loop with two LDS stages: while the MFMAs of stage kt run, the copies of stage kt+1 are in
-// flight into the other buffer.  One barrier per stage: it publishes the landed stage and retires the
-// buffer the next copies will overwrite.
+// Stage loop over a ring of NSTAGE LDS buffers: while the MFMAs of stage kt run, the copies of stages
+// kt+1 .. kt+NSTAGE-1 are in flight.  One barrier per stage: it publishes the landed stage and retires
+// the buffer that the next copies overwrite.  A wavefront's copies complete in issue order, so "stage
+// kt has landed" is "at most r * (copies per stage) still in flight", r = stages issued after it.
 // ------------------------------------------------------------------------------------------------
-template <int A_BYTES, int STAGE, class LA, class LB, class Compute>
+template <int NSTAGE, int KB, int A_BYTES, int STAGE, class LA, class LB, class Compute>
 __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, int kend, int nk, Compute&& compute) {
+  static_assert(NSTAGE == 2 || NSTAGE == 4, "ring of 2 or 4 stages");
+  constexpr int C = LA::NI + LB::NI;               // copies per wavefront and stage
   if (nk <= 0) return;
   const int t = threadIdx.x;
-  const bool tail = ((kend - k0) % BK) != 0;
+  const bool tail = ((kend - k0) % KB) != 0;
   auto issue = [&](int s) {
-    char* buf = smem + (s & 1) * STAGE;
-    const int kbase = k0 + s * BK;
+    char* buf = smem + (s % NSTAGE) * STAGE;
+    const int kbase = k0 + s * KB;
     if (tail && s == nk - 1) {
       la.template issue<true>(kbase, buf);
       lb.template issue<true>(kbase, buf + A_BYTES);
@@ -224,22 +238,25 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
       la.template issue<false>(kbase, buf);
       lb.template issue<false>(kbase, buf + A_BYTES);
     }
-    la.fetch_rows(kbase + BK);
-    lb.fetch_rows(kbase + BK);
   };
-  issue(0);
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nk) issue(s);
   for (int kt = 0; kt < nk; ++kt) {
-    char* cur = smem + (kt & 1) * STAGE;
-    wait_async_copies();
+    char* cur = smem + (kt % NSTAGE) * STAGE;
+    const int ahead = min(NSTAGE - 2, nk - 1 - kt);    // stages issued after stage kt
+    if (NSTAGE == 4 && ahead == 2) wait_async_copies<2 * C>();
+    else if (NSTAGE == 4 && ahead == 1) wait_async_copies<C>();
+    else wait_async_copies<0>();
     __syncthreads();
     if (tail && kt == nk - 1) {
-      const int kvalid = kend - (k0 + kt * BK);
+      const int kvalid = kend - (k0 + kt * KB);
       la.zero_tail(cur, kvalid, t);
       lb.zero_tail(cur + A_BYTES, kvalid, t);
       __syncthreads();
     }
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT == 3
-    if (kt + 1 < nk) issue(kt + 1);
+    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
 #endif
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
     compute(cur);
@@ -254,34 +271,34 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
 // tile is C[row l & 31][col 8 (v >> 2) + 4 (l >> 5) + (v & 3)].  The epilogue rounds to bf16, stages
 // 64 rows at a time through LDS and writes whole 16-byte pieces of the (scattered) dX rows.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NW>
+template <int BM, int BN, int NW, int KB, int NSTAGE>
 __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,
                                         const int32_t* __restrict__ idx_out, const uint16_t* __restrict__ W, int K,
                                         int Cin, int Cout, uint16_t* __restrict__ dX, int m0, int n0) {
   constexpr int WGN = NW / 2;                     // wavefront grid: 2 rows x WGN columns
   constexpr int FM = BM / 64, FN = BN / (32 * WGN);
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_BYTES = BM * KB * 2, B_BYTES = BN * KB * 2, STAGE = A_BYTES + B_BYTES;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = (wave / WGN) * (BM / 2), wn = (wave % WGN) * (BN / WGN);
 
-  RowTileLoader<BM, NW> la;
-  SlowTileLoader<BN, NW> lb;
+  RowTileLoader<BM, NW, KB> la;
+  SlowTileLoader<BN, NW, KB> lb;
   la.init(dY, idx_in, Cout, m0, K, Cout, lane, __builtin_amdgcn_readfirstlane(wave));
-  lb.init(W, nullptr, Cin, n0, Cin, Cout, lane, __builtin_amdgcn_readfirstlane(wave));
+  lb.init(W, nullptr, Cin, n0, Cin, 0, Cout, lane, __builtin_amdgcn_readfirstlane(wave));
 
   f32x16_t acc[FM][FN];
   zero_acc<FM, FN>(acc);
-  const int a_off = row_tile_lane_off(wm, lane);
+  const int a_off = row_tile_lane_off<KB>(wm, lane);
   int b_off[FN];
   slow_tile_lane_offs<BN, FN>(wn, lane, b_off);
-  const int nk = (Cout + BK - 1) / BK;
+  const int nk = (Cout + KB - 1) / KB;
 
   auto compute = [&](const char* cur) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < KB / 16; ++ks) {
       bf16x8_t a[FM], b[FN];
       read_slow_frags<BN, FN>(cur + A_BYTES, b_off, ks, b);
-      read_row_frags<FM>(cur, a_off, ks, lane, a);
+      read_row_frags<FM, KB>(cur, a_off, ks, lane, a);
 #pragma unroll
       for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -289,7 +306,7 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   };
-  stage_loop<A_BYTES, STAGE>(smem, la, lb, 0, Cout, nk, compute);
+  stage_loop<NSTAGE, KB, A_BYTES, STAGE>(smem, la, lb, 0, Cout, nk, compute);
 
   // epilogue
   constexpr int PITCH = BN * 2 + 16;              // staging row pitch (bytes)
@@ -331,32 +348,38 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 // as an fp32 partial.  Register v of lane l of a 32x32 tile is
 // C[row 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col l & 31].
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int NW>
+template <int BM, int BN, int NW, int KB, int NSTAGE>
 __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                                         const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
                                         float* __restrict__ part, int m0, int n0) {
   constexpr int WGN = NW / 2;                     // wavefront grid: 2 rows x WGN columns
   constexpr int FM = BM / 64, FN = BN / (32 * WGN);
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_BYTES = BM * KB * 2, B_BYTES = BN * KB * 2, STAGE = A_BYTES + B_BYTES;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = (wave / WGN) * (BM / 2), wn = (wave % WGN) * (BN / WGN);
+  const int nk = (j1 - j0 + KB - 1) / KB;
 
-  SlowTileLoader<BM, NW> la;
-  SlowTileLoader<BN, NW> lb;
-  la.init(dY, idx, Cout, m0, Cout, j1, lane, __builtin_amdgcn_readfirstlane(wave));
-  lb.init(Xk, nullptr, Cin, n0, Cin, j1, lane, __builtin_amdgcn_readfirstlane(wave));
-  la.fetch_rows(j0);
+  // row ids of the split's kept rows (clamped past the end), behind the stage ring
+  int* rows = nullptr;
+  if (idx) {
+    rows = reinterpret_cast<int*>(smem + NSTAGE * STAGE);
+    for (int i = t; i < nk * KB; i += 64 * NW) rows[i] = idx[min(j0 + i, j1 - 1)];
+    __syncthreads();
+  }
+  SlowTileLoader<BM, NW, KB> la;
+  SlowTileLoader<BN, NW, KB> lb;
+  la.init(dY, rows, Cout, m0, Cout, j0, j1, lane, __builtin_amdgcn_readfirstlane(wave));
+  lb.init(Xk, nullptr, Cin, n0, Cin, j0, j1, lane, __builtin_amdgcn_readfirstlane(wave));
 
   f32x16_t acc[FM][FN];
   zero_acc<FM, FN>(acc);
   int a_off[FM], b_off[FN];
   slow_tile_lane_offs<BM, FM>(wm, lane, a_off);
   slow_tile_lane_offs<BN, FN>(wn, lane, b_off);
-  const int nk = (j1 - j0 + BK - 1) / BK;
 
   auto compute = [&](const char* cur) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < KB / 16; ++ks) {
       bf16x8_t a[FM], b[FN];
       read_slow_frags<BN, FN>(cur + A_BYTES, b_off, ks, b);
       read_slow_frags<BM, FM>(cur, a_off, ks, a);
@@ -367,7 +390,7 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   };
-  stage_loop<A_BYTES, STAGE>(smem, la, lb, j0, j1, nk, compute);
+  stage_loop<NSTAGE, KB, A_BYTES, STAGE>(smem, la, lb, j0, j1, nk, compute);
 
   if (m0 + BM <= Cout && n0 + BN <= Cin) {         // interior tile: no bounds checks
 #pragma unroll
