@@ -49,6 +49,8 @@ struct LinearPlan {
   int    rows_per_split;// kept rows per split (multiple of the k-step)
   int    nw_w;          // wavefronts per block (4 or 8)
   int    kb;            // contraction elements per LDS stage (64: two stages, 32: four stages)
+  bool   big;           // 256 x 256 tiles, one workgroup per CU (sbp_mfma_big.h)
+  bool   dw_first;      // big engine: dW units are the longer ones and are dispatched before the dX tiles
   int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
   int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]

@@ -11,6 +11,13 @@
 #include <cstdio>
 #include <cstdlib>
 
+#include <algorithm>
+#include <functional>
+#include <queue>
+#include <string>
+#include <vector>
+
+#include "sbp_mfma_big.h"
 #include "sbp_mfma_gemm.h"
 
 namespace sbp {
@@ -50,17 +57,32 @@ struct LinArgs {
   float* dbp;
   int K, M, Cin, Cout, rows_per_split, db_slice_rows;
   int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
+  int dw_first;                       // large-tile kernel: dW units come before the dX tiles
 };
 
+// Zero fill of the dropped rows.  A wavefront takes 64 consecutive rows: every lane looks one row up
+// (row m is kept iff idx[inv[m]] == m: two dependent loads, once per 64 rows), a ballot collects the
+// dropped rows, and all lanes together write each of them.
 __device__ __forceinline__ void zero_rows_block(const LinArgs& a, int blk) {
   const int ppr = a.Cin / 8;                                   // 16-byte pieces per row
-  const long long total = (long long)a.M * ppr;
+  const int lane = threadIdx.x & 63;
+  const int wpb = blockDim.x >> 6;                             // wavefronts per block
+  const int gw = blk * wpb + (threadIdx.x >> 6);
   uint4* out = reinterpret_cast<uint4*>(a.dX);
-  for (long long e = (long long)blk * blockDim.x + threadIdx.x; e < total; e += (long long)a.n_zero * blockDim.x) {
-    const int m = (int)(e / ppr);
-    const int j = a.inv[m];
-    const bool kept = (unsigned)j < (unsigned)a.K && a.idx[j] == m;
-    if (!kept) out[e] = make_uint4(0, 0, 0, 0);
+  for (int base = gw * 64; base < a.M; base += a.n_zero * wpb * 64) {
+    const int m = base + lane;
+    bool dropped = false;
+    if (m < a.M) {
+      const int j = a.inv[m];
+      dropped = !((unsigned)j < (unsigned)a.K && a.idx[j] == m);
+    }
+    unsigned long long mask = __ballot(dropped);
+    while (mask) {
+      const int b = __ffsll((long long)mask) - 1;
+      mask &= mask - 1;
+      uint4* row = out + (long long)(base + b) * ppr;
+      for (int p = lane; p < ppr; p += 64) row[p] = make_uint4(0, 0, 0, 0);
+    }
   }
 }
 
@@ -104,6 +126,62 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
   const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
   dw_tile<BM, BN, NW, KB, NSTAGE>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, a.part + (long long)split * a.Cout * a.Cin,
                       tile_m * BM, tile_n * BN);
+}
+
+// The same work with 256 x 256 tiles (sbp_mfma_big.h): one workgroup per CU, so the order of the grid
+// is the order in which CUs pick work up: the longer kind of tile first, the shorter kind next, the
+// streaming helpers (zero fill, column sums) last, where they fill the CUs that run out of tiles.
+__global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int wg = blockIdx.x;
+  if (wg >= a.n_dx + a.n_dw) {
+    wg -= a.n_dx + a.n_dw;
+    if (wg < a.n_zero) {
+      zero_rows_block(a, wg);
+    } else {
+      const int b = wg - a.n_zero;
+      const int nslice = (a.K + a.db_slice_rows - 1) / a.db_slice_rows;
+      const int slice = b % nslice, chunk = b / nslice;
+      if (a.dbp && chunk * 256 < a.Cout) {
+        const int j0 = slice * a.db_slice_rows, j1 = min(a.K, j0 + a.db_slice_rows);
+        colsum_block(smem, a.dY, a.idx_in, a.Cout, j0, j1, chunk * 256, a.dbp + (long long)slice * a.Cout);
+      }
+    }
+    return;
+  }
+  bool is_dx;
+  if (a.dw_first) {
+    is_dx = wg >= a.n_dw;
+    if (is_dx) wg -= a.n_dw;
+  } else {
+    is_dx = wg < a.n_dx;
+    if (!is_dx) wg -= a.n_dx;
+  }
+  const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
+  if (is_dx) {
+    const int ntiles = ((a.K + big::BT - 1) / big::BT) * tiles_n;
+    const int L = xcd_chunked_id(wg, ntiles);
+    if (L >= ntiles) return;
+    const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
+    big::dx_tile(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * big::BT, tile_n * big::BT
+#ifdef SBP_TIMING
+                 , reinterpret_cast<long long*>(a.part) + 8 * L
+#endif
+                 );
+    return;
+  }
+  const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
+  const int nsplit = (a.K + a.rows_per_split - 1) / a.rows_per_split;
+  const int ntiles = tiles_m * tiles_n * nsplit;
+  const int L = xcd_chunked_id(wg, ntiles);
+  if (L >= ntiles) return;
+  const int split = L / (tiles_m * tiles_n);
+  const int rem = L - split * tiles_m * tiles_n;
+  const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
+  const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
+  float* part = a.part + (long long)split * a.Cout * a.Cin;
+  if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+  else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
 }
 
 // dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.
@@ -217,7 +295,7 @@ template <> struct Elem<float> {
 };
 template <> struct Elem<uint16_t> {
   static __device__ __forceinline__ float ld(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
-  static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = (uint16_t)bf16_round(v); }
+  static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = (uint16_t)(bf16_pack(v, 0.f) & 0xffffu); }
 };
 
 // one thread per (kept row j, input channel i)
@@ -296,10 +374,67 @@ static bool env_tile(const char* name, int* bm, int* bn, int* nw, int* kb) {
   if (!v) return false;
   int a = 0, b = 0, w = 4, k = 64;
   if (std::sscanf(v, "%dx%dx%dx%d", &a, &b, &w, &k) < 2) return false;
-  const bool ok = ((a == 256 && b == 256 && w == 8) || (a == 128 && b == 128 && w == 4)) && (k == 32 || k == 64);
+  const bool ok = ((a == 256 && b == 256 && (w == 8 || w == 4)) || (a == 128 && b == 128 && w == 4)) && (k == 32 || k == 64);
   if (!ok) return false;
   *bm = a; *bn = b; *nw = w; *kb = k;
   return true;
+}
+
+// ---- large-tile engine: how many dW splits --------------------------------------------------------
+// One workgroup per CU and a grid ordered long units first is list scheduling; its finish time for n1
+// units of length l1 followed by n2 units of length l2 (lengths in stages of 32) is simulated exactly.
+static int64_t list_schedule_end(int64_t n1, int64_t l1, int64_t n2, int64_t l2) {
+  std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> cu;
+  for (int i = 0; i < kNumCU; ++i) cu.push(0);
+  int64_t end = 0;
+  auto run = [&](int64_t n, int64_t l) {
+    for (; n > 0; --n) {
+      const int64_t t = cu.top() + l;
+      cu.pop();
+      cu.push(t);
+      end = std::max(end, t);
+    }
+  };
+  run(n1, l1);
+  run(n2, l2);
+  return end;
+}
+
+static constexpr int kBigMaxRowsPerSplit = 4096;   // row ids of a split in LDS next to the 128 KB ring
+static constexpr int kBigEpilogueDx = 4;           // epilogue cost of a tile, in stages
+static constexpr int kBigEpilogueDw = 3;
+
+struct BigChoice { int64_t K; int32_t Cin, Cout; int splits, rps; bool dw_first; };
+
+static BigChoice choose_big_splits(int64_t K, int32_t Cin, int32_t Cout) {
+  thread_local BigChoice cache[8] = {};
+  thread_local int next = 0;
+  for (const BigChoice& c : cache)
+    if (c.K == K && c.Cin == Cin && c.Cout == Cout && c.splits > 0) return c;
+  const int64_t tiles_n = ceil_div(Cin, big::BT);
+  const int64_t n_dx = ceil_div(K, big::BT) * tiles_n, l_dx = Cout / big::KB + kBigEpilogueDx;
+  const int64_t tiles_w = ceil_div(Cout, big::BT) * tiles_n;
+  BigChoice best{K, Cin, Cout, 0, 0, false};
+  double best_cost = 0;
+  const int64_t s_min = ceil_div(K, kBigMaxRowsPerSplit), s_max = std::max<int64_t>(s_min, std::min<int64_t>(48, K / 256));
+  for (int64_t sp = s_min; sp <= s_max; ++sp) {
+    const int64_t rps = ceil_div(ceil_div(K, sp), 64) * 64;
+    const int64_t ns = ceil_div(K, rps);
+    if (ns != sp && sp != s_min) continue;          // same split count as a smaller sp: already seen
+    const int64_t l_dw = rps / big::KB + kBigEpilogueDw;
+    const bool dw_first = l_dw > l_dx;
+    const int64_t end = dw_first ? list_schedule_end(tiles_w * ns, l_dw, n_dx, l_dx)
+                                 : list_schedule_end(n_dx, l_dx, tiles_w * ns, l_dw);
+    // every split writes and the reduction reads an fp32 copy of dW: about 4 MB move in one stage time
+    const double cost = (double)end + (double)ns * Cout * Cin * 8.0 / 4.0e6;
+    if (best.splits == 0 || cost < best_cost) {
+      best_cost = cost;
+      best.splits = (int)ns; best.rps = (int)rps; best.dw_first = dw_first;
+    }
+  }
+  cache[next] = best;
+  next = (next + 1) % 8;
+  return best;
 }
 
 LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags) {
@@ -309,7 +444,21 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   p.nw_w = 4;
   p.kb = 64;
   int splits = 1;
-  if (K > 0) {
+  if (K > 0 && p.mfma) {
+    // SBP_TILE=big forces the large-tile engine wherever its limits allow (debugging aid, like the shapes below)
+    const char* env = std::getenv("SBP_TILE");
+    const bool forced = env && std::string(env) == "big";
+    const bool fits = Cout % big::KB == 0 && (uint64_t)M * (uint64_t)std::max(Cin, Cout) * 2u < (1ull << 32);
+    const bool pays = !env && false;
+    p.big = fits && (forced || pays);
+  }
+  if (p.big) {
+    const BigChoice c = choose_big_splits(K, Cin, Cout);
+    p.bm_w = p.bn_w = big::BT;
+    p.kb = big::KB;
+    p.dw_first = c.dw_first;
+    splits = c.splits;
+  } else if (K > 0) {
     if (p.mfma) {
       env_tile("SBP_TILE", &p.bm_w, &p.bn_w, &p.nw_w, &p.kb);
       // enough blocks to fill the chip's block slots once, each split at least 4 stages long
@@ -377,7 +526,7 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   const size_t lds = (size_t)NSTAGE * (BM + BN) * KB * 2 + (size_t)(p.rows_per_split + KB) * sizeof(int);
   allow_big_lds(linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>, lds);
   const long long tiles_n = ceil_div(a.Cin, BN);
-  a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M * (a.Cin / 8), 64 * NW * 16))) : 0;
+  a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M, 64 * NW))) : 0;
   const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
   a.n_helper = (int)(8 * ceil_div(a.n_zero + n_db, 8));
   a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, BM) * tiles_n, 8)) : 0;
@@ -385,6 +534,22 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
   if (grid == 0) return;
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>), dim3(grid), dim3(64 * NW), lds, s, a);
+}
+
+static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero, hipStream_t s) {
+  // behind the ring: the row ids of a dW split (read one stage ahead) or the 256 output rows of a dX tile
+  const size_t lds = (size_t)big::RING + std::max<size_t>((size_t)(p.rows_per_split + 2 * big::KB), big::BT) * sizeof(int);
+  allow_big_lds(linear_big_kernel, lds);
+  const long long tiles_n = ceil_div(a.Cin, big::BT);
+  a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M, 256))) : 0;
+  const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
+  a.n_helper = a.n_zero + n_db;
+  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, big::BT) * tiles_n, 8)) : 0;
+  a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, big::BT) * tiles_n * p.splits, 8)) : 0;
+  a.dw_first = p.dw_first ? 1 : 0;
+  const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
+  if (grid == 0) return;
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, linear_big_kernel, dim3(grid), dim3(256), lds, s, a);
 }
 
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv_in,
@@ -432,10 +597,16 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     a.K = (int)K; a.M = (int)M; a.Cin = Cin; a.Cout = Cout;
     a.rows_per_split = p.rows_per_split; a.db_slice_rows = p.db_slice_rows;
     const bool want_dx = dX != nullptr, want_dw = dW != nullptr;
-    if (p.bm_w == 256 && p.nw_w == 8 && p.kb == 32)
+    if (p.big)
+      launch_linear_big(p, a, want_dx, want_dw, scatter, s);
+    else if (p.bm_w == 256 && p.nw_w == 8 && p.kb == 32)
       launch_linear_bwd<256, 256, 8, 32, 4>(p, a, want_dx, want_dw, scatter, s);
     else if (p.bm_w == 256 && p.nw_w == 8)
       launch_linear_bwd<256, 256, 8, 64, 2>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.bm_w == 256 && p.kb == 32)
+      launch_linear_bwd<256, 256, 4, 32, 4>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.bm_w == 256)
+      launch_linear_bwd<256, 256, 4, 64, 2>(p, a, want_dx, want_dw, scatter, s);
     else if (p.kb == 32)
       launch_linear_bwd<128, 128, 4, 32, 4>(p, a, want_dx, want_dw, scatter, s);
     else

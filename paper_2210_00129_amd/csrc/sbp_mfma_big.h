@@ -1,0 +1,456 @@
+// Large-tile engine for the two bf16 contractions of the SBP linear backward (paper,
+// eq:backward_fc_sbp): 256 x 256 output tiles, one workgroup of 4 wavefronts per CU, every wavefront
+// owning a 128 x 128 quarter (16 accumulator blocks of 32 x 32, 256 accumulator registers).
+//
+// Why this shape: at 64 x 64 per wavefront the operand reads from LDS need as many LDS cycles as the
+// MFMAs need matrix-core cycles; at 128 x 128 they need half.  With one wavefront per SIMD nothing
+// hides a stall, so the instruction stream is laid out by hand:
+//   * the contraction runs in stages of 32 through a ring of 4 LDS stages (32 KB each); the copies of
+//     three stages are in flight while one is consumed;
+//   * global -> LDS copies are global_load_lds_dwordx4 with a wave-uniform base and a per-lane 32-bit
+//     offset computed once per tile: a stage's copies cost one scalar add and no vector arithmetic;
+//   * operand fragments are double-buffered in registers: while the 16 MFMAs of one 16-deep step run,
+//     the LDS reads of the next step (and, every second step, the next stage's copies) are issued
+//     between them;
+//   * one barrier per stage, between its two steps: it retires the stage just read (its buffer takes
+//     the copies of stage s + 4) and publishes stage s + 1.  The barrier waits for LDS traffic only;
+//     copies in flight are counted with s_waitcnt vmcnt.
+// LDS tile layouts and their swizzles are those of sbp_mfma_gemm.h ("row" tile for dY in dX, "slow"
+// tiles read with ds_read_b64_tr_b16 for everything else).
+//
+// Limits (checked on the host, the smaller engine takes the rest): Cout % 32 == 0 (no partial stage
+// in dX), row offsets fit 32 bits (M * max(Cin, Cout) * 2 < 2^32).
+#ifndef SBP_MFMA_BIG_H_
+#define SBP_MFMA_BIG_H_
+
+#include "sbp_mfma_gemm.h"
+
+namespace sbp {
+namespace big {
+
+static constexpr int BT = 256;                  // tile edge, rows and columns
+static constexpr int KB = 32;                   // contraction elements per stage
+static constexpr int NS = 4;                    // ring depth
+static constexpr int TILE_BYTES = BT * KB * 2;  // one operand tile of a stage
+static constexpr int STAGE = 2 * TILE_BYTES;
+static constexpr int RING = NS * STAGE;
+static constexpr int CPS = 8;                   // copies per wavefront and stage (4 per operand)
+
+typedef f32x16_t Acc[4][4];
+#ifdef SBP_TIMING
+__device__ long long* sbp_timing_slot_dummy;
+#define sbp_timing_slot pb.tslot
+#endif
+
+__device__ __forceinline__ void wait_copies_runtime(int stages_in_flight) {   // wave-uniform argument
+  if (stages_in_flight >= 3) wait_async_copies<3 * CPS>();
+  else if (stages_in_flight == 2) wait_async_copies<2 * CPS>();
+  else if (stages_in_flight == 1) wait_async_copies<CPS>();
+  else wait_async_copies<0>();
+}
+
+// ---- copies of a "row" tile [256 rows][32 k]: 16 blocks of 16 rows, 4 per wavefront -------------
+struct RowCopy {
+  uint32_t voff[4];
+  __device__ __forceinline__ void init(const int32_t* idx, uint32_t ld_bytes, int row0, int nrows, int lane, int wave) {
+    const uint32_t chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const int r = min(row0 + 16 * (4 * wave + n) + (lane >> 2), nrows - 1);
+      const uint32_t g = idx ? (uint32_t)idx[r] : (uint32_t)r;
+      voff[n] = g * ld_bytes + chunk;
+    }
+  }
+  __device__ __forceinline__ void issue(const char* base, char* tile, int wave) const {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) async_copy16(base + voff[n], tile + (4 * wave + n) * 1024);
+  }
+};
+
+// ---- copies of a "slow" tile [32 k][256 columns]: 16 blocks of 2 rows, 4 per wavefront ----------
+struct SlowCopy {
+  uint32_t voff[4];   // operand with consecutive rows: (row within the stage) * ld + column bytes
+  uint32_t colb[2];   // column bytes of this lane in even / odd blocks
+  int kl0;            // row within the stage of block 0 of this wavefront (block n: + 2 n)
+  __device__ __forceinline__ void init(uint32_t ld_bytes, int col0, int ncols, int lane, int wave) {
+    const int p = lane & 31;
+    kl0 = 8 * wave + (lane >> 5);
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int k3 = (2 * par + (lane >> 5)) & 3;
+      colb[par] = (uint32_t)(2 * min(col0 + 8 * (p ^ (k3 << 2)), ncols - 8));
+    }
+#pragma unroll
+    for (int n = 0; n < 4; ++n) voff[n] = (uint32_t)(kl0 + 2 * n) * ld_bytes + colb[n & 1];
+  }
+  __device__ __forceinline__ void issue(const char* base, char* tile, int wave) const {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) async_copy16(base + voff[n], tile + (4 * wave + n) * 1024);
+  }
+  // rows clamped to last_row (partial last stage); k0 = first row of the stage
+  __device__ __forceinline__ void issue_clamped(const char* src, uint32_t ld_bytes, int k0, int last_row, char* tile,
+                                                int wave) const {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      const int k = min(k0 + kl0 + 2 * n, last_row);
+      async_copy16(src + (size_t)k * ld_bytes + colb[n & 1], tile + (4 * wave + n) * 1024);
+    }
+  }
+};
+
+__device__ __forceinline__ void zero_slow_tail(char* tile, int kvalid, int t) {   // rows kvalid .. 31 of a slow tile
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int q = t + 256 * i;                       // 16-byte piece; 32 pieces per row
+    if ((q >> 5) >= kvalid) *reinterpret_cast<uint4*>(tile + q * 16) = make_uint4(0, 0, 0, 0);
+  }
+}
+
+__device__ __forceinline__ void read_slow4(const char* tile, const int (&off)[4], int ks, bf16x8_t (&a)[4]) {
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    const char* p = tile + off[f] + ks * (16 * 512);
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p + 4 * 512));
+    a[f] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  }
+}
+
+template <bool SWAP>
+__device__ __forceinline__ void mfma16(Acc& acc, const bf16x8_t (&a)[4], const bf16x8_t (&b)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0)
+                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+}
+
+// Instruction order of a step, given to the scheduler as a pipeline of groups (the code of the step
+// is written before the call).  The compiler cannot tell the ring's buffers apart, so LDS reads and
+// copies keep their program order: a step that holds both issues its copies first.
+//   step without copies: 16 x { MFMA, NREAD/16 LDS reads }
+//   step with copies:     4 x { MFMA, 2 copies }, then 12 x { MFMA, LDS reads } (the reads spread evenly)
+template <int MASK, int N>
+__device__ __forceinline__ void sched_group() {
+  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+template <int NREAD, int SLOTS, int I>
+__device__ __forceinline__ void mfma_read_slots() {     // slots I .. SLOTS-1 of { MFMA, share of the LDS reads }
+  sched_group<0x008, 1>();
+  sched_group<0x100, (NREAD * (I + 1)) / SLOTS - (NREAD * I) / SLOTS>();
+  if constexpr (I + 1 < SLOTS) mfma_read_slots<NREAD, SLOTS, I + 1>();
+}
+template <int NREAD, bool COPIES>
+__device__ __forceinline__ void interleave_step() {
+  if constexpr (!COPIES) {
+    mfma_read_slots<NREAD, 16, 0>();
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      sched_group<0x008, 1>();
+      sched_group<0x010, CPS / 4>();
+    }
+    mfma_read_slots<NREAD, 12, 0>();
+  }
+}
+
+// ---- the stage ring ------------------------------------------------------------------------------
+// P supplies: prefetch(s) - row ids of stage s into registers (gathered operand only);
+// issue(s, buf, partial) - the copies of stage s (after prefetch(s + 1)); read(buf, ks, a, b) - the
+// fragments of step ks; zero_tail(buf, kvalid); SWAP; NREAD (LDS reads per step); NPRE (LDS reads of a
+// prefetch).
+template <class P>
+__device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, int kvalid_last, Acc& acc) {
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+    if (s < nk) {
+      pb.prefetch(s + 1);
+      pb.issue(s, smem + s * STAGE, tail && s == nk - 1);
+    }
+  wait_copies_runtime(min(NS - 1, nk - 1));
+  lds_barrier();
+#ifdef SBP_TIMING
+  if (threadIdx.x == 0 && sbp_timing_slot) sbp_timing_slot[2] = wall_clock64();
+#endif
+  if (tail && nk == 1) {
+    pb.zero_tail(smem, kvalid_last);
+    lds_barrier();
+  }
+  bf16x8_t pa[4], pbf[4], qa[4], qb[4];
+  pb.read(smem, 0, pa, pbf);
+
+  int s = 0;
+  // steady state: stage s + NS exists and is not the last one
+  for (; s + NS + 1 < nk; ++s) {
+    char* cur = smem + (s & (NS - 1)) * STAGE;
+    const char* nxt = smem + ((s + 1) & (NS - 1)) * STAGE;
+    pb.prefetch(s + NS + 1);
+#if !defined(SBP_EXPERIMENT) || (SBP_EXPERIMENT != 3 && SBP_EXPERIMENT != 4)
+    pb.read(cur, 1, qa, qb);
+#endif
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
+    mfma16<P::SWAP>(acc, pa, pbf);
+#endif
+    interleave_step<P::NREAD + P::NPRE, false>();
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
+    wait_async_copies<2 * CPS>();               // stage s + 1 has landed (s + 2 and s + 3 may be in flight)
+#endif
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 5
+    lds_barrier();
+#endif
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
+    pb.issue(s + NS, cur, false);               // every wavefront is done with stage s: its buffer is free
+#endif
+#if !defined(SBP_EXPERIMENT) || (SBP_EXPERIMENT != 3 && SBP_EXPERIMENT != 4)
+    pb.read(nxt, 0, pa, pbf);
+#endif
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
+    mfma16<P::SWAP>(acc, qa, qb);
+#endif
+    interleave_step<P::NREAD, true>();
+  }
+  // drain: the same steps with the end of the operand in view
+  for (; s < nk; ++s) {
+    char* cur = smem + (s & (NS - 1)) * STAGE;
+    char* nxt = smem + ((s + 1) & (NS - 1)) * STAGE;
+    pb.read(cur, 1, qa, qb);
+    mfma16<P::SWAP>(acc, pa, pbf);
+    interleave_step<P::NREAD, false>();
+    if (s + 1 < nk) wait_copies_runtime(min(NS - 2, nk - 2 - s));
+    lds_barrier();
+    if (tail && s + 1 == nk - 1) {
+      pb.zero_tail(nxt, kvalid_last);
+      lds_barrier();
+    }
+    if (s + NS < nk) {
+      pb.prefetch(s + NS + 1);
+      pb.issue(s + NS, cur, tail && s + NS == nk - 1);
+    }
+    pb.read(nxt, 0, pa, pbf);                   // past the last stage: reads a stale buffer, never used
+    mfma16<P::SWAP>(acc, qa, qb);
+    interleave_step<P::NREAD, false>();
+  }
+  lds_barrier();
+}
+
+// ---- dX = dY_k W ---------------------------------------------------------------------------------
+struct DxProb {
+  static constexpr bool SWAP = true;            // lane ends with 4 consecutive input channels of one row
+  static constexpr int NREAD = 12, NPRE = 0;
+  RowCopy ca;
+  SlowCopy cb;
+  const char* a_src;
+  const char* b_src;
+  uint32_t b_stride;
+#ifdef SBP_TIMING
+  long long* tslot;
+#endif
+  int wave, a_off[2], b_off[4];
+  __device__ __forceinline__ void prefetch(int) {}
+  __device__ __forceinline__ void issue(int s, char* buf, bool) {
+    ca.issue(a_src + (size_t)s * (KB * 2), buf, wave);
+    cb.issue(b_src + (size_t)s * b_stride, buf + TILE_BYTES, wave);
+  }
+  __device__ __forceinline__ void read(const char* buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) const {
+    read_slow4(buf + TILE_BYTES, b_off, ks, b);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) a[f] = *reinterpret_cast<const bf16x8_t*>(buf + a_off[ks] + f * (32 * KB * 2));
+  }
+  __device__ __forceinline__ void zero_tail(char*, int) const {}
+};
+
+__device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,
+                                        const int32_t* __restrict__ idx_out, const uint16_t* __restrict__ W, int K,
+                                        int Cin, int Cout, uint16_t* __restrict__ dX, int m0, int n0
+#ifdef SBP_TIMING
+                                        , long long* sbp_tslot
+#endif
+                                        ) {
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+
+  DxProb pb;
+#ifdef SBP_TIMING
+  pb.tslot = sbp_tslot;
+  if (t == 0 && sbp_tslot) sbp_tslot[0] = wall_clock64();
+#endif
+  pb.wave = wave;
+  pb.ca.init(idx_in, (uint32_t)Cout * 2u, m0, K, lane, wave);
+  pb.cb.init((uint32_t)Cin * 2u, n0, Cin, lane, wave);
+  pb.a_src = reinterpret_cast<const char*>(dY);
+  pb.b_src = reinterpret_cast<const char*>(W);
+  pb.b_stride = (uint32_t)KB * (uint32_t)Cin * 2u;
+  {
+    const int row = wm + (lane & 31), sw = (lane >> 2) & 3;
+    pb.a_off[0] = row * (KB * 2) + ((((lane >> 5)) ^ sw) << 4);
+    pb.a_off[1] = row * (KB * 2) + (((2 + (lane >> 5)) ^ sw) << 4);
+  }
+  slow_tile_lane_offs<BT, 4>(wn, lane, pb.b_off);
+  // output row of every tile row (-1 past the end), behind the ring; published by the ring's barriers
+  int* orow = reinterpret_cast<int*>(smem + RING);
+  orow[t] = m0 + t < K ? (idx_out ? idx_out[m0 + t] : m0 + t) : -1;
+
+  Acc acc;
+  zero_acc<4, 4>(acc);
+#ifdef SBP_TIMING
+  if (t == 0 && sbp_tslot) sbp_tslot[1] = wall_clock64() + (long long)(pb.ca.voff[0] & 0);
+#endif
+  ring_loop(smem, pb, Cout / KB, false, KB, acc);
+#ifdef SBP_TIMING
+  if (t == 0 && sbp_tslot) sbp_tslot[3] = wall_clock64();
+#endif
+
+  // epilogue: round to bf16, stage 128 rows at a time through LDS, write whole 16-byte pieces of the
+  // (scattered) rows.  Register v of lane l of block (i, j) is
+  // C[row wm + 32 i + (l & 31)][column wn + 32 j + 8 (v >> 2) + 4 (l >> 5) + (v & 3)].
+  constexpr int PITCH = BT * 2 + 16;
+  const int pc = t & 31, pr = t >> 5;
+  const bool col_ok = n0 + 8 * pc < Cin;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii) {
+      const int i = 2 * pass + ii;
+      char* row = smem + ((wave >> 1) * 64 + ii * 32 + (lane & 31)) * PITCH + (wn + 4 * (lane >> 5)) * 2;
+#pragma unroll
+      for (int jn = 0; jn < 4; ++jn)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          uint2 w;
+          w.x = bf16_pack(acc[i][jn][4 * q + 0], acc[i][jn][4 * q + 1]);
+          w.y = bf16_pack(acc[i][jn][4 * q + 2], acc[i][jn][4 * q + 3]);
+          *reinterpret_cast<uint2*>(row + (32 * jn + 8 * q) * 2) = w;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      const int r = pr + 8 * p;                   // staged row: half (r >> 6), block (r >> 5) & 1, row (r & 31)
+      const int o = orow[(r >> 6) * 128 + 32 * (2 * pass + ((r >> 5) & 1)) + (r & 31)];
+      if (o >= 0 && col_ok)
+        *reinterpret_cast<uint4*>(dX + (long long)o * Cin + n0 + 8 * pc) =
+            *reinterpret_cast<const uint4*>(smem + r * PITCH + pc * 16);
+    }
+    __syncthreads();
+  }
+#ifdef SBP_TIMING
+  if (t == 0 && sbp_tslot) sbp_tslot[4] = wall_clock64();
+#endif
+}
+
+// ---- dW partial = dY_k[j0:j1]^T X_k[j0:j1] -----------------------------------------------------------
+template <bool GATHER>
+struct DwProb {
+  static constexpr bool SWAP = false;
+  static constexpr int NREAD = 16, NPRE = GATHER ? 2 : 0;   // the 4 id reads pair up into 2 instructions
+  SlowCopy ca, cb;
+  const char* a_src;      // dY (GATHER) or dY + j0 rows
+  const char* b_src;      // X_k + j0 rows
+  const int* rows;        // LDS table: row of dY for kept row j0 + i
+  uint32_t a_ld, b_ld, rid[4], rid_next[4];
+#ifdef SBP_TIMING
+  long long* tslot;
+#endif
+  int wave, nrows, a_off[4], b_off[4];   // nrows = j1 - j0
+  __device__ __forceinline__ void prefetch(int s) {
+    if (GATHER) {
+#pragma unroll
+      for (int n = 0; n < 4; ++n) rid_next[n] = (uint32_t)rows[s * KB + ca.kl0 + 2 * n];
+    }
+  }
+  __device__ __forceinline__ void issue(int s, char* buf, bool partial) {
+    if (GATHER) {
+#pragma unroll
+      for (int n = 0; n < 4; ++n) async_copy16(a_src + (rid[n] * a_ld + ca.colb[n & 1]), buf + (4 * wave + n) * 1024);
+#pragma unroll
+      for (int n = 0; n < 4; ++n) rid[n] = rid_next[n];
+    } else if (!partial) {
+      ca.issue(a_src + (size_t)s * KB * a_ld, buf, wave);
+    } else {
+      ca.issue_clamped(a_src, a_ld, s * KB, nrows - 1, buf, wave);
+    }
+    if (!partial) cb.issue(b_src + (size_t)s * KB * b_ld, buf + TILE_BYTES, wave);
+    else cb.issue_clamped(b_src, b_ld, s * KB, nrows - 1, buf + TILE_BYTES, wave);
+  }
+  __device__ __forceinline__ void read(const char* buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) const {
+    read_slow4(buf + TILE_BYTES, b_off, ks, b);
+    read_slow4(buf, a_off, ks, a);
+  }
+  __device__ __forceinline__ void zero_tail(char* buf, int kvalid) const {
+    zero_slow_tail(buf, kvalid, threadIdx.x);
+    zero_slow_tail(buf + TILE_BYTES, kvalid, threadIdx.x);
+  }
+};
+
+template <bool GATHER>
+__device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
+                                        const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
+                                        float* __restrict__ part, int m0, int n0) {
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int nrows = j1 - j0;
+  const int nk = (nrows + KB - 1) / KB;
+
+  DwProb<GATHER> pb;
+#ifdef SBP_TIMING
+  pb.tslot = nullptr;
+#endif
+  pb.wave = wave;
+  pb.nrows = nrows;
+  pb.a_ld = (uint32_t)Cout * 2u;
+  pb.b_ld = (uint32_t)Cin * 2u;
+  pb.ca.init(pb.a_ld, m0, Cout, lane, wave);
+  pb.cb.init(pb.b_ld, n0, Cin, lane, wave);
+  pb.b_src = reinterpret_cast<const char*>(Xk) + (size_t)j0 * pb.b_ld;
+  pb.rows = nullptr;
+  if (GATHER) {
+    int* rows = reinterpret_cast<int*>(smem + RING);        // one stage more than the split has: ids are read ahead
+    for (int i = t; i < (nk + 1) * KB; i += 256) rows[i] = idx[min(j0 + i, j1 - 1)];
+    __syncthreads();
+    pb.rows = rows;
+    pb.a_src = reinterpret_cast<const char*>(dY);
+#pragma unroll
+    for (int n = 0; n < 4; ++n) pb.rid[n] = (uint32_t)rows[pb.ca.kl0 + 2 * n];
+  } else {
+    pb.a_src = reinterpret_cast<const char*>(dY) + (size_t)j0 * pb.a_ld;
+  }
+  slow_tile_lane_offs<BT, 4>(wm, lane, pb.a_off);
+  slow_tile_lane_offs<BT, 4>(wn, lane, pb.b_off);
+
+  Acc acc;
+  zero_acc<4, 4>(acc);
+  const bool tail = (nrows % KB) != 0;
+  ring_loop(smem, pb, nk, tail, nrows - (nk - 1) * KB, acc);
+
+  // register v of lane l of block (i, j) is C[row wm + 32 i + 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col wn + 32 j + (l & 31)]
+  if (m0 + BT <= Cout && n0 + BT <= Cin) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float* prow_ = part + (long long)(m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)) * Cin + n0 + wn +
+                       (lane & 31);
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) prow_[32 * jn] = acc[i][jn][v];
+      }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int o = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) {
+          const int col = n0 + wn + 32 * jn + (lane & 31);
+          if (o < Cout && col < Cin) part[(long long)o * Cin + col] = acc[i][jn][v];
+        }
+      }
+  }
+}
+
+}  // namespace big
+}  // namespace sbp
+#endif

@@ -33,12 +33,13 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 static constexpr int NTHREADS = 256;   // threads of the small kernels and of the 4-wavefront GEMM blocks
 // A GEMM block has NW = 4 wavefronts (2 x 2 over the tile) or NW = 8 (2 x 4: two wavefronts per SIMD).
 
-__device__ __forceinline__ uint32_t bf16_round(float f) {   // round-to-nearest-even, NaN kept quiet
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// fp32 -> bf16, round to nearest even, two values per instruction (v_cvt_pk_bf16_f32 on gfx950)
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
-__device__ __forceinline__ uint32_t bf16_pack(float lo, float hi) { return bf16_round(lo) | (bf16_round(hi) << 16); }
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -56,6 +57,12 @@ template <int N>
 __device__ __forceinline__ void wait_async_copies() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+// Workgroup barrier that orders LDS traffic only: every wavefront first drains its own LDS reads and
+// writes, then meets the others.  Unlike __syncthreads() it does not wait for the asynchronous copies
+// still in flight (those are counted by wait_async_copies), so later ring stages stay in flight.
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -248,12 +255,12 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
     if (NSTAGE == 4 && ahead == 2) wait_async_copies<2 * C>();
     else if (NSTAGE == 4 && ahead == 1) wait_async_copies<C>();
     else wait_async_copies<0>();
-    __syncthreads();
+    lds_barrier();
     if (tail && kt == nk - 1) {
       const int kvalid = kend - (k0 + kt * KB);
       la.zero_tail(cur, kvalid, t);
       lb.zero_tail(cur + A_BYTES, kvalid, t);
-      __syncthreads();
+      lds_barrier();
     }
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT == 3
     if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
@@ -262,7 +269,7 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
     compute(cur);
 #endif
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -418,26 +425,33 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
-// Partial bias gradient of one split: dbp[o] = sum_{j in [j0, j1)} dY[row(j), o] for 256 channels
+// Partial bias gradient of one row slice: dbp[o] = sum_{j in [j0, j1)} dY[row(j), o] for 256 channels
 // starting at c0.  Thread (x = t & 31, y = t >> 5) owns 8 channels and every 8th row; the eight row
-// lanes are added in a fixed order through LDS.  Pure streaming work for blocks that ride along with
-// the dW tiles (same launch, same rows, so the reads meet the GEMM's in cache).
+// lanes are added in a fixed order through LDS.  The slice's row ids are staged in LDS first, so the
+// row loads do not wait for index loads and eight of them are in flight per thread.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void colsum_block(char* smem, const uint16_t* __restrict__ dY,
                                              const int32_t* __restrict__ idx, int Cout, int j0, int j1, int c0,
                                              float* __restrict__ dbp) {
+  constexpr int CHUNK = 1024;                                 // row ids staged at a time
   float(*red)[32][9] = reinterpret_cast<float(*)[32][9]>(smem);
-  const int x = threadIdx.x & 31, y = threadIdx.x >> 5;     // wavefronts past the fourth only keep the barrier company
+  int* ids = reinterpret_cast<int*>(smem + sizeof(float) * 8 * 32 * 9);
+  const int x = threadIdx.x & 31, y = threadIdx.x >> 5;     // wavefronts past the fourth only keep the barriers company
   const int col = c0 + 8 * x;
   float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (col < Cout && y < 8) {
-#pragma unroll 4
-    for (int j = j0 + y; j < j1; j += 8) {
-      const long long g = idx ? (long long)idx[j] : (long long)j;
-      const uint4 v = *reinterpret_cast<const uint4*>(dY + g * Cout + col);
-      s[0] += bf16_lo(v.x); s[1] += bf16_hi(v.x); s[2] += bf16_lo(v.y); s[3] += bf16_hi(v.y);
-      s[4] += bf16_lo(v.z); s[5] += bf16_hi(v.z); s[6] += bf16_lo(v.w); s[7] += bf16_hi(v.w);
+  for (int b0 = j0; b0 < j1; b0 += CHUNK) {
+    const int n = min(CHUNK, j1 - b0);
+    for (int i = threadIdx.x; i < n; i += blockDim.x) ids[i] = idx ? idx[b0 + i] : b0 + i;
+    __syncthreads();
+    if (col < Cout && y < 8) {
+#pragma unroll 8
+      for (int j = y; j < n; j += 8) {
+        const uint4 v = *reinterpret_cast<const uint4*>(dY + (long long)ids[j] * Cout + col);
+        s[0] += bf16_lo(v.x); s[1] += bf16_hi(v.x); s[2] += bf16_lo(v.y); s[3] += bf16_hi(v.y);
+        s[4] += bf16_lo(v.z); s[5] += bf16_hi(v.z); s[6] += bf16_lo(v.w); s[7] += bf16_hi(v.w);
+      }
     }
+    __syncthreads();
   }
   if (y < 8) {
 #pragma unroll
