@@ -58,6 +58,9 @@ struct LinArgs {
   int K, M, Cin, Cout, rows_per_split, db_slice_rows;
   int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
   int dw_first;                       // large-tile kernel: dW units come before the dX tiles
+#ifdef SBP_TIMING
+  long long* tslots;
+#endif
 };
 
 // Zero fill of the dropped rows.  A wavefront takes 64 consecutive rows: every lane looks one row up
@@ -165,7 +168,7 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
     big::dx_tile(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * big::BT, tile_n * big::BT
 #ifdef SBP_TIMING
-                 , reinterpret_cast<long long*>(a.part) + 8 * L
+                 , a.tslots + 8 * L
 #endif
                  );
     return;
@@ -180,6 +183,9 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
   const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
   float* part = a.part + (long long)split * a.Cout * a.Cin;
+#ifdef SBP_TIMING
+  big::g_tslot = a.tslots + 8 * (128 + L);
+#endif
   if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
   else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
 }
@@ -404,7 +410,7 @@ static constexpr int kBigMaxRowsPerSplit = 4096;   // row ids of a split in LDS 
 static constexpr int kBigEpilogueDx = 4;           // epilogue cost of a tile, in stages
 static constexpr int kBigEpilogueDw = 3;
 
-struct BigChoice { int64_t K; int32_t Cin, Cout; int splits, rps; bool dw_first; };
+struct BigChoice { int64_t K; int32_t Cin, Cout; int splits, rps; bool dw_first; double fill; };   // fill: work / (CUs x finish time)
 
 static BigChoice choose_big_splits(int64_t K, int32_t Cin, int32_t Cout) {
   thread_local BigChoice cache[8] = {};
@@ -414,7 +420,7 @@ static BigChoice choose_big_splits(int64_t K, int32_t Cin, int32_t Cout) {
   const int64_t tiles_n = ceil_div(Cin, big::BT);
   const int64_t n_dx = ceil_div(K, big::BT) * tiles_n, l_dx = Cout / big::KB + kBigEpilogueDx;
   const int64_t tiles_w = ceil_div(Cout, big::BT) * tiles_n;
-  BigChoice best{K, Cin, Cout, 0, 0, false};
+  BigChoice best{K, Cin, Cout, 0, 0, false, 0.0};
   double best_cost = 0;
   const int64_t s_min = ceil_div(K, kBigMaxRowsPerSplit), s_max = std::max<int64_t>(s_min, std::min<int64_t>(48, K / 256));
   for (int64_t sp = s_min; sp <= s_max; ++sp) {
@@ -430,6 +436,7 @@ static BigChoice choose_big_splits(int64_t K, int32_t Cin, int32_t Cout) {
     if (best.splits == 0 || cost < best_cost) {
       best_cost = cost;
       best.splits = (int)ns; best.rps = (int)rps; best.dw_first = dw_first;
+      best.fill = (double)(n_dx * l_dx + tiles_w * ns * l_dw) / ((double)kNumCU * (double)end);
     }
   }
   cache[next] = best;
@@ -449,7 +456,9 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
     const char* env = std::getenv("SBP_TILE");
     const bool forced = env && std::string(env) == "big";
     const bool fits = Cout % big::KB == 0 && (uint64_t)M * (uint64_t)std::max(Cin, Cout) * 2u < (1ull << 32);
-    const bool pays = !env && false;
+    // it pays where whole 256-wide tiles exist and the simulated schedule keeps the CUs reasonably busy
+    const bool pays = !env && Cin >= big::BT && Cout >= big::BT && K >= 1024 &&
+                      choose_big_splits(K, Cin, Cout).fill >= 0.45;
     p.big = fits && (forced || pays);
   }
   if (p.big) {
@@ -596,6 +605,9 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     a.dX = static_cast<uint16_t*>(dX); a.part = part; a.dbp = db ? dbp : nullptr;
     a.K = (int)K; a.M = (int)M; a.Cin = Cin; a.Cout = Cout;
     a.rows_per_split = p.rows_per_split; a.db_slice_rows = p.db_slice_rows;
+#ifdef SBP_TIMING
+    a.tslots = reinterpret_cast<long long*>(inv_ws);
+#endif
     const bool want_dx = dX != nullptr, want_dw = dW != nullptr;
     if (p.big)
       launch_linear_big(p, a, want_dx, want_dw, scatter, s);

@@ -38,7 +38,7 @@ static constexpr int CPS = 8;                   // copies per wavefront and stag
 
 typedef f32x16_t Acc[4][4];
 #ifdef SBP_TIMING
-__device__ long long* sbp_timing_slot_dummy;
+static __shared__ long long* g_tslot;    // timing build only: where a dW unit writes its timestamps
 #define sbp_timing_slot pb.tslot
 #endif
 
@@ -396,7 +396,10 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
 
   DwProb<GATHER> pb;
 #ifdef SBP_TIMING
-  pb.tslot = nullptr;
+  __syncthreads();
+  long long* sbp_tslot = g_tslot;
+  pb.tslot = sbp_tslot;
+  if (t == 0) sbp_tslot[0] = wall_clock64();
 #endif
   pb.wave = wave;
   pb.nrows = nrows;
@@ -423,7 +426,13 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   Acc acc;
   zero_acc<4, 4>(acc);
   const bool tail = (nrows % KB) != 0;
+#ifdef SBP_TIMING
+  if (t == 0) sbp_tslot[1] = wall_clock64();
+#endif
   ring_loop(smem, pb, nk, tail, nrows - (nk - 1) * KB, acc);
+#ifdef SBP_TIMING
+  if (t == 0) sbp_tslot[3] = wall_clock64();
+#endif
 
   // register v of lane l of block (i, j) is C[row wm + 32 i + 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col wn + 32 j + (l & 31)]
   if (m0 + BT <= Cout && n0 + BT <= Cin) {
@@ -449,6 +458,10 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
         }
       }
   }
+#ifdef SBP_TIMING
+  __syncthreads();
+  if (t == 0) sbp_tslot[4] = wall_clock64();
+#endif
 }
 
 }  // namespace big
