@@ -51,6 +51,7 @@ struct LinearPlan {
   int    kb;            // contraction elements per LDS stage (64: two stages, 32: four stages)
   bool   big;           // 256 x 256 tiles, one workgroup per CU (sbp_mfma_big.h)
   bool   dw_first;      // big engine: dW units are the longer ones and are dispatched before the dX tiles
+  int    dx_bm;         // big engine: rows of a dX tile (256, or 128 where 256-row tiles are too few)
   int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
   int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]

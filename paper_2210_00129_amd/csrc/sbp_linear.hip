@@ -58,6 +58,7 @@ struct LinArgs {
   int K, M, Cin, Cout, rows_per_split, db_slice_rows;
   int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
   int dw_first;                       // large-tile kernel: dW units come before the dX tiles
+  int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
 #ifdef SBP_TIMING
   long long* tslots;
 #endif
@@ -162,15 +163,20 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   }
   const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
   if (is_dx) {
-    const int ntiles = ((a.K + big::BT - 1) / big::BT) * tiles_n;
+    const int ntiles = ((a.K + a.dx_bm - 1) / a.dx_bm) * tiles_n;
     const int L = xcd_chunked_id(wg, ntiles);
     if (L >= ntiles) return;
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-    big::dx_tile(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * big::BT, tile_n * big::BT
 #ifdef SBP_TIMING
-                 , a.tslots + 8 * L
+#define SBP_TSLOT , a.tslots + 8 * (L & 127)
+#else
+#define SBP_TSLOT
 #endif
-                 );
+    if (a.dx_bm == 128)
+      big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT SBP_TSLOT);
+    else
+      big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT SBP_TSLOT);
+#undef SBP_TSLOT
     return;
   }
   const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
@@ -184,7 +190,7 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
   float* part = a.part + (long long)split * a.Cout * a.Cin;
 #ifdef SBP_TIMING
-  big::g_tslot = a.tslots + 8 * (128 + L);
+  big::g_tslot = a.tslots + 8 * (128 + (L & 255));
 #endif
   if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
   else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
@@ -466,6 +472,8 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
     p.bm_w = p.bn_w = big::BT;
     p.kb = big::KB;
     p.dw_first = c.dw_first;
+    p.dx_bm = 256;
+    if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : 256;
     splits = c.splits;
   } else if (K > 0) {
     if (p.mfma) {
@@ -553,7 +561,8 @@ static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool
   a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M, 256))) : 0;
   const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
   a.n_helper = a.n_zero + n_db;
-  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, big::BT) * tiles_n, 8)) : 0;
+  a.dx_bm = p.dx_bm;
+  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, p.dx_bm) * tiles_n, 8)) : 0;
   a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, big::BT) * tiles_n * p.splits, 8)) : 0;
   a.dw_first = p.dw_first ? 1 : 0;
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);

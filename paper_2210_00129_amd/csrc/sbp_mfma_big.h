@@ -31,17 +31,16 @@ namespace big {
 static constexpr int BT = 256;                  // tile edge, rows and columns
 static constexpr int KB = 32;                   // contraction elements per stage
 static constexpr int NS = 4;                    // ring depth
-static constexpr int TILE_BYTES = BT * KB * 2;  // one operand tile of a stage
-static constexpr int STAGE = 2 * TILE_BYTES;
-static constexpr int RING = NS * STAGE;
-static constexpr int CPS = 8;                   // copies per wavefront and stage (4 per operand)
-
-typedef f32x16_t Acc[4][4];
+static constexpr int TILE_BYTES = BT * KB * 2;  // a 256-wide operand tile of a stage
+static constexpr int RING = NS * 2 * TILE_BYTES;   // the largest ring (two 256-wide operands): 128 KB
+// A tile is BMX x 256 with BMX = 256 (dW, dX) or 128 (dX where too few 256-row tiles exist to fill the
+// chip): FM = BMX / 64 accumulator block rows per wavefront, FM + 4 copies per wavefront and stage.
 #ifdef SBP_TIMING
 static __shared__ long long* g_tslot;    // timing build only: where a dW unit writes its timestamps
 #define sbp_timing_slot pb.tslot
 #endif
 
+template <int CPS>
 __device__ __forceinline__ void wait_copies_runtime(int stages_in_flight) {   // wave-uniform argument
   if (stages_in_flight >= 3) wait_async_copies<3 * CPS>();
   else if (stages_in_flight == 2) wait_async_copies<2 * CPS>();
@@ -49,21 +48,22 @@ __device__ __forceinline__ void wait_copies_runtime(int stages_in_flight) {   //
   else wait_async_copies<0>();
 }
 
-// ---- copies of a "row" tile [256 rows][32 k]: 16 blocks of 16 rows, 4 per wavefront -------------
+// ---- copies of a "row" tile [64 NI rows][32 k]: blocks of 16 rows, NI per wavefront ---------------
+template <int NI>
 struct RowCopy {
-  uint32_t voff[4];
+  uint32_t voff[NI];
   __device__ __forceinline__ void init(const int32_t* idx, uint32_t ld_bytes, int row0, int nrows, int lane, int wave) {
     const uint32_t chunk = (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) * 16);
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      const int r = min(row0 + 16 * (4 * wave + n) + (lane >> 2), nrows - 1);
+    for (int n = 0; n < NI; ++n) {
+      const int r = min(row0 + 16 * (NI * wave + n) + (lane >> 2), nrows - 1);
       const uint32_t g = idx ? (uint32_t)idx[r] : (uint32_t)r;
       voff[n] = g * ld_bytes + chunk;
     }
   }
   __device__ __forceinline__ void issue(const char* base, char* tile, int wave) const {
 #pragma unroll
-    for (int n = 0; n < 4; ++n) async_copy16(base + voff[n], tile + (4 * wave + n) * 1024);
+    for (int n = 0; n < NI; ++n) async_copy16(base + voff[n], tile + (NI * wave + n) * 1024);
   }
 };
 
@@ -106,20 +106,21 @@ __device__ __forceinline__ void zero_slow_tail(char* tile, int kvalid, int t) { 
   }
 }
 
-__device__ __forceinline__ void read_slow4(const char* tile, const int (&off)[4], int ks, bf16x8_t (&a)[4]) {
-#pragma unroll
-  for (int f = 0; f < 4; ++f) {
-    const char* p = tile + off[f] + ks * (16 * 512);
-    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p));
-    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p + 4 * 512));
-    a[f] = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-  }
+// one operand fragment (32 columns x 16 k) of a slow tile: two transposing reads
+__device__ __forceinline__ bf16x8_t read_slow1(const char* tile, int off, int ks) {
+  const char* p = tile + off + ks * (16 * 512);
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p + 4 * 512));
+  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-template <bool SWAP>
-__device__ __forceinline__ void mfma16(Acc& acc, const bf16x8_t (&a)[4], const bf16x8_t (&b)[4]) {
+// The MFMAs of a step run block row by block row (mfma_step below); the fragments are read in the
+// order in which they are first needed - b[0], a[0], b[1..3], a[1..] - so that the waits the compiler
+// places before each MFMA cover only reads issued long before.
+template <bool SWAP, int FM>
+__device__ __forceinline__ void mfma_step(f32x16_t (&acc)[FM][4], const bf16x8_t (&a)[FM], const bf16x8_t (&b)[4]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < FM; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
       acc[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0)
@@ -127,48 +128,66 @@ __device__ __forceinline__ void mfma16(Acc& acc, const bf16x8_t (&a)[4], const b
 }
 
 // Instruction order of a step, given to the scheduler as a pipeline of groups (the code of the step
-// is written before the call).  The compiler cannot tell the ring's buffers apart, so LDS reads and
-// copies keep their program order: a step that holds both issues its copies first.
-//   step without copies: 16 x { MFMA, NREAD/16 LDS reads }
-//   step with copies:     4 x { MFMA, 2 copies }, then 12 x { MFMA, LDS reads } (the reads spread evenly)
+// is written before the call): NM slots of one MFMA each; the first slots also take two LDS reads
+// each until the step's reads are out, the remaining slots share the step's copies evenly.
+//   * reads early: the last MFMAs of a step run while the last reads land, so the wait before the
+//     barrier (and before the next step's first MFMA) finds them done;
+//   * copies spread out: a burst of copies fills the address queue of the memory pipeline and the
+//     wavefront - and with it the MFMA stream - stalls at the next copy;
+//   * copies after reads, also in program order: the compiler cannot tell the ring's buffers apart
+//     and keeps LDS reads and copies in the order in which they are written.
 template <int MASK, int N>
 __device__ __forceinline__ void sched_group() {
   if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
 }
-template <int NREAD, int SLOTS, int I>
-__device__ __forceinline__ void mfma_read_slots() {     // slots I .. SLOTS-1 of { MFMA, share of the LDS reads }
+template <int NM, int NREAD, int NCOPY, int I>
+__device__ __forceinline__ void step_slots() {
+  constexpr int R = (NREAD + 1) / 2;                 // slots that carry reads
+  static_assert(R <= NM && (NCOPY == 0 || R < NM), "a step has room for its reads and copies");
   sched_group<0x008, 1>();
-  sched_group<0x100, (NREAD * (I + 1)) / SLOTS - (NREAD * I) / SLOTS>();
-  if constexpr (I + 1 < SLOTS) mfma_read_slots<NREAD, SLOTS, I + 1>();
-}
-template <int NREAD, bool COPIES>
-__device__ __forceinline__ void interleave_step() {
-  if constexpr (!COPIES) {
-    mfma_read_slots<NREAD, 16, 0>();
+  if constexpr (I < R) {
+    sched_group<0x100, (NREAD - 2 * I >= 2 ? 2 : 1)>();
   } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      sched_group<0x008, 1>();
-      sched_group<0x010, CPS / 4>();
-    }
-    mfma_read_slots<NREAD, 12, 0>();
+    constexpr int C = NM - R, j = I - R;
+    sched_group<0x010, (NCOPY * (j + 1)) / C - (NCOPY * j) / C>();
   }
+  if constexpr (I + 1 < NM) step_slots<NM, NREAD, NCOPY, I + 1>();
+}
+template <int NM, int NREAD, int NCOPY>
+__device__ __forceinline__ void interleave_step() {
+  step_slots<NM, NREAD, NCOPY, 0>();
 }
 
 // ---- the stage ring ------------------------------------------------------------------------------
 // P supplies: prefetch(s) - row ids of stage s into registers (gathered operand only);
-// issue(s, buf, partial) - the copies of stage s (after prefetch(s + 1)); read(buf, ks, a, b) - the
-// fragments of step ks; zero_tail(buf, kvalid); SWAP; NREAD (LDS reads per step); NPRE (LDS reads of a
-// prefetch).
+// issue_a / issue_b(s, buf, partial) - the copies of the two operands of stage s (issue_a after
+// prefetch(s + 1)); read(buf, ks, a, b) - the fragments of step ks; zero_tail(buf, kvalid); SWAP; FM
+// (accumulator block rows); STAGE (bytes of a stage); CPA, CPB (copies per wavefront and stage of the
+// two operands); NREAD (LDS reads per step); NPRE (LDS reads of a prefetch).
+//
+// Iteration s consumes stage s in two steps and issues stage s + 3: operand A behind the reads of step
+// 0, operand B behind those of step 1.  The barrier between the steps publishes stage s + 1 and
+// retires stage s, whose buffer takes stage s + 4 in the next iteration.
+template <class P, int CPS>
+__device__ __forceinline__ void wait_stage_runtime(bool next2, bool next3a) {   // wave-uniform arguments
+  if (next2 && next3a) wait_async_copies<CPS + P::CPA>();
+  else if (next2) wait_async_copies<CPS>();
+  else wait_async_copies<0>();
+}
+
 template <class P>
-__device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, int kvalid_last, Acc& acc) {
+__device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, int kvalid_last,
+                                          f32x16_t (&acc)[P::FM][4]) {
+  constexpr int STAGE = P::STAGE, CPS = P::CPA + P::CPB, FM = P::FM, NM = 4 * P::FM;
+  static_assert(NS == 4, "buffer arithmetic below assumes a ring of four");
 #pragma unroll
-  for (int s = 0; s < NS; ++s)
+  for (int s = 0; s < NS - 1; ++s)
     if (s < nk) {
       pb.prefetch(s + 1);
-      pb.issue(s, smem + s * STAGE, tail && s == nk - 1);
+      pb.issue_a(s, smem + s * STAGE, tail && s == nk - 1);
+      pb.issue_b(s, smem + s * STAGE, tail && s == nk - 1);
     }
-  wait_copies_runtime(min(NS - 1, nk - 1));
+  wait_copies_runtime<CPS>(min(NS - 2, nk - 1));
   lds_barrier();
 #ifdef SBP_TIMING
   if (threadIdx.x == 0 && sbp_timing_slot) sbp_timing_slot[2] = wall_clock64();
@@ -177,68 +196,73 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     pb.zero_tail(smem, kvalid_last);
     lds_barrier();
   }
-  bf16x8_t pa[4], pbf[4], qa[4], qb[4];
+  bf16x8_t pa[FM], pbf[4], qa[FM], qb[4];
   pb.read(smem, 0, pa, pbf);
 
   int s = 0;
-  // steady state: stage s + NS exists and is not the last one
-  for (; s + NS + 1 < nk; ++s) {
-    char* cur = smem + (s & (NS - 1)) * STAGE;
-    const char* nxt = smem + ((s + 1) & (NS - 1)) * STAGE;
-    pb.prefetch(s + NS + 1);
+  // steady state: stage s + 3 exists and is not the last one
+  for (; s + NS < nk; ++s) {
+    const char* cur = smem + (s & 3) * STAGE;
+    const char* nxt = smem + ((s + 1) & 3) * STAGE;
+    char* dst = smem + ((s + 3) & 3) * STAGE;
+    pb.prefetch(s + NS);
 #if !defined(SBP_EXPERIMENT) || (SBP_EXPERIMENT != 3 && SBP_EXPERIMENT != 4)
     pb.read(cur, 1, qa, qb);
 #endif
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
+    pb.issue_a(s + 3, dst, false);
+#endif
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
-    mfma16<P::SWAP>(acc, pa, pbf);
+    mfma_step<P::SWAP, FM>(acc, pa, pbf);
 #endif
-    interleave_step<P::NREAD + P::NPRE, false>();
+    interleave_step<NM, P::NREAD + P::NPRE, P::CPA>();
 #if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
-    wait_async_copies<2 * CPS>();               // stage s + 1 has landed (s + 2 and s + 3 may be in flight)
+    wait_async_copies<CPS + P::CPA>();          // stage s + 1 has landed (s + 2 and half of s + 3 may be in flight)
 #endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 5
     lds_barrier();
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
-    pb.issue(s + NS, cur, false);               // every wavefront is done with stage s: its buffer is free
-#endif
 #if !defined(SBP_EXPERIMENT) || (SBP_EXPERIMENT != 3 && SBP_EXPERIMENT != 4)
     pb.read(nxt, 0, pa, pbf);
 #endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
-    mfma16<P::SWAP>(acc, qa, qb);
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
+    pb.issue_b(s + 3, dst, false);
 #endif
-    interleave_step<P::NREAD, true>();
+#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
+    mfma_step<P::SWAP, FM>(acc, qa, qb);
+#endif
+    interleave_step<NM, P::NREAD, P::CPB>();
   }
   // drain: the same steps with the end of the operand in view
   for (; s < nk; ++s) {
-    char* cur = smem + (s & (NS - 1)) * STAGE;
-    char* nxt = smem + ((s + 1) & (NS - 1)) * STAGE;
+    const char* cur = smem + (s & 3) * STAGE;
+    char* nxt = smem + ((s + 1) & 3) * STAGE;
+    char* dst = smem + ((s + 3) & 3) * STAGE;
+    const bool more = s + 3 < nk, last_partial = tail && s + 3 == nk - 1;
+    if (more) pb.prefetch(s + NS);
     pb.read(cur, 1, qa, qb);
-    mfma16<P::SWAP>(acc, pa, pbf);
-    interleave_step<P::NREAD, false>();
-    if (s + 1 < nk) wait_copies_runtime(min(NS - 2, nk - 2 - s));
+    if (more) pb.issue_a(s + 3, dst, last_partial);
+    mfma_step<P::SWAP, FM>(acc, pa, pbf);
+    interleave_step<NM, P::NREAD, 0>();
+    if (s + 1 < nk) wait_stage_runtime<P, CPS>(s + 2 < nk, more);
     lds_barrier();
     if (tail && s + 1 == nk - 1) {
       pb.zero_tail(nxt, kvalid_last);
       lds_barrier();
     }
-    if (s + NS < nk) {
-      pb.prefetch(s + NS + 1);
-      pb.issue(s + NS, cur, tail && s + NS == nk - 1);
-    }
     pb.read(nxt, 0, pa, pbf);                   // past the last stage: reads a stale buffer, never used
-    mfma16<P::SWAP>(acc, qa, qb);
-    interleave_step<P::NREAD, false>();
+    if (more) pb.issue_b(s + 3, dst, last_partial);
+    mfma_step<P::SWAP, FM>(acc, qa, qb);
+    interleave_step<NM, P::NREAD, 0>();
   }
   lds_barrier();
 }
 
 // ---- dX = dY_k W ---------------------------------------------------------------------------------
+template <int BMX>
 struct DxProb {
   static constexpr bool SWAP = true;            // lane ends with 4 consecutive input channels of one row
-  static constexpr int NREAD = 12, NPRE = 0;
-  RowCopy ca;
+  static constexpr int FM = BMX / 64, CPA = FM, CPB = 4, NREAD = FM + 8, NPRE = 0;
+  static constexpr int A_BYTES = BMX * KB * 2, STAGE = A_BYTES + TILE_BYTES;
+  RowCopy<FM> ca;
   SlowCopy cb;
   const char* a_src;
   const char* b_src;
@@ -248,18 +272,25 @@ struct DxProb {
 #endif
   int wave, a_off[2], b_off[4];
   __device__ __forceinline__ void prefetch(int) {}
-  __device__ __forceinline__ void issue(int s, char* buf, bool) {
-    ca.issue(a_src + (size_t)s * (KB * 2), buf, wave);
-    cb.issue(b_src + (size_t)s * b_stride, buf + TILE_BYTES, wave);
+  __device__ __forceinline__ void issue_a(int s, char* buf, bool) { ca.issue(a_src + (size_t)s * (KB * 2), buf, wave); }
+  __device__ __forceinline__ void issue_b(int s, char* buf, bool) {
+    cb.issue(b_src + (size_t)s * b_stride, buf + A_BYTES, wave);
   }
-  __device__ __forceinline__ void read(const char* buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) const {
-    read_slow4(buf + TILE_BYTES, b_off, ks, b);
+  __device__ __forceinline__ bf16x8_t read_a(const char* buf, int ks, int f) const {
+    return *reinterpret_cast<const bf16x8_t*>(buf + a_off[ks] + f * (32 * KB * 2));
+  }
+  __device__ __forceinline__ void read(const char* buf, int ks, bf16x8_t (&a)[FM], bf16x8_t (&b)[4]) const {
+    b[0] = read_slow1(buf + A_BYTES, b_off[0], ks);
+    a[0] = read_a(buf, ks, 0);
 #pragma unroll
-    for (int f = 0; f < 4; ++f) a[f] = *reinterpret_cast<const bf16x8_t*>(buf + a_off[ks] + f * (32 * KB * 2));
+    for (int f = 1; f < 4; ++f) b[f] = read_slow1(buf + A_BYTES, b_off[f], ks);
+#pragma unroll
+    for (int f = 1; f < FM; ++f) a[f] = read_a(buf, ks, f);
   }
   __device__ __forceinline__ void zero_tail(char*, int) const {}
 };
 
+template <int BMX>
 __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,
                                         const int32_t* __restrict__ idx_out, const uint16_t* __restrict__ W, int K,
                                         int Cin, int Cout, uint16_t* __restrict__ dX, int m0, int n0
@@ -269,9 +300,10 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
                                         ) {
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  constexpr int FM = BMX / 64;
+  const int wm = (wave >> 1) * (BMX / 2), wn = (wave & 1) * 128;
 
-  DxProb pb;
+  DxProb<BMX> pb;
 #ifdef SBP_TIMING
   pb.tslot = sbp_tslot;
   if (t == 0 && sbp_tslot) sbp_tslot[0] = wall_clock64();
@@ -290,10 +322,10 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
   slow_tile_lane_offs<BT, 4>(wn, lane, pb.b_off);
   // output row of every tile row (-1 past the end), behind the ring; published by the ring's barriers
   int* orow = reinterpret_cast<int*>(smem + RING);
-  orow[t] = m0 + t < K ? (idx_out ? idx_out[m0 + t] : m0 + t) : -1;
+  if (t < BMX) orow[t] = m0 + t < K ? (idx_out ? idx_out[m0 + t] : m0 + t) : -1;
 
-  Acc acc;
-  zero_acc<4, 4>(acc);
+  f32x16_t acc[FM][4];
+  zero_acc<FM, 4>(acc);
 #ifdef SBP_TIMING
   if (t == 0 && sbp_tslot) sbp_tslot[1] = wall_clock64() + (long long)(pb.ca.voff[0] & 0);
 #endif
@@ -309,7 +341,7 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
   const int pc = t & 31, pr = t >> 5;
   const bool col_ok = n0 + 8 * pc < Cin;
 #pragma unroll
-  for (int pass = 0; pass < 2; ++pass) {
+  for (int pass = 0; pass < FM / 2; ++pass) {
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii) {
       const int i = 2 * pass + ii;
@@ -328,7 +360,7 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
       const int r = pr + 8 * p;                   // staged row: half (r >> 6), block (r >> 5) & 1, row (r & 31)
-      const int o = orow[(r >> 6) * 128 + 32 * (2 * pass + ((r >> 5) & 1)) + (r & 31)];
+      const int o = orow[(r >> 6) * (BMX / 2) + 32 * (2 * pass + ((r >> 5) & 1)) + (r & 31)];
       if (o >= 0 && col_ok)
         *reinterpret_cast<uint4*>(dX + (long long)o * Cin + n0 + 8 * pc) =
             *reinterpret_cast<const uint4*>(smem + r * PITCH + pc * 16);
@@ -344,6 +376,7 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 template <bool GATHER>
 struct DwProb {
   static constexpr bool SWAP = false;
+  static constexpr int FM = 4, CPA = 4, CPB = 4, STAGE = 2 * TILE_BYTES;
   static constexpr int NREAD = 16, NPRE = GATHER ? 2 : 0;   // the 4 id reads pair up into 2 instructions
   SlowCopy ca, cb;
   const char* a_src;      // dY (GATHER) or dY + j0 rows
@@ -360,7 +393,7 @@ struct DwProb {
       for (int n = 0; n < 4; ++n) rid_next[n] = (uint32_t)rows[s * KB + ca.kl0 + 2 * n];
     }
   }
-  __device__ __forceinline__ void issue(int s, char* buf, bool partial) {
+  __device__ __forceinline__ void issue_a(int s, char* buf, bool partial) {
     if (GATHER) {
 #pragma unroll
       for (int n = 0; n < 4; ++n) async_copy16(a_src + (rid[n] * a_ld + ca.colb[n & 1]), buf + (4 * wave + n) * 1024);
@@ -371,12 +404,18 @@ struct DwProb {
     } else {
       ca.issue_clamped(a_src, a_ld, s * KB, nrows - 1, buf, wave);
     }
+  }
+  __device__ __forceinline__ void issue_b(int s, char* buf, bool partial) {
     if (!partial) cb.issue(b_src + (size_t)s * KB * b_ld, buf + TILE_BYTES, wave);
     else cb.issue_clamped(b_src, b_ld, s * KB, nrows - 1, buf + TILE_BYTES, wave);
   }
   __device__ __forceinline__ void read(const char* buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) const {
-    read_slow4(buf + TILE_BYTES, b_off, ks, b);
-    read_slow4(buf, a_off, ks, a);
+    b[0] = read_slow1(buf + TILE_BYTES, b_off[0], ks);
+    a[0] = read_slow1(buf, a_off[0], ks);
+#pragma unroll
+    for (int f = 1; f < 4; ++f) b[f] = read_slow1(buf + TILE_BYTES, b_off[f], ks);
+#pragma unroll
+    for (int f = 1; f < 4; ++f) a[f] = read_slow1(buf, a_off[f], ks);
   }
   __device__ __forceinline__ void zero_tail(char* buf, int kvalid) const {
     zero_slow_tail(buf, kvalid, threadIdx.x);
@@ -423,7 +462,7 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   slow_tile_lane_offs<BT, 4>(wm, lane, pb.a_off);
   slow_tile_lane_offs<BT, 4>(wn, lane, pb.b_off);
 
-  Acc acc;
+  f32x16_t acc[4][4];
   zero_acc<4, 4>(acc);
   const bool tail = (nrows % KB) != 0;
 #ifdef SBP_TIMING

@@ -62,7 +62,8 @@ __device__ __forceinline__ void wait_async_copies() {
 // writes, then meets the others.  Unlike __syncthreads() it does not wait for the asynchronous copies
 // still in flight (those are counted by wait_async_copies), so later ring stages stay in flight.
 __device__ __forceinline__ void lds_barrier() {
-  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xc07f);                 // lgkmcnt(0) only; as a builtin the compiler's own wait
+  asm volatile("s_barrier" ::: "memory");             // bookkeeping sees it and adds no second wait afterwards
 }
 
 // ------------------------------------------------------------------------------------------------
