@@ -4,9 +4,11 @@
 //   dX[idx[j],:] = dY[idx[j],:] W              every other row of dX = +0
 // W is stored [Cout, Cin].
 //
-// bf16 path: both contractions run on the gfx950 matrix cores (see sbp_mfma_gemm.h).  dW is split
-// along the kept rows into fp32 partial sums that a second kernel adds in a fixed order
-// (deterministic, no floating-point atomics); db rides on the dW tiles.
+// bf16 path: both contractions run on the gfx950 matrix cores, in one launch per layer together with
+// the zero fill of the dropped rows and the column sums for db: linear_big_kernel (256-wide tiles,
+// sbp_mfma_big.h) where the layer is large enough to keep the CUs busy with them, linear_bwd_kernel
+// (128 x 128 tiles, sbp_mfma_gemm.h) otherwise.  dW is split along the kept rows into fp32 partial
+// sums that a second kernel adds in a fixed order (deterministic, no floating-point atomics).
 // fp32 and odd shapes take plain kernels.
 #include <cstdio>
 #include <cstdlib>
@@ -59,9 +61,6 @@ struct LinArgs {
   int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
   int dw_first;                       // large-tile kernel: dW units come before the dX tiles
   int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
-#ifdef SBP_TIMING
-  long long* tslots;
-#endif
 };
 
 // Zero fill of the dropped rows.  A wavefront takes 64 consecutive rows: every lane looks one row up
@@ -167,16 +166,10 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
     const int L = xcd_chunked_id(wg, ntiles);
     if (L >= ntiles) return;
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-#ifdef SBP_TIMING
-#define SBP_TSLOT , a.tslots + 8 * (L & 127)
-#else
-#define SBP_TSLOT
-#endif
     if (a.dx_bm == 128)
-      big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT SBP_TSLOT);
+      big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT);
     else
-      big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT SBP_TSLOT);
-#undef SBP_TSLOT
+      big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT);
     return;
   }
   const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
@@ -189,9 +182,6 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
   const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
   float* part = a.part + (long long)split * a.Cout * a.Cin;
-#ifdef SBP_TIMING
-  big::g_tslot = a.tslots + 8 * (128 + (L & 255));
-#endif
   if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
   else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
 }
@@ -379,8 +369,9 @@ __global__ void __launch_bounds__(NTHREADS) plain_db_kernel(const T* __restrict_
 // ------------------------------------------------------------------------------------------------
 static constexpr int kNumCU = 256;
 
-// Debug aid: SBP_TILE = "128x128x4x64" | "128x128x4x32" | "256x256x8x64" | "256x256x8x32" forces a tile
-// shape (rows x columns x wavefronts x stage length; stage length 32 runs a 4-deep ring, 64 a 2-deep one).
+// Debug aid: SBP_TILE = "128x128x4x64" | "128x128x4x32" | "256x256x8x64" | "256x256x8x32" | "256x256x4x64" |
+// "256x256x4x32" forces a tile shape of the general engine (rows x columns x wavefronts x stage length; stage
+// length 32 runs a 4-deep ring, 64 a 2-deep one); "big" forces the large-tile engine (see plan_linear).
 static bool env_tile(const char* name, int* bm, int* bn, int* nw, int* kb) {
   const char* v = std::getenv(name);
   if (!v) return false;
@@ -392,9 +383,9 @@ static bool env_tile(const char* name, int* bm, int* bn, int* nw, int* kb) {
   return true;
 }
 
-// ---- large-tile engine: how many dW splits --------------------------------------------------------
+// ---- large-tile engine: tile height of dX and number of dW splits -----------------------------------
 // One workgroup per CU and a grid ordered long units first is list scheduling; its finish time for n1
-// units of length l1 followed by n2 units of length l2 (lengths in stages of 32) is simulated exactly.
+// units of length l1 followed by n2 units of length l2 is simulated exactly (times in nanoseconds).
 static int64_t list_schedule_end(int64_t n1, int64_t l1, int64_t n2, int64_t l2) {
   std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> cu;
   for (int i = 0; i < kNumCU; ++i) cu.push(0);
@@ -413,36 +404,50 @@ static int64_t list_schedule_end(int64_t n1, int64_t l1, int64_t n2, int64_t l2)
 }
 
 static constexpr int kBigMaxRowsPerSplit = 4096;   // row ids of a split in LDS next to the 128 KB ring
-static constexpr int kBigEpilogueDx = 4;           // epilogue cost of a tile, in stages
-static constexpr int kBigEpilogueDw = 3;
+// Unit costs measured on the device (timestamps inside the kernel, ViT-Base shapes), nanoseconds:
+static constexpr int64_t kNsStage256 = 600;        // one stage of 32 of a 256 x 256 tile (dX or dW)
+static constexpr int64_t kNsStage128 = 390;        // one stage of a 128 x 256 dX tile
+static constexpr int64_t kNsFixedDx256 = 6000;     // index loads, first stage, epilogue
+static constexpr int64_t kNsFixedDx128 = 3600;
+static constexpr int64_t kNsFixedDw = 6300;        // + the row-id table, ~1 ns per kept row of the split
+static constexpr double kReduceBytesPerNs = 3500;  // the reduction streams the partials at about 3.5 TB/s
 
-struct BigChoice { int64_t K; int32_t Cin, Cout; int splits, rps; bool dw_first; double fill; };   // fill: work / (CUs x finish time)
+struct BigChoice {
+  int64_t K; int32_t Cin, Cout;
+  int splits, rps, dx_bm;
+  bool dw_first;
+  double fill;      // work / (CUs x finish time) of the simulated schedule
+};
 
-static BigChoice choose_big_splits(int64_t K, int32_t Cin, int32_t Cout) {
+static BigChoice choose_big(int64_t K, int32_t Cin, int32_t Cout) {
   thread_local BigChoice cache[8] = {};
   thread_local int next = 0;
   for (const BigChoice& c : cache)
     if (c.K == K && c.Cin == Cin && c.Cout == Cout && c.splits > 0) return c;
   const int64_t tiles_n = ceil_div(Cin, big::BT);
-  const int64_t n_dx = ceil_div(K, big::BT) * tiles_n, l_dx = Cout / big::KB + kBigEpilogueDx;
   const int64_t tiles_w = ceil_div(Cout, big::BT) * tiles_n;
-  BigChoice best{K, Cin, Cout, 0, 0, false, 0.0};
+  const int64_t nk_x = Cout / big::KB;
+  BigChoice best{K, Cin, Cout, 0, 0, 256, false, 0.0};
   double best_cost = 0;
   const int64_t s_min = ceil_div(K, kBigMaxRowsPerSplit), s_max = std::max<int64_t>(s_min, std::min<int64_t>(48, K / 256));
-  for (int64_t sp = s_min; sp <= s_max; ++sp) {
-    const int64_t rps = ceil_div(ceil_div(K, sp), 64) * 64;
-    const int64_t ns = ceil_div(K, rps);
-    if (ns != sp && sp != s_min) continue;          // same split count as a smaller sp: already seen
-    const int64_t l_dw = rps / big::KB + kBigEpilogueDw;
-    const bool dw_first = l_dw > l_dx;
-    const int64_t end = dw_first ? list_schedule_end(tiles_w * ns, l_dw, n_dx, l_dx)
-                                 : list_schedule_end(n_dx, l_dx, tiles_w * ns, l_dw);
-    // every split writes and the reduction reads an fp32 copy of dW: about 4 MB move in one stage time
-    const double cost = (double)end + (double)ns * Cout * Cin * 8.0 / 4.0e6;
-    if (best.splits == 0 || cost < best_cost) {
-      best_cost = cost;
-      best.splits = (int)ns; best.rps = (int)rps; best.dw_first = dw_first;
-      best.fill = (double)(n_dx * l_dx + tiles_w * ns * l_dw) / ((double)kNumCU * (double)end);
+  for (int bm : {256, 128}) {
+    const int64_t n_dx = ceil_div(K, bm) * tiles_n;
+    const int64_t l_dx = bm == 256 ? kNsFixedDx256 + kNsStage256 * nk_x : kNsFixedDx128 + kNsStage128 * nk_x;
+    for (int64_t sp = s_min; sp <= s_max; ++sp) {
+      const int64_t rps = ceil_div(ceil_div(K, sp), 64) * 64;
+      const int64_t ns = ceil_div(K, rps);
+      if (ns != sp && sp != s_min) continue;          // same split count as a smaller sp: already seen
+      const int64_t l_dw = kNsFixedDw + rps + kNsStage256 * (rps / big::KB);
+      const bool dw_first = l_dw > l_dx;
+      const int64_t end = dw_first ? list_schedule_end(tiles_w * ns, l_dw, n_dx, l_dx)
+                                   : list_schedule_end(n_dx, l_dx, tiles_w * ns, l_dw);
+      // the reduction kernel that follows reads every split's fp32 copy of dW and writes dW
+      const double cost = (double)end + 3000.0 + (double)(ns + 1) * Cout * Cin * 4.0 / kReduceBytesPerNs;
+      if (best.splits == 0 || cost < best_cost) {
+        best_cost = cost;
+        best.splits = (int)ns; best.rps = (int)rps; best.dw_first = dw_first; best.dx_bm = bm;
+        best.fill = (double)(n_dx * l_dx + tiles_w * ns * l_dw) / ((double)kNumCU * (double)end);
+      }
     }
   }
   cache[next] = best;
@@ -464,17 +469,22 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
     const bool fits = Cout % big::KB == 0 && (uint64_t)M * (uint64_t)std::max(Cin, Cout) * 2u < (1ull << 32);
     // it pays where whole 256-wide tiles exist and the simulated schedule keeps the CUs reasonably busy
     const bool pays = !env && Cin >= big::BT && Cout >= big::BT && K >= 1024 &&
-                      choose_big_splits(K, Cin, Cout).fill >= 0.45;
+                      choose_big(K, Cin, Cout).fill >= 0.45;
     p.big = fits && (forced || pays);
   }
   if (p.big) {
-    const BigChoice c = choose_big_splits(K, Cin, Cout);
+    const BigChoice c = choose_big(K, Cin, Cout);
     p.bm_w = p.bn_w = big::BT;
     p.kb = big::KB;
     p.dw_first = c.dw_first;
-    p.dx_bm = 256;
-    if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : 256;
+    p.dx_bm = c.dx_bm;
     splits = c.splits;
+    if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : 256;   // debugging aids
+    if (const char* e = std::getenv("SBP_SPLITS")) {
+      splits = std::max<int>(std::atoi(e), (int)ceil_div(K, kBigMaxRowsPerSplit));
+      const int64_t rps_e = ceil_div(ceil_div(K, splits), 64) * 64;
+      p.dw_first = kNsFixedDw + kNsStage256 * (rps_e / big::KB) > (p.dx_bm == 256 ? kNsFixedDx256 + kNsStage256 * (Cout / big::KB) : kNsFixedDx128 + kNsStage128 * (Cout / big::KB));
+    }
   } else if (K > 0) {
     if (p.mfma) {
       env_tile("SBP_TILE", &p.bm_w, &p.bn_w, &p.nw_w, &p.kb);
@@ -614,9 +624,6 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     a.dX = static_cast<uint16_t*>(dX); a.part = part; a.dbp = db ? dbp : nullptr;
     a.K = (int)K; a.M = (int)M; a.Cin = Cin; a.Cout = Cout;
     a.rows_per_split = p.rows_per_split; a.db_slice_rows = p.db_slice_rows;
-#ifdef SBP_TIMING
-    a.tslots = reinterpret_cast<long long*>(inv_ws);
-#endif
     const bool want_dx = dX != nullptr, want_dw = dW != nullptr;
     if (p.big)
       launch_linear_big(p, a, want_dx, want_dw, scatter, s);

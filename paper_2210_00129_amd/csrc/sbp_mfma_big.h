@@ -1,25 +1,26 @@
 // Large-tile engine for the two bf16 contractions of the SBP linear backward (paper,
-// eq:backward_fc_sbp): 256 x 256 output tiles, one workgroup of 4 wavefronts per CU, every wavefront
-// owning a 128 x 128 quarter (16 accumulator blocks of 32 x 32, 256 accumulator registers).
+// eq:backward_fc_sbp): 256-wide output tiles, one workgroup of 4 wavefronts per CU, every wavefront
+// owning a 128 x 128 quarter of a 256 x 256 tile (16 accumulator blocks of 32 x 32 = 256 accumulator
+// registers) or a 64 x 128 quarter of a 128 x 256 dX tile.
 //
 // Why this shape: at 64 x 64 per wavefront the operand reads from LDS need as many LDS cycles as the
 // MFMAs need matrix-core cycles; at 128 x 128 they need half.  With one wavefront per SIMD nothing
 // hides a stall, so the instruction stream is laid out by hand:
-//   * the contraction runs in stages of 32 through a ring of 4 LDS stages (32 KB each); the copies of
-//     three stages are in flight while one is consumed;
+//   * the contraction runs in stages of 32 through a ring of 4 LDS stages; while stage s is consumed,
+//     s + 1 and s + 2 are landing and the copies of s + 3 are being issued;
 //   * global -> LDS copies are global_load_lds_dwordx4 with a wave-uniform base and a per-lane 32-bit
-//     offset computed once per tile: a stage's copies cost one scalar add and no vector arithmetic;
-//   * operand fragments are double-buffered in registers: while the 16 MFMAs of one 16-deep step run,
-//     the LDS reads of the next step (and, every second step, the next stage's copies) are issued
-//     between them;
-//   * one barrier per stage, between its two steps: it retires the stage just read (its buffer takes
-//     the copies of stage s + 4) and publishes stage s + 1.  The barrier waits for LDS traffic only;
-//     copies in flight are counted with s_waitcnt vmcnt.
+//     offset computed once per tile: a stage's copies cost a scalar add and no vector arithmetic;
+//   * operand fragments are double-buffered in registers: while the MFMAs of one 16-deep step run,
+//     the LDS reads of the next step and then a share of the copies are issued between them, in an
+//     order given to the compiler's scheduler group by group (interleave_step);
+//   * one barrier per stage, between its two steps: it retires the stage just read and publishes
+//     stage s + 1.  The barrier waits for LDS traffic only; copies in flight are counted with
+//     s_waitcnt vmcnt.
 // LDS tile layouts and their swizzles are those of sbp_mfma_gemm.h ("row" tile for dY in dX, "slow"
 // tiles read with ds_read_b64_tr_b16 for everything else).
 //
-// Limits (checked on the host, the smaller engine takes the rest): Cout % 32 == 0 (no partial stage
-// in dX), row offsets fit 32 bits (M * max(Cin, Cout) * 2 < 2^32).
+// Limits (checked on the host, the general engine takes the rest): Cout % 32 == 0 (no partial stage
+// in dX), row offsets fit 32 bits (M * max(Cin, Cout) * 2 < 2^32), at most 4096 kept rows per dW split.
 #ifndef SBP_MFMA_BIG_H_
 #define SBP_MFMA_BIG_H_
 
@@ -35,10 +36,6 @@ static constexpr int TILE_BYTES = BT * KB * 2;  // a 256-wide operand tile of a 
 static constexpr int RING = NS * 2 * TILE_BYTES;   // the largest ring (two 256-wide operands): 128 KB
 // A tile is BMX x 256 with BMX = 256 (dW, dX) or 128 (dX where too few 256-row tiles exist to fill the
 // chip): FM = BMX / 64 accumulator block rows per wavefront, FM + 4 copies per wavefront and stage.
-#ifdef SBP_TIMING
-static __shared__ long long* g_tslot;    // timing build only: where a dW unit writes its timestamps
-#define sbp_timing_slot pb.tslot
-#endif
 
 template <int CPS>
 __device__ __forceinline__ void wait_copies_runtime(int stages_in_flight) {   // wave-uniform argument
@@ -189,9 +186,6 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     }
   wait_copies_runtime<CPS>(min(NS - 2, nk - 1));
   lds_barrier();
-#ifdef SBP_TIMING
-  if (threadIdx.x == 0 && sbp_timing_slot) sbp_timing_slot[2] = wall_clock64();
-#endif
   if (tail && nk == 1) {
     pb.zero_tail(smem, kvalid_last);
     lds_barrier();
@@ -206,29 +200,15 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     const char* nxt = smem + ((s + 1) & 3) * STAGE;
     char* dst = smem + ((s + 3) & 3) * STAGE;
     pb.prefetch(s + NS);
-#if !defined(SBP_EXPERIMENT) || (SBP_EXPERIMENT != 3 && SBP_EXPERIMENT != 4)
     pb.read(cur, 1, qa, qb);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
     pb.issue_a(s + 3, dst, false);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
     mfma_step<P::SWAP, FM>(acc, pa, pbf);
-#endif
     interleave_step<NM, P::NREAD + P::NPRE, P::CPA>();
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
     wait_async_copies<CPS + P::CPA>();          // stage s + 1 has landed (s + 2 and half of s + 3 may be in flight)
-#endif
     lds_barrier();
-#if !defined(SBP_EXPERIMENT) || (SBP_EXPERIMENT != 3 && SBP_EXPERIMENT != 4)
     pb.read(nxt, 0, pa, pbf);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 2
     pb.issue_b(s + 3, dst, false);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
     mfma_step<P::SWAP, FM>(acc, qa, qb);
-#endif
     interleave_step<NM, P::NREAD, P::CPB>();
   }
   // drain: the same steps with the end of the operand in view
@@ -267,9 +247,6 @@ struct DxProb {
   const char* a_src;
   const char* b_src;
   uint32_t b_stride;
-#ifdef SBP_TIMING
-  long long* tslot;
-#endif
   int wave, a_off[2], b_off[4];
   __device__ __forceinline__ void prefetch(int) {}
   __device__ __forceinline__ void issue_a(int s, char* buf, bool) { ca.issue(a_src + (size_t)s * (KB * 2), buf, wave); }
@@ -293,21 +270,13 @@ struct DxProb {
 template <int BMX>
 __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx_in,
                                         const int32_t* __restrict__ idx_out, const uint16_t* __restrict__ W, int K,
-                                        int Cin, int Cout, uint16_t* __restrict__ dX, int m0, int n0
-#ifdef SBP_TIMING
-                                        , long long* sbp_tslot
-#endif
-                                        ) {
+                                        int Cin, int Cout, uint16_t* __restrict__ dX, int m0, int n0) {
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   constexpr int FM = BMX / 64;
   const int wm = (wave >> 1) * (BMX / 2), wn = (wave & 1) * 128;
 
   DxProb<BMX> pb;
-#ifdef SBP_TIMING
-  pb.tslot = sbp_tslot;
-  if (t == 0 && sbp_tslot) sbp_tslot[0] = wall_clock64();
-#endif
   pb.wave = wave;
   pb.ca.init(idx_in, (uint32_t)Cout * 2u, m0, K, lane, wave);
   pb.cb.init((uint32_t)Cin * 2u, n0, Cin, lane, wave);
@@ -326,13 +295,7 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 
   f32x16_t acc[FM][4];
   zero_acc<FM, 4>(acc);
-#ifdef SBP_TIMING
-  if (t == 0 && sbp_tslot) sbp_tslot[1] = wall_clock64() + (long long)(pb.ca.voff[0] & 0);
-#endif
   ring_loop(smem, pb, Cout / KB, false, KB, acc);
-#ifdef SBP_TIMING
-  if (t == 0 && sbp_tslot) sbp_tslot[3] = wall_clock64();
-#endif
 
   // epilogue: round to bf16, stage 128 rows at a time through LDS, write whole 16-byte pieces of the
   // (scattered) rows.  Register v of lane l of block (i, j) is
@@ -367,9 +330,6 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
     }
     __syncthreads();
   }
-#ifdef SBP_TIMING
-  if (t == 0 && sbp_tslot) sbp_tslot[4] = wall_clock64();
-#endif
 }
 
 // ---- dW partial = dY_k[j0:j1]^T X_k[j0:j1] -----------------------------------------------------------
@@ -383,9 +343,6 @@ struct DwProb {
   const char* b_src;      // X_k + j0 rows
   const int* rows;        // LDS table: row of dY for kept row j0 + i
   uint32_t a_ld, b_ld, rid[4], rid_next[4];
-#ifdef SBP_TIMING
-  long long* tslot;
-#endif
   int wave, nrows, a_off[4], b_off[4];   // nrows = j1 - j0
   __device__ __forceinline__ void prefetch(int s) {
     if (GATHER) {
@@ -434,12 +391,6 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   const int nk = (nrows + KB - 1) / KB;
 
   DwProb<GATHER> pb;
-#ifdef SBP_TIMING
-  __syncthreads();
-  long long* sbp_tslot = g_tslot;
-  pb.tslot = sbp_tslot;
-  if (t == 0) sbp_tslot[0] = wall_clock64();
-#endif
   pb.wave = wave;
   pb.nrows = nrows;
   pb.a_ld = (uint32_t)Cout * 2u;
@@ -465,13 +416,7 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   f32x16_t acc[4][4];
   zero_acc<4, 4>(acc);
   const bool tail = (nrows % KB) != 0;
-#ifdef SBP_TIMING
-  if (t == 0) sbp_tslot[1] = wall_clock64();
-#endif
   ring_loop(smem, pb, nk, tail, nrows - (nk - 1) * KB, acc);
-#ifdef SBP_TIMING
-  if (t == 0) sbp_tslot[3] = wall_clock64();
-#endif
 
   // register v of lane l of block (i, j) is C[row wm + 32 i + 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col wn + 32 j + (l & 31)]
   if (m0 + BT <= Cout && n0 + BT <= Cin) {
@@ -497,10 +442,6 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
         }
       }
   }
-#ifdef SBP_TIMING
-  __syncthreads();
-  if (t == 0) sbp_tslot[4] = wall_clock64();
-#endif
 }
 
 }  // namespace big

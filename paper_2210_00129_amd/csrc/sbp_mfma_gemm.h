@@ -3,15 +3,17 @@
 //   dW tile:  C[o, i] = sum_j dY[row(j), o] X_k[j, i]        (j = kept rows of one split)
 // on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
-// A block of 256 threads (2 x 2 wavefronts) owns a BM x BN tile and walks the contraction in stages
-// of BK = 64 or 32.  Global memory is read in 16-byte pieces into registers NPRE stages ahead and stored to
-// a double-buffered LDS stage; the kept rows of dY are gathered by these loads, so dY_k never exists
-// in memory.  Two LDS tile layouts:
-//   * "row" tile  [rows][BK]   for an operand whose contraction index is contiguous in memory (dY in
+// A block of 4 or 8 wavefronts (2 x 2 or 2 x 4) owns a BM x BN tile and walks the contraction in
+// stages of KB = 64 or 32 through a ring of LDS stages filled by asynchronous global -> LDS copies;
+// the kept rows of dY are gathered by these copies, so dY_k never exists in memory.  Two LDS tile
+// layouts:
+//   * "row" tile  [rows][KB]   for an operand whose contraction index is contiguous in memory (dY in
 //     dX): MFMA operands are 16-byte LDS reads;
-//   * "slow" tile [BK][cols]   for an operand whose contraction index is the slow axis in memory (dY
+//   * "slow" tile [KB][cols]   for an operand whose contraction index is the slow axis in memory (dY
 //     and X_k in dW, W in dX): stored as it lies in memory and read with the transposing LDS read
 //     ds_read_b64_tr_b16, which hands every lane 4 consecutive contraction elements of its column.
+// This file holds the general engine (any shape, 128 x 128 tiles by default, two blocks per CU) and
+// the pieces shared with the large-tile engine of sbp_mfma_big.h.
 // The main loop is free of bounds checks: addresses are clamped into the operand (rows or columns
 // past the edge compute results that are never stored) and only the last, partial stage zeroes the
 // contraction rows past the end.
@@ -263,12 +265,8 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
       lb.zero_tail(cur + A_BYTES, kvalid, t);
       lds_barrier();
     }
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT == 3
     if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
-#endif
-#if !defined(SBP_EXPERIMENT) || SBP_EXPERIMENT != 3
     compute(cur);
-#endif
   }
   lds_barrier();
 }

@@ -93,6 +93,76 @@ def test_linear_bf16_mfma_tiles_and_ragged_tails(shape, k):
     check_linear(X, W, dY, idx, "bf16")
 
 
+class _env:
+    """Sets debugging variables the library reads at every call, for the duration of a test."""
+    def __init__(self, **kv):
+        self.kv = kv
+    def __enter__(self):
+        import os
+        self.old = {k: os.environ.get(k) for k in self.kv}
+        for k, v in self.kv.items():
+            os.environ[k] = str(v)
+    def __exit__(self, *exc):
+        import os
+        for k, v in self.old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+@pytest.mark.parametrize("dx_rows", [256, 128])
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [(192, 768), (768, 192), (512, 128), (72, 224), (8, 32), (264, 160)])
+def test_linear_large_tile_engine_forced_on_ragged_shapes(shape, k, dx_rows):
+    # the 256-wide engine on shapes it would not pick: partial tiles in every dimension, a partial last
+    # stage in the dW contraction (K not a multiple of 32), one or several splits
+    Cin, Cout = shape
+    X, W, dY, idx = _grid_case(6, 1, 14, 14, Cin, Cout, k, "bf16", 20 + k)
+    with _env(SBP_TILE="big", SBP_DXBM=dx_rows):
+        check_linear(X, W, dY, idx, "bf16")
+
+
+@pytest.mark.parametrize("splits", [1, 2, 5, 13])
+@pytest.mark.parametrize("flags", [0, sbp.FLAG_DY_COMPACT, sbp.FLAG_DX_COMPACT, sbp.FLAG_DY_COMPACT | sbp.FLAG_DX_COMPACT])
+def test_linear_large_tile_engine_splits_and_compact_flags(splits, flags):
+    X, W, dY, idx = _grid_case(16, 1, 14, 14, 320, 288, 3, "bf16", 33)     # K = 16 * 148 = 2368 = 74 stages of 32
+    assert idx.size == 2368
+    with _env(SBP_TILE="big", SBP_SPLITS=splits):
+        check_linear(X, W, dY, idx, "bf16", flags=flags)
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 95, 129, 257])
+def test_linear_large_tile_engine_short_contractions(K):
+    # fewer stages than the ring is deep, with and without a partial last stage
+    g = np.random.default_rng(K)
+    M, Cin, Cout = 300, 264, 96
+    idx = np.sort(g.choice(M, size=K, replace=False)).astype(np.int32)
+    X = si.normal((M, Cin), 1.0, 5, "bf16"); W = si.normal((Cout, Cin), 0.05, 6, "bf16"); dY = si.normal((M, Cout), 1.0, 7, "bf16")
+    with _env(SBP_TILE="big"):
+        check_linear(X, W, dY, idx, "bf16")
+    with _env(SBP_TILE="big", SBP_DXBM=128):
+        check_linear(X, W, dY, idx, "bf16")
+
+
+def test_linear_engines_agree_bit_for_bit_on_integers():
+    # exact arithmetic: whichever engine, tile height or split count runs, the results are the same bits
+    B, P, H, W_, Cin, Cout = 8, 1, 14, 14, 320, 288
+    M = B * (P + H * W_)
+    X = si.small_ints((M, Cin), -2, 2, 1, "bf16"); Wt = si.small_ints((Cout, Cin), -2, 2, 2, "bf16")
+    dY = si.small_ints((M, Cout), -2, 2, 3, "bf16")
+    idx = torch.from_numpy(oracle.sample_indices(B, P, H, W_, 2, 5, 9)).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idx)
+    outs = []
+    for env in (dict(SBP_TILE="128x128x4x64"), dict(SBP_TILE="big", SBP_DXBM=256, SBP_SPLITS=1),
+                dict(SBP_TILE="big", SBP_DXBM=128, SBP_SPLITS=4)):
+        with _env(**env):
+            outs.append([bits(t) if t.dtype == torch.bfloat16 else f64(t) for t in sbp.backward_linear(dY.cuda(), idx, Xk, Wt.cuda())])
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert np.array_equal(a, b)
+
+
 @pytest.mark.parametrize("inv_mode", ["sampler", "garbage"])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_linear_with_caller_supplied_inverse_map(inv_mode, dtype):
