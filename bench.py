@@ -302,10 +302,14 @@ def main():
     if dom:
         avg_ms, fl = per_launch[dom]
         achieved = fl / avg_ms / 1e9
-        roofline = {"bound": "mfma", "kernel": "linear_bwd_kernel (dW + dX tiles)" if fused else dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
+        # which kernel the library runs for these layers (one fused launch per layer on the bf16 path)
+        engines = sorted({sbp.backward_linear_engine(job.M, K_r, s.Cin, s.Cout, job.code)[0] for s in wl.linears})
+        kname = {"mfma_large": "linear_big_kernel", "mfma": "linear_bwd_kernel", "plain": "plain_dw_kernel"}
+        kernel = " / ".join(kname[e] for e in engines) + (" (dW + dX tiles, zero fill, db sums: one launch per layer)" if fused else "")
+        roofline = {"bound": "mfma", "kernel": kernel if fused else dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": measured_traffic("linear_bwd_kernel_vit_base_r0.5.md")
-                    if (wl.name == "vit_base" and args.ratio == 0.5) else None,
+                    "traffic": measured_traffic("linear_big_kernel_vit_base_r0.5.md")
+                    if (wl.name == "vit_base" and args.ratio == 0.5 and engines == ["mfma_large"]) else None,
                     "avg_launch_us": round(avg_ms * 1e3, 2),
                     "flops_per_launch": fl}
     breakdown = {c: {"ms_per_step": round(v[0] / max(2, min(args.steps, 5)), 4), "launches": v[1]}

@@ -117,6 +117,19 @@ size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t 
                                      int32_t dtype, uint32_t flags);
 
 /*
+ * Host only.  Which kernels sbp_backward_linear runs for these sizes (a report for logs and
+ * benchmarks; the results do not depend on it): SBP_ENGINE_PLAIN (fp32, or channel counts that are
+ * not multiples of 8), SBP_ENGINE_MFMA (128 x 128 tiles), SBP_ENGINE_MFMA_LARGE (256-wide tiles, one
+ * workgroup per CU); -1 on invalid sizes.  If split_count is not NULL it receives the number of
+ * fp32 partial sums of dW that the reduction adds.
+ */
+#define SBP_ENGINE_PLAIN 0
+#define SBP_ENGINE_MFMA 1
+#define SBP_ENGINE_MFMA_LARGE 2
+int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
+                                   uint32_t flags, int32_t* split_count);
+
+/*
  * Steps "gather dY", "dW", "db", "dX" (paper, eq:backward_fc_sbp with every dropped term
  * removed):
  *   dW[o, i] = sum_j dY[idx[j], o] * X_k[j, i]           fp32, [Cout, Cin]

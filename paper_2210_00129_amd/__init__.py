@@ -93,6 +93,19 @@ def backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags=0) -> int:
     return int(_lib.lib().sbp_backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags))
 
 
+ENGINE_NAMES = {0: "plain", 1: "mfma", 2: "mfma_large"}
+
+
+def backward_linear_engine(M, K, Cin, Cout, dtype_code, flags=0):
+    """(engine name, dW split count) that sbp_backward_linear uses for these sizes."""
+    import ctypes
+    n = ctypes.c_int32(0)
+    e = int(_lib.lib().sbp_backward_linear_engine(M, K, Cin, Cout, dtype_code, flags, ctypes.byref(n)))
+    if e < 0:
+        raise ValueError("invalid sizes")
+    return ENGINE_NAMES[e], int(n.value)
+
+
 def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), dW=None, db=None, dX=None,
                     workspace=None, inv=None):
     """SBP backward of Y = X W^T + b on the kept rows.  Returns (dW fp32, db fp32, dX)."""

@@ -137,6 +137,14 @@ size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t 
   return plan_linear(M, K, Cin, Cout, dtype, flags).bytes;
 }
 
+int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags,
+                                   int32_t* split_count) {
+  if (validate_linear(M, K, Cin, Cout, dtype, flags) != SBP_OK) return -1;
+  const LinearPlan p = plan_linear(M, K, Cin, Cout, dtype, flags);
+  if (split_count) *split_count = p.splits;
+  return !p.mfma ? SBP_ENGINE_PLAIN : (p.big ? SBP_ENGINE_MFMA_LARGE : SBP_ENGINE_MFMA);
+}
+
 int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* inv, const void* Xk, const void* W,
                             int64_t M,
                             int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, float* dW, float* db,

@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 12
+    assert len(names) == 13
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -131,6 +131,24 @@ def test_backward_linear_argument_errors():
     assert L.sbp_backward_linear_workspace(100, 500, 64, 128, 1, 0) == 0
     # compact dX needs no inverse map: smaller workspace
     assert L.sbp_backward_linear_workspace(100, 50, 64, 128, 1, 2) < ws
+
+
+def test_backward_linear_engine_report_and_plan():
+    # host logic of the plan: which kernels a shape gets, and how many partial sums of dW
+    assert sbp.backward_linear_engine(100, 50, 64, 128, sbp.F32)[0] == "plain"
+    assert sbp.backward_linear_engine(100, 50, 60, 36, sbp.BF16)[0] == "plain"          # channels not multiples of 8
+    assert sbp.backward_linear_engine(12608, 6336, 192, 768, sbp.BF16)[0] == "mfma"     # narrower than a 256 tile
+    for Cin, Cout in [(768, 2304), (768, 768), (768, 3072), (3072, 768)]:               # ViT-Base layers, r = 0.5
+        name, splits = sbp.backward_linear_engine(12608, 6336, Cin, Cout, sbp.BF16)
+        assert name == "mfma_large" and 2 <= splits <= 24
+        # the workspace holds that many fp32 copies of dW (+ db partials + the inverse map)
+        assert sbp.backward_linear_workspace(12608, 6336, Cin, Cout, sbp.BF16) >= splits * Cin * Cout * 4
+    assert sbp.backward_linear_engine(12608, 6336, 768, 2320, sbp.BF16)[0] == "mfma"    # Cout not a multiple of 32
+    assert sbp.backward_linear_engine(4200, 500, 512, 512, sbp.BF16)[0] == "mfma"       # too few kept rows
+    with pytest.raises(ValueError):
+        sbp.backward_linear_engine(100, 500, 64, 128, sbp.BF16)
+    # rows of dY that byte offsets of 32 bits cannot reach: the general engine takes the shape
+    assert sbp.backward_linear_engine(1 << 20, 1 << 19, 4096, 4096, sbp.BF16)[0] == "mfma"
 
 
 def test_backward_dwconv_argument_errors():
