@@ -15,4 +15,10 @@ from .sbp_oracle import (  # noqa: F401
     backward_linear,
     backward_dwconv,
     mix64,
+    gelu,
+    gelu_grad,
+    act_forward_rows,
+    act_backward_rows,
+    layernorm_rows,
+    backward_layernorm,
 )

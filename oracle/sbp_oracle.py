@@ -32,6 +32,14 @@ What follows the paper and what is this repository's own reading:
   the published SplitMix64 sequence, the structure to the properties the paper
   states: fixed keep ratio per cell, equal visiting frequency of every
   position).
+* ``act_forward_rows`` / ``act_backward_rows`` / ``backward_layernorm``: the
+  paper's implementation (Alg. ``alg:sbp_impl``) wraps "an arbitrary operation
+  f": the kept rows go through f with gradient, the dropped rows without, and
+  with one keep-set shared by a stack of layers the kept / dropped split passes
+  through the chain unchanged (``eq:backward_fc2_sbp_same_drop_loc``).  For a
+  row-wise f (GELU, LayerNorm) that is the ordinary backward of f on the kept
+  rows, zero on the dropped rows, parameter gradients summed over the kept
+  rows only.  GELU is the exact form x Phi(x) used by ViT and ConvNeXt.
 """
 from __future__ import annotations
 
@@ -187,3 +195,71 @@ def backward_dwconv(dY, idx, X, Wd, pad):
     db = g.sum(axis=(0, 1, 2))
     dX = dXp[:, pad:pad + H, pad:pad + Wi, :].copy()
     return dWd, db, dX
+
+
+# ---------------------------------------------------------------------------------------------
+# Row-wise operations between the linear layers, on the kept rows only (Alg. alg:sbp_impl with a
+# row-wise f; chain rule with a shared keep-set, eq:backward_fc2_sbp_same_drop_loc).
+# ---------------------------------------------------------------------------------------------
+def _phi_cdf(z):
+    from scipy.special import erf          # library primitive: the error function, fp64
+    return 0.5 * (1.0 + erf(z / np.sqrt(2.0)))
+
+
+def gelu(z):
+    """Exact GELU: z * Phi(z), Phi the standard normal distribution function."""
+    z = np.asarray(z, dtype=np.float64)
+    return z * _phi_cdf(z)
+
+
+def gelu_grad(z):
+    """d/dz [z Phi(z)] = Phi(z) + z phi(z), phi the standard normal density."""
+    z = np.asarray(z, dtype=np.float64)
+    return _phi_cdf(z) + z * np.exp(-0.5 * z * z) / np.sqrt(2.0 * np.pi)
+
+
+def act_forward_rows(Z_k):
+    """H_k = gelu(Z_k) on the cached kept rows of the pre-activation."""
+    return gelu(Z_k)
+
+
+def act_backward_rows(dH_k, Z_k):
+    """dZ_k = dH_k * gelu'(Z_k): backward of the activation on the kept rows."""
+    return np.asarray(dH_k, dtype=np.float64) * gelu_grad(Z_k)
+
+
+def layernorm_rows(X_k, gamma, beta, eps):
+    """Row-wise LayerNorm (biased variance), for the pins."""
+    X_k = np.asarray(X_k, dtype=np.float64)
+    mu = X_k.mean(axis=1, keepdims=True)
+    var = ((X_k - mu) ** 2).mean(axis=1, keepdims=True)
+    return (X_k - mu) / np.sqrt(var + eps) * gamma + beta
+
+
+def backward_layernorm(dU_k, X_k, gamma, eps, idx, M):
+    """Backward of U = LayerNorm(X) * gamma + beta restricted to the kept rows.
+
+    dU_k [K, C]: gradient at the kept rows of U; X_k [K, C]: the kept rows of X.
+    Returns dX [M, C] (zero off the keep-set), dgamma [C], dbeta [C].
+    Per kept row, with xhat = (x - mean) / sqrt(var + eps) and g = dU * gamma:
+    dx = (g - mean(g) - xhat * mean(g * xhat)) / sqrt(var + eps).
+    """
+    dU_k = np.asarray(dU_k, dtype=np.float64)
+    X_k = np.asarray(X_k, dtype=np.float64)
+    gamma = np.asarray(gamma, dtype=np.float64)
+    idx = np.asarray(idx, dtype=np.int64)
+    K, C = X_k.shape
+    dX = np.zeros((M, C), dtype=np.float64)
+    dgamma = np.zeros(C, dtype=np.float64)
+    dbeta = np.zeros(C, dtype=np.float64)
+    for j in range(K):
+        x = X_k[j]
+        mu = x.mean()
+        var = ((x - mu) ** 2).mean()
+        rstd = 1.0 / np.sqrt(var + eps)
+        xhat = (x - mu) * rstd
+        g = dU_k[j] * gamma
+        dX[idx[j]] = (g - g.mean() - xhat * (g * xhat).mean()) * rstd
+        dgamma += dU_k[j] * xhat
+        dbeta += dU_k[j]
+    return dX, dgamma, dbeta
