@@ -184,6 +184,53 @@ int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* i
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
+ * Row-wise steps between the linear layers, on compact rows (paper, Alg. alg:sbp_impl: "an arbitrary
+ * operation f" sees the kept rows with gradient and the dropped rows without; with one keep-set shared
+ * by a stack of layers the kept / dropped split passes through the chain unchanged,
+ * eq:backward_fc2_sbp_same_drop_loc).  With SBP_FLAG_DX_COMPACT / SBP_FLAG_DY_COMPACT on the linear
+ * layers around them, a whole MLP branch runs its backward on [K, .] rows and only its last step
+ * scatters to [M, .] and zero-fills.
+ *
+ * Activation, act = SBP_ACT_GELU (exact GELU, z * Phi(z), the ViT / ConvNeXt MLP activation):
+ *   sbp_act_forward_rows    H_k  = gelu(Z_k)                  recomputes the second layer's input from the
+ *                                                             cached kept rows of the pre-activation
+ *   sbp_act_backward_rows   dZ_k = dH_k * gelu'(Z_k),  gelu'(z) = Phi(z) + z phi(z)
+ *   Z_k, dH_k  device, in,  [K, C] of `dtype`;   H_k, dZ_k  device, out, [K, C] of `dtype`
+ *   (dZ_k may be the same buffer as dH_k: every element is read before it is written).
+ * fp32 arithmetic; bf16 outputs are rounded once (round-to-nearest-even).
+ */
+#define SBP_ACT_GELU 0
+int32_t sbp_act_forward_rows(const void* Z_k, int64_t K, int32_t C, int32_t dtype, int32_t act,
+                             void* H_k, void* stream);
+int32_t sbp_act_backward_rows(const void* dH_k, const void* Z_k, int64_t K, int32_t C, int32_t dtype,
+                              int32_t act, void* dZ_k, void* stream);
+
+/* Host only.  Bytes of workspace sbp_backward_layernorm needs (0 on invalid sizes). */
+size_t sbp_backward_layernorm_workspace(int64_t M, int64_t K, int32_t C, int32_t dtype, uint32_t flags);
+
+/*
+ * Backward of U = LayerNorm(X) * gamma + beta (normalisation over the C channels of a row, biased
+ * variance, `eps` inside the square root) restricted to the kept rows:
+ *   per kept row j:  xhat = (x - mean(x)) / sqrt(var(x) + eps),  g = dU_k[j] * gamma,
+ *                    dX[idx[j], :] = (g - mean(g) - xhat * mean(g * xhat)) / sqrt(var(x) + eps)
+ *   every other row of dX is +0.0;   dgamma = sum_j dU_k[j] * xhat_j,   dbeta = sum_j dU_k[j]
+ *   dU_k   device, in,  [K, C] of `dtype` (compact: the output of the linear backward with
+ *                       SBP_FLAG_DX_COMPACT)
+ *   X_k    device, in,  [K, C] kept rows of the LayerNorm input (sbp_forward_cache); mean and variance
+ *                       are recomputed from them in fp32
+ *   gamma  device, in,  [C] fp32
+ *   idx, inv            as for sbp_backward_linear (inv may be NULL; unused with SBP_FLAG_DX_COMPACT)
+ *   dgamma, dbeta  device, out, [C] fp32 (added to with SBP_FLAG_ACCUMULATE_DW); dX device, out,
+ *                       [M, C] of `dtype`, or [K, C] with SBP_FLAG_DX_COMPACT; each may be NULL
+ *   workspace           device, 256-byte aligned, sbp_backward_layernorm_workspace(...) bytes
+ * Deterministic (fixed summation order, no floating-point atomics).
+ */
+int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* gamma, float eps,
+                               const int32_t* idx, const int32_t* inv, int64_t M, int64_t K, int32_t C,
+                               int32_t dtype, float* dgamma, float* dbeta, void* dX,
+                               void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
  * Measurement aid (not a step of the method; for benchmarks only).  While enabled, every kernel
  * launch of the library is bracketed by a pair of HIP events on the caller's stream; this is the
  * one place where the library creates HIP objects (the events, destroyed again by the read call).

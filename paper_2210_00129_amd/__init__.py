@@ -134,6 +134,55 @@ def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), d
     return dW, db, dX
 
 
+ACT_GELU = 0
+
+
+def act_forward_rows(Z_k, out=None, act=ACT_GELU):
+    """H_k = gelu(Z_k) on compact kept rows [K, C]."""
+    K, C = Z_k.shape
+    if out is None:
+        out = torch.empty_like(Z_k)
+    _lib.check(_lib.lib().sbp_act_forward_rows(_dev(Z_k, "Z_k"), K, C, _dtype_code(Z_k), act, _dev(out, "H_k"),
+                                               _stream(Z_k.device)))
+    return out
+
+
+def act_backward_rows(dH_k, Z_k, out=None, act=ACT_GELU):
+    """dZ_k = dH_k * gelu'(Z_k) on compact kept rows [K, C] (out may be dH_k)."""
+    K, C = Z_k.shape
+    if out is None:
+        out = torch.empty_like(Z_k)
+    _lib.check(_lib.lib().sbp_act_backward_rows(_dev(dH_k, "dH_k"), _dev(Z_k, "Z_k"), K, C, _dtype_code(Z_k), act,
+                                                _dev(out, "dZ_k"), _stream(Z_k.device)))
+    return out
+
+
+def backward_layernorm_workspace(M, K, C, dtype_code, flags=0) -> int:
+    return int(_lib.lib().sbp_backward_layernorm_workspace(M, K, C, dtype_code, flags))
+
+
+def backward_layernorm(dU_k, X_k, gamma, eps, idx, M, inv=None, flags=0, want=("dgamma", "dbeta", "dX"),
+                       dgamma=None, dbeta=None, dX=None, workspace=None):
+    """LayerNorm backward on the kept rows.  dU_k, X_k: [K, C]; gamma fp32 [C].  Returns (dgamma, dbeta, dX)."""
+    K, C = X_k.shape
+    code = _dtype_code(X_k)
+    dev = X_k.device
+    if "dgamma" in want and dgamma is None:
+        dgamma = torch.empty((C,), dtype=torch.float32, device=dev)
+    if "dbeta" in want and dbeta is None:
+        dbeta = torch.empty((C,), dtype=torch.float32, device=dev)
+    if "dX" in want and dX is None:
+        dX = torch.empty((K if (flags & FLAG_DX_COMPACT) else M, C), dtype=X_k.dtype, device=dev)
+    need = backward_layernorm_workspace(M, K, C, code, flags)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _lib.check(_lib.lib().sbp_backward_layernorm(
+        _dev(dU_k, "dU_k"), _dev(X_k, "X_k"), _dev(gamma, "gamma"), float(eps), _dev(idx, "idx"), _dev(inv, "inv"),
+        M, K, C, code, _dev(dgamma, "dgamma"), _dev(dbeta, "dbeta"), _dev(dX, "dX"), _dev(workspace, "workspace"),
+        workspace.numel(), flags, _stream(dev)))
+    return dgamma, dbeta, dX
+
+
 def backward_dwconv_workspace(B, H, W, C, ks, K, dtype_code, flags=0) -> int:
     return int(_lib.lib().sbp_backward_dwconv_workspace(B, H, W, C, ks, K, dtype_code, flags))
 

@@ -180,6 +180,60 @@ static int32_t validate_dw(int32_t B, int32_t H, int32_t W, int32_t C, int32_t k
   return SBP_OK;
 }
 
+static int32_t validate_rows(int64_t K, int32_t C, int32_t dtype) {
+  if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (K < 0 || C < 1 || K > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad shape K=%lld C=%d", (long long)K, C);
+  return SBP_OK;
+}
+
+int32_t sbp_act_forward_rows(const void* Zk, int64_t K, int32_t C, int32_t dtype, int32_t act, void* Hk, void* stream) {
+  int32_t st = validate_rows(K, C, dtype);
+  if (st != SBP_OK) return st;
+  if (act != SBP_ACT_GELU) return fail(SBP_ERR_FLAGS, "unknown activation %d", act);
+  if (K == 0) return SBP_OK;
+  if (!Zk || !Hk) return fail(SBP_ERR_NULL, "Z_k or H_k is NULL");
+  return launch_act_rows(nullptr, Zk, K * (int64_t)C, dtype, act, false, Hk, static_cast<hipStream_t>(stream));
+}
+
+int32_t sbp_act_backward_rows(const void* dHk, const void* Zk, int64_t K, int32_t C, int32_t dtype, int32_t act,
+                              void* dZk, void* stream) {
+  int32_t st = validate_rows(K, C, dtype);
+  if (st != SBP_OK) return st;
+  if (act != SBP_ACT_GELU) return fail(SBP_ERR_FLAGS, "unknown activation %d", act);
+  if (K == 0) return SBP_OK;
+  if (!dHk || !Zk || !dZk) return fail(SBP_ERR_NULL, "dH_k, Z_k or dZ_k is NULL");
+  return launch_act_rows(dHk, Zk, K * (int64_t)C, dtype, act, true, dZk, static_cast<hipStream_t>(stream));
+}
+
+static int32_t validate_layernorm(int64_t M, int64_t K, int32_t C, int32_t dtype, uint32_t flags) {
+  if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (flags & ~(SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW)) return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);
+  if (M < 1 || M > INT32_MAX || C < 1) return fail(SBP_ERR_SHAPE, "bad shape M=%lld C=%d", (long long)M, C);
+  if (K < 0 || K > M) return fail(SBP_ERR_SHAPE, "need 0 <= K <= M, got K=%lld M=%lld", (long long)K, (long long)M);
+  return SBP_OK;
+}
+
+size_t sbp_backward_layernorm_workspace(int64_t M, int64_t K, int32_t C, int32_t dtype, uint32_t flags) {
+  if (validate_layernorm(M, K, C, dtype, flags) != SBP_OK) return 0;
+  return plan_layernorm(M, K, C, dtype, flags).bytes;
+}
+
+int32_t sbp_backward_layernorm(const void* dUk, const void* Xk, const float* gamma, float eps, const int32_t* idx,
+                               const int32_t* inv, int64_t M, int64_t K, int32_t C, int32_t dtype, float* dgamma,
+                               float* dbeta, void* dX, void* ws, size_t ws_bytes, uint32_t flags, void* stream) {
+  int32_t st = validate_layernorm(M, K, C, dtype, flags);
+  if (st != SBP_OK) return st;
+  if (!(eps >= 0.f)) return fail(SBP_ERR_SHAPE, "eps must be >= 0");
+  if (!dgamma && !dbeta && !dX) return SBP_OK;
+  if (K > 0 && (!dUk || !Xk || !gamma)) return fail(SBP_ERR_NULL, "dU_k, X_k or gamma is NULL");
+  if (dX && !(flags & SBP_FLAG_DX_COMPACT) && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL");
+  const LnPlan p = plan_layernorm(M, K, C, dtype, flags);
+  if (!ws || ws_bytes < p.bytes || (reinterpret_cast<uintptr_t>(ws) % 256) != 0)
+    return fail(SBP_ERR_WORKSPACE, "workspace missing, misaligned or smaller than %zu bytes", p.bytes);
+  return launch_backward_layernorm(p, dUk, Xk, gamma, eps, idx, inv, M, K, C, dtype, dgamma, dbeta, dX, ws, flags,
+                                   static_cast<hipStream_t>(stream));
+}
+
 size_t sbp_backward_dwconv_workspace(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int64_t K,
                                      int32_t dtype, uint32_t flags) {
   if (validate_dw(B, H, W, C, ks, ks / 2, K, dtype, flags) != SBP_OK) return 0;

@@ -64,6 +64,29 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
                                int32_t dtype, float* dW, float* db, void* dX, void* ws, uint32_t flags,
                                hipStream_t s);
 
+// inv[idx[j]] = j (no clearing needed: row m is kept iff 0 <= inv[m] < K and idx[inv[m]] == m), and +0 into
+// the rows of out[M][row_bytes] that are not kept (row_bytes a multiple of 2)
+void launch_build_inverse(const int32_t* idx, int64_t K, int32_t* inv, hipStream_t s);
+void launch_zero_dropped_rows(const int32_t* idx, const int32_t* inv, int64_t K, int64_t M, int64_t row_bytes,
+                              void* out, hipStream_t s);
+
+// ---- row-wise steps between the linear layers ------------------------------------------------
+int32_t launch_act_rows(const void* dH, const void* Z, int64_t n, int32_t dtype, int32_t act, bool backward, void* out,
+                        hipStream_t s);
+struct LnPlan {
+  bool   fast;          // one wavefront per row, the row in registers
+  int    nblocks;       // blocks = partial sums of dgamma / dbeta
+  size_t off_partial;   // fp32 [nblocks, 2, C]
+  size_t off_stats;     // fp32 [K, 2] (plain path)
+  size_t off_inv;       // int32 [M]
+  size_t bytes;
+};
+LnPlan plan_layernorm(int64_t M, int64_t K, int32_t C, int32_t dtype, uint32_t flags);
+int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* Xk, const float* gamma, float eps,
+                                  const int32_t* idx, const int32_t* inv, int64_t M, int64_t K, int32_t C,
+                                  int32_t dtype, float* dgamma, float* dbeta, void* dX, void* ws, uint32_t flags,
+                                  hipStream_t s);
+
 // ---- depthwise backward ------------------------------------------------------------------
 struct DwPlan {
   int    tiles_y, tiles_x; // spatial tiles of the dWd/db partial reduction

@@ -563,6 +563,33 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 
+// Writes +0 to the rows of out[M][row_bytes] that are not in idx (inv: inverse map, see mark_rows_kernel).
+void launch_build_inverse(const int32_t* idx, int64_t K, int32_t* inv, hipStream_t s) {
+  if (K > 0)
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, mark_rows_kernel, dim3((unsigned)ceil_div(K, NTHREADS)), dim3(NTHREADS), 0, s, idx,
+               (int)K, inv);
+}
+
+void launch_zero_dropped_rows(const int32_t* idx, const int32_t* inv, int64_t K, int64_t M, int64_t row_bytes,
+                              void* out, hipStream_t s) {
+  if (row_bytes % 16 == 0 && (uintptr_t)out % 16 == 0) {
+    const int ppr = (int)(row_bytes / 16);
+    unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * ppr, NTHREADS), 8192);
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, zero_dropped_rows_kernel, dim3(blocks), dim3(NTHREADS), 0, s, idx, inv, (int)K,
+               (long long)M, ppr, (uint4*)out);
+  } else if (row_bytes % 4 == 0 && (uintptr_t)out % 4 == 0) {
+    const int C = (int)(row_bytes / 4);
+    unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * C, NTHREADS), 8192);
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (zero_dropped_rows_elem_kernel<uint32_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
+               (int)K, (long long)M, C, (uint32_t*)out);
+  } else {
+    const int C = (int)(row_bytes / 2);
+    unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * C, NTHREADS), 8192);
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (zero_dropped_rows_elem_kernel<uint16_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
+               (int)K, (long long)M, C, (uint16_t*)out);
+  }
+}
+
 static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero, hipStream_t s) {
   // behind the ring: the row ids of a dW split (read one stage ahead) or the 256 output rows of a dX tile
   const size_t lds = (size_t)big::RING + std::max<size_t>((size_t)(p.rows_per_split + 2 * big::KB), big::BT) * sizeof(int);
@@ -608,8 +635,7 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
 
   const bool scatter = dX && !dx_compact;
   if (scatter && !inv) {   // no inverse map from the caller: build one (needs no clearing, see mark_rows_kernel)
-    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, mark_rows_kernel, dim3((unsigned)ceil_div(K, NTHREADS)), dim3(NTHREADS), 0, s, idx,
-               (int)K, inv_ws);
+    launch_build_inverse(idx, K, inv_ws, s);
     inv = inv_ws;
   }
 
@@ -661,23 +687,8 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     }
   }
 
-  if (scatter && !use_mfma) {   // the MFMA launch zero-fills by itself
-    const long long row_bytes = (long long)Cin * eb;
-    if (row_bytes % 16 == 0 && (uintptr_t)dX % 16 == 0) {
-      const int ppr = (int)(row_bytes / 16);
-      unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * ppr, NTHREADS), 8192);
-      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, zero_dropped_rows_kernel, dim3(blocks), dim3(NTHREADS), 0, s, idx, inv, (int)K,
-                         (long long)M, ppr, (uint4*)dX);
-    } else if (eb == 4) {
-      unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * Cin, NTHREADS), 8192);
-      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (zero_dropped_rows_elem_kernel<uint32_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
-                         (int)K, (long long)M, Cin, (uint32_t*)dX);
-    } else {
-      unsigned blocks = (unsigned)std::min<long long>(ceil_div(M * Cin, NTHREADS), 8192);
-      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (zero_dropped_rows_elem_kernel<uint16_t>), dim3(blocks), dim3(NTHREADS), 0, s, idx, inv,
-                         (int)K, (long long)M, Cin, (uint16_t*)dX);
-    }
-  }
+  if (scatter && !use_mfma)   // the MFMA launch zero-fills by itself
+    launch_zero_dropped_rows(idx, inv, K, M, (int64_t)Cin * eb, dX, s);
   return check_launch("backward_linear");
 }
 

@@ -1,0 +1,389 @@
+// Row-wise steps between the linear layers, on the kept rows only.  The paper's implementation (Alg.
+// alg:sbp_impl) wraps "an arbitrary operation f": kept rows pass through f with gradient, dropped rows
+// without, and with one keep-set shared by a stack of layers the split passes through the chain
+// unchanged (eq:backward_fc2_sbp_same_drop_loc).  For a row-wise f that is the ordinary backward of f on
+// the K kept rows, which therefore stay compact ([K, C]) from the output of one linear backward to the
+// input of the next; only the last step of a branch scatters to [M, C] and zero-fills.
+//   activation (exact GELU, z Phi(z)):  H_k = gelu(Z_k),  dZ_k = dH_k * (Phi(Z_k) + Z_k phi(Z_k))
+//   LayerNorm backward per kept row:    dx = (g - mean(g) - xhat mean(g xhat)) rstd,  g = dU gamma,
+//                                       dgamma = sum_k dU xhat,  dbeta = sum_k dU
+// All of it is streaming work bound by HBM: 16-byte accesses, fp32 arithmetic, rows in registers.
+#include <algorithm>
+
+#include "sbp_internal.h"
+
+namespace sbp {
+
+static constexpr int PW_THREADS = 256;
+
+__device__ __forceinline__ float pw_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float pw_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+typedef float pw_f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 pw_bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pw_pack(float lo, float hi) {   // round to nearest even (v_cvt_pk_bf16_f32)
+  const pw_f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pw_bf16x2));
+}
+
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+  const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752f));
+  return cdf + z * 0.39894228040143268f * expf(-0.5f * z * z);
+}
+
+// 8 values per thread and access.  T = uint16_t (bf16) or float.
+template <typename T> struct Vec8;
+template <> struct Vec8<uint16_t> {
+  static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) {
+    const uint4 w = *reinterpret_cast<const uint4*>(p);
+    v[0] = pw_lo(w.x); v[1] = pw_hi(w.x); v[2] = pw_lo(w.y); v[3] = pw_hi(w.y);
+    v[4] = pw_lo(w.z); v[5] = pw_hi(w.z); v[6] = pw_lo(w.w); v[7] = pw_hi(w.w);
+  }
+  static __device__ __forceinline__ void store(uint16_t* p, const float (&v)[8]) {
+    uint4 w;
+    w.x = pw_pack(v[0], v[1]); w.y = pw_pack(v[2], v[3]); w.z = pw_pack(v[4], v[5]); w.w = pw_pack(v[6], v[7]);
+    *reinterpret_cast<uint4*>(p) = w;
+  }
+  static __device__ __forceinline__ float load1(const uint16_t* p) { return __uint_as_float((uint32_t)*p << 16); }
+  static __device__ __forceinline__ void store1(uint16_t* p, float v) { *p = (uint16_t)(pw_pack(v, 0.f) & 0xffffu); }
+};
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
+    reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
+  }
+  static __device__ __forceinline__ float load1(const float* p) { return *p; }
+  static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
+};
+
+// ---- activation ------------------------------------------------------------------------------------
+// out = gelu(Z) (BACKWARD = false) or dH * gelu'(Z) (BACKWARD = true) over n values; groups of 8, two in flight.
+template <typename T, bool BACKWARD, bool VEC>
+__global__ void __launch_bounds__(PW_THREADS) act_rows_kernel(const T* dH, const T* __restrict__ Z,
+                                                               long long n, T* out) {   // out may be dH
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x;
+  if (VEC) {
+    const long long groups = n / 8;
+    for (; t < groups; t += stride) {
+      float z[8], g[8], o[8];
+      Vec8<T>::load(Z + 8 * t, z);
+      if (BACKWARD) Vec8<T>::load(dH + 8 * t, g);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = BACKWARD ? g[i] * gelu_grad_f(z[i]) : gelu_f(z[i]);
+      Vec8<T>::store(out + 8 * t, o);
+    }
+  } else {
+    for (; t < n; t += stride) {
+      const float z = Vec8<T>::load1(Z + t);
+      Vec8<T>::store1(out + t, BACKWARD ? Vec8<T>::load1(dH + t) * gelu_grad_f(z) : gelu_f(z));
+    }
+  }
+}
+
+template <typename T>
+static void launch_act_t(const T* dH, const T* Z, long long n, bool backward, T* out, hipStream_t s) {
+  const bool vec = n % 8 == 0 && (uintptr_t)Z % 16 == 0 && (uintptr_t)out % 16 == 0 && (!backward || (uintptr_t)dH % 16 == 0);
+  const long long work = vec ? n / 8 : n;
+  const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(work, PW_THREADS), 256 * 16));
+  if (vec) {
+    if (backward) SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, true, true>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
+    else SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, false, true>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
+  } else {
+    if (backward) SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, true, false>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
+    else SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, false, false>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
+  }
+}
+
+int32_t launch_act_rows(const void* dH, const void* Z, int64_t n, int32_t dtype, int32_t, bool backward, void* out,
+                        hipStream_t s) {
+  if (n == 0) return SBP_OK;
+  if (dtype == SBP_F32) launch_act_t<float>((const float*)dH, (const float*)Z, n, backward, (float*)out, s);
+  else launch_act_t<uint16_t>((const uint16_t*)dH, (const uint16_t*)Z, n, backward, (uint16_t*)out, s);
+  return check_launch(backward ? "act_backward_rows" : "act_forward_rows");
+}
+
+// ---- LayerNorm backward ----------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {   // all lanes get the sum; fixed butterfly order
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Fast path: C a multiple of 8, C <= 64 * 8 * NV.  A wavefront owns a row: lane l holds the 8-value groups
+// l, l + 64, ... of it in registers.  A block of 4 wavefronts walks the rows [r0, r1) of its slice and keeps
+// per-lane sums of dU * xhat and dU for its columns; the four wavefronts' sums are added in a fixed order
+// through LDS and written as the block's partial.
+template <typename T, int NV>
+__global__ void __launch_bounds__(PW_THREADS) ln_bwd_rows_kernel(const T* __restrict__ dU, const T* __restrict__ Xk,
+                                                                  const float* __restrict__ gamma, float eps,
+                                                                  const int32_t* __restrict__ idx_out, int K, int C,
+                                                                  int rows_per_block, T* __restrict__ dX,
+                                                                  float* __restrict__ partial) {
+  extern __shared__ float red[];                       // [4][C]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ngroups = C / 8;
+  const int r0 = blockIdx.x * rows_per_block, r1 = min(K, r0 + rows_per_block);
+  float gam[NV][8], sg[NV][8], sb[NV][8];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int grp = lane + 64 * v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      gam[v][i] = grp < ngroups ? gamma[8 * grp + i] : 0.f;
+      sg[v][i] = 0.f;
+      sb[v][i] = 0.f;
+    }
+  }
+  const float invC = 1.0f / (float)C;
+  for (int j = r0 + wave; j < r1; j += 4) {
+    float x[NV][8], du[NV][8];
+    float s1 = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int grp = lane + 64 * v;
+      if (grp < ngroups) {
+        Vec8<T>::load(Xk + (long long)j * C + 8 * grp, x[v]);
+        Vec8<T>::load(dU + (long long)j * C + 8 * grp, du[v]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { x[v][i] = 0.f; du[v][i] = 0.f; }
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s1 += x[v][i];
+    }
+    const float mean = wave_sum(s1) * invC;
+    float s2 = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const bool ok = lane + 64 * v < ngroups;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float d = ok ? x[v][i] - mean : 0.f;
+        x[v][i] = d;
+        s2 += d * d;
+      }
+    }
+    const float rstd = rsqrtf(wave_sum(s2) * invC + eps);
+    float m1 = 0.f, m2 = 0.f;
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float xh = x[v][i] * rstd;
+        const float g = du[v][i] * gam[v][i];
+        x[v][i] = xh;
+        m1 += g;
+        m2 += g * xh;
+        sg[v][i] += du[v][i] * xh;
+        sb[v][i] += du[v][i];
+      }
+    m1 = wave_sum(m1) * invC;
+    m2 = wave_sum(m2) * invC;
+    if (dX) {
+      const long long orow = idx_out ? (long long)idx_out[j] : (long long)j;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const int grp = lane + 64 * v;
+        if (grp < ngroups) {
+          float o[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) o[i] = (du[v][i] * gam[v][i] - m1 - x[v][i] * m2) * rstd;
+          Vec8<T>::store(dX + orow * C + 8 * grp, o);
+        }
+      }
+    }
+  }
+  if (!partial) return;
+  // the block's partial sums: wavefronts added in the order 0, 1, 2, 3; first dgamma's, then dbeta's
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int grp = lane + 64 * v;
+      if (grp < ngroups) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) red[wave * C + 8 * grp + i] = which == 0 ? sg[v][i] : sb[v][i];
+      }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < C; c += PW_THREADS)
+      partial[((long long)blockIdx.x * 2 + which) * C + c] = ((red[c] + red[C + c]) + red[2 * C + c]) + red[3 * C + c];
+    __syncthreads();
+  }
+}
+
+// Plain path, any C: one wavefront per row, the row read from memory in every pass; mean and rstd go to
+// stats[K][2] for the column kernel.
+template <typename T>
+__global__ void __launch_bounds__(64) ln_bwd_plain_rows_kernel(const T* __restrict__ dU, const T* __restrict__ Xk,
+                                                                const float* __restrict__ gamma, float eps,
+                                                                const int32_t* __restrict__ idx_out, int K, int C,
+                                                                T* __restrict__ dX, float* __restrict__ stats) {
+  const int lane = threadIdx.x;
+  for (int j = blockIdx.x; j < K; j += gridDim.x) {
+    const T* x = Xk + (long long)j * C;
+    const T* du = dU + (long long)j * C;
+    float s = 0.f;
+    for (int c = lane; c < C; c += 64) s += Vec8<T>::load1(x + c);
+    const float mean = wave_sum(s) / (float)C;
+    s = 0.f;
+    for (int c = lane; c < C; c += 64) { const float d = Vec8<T>::load1(x + c) - mean; s += d * d; }
+    const float rstd = rsqrtf(wave_sum(s) / (float)C + eps);
+    float m1 = 0.f, m2 = 0.f;
+    for (int c = lane; c < C; c += 64) {
+      const float g = Vec8<T>::load1(du + c) * gamma[c];
+      m1 += g;
+      m2 += g * (Vec8<T>::load1(x + c) - mean) * rstd;
+    }
+    m1 = wave_sum(m1) / (float)C;
+    m2 = wave_sum(m2) / (float)C;
+    if (lane == 0) { stats[2 * j] = mean; stats[2 * j + 1] = rstd; }
+    if (dX) {
+      T* o = dX + (idx_out ? (long long)idx_out[j] : (long long)j) * C;
+      for (int c = lane; c < C; c += 64) {
+        const float xh = (Vec8<T>::load1(x + c) - mean) * rstd;
+        Vec8<T>::store1(o + c, (Vec8<T>::load1(du + c) * gamma[c] - m1 - xh * m2) * rstd);
+      }
+    }
+  }
+}
+
+// plain path: partial[slice][0/1][c] over the rows of a slice, a thread per column
+template <typename T>
+__global__ void __launch_bounds__(PW_THREADS) ln_bwd_plain_cols_kernel(const T* __restrict__ dU, const T* __restrict__ Xk,
+                                                                        const float* __restrict__ stats, int K, int C,
+                                                                        int rows_per_block, float* __restrict__ partial) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= C) return;
+  const int r0 = blockIdx.y * rows_per_block, r1 = min(K, r0 + rows_per_block);
+  float sg = 0.f, sb = 0.f;
+  for (int j = r0; j < r1; ++j) {
+    const float du = Vec8<T>::load1(dU + (long long)j * C + c);
+    sg += du * (Vec8<T>::load1(Xk + (long long)j * C + c) - stats[2 * j]) * stats[2 * j + 1];
+    sb += du;
+  }
+  partial[((long long)blockIdx.y * 2 + 0) * C + c] = sg;
+  partial[((long long)blockIdx.y * 2 + 1) * C + c] = sb;
+}
+
+// dgamma / dbeta = sum over the blocks' partials, in block order
+__global__ void __launch_bounds__(PW_THREADS) ln_reduce_kernel(const float* __restrict__ partial, int nblocks, int C,
+                                                                float* __restrict__ dgamma, float* __restrict__ dbeta,
+                                                                int accumulate) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= 2 * C) return;
+  const int which = t / C, c = t - which * C;
+  float* out = which == 0 ? dgamma : dbeta;
+  if (!out) return;
+  float a = accumulate ? out[c] : 0.f;
+  for (int b0 = 0; b0 < nblocks; b0 += 8) {              // eight loads in flight, added in block order
+    float p[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) p[u] = b0 + u < nblocks ? partial[((long long)(b0 + u) * 2 + which) * C + c] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a += p[u];
+  }
+  out[c] = a;
+}
+
+__global__ void __launch_bounds__(PW_THREADS) ln_fill_zero_kernel(float* __restrict__ p, int n) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n) p[t] = 0.f;
+}
+
+static constexpr int kLnMaxBlocks = 1024;
+static constexpr int kLnMaxNV = 8;                       // fast path up to C = 64 * 8 * 8 = 4096
+
+LnPlan plan_layernorm(int64_t M, int64_t K, int32_t C, int32_t, uint32_t flags) {
+  LnPlan p{};
+  p.fast = C % 8 == 0 && C <= 64 * 8 * kLnMaxNV;
+  // a block walks at least 8 rows (two per wavefront); at most kLnMaxBlocks partial sums
+  p.nblocks = (int)std::max<int64_t>(1, std::min<int64_t>(kLnMaxBlocks, ceil_div(K, 8)));
+  size_t off = 0;
+  p.off_partial = off;
+  off += align_up((size_t)p.nblocks * 2 * C * sizeof(float), 256);
+  p.off_stats = off;
+  if (!p.fast) off += align_up((size_t)std::max<int64_t>(K, 1) * 2 * sizeof(float), 256);
+  p.off_inv = off;
+  if (!(flags & SBP_FLAG_DX_COMPACT)) off += align_up((size_t)M * sizeof(int32_t), 256);
+  p.bytes = off;
+  return p;
+}
+
+template <typename T, int NV>
+static void launch_ln_fast(const LnPlan& p, const T* dU, const T* Xk, const float* gamma, float eps,
+                           const int32_t* idx_out, int K, int C, int rpb, T* dX, float* partial, hipStream_t s) {
+  const size_t lds = (size_t)4 * C * sizeof(float);   // at most 64 KB (C <= 4096)
+  SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_rows_kernel<T, NV>), dim3(p.nblocks), dim3(PW_THREADS), lds, s, dU, Xk, gamma, eps,
+             idx_out, K, C, rpb, dX, partial);
+}
+
+template <typename T>
+static void launch_ln_t(const LnPlan& p, const T* dU, const T* Xk, const float* gamma, float eps, const int32_t* idx_out,
+                        int K, int C, T* dX, float* partial, float* stats, hipStream_t s) {
+  const int rpb = (int)ceil_div(K, p.nblocks);
+  const bool aligned = (uintptr_t)dU % 16 == 0 && (uintptr_t)Xk % 16 == 0 && (uintptr_t)dX % 16 == 0;
+  if (p.fast && aligned) {
+    const int nv = (int)ceil_div(C / 8, 64);
+    switch (nv) {
+      case 1: launch_ln_fast<T, 1>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
+      case 2: launch_ln_fast<T, 2>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
+      case 3: case 4: launch_ln_fast<T, 4>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
+      default: launch_ln_fast<T, 8>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
+    }
+  } else {
+    const unsigned rows_grid = (unsigned)std::min<int64_t>(K, 8192);
+    SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_plain_rows_kernel<T>), dim3(rows_grid), dim3(64), 0, s, dU, Xk, gamma, eps, idx_out, K,
+               C, dX, stats);
+    if (partial)
+      SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_plain_cols_kernel<T>), dim3((unsigned)ceil_div(C, PW_THREADS), p.nblocks),
+                 dim3(PW_THREADS), 0, s, dU, Xk, stats, K, C, rpb, partial);
+  }
+}
+
+int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* Xk, const float* gamma, float eps,
+                                  const int32_t* idx, const int32_t* inv_in, int64_t M, int64_t K, int32_t C,
+                                  int32_t dtype, float* dgamma, float* dbeta, void* dX, void* ws, uint32_t flags,
+                                  hipStream_t s) {
+  const int eb = dtype == SBP_F32 ? 4 : 2;
+  const bool dx_compact = flags & SBP_FLAG_DX_COMPACT;
+  const int accumulate = (flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
+  float* partial = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_partial);
+  float* stats = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_stats);
+  int32_t* inv_ws = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.off_inv);
+  const bool want_params = dgamma || dbeta;
+
+  if (K == 0) {   // nothing kept: gradients are zero
+    if (!accumulate && want_params) {
+      if (dgamma) SBP_LAUNCH(SBP_PROF_OTHER, s, ln_fill_zero_kernel, dim3((unsigned)ceil_div(C, PW_THREADS)), dim3(PW_THREADS), 0, s, dgamma, C);
+      if (dbeta) SBP_LAUNCH(SBP_PROF_OTHER, s, ln_fill_zero_kernel, dim3((unsigned)ceil_div(C, PW_THREADS)), dim3(PW_THREADS), 0, s, dbeta, C);
+    }
+  } else {
+    const int32_t* idx_out = dx_compact ? nullptr : idx;
+    if (dtype == SBP_F32)
+      launch_ln_t<float>(p, (const float*)dU, (const float*)Xk, gamma, eps, idx_out, (int)K, C, (float*)dX,
+                         want_params ? partial : nullptr, stats, s);
+    else
+      launch_ln_t<uint16_t>(p, (const uint16_t*)dU, (const uint16_t*)Xk, gamma, eps, idx_out, (int)K, C, (uint16_t*)dX,
+                            want_params ? partial : nullptr, stats, s);
+    if (want_params)
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, ln_reduce_kernel, dim3((unsigned)ceil_div(2 * C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+                 partial, p.nblocks, C, dgamma, dbeta, accumulate);
+  }
+  if (dX && !dx_compact) {
+    const int32_t* inv = inv_in;
+    if (!inv) {
+      launch_build_inverse(idx, K, inv_ws, s);
+      inv = inv_ws;
+    }
+    launch_zero_dropped_rows(idx, inv, K, M, (int64_t)C * eb, dX, s);
+  }
+  return check_launch("backward_layernorm");
+}
+
+}  // namespace sbp

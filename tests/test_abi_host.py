@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 13
+    assert len(names) == 17
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -149,6 +149,32 @@ def test_backward_linear_engine_report_and_plan():
         sbp.backward_linear_engine(100, 500, 64, 128, sbp.BF16)
     # rows of dY that byte offsets of 32 bits cannot reach: the general engine takes the shape
     assert sbp.backward_linear_engine(1 << 20, 1 << 19, 4096, 4096, sbp.BF16)[0] == "mfma"
+
+
+def test_rowwise_steps_argument_errors():
+    L = _lib.lib()
+    p = 4096
+    assert L.sbp_act_forward_rows(p, 10, 8, 7, 0, p, None) == -4
+    assert L.sbp_act_forward_rows(p, 10, 8, 1, 3, p, None) == -8
+    assert L.sbp_act_forward_rows(None, 10, 8, 1, 0, p, None) == -1
+    assert L.sbp_act_forward_rows(p, -1, 8, 1, 0, p, None) == -2
+    assert L.sbp_act_forward_rows(None, 0, 8, 1, 0, None, None) == 0            # nothing to do
+    assert L.sbp_act_backward_rows(p, None, 10, 8, 1, 0, p, None) == -1
+    assert L.sbp_act_backward_rows(p, p, 10, 0, 1, 0, p, None) == -2
+    ws = L.sbp_backward_layernorm_workspace(100, 50, 64, 1, 0)
+    assert ws > 0 and ws % 256 == 0
+    assert L.sbp_backward_layernorm_workspace(100, 50, 64, 1, 2) < ws            # compact dX: no inverse map
+    assert L.sbp_backward_layernorm_workspace(100, 500, 64, 1, 0) == 0
+    assert L.sbp_backward_layernorm_workspace(100, 50, 64, 1, 1) == 0            # dU is always compact: no such flag
+
+    def ln(dU=p, Xk=p, gamma=p, eps=1e-5, idx=p, M=100, K=50, C=64, dtype=1, dg=p, db=p, dX=p, w=p * 4, wb=ws, flags=0):
+        return L.sbp_backward_layernorm(dU, Xk, gamma, eps, idx, None, M, K, C, dtype, dg, db, dX, w, wb, flags, None)
+
+    assert ln(dU=None) == -1 and ln(Xk=None) == -1 and ln(gamma=None) == -1 and ln(idx=None) == -1
+    assert ln(dtype=9) == -4 and ln(K=101) == -2 and ln(C=0) == -2 and ln(flags=1) == -8
+    assert ln(eps=-1.0) == -2
+    assert ln(w=None) == -6 and ln(wb=ws - 1) == -6 and ln(w=p * 4 + 16) == -6
+    assert ln(dg=None, db=None, dX=None) == 0
 
 
 def test_backward_dwconv_argument_errors():
