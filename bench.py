@@ -257,6 +257,82 @@ def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3):
     return out
 
 
+def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5):
+    """Backward of one ViT-Base MLP branch (LayerNorm -> fc1 -> GELU -> fc2, one keep-set) on compact rows with a
+    single final scatter, against the same kernels scattering to full size after every linear layer; plus the
+    row-wise kernels on their own against the HBM roofline."""
+    wl = si.WORKLOADS["vit_base"]
+    M = wl.B * (wl.P + wl.H * wl.W)
+    C, Hd = 768, 3072
+    k = sbp.k_from_ratio(r)
+    idx, inv = sbp.sample_indices(wl.B, wl.P, wl.H, wl.W, k, 0, 1, want_inv=True)
+    K = idx.numel()
+    nset = 4                                              # rotate buffer sets: 4 x ~150 MB defeats the last-level cache
+    sets = []
+    for i in range(nset):
+        t = lambda shape, std, seed: si.normal(shape, std, 300 + 10 * i + seed, "bf16").cuda()
+        sets.append(dict(Xk=t((K, C), 1.0, 0), Uk=t((K, C), 1.0, 1), Zk=t((K, Hd), 1.5, 2), dY=t((M, C), 1.0, 3),
+                         W1=t((Hd, C), C ** -0.5, 4), W2=t((C, Hd), Hd ** -0.5, 5),
+                         gamma=torch.ones(C, device="cuda"), Hk=torch.empty((K, Hd), dtype=torch.bfloat16, device="cuda"),
+                         dHk=torch.empty((K, Hd), dtype=torch.bfloat16, device="cuda"),
+                         dHf=torch.empty((M, Hd), dtype=torch.bfloat16, device="cuda"),
+                         dUk=torch.empty((K, C), dtype=torch.bfloat16, device="cuda"),
+                         dUf=torch.empty((M, C), dtype=torch.bfloat16, device="cuda"),
+                         dX=torch.empty((M, C), dtype=torch.bfloat16, device="cuda"),
+                         dW1=torch.empty((Hd, C), device="cuda"), db1=torch.empty(Hd, device="cuda"),
+                         dW2=torch.empty((C, Hd), device="cuda"), db2=torch.empty(C, device="cuda"),
+                         dg=torch.empty(C, device="cuda"), dbt=torch.empty(C, device="cuda")))
+    ws_bytes = max(sbp.backward_linear_workspace(M, K, Hd, C, sbp.BF16), sbp.backward_linear_workspace(M, K, C, Hd, sbp.BF16),
+                   sbp.backward_layernorm_workspace(M, K, C, sbp.BF16))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    CF = sbp.FLAG_DX_COMPACT
+    CB = sbp.FLAG_DY_COMPACT | sbp.FLAG_DX_COMPACT
+
+    def compact(b):
+        sbp.act_forward_rows(b["Zk"], out=b["Hk"])
+        sbp.backward_linear(b["dY"], idx, b["Hk"], b["W2"], M=M, flags=CF, inv=inv, dW=b["dW2"], db=b["db2"], dX=b["dHk"], workspace=ws)
+        sbp.act_backward_rows(b["dHk"], b["Zk"], out=b["dHk"])
+        sbp.backward_linear(b["dHk"], idx, b["Uk"], b["W1"], M=M, flags=CB, inv=inv, dW=b["dW1"], db=b["db1"], dX=b["dUk"], workspace=ws)
+        sbp.backward_layernorm(b["dUk"], b["Xk"], b["gamma"], 1e-6, idx, M, inv=inv, dgamma=b["dg"], dbeta=b["dbt"], dX=b["dX"], workspace=ws)
+
+    def scattered(b):
+        sbp.act_forward_rows(b["Zk"], out=b["Hk"])
+        sbp.backward_linear(b["dY"], idx, b["Hk"], b["W2"], M=M, inv=inv, dW=b["dW2"], db=b["db2"], dX=b["dHf"], workspace=ws)
+        sbp.forward_cache(b["dHf"], idx, out=b["dHk"])                   # the row-wise step gathers its input again
+        sbp.act_backward_rows(b["dHk"], b["Zk"], out=b["dHk"])
+        sbp.backward_linear(b["dHk"], idx, b["Uk"], b["W1"], M=M, flags=sbp.FLAG_DY_COMPACT, inv=inv, dW=b["dW1"], db=b["db1"], dX=b["dUf"], workspace=ws)
+        sbp.forward_cache(b["dUf"], idx, out=b["dUk"])
+        sbp.backward_layernorm(b["dUk"], b["Xk"], b["gamma"], 1e-6, idx, M, inv=inv, dgamma=b["dg"], dbeta=b["dbt"], dX=b["dX"], workspace=ws)
+
+    def timed(fn, n=iters):
+        for i in range(warmup):
+            fn(sets[i % nset])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(sets[i % nset])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    flops = 2 * 4.0 * K * C * Hd
+    ms_c, ms_s = timed(compact), timed(scattered)
+    kern = {}
+    for name, fn, nbytes in (
+            ("act_forward_rows", lambda b: sbp.act_forward_rows(b["Zk"], out=b["Hk"]), 2 * K * Hd * 2),
+            ("act_backward_rows", lambda b: sbp.act_backward_rows(b["dHk"], b["Zk"], out=b["dHk"]), 3 * K * Hd * 2),
+            ("backward_layernorm", lambda b: sbp.backward_layernorm(b["dUk"], b["Xk"], b["gamma"], 1e-6, idx, M, inv=inv,
+                                                                    dgamma=b["dg"], dbeta=b["dbt"], dX=b["dX"], workspace=ws),
+             (2 * K * C + M * C) * 2 + 3 * C * 4 + 8 * K)):
+        ms = timed(fn, 50)
+        kern[name] = {"us": round(ms * 1e3, 2), "algorithmic_mb": round(nbytes / 1e6, 2),
+                      "gbs": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / 8000.0, 4)}
+    return {"workload": f"vit_base MLP branch backward (LayerNorm, fc1 768->3072, GELU, fc2 3072->768), K={K} of M={M}",
+            "compact_ms": round(ms_c, 4), "scatter_every_layer_ms": round(ms_s, 4), "speedup": round(ms_s / ms_c, 3),
+            "tflops_compact": round(flops / ms_c / 1e9, 1), "row_wise_kernels": kern}
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -347,6 +423,7 @@ def main():
             if name != wl.name:
                 extras.append(measure_extra(name, args.ratio, torch, sbp, si))
         result["other_workloads"] = extras
+        result["mlp_branch_compact"] = measure_mlp_branch(torch, sbp, si, args.ratio)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.ratio, args.cpu_seconds, si)
     print(json.dumps(result))

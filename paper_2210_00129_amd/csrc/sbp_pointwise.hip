@@ -69,6 +69,20 @@ __global__ void __launch_bounds__(PW_THREADS) act_rows_kernel(const T* dH, const
   long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x;
   if (VEC) {
     const long long groups = n / 8;
+    for (; t + stride < groups; t += 2 * stride) {       // two groups in flight per thread
+      float z[2][8], g[2][8], o[8];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        Vec8<T>::load(Z + 8 * (t + u * stride), z[u]);
+        if (BACKWARD) Vec8<T>::load(dH + 8 * (t + u * stride), g[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = BACKWARD ? g[u][i] * gelu_grad_f(z[u][i]) : gelu_f(z[u][i]);
+        Vec8<T>::store(out + 8 * (t + u * stride), o);
+      }
+    }
     for (; t < groups; t += stride) {
       float z[8], g[8], o[8];
       Vec8<T>::load(Z + 8 * t, z);
@@ -89,7 +103,7 @@ template <typename T>
 static void launch_act_t(const T* dH, const T* Z, long long n, bool backward, T* out, hipStream_t s) {
   const bool vec = n % 8 == 0 && (uintptr_t)Z % 16 == 0 && (uintptr_t)out % 16 == 0 && (!backward || (uintptr_t)dH % 16 == 0);
   const long long work = vec ? n / 8 : n;
-  const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(work, PW_THREADS), 256 * 16));
+  const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(work, 2 * PW_THREADS), 256 * 16));
   if (vec) {
     if (backward) SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, true, true>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
     else SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, false, true>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
@@ -271,24 +285,30 @@ __global__ void __launch_bounds__(PW_THREADS) ln_bwd_plain_cols_kernel(const T* 
   partial[((long long)blockIdx.y * 2 + 1) * C + c] = sb;
 }
 
-// dgamma / dbeta = sum over the blocks' partials, in block order
+// dgamma / dbeta = sum over the blocks' partials.  Eight lanes per output: lane q adds the partials
+// q, q + 8, ... in order (four loads in flight), then the eight sums are added in lane order.
 __global__ void __launch_bounds__(PW_THREADS) ln_reduce_kernel(const float* __restrict__ partial, int nblocks, int C,
                                                                 float* __restrict__ dgamma, float* __restrict__ dbeta,
                                                                 int accumulate) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= 2 * C) return;
-  const int which = t / C, c = t - which * C;
-  float* out = which == 0 ? dgamma : dbeta;
-  if (!out) return;
-  float a = accumulate ? out[c] : 0.f;
-  for (int b0 = 0; b0 < nblocks; b0 += 8) {              // eight loads in flight, added in block order
-    float p[8];
+  const int o = t >> 3, q = t & 7;
+  const bool live = o < 2 * C;
+  const int which = live ? o / C : 0, c = live ? o - which * C : 0;
+  float a = 0.f;
+  if (live) {
+    for (int b0 = q; b0 < nblocks; b0 += 32) {
+      float p[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) p[u] = b0 + u < nblocks ? partial[((long long)(b0 + u) * 2 + which) * C + c] : 0.f;
+      for (int u = 0; u < 4; ++u) p[u] = b0 + 8 * u < nblocks ? partial[((long long)(b0 + 8 * u) * 2 + which) * C + c] : 0.f;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) a += p[u];
+      for (int u = 0; u < 4; ++u) a += p[u];
+    }
   }
-  out[c] = a;
+  float tot = 0.f;
+#pragma unroll
+  for (int l = 0; l < 8; ++l) tot += __shfl(a, (threadIdx.x & 56) + l, 64);     // every lane takes part
+  float* out = which == 0 ? dgamma : dbeta;
+  if (live && q == 0 && out) out[c] = (accumulate ? out[c] : 0.f) + tot;
 }
 
 __global__ void __launch_bounds__(PW_THREADS) ln_fill_zero_kernel(float* __restrict__ p, int n) {
@@ -296,14 +316,14 @@ __global__ void __launch_bounds__(PW_THREADS) ln_fill_zero_kernel(float* __restr
   if (t < n) p[t] = 0.f;
 }
 
-static constexpr int kLnMaxBlocks = 1024;
+static constexpr int kLnMaxBlocks = 512;
 static constexpr int kLnMaxNV = 8;                       // fast path up to C = 64 * 8 * 8 = 4096
 
 LnPlan plan_layernorm(int64_t M, int64_t K, int32_t C, int32_t, uint32_t flags) {
   LnPlan p{};
   p.fast = C % 8 == 0 && C <= 64 * 8 * kLnMaxNV;
-  // a block walks at least 8 rows (two per wavefront); at most kLnMaxBlocks partial sums
-  p.nblocks = (int)std::max<int64_t>(1, std::min<int64_t>(kLnMaxBlocks, ceil_div(K, 8)));
+  // a block walks at least 16 rows (four per wavefront); at most kLnMaxBlocks partial sums
+  p.nblocks = (int)std::max<int64_t>(1, std::min<int64_t>(kLnMaxBlocks, ceil_div(K, 16)));
   size_t off = 0;
   p.off_partial = off;
   off += align_up((size_t)p.nblocks * 2 * C * sizeof(float), 256);
@@ -372,7 +392,7 @@ int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* X
       launch_ln_t<uint16_t>(p, (const uint16_t*)dU, (const uint16_t*)Xk, gamma, eps, idx_out, (int)K, C, (uint16_t*)dX,
                             want_params ? partial : nullptr, stats, s);
     if (want_params)
-      SBP_LAUNCH(SBP_PROF_REDUCE, s, ln_reduce_kernel, dim3((unsigned)ceil_div(2 * C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, ln_reduce_kernel, dim3((unsigned)ceil_div(16 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
                  partial, p.nblocks, C, dgamma, dbeta, accumulate);
   }
   if (dX && !dx_compact) {
