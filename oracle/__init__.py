@@ -21,4 +21,6 @@ from .sbp_oracle import (  # noqa: F401
     act_backward_rows,
     layernorm_rows,
     backward_layernorm,
+    forward_cache_patches,
+    backward_downsample,
 )

@@ -40,6 +40,12 @@ What follows the paper and what is this repository's own reading:
   row-wise f (GELU, LayerNorm) that is the ordinary backward of f on the kept
   rows, zero on the dropped rows, parameter gradients summed over the kept
   rows only.  GELU is the exact form x Phi(x) used by ViT and ConvNeXt.
+* ``backward_downsample`` / ``forward_cache_patches``: a convolution whose stride
+  is at least its kernel size (the p x p, stride p down-sampling layers of
+  ConvNeXt).  The paper's section "Calculation of Convolutional Layers" notes
+  that for s >= k the neighbour effects vanish and the layer behaves like a
+  point-wise one: every kept output position owns its own p x p patch of inputs.
+  The oracle writes the convolution backward out position by position.
 """
 from __future__ import annotations
 
@@ -263,3 +269,47 @@ def backward_layernorm(dU_k, X_k, gamma, eps, idx, M):
         dgamma += dU_k[j] * xhat
         dbeta += dU_k[j]
     return dX, dgamma, dbeta
+
+
+# ---------------------------------------------------------------------------------------------
+# Down-sampling convolution, kernel p x p, stride p (section "Calculation of Convolutional Layers",
+# the case s >= k): Y[b, yo, xo, o] = sum_{dy, dx, c} X[b, p yo + dy, p xo + dx, c] Wc[o, dy, dx, c] + bias[o].
+# ---------------------------------------------------------------------------------------------
+def forward_cache_patches(X, idx, p):
+    """Rows [K, p*p*C]: the p x p input patch under every kept output position, (dy, dx, c) order."""
+    X = np.asarray(X)
+    B, H, W, C = X.shape
+    Ho, Wo = H // p, W // p
+    out = np.zeros((len(idx), p * p * C), dtype=X.dtype)
+    for j, f in enumerate(np.asarray(idx, dtype=np.int64)):
+        b, rem = divmod(int(f), Ho * Wo)
+        yo, xo = divmod(rem, Wo)
+        out[j] = X[b, p * yo:p * yo + p, p * xo:p * xo + p, :].reshape(-1)
+    return out
+
+
+def backward_downsample(dY, idx, X, Wc, p):
+    """Backward of the p x p, stride p convolution with dY zero off the kept output positions.
+
+    dY [B, Ho, Wo, Cout]; idx: kept flat output positions b*Ho*Wo + yo*Wo + xo; X [B, H, W, C] with
+    H = p Ho, W = p Wo; Wc [Cout, p, p, C].  Returns dWc [Cout, p, p, C], db [Cout], dX [B, H, W, C]
+    (zero outside the patches of the kept outputs, exact inside).
+    """
+    dY = np.asarray(dY, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    Wc = np.asarray(Wc, dtype=np.float64)
+    B, Ho, Wo, Cout = dY.shape
+    dWc = np.zeros_like(Wc)
+    db = np.zeros(Cout, dtype=np.float64)
+    dX = np.zeros_like(X)
+    for f in np.asarray(idx, dtype=np.int64):
+        b, rem = divmod(int(f), Ho * Wo)
+        yo, xo = divmod(rem, Wo)
+        g = dY[b, yo, xo]                                   # [Cout]
+        db += g
+        for dy in range(p):
+            for dx in range(p):
+                x = X[b, p * yo + dy, p * xo + dx]          # [C]
+                dWc[:, dy, dx, :] += np.outer(g, x)
+                dX[b, p * yo + dy, p * xo + dx] = g @ Wc[:, dy, dx, :]
+    return dWc, db, dX
