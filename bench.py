@@ -333,6 +333,58 @@ def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5):
             "tflops_compact": round(flops / ms_c / 1e9, 1), "row_wise_kernels": kern}
 
 
+def measure_downsample(torch, sbp, si, r, iters=20, warmup=5):
+    """Backward of a ConvNeXt down-sampling layer (2 x 2, stride 2 convolution, 128 -> 256 channels on a
+    2 x 200 x 336 detection map) on kept output positions: patch gather, linear backward on patch rows, patch scatter."""
+    B, H, W, C, Cout, p = 2, 200, 336, 128, 256, 2
+    Ho, Wo = H // p, W // p
+    Mo = B * Ho * Wo
+    k = sbp.k_from_ratio(r)
+    idx, inv = sbp.sample_indices(B, 0, Ho, Wo, k, 0, 1, want_inv=True)
+    K = idx.numel()
+    nset = 6
+    sets = []
+    for i in range(nset):
+        t = lambda shape, std, seed: si.normal(shape, std, 500 + 10 * i + seed, "bf16").cuda()
+        sets.append(dict(X=t((B, H, W, C), 1.0, 0), dY=t((Mo, Cout), 1.0, 1), Wc=t((Cout, p * p * C), (p * p * C) ** -0.5, 2),
+                         Xk=torch.empty((K, p * p * C), dtype=torch.bfloat16, device="cuda"),
+                         dXp=torch.empty((K, p * p * C), dtype=torch.bfloat16, device="cuda"),
+                         dX=torch.empty((B, H, W, C), dtype=torch.bfloat16, device="cuda"),
+                         dW=torch.empty((Cout, p * p * C), device="cuda"), db=torch.empty(Cout, device="cuda")))
+    ws = torch.empty(sbp.backward_linear_workspace(Mo, K, p * p * C, Cout, sbp.BF16, sbp.FLAG_DX_COMPACT), dtype=torch.uint8, device="cuda")
+
+    def gather(b): sbp.forward_cache_patches(b["X"], idx, p, out=b["Xk"])
+    def linear(b): sbp.backward_linear(b["dY"], idx, b["Xk"], b["Wc"], M=Mo, flags=sbp.FLAG_DX_COMPACT, inv=inv, dW=b["dW"], db=b["db"], dX=b["dXp"], workspace=ws)
+    def scatter(b): sbp.scatter_patches(b["dXp"], idx, (B, H, W, C), p, inv=inv, out=b["dX"])
+    def layer(b): gather(b); linear(b); scatter(b)
+
+    def timed(fn, n=iters):
+        for i in range(warmup):
+            fn(sets[i % nset])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(sets[i % nset])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    flops = 4.0 * K * p * p * C * Cout
+    ms = timed(layer)
+    out = {"workload": f"convnext down-sampling layer 2x2/2, {C}->{Cout}, map {B}x{H}x{W}, K={K} of {Mo} output positions",
+           "ms": round(ms, 4), "tflops": round(flops / ms / 1e9, 1), "kernels": {}}
+    for name, fn, nbytes in (("forward_cache_patches", gather, 2 * K * p * p * C * 2 + 4 * K),
+                             ("backward_linear(patch rows)", linear, None),
+                             ("scatter_patches", scatter, (K * p * p * C + B * H * W * C) * 2 + 4 * Mo + 4 * K)):
+        m = timed(fn, 50)
+        out["kernels"][name] = {"us": round(m * 1e3, 2)}
+        if nbytes:
+            out["kernels"][name].update({"algorithmic_mb": round(nbytes / 1e6, 2), "gbs": round(nbytes / m / 1e6, 1),
+                                         "frac_of_hbm_peak": round(nbytes / m / 1e6 / 8000.0, 4)})
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -424,6 +476,7 @@ def main():
                 extras.append(measure_extra(name, args.ratio, torch, sbp, si))
         result["other_workloads"] = extras
         result["mlp_branch_compact"] = measure_mlp_branch(torch, sbp, si, args.ratio)
+        result["downsample_layer"] = measure_downsample(torch, sbp, si, args.ratio)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.ratio, args.cpu_seconds, si)
     print(json.dumps(result))

@@ -184,6 +184,28 @@ int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* i
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
+ * Down-sampling layers: a convolution with kernel p x p and stride p (paper, section "Calculation of
+ * Convolutional Layers": for a stride not smaller than the kernel the neighbour effects vanish and the
+ * layer behaves like a point-wise one; ConvNeXt applies SBP to its 2 x 2, stride 2 down-sampling
+ * layers).  idx holds kept OUTPUT positions b*Ho*Wo + yo*Wo + xo (Ho = H / p, Wo = W / p; a sampler
+ * draw on the Ho x Wo grid).  The layer then is sbp_backward_linear on patch rows:
+ *   sbp_forward_cache_patches   X_k[j, (dy*p + dx)*C + c] = X[b, p*yo + dy, p*xo + dx, c]   [K, p*p*C]
+ *   sbp_backward_linear         with M = B*Ho*Wo, Cin = p*p*C, W viewed as [Cout, p*p*C] (= [Cout, p, p, C]),
+ *                               SBP_FLAG_DX_COMPACT: dW, db and the compact gradient rows dXp_k [K, p*p*C]
+ *   sbp_scatter_patches         dX[b, y, x, :] = the piece of dXp_k that belongs to input pixel (y, x) if its
+ *                               output position is kept, +0.0 otherwise                          [B, H, W, C]
+ *   X, dX   device, [B, H, W, C] of `dtype`, H and W multiples of p, 1 <= p <= 8
+ *   inv     device, in, [B*Ho*Wo] inverse of idx (as written by sbp_sample_indices) or NULL: then it is built
+ *           in the workspace (sbp_scatter_patches_workspace bytes, 256-byte aligned; may be NULL if inv is given)
+ */
+int32_t sbp_forward_cache_patches(const void* X, const int32_t* idx, int32_t B, int32_t H, int32_t W,
+                                  int32_t C, int32_t p, int64_t K, int32_t dtype, void* X_k, void* stream);
+size_t sbp_scatter_patches_workspace(int32_t B, int32_t H, int32_t W, int32_t p);
+int32_t sbp_scatter_patches(const void* dXp_k, const int32_t* idx, const int32_t* inv, int32_t B, int32_t H,
+                            int32_t W, int32_t C, int32_t p, int64_t K, int32_t dtype, void* dX,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Row-wise steps between the linear layers, on compact rows (paper, Alg. alg:sbp_impl: "an arbitrary
  * operation f" sees the kept rows with gradient and the dropped rows without; with one keep-set shared
  * by a stack of layers the kept / dropped split passes through the chain unchanged,

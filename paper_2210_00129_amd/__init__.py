@@ -134,6 +134,32 @@ def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), d
     return dW, db, dX
 
 
+def forward_cache_patches(X, idx, p, out=None):
+    """Rows [K, p*p*C]: the p x p input patch of X [B, H, W, C] under every kept output position."""
+    B, H, W, C = X.shape
+    K = idx.numel()
+    Xk = out if out is not None else torch.empty((K, p * p * C), dtype=X.dtype, device=X.device)
+    _lib.check(_lib.lib().sbp_forward_cache_patches(_dev(X, "X"), _dev(idx, "idx"), B, H, W, C, p, K, _dtype_code(X),
+                                                    _dev(Xk, "X_k"), _stream(X.device)))
+    return Xk
+
+
+def scatter_patches(dXp_k, idx, shape, p, inv=None, out=None):
+    """dX [B, H, W, C] from the compact gradient rows [K, p*p*C] of a down-sampling layer (zeros elsewhere)."""
+    B, H, W, C = shape
+    K = idx.numel()
+    dX = out if out is not None else torch.empty((B, H, W, C), dtype=dXp_k.dtype, device=dXp_k.device)
+    ws = None
+    nbytes = 0
+    if inv is None:
+        nbytes = int(_lib.lib().sbp_scatter_patches_workspace(B, H, W, p))
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dXp_k.device)
+    _lib.check(_lib.lib().sbp_scatter_patches(_dev(dXp_k, "dXp_k"), _dev(idx, "idx"), _dev(inv, "inv"), B, H, W, C, p, K,
+                                              _dtype_code(dXp_k), _dev(dX, "dX"), _dev(ws, "workspace"),
+                                              ws.numel() if ws is not None else 0, _stream(dXp_k.device)))
+    return dX
+
+
 ACT_GELU = 0
 
 

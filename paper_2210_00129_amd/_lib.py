@@ -30,6 +30,9 @@ PROTOTYPES = {
     "sbp_sample_indices": (c_i32, [ctypes.POINTER(SampleDesc), c_vp, c_i64, c_vp, c_vp]),
     "sbp_forward_cache": (c_i32, [c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_vp, c_vp]),
     "sbp_backward_linear_workspace": (c_sz, [c_i64, c_i64, c_i32, c_i32, c_i32, c_u32]),
+    "sbp_forward_cache_patches": (c_i32, [c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i64, c_i32, c_vp, c_vp]),
+    "sbp_scatter_patches_workspace": (c_sz, [c_i32, c_i32, c_i32, c_i32]),
+    "sbp_scatter_patches": (c_i32, [c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i64, c_i32, c_vp, c_vp, c_sz, c_vp]),
     "sbp_act_forward_rows": (c_i32, [c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp]),
     "sbp_act_backward_rows": (c_i32, [c_vp, c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp]),
     "sbp_backward_layernorm_workspace": (c_sz, [c_i64, c_i64, c_i32, c_i32, c_u32]),

@@ -180,6 +180,49 @@ static int32_t validate_dw(int32_t B, int32_t H, int32_t W, int32_t C, int32_t k
   return SBP_OK;
 }
 
+static int32_t validate_patches(int32_t B, int32_t H, int32_t W, int32_t C, int32_t p, int64_t K, int32_t dtype) {
+  if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (p < 1 || p > 8) return fail(SBP_ERR_SHAPE, "patch size %d not in [1, 8]", p);
+  if (B < 1 || H < 1 || W < 1 || C < 1 || H % p || W % p)
+    return fail(SBP_ERR_SHAPE, "bad shape B=%d H=%d W=%d C=%d for patch size %d", B, H, W, C, p);
+  if ((int64_t)B * H * W > INT32_MAX) return fail(SBP_ERR_SHAPE, "B*H*W too large");
+  const int64_t Mo = (int64_t)B * (H / p) * (W / p);
+  if (K < 0 || K > Mo) return fail(SBP_ERR_SHAPE, "need 0 <= K <= B*Ho*Wo, got K=%lld", (long long)K);
+  return SBP_OK;
+}
+
+int32_t sbp_forward_cache_patches(const void* X, const int32_t* idx, int32_t B, int32_t H, int32_t W, int32_t C, int32_t p,
+                                  int64_t K, int32_t dtype, void* Xk, void* stream) {
+  int32_t st = validate_patches(B, H, W, C, p, K, dtype);
+  if (st != SBP_OK) return st;
+  if (K == 0) return SBP_OK;
+  if (!X || !idx || !Xk) return fail(SBP_ERR_NULL, "X, idx or X_k is NULL");
+  return launch_patches(false, X, idx, nullptr, B, H, W, C, p, K, elem_bytes(dtype), Xk, static_cast<hipStream_t>(stream));
+}
+
+size_t sbp_scatter_patches_workspace(int32_t B, int32_t H, int32_t W, int32_t p) {
+  if (p < 1 || p > 8 || B < 1 || H < 1 || W < 1 || H % p || W % p) return 0;
+  return align_up((size_t)B * (H / p) * (W / p) * sizeof(int32_t), 256);
+}
+
+int32_t sbp_scatter_patches(const void* dXp, const int32_t* idx, const int32_t* inv, int32_t B, int32_t H, int32_t W,
+                            int32_t C, int32_t p, int64_t K, int32_t dtype, void* dX, void* ws, size_t ws_bytes,
+                            void* stream) {
+  int32_t st = validate_patches(B, H, W, C, p, K, dtype);
+  if (st != SBP_OK) return st;
+  if (!dX) return fail(SBP_ERR_NULL, "dX is NULL");
+  if (K > 0 && (!dXp || !idx)) return fail(SBP_ERR_NULL, "dXp_k or idx is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!inv) {
+    const size_t need = sbp_scatter_patches_workspace(B, H, W, p);
+    if (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) % 256) != 0)
+      return fail(SBP_ERR_WORKSPACE, "workspace missing, misaligned or smaller than %zu bytes", need);
+    launch_build_inverse(idx, K, static_cast<int32_t*>(ws), s);
+    inv = static_cast<const int32_t*>(ws);
+  }
+  return launch_patches(true, dXp, idx, inv, B, H, W, C, p, K, elem_bytes(dtype), dX, s);
+}
+
 static int32_t validate_rows(int64_t K, int32_t C, int32_t dtype) {
   if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
   if (K < 0 || C < 1 || K > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad shape K=%lld C=%d", (long long)K, C);

@@ -2,6 +2,8 @@
 // only a subset of each layer input for the backward pass).  Pure data movement, bound by
 // HBM: every thread moves 16-byte pieces, several in flight, rows laid out so that a
 // wavefront reads and writes whole contiguous row segments.
+#include <algorithm>
+
 #include "sbp_internal.h"
 
 namespace sbp {
@@ -70,6 +72,87 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
                          idx, (long long)K, C, (uint16_t*)Xk);
   }
   return check_launch("gather_rows");
+}
+
+// ------------------------------------------------------------------------------------------------
+// Down-sampling layers (convolution with kernel p x p and stride p: the paper's case s >= k, where
+// every output position owns its own patch of inputs and the layer behaves like a point-wise one).
+// The forward-side cache holds, per kept output position, its p x p input patch as one row
+// [p * p * C] in (dy, dx, c) order; the linear backward then runs on these rows, and the compact
+// gradient rows are written back to the patches of the [B, H, W, C] input gradient in one pass that
+// also writes the zeros of every other position.
+// Unit = one element of `unit_t` (16 bytes when rows allow, else one value).
+// ------------------------------------------------------------------------------------------------
+struct PatchGeom {
+  int H, W, Ho, Wo, p, seg;      // seg = units per pixel
+};
+
+template <typename U>
+__global__ void __launch_bounds__(256) gather_patches_kernel(const U* __restrict__ X, const int32_t* __restrict__ idx,
+                                                             long long K, PatchGeom g, U* __restrict__ Xk) {
+  const int per_row = g.p * g.p * g.seg;
+  const long long total = K * per_row;
+  for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+    const long long j = t / per_row;
+    const int rem = (int)(t - j * per_row);
+    const int s = rem / g.seg, c = rem - s * g.seg;
+    const int dy = s / g.p, dx = s - dy * g.p;
+    const int f = idx[j];
+    const int b = f / (g.Ho * g.Wo), r = f - b * (g.Ho * g.Wo);
+    const int yo = r / g.Wo, xo = r - yo * g.Wo;
+    const long long pix = ((long long)b * g.H + g.p * yo + dy) * g.W + g.p * xo + dx;
+    Xk[t] = X[pix * g.seg + c];
+  }
+}
+
+template <typename U>
+__global__ void __launch_bounds__(256) scatter_patches_kernel(const U* __restrict__ dXp, const int32_t* __restrict__ idx,
+                                                              const int32_t* __restrict__ inv, int K, long long npix,
+                                                              PatchGeom g, U* __restrict__ dX) {
+  const long long total = npix * g.seg;
+  const int per_row = g.p * g.p * g.seg;
+  U zero;
+  __builtin_memset(&zero, 0, sizeof(U));
+  for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+    const long long pix = t / g.seg;
+    const int c = (int)(t - pix * g.seg);
+    const int x = (int)(pix % g.W);
+    const long long by = pix / g.W;
+    const int y = (int)(by % g.H), b = (int)(by / g.H);
+    const int f = (b * g.Ho + y / g.p) * g.Wo + x / g.p;
+    const int j = inv[f];
+    const bool kept = (unsigned)j < (unsigned)K && idx[j] == f;
+    dX[t] = kept ? dXp[(long long)j * per_row + ((y % g.p) * g.p + x % g.p) * g.seg + c] : zero;
+  }
+}
+
+template <typename U>
+static void launch_patches_t(bool scatter, const void* src, const int32_t* idx, const int32_t* inv, int64_t K, long long npix,
+                             PatchGeom g, void* dst, hipStream_t s) {
+  const long long total = scatter ? npix * g.seg : K * (long long)g.p * g.p * g.seg;
+  const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(total, 256), 256 * 32));
+  if (scatter)
+    SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (scatter_patches_kernel<U>), dim3(blocks), dim3(256), 0, s, (const U*)src, idx, inv, (int)K,
+               npix, g, (U*)dst);
+  else
+    SBP_LAUNCH(SBP_PROF_GATHER, s, (gather_patches_kernel<U>), dim3(blocks), dim3(256), 0, s, (const U*)src, idx, (long long)K, g,
+               (U*)dst);
+}
+
+int32_t launch_patches(bool scatter, const void* src, const int32_t* idx, const int32_t* inv, int32_t B, int32_t H, int32_t W,
+                       int32_t C, int32_t p, int64_t K, int32_t elem_bytes, void* dst, hipStream_t s) {
+  PatchGeom g{H, W, H / p, W / p, p, C};
+  const long long npix = (long long)B * H * W;
+  const long long pix_bytes = (long long)C * elem_bytes;
+  if (pix_bytes % 16 == 0 && (uintptr_t)src % 16 == 0 && (uintptr_t)dst % 16 == 0) {
+    g.seg = (int)(pix_bytes / 16);
+    launch_patches_t<uint4>(scatter, src, idx, inv, K, npix, g, dst, s);
+  } else if (elem_bytes == 4) {
+    launch_patches_t<uint32_t>(scatter, src, idx, inv, K, npix, g, dst, s);
+  } else {
+    launch_patches_t<uint16_t>(scatter, src, idx, inv, K, npix, g, dst, s);
+  }
+  return check_launch(scatter ? "scatter_patches" : "gather_patches");
 }
 
 }  // namespace sbp

@@ -41,6 +41,10 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
 int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t C, int32_t elem_bytes,
                            void* Xk, hipStream_t s);
 
+// patches of a p x p, stride p down-sampling layer: gather [K, p*p*C] rows / scatter them back with zero fill
+int32_t launch_patches(bool scatter, const void* src, const int32_t* idx, const int32_t* inv, int32_t B, int32_t H, int32_t W,
+                       int32_t C, int32_t p, int64_t K, int32_t elem_bytes, void* dst, hipStream_t s);
+
 // ---- linear backward ---------------------------------------------------------------------
 struct LinearPlan {
   bool   mfma;          // bf16 MFMA path (else plain kernels)

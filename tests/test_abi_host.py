@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 17
+    assert len(names) == 20
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -149,6 +149,22 @@ def test_backward_linear_engine_report_and_plan():
         sbp.backward_linear_engine(100, 500, 64, 128, sbp.BF16)
     # rows of dY that byte offsets of 32 bits cannot reach: the general engine takes the shape
     assert sbp.backward_linear_engine(1 << 20, 1 << 19, 4096, 4096, sbp.BF16)[0] == "mfma"
+
+
+def test_patch_steps_argument_errors():
+    L = _lib.lib()
+    p = 4096
+    assert L.sbp_forward_cache_patches(p, p, 2, 8, 8, 16, 3, 10, 1, p, None) == -2      # H not a multiple of p
+    assert L.sbp_forward_cache_patches(p, p, 2, 8, 8, 16, 9, 10, 1, p, None) == -2
+    assert L.sbp_forward_cache_patches(p, p, 2, 8, 8, 16, 2, 33, 1, p, None) == -2      # K > B*Ho*Wo = 32
+    assert L.sbp_forward_cache_patches(None, p, 2, 8, 8, 16, 2, 10, 1, p, None) == -1
+    assert L.sbp_forward_cache_patches(p, p, 2, 8, 8, 16, 2, 10, 4, p, None) == -4
+    assert L.sbp_forward_cache_patches(None, None, 2, 8, 8, 16, 2, 0, 1, None, None) == 0
+    assert L.sbp_scatter_patches_workspace(2, 8, 8, 2) == 256                           # 32 output positions
+    assert L.sbp_scatter_patches_workspace(2, 8, 8, 3) == 0
+    assert L.sbp_scatter_patches(p, p, None, 2, 8, 8, 16, 2, 10, 1, p, None, 0, None) == -6   # no inv, no workspace
+    assert L.sbp_scatter_patches(p, p, None, 2, 8, 8, 16, 2, 10, 1, None, p, 256, None) == -1
+    assert L.sbp_scatter_patches(None, p, p, 2, 8, 8, 16, 2, 10, 1, p, None, 0, None) == -1
 
 
 def test_rowwise_steps_argument_errors():
