@@ -7,6 +7,12 @@ path; it is a plain fp64 write-out of what the paper defines.
 from .sbp_oracle import (  # noqa: F401
     GRID_PER_CELL,
     GRID_SHARED,
+    RANDOM_MASK,
+    TEMPORAL,
+    random_keep_count,
+    sample_indices_random,
+    temporal_keep_frames,
+    sample_indices_temporal,
     k_from_ratio,
     keep_count,
     sample_indices,

@@ -53,6 +53,8 @@ import numpy as np
 
 GRID_PER_CELL = 0  # independent draw in every 2x2 cell
 GRID_SHARED = 1    # one slot permutation shared by all cells of a sample
+RANDOM_MASK = 2    # uniformly random subset of the grid positions of a sample (the paper's "random mask sampling")
+TEMPORAL = 3       # whole frames: k of every `cell` consecutive frames (the temporal special case the paper cites)
 
 _MASK64 = (1 << 64) - 1
 _GAMMA = 0x9E3779B97F4A7C15
@@ -138,6 +140,64 @@ def sample_indices(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sampl
                 for s in chosen:
                     y, x = 2 * cy + (s >> 1), 2 * cx + (s & 1)
                     out.append(b * N + P + y * W + x)
+    return np.asarray(out, dtype=np.int32)
+
+
+def random_keep_count(H: int, W: int, k: int) -> int:
+    """Kept grid positions per sample of the random mask at ratio k/4: round-half-up(k*H*W/4), >= 1."""
+    return max(1, (k * H * W + 2) // 4)
+
+
+def sample_indices_random(B, P, H, W, k, seed, stream_id, per_sample=True):
+    """Random mask sampling (section "Design Strategies", "How to sample the gradient keep mask?"): per sample
+    a uniformly random subset of exactly round(k/4 * H*W) grid positions, no grid structure.
+
+    This repository's construction (the paper gives none): every position p draws the key
+    absorb(h_sample, p) from the counter hash; the positions with the smallest (key, p) are kept.
+    Canonical order: sample-major, the P prefix rows, then the kept positions in ascending order.
+    """
+    if not (1 <= k <= 4):
+        raise ValueError("k must be in 1..4")
+    N = P + H * W
+    n_keep = random_keep_count(H, W, k)
+    base = _absorb(_absorb(0, seed), stream_id)
+    out = []
+    for b in range(B):
+        hb = _absorb(base, b if per_sample else 0)
+        keys = [(_absorb(hb, p), p) for p in range(H * W)]
+        kept = sorted(p for _, p in sorted(keys)[:n_keep])
+        out.extend(b * N + p for p in range(P))
+        out.extend(b * N + P + p for p in kept)
+    return np.asarray(out, dtype=np.int32)
+
+
+def temporal_keep_frames(T: int, c: int, k: int) -> int:
+    """Kept frames per sample: k of every full cell of c frames, round-half-up(k*c'/c) >= 1 of a tail of c' frames."""
+    tail = T % c
+    return k * (T // c) + (max(1, (2 * k * tail + c) // (2 * c)) if tail else 0)
+
+
+def sample_indices_temporal(B, P, T, HW, c, k, seed, stream_id, per_sample=True):
+    """Temporal subsets (the special case on the temporal dimension that the paper cites under eq:sbp_formula):
+    the rows of a sample are P prefix rows and T frames of HW positions; of every c consecutive frames k are kept
+    whole.  Inside a cell frame s draws the key absorb(h_cell, s); the frames with the smallest (key, s) are kept.
+    Canonical order: sample-major, prefix rows, then kept frames ascending, positions ascending.
+    """
+    if not (2 <= c <= 4 and 1 <= k <= c):
+        raise ValueError("need 2 <= c <= 4 and 1 <= k <= c")
+    N = P + T * HW
+    base = _absorb(_absorb(0, seed), stream_id)
+    out = []
+    for b in range(B):
+        hb = _absorb(base, b if per_sample else 0)
+        out.extend(b * N + p for p in range(P))
+        for cell in range((T + c - 1) // c):
+            frames = [f for f in range(cell * c, min(T, cell * c + c))]
+            kc = k if len(frames) == c else max(1, (2 * k * len(frames) + c) // (2 * c))
+            hc = _absorb(hb, cell)
+            ranked = sorted(frames, key=lambda f: (_absorb(hc, f - cell * c), f))
+            for f in sorted(ranked[:kc]):
+                out.extend(b * N + P + f * HW + p for p in range(HW))
     return np.asarray(out, dtype=np.int32)
 
 
