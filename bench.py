@@ -385,6 +385,36 @@ def measure_downsample(torch, sbp, si, r, iters=20, warmup=5):
     return out
 
 
+def measure_samplers(torch, sbp, si):
+    """One draw (keep list + inverse map) of every sampler mode on the ViT-Base batch and on a detection map."""
+    out = {}
+    for tag, (B, P, H, W) in (("vit_base 64x(1+14x14)", (64, 1, 14, 14)), ("detection 2x200x336", (2, 0, 200, 336))):
+        M = B * (P + H * W)
+        idx = torch.empty(M, dtype=torch.int32, device="cuda")
+        inv = torch.empty(M, dtype=torch.int32, device="cuda")
+        res = {}
+        for name, kw in (("grid", dict(mode=sbp.GRID_PER_CELL)), ("random_mask", dict(mode=sbp.RANDOM_MASK)),
+                         ("temporal(8 frames, 2 of 4)", dict(mode=sbp.TEMPORAL, cell=4))):
+            if name.startswith("temporal"):
+                if (H * W) % 8:
+                    continue
+                geom = (B, P, 8, H * W // 8)
+            else:
+                geom = (B, P, H, W)
+            for i in range(3):
+                sbp.sample_indices(*geom, 2, 0, i, idx_out=idx, inv_out=inv, **kw)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(50):
+                sbp.sample_indices(*geom, 2, 0, 10 + i, idx_out=idx, inv_out=inv, **kw)
+            e1.record()
+            torch.cuda.synchronize()
+            res[name] = {"us": round(e0.elapsed_time(e1) / 50 * 1e3, 2)}
+        out[tag] = res
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -477,6 +507,7 @@ def main():
         result["other_workloads"] = extras
         result["mlp_branch_compact"] = measure_mlp_branch(torch, sbp, si, args.ratio)
         result["downsample_layer"] = measure_downsample(torch, sbp, si, args.ratio)
+        result["sampler_modes"] = measure_samplers(torch, sbp, si)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.ratio, args.cpu_seconds, si)
     print(json.dumps(result))

@@ -51,6 +51,15 @@ extern "C" {
 /* sampler modes */
 #define SBP_GRID_PER_CELL 0  /* independent draw in every 2x2 cell */
 #define SBP_GRID_SHARED   1  /* one slot permutation shared by all cells of a sample (regular lattice) */
+/* The paper's other strategy, "random mask sampling": per sample exactly round-half-up(k/4 * H*W) (>= 1) of
+ * the grid positions, a uniformly random subset without grid structure (those with the smallest hashed keys;
+ * ties by position).  idx order: sample-major, prefix rows, kept positions ascending.  cell must be 2. */
+#define SBP_RANDOM_MASK   2
+/* Temporal subsets (the special case on the temporal dimension cited under eq:sbp_formula): the rows of a
+ * sample are P prefix rows and H frames of W positions each; of every `cell` (2..4) consecutive frames k
+ * (1..cell) are kept whole, drawn independently per cell; a partial last cell of c' frames keeps
+ * round-half-up(k*c'/cell) (>= 1).  idx order: sample-major, prefix rows, kept frames ascending. */
+#define SBP_TEMPORAL      3
 
 /* flags of sbp_backward_linear */
 #define SBP_FLAG_DY_COMPACT     1u  /* dY is already compact: [K, Cout], row j belongs to idx[j] */
@@ -71,9 +80,9 @@ typedef struct sbp_sample_desc {
   int32_t  B;          /* samples in the batch, >= 1 */
   int32_t  P;          /* always-kept prefix rows per sample, >= 0 */
   int32_t  H, W;       /* grid, >= 1 each */
-  int32_t  cell;       /* cell edge; must be 2 */
-  int32_t  k;          /* kept slots per full cell, 1..4 */
-  int32_t  mode;       /* SBP_GRID_PER_CELL or SBP_GRID_SHARED */
+  int32_t  cell;       /* cell edge; must be 2 (SBP_TEMPORAL: frames per cell, 2..4) */
+  int32_t  k;          /* kept slots per full cell, 1..4 (SBP_TEMPORAL: kept frames per cell, 1..cell) */
+  int32_t  mode;       /* SBP_GRID_PER_CELL, SBP_GRID_SHARED, SBP_RANDOM_MASK or SBP_TEMPORAL */
   int32_t  per_sample; /* 1: every sample draws its own mask; 0: one mask for the batch */
   uint64_t seed;       /* run seed */
   uint64_t stream_id;  /* caller's (step, layer) counter: a new value gives a new mask */
@@ -94,8 +103,9 @@ int64_t sbp_keep_count(const sbp_sample_desc* desc);
 
 /*
  * Step "sample keep-set".  Writes the kept row ids, int32, into idx[0..K) in canonical
- * order: sample-major; inside a sample the P prefix rows, then the cells in row-major cell
- * order, and inside a cell the kept slots in ascending slot number 2*(y%2) + (x%2).
+ * order: sample-major; inside a sample the P prefix rows, then (grid modes) the cells in row-major cell
+ * order, and inside a cell the kept slots in ascending slot number 2*(y%2) + (x%2); the other modes
+ * write ascending row ids.
  *   idx          device, out, capacity idx_capacity elements (>= K else SBP_ERR_CAPACITY)
  *   inv          device, out, [B*(P+H*W)] or NULL: inv[row] = position of row in idx, -1 if dropped
  */

@@ -19,7 +19,7 @@ from . import _lib
 from ._lib import SampleDesc, SbpError  # noqa: F401
 
 F32, BF16 = 0, 1
-GRID_PER_CELL, GRID_SHARED = 0, 1
+GRID_PER_CELL, GRID_SHARED, RANDOM_MASK, TEMPORAL = 0, 1, 2, 3
 FLAG_DY_COMPACT, FLAG_DX_COMPACT, FLAG_ACCUMULATE_DW = 1, 2, 4
 
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
@@ -46,8 +46,9 @@ def _stream(device) -> int:
     return torch.cuda.current_stream(device).cuda_stream
 
 
-def make_desc(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sample=True) -> SampleDesc:
-    return SampleDesc(int(B), int(P), int(H), int(W), 2, int(k), int(mode), int(bool(per_sample)),
+def make_desc(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sample=True, cell=2) -> SampleDesc:
+    """cell: 2 for the grid and random modes; TEMPORAL: frames per cell (H = frames, W = positions per frame)."""
+    return SampleDesc(int(B), int(P), int(H), int(W), int(cell), int(k), int(mode), int(bool(per_sample)),
                       int(seed) & 0xFFFFFFFFFFFFFFFF, int(stream_id) & 0xFFFFFFFFFFFFFFFF)
 
 
@@ -56,16 +57,16 @@ def k_from_ratio(r: float, cell: int = 2) -> int:
     return _lib.check(_lib.lib().sbp_k_from_ratio(float(r), int(cell)))
 
 
-def keep_count(B, P, H, W, k, mode=GRID_PER_CELL, per_sample=True) -> int:
+def keep_count(B, P, H, W, k, mode=GRID_PER_CELL, per_sample=True, cell=2) -> int:
     """Number of kept rows K of a draw (host only, closed form)."""
-    d = make_desc(B, P, H, W, k, 0, 0, mode, per_sample)
+    d = make_desc(B, P, H, W, k, 0, 0, mode, per_sample, cell)
     return _lib.check(_lib.lib().sbp_keep_count(d))
 
 
 def sample_indices(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sample=True, want_inv=False,
-                   device="cuda", idx_out=None, inv_out=None):
-    """Draws the grid-wise keep-set on the GPU; returns (idx [K] int32, inv [B*(P+H*W)] int32 or None)."""
-    d = make_desc(B, P, H, W, k, seed, stream_id, mode, per_sample)
+                   device="cuda", idx_out=None, inv_out=None, cell=2):
+    """Draws the keep-set on the GPU; returns (idx [K] int32, inv [B*(P+H*W)] int32 or None)."""
+    d = make_desc(B, P, H, W, k, seed, stream_id, mode, per_sample, cell)
     K = _lib.check(_lib.lib().sbp_keep_count(d))
     dev = torch.device(device)
     idx = idx_out if idx_out is not None else torch.empty(K, dtype=torch.int32, device=dev)

@@ -48,9 +48,14 @@ static int32_t validate_desc(const sbp_sample_desc* d) {
   if (!d) return fail(SBP_ERR_NULL, "sample descriptor is NULL");
   if (d->B < 1 || d->P < 0 || d->H < 1 || d->W < 1)
     return fail(SBP_ERR_SHAPE, "bad geometry B=%d P=%d H=%d W=%d", d->B, d->P, d->H, d->W);
-  if (d->cell != 2) return fail(SBP_ERR_SHAPE, "cell must be 2, got %d", d->cell);
-  if (d->k < 1 || d->k > 4) return fail(SBP_ERR_RATIO, "k must be in 1..4, got %d", d->k);
-  if (d->mode != SBP_GRID_PER_CELL && d->mode != SBP_GRID_SHARED)
+  if (d->mode == SBP_TEMPORAL) {
+    if (d->cell < 2 || d->cell > 4) return fail(SBP_ERR_SHAPE, "temporal cell must be 2..4 frames, got %d", d->cell);
+    if (d->k < 1 || d->k > d->cell) return fail(SBP_ERR_RATIO, "k must be in 1..cell, got %d", d->k);
+  } else {
+    if (d->cell != 2) return fail(SBP_ERR_SHAPE, "cell must be 2, got %d", d->cell);
+    if (d->k < 1 || d->k > 4) return fail(SBP_ERR_RATIO, "k must be in 1..4, got %d", d->k);
+  }
+  if (d->mode != SBP_GRID_PER_CELL && d->mode != SBP_GRID_SHARED && d->mode != SBP_RANDOM_MASK && d->mode != SBP_TEMPORAL)
     return fail(SBP_ERR_FLAGS, "unknown sampler mode %d", d->mode);
   if (d->per_sample != 0 && d->per_sample != 1)
     return fail(SBP_ERR_FLAGS, "per_sample must be 0 or 1, got %d", d->per_sample);

@@ -5,6 +5,8 @@
 // Here every 2x2 cell keeps k of its 4 slots, the slot permutation coming from a
 // SplitMix64-style counter hash of (seed, stream_id, sample, cell).  Integer arithmetic
 // only; the position of every cell's output in idx is a closed form, so no scan is needed.
+#include <algorithm>
+
 #include "sbp_internal.h"
 
 namespace sbp {
@@ -49,9 +51,173 @@ static SampleGeom make_geom(const sbp_sample_desc& d) {
   return g;
 }
 
+// ---- the other samplers: same row numbering, same hash --------------------------------------------------
+// random mask: exactly n_keep of the H*W grid positions of a sample, those with the smallest (key, position),
+// key = absorb(h_sample, position); temporal subsets: H frames of W positions, k of every `cell` frames kept whole.
+static inline int random_keep(const sbp_sample_desc& d) {
+  const long long v = ((long long)d.k * d.H * d.W + 2) / 4;
+  return (int)(v < 1 ? 1 : v);
+}
+static inline int temporal_tail_keep(int k, int tail, int c) {
+  const int v = (2 * k * tail + c) / (2 * c);
+  return v < 1 ? 1 : v;
+}
+static inline int temporal_keep_frames(const sbp_sample_desc& d) {
+  const int tail = d.H % d.cell;
+  return d.k * (d.H / d.cell) + (tail ? temporal_tail_keep(d.k, tail, d.cell) : 0);
+}
+
 int64_t keep_count_host(const sbp_sample_desc& d) {
+  if (d.mode == SBP_RANDOM_MASK) return (int64_t)d.B * (d.P + random_keep(d));
+  if (d.mode == SBP_TEMPORAL) return (int64_t)d.B * (d.P + (int64_t)temporal_keep_frames(d) * d.W);
   SampleGeom g = make_geom(d);
   return (int64_t)g.B * g.per_sample_K;
+}
+
+struct VariantGeom {
+  int B, P, H, W, k, cell, per_sample;
+  int N;              // rows per sample
+  int n_keep;         // random mask: kept grid positions per sample; temporal: kept frames per sample
+  int tail_keep;      // temporal: kept frames of the partial last cell
+  uint64_t base;
+};
+
+// Random mask: one block per sample.  The n_keep-th smallest key is found by a radix select over the 64-bit
+// keys, 8 bits per pass from the top, the keys being recomputed from the hash in every pass (nothing is
+// stored); a last pass writes the kept positions in ascending order with a block-wide running count.
+// Equal keys (never seen in practice, but possible) are broken by position, smallest first.
+template <int NT>
+__global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_t* __restrict__ idx,
+                                                           int32_t* __restrict__ inv) {
+  constexpr int NWAVE = NT / 64;
+  __shared__ int hist[256];
+  __shared__ uint64_t s_prefix;
+  __shared__ int s_remaining;
+  __shared__ int s_wave_lt[NWAVE], s_wave_eq[NWAVE];
+  __shared__ int s_run_lt, s_run_eq;
+  const int b = blockIdx.x, t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int n = g.H * g.W;
+  const uint64_t hb = absorb(g.base, g.per_sample ? (uint64_t)b : 0ull);
+  const int row0 = b * g.N, out0 = b * (g.P + g.n_keep);
+  for (int p = t; p < g.P; p += NT) {
+    idx[out0 + p] = row0 + p;
+    if (inv) inv[row0 + p] = out0 + p;
+  }
+  if (t == 0) { s_prefix = 0; s_remaining = g.n_keep; }
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+    if (t < 256) hist[t] = 0;
+    __syncthreads();
+    const uint64_t prefix = s_prefix;
+    for (int p = t; p < n; p += NT) {
+      const uint64_t key = absorb(hb, (uint64_t)p);
+      if (pass == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
+    }
+    __syncthreads();
+    // bucket in which the running count reaches what is still wanted: inclusive scan of the 256 counts
+    // by the first four wavefronts
+    const int rem = s_remaining;
+    int incl = t < 256 ? hist[t] : 0;
+    const int mine = incl;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63 && wave < 4) s_wave_lt[wave] = incl;     // (scratch reuse: totals of the four wavefronts)
+    __syncthreads();
+    for (int w = 0; w < wave && w < 4; ++w) incl += s_wave_lt[w];
+    const int excl = incl - mine;
+    __syncthreads();                                // everyone has read s_remaining / s_prefix / s_wave_lt
+    if (t < 256 && excl < rem && rem <= incl) {     // exactly one thread
+      s_remaining = rem - excl;                     // keys still to take inside the chosen bucket
+      s_prefix = prefix | ((uint64_t)t << shift);
+    }
+    __syncthreads();
+  }
+  const uint64_t thr = s_prefix;                    // the n_keep-th smallest key
+  const int take_eq = s_remaining;                  // how many keys equal to it are kept (smallest positions first)
+  if (t == 0) { s_run_lt = 0; s_run_eq = 0; }
+  __syncthreads();
+  for (int p0 = 0; p0 < n; p0 += NT) {
+    const int p = p0 + t;
+    bool lt = false, eq = false;
+    if (p < n) {
+      const uint64_t key = absorb(hb, (uint64_t)p);
+      lt = key < thr;
+      eq = key == thr;
+    }
+    const unsigned long long mlt = __ballot(lt), meq = __ballot(eq);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    if (lane == 0) { s_wave_lt[wave] = __popcll(mlt); s_wave_eq[wave] = __popcll(meq); }
+    __syncthreads();
+    int lt_before = s_run_lt + __popcll(mlt & below), eq_before = s_run_eq + __popcll(meq & below);
+    for (int w = 0; w < wave; ++w) { lt_before += s_wave_lt[w]; eq_before += s_wave_eq[w]; }
+    if (p < n) {
+      const bool keep = lt || (eq && eq_before < take_eq);
+      const int row = row0 + g.P + p;
+      if (keep) {
+        const int pos = out0 + g.P + lt_before + min(eq_before, take_eq);
+        idx[pos] = row;
+        if (inv) inv[row] = pos;
+      } else if (inv) {
+        inv[row] = -1;
+      }
+    }
+    __syncthreads();
+    if (t == 0) {
+      int a = 0, e = 0;
+      for (int w = 0; w < NWAVE; ++w) { a += s_wave_lt[w]; e += s_wave_eq[w]; }
+      s_run_lt += a;
+      s_run_eq += e;
+    }
+    __syncthreads();
+  }
+}
+
+// Temporal subsets: one thread per row.  A frame's fate is a closed form of its cell: frame s of the cell draws
+// the key absorb(h_cell, s); its rank among the cell's frames decides, and the kept frames before it are
+// cell * k + (kept frames of the cell with a smaller slot number).
+__global__ void __launch_bounds__(256) sample_temporal_kernel(VariantGeom g, int32_t* __restrict__ idx,
+                                                              int32_t* __restrict__ inv) {
+  const long long total = (long long)g.B * g.N;
+  for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
+    const int b = (int)(e / g.N), r = (int)(e - (long long)b * g.N);
+    const int out0 = b * (g.P + g.n_keep * g.W);
+    if (r < g.P) {
+      idx[out0 + r] = (int)e;
+      if (inv) inv[e] = out0 + r;
+      continue;
+    }
+    const int f = (r - g.P) / g.W, p = (r - g.P) - f * g.W;
+    const int cell = f / g.cell, s = f - cell * g.cell;
+    const int nvalid = min(g.cell, g.H - cell * g.cell);
+    const int kc = nvalid == g.cell ? g.k : g.tail_keep;
+    const uint64_t hc = absorb(absorb(g.base, g.per_sample ? (uint64_t)b : 0ull), (uint64_t)cell);
+    uint64_t key[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) key[q] = absorb(hc, (uint64_t)q);
+    int kept_before = 0;
+    bool mine = false;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (q >= nvalid) continue;
+      int rank = 0;
+#pragma unroll
+      for (int o = 0; o < 4; ++o)
+        if (o < nvalid && (key[o] < key[q] || (key[o] == key[q] && o < q))) ++rank;
+      const bool kq = rank < kc;
+      if (q < s && kq) ++kept_before;
+      if (q == s) mine = kq;
+    }
+    if (mine) {
+      const int pos = out0 + g.P + (cell * g.k + kept_before) * g.W + p;
+      idx[pos] = (int)e;
+      if (inv) inv[e] = pos;
+    } else if (inv) {
+      inv[e] = -1;
+    }
+  }
 }
 
 // One work item: a prefix row or a cell of sample b.
@@ -127,6 +293,24 @@ __global__ void __launch_bounds__(256) sample_kernel(SampleGeom g, int32_t* __re
 }
 
 int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipStream_t s) {
+  if (d.mode == SBP_RANDOM_MASK || d.mode == SBP_TEMPORAL) {
+    VariantGeom v;
+    v.B = d.B; v.P = d.P; v.H = d.H; v.W = d.W; v.k = d.k; v.cell = d.cell; v.per_sample = d.per_sample;
+    v.N = d.P + d.H * d.W;
+    v.base = absorb(absorb(0, d.seed), d.stream_id);
+    if (d.mode == SBP_RANDOM_MASK) {
+      v.n_keep = random_keep(d); v.tail_keep = 0;
+      if (d.H * d.W > 2048) SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_random_kernel<1024>, dim3(d.B), dim3(1024), 0, s, v, idx, inv);
+      else SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_random_kernel<256>, dim3(d.B), dim3(256), 0, s, v, idx, inv);
+      return check_launch("sample_random_kernel");
+    }
+    v.n_keep = temporal_keep_frames(d);
+    v.tail_keep = d.H % d.cell ? temporal_tail_keep(d.k, d.H % d.cell, d.cell) : 0;
+    const long long total = (long long)v.B * v.N;
+    const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>((total + 255) / 256, 65535));
+    SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_temporal_kernel, dim3(blocks), dim3(256), 0, s, v, idx, inv);
+    return check_launch("sample_temporal_kernel");
+  }
   SampleGeom g = make_geom(d);
   long long total = (long long)g.B * (g.P + g.ch * g.cw);
   int blocks = (int)((total + 255) / 256);

@@ -151,6 +151,21 @@ def test_backward_linear_engine_report_and_plan():
     assert sbp.backward_linear_engine(1 << 20, 1 << 19, 4096, 4096, sbp.BF16)[0] == "mfma"
 
 
+def test_other_sampler_modes_counts_and_errors():
+    for (B, P, H, W) in [(2, 1, 14, 14), (3, 0, 5, 7), (1, 0, 1, 1), (2, 0, 100, 168)]:
+        for k in (1, 2, 3, 4):
+            assert sbp.keep_count(B, P, H, W, k, mode=sbp.RANDOM_MASK) == B * (P + oracle.random_keep_count(H, W, k))
+    for (B, P, T, HW) in [(2, 1, 8, 196), (3, 0, 9, 5), (1, 0, 1, 7), (2, 0, 10, 3)]:
+        for c in (2, 3, 4):
+            for k in range(1, c + 1):
+                assert sbp.keep_count(B, P, T, HW, k, mode=sbp.TEMPORAL, cell=c) == B * (P + oracle.temporal_keep_frames(T, c, k) * HW)
+    L = _lib.lib()
+    assert L.sbp_keep_count(sbp.make_desc(2, 0, 8, 4, 1, 0, 0, mode=sbp.TEMPORAL, cell=5)) == -2
+    assert L.sbp_keep_count(sbp.make_desc(2, 0, 8, 4, 4, 0, 0, mode=sbp.TEMPORAL, cell=3)) == -3
+    assert L.sbp_keep_count(sbp.make_desc(2, 0, 8, 4, 2, 0, 0, mode=sbp.RANDOM_MASK, cell=3)) == -2
+    assert L.sbp_keep_count(sbp.make_desc(2, 0, 8, 4, 2, 0, 0, mode=4)) == -8
+
+
 def test_patch_steps_argument_errors():
     L = _lib.lib()
     p = 4096

@@ -45,6 +45,38 @@ def test_sampler_golden_vectors():
         assert np.array_equal(idx.cpu().numpy(), want)
 
 
+@pytest.mark.parametrize("geom", [(2, 1, 14, 14), (64, 1, 14, 14), (3, 0, 5, 7), (1, 2, 1, 1), (2, 0, 100, 168), (5, 0, 17, 15)])
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_random_mask_sampler_bit_exact(geom, k):
+    B, P, H, W = geom
+    ref = oracle.sample_indices_random(B, P, H, W, k, 11, 12)
+    idx, inv = sbp.sample_indices(B, P, H, W, k, 11, 12, mode=sbp.RANDOM_MASK, want_inv=True)
+    assert idx.numel() == sbp.keep_count(B, P, H, W, k, mode=sbp.RANDOM_MASK) == ref.size
+    assert np.array_equal(idx.cpu().numpy(), ref)
+    assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(ref, B * (P + H * W)))
+    one = sbp.sample_indices(B, P, H, W, k, 11, 12, mode=sbp.RANDOM_MASK, per_sample=False)[0]
+    assert np.array_equal(one.cpu().numpy(), oracle.sample_indices_random(B, P, H, W, k, 11, 12, per_sample=False))
+
+
+@pytest.mark.parametrize("c,k", [(2, 1), (2, 2), (3, 2), (4, 1), (4, 3)])
+@pytest.mark.parametrize("geom", [(2, 1, 8, 196), (3, 0, 9, 5), (1, 0, 1, 7), (2, 2, 10, 49), (2, 0, 16, 3136)])
+def test_temporal_sampler_bit_exact(geom, c, k):
+    B, P, T, HW = geom
+    ref = oracle.sample_indices_temporal(B, P, T, HW, c, k, 21, 22)
+    idx, inv = sbp.sample_indices(B, P, T, HW, k, 21, 22, mode=sbp.TEMPORAL, want_inv=True, cell=c)
+    assert idx.numel() == sbp.keep_count(B, P, T, HW, k, mode=sbp.TEMPORAL, cell=c) == ref.size
+    assert np.array_equal(idx.cpu().numpy(), ref)
+    assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(ref, B * (P + T * HW)))
+
+
+def test_other_samplers_feed_the_linear_backward():
+    # a random mask and a temporal subset are keep lists like any other: cache + backward against the oracle
+    for ref in (oracle.sample_indices_random(4, 1, 14, 14, 2, 3, 4), oracle.sample_indices_temporal(2, 0, 8, 98, 4, 2, 3, 4)):
+        M = 4 * 197 if ref.size == 4 * 99 else 2 * 8 * 98
+        X, W, dY = si.linear_case(M, 64, 128, 9, "bf16")
+        check_linear(X, W, dY, ref, "bf16")
+
+
 # ------------------------------------------------------------------ forward cache
 @pytest.mark.parametrize("dtype,C", [("f32", 64), ("bf16", 192), ("bf16", 768), ("bf16", 20), ("f32", 7), ("bf16", 3)])
 def test_forward_cache_bit_exact(dtype, C):
