@@ -51,10 +51,12 @@ struct LinearPlan {
   int    bm_w, bn_w;    // tile of both contractions (rows x columns)
   int    splits;        // split-K factor of the dW contraction
   int    rows_per_split;// kept rows per split (multiple of the k-step)
+  int    n_big;         // big engine: the first n_big splits have rows_per_split rows, the others rows_small
+  int    rows_small;    // big engine: rows of the short splits that fill the end of the schedule (0: none)
+  int    seg_order[3];  // big engine: dispatch order of the unit kinds 0 = dX tiles, 1 = long dW units, 2 = short dW units
   int    nw_w;          // wavefronts per block (4 or 8)
   int    kb;            // contraction elements per LDS stage (64: two stages, 32: four stages)
   bool   big;           // 256 x 256 tiles, one workgroup per CU (sbp_mfma_big.h)
-  bool   dw_first;      // big engine: dW units are the longer ones and are dispatched before the dX tiles
   int    dx_bm;         // big engine: rows of a dX tile (256, or 128 where 256-row tiles are too few)
   int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
   int    db_slice_rows; // kept rows per db slice

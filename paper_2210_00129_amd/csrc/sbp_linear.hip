@@ -59,7 +59,8 @@ struct LinArgs {
   float* dbp;
   int K, M, Cin, Cout, rows_per_split, db_slice_rows;
   int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
-  int dw_first;                       // large-tile kernel: dW units come before the dX tiles
+  int n_big, rows_small, n_dw_big;     // large-tile kernel: long and short dW splits; n_dw_big of the n_dw units are long
+  int seg_order[3];                   // large-tile kernel: dispatch order of 0 = dX tiles, 1 = long dW, 2 = short dW units
   int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
 };
 
@@ -131,9 +132,22 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
                       tile_m * BM, tile_n * BN);
 }
 
+// Workgroups go to the 8 XCDs round robin by their index in the grid, and every XCD queues its own: a
+// workgroup waits for a CU of its XCD although another XCD has one free.  segment_unit gives the workgroups of
+// one XCD a contiguous run of the units of a grid segment [s, s + n) (they share operand panels in that XCD's
+// L2); the runs differ by at most one unit and no workgroup is left without work.
+__device__ __forceinline__ int congruent_below(int y, int t) { return (t - y + 7) >> 3; }   // #{i in [0,t): i % 8 == y}
+__device__ __forceinline__ int segment_unit(int wg_global, int s, int n) {
+  const int x = wg_global & 7;
+  int before = 0;
+  for (int y = 0; y < 8; ++y)
+    if (y < x) before += congruent_below(y, s + n) - congruent_below(y, s);
+  return before + congruent_below(x, wg_global) - congruent_below(x, s);
+}
+
 // The same work with 256 x 256 tiles (sbp_mfma_big.h): one workgroup per CU, so the order of the grid
-// is the order in which CUs pick work up: the longer kind of tile first, the shorter kind next, the
-// streaming helpers (zero fill, column sums) last, where they fill the CUs that run out of tiles.
+// is the order in which the CUs of an XCD pick work up: the longer kind of tile first, the shorter kind next,
+// the streaming helpers (zero fill, column sums) last, where they fill the CUs that run out of tiles.
 __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int wg = blockIdx.x;
@@ -152,19 +166,18 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
     }
     return;
   }
-  bool is_dx;
-  if (a.dw_first) {
-    is_dx = wg >= a.n_dw;
-    if (is_dx) wg -= a.n_dw;
-  } else {
-    is_dx = wg < a.n_dx;
-    if (!is_dx) wg -= a.n_dx;
+  // which kind of unit: the three kinds lie in the grid in the order the host chose
+  int kind = 0, seg_start = 0, seg_n = 0;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    kind = a.seg_order[q];
+    seg_n = kind == 0 ? a.n_dx : (kind == 1 ? a.n_dw_big : a.n_dw - a.n_dw_big);
+    if (wg < seg_start + seg_n) break;
+    seg_start += seg_n;
   }
+  const int L = segment_unit(wg, seg_start, seg_n);
   const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
-  if (is_dx) {
-    const int ntiles = ((a.K + a.dx_bm - 1) / a.dx_bm) * tiles_n;
-    const int L = xcd_chunked_id(wg, ntiles);
-    if (L >= ntiles) return;
+  if (kind == 0) {
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
     if (a.dx_bm == 128)
       big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT);
@@ -172,15 +185,16 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
       big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT);
     return;
   }
-  const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
-  const int nsplit = (a.K + a.rows_per_split - 1) / a.rows_per_split;
-  const int ntiles = tiles_m * tiles_n * nsplit;
-  const int L = xcd_chunked_id(wg, ntiles);
-  if (L >= ntiles) return;
-  const int split = L / (tiles_m * tiles_n);
-  const int rem = L - split * tiles_m * tiles_n;
+  // dW unit: a tile over the kept rows of one split; the first n_big splits have rows_per_split rows each, the
+  // others rows_small
+  const int tiles_w = ((a.Cout + big::BT - 1) / big::BT) * tiles_n;
+  const int covered = min(a.K, a.n_big * a.rows_per_split);
+  const int sl = L / tiles_w;                                  // split within its kind
+  const int rem = L - sl * tiles_w;
   const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
-  const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
+  const int j0 = kind == 1 ? sl * a.rows_per_split : covered + sl * a.rows_small;
+  const int j1 = min(a.K, j0 + (kind == 1 ? a.rows_per_split : a.rows_small));
+  const int split = kind == 1 ? sl : a.n_big + sl;
   float* part = a.part + (long long)split * a.Cout * a.Cin;
   if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
   else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
@@ -383,75 +397,118 @@ static bool env_tile(const char* name, int* bm, int* bn, int* nw, int* kb) {
   return true;
 }
 
-// ---- large-tile engine: tile height of dX and number of dW splits -----------------------------------
-// One workgroup per CU and a grid ordered long units first is list scheduling; its finish time for n1
-// units of length l1 followed by n2 units of length l2 is simulated exactly (times in nanoseconds).
-static int64_t list_schedule_end(int64_t n1, int64_t l1, int64_t n2, int64_t l2) {
-  std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> cu;
-  for (int i = 0; i < kNumCU; ++i) cu.push(0);
-  int64_t end = 0;
-  auto run = [&](int64_t n, int64_t l) {
-    for (; n > 0; --n) {
-      const int64_t t = cu.top() + l;
-      cu.pop();
-      cu.push(t);
-      end = std::max(end, t);
-    }
-  };
-  run(n1, l1);
-  run(n2, l2);
-  return end;
-}
-
+// ---- large-tile engine: tile height of dX and the dW splits ----------------------------------------
+// Workgroup i of the grid goes to XCD i % 8, every XCD hands its workgroups in order to its 32 CUs, one per CU:
+// list scheduling per XCD.  The host simulates it from unit costs and takes the cheapest schedule.
 static constexpr int kBigMaxRowsPerSplit = 4096;   // row ids of a split in LDS next to the 128 KB ring
-// Unit costs measured on the device (timestamps inside the kernel, ViT-Base shapes), nanoseconds:
-static constexpr int64_t kNsStage256 = 600;        // one stage of 32 of a 256 x 256 tile (dX or dW)
-static constexpr int64_t kNsStage128 = 390;        // one stage of a 128 x 256 dX tile
-static constexpr int64_t kNsFixedDx256 = 6000;     // index loads, first stage, epilogue
-static constexpr int64_t kNsFixedDx128 = 3600;
-static constexpr int64_t kNsFixedDw = 6300;        // + the row-id table, ~1 ns per kept row of the split
-static constexpr double kReduceBytesPerNs = 3500;  // the reduction streams the partials at about 3.5 TB/s
+// Unit costs in nanoseconds: durations of the workgroups read from the device clock inside a training-like
+// step (operands cold, all CUs busy) for the four ViT-Base layer shapes: a straight line through the units of
+// 20 to 96 stages of 32.  The fixed part is the first stages' latency, the index tables and the epilogue (a
+// dW unit stores 256 KB of partial sums).
+static constexpr int64_t kNsStage256 = 750, kNsFixedDx256 = 6500;     // 256 x 256 dX tile
+static constexpr int64_t kNsStage128 = 450, kNsFixedDx128 = 8000;     // 128 x 256 dX tile
+static constexpr int64_t kNsStageDw = 667, kNsFixedDw = 10000;        // 256 x 256 dW unit
+static constexpr int64_t kNsFixedHelper = 1800;                       // zero-fill and column-sum blocks: fixed part
+static constexpr int64_t kHelperBytesPerNs = 50;                      //   and the rate at which one CU streams
+static constexpr double kReduceBytesPerNs = 2650;                     // the reduction streams the partials
 
 struct BigChoice {
-  int64_t K; int32_t Cin, Cout;
-  int splits, rps, dx_bm;
-  bool dw_first;
+  int64_t M, K; int32_t Cin, Cout;
+  int splits, rps, n_big, rows_small, dx_bm;
+  int seg_order[3];
   double fill;      // work / (CUs x finish time) of the simulated schedule
 };
 
-static BigChoice choose_big(int64_t K, int32_t Cin, int32_t Cout) {
-  thread_local BigChoice cache[8] = {};
+static int64_t congruent_below_host(int64_t y, int64_t t) { return (t - y + 7) >> 3; }
+
+// finish time of the grid: segments {count, unit length} in grid order
+static int64_t simulate_grid(const int64_t* n, const int64_t* l, int nseg) {
+  int64_t end = 0;
+  for (int x = 0; x < kNumXCD; ++x) {
+    std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> cu;
+    for (int i = 0; i < kNumCU / kNumXCD; ++i) cu.push(0);
+    int64_t start = 0;
+    for (int q = 0; q < nseg; ++q) {
+      const int64_t mine = congruent_below_host(x, start + n[q]) - congruent_below_host(x, start);
+      for (int64_t i = 0; i < mine; ++i) {
+        const int64_t t = cu.top() + l[q];
+        cu.pop();
+        cu.push(t);
+        end = std::max(end, t);
+      }
+      start += n[q];
+    }
+  }
+  return end;
+}
+
+static int big_zero_blocks(int64_t M) { return (int)std::min<int64_t>(128, std::max<int64_t>(8, ceil_div(M, 256))); }
+static int db_slice_rows_for(int64_t K) { return (int)std::max<int64_t>(kDbSliceRows, ceil_div(ceil_div(K, kMaxDbSlices), 8) * 8); }
+
+// The dW rows are cut into n_big long splits and, optionally, a few short ones: the short units are
+// dispatched last and fill the CUs that finish early, which evens out schedules whose unit count just
+// misses a multiple of the CU count.
+static BigChoice choose_big(int64_t M, int64_t K, int32_t Cin, int32_t Cout) {
+  thread_local BigChoice cache[32] = {};
   thread_local int next = 0;
   for (const BigChoice& c : cache)
-    if (c.K == K && c.Cin == Cin && c.Cout == Cout && c.splits > 0) return c;
+    if (c.M == M && c.K == K && c.Cin == Cin && c.Cout == Cout && c.splits > 0) return c;
   const int64_t tiles_n = ceil_div(Cin, big::BT);
   const int64_t tiles_w = ceil_div(Cout, big::BT) * tiles_n;
   const int64_t nk_x = Cout / big::KB;
-  BigChoice best{K, Cin, Cout, 0, 0, 256, false, 0.0};
+  // the helpers that share the launch (all of them assumed wanted)
+  const int64_t n_zero = big_zero_blocks(M);
+  const int64_t l_zero = kNsFixedHelper + (M - K) * Cin * 2 / n_zero / kHelperBytesPerNs;
+  const int64_t slice_rows = db_slice_rows_for(K);
+  const int64_t n_db = ceil_div(Cout, 256) * ceil_div(K, slice_rows);
+  const int64_t l_db = kNsFixedHelper + slice_rows * 512 / kHelperBytesPerNs;
+  BigChoice best{M, K, Cin, Cout, 0, 0, 0, 0, 256, {0, 1, 2}, 0.0};
   double best_cost = 0;
-  const int64_t s_min = ceil_div(K, kBigMaxRowsPerSplit), s_max = std::max<int64_t>(s_min, std::min<int64_t>(48, K / 256));
+  auto l_dw = [](int64_t rows) { return kNsFixedDw + kNsStageDw * ceil_div(rows, big::KB); };
+  static const int small_rows[] = {0, 256, 384, 512, 768, 1024, 1536};
   for (int bm : {256, 128}) {
     const int64_t n_dx = ceil_div(K, bm) * tiles_n;
     const int64_t l_dx = bm == 256 ? kNsFixedDx256 + kNsStage256 * nk_x : kNsFixedDx128 + kNsStage128 * nk_x;
-    for (int64_t sp = s_min; sp <= s_max; ++sp) {
-      const int64_t rps = ceil_div(ceil_div(K, sp), 64) * 64;
-      const int64_t ns = ceil_div(K, rps);
-      if (ns != sp && sp != s_min) continue;          // same split count as a smaller sp: already seen
-      const int64_t l_dw = kNsFixedDw + rps + kNsStage256 * (rps / big::KB);
-      const bool dw_first = l_dw > l_dx;
-      const int64_t end = dw_first ? list_schedule_end(tiles_w * ns, l_dw, n_dx, l_dx)
-                                   : list_schedule_end(n_dx, l_dx, tiles_w * ns, l_dw);
-      // the reduction kernel that follows reads every split's fp32 copy of dW and writes dW
-      const double cost = (double)end + 3000.0 + (double)(ns + 1) * Cout * Cin * 4.0 / kReduceBytesPerNs;
-      if (best.splits == 0 || cost < best_cost) {
-        best_cost = cost;
-        best.splits = (int)ns; best.rps = (int)rps; best.dw_first = dw_first; best.dx_bm = bm;
-        best.fill = (double)(n_dx * l_dx + tiles_w * ns * l_dw) / ((double)kNumCU * (double)end);
+    for (int64_t a : small_rows) {
+      for (int64_t ns = (a ? 1 : 0); ns <= (a ? 4 : 0); ++ns) {
+        if (ns * a >= K) break;
+        for (int64_t nb = 1; nb <= 16; ++nb) {
+          const int64_t A = ceil_div(ceil_div(K - ns * a, nb), 64) * 64;
+          if (A > kBigMaxRowsPerSplit || A <= a) continue;
+          const int64_t nb_real = a ? nb : ceil_div(K, A);
+          const int64_t rest = K - std::min<int64_t>(K, nb_real * A);
+          if (a && rest <= 0) continue;                        // the long splits already cover everything
+          const int64_t ns_real = a ? ceil_div(rest, a) : 0;
+          if (A < 512 && nb_real > 1) continue;                // splits shorter than 16 stages do not pay
+          const int64_t kn[3] = {n_dx, tiles_w * nb_real, tiles_w * ns_real};
+          const int64_t kl[3] = {l_dx, l_dw(std::min<int64_t>(A, K)), a ? l_dw(a) : 0};
+          int order[3] = {0, 1, 2};
+          std::sort(order, order + 3, [&](int x, int y) { return kl[x] > kl[y]; });   // longest kind first
+          const int64_t n[5] = {kn[order[0]], kn[order[1]], kn[order[2]], n_zero, n_db};
+          const int64_t l[5] = {kl[order[0]], kl[order[1]], kl[order[2]], l_zero, l_db};
+          const int64_t end = simulate_grid(n, l, 5);
+          const int64_t splits = nb_real + ns_real;
+          // the reduction kernel that follows reads every split's fp32 copy of dW and writes dW
+          const double cost = (double)end + 3000.0 + (double)(splits + 1) * Cout * Cin * 4.0 / kReduceBytesPerNs;
+          if (best.splits == 0 || cost < best_cost) {
+            best_cost = cost;
+            best.splits = (int)splits; best.rps = (int)A; best.n_big = (int)nb_real; best.rows_small = (int)(ns_real ? a : 0);
+            best.dx_bm = bm;
+            for (int q = 0; q < 3; ++q) best.seg_order[q] = order[q];
+            double work = 0;
+            for (int q = 0; q < 5; ++q) work += (double)n[q] * (double)l[q];
+            best.fill = work / ((double)kNumCU * (double)end);
+          }
+        }
       }
     }
   }
+  if (std::getenv("SBP_DEBUG_PLAN"))
+    std::fprintf(stderr, "sbp plan M=%lld K=%lld %d->%d: dx rows %d, %d long splits of %d rows, short splits of %d rows (%d splits), order %d%d%d, fill %.2f, cost %.1f us\n",
+                 (long long)M, (long long)K, Cin, Cout, best.dx_bm, best.n_big, best.rps, best.rows_small, best.splits, best.seg_order[0],
+                 best.seg_order[1], best.seg_order[2], best.fill, best_cost / 1e3);
   cache[next] = best;
-  next = (next + 1) % 8;
+  next = (next + 1) % 32;
   return best;
 }
 
@@ -469,21 +526,41 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
     const bool fits = Cout % big::KB == 0 && (uint64_t)M * (uint64_t)std::max(Cin, Cout) * 2u < (1ull << 32);
     // it pays where whole 256-wide tiles exist and the simulated schedule keeps the CUs reasonably busy
     const bool pays = !env && Cin >= big::BT && Cout >= big::BT && K >= 1024 &&
-                      choose_big(K, Cin, Cout).fill >= 0.45;
+                      choose_big(M, K, Cin, Cout).fill >= 0.45;
     p.big = fits && (forced || pays);
   }
+  bool two_sizes = false;
   if (p.big) {
-    const BigChoice c = choose_big(K, Cin, Cout);
+    const BigChoice c = choose_big(M, K, Cin, Cout);
     p.bm_w = p.bn_w = big::BT;
     p.kb = big::KB;
-    p.dw_first = c.dw_first;
     p.dx_bm = c.dx_bm;
     splits = c.splits;
+    p.rows_per_split = c.rps; p.n_big = c.n_big; p.rows_small = c.rows_small;
+    for (int q = 0; q < 3; ++q) p.seg_order[q] = c.seg_order[q];
+    two_sizes = true;
     if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : 256;   // debugging aids
-    if (const char* e = std::getenv("SBP_SPLITS")) {
+    char plan_var[48];
+    std::snprintf(plan_var, sizeof plan_var, "SBP_PLAN_%dx%d", Cin, Cout);   // a schedule by hand for one layer shape ...
+    const char* plan_env = std::getenv(plan_var);
+    if (!plan_env) plan_env = std::getenv("SBP_PLAN");                         // ... or for all: "bm,rows_big,n_big,rows_small"
+    if (const char* e = plan_env) {
+      int bm = 256, A = 0, nb = 1, a = 0;
+      if (std::sscanf(e, "%d,%d,%d,%d", &bm, &A, &nb, &a) == 4 && A >= 64 && A % 64 == 0 && A <= kBigMaxRowsPerSplit &&
+          nb >= 1 && a % 64 == 0 && a >= 0 && a <= A && (int64_t)nb * A < K + A && (a > 0 || (int64_t)nb * A >= K)) {
+        p.dx_bm = bm == 128 ? 128 : 256;
+        p.rows_per_split = A; p.n_big = (int)std::min<int64_t>(nb, ceil_div(K, A)); p.rows_small = a;
+        const int64_t rest = K - std::min<int64_t>(K, (int64_t)p.n_big * A);
+        if (rest <= 0) p.rows_small = 0;
+        splits = p.n_big + (p.rows_small ? (int)ceil_div(rest, p.rows_small) : 0);
+        p.seg_order[0] = 1; p.seg_order[1] = 0; p.seg_order[2] = 2;
+        if (const char* o = std::getenv("SBP_ORDER")) std::sscanf(o, "%d,%d,%d", &p.seg_order[0], &p.seg_order[1], &p.seg_order[2]);
+      }
+    }
+    if (const char* e = std::getenv("SBP_SPLITS")) {            // equal splits, dW units first
       splits = std::max<int>(std::atoi(e), (int)ceil_div(K, kBigMaxRowsPerSplit));
-      const int64_t rps_e = ceil_div(ceil_div(K, splits), 64) * 64;
-      p.dw_first = kNsFixedDw + kNsStage256 * (rps_e / big::KB) > (p.dx_bm == 256 ? kNsFixedDx256 + kNsStage256 * (Cout / big::KB) : kNsFixedDx128 + kNsStage128 * (Cout / big::KB));
+      two_sizes = false;
+      p.seg_order[0] = 1; p.seg_order[1] = 0; p.seg_order[2] = 2;
     }
   } else if (K > 0) {
     if (p.mfma) {
@@ -499,14 +576,18 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(K, 512), 64));
     }
   }
-  int64_t rps = K > 0 ? ceil_div(K, splits) : 0;
-  rps = ceil_div(rps, 64) * 64;
-  if (rps > 0) splits = (int)ceil_div(K, rps);
+  if (!two_sizes) {
+    int64_t rps = K > 0 ? ceil_div(K, splits) : 0;
+    rps = ceil_div(rps, 64) * 64;
+    if (rps > 0) splits = (int)ceil_div(K, rps);
+    p.rows_per_split = (int)rps;
+    p.n_big = splits;
+    p.rows_small = 0;
+  }
   p.splits = splits;
-  p.rows_per_split = (int)rps;
   size_t off = 0;
   p.off_partial = off;
-  p.db_slice_rows = (int)std::max<int64_t>(kDbSliceRows, ceil_div(ceil_div(K, kMaxDbSlices), 8) * 8);
+  p.db_slice_rows = db_slice_rows_for(K);
   p.db_slices = p.mfma ? (int)std::max<int64_t>(1, ceil_div(K, p.db_slice_rows)) : splits;
   off += align_up(((size_t)splits * Cout * Cin + (size_t)std::max(p.db_slices, splits) * Cout) * sizeof(float), 256);
   p.off_inv = off;
@@ -592,16 +673,19 @@ void launch_zero_dropped_rows(const int32_t* idx, const int32_t* inv, int64_t K,
 
 static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero, hipStream_t s) {
   // behind the ring: the row ids of a dW split (read one stage ahead) or the 256 output rows of a dX tile
-  const size_t lds = (size_t)big::RING + std::max<size_t>((size_t)(p.rows_per_split + 2 * big::KB), big::BT) * sizeof(int);
+  const size_t lds = (size_t)big::RING + std::max<size_t>((size_t)(std::max(p.rows_per_split, p.rows_small) + 2 * big::KB), big::BT) * sizeof(int);
   allow_big_lds(linear_big_kernel, lds);
   const long long tiles_n = ceil_div(a.Cin, big::BT);
-  a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M, 256))) : 0;
+  a.n_zero = want_zero ? big_zero_blocks(a.M) : 0;
   const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
   a.n_helper = a.n_zero + n_db;
   a.dx_bm = p.dx_bm;
-  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, p.dx_bm) * tiles_n, 8)) : 0;
-  a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, big::BT) * tiles_n * p.splits, 8)) : 0;
-  a.dw_first = p.dw_first ? 1 : 0;
+  a.n_dx = want_dx ? (int)(ceil_div(a.K, p.dx_bm) * tiles_n) : 0;
+  const long long tiles_w = ceil_div(a.Cout, big::BT) * tiles_n;
+  a.n_big = p.n_big; a.rows_small = p.rows_small;
+  a.n_dw_big = want_dw ? (int)(tiles_w * p.n_big) : 0;
+  a.n_dw = a.n_dw_big + (want_dw ? (int)(tiles_w * (p.splits - p.n_big)) : 0);
+  for (int q = 0; q < 3; ++q) a.seg_order[q] = p.seg_order[q];
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
   if (grid == 0) return;
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, linear_big_kernel, dim3(grid), dim3(256), lds, s, a);
