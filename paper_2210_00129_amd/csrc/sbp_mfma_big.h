@@ -401,6 +401,7 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   pb.rows = nullptr;
   if (GATHER) {
     int* rows = reinterpret_cast<int*>(smem + RING);        // one stage more than the split has: ids are read ahead
+#pragma unroll 4
     for (int i = t; i < (nk + 1) * KB; i += 256) rows[i] = idx[min(j0 + i, j1 - 1)];
     __syncthreads();
     pb.rows = rows;
