@@ -28,5 +28,7 @@ from .sbp_oracle import (  # noqa: F401
     layernorm_rows,
     backward_layernorm,
     forward_cache_patches,
+    attention_scores,
+    backward_attention,
     backward_downsample,
 )

@@ -46,6 +46,20 @@ What follows the paper and what is this repository's own reading:
   that for s >= k the neighbour effects vanish and the layer behaves like a
   point-wise one: every kept output position owns its own p x p patch of inputs.
   The oracle writes the convolution backward out position by position.
+* ``backward_attention``: the supplement's section "Gradient Calculation of
+  Attention Layers" applies the gradient dropout to the attention map M
+  (``eq:sbp_attn_drop_query`` .. ``eq:sbp_sep_on_key``) and writes the case
+  "drop on the query" out; the main text (section Design Strategies, "How to
+  apply SBP on MHSA?") picks "Drop QKV" for image transformers and leaves its
+  derivation to the reader.  The reading taken here: the forward is the
+  ordinary full attention; in the backward every entry of dM whose query OR key
+  token is dropped is set to zero, the kept entries keep their exact value
+  (``eq:grad_qkv`` with the ordinary softmax derivative over the whole row),
+  and the gradients of Q, K and V are taken at the kept tokens only (zero at the
+  dropped ones).  dA arrives with zero rows at the dropped tokens (the chain
+  rule effect of the section "Chain Rule Effect of Transformer Blocks").
+  Of the two forms of dQ the supplement prints, the shape-consistent one is
+  used: dQ = dM K / sqrt(d), dK = dM^T Q / sqrt(d).
 """
 from __future__ import annotations
 
@@ -373,3 +387,63 @@ def backward_downsample(dY, idx, X, Wc, p):
                 dWc[:, dy, dx, :] += np.outer(g, x)
                 dX[b, p * yo + dy, p * xo + dx] = g @ Wc[:, dy, dx, :]
     return dWc, db, dX
+
+
+def attention_scores(Q, K, scale):
+    """M = Q K^T * scale and S = softmax(M) over the keys, per sample and head (``eq:attention``).
+
+    Q, K: [B, n, h, d].  Returns M, S: [B, h, n, n].
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    B, n, h, d = Q.shape
+    M = np.empty((B, h, n, n))
+    S = np.empty((B, h, n, n))
+    for b in range(B):
+        for a in range(h):
+            m = (Q[b, :, a, :] @ K[b, :, a, :].T) * scale
+            e = np.exp(m - m.max(axis=1, keepdims=True))
+            M[b, a] = m
+            S[b, a] = e / e.sum(axis=1, keepdims=True)
+    return M, S
+
+
+def backward_attention(dA_k, Q, K, V, keep, scale):
+    """Backward of scaled dot-product attention with the gradient dropout on the attention map
+    ("Drop QKV": section Design Strategies; supplement ``eq:grad_qkv``, ``eq:sbp_sep_on_query``,
+    ``eq:sbp_sep_on_key`` carried over to dropped keys and values).
+
+    Q, K, V : [B, n, h, d]  the full forward tensors of one attention layer
+    keep    : [B, n_k]      kept token positions of every sample (ascending)
+    dA_k    : [B, n_k, h, d] gradient of the attention output at the kept tokens (zero elsewhere)
+    Returns dQ_k, dK_k, dV_k : [B, n_k, h, d], the gradients at the kept tokens (zero elsewhere).
+    """
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    V = np.asarray(V, dtype=np.float64)
+    dA_k = np.asarray(dA_k, dtype=np.float64)
+    keep = np.asarray(keep)
+    B, n, h, d = Q.shape
+    n_k = keep.shape[1]
+    _, S = attention_scores(Q, K, scale)
+    dQ_k = np.zeros((B, n_k, h, d))
+    dK_k = np.zeros((B, n_k, h, d))
+    dV_k = np.zeros((B, n_k, h, d))
+    for b in range(B):
+        kp = keep[b]
+        for a in range(h):
+            dA = np.zeros((n, d))
+            dA[kp] = dA_k[b, :, a, :]                       # dA^drop = 0
+            dS = dA @ V[b, :, a, :].T                       # from A = S V
+            s = S[b, a]
+            dM = s * (dS - (s * dS).sum(axis=1, keepdims=True))   # softmax derivative, whole rows
+            mask = np.zeros((n, n))
+            mask[np.ix_(kp, kp)] = 1.0
+            dM = dM * mask                                  # dM^drop = 0: dropped query or dropped key
+            dQ = (dM @ K[b, :, a, :]) * scale
+            dK = (dM.T @ Q[b, :, a, :]) * scale
+            dV = s.T @ dA
+            dQ_k[b, :, a, :] = dQ[kp]
+            dK_k[b, :, a, :] = dK[kp]
+            dV_k[b, :, a, :] = dV[kp]                       # V's gradient is taken at the kept tokens only
+    return dQ_k, dK_k, dV_k

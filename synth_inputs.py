@@ -112,3 +112,27 @@ def dwconv_case(B: int, H: int, W: int, C: int, ks: int, seed: int, dtype: str):
 def to_f64(t: torch.Tensor):
     """Exact widening of a stored tensor to a float64 numpy array."""
     return t.detach().cpu().to(torch.float64).numpy()
+
+
+def attention_case(B: int, n: int, h: int, d: int, seed: int, dtype: str):
+    """Tensors of one self-attention layer, token-major as a qkv projection leaves them.
+
+    Returns qkv [B*n, 3*h*d] (q | k | v thirds, each head-major [h, d]) and dA [B*n, h*d] in the
+    storage type: unit-variance queries, keys and values (scores q.k/sqrt(d) of unit variance, the
+    regime of a trained ViT's pre-softmax logits) and a unit-variance output gradient.
+    """
+    qkv = normal((B * n, 3 * h * d), 1.0, seed * 7919 + 21, dtype)
+    dA = normal((B * n, h * d), 1.0, seed * 7919 + 22, dtype)
+    return qkv, dA
+
+
+def attention_forward(qkv: torch.Tensor, B: int, n: int, h: int, d: int, scale: float):
+    """The model's forward over all n tokens (library softmax, float64): the attention output
+    A [B*n, h*d] and the row-wise log-sum-exp of the scaled scores lse [B*n, h], both float64.
+    A training forward hands these to the backward; they are inputs of the path, not part of it."""
+    x = qkv.detach().cpu().to(torch.float64).view(B, n, 3, h, d)
+    q, k, v = (x[:, :, i].permute(0, 2, 1, 3) for i in range(3))          # [B, h, n, d]
+    m = torch.matmul(q, k.transpose(-1, -2)) * scale
+    lse = torch.logsumexp(m, dim=-1)                                      # [B, h, n]
+    A = torch.matmul(torch.softmax(m, dim=-1), v)                         # [B, h, n, d]
+    return A.permute(0, 2, 1, 3).reshape(B * n, h * d).contiguous(), lse.permute(0, 2, 1).reshape(B * n, h).contiguous()
