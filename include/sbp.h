@@ -237,6 +237,41 @@ int32_t sbp_act_forward_rows(const void* Z_k, int64_t K, int32_t C, int32_t dtyp
 int32_t sbp_act_backward_rows(const void* dH_k, const void* Z_k, int64_t K, int32_t C, int32_t dtype,
                               int32_t act, void* dZ_k, void* stream);
 
+/*
+ * Backward of scaled dot-product attention on the kept tokens: the variant "Drop QKV" that the paper picks
+ * for image transformers (main text, section Design Strategies, "How to apply SBP on MHSA?"; supplement,
+ * section Gradient Calculation of Attention Layers: eq:attention, eq:grad_qkv, and the gradient dropout on
+ * the attention map M of eq:sbp_sep_on_query / eq:sbp_sep_on_key, carried over to dropped keys and values).
+ * The forward is the ordinary attention over all n tokens of a sample; in the backward every entry of dM
+ * whose query or key token is dropped is zero, the kept entries are exact, and dQ, dK, dV are produced at
+ * the kept tokens only.  Per sample b and head a, with i, j running over the n_k kept tokens:
+ *   S_ij  = exp(scale * q_i.k_j - lse_i)
+ *   dV_j  = sum_i S_ij dA_i
+ *   dM_ij = S_ij * (dA_i.v_j - dA_i.A_i)      (the softmax row term sum_l S_il dS_il over ALL keys l equals
+ *                                              dA_i.A_i because A_i = sum_l S_il v_l)
+ *   dQ_i  = scale * sum_j dM_ij k_j           dK_j = scale * sum_i dM_ij q_i
+ * (of the two forms of dQ the supplement prints, the shape-consistent one).  Every sample keeps the same
+ * number n_k of tokens (the samplers of this library do); all tensors hold kept tokens only, sample-major:
+ * row b * n_k + t is the t-th kept token of sample b, i.e. the rows sbp_forward_cache gathers.
+ *   qkv_k   device, in,  [B*n_k, 3*h*d] of `dtype`: kept rows of the qkv projection's output, q | k | v thirds,
+ *           each third head-major [h, d]
+ *   A_k     device, in,  [B*n_k, h*d]  kept rows of the attention output (the proj layer's cached input)
+ *   dA_k    device, in,  [B*n_k, h*d]  gradient of the attention output at the kept rows (the proj layer's
+ *           backward with SBP_FLAG_DX_COMPACT writes exactly this)
+ *   lse_k   device, in,  [B*n_k, h] fp32: natural-log sum over ALL n keys of exp(scale * q_i.k_l), kept queries
+ *   dqkv_k  device, out, [B*n_k, 3*h*d] of `dtype`: dQ | dK | dV in the layout of qkv_k; it is the compact
+ *           dY (SBP_FLAG_DY_COMPACT) of the qkv projection's backward
+ *   d       head dimension: 16, 32, 64 or 128.   scale: usually 1/sqrt(d).
+ * All pointers 16-byte aligned.  fp32 arithmetic and accumulation; in bf16 the probabilities S and dM are
+ * rounded to bf16 before the second products (matrix cores), outputs rounded once.  Deterministic.
+ * sbp_backward_attention_engine (host only) reports which kernel serves a size: 1 = matrix-core kernel
+ * (bf16, d in {32, 64, 128}, the kept tokens of one head fit LDS: n_k <= 256 at d = 64), 0 = plain kernel.
+ */
+int32_t sbp_backward_attention_engine(int32_t n_k, int32_t d, int32_t dtype);
+int32_t sbp_backward_attention(const void* qkv_k, const void* A_k, const void* dA_k, const float* lse_k,
+                               int32_t B, int32_t n_k, int32_t h, int32_t d, float scale, int32_t dtype,
+                               void* dqkv_k, void* stream);
+
 /* Host only.  Bytes of workspace sbp_backward_layernorm needs (0 on invalid sizes). */
 size_t sbp_backward_layernorm_workspace(int64_t M, int64_t K, int32_t C, int32_t dtype, uint32_t flags);
 
@@ -280,7 +315,8 @@ int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* g
 #define SBP_PROF_DWCONV_DX   7
 #define SBP_PROF_DWCONV_DW   8
 #define SBP_PROF_OTHER       9
-#define SBP_PROF_NCLASSES   10
+#define SBP_PROF_ATTENTION  10   /* attention backward on the kept tokens */
+#define SBP_PROF_NCLASSES   11
 #define SBP_PROF_RESET     (-1)
 int32_t sbp_profile_enable(int32_t on);
 int32_t sbp_profile_read(int32_t which, double* total_ms, int64_t* launches);

@@ -238,8 +238,31 @@ def backward_dwconv(dY, idx, X, Wd, inv=None, want=("dWd", "db", "dX"), dWd=None
     return dWd, db, dX
 
 
+def backward_attention_engine(n_k, d, dtype_code) -> str:
+    """Which kernel serves an attention backward of n_k kept tokens per sample: 'mfma' or 'plain'."""
+    e = int(_lib.lib().sbp_backward_attention_engine(n_k, d, dtype_code))
+    if e < 0:
+        raise ValueError(_lib.lib().sbp_last_error().decode())
+    return "mfma" if e == 1 else "plain"
+
+
+def backward_attention(qkv_k, A_k, dA_k, lse_k, B, h, d, scale, out=None):
+    """Attention backward on the kept tokens ("Drop QKV").  qkv_k: [B*n_k, 3*h*d]; A_k, dA_k: [B*n_k, h*d];
+    lse_k: fp32 [B*n_k, h].  Returns dqkv_k [B*n_k, 3*h*d] (dQ | dK | dV)."""
+    rows = qkv_k.shape[0]
+    if rows % B:
+        raise ValueError("rows of qkv_k must be B * n_k")
+    n_k = rows // B
+    if out is None:
+        out = torch.empty_like(qkv_k)
+    _lib.check(_lib.lib().sbp_backward_attention(
+        _dev(qkv_k, "qkv_k"), _dev(A_k, "A_k"), _dev(dA_k, "dA_k"), _dev(lse_k, "lse_k"), B, n_k, h, d, float(scale),
+        _dtype_code(qkv_k), _dev(out, "dqkv_k"), _stream(qkv_k.device)))
+    return out
+
+
 PROF_CLASSES = ("sample", "gather", "dw_gemm", "dx_gemm", "reduce", "colsum", "zero_rows", "dwconv_dx",
-                "dwconv_dw", "other")
+                "dwconv_dw", "other", "attention")
 
 
 def profile_enable(on: bool) -> None:

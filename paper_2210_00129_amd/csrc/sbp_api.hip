@@ -253,6 +253,34 @@ int32_t sbp_act_backward_rows(const void* dHk, const void* Zk, int64_t K, int32_
   return launch_act_rows(dHk, Zk, K * (int64_t)C, dtype, act, true, dZk, static_cast<hipStream_t>(stream));
 }
 
+static int32_t validate_attention(int32_t B, int32_t n_k, int32_t h, int32_t d, int32_t dtype) {
+  if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (B < 1 || n_k < 0 || h < 1) return fail(SBP_ERR_SHAPE, "bad shape B=%d n_k=%d h=%d", B, n_k, h);
+  if (d != 16 && d != 32 && d != 64 && d != 128) return fail(SBP_ERR_SHAPE, "head dimension %d is not 16, 32, 64 or 128", d);
+  if ((int64_t)B * n_k > INT32_MAX || (int64_t)h * d * 3 > INT32_MAX || h > 65535 || B > 65535)
+    return fail(SBP_ERR_SHAPE, "B=%d n_k=%d h=%d d=%d overflows the row / grid range", B, n_k, h, d);
+  return SBP_OK;
+}
+
+int32_t sbp_backward_attention_engine(int32_t n_k, int32_t d, int32_t dtype) {
+  if (validate_attention(1, n_k, 1, d, dtype) != SBP_OK) return -1;
+  return attention_engine(n_k, d, dtype);
+}
+
+int32_t sbp_backward_attention(const void* qkv_k, const void* A_k, const void* dA_k, const float* lse_k, int32_t B,
+                               int32_t n_k, int32_t h, int32_t d, float scale, int32_t dtype, void* dqkv_k,
+                               void* stream) {
+  int32_t st = validate_attention(B, n_k, h, d, dtype);
+  if (st != SBP_OK) return st;
+  if (!(scale == scale) || scale <= 0.f) return fail(SBP_ERR_SHAPE, "scale must be positive");
+  if (n_k == 0) return SBP_OK;
+  if (!qkv_k || !A_k || !dA_k || !lse_k || !dqkv_k) return fail(SBP_ERR_NULL, "qkv_k, A_k, dA_k, lse_k or dqkv_k is NULL");
+  if (((uintptr_t)qkv_k | (uintptr_t)A_k | (uintptr_t)dA_k | (uintptr_t)dqkv_k) & 15)
+    return fail(SBP_ERR_SHAPE, "tensors must be 16-byte aligned");
+  return launch_backward_attention(qkv_k, A_k, dA_k, lse_k, B, n_k, h, d, scale, dtype, dqkv_k,
+                                   static_cast<hipStream_t>(stream));
+}
+
 static int32_t validate_layernorm(int64_t M, int64_t K, int32_t C, int32_t dtype, uint32_t flags) {
   if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
   if (flags & ~(SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW)) return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);

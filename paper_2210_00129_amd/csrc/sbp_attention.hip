@@ -1,0 +1,402 @@
+// Backward of scaled dot-product attention on the kept tokens (paper: main text section Design Strategies,
+// "How to apply SBP on MHSA?", variant "Drop QKV"; supplement section Gradient Calculation of Attention
+// Layers, eq:grad_qkv with the gradient dropout of eq:sbp_sep_on_query / eq:sbp_sep_on_key applied to dropped
+// queries AND dropped keys).  Per sample and head, over the kept tokens i, j only:
+//   S_ij  = exp(scale q_i.k_j - lse_i)          lse_i: log-sum-exp of the forward over ALL keys
+//   dV_j  = sum_i S_ij dA_i
+//   dM_ij = S_ij (dA_i.v_j - dA_i.A_i)          the softmax row term sum_l S_il dS_il equals dA_i.A_i (A = S V)
+//   dQ_i  = scale sum_j dM_ij k_j,   dK_j = scale sum_i dM_ij q_i
+// Two kernels: an MFMA kernel for bf16 (one workgroup per sample and head, all kept tokens of the head in
+// LDS) and a plain fp32-arithmetic kernel for fp32 tensors and for sizes beyond the LDS budget.
+#include <cstdlib>
+#include <cstring>
+
+#include "sbp_internal.h"
+#include "sbp_mfma_gemm.h"
+
+namespace sbp {
+
+static constexpr float kLog2e = 1.4426950408889634f;
+
+// ------------------------------------------------------------------------------------------------
+// plain kernel: an "owner" token per group of d/16 lanes; PHASE 0 owns a key (dK, dV, loop over the
+// queries), PHASE 1 owns a query (dQ, loop over the keys).  Sums run in token order: deterministic.
+// ------------------------------------------------------------------------------------------------
+template <typename T> struct AtIO;
+template <> struct AtIO<uint16_t> {
+  static __device__ __forceinline__ void load16(const uint16_t* p, float (&v)[16]) {
+    const uint4 a = reinterpret_cast<const uint4*>(p)[0], b = reinterpret_cast<const uint4*>(p)[1];
+    const uint32_t w[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { v[2 * i] = bf16_lo(w[i]); v[2 * i + 1] = bf16_hi(w[i]); }
+  }
+  static __device__ __forceinline__ void store16(uint16_t* p, const float (&v)[16]) {
+    uint32_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = bf16_pack(v[2 * i], v[2 * i + 1]);
+    reinterpret_cast<uint4*>(p)[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    reinterpret_cast<uint4*>(p)[1] = make_uint4(w[4], w[5], w[6], w[7]);
+  }
+};
+template <> struct AtIO<float> {
+  static __device__ __forceinline__ void load16(const float* p, float (&v)[16]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float4 a = reinterpret_cast<const float4*>(p)[i];
+      v[4 * i] = a.x; v[4 * i + 1] = a.y; v[4 * i + 2] = a.z; v[4 * i + 3] = a.w;
+    }
+  }
+  static __device__ __forceinline__ void store16(float* p, const float (&v)[16]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) reinterpret_cast<float4*>(p)[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+  }
+};
+
+__device__ __forceinline__ float dot16(const float (&a)[16], const float (&b)[16]) {
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s = fmaf(a[i], b[i], s);
+  return s;
+}
+__device__ __forceinline__ float group_sum(float v, int lanes) {   // over `lanes` (1, 2, 4 or 8) adjacent lanes
+  for (int m = 1; m < lanes; m <<= 1) v += __shfl_xor(v, m);
+  return v;
+}
+
+template <typename T, int PHASE>
+__global__ void __launch_bounds__(256) attn_bwd_plain_kernel(const T* __restrict__ qkv, const T* __restrict__ A,
+                                                              const T* __restrict__ dA, const float* __restrict__ lse,
+                                                              int n_k, int h, int d, float scale, T* __restrict__ dqkv) {
+  const int cper = d / 16, owners = 256 / cper;
+  const int o = blockIdx.x * owners + (int)threadIdx.x / cper, c = (int)threadIdx.x % cper;
+  const int head = blockIdx.y, b = blockIdx.z;
+  const int tok = min(o, n_k - 1);
+  const long long row0 = (long long)b * n_k, ldq = 3LL * h * d, lda = (long long)h * d;
+  const int col = head * d + 16 * c;
+  const T* q_base = qkv + col;
+  const T* k_base = qkv + (long long)h * d + col;
+  const T* v_base = qkv + 2LL * h * d + col;
+  float own1[16], own2[16], acc1[16], acc2[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc1[i] = acc2[i] = 0.f;
+  if (PHASE == 0) {
+    AtIO<T>::load16(k_base + (row0 + tok) * ldq, own1);
+    AtIO<T>::load16(v_base + (row0 + tok) * ldq, own2);
+    for (int t = 0; t < n_k; ++t) {
+      float q[16], g[16], a[16];
+      AtIO<T>::load16(q_base + (row0 + t) * ldq, q);
+      AtIO<T>::load16(dA + (row0 + t) * lda + col, g);
+      AtIO<T>::load16(A + (row0 + t) * lda + col, a);
+      const float s = group_sum(dot16(q, own1), cper);
+      const float dp = group_sum(dot16(g, own2), cper);
+      const float delta = group_sum(dot16(g, a), cper);
+      const float p = expf(scale * s - lse[(row0 + t) * h + head]);
+      const float ds = p * (dp - delta) * scale;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        acc2[i] = fmaf(p, g[i], acc2[i]);       // dV_j += S_ij dA_i
+        acc1[i] = fmaf(ds, q[i], acc1[i]);      // dK_j += scale dM_ij q_i
+      }
+    }
+    if (o < n_k) {
+      AtIO<T>::store16(dqkv + (row0 + o) * ldq + (long long)h * d + col, acc1);
+      AtIO<T>::store16(dqkv + (row0 + o) * ldq + 2LL * h * d + col, acc2);
+    }
+  } else {
+    float a[16];
+    AtIO<T>::load16(q_base + (row0 + tok) * ldq, own1);
+    AtIO<T>::load16(dA + (row0 + tok) * lda + col, own2);
+    AtIO<T>::load16(A + (row0 + tok) * lda + col, a);
+    const float delta = group_sum(dot16(own2, a), cper);
+    const float l = lse[(row0 + tok) * h + head];
+    for (int t = 0; t < n_k; ++t) {
+      float k[16], v[16];
+      AtIO<T>::load16(k_base + (row0 + t) * ldq, k);
+      AtIO<T>::load16(v_base + (row0 + t) * ldq, v);
+      const float s = group_sum(dot16(own1, k), cper);
+      const float dp = group_sum(dot16(own2, v), cper);
+      const float p = expf(scale * s - l);
+      const float ds = p * (dp - delta) * scale;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc1[i] = fmaf(ds, k[i], acc1[i]);   // dQ_i += scale dM_ij k_j
+    }
+    if (o < n_k) AtIO<T>::store16(dqkv + (row0 + o) * ldq + col, acc1);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// MFMA kernel (bf16).  One workgroup of 4 wavefronts per (sample, head).  LDS: the kept rows of q, k, v
+// and dA of the head as [NPAD][D] tiles (rows padded with zeros to a multiple of 32, pitch 2 D + 16
+// bytes: 16-byte reads of 16 consecutive rows and the transposing reads hit distinct banks), and the
+// per-token tables lse * log2(e) and delta = dA.A.
+//
+// v_mfma_f32_32x32x16_bf16 register layouts (lane l, u = l >> 5):  A[row l & 31][k 8u .. 8u+7],
+// B[k 8u .. 8u+7][col l & 31],  C register v = C[row 8 (v >> 2) + 4u + (v & 3)][col l & 31].
+// Phase 1, wavefront = block of 32 keys j, loop over blocks of 32 queries i:
+//   S = Q_i K_j^T and dP = dA_i V_j^T   (operands: 16-byte row reads, contraction over the head dim)
+//   P = exp2(S c - lse_i),  dS = P (dP - delta_i)          in the C layout: rows i, column j = lane
+//   dV_j^T += dA_i^T P,  dK_j^T += Q_i^T dS                 contraction over i: C registers 8 ks .. 8 ks + 7
+//     hold rows 16 ks + 4u + (0..3) and 16 ks + 8 + 4u + (0..3) of the lane's column, which is a valid B
+//     operand if the A operand lists the same rows: two ds_read_b64_tr_b16 of those 4 + 4 token rows.
+// Phase 2, wavefront = block of 32 queries i, loop over blocks of keys j: the transposes S^T = K_j Q_i^T,
+//   dP^T = V_j dA_i^T (lse_i and delta_i are then per-lane scalars), dQ_i^T += K_j^T dS^T.
+// Recomputing S and dP in phase 2 costs 2 of 7 products and saves every cross-wavefront reduction:
+// results are deterministic.  Padded rows are zero, so padded queries add nothing (dA = 0, delta = 0) and
+// padded keys add nothing to dQ (k = 0); their own outputs are not stored.
+// ------------------------------------------------------------------------------------------------
+template <int D>
+struct AttnLds {
+  static constexpr int PITCH = 2 * D + 16;
+  static size_t bytes(int npad) { return (size_t)4 * npad * PITCH + (size_t)2 * npad * sizeof(float); }
+};
+
+__device__ __forceinline__ bf16x8_t pack8(const f32x16_t& c, int ks) {
+  uint32_t w[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) w[e] = bf16_pack(c[8 * ks + 2 * e], c[8 * ks + 2 * e + 1]);
+  return __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+}
+
+// A operand [32 head-dim rows from dcol0][16 tokens]: token rows row0 + 4u + (0..3) and row0 + 8 + 4u + (0..3)
+template <int PITCH>
+__device__ __forceinline__ bf16x8_t read_tr_tokens(const char* tile, int row0, int dcol0, int lane) {
+  const int g = lane >> 4, i = lane & 15;
+  const char* p = tile + (row0 + 4 * (g >> 1) + (i >> 2)) * PITCH + (dcol0 + 16 * (g & 1) + 4 * (i & 3)) * 2;
+  const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p));
+  const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((SBP_LDS s16x4_t*)(p + 8 * PITCH));
+  return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) attn_bwd_mfma_kernel(const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ A,
+                                                             const uint16_t* __restrict__ dA, const float* __restrict__ lse,
+                                                             int n_k, int h, float scale, uint16_t* __restrict__ dqkv) {
+  constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32, CH = D / 8;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int npad = (n_k + 31) & ~31, nblk = npad >> 5;
+  char* tq = smem;
+  char* tk = tq + npad * PITCH;
+  char* tv = tk + npad * PITCH;
+  char* tg = tv + npad * PITCH;                                   // dA
+  float* lse_s = reinterpret_cast<float*>(tg + npad * PITCH);     // lse * log2(e)
+  float* delta_s = lse_s + npad;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, u = lane >> 5;
+  const int head = blockIdx.x, b = blockIdx.y;
+  const long long row0 = (long long)b * n_k, ldq = 3LL * h * D, lda = (long long)h * D;
+
+  // ---- load: 16-byte pieces, CH per token and tensor; delta from the dA and A pieces
+  for (int p = t; p < npad * CH; p += 256) {
+    const int tok = p / CH, ch = p % CH;
+    uint4 q = make_uint4(0, 0, 0, 0), k = q, v = q, g = q, a = q;
+    if (tok < n_k) {
+      const uint16_t* r = qkv + (row0 + tok) * ldq + head * D + 8 * ch;
+      q = *reinterpret_cast<const uint4*>(r);
+      k = *reinterpret_cast<const uint4*>(r + (long long)h * D);
+      v = *reinterpret_cast<const uint4*>(r + 2LL * h * D);
+      g = *reinterpret_cast<const uint4*>(dA + (row0 + tok) * lda + head * D + 8 * ch);
+      a = *reinterpret_cast<const uint4*>(A + (row0 + tok) * lda + head * D + 8 * ch);
+    }
+    const int off = tok * PITCH + ch * 16;
+    *reinterpret_cast<uint4*>(tq + off) = q;
+    *reinterpret_cast<uint4*>(tk + off) = k;
+    *reinterpret_cast<uint4*>(tv + off) = v;
+    *reinterpret_cast<uint4*>(tg + off) = g;
+    const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, aw[4] = {a.x, a.y, a.z, a.w};
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
+    for (int m = 1; m < CH; m <<= 1) s += __shfl_xor(s, m);
+    if (ch == 0) delta_s[tok] = s;
+  }
+  for (int i = t; i < npad; i += 256) lse_s[i] = i < n_k ? lse[(row0 + i) * h + head] * kLog2e : 0.f;
+  __syncthreads();
+
+  const float c2 = scale * kLog2e;
+  const int lrow = lane & 31;
+  const int foff = lrow * PITCH + 16 * u;              // 16-byte operand read of row (lane & 31), k chunk 8u
+
+  // ---- phase 1: dK, dV of the key blocks of this wavefront
+  for (int jb = wave; jb < nblk; jb += 4) {
+    f32x16_t dv[DB], dk[DB];
+#pragma unroll
+    for (int x = 0; x < DB; ++x)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dv[x][e] = dk[x][e] = 0.f;
+    bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8_t*>(tk + jb * 32 * PITCH + foff + ks * 32);
+      vf[ks] = *reinterpret_cast<const bf16x8_t*>(tv + jb * 32 * PITCH + foff + ks * 32);
+    }
+    for (int ib = 0; ib < nblk; ++ib) {
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(tq + ib * 32 * PITCH + foff + ks * 32);
+        const bf16x8_t gf = *reinterpret_cast<const bf16x8_t*>(tg + ib * 32 * PITCH + foff + ks * 32);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], s, 0, 0, 0);      // rows i, columns j
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float4 l4 = *reinterpret_cast<const float4*>(lse_s + ib * 32 + 8 * q4 + 4 * u);
+        const float4 d4 = *reinterpret_cast<const float4*>(delta_s + ib * 32 + 8 * q4 + 4 * u);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = __builtin_amdgcn_exp2f(s[4 * q4 + e] * c2 - lv[e]);
+          s[4 * q4 + e] = p;
+          dp[4 * q4 + e] = p * (dp[4 * q4 + e] - dl[e]);
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8_t pf = pack8(s, ks), dsf = pack8(dp, ks);
+#pragma unroll
+        for (int x = 0; x < DB; ++x) {
+          const bf16x8_t gt = read_tr_tokens<PITCH>(tg, ib * 32 + 16 * ks, 32 * x, lane);
+          const bf16x8_t qt = read_tr_tokens<PITCH>(tq, ib * 32 + 16 * ks, 32 * x, lane);
+          dv[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf, dv[x], 0, 0, 0);   // rows head dim, columns j
+          dk[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[x], 0, 0, 0);
+        }
+      }
+    }
+    const int j = jb * 32 + lrow;
+    if (j < n_k) {
+      uint16_t* o = dqkv + (row0 + j) * ldq + head * D;
+#pragma unroll
+      for (int x = 0; x < DB; ++x)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int dcol = 32 * x + 8 * q4 + 4 * u;
+          uint2 w;
+          w.x = bf16_pack(dk[x][4 * q4] * scale, dk[x][4 * q4 + 1] * scale);
+          w.y = bf16_pack(dk[x][4 * q4 + 2] * scale, dk[x][4 * q4 + 3] * scale);
+          *reinterpret_cast<uint2*>(o + (long long)h * D + dcol) = w;
+          w.x = bf16_pack(dv[x][4 * q4], dv[x][4 * q4 + 1]);
+          w.y = bf16_pack(dv[x][4 * q4 + 2], dv[x][4 * q4 + 3]);
+          *reinterpret_cast<uint2*>(o + 2LL * h * D + dcol) = w;
+        }
+    }
+  }
+
+  // ---- phase 2: dQ of the query blocks of this wavefront
+  for (int ib = wave; ib < nblk; ib += 4) {
+    f32x16_t dq[DB];
+#pragma unroll
+    for (int x = 0; x < DB; ++x)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[x][e] = 0.f;
+    bf16x8_t qf[KS], gf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8_t*>(tq + ib * 32 * PITCH + foff + ks * 32);
+      gf[ks] = *reinterpret_cast<const bf16x8_t*>(tg + ib * 32 * PITCH + foff + ks * 32);
+    }
+    const float l = lse_s[ib * 32 + lrow], dl = delta_s[ib * 32 + lrow];
+    for (int jb = 0; jb < nblk; ++jb) {
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(tk + jb * 32 * PITCH + foff + ks * 32);
+        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(tv + jb * 32 * PITCH + foff + ks * 32);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);      // rows j, columns i
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = __builtin_amdgcn_exp2f(s[e] * c2 - l);
+        dp[e] = p * (dp[e] - dl);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8_t dsf = pack8(dp, ks);
+#pragma unroll
+        for (int x = 0; x < DB; ++x) {
+          const bf16x8_t kt = read_tr_tokens<PITCH>(tk, jb * 32 + 16 * ks, 32 * x, lane);
+          dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dq[x], 0, 0, 0);   // rows head dim, columns i
+        }
+      }
+    }
+    const int i = ib * 32 + lrow;
+    if (i < n_k) {
+      uint16_t* o = dqkv + (row0 + i) * ldq + head * D;
+#pragma unroll
+      for (int x = 0; x < DB; ++x)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          uint2 w;
+          w.x = bf16_pack(dq[x][4 * q4] * scale, dq[x][4 * q4 + 1] * scale);
+          w.y = bf16_pack(dq[x][4 * q4 + 2] * scale, dq[x][4 * q4 + 3] * scale);
+          *reinterpret_cast<uint2*>(o + 32 * x + 8 * q4 + 4 * u) = w;
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+static constexpr size_t kAttnMaxLds = 160 * 1024;
+
+static size_t attn_lds_bytes(int n_k, int d) {
+  const int npad = (n_k + 31) & ~31;
+  return d == 32 ? AttnLds<32>::bytes(npad) : d == 64 ? AttnLds<64>::bytes(npad) : AttnLds<128>::bytes(npad);
+}
+
+// 1: MFMA kernel, 0: plain kernel
+int attention_engine(int32_t n_k, int32_t d, int32_t dtype) {
+  if (dtype != SBP_BF16) return 0;
+  if (d != 32 && d != 64 && d != 128) return 0;
+  if (const char* e = std::getenv("SBP_ATTN")) {            // debugging aid: "plain" forces the plain kernel
+    if (std::strcmp(e, "plain") == 0) return 0;
+  }
+  return attn_lds_bytes(n_k, d) <= kAttnMaxLds ? 1 : 0;
+}
+
+template <int D>
+static void launch_attn_mfma(const uint16_t* qkv, const uint16_t* A, const uint16_t* dA, const float* lse, int B, int n_k,
+                             int h, float scale, uint16_t* dqkv, hipStream_t s) {
+  const size_t lds = AttnLds<D>::bytes((n_k + 31) & ~31);
+  static size_t allowed = 0;                                // raise the dynamic LDS limit once per size class
+  if (lds > 64 * 1024 && lds > allowed) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_mfma_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)kAttnMaxLds);
+    allowed = kAttnMaxLds;
+  }
+  SBP_LAUNCH(SBP_PROF_ATTENTION, s, (attn_bwd_mfma_kernel<D>), dim3(h, B), dim3(256), lds, s, qkv, A, dA, lse, n_k, h, scale, dqkv);
+}
+
+template <typename T>
+static void launch_attn_plain(const T* qkv, const T* A, const T* dA, const float* lse, int B, int n_k, int h, int d, float scale,
+                              T* dqkv, hipStream_t s) {
+  const int owners = 256 / (d / 16);
+  const dim3 grid((unsigned)ceil_div(n_k, owners), h, B);
+  {
+    ProfScope scope(SBP_PROF_ATTENTION, s);
+    hipLaunchKernelGGL((attn_bwd_plain_kernel<T, 0>), grid, dim3(256), 0, s, qkv, A, dA, lse, n_k, h, d, scale, dqkv);
+    hipLaunchKernelGGL((attn_bwd_plain_kernel<T, 1>), grid, dim3(256), 0, s, qkv, A, dA, lse, n_k, h, d, scale, dqkv);
+  }
+}
+
+int32_t launch_backward_attention(const void* qkv, const void* A, const void* dA, const float* lse, int32_t B, int32_t n_k,
+                                  int32_t h, int32_t d, float scale, int32_t dtype, void* dqkv, hipStream_t s) {
+  if (attention_engine(n_k, d, dtype)) {
+    const uint16_t* q = (const uint16_t*)qkv; const uint16_t* a = (const uint16_t*)A; const uint16_t* g = (const uint16_t*)dA;
+    if (d == 32) launch_attn_mfma<32>(q, a, g, lse, B, n_k, h, scale, (uint16_t*)dqkv, s);
+    else if (d == 64) launch_attn_mfma<64>(q, a, g, lse, B, n_k, h, scale, (uint16_t*)dqkv, s);
+    else launch_attn_mfma<128>(q, a, g, lse, B, n_k, h, scale, (uint16_t*)dqkv, s);
+  } else if (dtype == SBP_BF16) {
+    launch_attn_plain<uint16_t>((const uint16_t*)qkv, (const uint16_t*)A, (const uint16_t*)dA, lse, B, n_k, h, d, scale,
+                                (uint16_t*)dqkv, s);
+  } else {
+    launch_attn_plain<float>((const float*)qkv, (const float*)A, (const float*)dA, lse, B, n_k, h, d, scale, (float*)dqkv, s);
+  }
+  return check_launch("backward_attention");
+}
+
+}  // namespace sbp

@@ -76,6 +76,11 @@ void launch_build_inverse(const int32_t* idx, int64_t K, int32_t* inv, hipStream
 void launch_zero_dropped_rows(const int32_t* idx, const int32_t* inv, int64_t K, int64_t M, int64_t row_bytes,
                               void* out, hipStream_t s);
 
+// ---- attention backward on the kept tokens -------------------------------------------------------
+int attention_engine(int32_t n_k, int32_t d, int32_t dtype);   // 1: matrix-core kernel, 0: plain kernel
+int32_t launch_backward_attention(const void* qkv, const void* A, const void* dA, const float* lse, int32_t B, int32_t n_k,
+                                  int32_t h, int32_t d, float scale, int32_t dtype, void* dqkv, hipStream_t s);
+
 // ---- row-wise steps between the linear layers ------------------------------------------------
 int32_t launch_act_rows(const void* dH, const void* Z, int64_t n, int32_t dtype, int32_t act, bool backward, void* out,
                         hipStream_t s);

@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 20
+    assert len(names) == 22
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -206,6 +206,27 @@ def test_rowwise_steps_argument_errors():
     assert ln(eps=-1.0) == -2
     assert ln(w=None) == -6 and ln(wb=ws - 1) == -6 and ln(w=p * 4 + 16) == -6
     assert ln(dg=None, db=None, dX=None) == 0
+
+
+def test_backward_attention_argument_errors_and_engine():
+    L = _lib.lib()
+    p = ctypes.c_void_p(256)     # never dereferenced: validation comes first and enqueues nothing
+
+    def call(B=2, n_k=10, h=3, d=64, scale=0.125, dtype=1, q=p, a=p, g=p, l=p, o=p):
+        return L.sbp_backward_attention(q, a, g, l, B, n_k, h, d, scale, dtype, o, None)
+
+    assert call(dtype=7) == -4
+    assert call(B=0) == -2 and call(h=0) == -2 and call(n_k=-1) == -2
+    assert call(d=48) == -2 and call(d=256) == -2
+    assert call(scale=0.0) == -2 and call(scale=float("nan")) == -2
+    assert call(n_k=0, q=None, a=None, g=None, l=None, o=None) == 0          # nothing kept: nothing to do
+    assert call(q=None) == -1 and call(l=None) == -1 and call(o=None) == -1
+    assert call(a=ctypes.c_void_p(260)) == -2                                # alignment
+    assert L.sbp_backward_attention_engine(99, 64, 1) == 1                   # bf16: matrix-core kernel
+    assert L.sbp_backward_attention_engine(256, 64, 1) == 1 and L.sbp_backward_attention_engine(257, 64, 1) == 0
+    assert L.sbp_backward_attention_engine(128, 128, 1) == 1 and L.sbp_backward_attention_engine(129, 128, 1) == 0
+    assert L.sbp_backward_attention_engine(99, 64, 0) == 0 and L.sbp_backward_attention_engine(99, 16, 1) == 0
+    assert L.sbp_backward_attention_engine(99, 48, 1) == -1
 
 
 def test_backward_dwconv_argument_errors():
