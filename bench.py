@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed region at the chosen ratio (for profiler runs: no r=1 leg, no event pass)")
+    ap.add_argument("--attention-only", action="store_true",
+                    help="only the attention-backward side measurement (for profiler runs)")
     return ap.parse_args()
 
 
@@ -385,6 +387,43 @@ def measure_downsample(torch, sbp, si, r, iters=20, warmup=5):
     return out
 
 
+def measure_attention(torch, sbp, si, iters=30, warmup=6):
+    """Attention backward on the kept tokens ("Drop QKV") at the ViT-Base sizes: 64 samples, 12 heads of 64, 99 of
+    197 tokens kept (r = 0.5) and all 197 (r = 1).  Six rotating input sets; algorithmic bytes = kept rows of qkv,
+    A, dA read once, lse read, dqkv written; flops = the five products of the backward (10 n_k^2 d per head)."""
+    import math
+    B, h, d = 64, 12, 64
+    out = {"workload": f"vit_base attention core backward, B={B}, {h} heads of {d}", "sizes": {}}
+    for tag, n_k in (("r0.5", 99), ("r1", 197)):
+        K = B * n_k
+        sets = []
+        for i in range(6):
+            qkv, dA = si.attention_case(B, n_k, h, d, 700 + i, "bf16")
+            sets.append((qkv.cuda(), si.normal((K, h * d), 0.2, 800 + i, "bf16").cuda(), dA.cuda(),
+                         torch.full((K, h), 5.5, dtype=torch.float32, device="cuda"),
+                         torch.empty((K, 3 * h * d), dtype=torch.bfloat16, device="cuda")))
+        sc = 1.0 / math.sqrt(d)
+        for i in range(warmup):
+            b = sets[i % 6]
+            sbp.backward_attention(b[0], b[1], b[2], b[3], B, h, d, sc, out=b[4])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            b = sets[i % 6]
+            sbp.backward_attention(b[0], b[1], b[2], b[3], B, h, d, sc, out=b[4])
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / iters * 1e3
+        nbytes = K * h * d * 2 * 8 + K * h * 4
+        flops = 10.0 * B * h * n_k * n_k * d
+        out["sizes"][tag] = {"n_k": n_k, "us": round(us, 2), "engine": sbp.backward_attention_engine(n_k, d, sbp.BF16),
+                             "algorithmic_mb": round(nbytes / 1e6, 2), "gbs": round(nbytes / us / 1e3, 1),
+                             "frac_of_hbm_peak": round(nbytes / us / 1e3 / 8000.0, 4), "tflops": round(flops / us / 1e6, 1)}
+    out["speedup_vs_r1"] = round(out["sizes"]["r1"]["us"] / out["sizes"]["r0.5"]["us"], 3)
+    return out
+
+
 def measure_samplers(torch, sbp, si):
     """One draw (keep list + inverse map) of every sampler mode on the ViT-Base batch and on a detection map."""
     out = {}
@@ -428,6 +467,9 @@ def main():
         print("bench.py needs a GPU: the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    if args.attention_only:
+        print(json.dumps({"attention_drop_qkv": measure_attention(torch, sbp, si)}))
+        return
     wl = si.WORKLOADS[args.workload]
     job = Job(wl, torch, sbp, si)
 
@@ -508,6 +550,7 @@ def main():
         result["mlp_branch_compact"] = measure_mlp_branch(torch, sbp, si, args.ratio)
         result["downsample_layer"] = measure_downsample(torch, sbp, si, args.ratio)
         result["sampler_modes"] = measure_samplers(torch, sbp, si)
+        result["attention_drop_qkv"] = measure_attention(torch, sbp, si)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.ratio, args.cpu_seconds, si)
     print(json.dumps(result))

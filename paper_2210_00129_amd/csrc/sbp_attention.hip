@@ -147,7 +147,7 @@ __global__ void __launch_bounds__(256) attn_bwd_plain_kernel(const T* __restrict
 template <int D>
 struct AttnLds {
   static constexpr int PITCH = 2 * D + 16;
-  static size_t bytes(int npad) { return (size_t)4 * npad * PITCH + (size_t)2 * npad * sizeof(float); }
+  static __host__ __device__ size_t bytes(int npad) { return (size_t)4 * npad * PITCH + (size_t)2 * npad * sizeof(float); }
 };
 
 __device__ __forceinline__ bf16x8_t pack8(const f32x16_t& c, int ks) {
@@ -167,175 +167,241 @@ __device__ __forceinline__ bf16x8_t read_tr_tokens(const char* tile, int row0, i
   return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// The LDS image of one (sample, head): four tiles and two tables.
 template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_mfma_kernel(const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ A,
-                                                             const uint16_t* __restrict__ dA, const float* __restrict__ lse,
-                                                             int n_k, int h, float scale, uint16_t* __restrict__ dqkv) {
-  constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32, CH = D / 8;
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  const int npad = (n_k + 31) & ~31, nblk = npad >> 5;
-  char* tq = smem;
-  char* tk = tq + npad * PITCH;
-  char* tv = tk + npad * PITCH;
-  char* tg = tv + npad * PITCH;                                   // dA
-  float* lse_s = reinterpret_cast<float*>(tg + npad * PITCH);     // lse * log2(e)
-  float* delta_s = lse_s + npad;
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, u = lane >> 5;
-  const int head = blockIdx.x, b = blockIdx.y;
-  const long long row0 = (long long)b * n_k, ldq = 3LL * h * D, lda = (long long)h * D;
-
-  // ---- load: 16-byte pieces, CH per token and tensor; delta from the dA and A pieces
-  for (int p = t; p < npad * CH; p += 256) {
-    const int tok = p / CH, ch = p % CH;
-    uint4 q = make_uint4(0, 0, 0, 0), k = q, v = q, g = q, a = q;
-    if (tok < n_k) {
-      const uint16_t* r = qkv + (row0 + tok) * ldq + head * D + 8 * ch;
-      q = *reinterpret_cast<const uint4*>(r);
-      k = *reinterpret_cast<const uint4*>(r + (long long)h * D);
-      v = *reinterpret_cast<const uint4*>(r + 2LL * h * D);
-      g = *reinterpret_cast<const uint4*>(dA + (row0 + tok) * lda + head * D + 8 * ch);
-      a = *reinterpret_cast<const uint4*>(A + (row0 + tok) * lda + head * D + 8 * ch);
-    }
-    const int off = tok * PITCH + ch * 16;
-    *reinterpret_cast<uint4*>(tq + off) = q;
-    *reinterpret_cast<uint4*>(tk + off) = k;
-    *reinterpret_cast<uint4*>(tv + off) = v;
-    *reinterpret_cast<uint4*>(tg + off) = g;
-    const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, aw[4] = {a.x, a.y, a.z, a.w};
-    float s = 0.f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) s += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
-    for (int m = 1; m < CH; m <<= 1) s += __shfl_xor(s, m);
-    if (ch == 0) delta_s[tok] = s;
+struct AttnTiles {
+  static constexpr int PITCH = AttnLds<D>::PITCH;
+  char *tq, *tk, *tv, *tg;       // q, k, v, dA
+  float *lse_s, *delta_s;        // lse * log2(e), dA.A
+  __device__ __forceinline__ void place(char* base, int npad) {
+    tq = base;
+    tk = tq + npad * PITCH;
+    tv = tk + npad * PITCH;
+    tg = tv + npad * PITCH;
+    lse_s = reinterpret_cast<float*>(tg + npad * PITCH);
+    delta_s = lse_s + npad;
   }
-  for (int i = t; i < npad; i += 256) lse_s[i] = i < n_k ? lse[(row0 + i) * h + head] * kLog2e : 0.f;
-  __syncthreads();
+};
 
-  const float c2 = scale * kLog2e;
-  const int lrow = lane & 31;
+// Where one (sample, head) lives in global memory.
+struct AttnItem {
+  const uint16_t *q, *a, *g;     // row 0 of the head's columns in qkv (q third), A and dA
+  const float* lse;              // lse[row 0][head]
+  uint16_t* o;                   // row 0 of the head's columns in dqkv (dQ third)
+};
+__device__ __forceinline__ AttnItem attn_item(const uint16_t* qkv, const uint16_t* A, const uint16_t* dA, const float* lse,
+                                              uint16_t* dqkv, int b, int head, int n_k, int h, int D) {
+  const long long row0 = (long long)b * n_k;
+  AttnItem it;
+  it.q = qkv + row0 * (3LL * h * D) + head * D;
+  it.a = A + row0 * ((long long)h * D) + head * D;
+  it.g = dA + row0 * ((long long)h * D) + head * D;
+  it.lse = lse + row0 * h + head;
+  it.o = dqkv + row0 * (3LL * h * D) + head * D;
+  return it;
+}
+
+// R rounds of 16-byte pieces per thread (NT threads): piece p = token p / CH, chunk p % CH of q, k, v, dA and A.
+template <int D, int R>
+struct AttnPieces {
+  uint4 q[R], k[R], v[R], g[R], a[R];
+  template <int NT>
+  __device__ __forceinline__ void load(const AttnItem& it, int p0, int n_k, int h) {
+    constexpr int CH = D / 8;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int p = p0 + NT * r, tok = p / CH, ch = p % CH;
+      q[r] = k[r] = v[r] = g[r] = a[r] = make_uint4(0, 0, 0, 0);
+      if (tok < n_k) {                                   // also false for pieces past the padded tile
+        const uint16_t* src = it.q + (long long)tok * (3LL * h * D) + 8 * ch;
+        q[r] = *reinterpret_cast<const uint4*>(src);
+        k[r] = *reinterpret_cast<const uint4*>(src + (long long)h * D);
+        v[r] = *reinterpret_cast<const uint4*>(src + 2LL * h * D);
+        g[r] = *reinterpret_cast<const uint4*>(it.g + (long long)tok * ((long long)h * D) + 8 * ch);
+        a[r] = *reinterpret_cast<const uint4*>(it.a + (long long)tok * ((long long)h * D) + 8 * ch);
+      }
+    }
+  }
+  template <int NT>
+  __device__ __forceinline__ void store(const AttnTiles<D>& T, int p0, int npieces) const {
+    constexpr int CH = D / 8, PITCH = AttnLds<D>::PITCH;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int p = p0 + NT * r, tok = p / CH, ch = p % CH;
+      if (p < npieces) {                                 // uniform per wavefront: npieces is a multiple of 64
+        const int off = tok * PITCH + ch * 16;
+        *reinterpret_cast<uint4*>(T.tq + off) = q[r];
+        *reinterpret_cast<uint4*>(T.tk + off) = k[r];
+        *reinterpret_cast<uint4*>(T.tv + off) = v[r];
+        *reinterpret_cast<uint4*>(T.tg + off) = g[r];
+        const uint32_t gw[4] = {g[r].x, g[r].y, g[r].z, g[r].w}, aw[4] = {a[r].x, a[r].y, a[r].z, a[r].w};
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
+        for (int m = 1; m < CH; m <<= 1) s += __shfl_xor(s, m);
+        if (ch == 0) T.delta_s[tok] = s;
+      }
+    }
+  }
+};
+
+// dK and dV of the 32 keys of block jb (one wavefront)
+template <int D>
+__device__ __forceinline__ void attn_key_block(const AttnTiles<D>& T, int jb, int nblk, int n_k, int h, float scale,
+                                               uint16_t* __restrict__ out, int lane) {
+  constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32;
+  const int u = lane >> 5, lrow = lane & 31;
   const int foff = lrow * PITCH + 16 * u;              // 16-byte operand read of row (lane & 31), k chunk 8u
-
-  // ---- phase 1: dK, dV of the key blocks of this wavefront
-  for (int jb = wave; jb < nblk; jb += 4) {
-    f32x16_t dv[DB], dk[DB];
+  const float c2 = scale * kLog2e;
+  f32x16_t dv[DB], dk[DB];
 #pragma unroll
-    for (int x = 0; x < DB; ++x)
+  for (int x = 0; x < DB; ++x)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) dv[x][e] = dk[x][e] = 0.f;
-    bf16x8_t kf[KS], vf[KS];
+    for (int e = 0; e < 16; ++e) dv[x][e] = dk[x][e] = 0.f;
+  bf16x8_t kf[KS], vf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tk + jb * 32 * PITCH + foff + ks * 32);
+    vf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tv + jb * 32 * PITCH + foff + ks * 32);
+  }
+  for (int ib = 0; ib < nblk; ++ib) {
+    f32x16_t s, dp;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      kf[ks] = *reinterpret_cast<const bf16x8_t*>(tk + jb * 32 * PITCH + foff + ks * 32);
-      vf[ks] = *reinterpret_cast<const bf16x8_t*>(tv + jb * 32 * PITCH + foff + ks * 32);
+      const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(T.tq + ib * 32 * PITCH + foff + ks * 32);
+      const bf16x8_t gf = *reinterpret_cast<const bf16x8_t*>(T.tg + ib * 32 * PITCH + foff + ks * 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], s, 0, 0, 0);      // rows i, columns j
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks], dp, 0, 0, 0);
     }
-    for (int ib = 0; ib < nblk; ++ib) {
-      f32x16_t s, dp;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const float4 l4 = *reinterpret_cast<const float4*>(T.lse_s + ib * 32 + 8 * q4 + 4 * u);
+      const float4 d4 = *reinterpret_cast<const float4*>(T.delta_s + ib * 32 + 8 * q4 + 4 * u);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(tq + ib * 32 * PITCH + foff + ks * 32);
-        const bf16x8_t gf = *reinterpret_cast<const bf16x8_t*>(tg + ib * 32 * PITCH + foff + ks * 32);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], s, 0, 0, 0);      // rows i, columns j
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks], dp, 0, 0, 0);
+      for (int e = 0; e < 4; ++e) {
+        const float p = __builtin_amdgcn_exp2f(s[4 * q4 + e] * c2 - lv[e]);
+        s[4 * q4 + e] = p;
+        dp[4 * q4 + e] = p * (dp[4 * q4 + e] - dl[e]);
       }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const bf16x8_t pf = pack8(s, ks), dsf = pack8(dp, ks);
+#pragma unroll
+      for (int x = 0; x < DB; ++x) {
+        const bf16x8_t gt = read_tr_tokens<PITCH>(T.tg, ib * 32 + 16 * ks, 32 * x, lane);
+        const bf16x8_t qt = read_tr_tokens<PITCH>(T.tq, ib * 32 + 16 * ks, 32 * x, lane);
+        dv[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf, dv[x], 0, 0, 0);   // rows head dim, columns j
+        dk[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[x], 0, 0, 0);
+      }
+    }
+  }
+  const int j = jb * 32 + lrow;
+  if (j < n_k) {
+    uint16_t* o = out + (long long)j * (3LL * h * D);
+#pragma unroll
+    for (int x = 0; x < DB; ++x)
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const float4 l4 = *reinterpret_cast<const float4*>(lse_s + ib * 32 + 8 * q4 + 4 * u);
-        const float4 d4 = *reinterpret_cast<const float4*>(delta_s + ib * 32 + 8 * q4 + 4 * u);
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float p = __builtin_amdgcn_exp2f(s[4 * q4 + e] * c2 - lv[e]);
-          s[4 * q4 + e] = p;
-          dp[4 * q4 + e] = p * (dp[4 * q4 + e] - dl[e]);
-        }
+        const int dcol = 32 * x + 8 * q4 + 4 * u;
+        uint2 w;
+        w.x = bf16_pack(dk[x][4 * q4] * scale, dk[x][4 * q4 + 1] * scale);
+        w.y = bf16_pack(dk[x][4 * q4 + 2] * scale, dk[x][4 * q4 + 3] * scale);
+        *reinterpret_cast<uint2*>(o + (long long)h * D + dcol) = w;
+        w.x = bf16_pack(dv[x][4 * q4], dv[x][4 * q4 + 1]);
+        w.y = bf16_pack(dv[x][4 * q4 + 2], dv[x][4 * q4 + 3]);
+        *reinterpret_cast<uint2*>(o + 2LL * h * D + dcol) = w;
       }
+  }
+}
+
+// dQ of the 32 queries of block ib (one wavefront)
+template <int D>
+__device__ __forceinline__ void attn_query_block(const AttnTiles<D>& T, int ib, int nblk, int n_k, int h, float scale,
+                                                 uint16_t* __restrict__ out, int lane) {
+  constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32;
+  const int u = lane >> 5, lrow = lane & 31;
+  const int foff = lrow * PITCH + 16 * u;
+  const float c2 = scale * kLog2e;
+  f32x16_t dq[DB];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8_t pf = pack8(s, ks), dsf = pack8(dp, ks);
+  for (int x = 0; x < DB; ++x)
 #pragma unroll
-        for (int x = 0; x < DB; ++x) {
-          const bf16x8_t gt = read_tr_tokens<PITCH>(tg, ib * 32 + 16 * ks, 32 * x, lane);
-          const bf16x8_t qt = read_tr_tokens<PITCH>(tq, ib * 32 + 16 * ks, 32 * x, lane);
-          dv[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf, dv[x], 0, 0, 0);   // rows head dim, columns j
-          dk[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[x], 0, 0, 0);
-        }
-      }
+    for (int e = 0; e < 16; ++e) dq[x][e] = 0.f;
+  bf16x8_t qf[KS], gf[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tq + ib * 32 * PITCH + foff + ks * 32);
+    gf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tg + ib * 32 * PITCH + foff + ks * 32);
+  }
+  const float l = T.lse_s[ib * 32 + lrow], dl = T.delta_s[ib * 32 + lrow];
+  for (int jb = 0; jb < nblk; ++jb) {
+    f32x16_t s, dp;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(T.tk + jb * 32 * PITCH + foff + ks * 32);
+      const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(T.tv + jb * 32 * PITCH + foff + ks * 32);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);      // rows j, columns i
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks], dp, 0, 0, 0);
     }
-    const int j = jb * 32 + lrow;
-    if (j < n_k) {
-      uint16_t* o = dqkv + (row0 + j) * ldq + head * D;
 #pragma unroll
-      for (int x = 0; x < DB; ++x)
+    for (int e = 0; e < 16; ++e) {
+      const float p = __builtin_amdgcn_exp2f(s[e] * c2 - l);
+      dp[e] = p * (dp[e] - dl);
+    }
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int dcol = 32 * x + 8 * q4 + 4 * u;
-          uint2 w;
-          w.x = bf16_pack(dk[x][4 * q4] * scale, dk[x][4 * q4 + 1] * scale);
-          w.y = bf16_pack(dk[x][4 * q4 + 2] * scale, dk[x][4 * q4 + 3] * scale);
-          *reinterpret_cast<uint2*>(o + (long long)h * D + dcol) = w;
-          w.x = bf16_pack(dv[x][4 * q4], dv[x][4 * q4 + 1]);
-          w.y = bf16_pack(dv[x][4 * q4 + 2], dv[x][4 * q4 + 3]);
-          *reinterpret_cast<uint2*>(o + 2LL * h * D + dcol) = w;
-        }
+    for (int ks = 0; ks < 2; ++ks) {
+      const bf16x8_t dsf = pack8(dp, ks);
+#pragma unroll
+      for (int x = 0; x < DB; ++x) {
+        const bf16x8_t kt = read_tr_tokens<PITCH>(T.tk, jb * 32 + 16 * ks, 32 * x, lane);
+        dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dq[x], 0, 0, 0);   // rows head dim, columns i
+      }
     }
   }
-
-  // ---- phase 2: dQ of the query blocks of this wavefront
-  for (int ib = wave; ib < nblk; ib += 4) {
-    f32x16_t dq[DB];
+  const int i = ib * 32 + lrow;
+  if (i < n_k) {
+    uint16_t* o = out + (long long)i * (3LL * h * D);
 #pragma unroll
     for (int x = 0; x < DB; ++x)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) dq[x][e] = 0.f;
-    bf16x8_t qf[KS], gf[KS];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      qf[ks] = *reinterpret_cast<const bf16x8_t*>(tq + ib * 32 * PITCH + foff + ks * 32);
-      gf[ks] = *reinterpret_cast<const bf16x8_t*>(tg + ib * 32 * PITCH + foff + ks * 32);
-    }
-    const float l = lse_s[ib * 32 + lrow], dl = delta_s[ib * 32 + lrow];
-    for (int jb = 0; jb < nblk; ++jb) {
-      f32x16_t s, dp;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(tk + jb * 32 * PITCH + foff + ks * 32);
-        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(tv + jb * 32 * PITCH + foff + ks * 32);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);      // rows j, columns i
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks], dp, 0, 0, 0);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        uint2 w;
+        w.x = bf16_pack(dq[x][4 * q4] * scale, dq[x][4 * q4 + 1] * scale);
+        w.y = bf16_pack(dq[x][4 * q4 + 2] * scale, dq[x][4 * q4 + 3] * scale);
+        *reinterpret_cast<uint2*>(o + 32 * x + 8 * q4 + 4 * u) = w;
       }
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const float p = __builtin_amdgcn_exp2f(s[e] * c2 - l);
-        dp[e] = p * (dp[e] - dl);
-      }
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const bf16x8_t dsf = pack8(dp, ks);
-#pragma unroll
-        for (int x = 0; x < DB; ++x) {
-          const bf16x8_t kt = read_tr_tokens<PITCH>(tk, jb * 32 + 16 * ks, 32 * x, lane);
-          dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dq[x], 0, 0, 0);   // rows head dim, columns i
-        }
-      }
-    }
-    const int i = ib * 32 + lrow;
-    if (i < n_k) {
-      uint16_t* o = dqkv + (row0 + i) * ldq + head * D;
-#pragma unroll
-      for (int x = 0; x < DB; ++x)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          uint2 w;
-          w.x = bf16_pack(dq[x][4 * q4] * scale, dq[x][4 * q4 + 1] * scale);
-          w.y = bf16_pack(dq[x][4 * q4 + 2] * scale, dq[x][4 * q4 + 3] * scale);
-          *reinterpret_cast<uint2*>(o + 32 * x + 8 * q4 + 4 * u) = w;
-        }
-    }
   }
+}
+
+// One (sample, head) per workgroup of 4 wavefronts: load, then the key blocks, then the query blocks.  Any
+// number of kept tokens whose tiles fit LDS.
+template <int D>
+__global__ void __launch_bounds__(256, D == 128 ? 1 : 2) attn_bwd_mfma_kernel(const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ A,
+                                                             const uint16_t* __restrict__ dA, const float* __restrict__ lse,
+                                                             int n_k, int h, float scale, uint16_t* __restrict__ dqkv) {
+  constexpr int CH = D / 8;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int npad = (n_k + 31) & ~31, nblk = npad >> 5;
+  AttnTiles<D> T;
+  T.place(smem, npad);
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const AttnItem it = attn_item(qkv, A, dA, lse, dqkv, blockIdx.y, blockIdx.x, n_k, h, D);
+  const int npieces = npad * CH;
+  for (int p0 = t; p0 < npieces; p0 += 4 * 256) {      // four rounds of loads in flight per thread
+    AttnPieces<D, 4> pc;
+    pc.template load<256>(it, p0, n_k, h);
+    pc.template store<256>(T, p0, npieces);
+  }
+  for (int i = t; i < npad; i += 256) T.lse_s[i] = i < n_k ? it.lse[(long long)i * h] * kLog2e : 0.f;
+  __syncthreads();
+  for (int jb = wave; jb < nblk; jb += 4) attn_key_block<D>(T, jb, nblk, n_k, h, scale, it.o, lane);
+  for (int ib = wave; ib < nblk; ib += 4) attn_query_block<D>(T, ib, nblk, n_k, h, scale, it.o, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -361,14 +427,12 @@ int attention_engine(int32_t n_k, int32_t d, int32_t dtype) {
 template <int D>
 static void launch_attn_mfma(const uint16_t* qkv, const uint16_t* A, const uint16_t* dA, const float* lse, int B, int n_k,
                              int h, float scale, uint16_t* dqkv, hipStream_t s) {
-  const size_t lds = AttnLds<D>::bytes((n_k + 31) & ~31);
-  static size_t allowed = 0;                                // raise the dynamic LDS limit once per size class
-  if (lds > 64 * 1024 && lds > allowed) {
+  const size_t image = AttnLds<D>::bytes((n_k + 31) & ~31);
+  if (image > 64 * 1024)
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_mfma_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
                               (int)kAttnMaxLds);
-    allowed = kAttnMaxLds;
-  }
-  SBP_LAUNCH(SBP_PROF_ATTENTION, s, (attn_bwd_mfma_kernel<D>), dim3(h, B), dim3(256), lds, s, qkv, A, dA, lse, n_k, h, scale, dqkv);
+  SBP_LAUNCH(SBP_PROF_ATTENTION, s, (attn_bwd_mfma_kernel<D>), dim3(h, B), dim3(256), image, s, qkv, A, dA, lse, n_k, h, scale,
+             dqkv);
 }
 
 template <typename T>
