@@ -6,6 +6,8 @@
 // Channels-last: a wavefront's lanes are adjacent channels, so "is this neighbour kept" is the same
 // for the whole wavefront and dropped taps are skipped by a scalar branch.  bf16 or fp32 storage,
 // fp32 arithmetic on the vector ALUs (a depthwise conv is no dense contraction: no MFMA).
+#include <cstdlib>
+
 #include "sbp_internal.h"
 
 namespace sbp {
@@ -124,110 +126,168 @@ __global__ void __launch_bounds__(DW_THREADS) dw_reduce_kernel(const float* __re
 
 // ------------------------------------------------------------------------------------------------
 // bf16 fast path (even channel count).  A lane owns two adjacent channels (one 32-bit word), so a
-// wavefront reads 256 contiguous bytes per position and the "is this position kept" test is uniform
-// over the block (a scalar load and a scalar branch).
-//
-// dX: a block produces TX consecutive positions of one row for 2 * blockDim.x channels.  The KS*KS
-// weights of its channels sit in registers; it walks the KS x (TX + KS - 1) window of dY once, skips
-// the dropped positions, and adds each kept gradient to the (up to KS) outputs it reaches.
+// wavefront reads 256 contiguous bytes per position and "is this position kept" is uniform over the
+// wavefront (a ballot over a row of inverse-map lookups).  Work is cut into strips of DW_TX columns.
 // ------------------------------------------------------------------------------------------------
 static constexpr int DW_TX = 8;
 
 __device__ __forceinline__ float dw_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float dw_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ uint32_t dw_round(float v) {
-  uint32_t u = __float_as_uint(v);
-  return ((u & 0x7fffffffu) > 0x7f800000u) ? ((u >> 16) | 0x40u) : ((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+
+// Strip kernels: a workgroup (dX) or a group of a workgroup (dWd, db) walks down a strip of DW_TX columns over a
+// chunk of rows: each row of the map is fetched once per strip instead of KS times, the weights once per chunk,
+// the next row's loads (and its inverse-map lookups) are in flight while the current row is computed, and the
+// row loops have no per-position branches: dropped and outside positions are zeroed when a row arrives.
+typedef __bf16 dw_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float dw_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t dw_pack(float lo, float hi) {      // round to nearest even (v_cvt_pk_bf16_f32)
+  const dw_f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, dw_bf16x2));
 }
 
-// kept-mask of a window of positions: lane p tests position p, the ballot makes it wave-uniform
+struct DwStrip {
+  int b, x0, y0, y1;
+};
+__device__ __forceinline__ DwStrip dw_strip(int strip, int tiles_x, int chunks, int rows_per_chunk, int H) {
+  DwStrip t;
+  const int xt = strip % tiles_x, rest = strip / tiles_x;
+  const int ch = rest % chunks;
+  t.b = rest / chunks;
+  t.x0 = xt * DW_TX;
+  t.y0 = ch * rows_per_chunk;
+  t.y1 = min(H, t.y0 + rows_per_chunk);
+  return t;
+}
+
+// one window row of a [B, H, W, C2] tensor of channel pairs: columns x0 - PAD .. x0 + DW_TX + PAD - 1 of row yy,
+// addresses clamped into the map (values outside are never used)
 template <int KS>
-__device__ __forceinline__ void dw_window_masks(const int32_t* __restrict__ inv, int row, int y, int x0, int H, int W,
-                                                unsigned long long (&mask)[2]) {
+__device__ __forceinline__ void dw_load_row(const uint32_t* __restrict__ src, int b, int yy, int x0, int H, int W, int C2, int cp,
+                                            uint32_t (&dst)[DW_TX + KS - 1]) {
   constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1;
-  const int lane = threadIdx.x & 63;
+  const long long prow = ((long long)b * H + min(max(yy, 0), H - 1)) * W;
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int p = lane + 64 * h;                 // window position p = r * WIN + col
-    const int r = p / WIN, col = p - r * WIN;
-    const int yy = y + r - PAD, xx = x0 + col - PAD;
-    bool kept = false;
-    if (p < KS * WIN && yy >= 0 && yy < H && xx >= 0 && xx < W) kept = inv[(long long)(row + r - PAD) * W + xx] >= 0;
-    mask[h] = __ballot(kept);
-  }
+  for (int col = 0; col < WIN; ++col) dst[col] = src[(prow + min(max(x0 + col - PAD, 0), W - 1)) * C2 + cp];
 }
-__device__ __forceinline__ bool dw_bit(const unsigned long long (&mask)[2], int p) {
-  return (mask[p >> 6] >> (p & 63)) & 1ull;
+// dst[col] &= all-ones where bit col of `bits` is set, zero elsewhere (the mask is wave-uniform: scalar operands)
+template <int N>
+__device__ __forceinline__ void dw_mask_words(uint32_t (&dst)[N], unsigned bits) {
+#pragma unroll
+  for (int col = 0; col < N; ++col) dst[col] &= ((bits >> col) & 1u) ? 0xffffffffu : 0u;
+}
+// Lane c looks window column c of row yy up in the inverse map (-1: outside the map or dropped).  The ballot
+// over (value >= 0) that turns it into a wave-uniform mask is taken later, by the caller, so that the lookup's
+// latency overlaps the other loads instead of stopping the wavefront at every row.
+template <int KS>
+__device__ __forceinline__ int dw_row_lookup(const int32_t* __restrict__ inv, int b, int yy, int x0, int H, int W) {
+  constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1;
+  const int lane = threadIdx.x & 63, xx = x0 + lane - PAD;
+  const bool inside = lane < WIN && yy >= 0 && yy < H && xx >= 0 && xx < W;
+  const int v = inv[((long long)b * H + min(max(yy, 0), H - 1)) * W + min(max(xx, 0), W - 1)];   // unconditional: no branch, no wait here
+  return inside ? v : -1;
 }
 
+// Two bf16 values of ONE channel side by side (v_dot2c_f32_bf16 multiplies them pairwise and adds both products
+// to an fp32 accumulator): a loaded word holds two channels of one position, so pairs along x are made with one
+// byte permute per word.
+typedef __bf16 dw_bf16x2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t dw_pair_lo(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x05040100u); }  // (x.lo, y.lo)
+__device__ __forceinline__ uint32_t dw_pair_hi(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }  // (x.hi, y.hi)
+__device__ __forceinline__ float dw_dot2(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(dw_bf16x2v, a), __builtin_bit_cast(dw_bf16x2v, b), acc, false);
+}
+
+// dX, gradient row by gradient row: the workgroup walks down its strip, every masked row of dY is fetched once,
+// paired along x, and added to the KS output rows it reaches, whose DW_TX x 2 running sums each stay in registers
+// (slot j holds output row yy - PAD + j; after gradient row yy slot 0 is complete, is stored, and the slots
+// move up).  Products are exact (bf16 x bf16 in fp32), sums fp32.
 template <int KS>
-__global__ void __launch_bounds__(DW_THREADS) dw_dx_fast_kernel(const uint32_t* __restrict__ dY, const int32_t* __restrict__ inv,
-                                                                const uint32_t* __restrict__ Wd, int H, int W, int C2,
-                                                                uint32_t* __restrict__ dX, int tiles_x) {
-  constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1;
-  static_assert(KS * WIN <= 128, "window must fit two ballots");
+__global__ void __launch_bounds__(DW_THREADS) dw_dx_strip_kernel(const uint32_t* __restrict__ dY, const int32_t* __restrict__ inv,
+                                                                 const uint32_t* __restrict__ Wd, int H, int W, int C2,
+                                                                 uint32_t* __restrict__ dX, int tiles_x, int chunks,
+                                                                 int rows_per_chunk) {
+  constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1, NP = (KS + 1) / 2, NG = WIN / 2;
+  static_assert(WIN % 2 == 0, "pairs along the window row");
   const int cp_raw = blockIdx.y * blockDim.x + threadIdx.x;
   const bool active = cp_raw < C2;
   const int cp = active ? cp_raw : C2 - 1;
-  const int tile = blockIdx.x;
-  const int x0 = (tile % tiles_x) * DW_TX;
-  const int row = tile / tiles_x;            // b * H + y
-  const int y = row % H;
-  unsigned long long mask[2];
-  dw_window_masks<KS>(inv, row, y, x0, H, W, mask);
-  float w0[KS * KS], w1[KS * KS];
+  const DwStrip t = dw_strip(blockIdx.x, tiles_x, chunks, rows_per_chunk, H);
+  // weight pairs of tap row u: (w[u][KS-1-2m], w[u][KS-2-2m]) meet the gradients of columns (ox + 2m, ox + 2m + 1)
+  uint32_t wp[KS][NP][2];
 #pragma unroll
-  for (int tp = 0; tp < KS * KS; ++tp) {
-    const uint32_t w = Wd[tp * C2 + cp];
-    w0[tp] = dw_lo(w); w1[tp] = dw_hi(w);
-  }
-  float a0[DW_TX], a1[DW_TX];
+  for (int u = 0; u < KS; ++u)
 #pragma unroll
-  for (int ox = 0; ox < DW_TX; ++ox) { a0[ox] = 0.f; a1[ox] = 0.f; }
-  // all loads of the window are issued together (clamped addresses; values of dropped or outside
-  // positions are never used), then the kept positions are accumulated
-  uint32_t g[KS][WIN];
-#pragma unroll
-  for (int r = 0; r < KS; ++r) {
-    const long long prow = (long long)(row - y + min(max(y + r - PAD, 0), H - 1)) * W;
-#pragma unroll
-    for (int col = 0; col < WIN; ++col) g[r][col] = dY[(prow + min(max(x0 + col - PAD, 0), W - 1)) * C2 + cp];
-  }
-#pragma unroll
-  for (int r = 0; r < KS; ++r) {
-    const int u = KS - 1 - r;                // tap row that links output row y to gradient row y + r - PAD
-#pragma unroll
-    for (int col = 0; col < WIN; ++col) {
-      if (!dw_bit(mask, r * WIN + col)) continue;     // dropped or outside: wave-uniform
-      const float g0 = dw_lo(g[r][col]), g1 = dw_hi(g[r][col]);
-#pragma unroll
-      for (int ox = 0; ox < DW_TX; ++ox) {
-        const int v = ox - col + 2 * PAD;
-        if (v >= 0 && v < KS) {
-          a0[ox] = fmaf(g0, w0[u * KS + v], a0[ox]);
-          a1[ox] = fmaf(g1, w1[u * KS + v], a1[ox]);
-        }
-      }
+    for (int m = 0; m < NP; ++m) {
+      const uint32_t lo = Wd[(u * KS + KS - 1 - 2 * m) * C2 + cp];
+      const uint32_t hi = KS - 2 - 2 * m >= 0 ? Wd[(u * KS + KS - 2 - 2 * m) * C2 + cp] : 0u;
+      wp[u][m][0] = dw_pair_lo(lo, hi);
+      wp[u][m][1] = dw_pair_hi(lo, hi);
     }
-  }
-  if (active) {
+  float acc[KS][DW_TX][2];
 #pragma unroll
-    for (int ox = 0; ox < DW_TX; ++ox)
-      if (x0 + ox < W) dX[((long long)row * W + x0 + ox) * C2 + cp] = dw_round(a0[ox]) | (dw_round(a1[ox]) << 16);
+  for (int j = 0; j < KS; ++j)
+#pragma unroll
+    for (int ox = 0; ox < DW_TX; ++ox) acc[j][ox][0] = acc[j][ox][1] = 0.f;
+  uint32_t raw[WIN], nxt[WIN];
+  dw_load_row<KS>(dY, t.b, t.y0 - PAD, t.x0, H, W, C2, cp, raw);
+  int look = dw_row_lookup<KS>(inv, t.b, t.y0 - PAD, t.x0, H, W);
+  for (int yy = t.y0 - PAD; yy < t.y1 + PAD; ++yy) {
+    int lookn = -1;
+    if (yy + 1 < t.y1 + PAD) {                 // the next gradient row: in flight during this one
+      dw_load_row<KS>(dY, t.b, yy + 1, t.x0, H, W, C2, cp, nxt);
+      lookn = dw_row_lookup<KS>(inv, t.b, yy + 1, t.x0, H, W);
+    }
+    dw_mask_words<WIN>(raw, (unsigned)__ballot(look >= 0));    // dropped and outside positions: zero
+    uint32_t ge[2][NG], go[2][NG];             // (g[2k], g[2k+1]) and (g[2k+1], g[2k+2]) per channel
+#pragma unroll
+    for (int k = 0; k < NG; ++k) {
+      const uint32_t r0 = raw[2 * k], r1 = raw[2 * k + 1], r2 = 2 * k + 2 < WIN ? raw[2 * k + 2] : 0u;
+      ge[0][k] = dw_pair_lo(r0, r1); ge[1][k] = dw_pair_hi(r0, r1);
+      go[0][k] = dw_pair_lo(r1, r2); go[1][k] = dw_pair_hi(r1, r2);
+    }
+#pragma unroll
+    for (int j = 0; j < KS; ++j) {             // tap row j links this gradient row to output row yy - PAD + j
+      const int y = yy - PAD + j;
+      if (y < t.y0 || y >= t.y1) continue;     // another chunk's row: wave-uniform
+#pragma unroll
+      for (int ox = 0; ox < DW_TX; ++ox)
+#pragma unroll
+        for (int m = 0; m < NP; ++m) {
+          const int col = ox + 2 * m;          // gradient columns col, col + 1 of the window
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const uint32_t g = (col & 1) ? go[c][(col - 1) / 2] : ge[c][col / 2];
+            acc[j][ox][c] = dw_dot2(g, wp[j][m][c], acc[j][ox][c]);
+          }
+        }
+    }
+    const int yo = yy - PAD;                   // slot 0 is complete
+    if (yo >= t.y0 && active) {
+      uint32_t* orow = dX + (((long long)t.b * H + yo) * W + t.x0) * C2 + cp;
+#pragma unroll
+      for (int ox = 0; ox < DW_TX; ++ox)
+        if (t.x0 + ox < W) orow[(long long)ox * C2] = dw_pack(acc[0][ox][0], acc[0][ox][1]);
+    }
+#pragma unroll
+    for (int j = 0; j + 1 < KS; ++j)
+#pragma unroll
+      for (int ox = 0; ox < DW_TX; ++ox) { acc[j][ox][0] = acc[j + 1][ox][0]; acc[j][ox][1] = acc[j + 1][ox][1]; }
+#pragma unroll
+    for (int ox = 0; ox < DW_TX; ++ox) acc[KS - 1][ox][0] = acc[KS - 1][ox][1] = 0.f;
+#pragma unroll
+    for (int col = 0; col < WIN; ++col) raw[col] = nxt[col];
+    look = lookn;
   }
 }
 
-// dWd, db: blockDim = (channel pairs, GROUPS).  Every group walks its share of the row tiles, keeping
-// KS*KS + 1 running sums per channel in registers: for a tile it issues all loads at once (the up to TX
-// gradients of the row and the KS x (TX + KS - 1) inputs under the window), then adds g[x] * X[x + v] for
-// the kept x only.  The groups of a block are then added in a fixed order through LDS and the block
-// writes one partial; a second kernel adds the partials of all blocks.
+// dWd, db: blockDim = (channel pairs, GROUPS); every group walks strips with the window of X in registers and
+// KS*KS + 1 running sums per channel.  Groups are added through LDS in a fixed order, one partial per block.
 template <int KS, int GROUPS>
-__global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_fast_kernel(const uint32_t* __restrict__ dY,
-                                                                         const int32_t* __restrict__ inv,
-                                                                         const uint32_t* __restrict__ X, int H, int W,
-                                                                         int C2, int tiles_x, int ntiles,
-                                                                         float* __restrict__ part) {
+__global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_strip_kernel(const uint32_t* __restrict__ dY,
+                                                                          const int32_t* __restrict__ inv,
+                                                                          const uint32_t* __restrict__ X, int H, int W,
+                                                                          int C2, int tiles_x, int chunks, int rows_per_chunk,
+                                                                          int nstrips, float* __restrict__ part) {
   constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1, NT = KS * KS + 1;
   extern __shared__ float red[];             // [GROUPS - 1][CHUNK][blockDim.x][2]
   const int cp_raw = blockIdx.y * blockDim.x + threadIdx.x;
@@ -239,52 +299,68 @@ __global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_fast_kernel(const u
 #pragma unroll
   for (int tp = 0; tp < NT; ++tp) { s0[tp] = 0.f; s1[tp] = 0.f; }
 
-  for (int tile = blockIdx.x * GROUPS + grp; tile < ntiles; tile += gridDim.x * GROUPS) {
-    const int x0 = (tile % tiles_x) * DW_TX;
-    const int row = tile / tiles_x;          // b * H + y
-    const int y = row % H;
-    const long long prow = (long long)row * W;
-    const unsigned long long keep =
-        __ballot(lane < DW_TX && x0 + lane < W && inv[prow + min(x0 + lane, W - 1)] >= 0);   // wave-uniform
-    if (keep == 0) continue;
-    // every load of the tile is issued before the first use: clamped addresses, unused values ignored
-    uint32_t g[DW_TX], xw[KS][WIN];
-    {
-      const uint32_t* grow = dY + prow * C2 + cp;
+  for (int strip = blockIdx.x * GROUPS + grp; strip < nstrips; strip += gridDim.x * GROUPS) {
+    const DwStrip t = dw_strip(strip, tiles_x, chunks, rows_per_chunk, H);
+    unsigned colmask = 0;                     // window columns inside the map
 #pragma unroll
-      for (int ox = 0; ox < DW_TX; ++ox) g[ox] = grow[(long long)min(x0 + ox, W - 1) * C2];
+    for (int col = 0; col < WIN; ++col)
+      if (t.x0 + col - PAD >= 0 && t.x0 + col - PAD < W) colmask |= 1u << col;
+    // window rows of X: positions outside the map are zeroed as a row enters the window (zero padding), the
+    // gradients of dropped positions are zeroed too, and the row loop has no branches
+    uint32_t win[KS][WIN], nxt[WIN], g[DW_TX], gn[DW_TX];
+#pragma unroll
+    for (int r = 0; r < KS; ++r) {
+      const int yy = t.y0 + r - PAD;
+      dw_load_row<KS>(X, t.b, yy, t.x0, H, W, C2, cp, win[r]);
+      dw_mask_words<WIN>(win[r], (yy >= 0 && yy < H) ? colmask : 0u);
     }
+    // gradients of row y and, per lane, the inverse-map entry of position x0 + lane (-1: outside or dropped);
+    // the ballot that makes the kept mask is taken when the values are needed, a row later
+    auto load_g = [&](int y, uint32_t (&dst)[DW_TX]) -> int {
+      const long long prow = ((long long)t.b * H + y) * W;
 #pragma unroll
-    for (int u = 0; u < KS; ++u) {
-      const uint32_t* xrow = X + (long long)(row - y + min(max(y + u - PAD, 0), H - 1)) * W * C2 + cp;
-#pragma unroll
-      for (int col = 0; col < WIN; ++col) xw[u][col] = xrow[(long long)min(max(x0 + col - PAD, 0), W - 1) * C2];
-    }
-    float g0[DW_TX], g1[DW_TX];
-#pragma unroll
-    for (int ox = 0; ox < DW_TX; ++ox) {
-      const bool k = (keep >> ox) & 1ull;
-      g0[ox] = k ? dw_lo(g[ox]) : 0.f;
-      g1[ox] = k ? dw_hi(g[ox]) : 0.f;
-      s0[KS * KS] += g0[ox]; s1[KS * KS] += g1[ox];
-    }
-#pragma unroll
-    for (int u = 0; u < KS; ++u) {
-      const int yy = y + u - PAD;
-      if (yy < 0 || yy >= H) continue;               // zero padding: uniform
-#pragma unroll
-      for (int col = 0; col < WIN; ++col) {
-        const int xx = x0 + col - PAD;
-        if (xx < 0 || xx >= W) continue;             // zero padding: uniform
-        const float xa = dw_lo(xw[u][col]), xb = dw_hi(xw[u][col]);
-#pragma unroll
-        for (int ox = 0; ox < DW_TX; ++ox) {
-          const int v = col - ox;
-          if (v < 0 || v >= KS) continue;            // compile time
-          s0[u * KS + v] = fmaf(g0[ox], xa, s0[u * KS + v]);   // g is zero at dropped positions
-          s1[u * KS + v] = fmaf(g1[ox], xb, s1[u * KS + v]);
-        }
+      for (int ox = 0; ox < DW_TX; ++ox) dst[ox] = dY[(prow + min(t.x0 + ox, W - 1)) * C2 + cp];
+      const int v = inv[prow + min(t.x0 + lane, W - 1)];                 // unconditional: no branch, no wait here
+      return (lane < DW_TX && t.x0 + lane < W) ? v : -1;
+    };
+    const int look0 = load_g(t.y0, g);
+    dw_mask_words<DW_TX>(g, (unsigned)__ballot(look0 >= 0));
+    for (int y = t.y0; y < t.y1; ++y) {
+      int lookn = -1;
+      if (y + 1 < t.y1) {
+        dw_load_row<KS>(X, t.b, y + 1 + PAD, t.x0, H, W, C2, cp, nxt);
+        lookn = load_g(y + 1, gn);
       }
+      float g0[DW_TX], g1[DW_TX];
+#pragma unroll
+      for (int ox = 0; ox < DW_TX; ++ox) {
+        g0[ox] = dw_lo(g[ox]);
+        g1[ox] = dw_hi(g[ox]);
+        s0[KS * KS] += g0[ox]; s1[KS * KS] += g1[ox];
+      }
+#pragma unroll
+      for (int u = 0; u < KS; ++u)
+#pragma unroll
+        for (int col = 0; col < WIN; ++col) {
+          const float xa = dw_lo(win[u][col]), xb = dw_hi(win[u][col]);
+#pragma unroll
+          for (int ox = 0; ox < DW_TX; ++ox) {
+            const int v = col - ox;
+            if (v < 0 || v >= KS) continue;            // compile time
+            s0[u * KS + v] = fmaf(g0[ox], xa, s0[u * KS + v]);
+            s1[u * KS + v] = fmaf(g1[ox], xb, s1[u * KS + v]);
+          }
+        }
+#pragma unroll
+      for (int r = 0; r + 1 < KS; ++r)
+#pragma unroll
+        for (int col = 0; col < WIN; ++col) win[r][col] = win[r + 1][col];
+#pragma unroll
+      for (int col = 0; col < WIN; ++col) win[KS - 1][col] = nxt[col];
+      dw_mask_words<WIN>(win[KS - 1], (y + 1 + PAD < H) ? colmask : 0u);
+#pragma unroll
+      for (int ox = 0; ox < DW_TX; ++ox) g[ox] = gn[ox];
+      dw_mask_words<DW_TX>(g, (unsigned)__ballot(lookn >= 0));
     }
   }
 
@@ -384,26 +460,40 @@ int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* i
     const int ct = (int)std::min<int64_t>(DW_THREADS, ceil_div(C2, 64) * 64);
     const int cblocks = (int)ceil_div(C2, ct);
     const int tiles_x = (int)ceil_div(W, DW_TX);
-    const int ntiles = tiles_x * B * H;
+    // rows per strip chunk: a chunk pays for KS - 1 halo rows on top of its own, a short chunk for its start-up;
+    // about one workgroup per CU for dX, somewhat more for the weight gradient (measured on the 50 x 84 x 512 map)
+    const int64_t row_tiles = (int64_t)tiles_x * B * H * cblocks;
+    const char* env_rows = std::getenv("SBP_DW_ROWS");                         // debugging aid for sweeps
+    auto pick_rows = [&](int64_t per) {
+      int r = (int)std::min<int64_t>(16, std::max<int64_t>(3, ceil_div(row_tiles, per)));
+      if (env_rows) r = std::max(1, std::atoi(env_rows));
+      return std::min(r, H);
+    };
+    int rows = pick_rows(256);
+    int chunks = (int)ceil_div(H, rows);
+    int nstrips = tiles_x * chunks * B;
     if (dX) {
-      dim3 grid((unsigned)ntiles, (unsigned)cblocks);
+      dim3 grid((unsigned)nstrips, (unsigned)cblocks);
       if (ks == 7)
-        SBP_LAUNCH(SBP_PROF_DWCONV_DX, s, (dw_dx_fast_kernel<7>), grid, dim3(ct), 0, s, (const uint32_t*)dY, inv,
-                   (const uint32_t*)Wd, H, W, C2, (uint32_t*)dX, tiles_x);
+        SBP_LAUNCH(SBP_PROF_DWCONV_DX, s, (dw_dx_strip_kernel<7>), grid, dim3(ct), 0, s, (const uint32_t*)dY, inv,
+                   (const uint32_t*)Wd, H, W, C2, (uint32_t*)dX, tiles_x, chunks, rows);
       else
-        SBP_LAUNCH(SBP_PROF_DWCONV_DX, s, (dw_dx_fast_kernel<3>), grid, dim3(ct), 0, s, (const uint32_t*)dY, inv,
-                   (const uint32_t*)Wd, H, W, C2, (uint32_t*)dX, tiles_x);
+        SBP_LAUNCH(SBP_PROF_DWCONV_DX, s, (dw_dx_strip_kernel<3>), grid, dim3(ct), 0, s, (const uint32_t*)dY, inv,
+                   (const uint32_t*)Wd, H, W, C2, (uint32_t*)dX, tiles_x, chunks, rows);
     }
     if (dWd || db) {
-      const int nblk = (int)std::min<int64_t>(p.nparts, ceil_div(ntiles, DW_GROUPS));
+      rows = pick_rows(400);
+      chunks = (int)ceil_div(H, rows);
+      nstrips = tiles_x * chunks * B;
+      const int nblk = (int)std::min<int64_t>(p.nparts, ceil_div(nstrips, DW_GROUPS));
       dim3 grid((unsigned)nblk, (unsigned)cblocks);
       const size_t lds = (size_t)(DW_GROUPS - 1) * 10 * ct * 2 * sizeof(float);
       if (ks == 7)
-        SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_dw_fast_kernel<7, DW_GROUPS>), grid, dim3(ct, DW_GROUPS), lds, s,
-                   (const uint32_t*)dY, inv, (const uint32_t*)X, H, W, C2, tiles_x, ntiles, part);
+        SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_dw_strip_kernel<7, DW_GROUPS>), grid, dim3(ct, DW_GROUPS), lds, s,
+                   (const uint32_t*)dY, inv, (const uint32_t*)X, H, W, C2, tiles_x, chunks, rows, nstrips, part);
       else
-        SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_dw_fast_kernel<3, DW_GROUPS>), grid, dim3(ct, DW_GROUPS), lds, s,
-                   (const uint32_t*)dY, inv, (const uint32_t*)X, H, W, C2, tiles_x, ntiles, part);
+        SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_dw_strip_kernel<3, DW_GROUPS>), grid, dim3(ct, DW_GROUPS), lds, s,
+                   (const uint32_t*)dY, inv, (const uint32_t*)X, H, W, C2, tiles_x, chunks, rows, nstrips, part);
       const int n = (ks * ks + 1) * C;
       SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, dw_reduce_kernel, dim3((unsigned)ceil_div(n, 32)), dim3(DW_THREADS), 0,
                  s, part, nblk, ks * ks, C, dWd, db);
