@@ -34,7 +34,8 @@ __device__ __forceinline__ int xcd_chunked_id(int wg, int ntiles) {
   return (wg % kNumXCD) * per + wg / kNumXCD;
 }
 
-static constexpr int kDbSliceRows = 128;     // smallest row slice of a column-sum block
+static constexpr int kDbSliceRows = 128;      // smallest row slice of a column-sum block (general engine)
+static constexpr int kDbSliceRowsBig = 512;   // large-tile engine: fewer, longer blocks with 16 row loads in flight per thread
 static constexpr int kMaxDbSlices = 64;      // at most this many partial sums per channel
 static constexpr int kMaxRowsPerSplit = 2048;   // kept rows per dW split (their ids are staged in LDS)
 
@@ -103,7 +104,7 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
       const int slice = b % nslice, chunk = b / nslice;
       if (a.dbp && chunk * 256 < a.Cout) {
         const int j0 = slice * a.db_slice_rows, j1 = min(a.K, j0 + a.db_slice_rows);
-        colsum_block(smem, a.dY, a.idx_in, a.Cout, j0, j1, chunk * 256, a.dbp + (long long)slice * a.Cout);
+        colsum_block<8>(smem, a.dY, a.idx_in, a.Cout, j0, j1, chunk * 256, a.dbp + (long long)slice * a.Cout);
       }
     }
     return;
@@ -161,7 +162,7 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
       const int slice = b % nslice, chunk = b / nslice;
       if (a.dbp && chunk * 256 < a.Cout) {
         const int j0 = slice * a.db_slice_rows, j1 = min(a.K, j0 + a.db_slice_rows);
-        colsum_block(smem, a.dY, a.idx_in, a.Cout, j0, j1, chunk * 256, a.dbp + (long long)slice * a.Cout);
+        colsum_block<16>(smem, a.dY, a.idx_in, a.Cout, j0, j1, chunk * 256, a.dbp + (long long)slice * a.Cout);
       }
     }
     return;
@@ -443,7 +444,9 @@ static int64_t simulate_grid(const int64_t* n, const int64_t* l, int nseg) {
 }
 
 static int big_zero_blocks(int64_t M) { return (int)std::min<int64_t>(128, std::max<int64_t>(8, ceil_div(M, 256))); }
-static int db_slice_rows_for(int64_t K) { return (int)std::max<int64_t>(kDbSliceRows, ceil_div(ceil_div(K, kMaxDbSlices), 8) * 8); }
+static int db_slice_rows_for(int64_t K, bool big) {
+  return (int)std::max<int64_t>(big ? kDbSliceRowsBig : kDbSliceRows, ceil_div(ceil_div(K, kMaxDbSlices), 8) * 8);
+}
 
 // The dW rows are cut into n_big long splits and, optionally, a few short ones: the short units are
 // dispatched last and fill the CUs that finish early, which evens out schedules whose unit count just
@@ -459,7 +462,7 @@ static BigChoice choose_big(int64_t M, int64_t K, int32_t Cin, int32_t Cout) {
   // the helpers that share the launch (all of them assumed wanted)
   const int64_t n_zero = big_zero_blocks(M);
   const int64_t l_zero = kNsFixedHelper + (M - K) * Cin * 2 / n_zero / kHelperBytesPerNs;
-  const int64_t slice_rows = db_slice_rows_for(K);
+  const int64_t slice_rows = db_slice_rows_for(K, true);
   const int64_t n_db = ceil_div(Cout, 256) * ceil_div(K, slice_rows);
   const int64_t l_db = kNsFixedHelper + slice_rows * 512 / kHelperBytesPerNs;
   BigChoice best{M, K, Cin, Cout, 0, 0, 0, 0, 256, {0, 1, 2}, 0.0};
@@ -587,7 +590,7 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   p.splits = splits;
   size_t off = 0;
   p.off_partial = off;
-  p.db_slice_rows = db_slice_rows_for(K);
+  p.db_slice_rows = db_slice_rows_for(K, p.big);
   p.db_slices = p.mfma ? (int)std::max<int64_t>(1, ceil_div(K, p.db_slice_rows)) : splits;
   off += align_up(((size_t)splits * Cout * Cin + (size_t)std::max(p.db_slices, splits) * Cout) * sizeof(float), 256);
   p.off_inv = off;

@@ -427,8 +427,9 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
 // Partial bias gradient of one row slice: dbp[o] = sum_{j in [j0, j1)} dY[row(j), o] for 256 channels
 // starting at c0.  Thread (x = t & 31, y = t >> 5) owns 8 channels and every 8th row; the eight row
 // lanes are added in a fixed order through LDS.  The slice's row ids are staged in LDS first, so the
-// row loads do not wait for index loads and eight of them are in flight per thread.
+// row loads do not wait for index loads and UNR of them are in flight per thread.
 // ------------------------------------------------------------------------------------------------
+template <int UNR>
 __device__ __forceinline__ void colsum_block(char* smem, const uint16_t* __restrict__ dY,
                                              const int32_t* __restrict__ idx, int Cout, int j0, int j1, int c0,
                                              float* __restrict__ dbp) {
@@ -443,7 +444,7 @@ __device__ __forceinline__ void colsum_block(char* smem, const uint16_t* __restr
     for (int i = threadIdx.x; i < n; i += blockDim.x) ids[i] = idx ? idx[b0 + i] : b0 + i;
     __syncthreads();
     if (col < Cout && y < 8) {
-#pragma unroll 8
+#pragma unroll UNR
       for (int j = y; j < n; j += 8) {
         const uint4 v = *reinterpret_cast<const uint4*>(dY + (long long)ids[j] * Cout + col);
         s[0] += bf16_lo(v.x); s[1] += bf16_hi(v.x); s[2] += bf16_lo(v.y); s[3] += bf16_hi(v.y);
