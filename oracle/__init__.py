@@ -16,6 +16,8 @@ from .sbp_oracle import (  # noqa: F401
     k_from_ratio,
     keep_count,
     sample_indices,
+    sample_indices_cells,
+    keep_count_cells,
     inverse_map,
     forward_cache,
     backward_linear,

@@ -31,7 +31,11 @@ What follows the paper and what is this repository's own reading:
   PARITY UNPINNED by the paper for the generator itself (the mixer is pinned to
   the published SplitMix64 sequence, the structure to the properties the paper
   states: fixed keep ratio per cell, equal visiting frequency of every
-  position).
+  position).  Cells of 3 x 3 and 4 x 4 slots (keep ratios k/9 and k/16) follow
+  the same construction: a permutation of the cell's slots from the hash (the
+  hash scaled to [0, slots!) by a 64 x 64 -> high 64 bit product, Lehmer
+  decoded), the k slots of smallest rank kept, edge cells with v valid slots
+  keeping max(1, round-half-up(k v / slots)) of them.
 * ``act_forward_rows`` / ``act_backward_rows`` / ``backward_layernorm``: the
   paper's implementation (Alg. ``alg:sbp_impl``) wraps "an arbitrary operation
   f": the kept rows go through f with gradient, the dropped rows without, and
@@ -154,6 +158,70 @@ def sample_indices(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sampl
                 for s in chosen:
                     y, x = 2 * cy + (s >> 1), 2 * cx + (s & 1)
                     out.append(b * N + P + y * W + x)
+    return np.asarray(out, dtype=np.int32)
+
+
+def _factorial(n: int) -> int:
+    f = 1
+    for i in range(2, n + 1):
+        f *= i
+    return f
+
+
+def _k_partial_cell(k: int, valid: int, slots: int) -> int:
+    """Kept slots of an edge cell with `valid` of `slots` slots inside the map: round-half-up(k*valid/slots), >= 1."""
+    return max(1, (2 * k * valid + slots) // (2 * slots))
+
+
+def keep_count_cells(B: int, P: int, H: int, W: int, k: int, cell: int) -> int:
+    """Number of kept rows of sample_indices_cells (closed form)."""
+    n = cell * cell
+    fh, fw, rh, rw = H // cell, W // cell, H % cell, W % cell
+    total = k * fh * fw
+    if rw:
+        total += fh * _k_partial_cell(k, cell * rw, n)
+    if rh:
+        total += fw * _k_partial_cell(k, rh * cell, n)
+    if rh and rw:
+        total += _k_partial_cell(k, rh * rw, n)
+    return B * (P + total)
+
+
+def _slot_ranks_cells(h: int, n: int):
+    """Rank of each of the n slots in the permutation drawn from the 64-bit hash h: p = floor(h * n! / 2^64),
+    Lehmer decoded (digit t, most significant first, picks the d_t-th of the slots not yet placed)."""
+    p = (h * _factorial(n)) >> 64
+    remaining = list(range(n))
+    rank = [0] * n
+    for t in range(n):
+        f = _factorial(n - 1 - t)
+        d, p = divmod(p, f)
+        rank[remaining.pop(d)] = t
+    return rank
+
+
+def sample_indices_cells(B, P, H, W, k, cell, seed, stream_id, mode=GRID_PER_CELL, per_sample=True):
+    """Grid-wise keep-set with cells of cell x cell slots (cell = 3 or 4), k of the cell^2 slots of every cell kept:
+    keep ratio k / cell^2.  Same hash chain and canonical order as sample_indices (sample-major; prefix rows; cells
+    row-major; inside a cell the kept slots ascending, slot s = cell * (y % cell) + (x % cell))."""
+    n = cell * cell
+    if cell not in (3, 4) or not (1 <= k <= n):
+        raise ValueError("need cell in (3, 4) and 1 <= k <= cell^2")
+    N = P + H * W
+    ch, cw = -(-H // cell), -(-W // cell)
+    base = _absorb(_absorb(0, seed), stream_id)
+    out = []
+    for b in range(B):
+        hb = _absorb(base, b if per_sample else 0)
+        out.extend(b * N + p for p in range(P))
+        for cy in range(ch):
+            for cx in range(cw):
+                c = 0 if mode == GRID_SHARED else cy * cw + cx
+                rank = _slot_ranks_cells(_absorb(hb, c), n)
+                valid = [s for s in range(n) if cell * cy + s // cell < H and cell * cx + s % cell < W]
+                kc = k if len(valid) == n else _k_partial_cell(k, len(valid), n)
+                for s in sorted(sorted(valid, key=lambda q: rank[q])[:kc]):
+                    out.append(b * N + P + (cell * cy + s // cell) * W + cell * cx + s % cell)
     return np.asarray(out, dtype=np.int32)
 
 

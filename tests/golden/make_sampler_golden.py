@@ -26,7 +26,32 @@ CASES = [
 ]
 
 
+CELL_CASES = [
+    # B P H  W  k cell mode per_sample seed stream
+    (2, 0, 6, 6, 4, 3, 0, 1, 0, 0),
+    (1, 1, 7, 10, 5, 3, 0, 1, 7, 70),
+    (2, 0, 8, 8, 4, 4, 0, 1, 1, 2),
+    (1, 1, 14, 14, 8, 4, 0, 1, 3, 4),
+    (2, 0, 9, 9, 3, 3, 1, 1, 5, 6),
+    (2, 1, 5, 11, 2, 4, 0, 0, 18446744073709551615, 9),
+]
+
+
+def write_cells():
+    path = os.path.join(HERE, "sampler_cells_golden.txt")
+    with open(path, "w") as f:
+        f.write("# keep-index vectors of the 3 x 3 and 4 x 4 cell samplers, written by tests/golden/make_sampler_golden.py\n")
+        f.write("# from the CPU oracle.  Not from the paper: they freeze this repository's sampler specification.\n")
+        f.write("# Format:  B P H W k cell mode per_sample seed stream : idx...\n")
+        for c in CELL_CASES:
+            B, P, H, W, k, cell, mode, ps, seed, stream = c
+            idx = oracle.sample_indices_cells(B, P, H, W, k, cell, seed, stream, mode=mode, per_sample=bool(ps))
+            f.write(" ".join(str(v) for v in c) + " : " + " ".join(str(int(v)) for v in idx) + "\n")
+    print("wrote", path)
+
+
 def main():
+    write_cells()
     path = os.path.join(HERE, "sampler_golden.txt")
     with open(path, "w") as f:
         f.write("# keep-index vectors written by tests/golden/make_sampler_golden.py from the CPU oracle.\n")
