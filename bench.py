@@ -432,8 +432,11 @@ def measure_samplers(torch, sbp, si):
         idx = torch.empty(M, dtype=torch.int32, device="cuda")
         inv = torch.empty(M, dtype=torch.int32, device="cuda")
         res = {}
-        for name, kw in (("grid", dict(mode=sbp.GRID_PER_CELL)), ("random_mask", dict(mode=sbp.RANDOM_MASK)),
+        for name, kw in (("grid", dict(mode=sbp.GRID_PER_CELL)), ("grid 4x4 cells, 8 of 16", dict(mode=sbp.GRID_PER_CELL, cell=4, k=8)),
+                         ("random_mask", dict(mode=sbp.RANDOM_MASK)),
                          ("temporal(8 frames, 2 of 4)", dict(mode=sbp.TEMPORAL, cell=4))):
+            kw = dict(kw)
+            k = kw.pop("k", 2)
             if name.startswith("temporal"):
                 if (H * W) % 8:
                     continue
@@ -441,12 +444,12 @@ def measure_samplers(torch, sbp, si):
             else:
                 geom = (B, P, H, W)
             for i in range(3):
-                sbp.sample_indices(*geom, 2, 0, i, idx_out=idx, inv_out=inv, **kw)
+                sbp.sample_indices(*geom, k, 0, i, idx_out=idx, inv_out=inv, **kw)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for i in range(50):
-                sbp.sample_indices(*geom, 2, 0, 10 + i, idx_out=idx, inv_out=inv, **kw)
+                sbp.sample_indices(*geom, k, 0, 10 + i, idx_out=idx, inv_out=inv, **kw)
             e1.record()
             torch.cuda.synchronize()
             res[name] = {"us": round(e0.elapsed_time(e1) / 50 * 1e3, 2)}

@@ -49,7 +49,7 @@ extern "C" {
 #define SBP_BF16  1   /* bf16 storage, fp32 accumulate (MFMA) */
 
 /* sampler modes */
-#define SBP_GRID_PER_CELL 0  /* independent draw in every 2x2 cell */
+#define SBP_GRID_PER_CELL 0  /* independent draw in every cell */
 #define SBP_GRID_SHARED   1  /* one slot permutation shared by all cells of a sample (regular lattice) */
 /* The paper's other strategy, "random mask sampling": per sample exactly round-half-up(k/4 * H*W) (>= 1) of
  * the grid positions, a uniformly random subset without grid structure (those with the smallest hashed keys;
@@ -71,8 +71,9 @@ extern "C" {
  * structured sample drawn afresh every step).  The paper gives no algorithm; the reading
  * implemented here: the H x W map of each sample is tiled into 2x2 cells and k of the 4
  * slots of every cell are kept (k = round(4 r)); partial cells on an odd edge with c valid
- * slots keep max(1, round(k c / 4)) of them.  The draw is a pure function of
- * (seed, stream_id, sample, cell): a SplitMix64-based counter hash, no state.
+ * slots keep max(1, round(k c / 4)) of them.  cell = 3 or 4 tiles the map into 3x3 or 4x4 cells and keeps k of
+ * the 9 or 16 slots (keep ratios k/9, k/16; edge cells with v valid slots keep max(1, round(k v / cell^2))).
+ * The draw is a pure function of (seed, stream_id, sample, cell): a SplitMix64-based counter hash, no state.
  * Rows are numbered b*(P + H*W) + p for the P always-kept prefix rows of sample b (the
  * ViT class token) and b*(P + H*W) + P + y*W + x for grid position (y, x).
  */
@@ -80,8 +81,8 @@ typedef struct sbp_sample_desc {
   int32_t  B;          /* samples in the batch, >= 1 */
   int32_t  P;          /* always-kept prefix rows per sample, >= 0 */
   int32_t  H, W;       /* grid, >= 1 each */
-  int32_t  cell;       /* cell edge; must be 2 (SBP_TEMPORAL: frames per cell, 2..4) */
-  int32_t  k;          /* kept slots per full cell, 1..4 (SBP_TEMPORAL: kept frames per cell, 1..cell) */
+  int32_t  cell;       /* cell edge: 2 (the default), 3 or 4 in the grid modes; 2 for SBP_RANDOM_MASK; SBP_TEMPORAL: frames per cell, 2..4 */
+  int32_t  k;          /* kept slots per full cell, 1..cell^2 (SBP_TEMPORAL: kept frames per cell, 1..cell) */
   int32_t  mode;       /* SBP_GRID_PER_CELL, SBP_GRID_SHARED, SBP_RANDOM_MASK or SBP_TEMPORAL */
   int32_t  per_sample; /* 1: every sample draws its own mask; 0: one mask for the batch */
   uint64_t seed;       /* run seed */
@@ -94,7 +95,7 @@ const char* sbp_status_string(int32_t status);
 const char* sbp_last_error(void);
 
 /* Host only.  Kept slots per cell for keep ratio r: round-half-up(r*cell*cell), clamped to
- * [1, cell*cell].  Returns SBP_ERR_RATIO if r is not in (0, 1], SBP_ERR_SHAPE if cell != 2. */
+ * [1, cell*cell].  Returns SBP_ERR_RATIO if r is not in (0, 1], SBP_ERR_SHAPE if cell is not 2, 3 or 4. */
 int32_t sbp_k_from_ratio(double r, int32_t cell);
 
 /* Host only.  Number of kept rows K of a draw (closed form), or a negative SBP_ERR_* code.
@@ -104,7 +105,7 @@ int64_t sbp_keep_count(const sbp_sample_desc* desc);
 /*
  * Step "sample keep-set".  Writes the kept row ids, int32, into idx[0..K) in canonical
  * order: sample-major; inside a sample the P prefix rows, then (grid modes) the cells in row-major cell
- * order, and inside a cell the kept slots in ascending slot number 2*(y%2) + (x%2); the other modes
+ * order, and inside a cell the kept slots in ascending slot number cell*(y%cell) + (x%cell); the other modes
  * write ascending row ids.
  *   idx          device, out, capacity idx_capacity elements (>= K else SBP_ERR_CAPACITY)
  *   inv          device, out, [B*(P+H*W)] or NULL: inv[row] = position of row in idx, -1 if dropped

@@ -51,9 +51,12 @@ static int32_t validate_desc(const sbp_sample_desc* d) {
   if (d->mode == SBP_TEMPORAL) {
     if (d->cell < 2 || d->cell > 4) return fail(SBP_ERR_SHAPE, "temporal cell must be 2..4 frames, got %d", d->cell);
     if (d->k < 1 || d->k > d->cell) return fail(SBP_ERR_RATIO, "k must be in 1..cell, got %d", d->k);
-  } else {
+  } else if (d->mode == SBP_RANDOM_MASK) {
     if (d->cell != 2) return fail(SBP_ERR_SHAPE, "cell must be 2, got %d", d->cell);
     if (d->k < 1 || d->k > 4) return fail(SBP_ERR_RATIO, "k must be in 1..4, got %d", d->k);
+  } else {
+    if (d->cell < 2 || d->cell > 4) return fail(SBP_ERR_SHAPE, "cell must be 2, 3 or 4, got %d", d->cell);
+    if (d->k < 1 || d->k > d->cell * d->cell) return fail(SBP_ERR_RATIO, "k must be in 1..cell^2, got %d", d->k);
   }
   if (d->mode != SBP_GRID_PER_CELL && d->mode != SBP_GRID_SHARED && d->mode != SBP_RANDOM_MASK && d->mode != SBP_TEMPORAL)
     return fail(SBP_ERR_FLAGS, "unknown sampler mode %d", d->mode);
@@ -90,7 +93,7 @@ const char* sbp_status_string(int32_t st) {
 const char* sbp_last_error(void) { return g_err; }
 
 int32_t sbp_k_from_ratio(double r, int32_t cell) {
-  if (cell != 2) return fail(SBP_ERR_SHAPE, "cell must be 2, got %d", cell);
+  if (cell < 2 || cell > 4) return fail(SBP_ERR_SHAPE, "cell must be 2, 3 or 4, got %d", cell);
   if (!(r > 0.0 && r <= 1.0)) return fail(SBP_ERR_RATIO, "keep ratio %g not in (0,1]", r);
   int32_t n = cell * cell;
   int32_t k = (int32_t)std::floor(r * n + 0.5);

@@ -1,4 +1,4 @@
-// Grid-wise keep-set sampler: one thread per 2x2 cell (plus one per prefix row).
+// Grid-wise keep-set sampler: one thread per cell (plus one per prefix row); 2 x 2 cells, and 3 x 3 / 4 x 4 further down.
 //
 // The paper ("How to sample the gradient keep mask?") asks for a structured sample that is
 // drawn afresh every step and visits every position equally often; it gives no algorithm.
@@ -51,6 +51,42 @@ static SampleGeom make_geom(const sbp_sample_desc& d) {
   return g;
 }
 
+// ---- cells of 3 x 3 and 4 x 4 slots (keep ratios k/9 and k/16) ---------------------------------------
+// Same hash chain, same canonical order.  The permutation of the n = cell^2 slots is Lehmer-decoded from
+// p = floor(h n! / 2^64) (digit t, most significant first, picks the d_t-th slot not yet placed); the k slots of
+// smallest rank are kept; an edge cell with v valid slots keeps max(1, round-half-up(k v / n)) of them.
+struct CellGeom {
+  int B, P, H, W, k, cell, shared, per_sample;
+  int cw, fh, fw, rh, rw;     // cells per row; full cells per column / row; rows / columns of the partial cells
+  int k_fe, k_ef, k_ee;       // kept slots of right-edge, bottom-edge and corner cells
+  int row_full, row_last;     // idx entries of a row of full-height cells / of the partial last row
+  int units;                  // work items per sample: prefix rows + cells
+  int per_sample_K, N;
+  uint64_t base;
+};
+__host__ __device__ static inline int k_partial_cell(int k, int valid, int slots) {
+  const int v = (2 * k * valid + slots) / (2 * slots);
+  return v < 1 ? 1 : v;
+}
+static CellGeom make_cell_geom(const sbp_sample_desc& d) {
+  CellGeom g;
+  const int c = d.cell, n = c * c;
+  g.B = d.B; g.P = d.P; g.H = d.H; g.W = d.W; g.k = d.k; g.cell = c;
+  g.shared = d.mode == SBP_GRID_SHARED; g.per_sample = d.per_sample;
+  g.cw = (d.W + c - 1) / c; g.fh = d.H / c; g.fw = d.W / c; g.rh = d.H % c; g.rw = d.W % c;
+  g.k_fe = g.rw ? k_partial_cell(d.k, c * g.rw, n) : 0;
+  g.k_ef = g.rh ? k_partial_cell(d.k, g.rh * c, n) : 0;
+  g.k_ee = (g.rh && g.rw) ? k_partial_cell(d.k, g.rh * g.rw, n) : 0;
+  g.row_full = d.k * g.fw + g.k_fe;
+  g.row_last = g.k_ef * g.fw + g.k_ee;
+  const int ch = (d.H + c - 1) / c;
+  g.units = d.P + ch * g.cw;
+  g.per_sample_K = d.P + g.fh * g.row_full + (g.rh ? g.row_last : 0);
+  g.N = d.P + d.H * d.W;
+  g.base = absorb(absorb(0, d.seed), d.stream_id);
+  return g;
+}
+
 // ---- the other samplers: same row numbering, same hash --------------------------------------------------
 // random mask: exactly n_keep of the H*W grid positions of a sample, those with the smallest (key, position),
 // key = absorb(h_sample, position); temporal subsets: H frames of W positions, k of every `cell` frames kept whole.
@@ -70,6 +106,10 @@ static inline int temporal_keep_frames(const sbp_sample_desc& d) {
 int64_t keep_count_host(const sbp_sample_desc& d) {
   if (d.mode == SBP_RANDOM_MASK) return (int64_t)d.B * (d.P + random_keep(d));
   if (d.mode == SBP_TEMPORAL) return (int64_t)d.B * (d.P + (int64_t)temporal_keep_frames(d) * d.W);
+  if (d.cell != 2) {
+    const CellGeom c = make_cell_geom(d);
+    return (int64_t)c.B * c.per_sample_K;
+  }
   SampleGeom g = make_geom(d);
   return (int64_t)g.B * g.per_sample_K;
 }
@@ -284,6 +324,57 @@ __host__ __device__ static inline void sample_unit(const SampleGeom& g, long lon
   }
 }
 
+__global__ void __launch_bounds__(256) sample_cells_kernel(CellGeom g, int32_t* __restrict__ idx, int32_t* __restrict__ inv) {
+  const long long total = (long long)g.B * g.units;
+  const int c = g.cell, n = c * c;
+  for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < total; t += (long long)gridDim.x * blockDim.x) {
+    const int b = (int)(t / g.units), u = (int)(t - (long long)b * g.units);
+    const int row0 = b * g.N, out0 = b * g.per_sample_K;
+    if (u < g.P) {
+      idx[out0 + u] = row0 + u;
+      if (inv) inv[row0 + u] = out0 + u;
+      continue;
+    }
+    const int ci = u - g.P, cy = ci / g.cw, cx = ci - cy * g.cw;
+    const bool full_h = cy < g.fh, full_w = cx < g.fw;
+    const int vh = full_h ? c : g.rh, vw = full_w ? c : g.rw;
+    const int kc = full_h ? (full_w ? g.k : g.k_fe) : (full_w ? g.k_ef : g.k_ee);
+    const int off = g.P + (full_h ? cy * g.row_full : g.fh * g.row_full) + cx * (full_h ? g.k : g.k_ef);
+    uint64_t h = absorb(g.base, g.per_sample ? (uint64_t)b : 0ull);
+    h = absorb(h, g.shared ? 0ull : (uint64_t)ci);
+    // p = floor(h * n! / 2^64); factorial-base digits most significant first
+    uint64_t fact = 1;
+    for (int i = 2; i <= n; ++i) fact *= (uint64_t)i;
+    uint64_t p = __umul64hi(h, fact);
+    uint32_t freem = (1u << n) - 1u, keepm = 0;
+    int taken = 0;
+    uint64_t f = fact;
+    for (int r = 0; r < n && taken < kc; ++r) {       // slots by increasing rank, until kc valid ones are kept
+      f /= (uint64_t)(n - r);                          // (n - 1 - r)!
+      const uint32_t d = (uint32_t)(p / f);
+      p -= (uint64_t)d * f;
+      uint32_t m = freem;                              // the d-th set bit of freem
+      for (uint32_t q = 0; q < d; ++q) m &= m - 1u;
+      const uint32_t slot = (uint32_t)__ffs((int)m) - 1u;
+      freem &= ~(1u << slot);
+      const int sy = (int)slot / c, sx = (int)slot - sy * c;
+      if (sy < vh && sx < vw) { keepm |= 1u << slot; ++taken; }
+    }
+    int pos = out0 + off;
+    for (int sy = 0; sy < vh; ++sy)
+      for (int sx = 0; sx < vw; ++sx) {                // ascending slot number
+        const int row = row0 + g.P + (c * cy + sy) * g.W + c * cx + sx;
+        if ((keepm >> (sy * c + sx)) & 1u) {
+          idx[pos] = row;
+          if (inv) inv[row] = pos;
+          ++pos;
+        } else if (inv) {
+          inv[row] = -1;
+        }
+      }
+  }
+}
+
 __global__ void __launch_bounds__(256) sample_kernel(SampleGeom g, int32_t* __restrict__ idx,
                                                      int32_t* __restrict__ inv) {
   const long long total = (long long)g.B * (g.P + g.ch * g.cw);
@@ -310,6 +401,13 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
     const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>((total + 255) / 256, 65535));
     SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_temporal_kernel, dim3(blocks), dim3(256), 0, s, v, idx, inv);
     return check_launch("sample_temporal_kernel");
+  }
+  if (d.cell != 2) {
+    const CellGeom c = make_cell_geom(d);
+    const long long total = (long long)c.B * c.units;
+    const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>((total + 255) / 256, 65535));
+    SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_cells_kernel, dim3(blocks), dim3(256), 0, s, c, idx, inv);
+    return check_launch("sample_cells_kernel");
   }
   SampleGeom g = make_geom(d);
   long long total = (long long)g.B * (g.P + g.ch * g.cw);

@@ -47,8 +47,10 @@ def test_k_from_ratio_rejects_bad_input():
             sbp.k_from_ratio(r)
         assert e.value.status == -3
     with pytest.raises(sbp.SbpError) as e:
-        sbp.k_from_ratio(0.5, cell=3)
+        sbp.k_from_ratio(0.5, cell=5)
     assert e.value.status == -2
+    assert sbp.k_from_ratio(0.5, cell=3) == oracle.k_from_ratio(0.5, 3) == 5      # round-half-up(4.5)
+    assert sbp.k_from_ratio(0.25, cell=4) == oracle.k_from_ratio(0.25, 4) == 4
 
 
 @pytest.mark.parametrize("geom", [(2, 0, 14, 14), (64, 1, 14, 14), (2, 0, 200, 336), (2, 0, 5, 7), (1, 2, 3, 3),
@@ -57,6 +59,15 @@ def test_keep_count_matches_oracle(geom):
     B, P, H, W = geom
     for k in (1, 2, 3, 4):
         assert sbp.keep_count(B, P, H, W, k) == oracle.keep_count(B, P, H, W, k)
+
+
+@pytest.mark.parametrize("geom", [(2, 1, 14, 14), (2, 0, 200, 336), (2, 0, 5, 7), (1, 2, 3, 3), (3, 1, 1, 6), (1, 0, 1, 1),
+                                  (2, 0, 50, 84), (1, 0, 13, 9)])
+def test_keep_count_of_larger_cells_matches_oracle(geom):
+    B, P, H, W = geom
+    for cell, ks in ((3, (1, 4, 5, 9)), (4, (1, 4, 8, 16))):
+        for k in ks:
+            assert sbp.keep_count(B, P, H, W, k, cell=cell) == oracle.keep_count_cells(B, P, H, W, k, cell)
 
 
 def _desc(**kw):
@@ -70,7 +81,7 @@ def _desc(**kw):
 
 
 @pytest.mark.parametrize("kw,status", [
-    (dict(B=0), -2), (dict(P=-1), -2), (dict(H=0), -2), (dict(W=0), -2), (dict(cell=4), -2),
+    (dict(B=0), -2), (dict(P=-1), -2), (dict(H=0), -2), (dict(W=0), -2), (dict(cell=5), -2), (dict(cell=1), -2), (dict(cell=3, k=10), -3), (dict(cell=3, mode=2), -2),
     (dict(k=0), -3), (dict(k=5), -3), (dict(mode=7), -8), (dict(per_sample=2), -8),
     (dict(B=70000, H=200, W=200), -2),
 ])

@@ -410,3 +410,21 @@ def test_convnext_block_chain():
     full = np.arange(M, dtype=np.int32)
     fWd, fb, fX = oracle.backward_dwconv(f64(g1).reshape(B, H, W, C), full, si.to_f64(Xd), si.to_f64(Wdw), 3)
     assert np.array_equal(fWd, rWd) and np.array_equal(fX, rX)
+
+
+@pytest.mark.parametrize("geom", [(2, 1, 14, 14, 4, 3), (64, 1, 14, 14, 8, 4), (2, 0, 200, 336, 4, 4), (2, 0, 50, 84, 5, 3),
+                                  (3, 2, 7, 10, 9, 3), (1, 0, 1, 1, 3, 4), (2, 0, 5, 11, 2, 4), (1, 0, 13, 9, 16, 4)])
+@pytest.mark.parametrize("mode", ["per_cell", "shared"])
+def test_sampler_with_larger_cells_bit_exact(geom, mode):
+    B, P, H, W, k, cell = geom
+    m = sbp.GRID_SHARED if mode == "shared" else sbp.GRID_PER_CELL
+    om = oracle.GRID_SHARED if mode == "shared" else oracle.GRID_PER_CELL
+    for seed, stream, ps in ((0, 0, True), (7, 123456789, True), (2**64 - 1, 5, False)):
+        idx, inv = sbp.sample_indices(B, P, H, W, k, seed, stream, mode=m, per_sample=ps, want_inv=True, cell=cell)
+        torch.cuda.synchronize()
+        ref = oracle.sample_indices_cells(B, P, H, W, k, cell, seed, stream, mode=om, per_sample=ps)
+        got = idx.cpu().numpy()
+        assert np.array_equal(got, ref)
+        want_inv = np.full(B * (P + H * W), -1, dtype=np.int32)
+        want_inv[ref] = np.arange(len(ref), dtype=np.int32)
+        assert np.array_equal(inv.cpu().numpy(), want_inv)
