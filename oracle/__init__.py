@@ -29,6 +29,7 @@ from .sbp_oracle import (  # noqa: F401
     act_backward_rows,
     layernorm_rows,
     backward_layernorm,
+    backward_layerscale,
     forward_cache_patches,
     attention_scores,
     backward_attention,

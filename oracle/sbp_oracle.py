@@ -44,6 +44,8 @@ What follows the paper and what is this repository's own reading:
   row-wise f (GELU, LayerNorm) that is the ordinary backward of f on the kept
   rows, zero on the dropped rows, parameter gradients summed over the kept
   rows only.  GELU is the exact form x Phi(x) used by ViT and ConvNeXt.
+  ``backward_layerscale`` is the same for ConvNeXt's per-channel layer scale
+  U = gamma * Y at the end of the block's branch.
 * ``backward_downsample`` / ``forward_cache_patches``: a convolution whose stride
   is at least its kernel size (the p x p, stride p down-sampling layers of
   ConvNeXt).  The paper's section "Calculation of Convolutional Layers" notes
@@ -417,6 +419,15 @@ def backward_layernorm(dU_k, X_k, gamma, eps, idx, M):
 # Down-sampling convolution, kernel p x p, stride p (section "Calculation of Convolutional Layers",
 # the case s >= k): Y[b, yo, xo, o] = sum_{dy, dx, c} X[b, p yo + dy, p xo + dx, c] Wc[o, dy, dx, c] + bias[o].
 # ---------------------------------------------------------------------------------------------
+def backward_layerscale(dU_k, Y_k, gamma):
+    """Backward of the per-channel scale U = gamma * Y on the kept rows (Alg. alg:sbp_impl with f = the scale):
+    dY_k = dU_k * gamma, dgamma = sum over the kept rows of dU_k * Y_k (dropped rows contribute nothing)."""
+    dU_k = np.asarray(dU_k, dtype=np.float64)
+    Y_k = np.asarray(Y_k, dtype=np.float64)
+    gamma = np.asarray(gamma, dtype=np.float64)
+    return dU_k * gamma[None, :], (dU_k * Y_k).sum(axis=0)
+
+
 def forward_cache_patches(X, idx, p):
     """Rows [K, p*p*C]: the p x p input patch under every kept output position, (dy, dx, c) order."""
     X = np.asarray(X)

@@ -134,3 +134,22 @@ def test_mlp_branch_chain_with_one_keep_set_is_autograd_of_the_wrapped_layers():
     dX, dgamma, dbeta = oracle.backward_layernorm(dU[idx], X.detach().numpy()[idx], gamma.detach().numpy(), eps, idx, M)
     for got, ref in ((dW2, W2.grad), (db2, b2.grad), (dW1, W1.grad), (db1, b1.grad), (dX, X.grad), (dgamma, gamma.grad), (dbeta, beta.grad)):
         assert np.allclose(got, ref.numpy(), atol=1e-11)
+
+
+def test_backward_layerscale_is_autograd_of_the_wrapped_scale_and_closed_forms():
+    M, C, K = 37, 11, 15
+    g, idx, drop = _case(M, C, K, 21)
+    Y = torch.tensor(g.normal(size=(M, C)), requires_grad=True)
+    gamma = torch.tensor(g.normal(size=C) * 0.3 + 1.0, requires_grad=True)
+    G = np.zeros((M, C)); G[idx] = g.normal(size=(K, C))          # the gradient arrives with zero rows at dropped positions
+    out = _sbp_f(lambda y: y * gamma, Y, idx, drop, C)
+    (out * torch.tensor(G)).sum().backward()
+    dY_k, dgamma = oracle.backward_layerscale(G[idx], Y.detach().numpy()[idx], gamma.detach().numpy())
+    np.testing.assert_allclose(dY_k, Y.grad.numpy()[idx], rtol=1e-13, atol=1e-15)
+    assert np.all(Y.grad.numpy()[drop] == 0)
+    np.testing.assert_allclose(dgamma, gamma.grad.numpy(), rtol=1e-12, atol=1e-14)
+    # closed forms: gamma = 1 passes the gradient through; rows of ones count the kept rows
+    dY1, dg1 = oracle.backward_layerscale(np.ones((K, C)), np.ones((K, C)), np.ones(C))
+    assert np.all(dY1 == 1.0) and np.all(dg1 == K)
+    # a planted mistake (dgamma taken against the gradient instead of the input) differs
+    assert not np.allclose((G[idx] * G[idx]).sum(0), dgamma)
