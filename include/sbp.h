@@ -239,6 +239,23 @@ int32_t sbp_act_backward_rows(const void* dH_k, const void* Z_k, int64_t K, int3
                               int32_t act, void* dZ_k, void* stream);
 
 /*
+ * Backward of the per-channel layer scale U = gamma * Y (the last step of a ConvNeXt block's branch) on the kept
+ * rows (paper, Alg. alg:sbp_impl with f = the scale; kept rows through f with gradient, dropped rows without):
+ *   dY_k = dU_k * gamma,     dgamma[c] = sum over the kept rows j of dU_k[j, c] * Y_k[j, c]
+ *   dU_k, Y_k  device, in,  [K, C] of `dtype` (compact: gather the kept rows of the block output's gradient with
+ *              sbp_forward_cache; Y_k is the cached kept rows of the scale's input)
+ *   gamma      device, in,  fp32 [C];   dgamma  device, out, fp32 [C] or NULL;   dY_k  device, out, [K, C] or NULL
+ *              (dY_k may be dU_k: every element is read before it is written)
+ *   workspace  sbp_backward_layerscale_workspace(K, C) bytes, 256-byte aligned (partial sums of dgamma)
+ *   flags      SBP_FLAG_ACCUMULATE_DW: dgamma += instead of overwrite; nothing else
+ * fp32 arithmetic, dgamma summed in a fixed order (deterministic); bf16 outputs rounded once.
+ */
+size_t sbp_backward_layerscale_workspace(int64_t K, int32_t C);
+int32_t sbp_backward_layerscale(const void* dU_k, const void* Y_k, const float* gamma, int64_t K, int32_t C,
+                                int32_t dtype, float* dgamma, void* dY_k, void* workspace, size_t workspace_bytes,
+                                uint32_t flags, void* stream);
+
+/*
  * Backward of scaled dot-product attention on the kept tokens: the variant "Drop QKV" that the paper picks
  * for image transformers (main text, section Design Strategies, "How to apply SBP on MHSA?"; supplement,
  * section Gradient Calculation of Attention Layers: eq:attention, eq:grad_qkv, and the gradient dropout on

@@ -210,6 +210,23 @@ def backward_layernorm(dU_k, X_k, gamma, eps, idx, M, inv=None, flags=0, want=("
     return dgamma, dbeta, dX
 
 
+def backward_layerscale(dU_k, Y_k, gamma, flags=0, want=("dgamma", "dY"), dgamma=None, dY=None, workspace=None):
+    """Per-channel layer scale backward on the kept rows.  dU_k, Y_k: [K, C]; gamma fp32 [C].  Returns (dgamma, dY_k)."""
+    K, C = Y_k.shape
+    dev = Y_k.device
+    if "dgamma" in want and dgamma is None:
+        dgamma = torch.empty((C,), dtype=torch.float32, device=dev)
+    if "dY" in want and dY is None:
+        dY = torch.empty_like(dU_k)
+    need = int(_lib.lib().sbp_backward_layerscale_workspace(K, C))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _lib.check(_lib.lib().sbp_backward_layerscale(
+        _dev(dU_k, "dU_k"), _dev(Y_k, "Y_k"), _dev(gamma, "gamma"), K, C, _dtype_code(Y_k), _dev(dgamma, "dgamma"),
+        _dev(dY, "dY_k"), _dev(workspace, "workspace"), workspace.numel(), flags, _stream(dev)))
+    return dgamma, dY
+
+
 def backward_dwconv_workspace(B, H, W, C, ks, K, dtype_code, flags=0) -> int:
     return int(_lib.lib().sbp_backward_dwconv_workspace(B, H, W, C, ks, K, dtype_code, flags))
 

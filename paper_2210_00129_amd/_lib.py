@@ -38,6 +38,8 @@ PROTOTYPES = {
     "sbp_backward_layernorm_workspace": (c_sz, [c_i64, c_i64, c_i32, c_i32, c_u32]),
     "sbp_backward_layernorm": (c_i32, [c_vp, c_vp, c_vp, ctypes.c_float, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32,
                                        c_vp, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),
+    "sbp_backward_layerscale_workspace": (c_sz, [c_i64, c_i32]),
+    "sbp_backward_layerscale": (c_i32, [c_vp, c_vp, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),
     "sbp_backward_attention_engine": (c_i32, [c_i32, c_i32, c_i32]),
     "sbp_backward_attention": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, ctypes.c_float, c_i32, c_vp, c_vp]),
     "sbp_backward_linear_engine": (c_i32, [c_i64, c_i64, c_i32, c_i32, c_i32, c_u32, ctypes.POINTER(c_i32)]),

@@ -256,6 +256,25 @@ int32_t sbp_act_backward_rows(const void* dHk, const void* Zk, int64_t K, int32_
   return launch_act_rows(dHk, Zk, K * (int64_t)C, dtype, act, true, dZk, static_cast<hipStream_t>(stream));
 }
 
+size_t sbp_backward_layerscale_workspace(int64_t K, int32_t C) {
+  if (K < 0 || K > INT32_MAX || C < 1) return 0;
+  return align_up((size_t)ls_blocks(K) * C * sizeof(float), 256);
+}
+
+int32_t sbp_backward_layerscale(const void* dUk, const void* Yk, const float* gamma, int64_t K, int32_t C, int32_t dtype,
+                                float* dgamma, void* dYk, void* ws, size_t ws_bytes, uint32_t flags, void* stream) {
+  int32_t st = validate_rows(K, C, dtype);
+  if (st != SBP_OK) return st;
+  if (flags & ~SBP_FLAG_ACCUMULATE_DW) return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);
+  if (!dgamma && !dYk) return SBP_OK;
+  if (K > 0 && (!dUk || !Yk || !gamma)) return fail(SBP_ERR_NULL, "dU_k, Y_k or gamma is NULL");
+  const size_t need = sbp_backward_layerscale_workspace(K, C);
+  if (dgamma && K > 0 && (!ws || ws_bytes < need || (reinterpret_cast<uintptr_t>(ws) % 256) != 0))
+    return fail(SBP_ERR_WORKSPACE, "workspace missing, misaligned or smaller than %zu bytes", need);
+  return launch_backward_layerscale(dUk, Yk, gamma, K, C, dtype, dgamma, dYk, static_cast<float*>(ws), flags,
+                                    static_cast<hipStream_t>(stream));
+}
+
 static int32_t validate_attention(int32_t B, int32_t n_k, int32_t h, int32_t d, int32_t dtype) {
   if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
   if (B < 1 || n_k < 0 || h < 1) return fail(SBP_ERR_SHAPE, "bad shape B=%d n_k=%d h=%d", B, n_k, h);

@@ -76,6 +76,11 @@ void launch_build_inverse(const int32_t* idx, int64_t K, int32_t* inv, hipStream
 void launch_zero_dropped_rows(const int32_t* idx, const int32_t* inv, int64_t K, int64_t M, int64_t row_bytes,
                               void* out, hipStream_t s);
 
+// per-channel layer scale on compact rows: partial sums [ls_blocks(K)][C]
+int ls_blocks(int64_t K);
+int32_t launch_backward_layerscale(const void* dU, const void* Y, const float* gamma, int64_t K, int32_t C, int32_t dtype,
+                                   float* dgamma, void* dY, float* partial, uint32_t flags, hipStream_t s);
+
 // ---- attention backward on the kept tokens -------------------------------------------------------
 int attention_engine(int32_t n_k, int32_t d, int32_t dtype);   // 1: matrix-core kernel, 0: plain kernel
 int32_t launch_backward_attention(const void* qkv, const void* A, const void* dA, const float* lse, int32_t B, int32_t n_k,

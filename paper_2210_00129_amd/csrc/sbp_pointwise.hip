@@ -406,4 +406,89 @@ int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* X
   return check_launch("backward_layernorm");
 }
 
+// ---- per-channel layer scale U = gamma * Y on the kept rows ---------------------------------------------
+// dY_k = dU_k * gamma, dgamma = sum_j dU_k[j] * Y_k[j].  A thread owns VEC (8 or 1) adjacent channels and walks
+// the rows of its block's slab, four rows in flight; the block writes one partial of dgamma, a second launch adds
+// the partials in block order (deterministic).
+static constexpr int kLsMaxBlocks = 512;
+
+template <typename T, int VEC>
+__global__ void __launch_bounds__(PW_THREADS) layerscale_bwd_kernel(const T* __restrict__ dU, const T* __restrict__ Y,
+                                                                    const float* __restrict__ gamma, int K, int C,
+                                                                    int rows_per_block, T* __restrict__ dY,
+                                                                    float* __restrict__ partial) {
+  const int g = blockIdx.y * blockDim.x + threadIdx.x;           // channel group
+  const int c0 = g * VEC;
+  if (c0 >= C) return;
+  const int r0 = blockIdx.x * rows_per_block, r1 = min(K, r0 + rows_per_block);
+  float gam[VEC], acc[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) { gam[e] = gamma[c0 + e]; acc[e] = 0.f; }
+  for (int r = r0; r < r1; r += 4) {
+    float u[4][VEC], y[4][VEC];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const long long o = (long long)min(r + q, r1 - 1) * C + c0;
+      if (VEC == 8) { Vec8<T>::load(dU + o, reinterpret_cast<float(&)[8]>(u[q])); Vec8<T>::load(Y + o, reinterpret_cast<float(&)[8]>(y[q])); }
+      else { u[q][0] = Vec8<T>::load1(dU + o); y[q][0] = Vec8<T>::load1(Y + o); }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (r + q >= r1) break;
+      float o8[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { acc[e] = fmaf(u[q][e], y[q][e], acc[e]); o8[e] = u[q][e] * gam[e]; }
+      if (dY) {
+        const long long o = (long long)(r + q) * C + c0;
+        if (VEC == 8) Vec8<T>::store(dY + o, reinterpret_cast<float(&)[8]>(o8));
+        else Vec8<T>::store1(dY + o, o8[0]);
+      }
+    }
+  }
+  if (partial) {
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) partial[(long long)blockIdx.x * C + c0 + e] = acc[e];
+  }
+}
+
+__global__ void __launch_bounds__(PW_THREADS) cols_reduce_kernel(const float* __restrict__ partial, int nblocks, int C,
+                                                                 float* __restrict__ out, int accumulate) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  const int c = t >> 3, q = t & 7;                                // eight lanes per channel
+  float a = 0.f;
+  if (c < C)
+    for (int b = q; b < nblocks; b += 8) a += partial[(long long)b * C + c];
+  a += __shfl_xor(a, 1); a += __shfl_xor(a, 2); a += __shfl_xor(a, 4);
+  if (c < C && q == 0) out[c] = accumulate ? out[c] + a : a;
+}
+
+int ls_blocks(int64_t K) { return (int)std::max<int64_t>(1, std::min<int64_t>(kLsMaxBlocks, ceil_div(K, 16))); }
+
+int32_t launch_backward_layerscale(const void* dU, const void* Y, const float* gamma, int64_t K, int32_t C, int32_t dtype,
+                                   float* dgamma, void* dY, float* partial, uint32_t flags, hipStream_t s) {
+  const int accumulate = (flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
+  if (K == 0) {
+    if (dgamma)   // no partials: writes zeros (or leaves dgamma as it is when accumulating)
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, cols_reduce_kernel, dim3((unsigned)ceil_div(8 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+                 partial, 0, C, dgamma, accumulate);
+    return check_launch("backward_layerscale (K = 0)");
+  }
+  const int nblocks = ls_blocks(K), rpb = (int)ceil_div(K, nblocks);
+  const int eb = dtype == SBP_F32 ? 4 : 2;
+  const bool vec = C % 8 == 0 && (uintptr_t)dU % 16 == 0 && (uintptr_t)Y % 16 == 0 && (uintptr_t)dY % 16 == 0 && ((size_t)C * eb) % 16 == 0;
+  const int groups = vec ? C / 8 : C;
+  const int ct = (int)std::min<int64_t>(PW_THREADS, ceil_div(groups, 64) * 64);
+  const dim3 grid((unsigned)nblocks, (unsigned)ceil_div(groups, ct));
+  float* part = dgamma ? partial : nullptr;
+#define SBP_LS(T, V) SBP_LAUNCH(SBP_PROF_OTHER, s, (layerscale_bwd_kernel<T, V>), grid, dim3(ct), 0, s, (const T*)dU, (const T*)Y, gamma, \
+                                (int)K, C, rpb, (T*)dY, part)
+  if (dtype == SBP_F32) { if (vec) SBP_LS(float, 8); else SBP_LS(float, 1); }
+  else { if (vec) SBP_LS(uint16_t, 8); else SBP_LS(uint16_t, 1); }
+#undef SBP_LS
+  if (dgamma)
+    SBP_LAUNCH(SBP_PROF_REDUCE, s, cols_reduce_kernel, dim3((unsigned)ceil_div(8 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+               partial, nblocks, C, dgamma, accumulate);
+  return check_launch("backward_layerscale");
+}
+
 }  // namespace sbp

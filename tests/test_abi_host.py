@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 22
+    assert len(names) == 24
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -238,6 +238,22 @@ def test_backward_attention_argument_errors_and_engine():
     assert L.sbp_backward_attention_engine(128, 128, 1) == 1 and L.sbp_backward_attention_engine(129, 128, 1) == 0
     assert L.sbp_backward_attention_engine(99, 64, 0) == 0 and L.sbp_backward_attention_engine(99, 16, 1) == 0
     assert L.sbp_backward_attention_engine(99, 48, 1) == -1
+
+
+def test_backward_layerscale_argument_errors():
+    L = _lib.lib()
+    p = ctypes.c_void_p(256)
+    need = L.sbp_backward_layerscale_workspace(100, 64)
+    assert need >= 7 * 64 * 4 and need % 256 == 0 and L.sbp_backward_layerscale_workspace(-1, 64) == 0
+
+    def call(K=100, C=64, dtype=1, dU=p, Y=p, gamma=p, dg=p, dY=p, ws=p, wb=need, flags=0):
+        return L.sbp_backward_layerscale(dU, Y, gamma, K, C, dtype, dg, dY, ws, wb, flags, None)
+
+    assert call(dtype=9) == -4 and call(K=-1) == -2 and call(C=0) == -2
+    assert call(flags=2) == -8
+    assert call(dU=None) == -1 and call(gamma=None) == -1
+    assert call(ws=None) == -6 and call(wb=need - 1) == -6 and call(ws=ctypes.c_void_p(260)) == -6
+    assert call(dg=None, dY=None) == 0                                      # nothing asked for
 
 
 def test_backward_dwconv_argument_errors():

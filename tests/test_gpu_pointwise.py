@@ -185,3 +185,36 @@ def test_mlp_branch_backward_on_compact_rows(geom):
     dZ_scat = torch.zeros((M, Hd), dtype=torch.bfloat16, device="cuda"); dZ_scat[idxd.long()] = dZ_s
     dW1s, db1s, dU_full = sbp.backward_linear(dZ_scat, idxd, Uk, W1.cuda(), M=M, inv=inv)
     assert torch.equal(dW1s, dW1) and torch.equal(db1s, db1) and torch.equal(dU_full[idxd.long()], dUk)
+
+
+# ------------------------------------------------------------------ layer scale
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(8400, 512), (6336, 768), (33, 24), (17, 7), (1, 1), (5000, 8)])
+def test_backward_layerscale_matches_oracle(shape, dtype):
+    K, C = shape
+    dU = si.normal((K, C), 1.0, 31, dtype)
+    Y = si.normal((K, C), 1.0, 32, dtype)
+    gamma = (si.normal((C,), 0.1, 33, "f32") + 0.5).float()
+    dg, dY = sbp.backward_layerscale(dU.cuda(), Y.cuda(), gamma.cuda())
+    torch.cuda.synchronize()
+    rY, rg = oracle.backward_layerscale(si.to_f64(dU), si.to_f64(Y), si.to_f64(gamma))
+    assert nerr(f64(dY), rY) <= _tol(dtype)
+    assert nerr(f64(dg), rg) <= TOL_F32
+
+
+def test_backward_layerscale_in_place_accumulate_empty_and_exact():
+    K, C = 300, 64
+    dU = si.small_ints((K, C), -3, 3, 41, "bf16").cuda()
+    Y = si.small_ints((K, C), -3, 3, 42, "bf16").cuda()
+    gamma = torch.full((C,), 2.0, device="cuda")
+    ref_Y, ref_g = oracle.backward_layerscale(si.to_f64(dU), si.to_f64(Y), si.to_f64(gamma))
+    buf = dU.clone()
+    dg = torch.ones(C, device="cuda")
+    out_g, out_Y = sbp.backward_layerscale(buf, Y, gamma, flags=sbp.FLAG_ACCUMULATE_DW, dgamma=dg, dY=buf)   # in place, dgamma +=
+    torch.cuda.synchronize()
+    assert out_Y.data_ptr() == buf.data_ptr()
+    assert np.array_equal(f64(out_Y), ref_Y) and np.array_equal(f64(out_g), ref_g + 1.0)      # small integers: exact
+    e = torch.empty((0, C), dtype=torch.bfloat16, device="cuda")
+    g0, y0 = sbp.backward_layerscale(e, e, gamma)
+    torch.cuda.synchronize()
+    assert y0.shape == (0, C) and np.all(f64(g0) == 0)
