@@ -326,7 +326,10 @@ def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5):
             ("act_backward_rows", lambda b: sbp.act_backward_rows(b["dHk"], b["Zk"], out=b["dHk"]), 3 * K * Hd * 2),
             ("backward_layernorm", lambda b: sbp.backward_layernorm(b["dUk"], b["Xk"], b["gamma"], 1e-6, idx, M, inv=inv,
                                                                     dgamma=b["dg"], dbeta=b["dbt"], dX=b["dX"], workspace=ws),
-             (2 * K * C + M * C) * 2 + 3 * C * 4 + 8 * K)):
+             (2 * K * C + M * C) * 2 + 3 * C * 4 + 8 * K),
+            ("backward_layerscale", lambda b: sbp.backward_layerscale(b["dUk"], b["Xk"], b["gamma"], dgamma=b["dg"], dY=b["dUk"],
+                                                                      workspace=ws),
+             3 * K * C * 2 + 2 * C * 4)):
         ms = timed(fn, 50)
         kern[name] = {"us": round(ms * 1e3, 2), "algorithmic_mb": round(nbytes / 1e6, 2),
                       "gbs": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / 8000.0, 4)}

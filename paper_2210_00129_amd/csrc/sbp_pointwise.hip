@@ -457,7 +457,13 @@ __global__ void __launch_bounds__(PW_THREADS) cols_reduce_kernel(const float* __
   const int c = t >> 3, q = t & 7;                                // eight lanes per channel
   float a = 0.f;
   if (c < C)
-    for (int b = q; b < nblocks; b += 8) a += partial[(long long)b * C + c];
+    for (int b0 = q; b0 < nblocks; b0 += 64) {        // eight loads in flight, added in block order
+      float p[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) p[u] = b0 + 8 * u < nblocks ? partial[(long long)(b0 + 8 * u) * C + c] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) a += p[u];
+    }
   a += __shfl_xor(a, 1); a += __shfl_xor(a, 2); a += __shfl_xor(a, 4);
   if (c < C && q == 0) out[c] = accumulate ? out[c] + a : a;
 }
