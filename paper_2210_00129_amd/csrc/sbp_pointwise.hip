@@ -296,12 +296,12 @@ __global__ void __launch_bounds__(PW_THREADS) ln_reduce_kernel(const float* __re
   const int which = live ? o / C : 0, c = live ? o - which * C : 0;
   float a = 0.f;
   if (live) {
-    for (int b0 = q; b0 < nblocks; b0 += 32) {
-      float p[4];
+    for (int b0 = q; b0 < nblocks; b0 += 128) {       // sixteen loads in flight, added in block order
+      float p[16];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) p[u] = b0 + 8 * u < nblocks ? partial[((long long)(b0 + 8 * u) * 2 + which) * C + c] : 0.f;
+      for (int u = 0; u < 16; ++u) p[u] = b0 + 8 * u < nblocks ? partial[((long long)(b0 + 8 * u) * 2 + which) * C + c] : 0.f;
 #pragma unroll
-      for (int u = 0; u < 4; ++u) a += p[u];
+      for (int u = 0; u < 16; ++u) a += p[u];
     }
   }
   float tot = 0.f;
@@ -457,12 +457,12 @@ __global__ void __launch_bounds__(PW_THREADS) cols_reduce_kernel(const float* __
   const int c = t >> 3, q = t & 7;                                // eight lanes per channel
   float a = 0.f;
   if (c < C)
-    for (int b0 = q; b0 < nblocks; b0 += 64) {        // eight loads in flight, added in block order
-      float p[8];
+    for (int b0 = q; b0 < nblocks; b0 += 128) {       // sixteen loads in flight, added in block order
+      float p[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) p[u] = b0 + 8 * u < nblocks ? partial[(long long)(b0 + 8 * u) * C + c] : 0.f;
+      for (int u = 0; u < 16; ++u) p[u] = b0 + 8 * u < nblocks ? partial[(long long)(b0 + 8 * u) * C + c] : 0.f;
 #pragma unroll
-      for (int u = 0; u < 8; ++u) a += p[u];
+      for (int u = 0; u < 16; ++u) a += p[u];
     }
   a += __shfl_xor(a, 1); a += __shfl_xor(a, 2); a += __shfl_xor(a, 4);
   if (c < C && q == 0) out[c] = accumulate ? out[c] + a : a;
