@@ -623,11 +623,16 @@ static int32_t launch_plain(const LinearPlan& p, const T* dY, const int32_t* idx
   return SBP_OK;
 }
 
+// Dynamic LDS beyond 64 KB has to be granted per kernel; asked for once per kernel and size (one device per process).
 template <typename KernelT>
 static void allow_big_lds(KernelT kernel, size_t lds) {
-  if (lds > 64 * 1024)
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds);
+  static size_t granted = 0;                    // one instance per kernel type
+  static KernelT granted_for = nullptr;
+  if (lds <= 64 * 1024 || (granted_for == kernel && lds <= granted)) return;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess) {
+    granted = lds;
+    granted_for = kernel;
+  }
 }
 
 template <int BM, int BN, int NW, int KB, int NSTAGE>
