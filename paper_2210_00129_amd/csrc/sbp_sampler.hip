@@ -6,6 +6,8 @@
 // SplitMix64-style counter hash of (seed, stream_id, sample, cell).  Integer arithmetic
 // only; the position of every cell's output in idx is a closed form, so no scan is needed.
 #include <algorithm>
+#include <cmath>
+#include <cstdlib>
 
 #include "sbp_internal.h"
 
@@ -120,16 +122,23 @@ struct VariantGeom {
   int n_keep;         // random mask: kept grid positions per sample; temporal: kept frames per sample
   int tail_keep;      // temporal: kept frames of the partial last cell
   uint64_t base;
+  uint64_t win_lo, win_hi;   // random mask on large maps: the n_keep-th smallest key is expected in [win_lo, win_hi)
 };
 
 // Random mask: one block per sample.  The n_keep-th smallest key is found by a radix select over the 64-bit
 // keys, 8 bits per pass from the top, the keys being recomputed from the hash in every pass (nothing is
 // stored); a last pass writes the kept positions in ascending order with a block-wide running count.
 // Equal keys (never seen in practice, but possible) are broken by position, smallest first.
-template <int NT>
+// WINDOW (large maps): the keys are uniform, so that key lies near n_keep / n * 2^64.  One pass over the positions
+// counts the keys below a window around that value and collects the keys inside it in LDS; if the wanted rank
+// falls into the window (it does unless the hash misbehaves by many standard deviations) the radix select runs
+// over those few keys instead of recomputing all hashes eight times; otherwise the full select runs as before.
+template <int NT, bool WINDOW>
 __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_t* __restrict__ idx,
                                                            int32_t* __restrict__ inv) {
-  constexpr int NWAVE = NT / 64;
+  constexpr int NWAVE = NT / 64, CAP = WINDOW ? 4096 : 1;
+  __shared__ uint64_t cand[CAP];
+  __shared__ int s_ncand, s_below;
   __shared__ int hist[256];
   __shared__ uint64_t s_prefix;
   __shared__ int s_remaining;
@@ -143,15 +152,46 @@ __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_
     idx[out0 + p] = row0 + p;
     if (inv) inv[row0 + p] = out0 + p;
   }
-  if (t == 0) { s_prefix = 0; s_remaining = g.n_keep; }
+  bool windowed = false;                             // uniform over the block
+  int ncand = 0, want = g.n_keep;
+  if (WINDOW) {
+    if (t == 0) { s_ncand = 0; s_below = 0; }
+    __syncthreads();
+    int below = 0;
+    for (int p = t; p < n; p += NT) {
+      const uint64_t key = absorb(hb, (uint64_t)p);
+      if (key < g.win_lo) {
+        ++below;
+      } else if (key < g.win_hi) {
+        const int slot = atomicAdd(&s_ncand, 1);
+        if (slot < CAP) cand[slot] = key;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) below += __shfl_xor(below, o, 64);
+    if (lane == 0) atomicAdd(&s_below, below);
+    __syncthreads();
+    ncand = s_ncand;
+    const int rank = g.n_keep - s_below;             // 1-based rank of the wanted key among the collected ones
+    windowed = ncand <= CAP && rank >= 1 && rank <= ncand;
+    if (windowed) want = rank;
+  }
+  if (t == 0) { s_prefix = 0; s_remaining = want; }
   for (int pass = 0; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
     if (t < 256) hist[t] = 0;
     __syncthreads();
     const uint64_t prefix = s_prefix;
-    for (int p = t; p < n; p += NT) {
-      const uint64_t key = absorb(hb, (uint64_t)p);
-      if (pass == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
+    if (windowed) {
+      for (int i = t; i < ncand; i += NT) {
+        const uint64_t key = cand[i];
+        if (pass == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
+      }
+    } else {
+      for (int p = t; p < n; p += NT) {
+        const uint64_t key = absorb(hb, (uint64_t)p);
+        if (pass == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8))) atomicAdd(&hist[(int)((key >> shift) & 255u)], 1);
+      }
     }
     __syncthreads();
     // bucket in which the running count reaches what is still wanted: inclusive scan of the 256 counts
@@ -391,8 +431,20 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
     v.base = absorb(absorb(0, d.seed), d.stream_id);
     if (d.mode == SBP_RANDOM_MASK) {
       v.n_keep = random_keep(d); v.tail_keep = 0;
-      if (d.H * d.W > 2048) SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_random_kernel<1024>, dim3(d.B), dim3(1024), 0, s, v, idx, inv);
-      else SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_random_kernel<256>, dim3(d.B), dim3(256), 0, s, v, idx, inv);
+      v.win_lo = v.win_hi = 0;
+      if (d.H * d.W > 2048) {
+        // window of +-(6 standard deviations + 16) ranks around the expected key n_keep / n * 2^64
+        const double n = (double)d.H * d.W, q = v.n_keep / n;
+        const double half = (6.0 * std::sqrt(n * q * (1.0 - q)) + 16.0) / n;
+        const double two64 = 18446744073709551616.0;
+        const double lo = std::max(0.0, q - half), hi = q + half;
+        v.win_lo = (uint64_t)(lo * two64);
+        v.win_hi = hi >= 1.0 ? ~0ull : (uint64_t)(hi * two64);
+        if (std::getenv("SBP_SAMPLER_NO_WINDOW")) v.win_lo = v.win_hi = 0;   // debugging aid: an empty window, i.e. the full select
+        SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<1024, true>), dim3(d.B), dim3(1024), 0, s, v, idx, inv);
+      } else {
+        SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<256, false>), dim3(d.B), dim3(256), 0, s, v, idx, inv);
+      }
       return check_launch("sample_random_kernel");
     }
     v.n_keep = temporal_keep_frames(d);
