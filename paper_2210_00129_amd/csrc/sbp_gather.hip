@@ -8,29 +8,31 @@
 
 namespace sbp {
 
-// rows whose byte length is a multiple of 16: 16-byte pieces, UNROLL in flight per thread
+// rows whose byte length is a multiple of 16: 16-byte pieces, UNROLL in flight per thread.  Piece numbers fit 32 bits
+// (the host cuts larger inputs into several launches), so row and column come from a multiply and a shift.
 template <int UNROLL>
 __global__ void __launch_bounds__(256) gather_rows_vec16(const uint4* __restrict__ X, const int32_t* __restrict__ idx,
-                                                         long long K, int pieces_per_row, uint4* __restrict__ Xk) {
-  const long long total = K * pieces_per_row;
-  const long long stride = (long long)gridDim.x * blockDim.x;
-  long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x;
-  for (; t + (UNROLL - 1) * stride < total; t += UNROLL * stride) {
+                                                         uint32_t total, FastDiv pieces_per_row, uint4* __restrict__ Xk) {
+  const uint32_t stride = gridDim.x * 256u;
+  uint32_t t = blockIdx.x * 256u + threadIdx.x;
+  const uint32_t ppr = pieces_per_row.d;
+  for (; t < total && total - t > (UNROLL - 1) * stride; t += UNROLL * stride) {
     uint4 v[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-      long long e = t + u * stride;
-      long long j = e / pieces_per_row;
-      int c = (int)(e - j * pieces_per_row);
-      v[u] = X[(long long)idx[j] * pieces_per_row + c];
+      uint32_t j, c;
+      pieces_per_row.divmod(t + u * stride, j, c);
+      v[u] = X[(long long)idx[j] * ppr + c];
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) Xk[t + u * stride] = v[u];
+    if (UNROLL * stride > ~t) return;                       // the next step would wrap
   }
   for (; t < total; t += stride) {
-    long long j = t / pieces_per_row;
-    int c = (int)(t - j * pieces_per_row);
-    Xk[t] = X[(long long)idx[j] * pieces_per_row + c];
+    uint32_t j, c;
+    pieces_per_row.divmod(t, j, c);
+    Xk[t] = X[(long long)idx[j] * ppr + c];
+    if (stride > ~t) return;
   }
 }
 
@@ -53,13 +55,17 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
   const bool vec = row_bytes % 16 == 0 && ((uintptr_t)X % 16 == 0) && ((uintptr_t)Xk % 16 == 0);
   if (vec) {
     const int ppr = (int)(row_bytes / 16);
-    const long long total = K * ppr;
     constexpr int U = 4;
-    long long blocks = ceil_div(total, 256LL * U);
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    if (blocks < 1) blocks = 1;
-    SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_vec16<U>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)X, idx,
-                       (long long)K, ppr, (uint4*)Xk);
+    const int64_t rows_per_launch = std::max<int64_t>(1, 0xFFFFFFFFll / ppr);   // piece numbers of a launch fit 32 bits
+    for (int64_t j0 = 0; j0 < K; j0 += rows_per_launch) {
+      const int64_t rows = std::min(rows_per_launch, K - j0);
+      const uint32_t total = (uint32_t)(rows * ppr);
+      long long blocks = ceil_div(total, 256LL * U);
+      if (blocks > 256 * 16) blocks = 256 * 16;
+      if (blocks < 1) blocks = 1;
+      SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_vec16<U>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)X, idx + j0,
+                 total, FastDiv((uint32_t)ppr), (uint4*)Xk + j0 * ppr);
+    }
   } else {
     const long long total = K * C;
     long long blocks = ceil_div(total, 256);

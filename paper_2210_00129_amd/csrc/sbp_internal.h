@@ -7,6 +7,7 @@
 #include <stddef.h>
 
 #include "sbp.h"
+#include "sbp_fastdiv.h"
 
 namespace sbp {
 

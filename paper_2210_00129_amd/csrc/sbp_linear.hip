@@ -45,8 +45,10 @@ static constexpr int kMaxRowsPerSplit = 2048;   // kept rows per dW split (their
 //   [db]    column sums of the kept rows of dY, one block per (row slice, 256 channels)
 //   [dX]    BM x BN tiles of dX = dY_k W, scattered to the kept rows
 //   [dW]    BM x BN tiles of the per-split partial sums of dW = dY_k^T X_k
-// The helper segments come first (short, they share the CUs with the tiles); zero + db is padded to a
-// multiple of 8 and each tile segment is a multiple of 8, so the XCD chunking of a segment is exact.
+// The host orders the segments [zero + db], [dX], [dW] by the expected length of their workgroups, longest
+// first (seg_order): the CUs take workgroups in grid order, and a long kind dispatched last would run on alone
+// when everything else is done.  zero + db is padded to a multiple of 8 and each tile segment is a multiple of
+// 8, so the XCD chunking of a segment is exact wherever it starts.
 struct LinArgs {
   const uint16_t* dY;
   const int32_t* idx_in;    // rows of dY (NULL: dY is compact)
@@ -61,7 +63,8 @@ struct LinArgs {
   int K, M, Cin, Cout, rows_per_split, db_slice_rows;
   int n_zero, n_helper, n_dx, n_dw;   // n_helper = zero + db blocks rounded up to a multiple of 8
   int n_big, rows_small, n_dw_big;     // large-tile kernel: long and short dW splits; n_dw_big of the n_dw units are long
-  int seg_order[3];                   // large-tile kernel: dispatch order of 0 = dX tiles, 1 = long dW, 2 = short dW units
+  int seg_order[3];                   // dispatch order: large-tile kernel 0 = dX tiles, 1 = long dW, 2 = short dW units;
+                                      // general kernel 0 = dX tiles, 1 = dW units, 2 = zero-fill and column-sum blocks
   int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
 };
 
@@ -95,7 +98,15 @@ template <int BM, int BN, int NW, int KB, int NSTAGE>
 __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_kernel(const LinArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int wg = blockIdx.x;
-  if (wg < a.n_helper) {
+  int kind = 0;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    kind = a.seg_order[q];
+    const int n = kind == 0 ? a.n_dx : (kind == 1 ? a.n_dw : a.n_helper);
+    if (wg < n) break;
+    wg -= n;
+  }
+  if (kind == 2) {
     if (wg < a.n_zero) {
       zero_rows_block(a, wg);
     } else {
@@ -109,9 +120,8 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
     }
     return;
   }
-  wg -= a.n_helper;
   const int tiles_n = (a.Cin + BN - 1) / BN;
-  if (wg < a.n_dx) {
+  if (kind == 0) {
     const int ntiles = ((a.K + BM - 1) / BM) * tiles_n;
     const int L = xcd_chunked_id(wg, ntiles);
     if (L >= ntiles) return;
@@ -119,7 +129,6 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
     dx_tile<BM, BN, NW, KB, NSTAGE>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * BM, tile_n * BN);
     return;
   }
-  wg -= a.n_dx;
   const int tiles_m = (a.Cout + BM - 1) / BM;
   const int nsplit = (a.K + a.rows_per_split - 1) / a.rows_per_split;
   const int ntiles = tiles_m * tiles_n * nsplit;
@@ -649,6 +658,20 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, BM) * tiles_n * p.splits, 8)) : 0;
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
   if (grid == 0) return;
+  // Longest kind first.  Lengths in nanoseconds, read from the device clock on the detection and ViT-Tiny shapes: a
+  // tile costs about 3 us plus 1 us per stage of 64 (two stages in flight do not hide the memory latency), a
+  // streaming block 1.8 us plus its bytes at what one CU gets while the others stream too.
+  const int64_t len[3] = {
+      3000 + 1000 * ceil_div(a.Cout, 64), 3000 + 1000 * ceil_div(p.rows_per_split, 64),
+      1800 + std::max<int64_t>(a.n_zero ? (int64_t)(a.M - a.K) * a.Cin * 2 / a.n_zero : 0, n_db ? (int64_t)a.db_slice_rows * 512 : 0) / 40};
+  for (int q = 0; q < 3; ++q) a.seg_order[q] = q;
+  std::sort(a.seg_order, a.seg_order + 3, [&](int x, int y) { return len[x] != len[y] ? len[x] > len[y] : x < y; });
+  if (const char* o = std::getenv("SBP_ORDER")) {   // debugging aid: the order by hand
+    int v[3];
+    if (std::sscanf(o, "%d,%d,%d", &v[0], &v[1], &v[2]) == 3 && (unsigned)v[0] < 3 && (unsigned)v[1] < 3 && (unsigned)v[2] < 3 &&
+        (1 << v[0] | 1 << v[1] | 1 << v[2]) == 7)
+      for (int q = 0; q < 3; ++q) a.seg_order[q] = v[q];
+  }
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 

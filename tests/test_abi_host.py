@@ -288,3 +288,15 @@ def test_binding_refuses_cpu_tensors():
     idx = torch.zeros(2, dtype=torch.int32)
     with pytest.raises(ValueError):
         sbp.forward_cache(X, idx)
+
+
+def test_fast_division_of_the_streaming_kernels_is_exact(tmp_path):
+    # the kernels turn flat element numbers into (row, column) with a multiply and a shift; the same header compiled
+    # for the host must agree with the compiler's division on edge values and a pseudo-random sample
+    import subprocess
+    here = os.path.dirname(os.path.abspath(__file__))
+    exe = str(tmp_path / "fastdiv_check")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-I", os.path.join(here, "..", "paper_2210_00129_amd", "csrc"),
+                    os.path.join(here, "fastdiv_check.cpp"), "-o", exe], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("ok "), out
