@@ -197,6 +197,16 @@ def test_linear_large_tile_engine_short_contractions(K):
         check_linear(X, W, dY, idx, "bf16")
 
 
+@pytest.mark.parametrize("order", ["0,1,2", "0,2,1", "1,0,2", "1,2,0", "2,0,1", "2,1,0"])
+def test_linear_general_engine_every_segment_order(order):
+    # the 128-tile engine lays its three kinds of workgroups (dX tiles, dW units, zero-fill / column-sum blocks) in
+    # the grid longest first; every order gives the same gradients (ragged tiles, several splits, scatter with zero fill)
+    X, W, dY, idx = _grid_case(6, 1, 14, 14, 200, 136, 2, "bf16", 41)
+    with _env(SBP_TILE="128x128x4x64", SBP_ORDER=order):
+        check_linear(X, W, dY, idx, "bf16")
+        check_linear(X, W, dY, idx, "bf16", flags=sbp.FLAG_DX_COMPACT)
+
+
 def test_linear_engines_agree_bit_for_bit_on_integers():
     # exact arithmetic: whichever engine, tile height or split count runs, the results are the same bits
     B, P, H, W_, Cin, Cout = 8, 1, 14, 14, 320, 288
