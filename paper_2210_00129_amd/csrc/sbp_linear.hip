@@ -210,7 +210,11 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
 }
 
-// dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.
+// dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.  G lanes share an output: lane g
+// adds a contiguous run of the splits (four loads in flight) and the G sums are added in lane order, so the order
+// depends on G and the split count only.  G > 1 is for small weight matrices cut into many splits, where one thread
+// per output would leave most CUs idle behind a long chain of dependent loads.
+template <int G>
 __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __restrict__ partial, int nsplit_w,
                                                                   long long nW, float* __restrict__ dW,
                                                                   const float* __restrict__ dbp, int nsplit_b, int Cout,
@@ -218,31 +222,49 @@ __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __
   const long long nW4 = dW ? nW / 4 : 0;
   const long long nB = db ? Cout : 0;
   const long long total = nW4 + nB;
-  for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
-       e += (long long)gridDim.x * blockDim.x) {
+  const int g = threadIdx.x & (G - 1), lane = threadIdx.x & 63;
+  for (long long e = (blockIdx.x * (long long)blockDim.x + threadIdx.x) / G; e < total;
+       e += (long long)gridDim.x * blockDim.x / G) {
     if (e < nW4) {
-      float4 a = accumulate ? reinterpret_cast<const float4*>(dW)[e] : make_float4(0, 0, 0, 0);
-      for (int s0 = 0; s0 < nsplit_w; s0 += 4) {   // four loads in flight, added in split order
+      const int chunk = (nsplit_w + G - 1) / G, s_begin = g * chunk, s_end = min(nsplit_w, s_begin + chunk);
+      float4 a = make_float4(0, 0, 0, 0);
+      for (int s0 = s_begin; s0 < s_end; s0 += 4) {
         float4 p[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-          p[u] = s0 + u < nsplit_w ? reinterpret_cast<const float4*>(partial + (long long)(s0 + u) * nW)[e]
-                                   : make_float4(0, 0, 0, 0);
+          p[u] = s0 + u < s_end ? reinterpret_cast<const float4*>(partial + (long long)(s0 + u) * nW)[e]
+                                : make_float4(0, 0, 0, 0);
 #pragma unroll
         for (int u = 0; u < 4; ++u) { a.x += p[u].x; a.y += p[u].y; a.z += p[u].z; a.w += p[u].w; }
       }
-      reinterpret_cast<float4*>(dW)[e] = a;
+      float4 t = a;
+#pragma unroll
+      for (int k = 1; k < G; ++k) {
+        const int src = (lane & ~(G - 1)) + k;
+        t.x += __shfl(a.x, src); t.y += __shfl(a.y, src); t.z += __shfl(a.z, src); t.w += __shfl(a.w, src);
+      }
+      if (g == 0) {
+        if (accumulate) {
+          const float4 old = reinterpret_cast<const float4*>(dW)[e];
+          t.x = old.x + t.x; t.y = old.y + t.y; t.z = old.z + t.z; t.w = old.w + t.w;
+        }
+        reinterpret_cast<float4*>(dW)[e] = t;
+      }
     } else {
       const long long o = e - nW4;
-      float a = accumulate ? db[o] : 0.f;
-      for (int s0 = 0; s0 < nsplit_b; s0 += 8) {
+      const int chunk = (nsplit_b + G - 1) / G, s_begin = g * chunk, s_end = min(nsplit_b, s_begin + chunk);
+      float a = 0.f;
+      for (int s0 = s_begin; s0 < s_end; s0 += 8) {
         float p[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = s0 + u < nsplit_b ? dbp[(long long)(s0 + u) * Cout + o] : 0.f;
+        for (int u = 0; u < 8; ++u) p[u] = s0 + u < s_end ? dbp[(long long)(s0 + u) * Cout + o] : 0.f;
 #pragma unroll
         for (int u = 0; u < 8; ++u) a += p[u];
       }
-      db[o] = a;
+      float t = a;
+#pragma unroll
+      for (int k = 1; k < G; ++k) t += __shfl(a, (lane & ~(G - 1)) + k);
+      if (g == 0) db[o] = accumulate ? db[o] + t : t;
     }
   }
 }
@@ -791,9 +813,13 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   if (dW || db) {
     if (nW % 4 == 0) {
       const long long total = (dW ? nW / 4 : 0) + (db ? Cout : 0);
-      unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
-      SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW, dbp,
-                         use_mfma ? p.db_slices : p.splits, Cout, db, accumulate);
+      const int nsplit_b = use_mfma ? p.db_slices : p.splits;
+      const int deepest = std::max(dW ? p.splits : 0, db ? nsplit_b : 0);
+      const int G = total <= 20000 && deepest >= 16 ? 8 : (total <= 40000 && deepest >= 8 ? 4 : 1);
+      unsigned blocks = (unsigned)std::min<long long>(ceil_div(total * G, NTHREADS), 4096);
+      auto kernel = G == 8 ? reduce_splits_kernel<8> : (G == 4 ? reduce_splits_kernel<4> : reduce_splits_kernel<1>);
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW, dbp, nsplit_b, Cout, db,
+                 accumulate);
     } else {
       const long long total = (dW ? nW : 0) + (db ? Cout : 0);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
