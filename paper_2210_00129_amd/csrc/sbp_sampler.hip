@@ -123,6 +123,7 @@ struct VariantGeom {
   int tail_keep;      // temporal: kept frames of the partial last cell
   uint64_t base;
   uint64_t win_lo, win_hi;   // random mask on large maps: the n_keep-th smallest key is expected in [win_lo, win_hi)
+  int mask_chunks;           // random mask on large maps: chunks of 64 positions whose keep bits fit the dynamic LDS (0: none)
 };
 
 // Random mask: one block per sample.  The n_keep-th smallest key is found by a radix select over the 64-bit
@@ -133,6 +134,9 @@ struct VariantGeom {
 // counts the keys below a window around that value and collects the keys inside it in LDS; if the wanted rank
 // falls into the window (it does unless the hash misbehaves by many standard deviations) the radix select runs
 // over those few keys instead of recomputing all hashes eight times; otherwise the full select runs as before.
+// The ordered write-out of a large map keeps one 64-bit "below" and one "equal" mask per chunk of 64 positions in
+// LDS (one hash pass, a ballot per chunk), scans the chunk counts once, and every wavefront then writes its chunks
+// without further barriers; where the masks do not fit (mask_chunks == 0) the chunked loop of the small maps runs.
 template <int NT, bool WINDOW>
 __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_t* __restrict__ idx,
                                                            int32_t* __restrict__ inv) {
@@ -217,6 +221,64 @@ __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_
   }
   const uint64_t thr = s_prefix;                    // the n_keep-th smallest key
   const int take_eq = s_remaining;                  // how many keys equal to it are kept (smallest positions first)
+  if (WINDOW && g.mask_chunks > 0) {
+    extern __shared__ __attribute__((aligned(16))) unsigned long long dyn[];
+    const int nchunks = g.mask_chunks;              // = ceil(n / 64)
+    unsigned long long* m_lt = dyn;
+    unsigned long long* m_eq = dyn + nchunks;
+    int* pre_lt = reinterpret_cast<int*>(dyn + 2 * nchunks);
+    int* pre_eq = pre_lt + nchunks;
+    __syncthreads();                                // s_prefix / s_remaining read by everyone
+    for (int c = wave; c < nchunks; c += NWAVE) {
+      const int p = 64 * c + lane;
+      bool lt = false, eq = false;
+      if (p < n) {
+        const uint64_t key = absorb(hb, (uint64_t)p);
+        lt = key < thr;
+        eq = key == thr;
+      }
+      const unsigned long long mlt = __ballot(lt), meq = __ballot(eq);
+      if (lane == 0) { m_lt[c] = mlt; m_eq[c] = meq; }
+    }
+    __syncthreads();
+    // exclusive scan of the chunk counts: a thread owns a contiguous run of chunks
+    const int per = (nchunks + NT - 1) / NT, c0 = min(nchunks, t * per), c1 = min(nchunks, c0 + per);
+    int sum_lt = 0, sum_eq = 0;
+    for (int c = c0; c < c1; ++c) { sum_lt += __popcll(m_lt[c]); sum_eq += __popcll(m_eq[c]); }
+    int inc_lt = sum_lt, inc_eq = sum_eq;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int a = __shfl_up(inc_lt, o, 64), e = __shfl_up(inc_eq, o, 64);
+      if (lane >= o) { inc_lt += a; inc_eq += e; }
+    }
+    if (lane == 63) { s_wave_lt[wave] = inc_lt; s_wave_eq[wave] = inc_eq; }
+    __syncthreads();
+    int run_lt = inc_lt - sum_lt, run_eq = inc_eq - sum_eq;
+    for (int w = 0; w < wave; ++w) { run_lt += s_wave_lt[w]; run_eq += s_wave_eq[w]; }
+    for (int c = c0; c < c1; ++c) {
+      pre_lt[c] = run_lt; pre_eq[c] = run_eq;
+      run_lt += __popcll(m_lt[c]); run_eq += __popcll(m_eq[c]);
+    }
+    __syncthreads();
+    const unsigned long long lower = (1ull << lane) - 1ull;
+    for (int c = wave; c < nchunks; c += NWAVE) {
+      const int p = 64 * c + lane;
+      if (p >= n) continue;
+      const unsigned long long mlt = m_lt[c], meq = m_eq[c];
+      const bool lt = (mlt >> lane) & 1ull, eq = (meq >> lane) & 1ull;
+      const int lt_before = pre_lt[c] + __popcll(mlt & lower), eq_before = pre_eq[c] + __popcll(meq & lower);
+      const bool keep = lt || (eq && eq_before < take_eq);
+      const int row = row0 + g.P + p;
+      if (keep) {
+        const int pos = out0 + g.P + lt_before + min(eq_before, take_eq);
+        idx[pos] = row;
+        if (inv) inv[row] = pos;
+      } else if (inv) {
+        inv[row] = -1;
+      }
+    }
+    return;
+  }
   if (t == 0) { s_run_lt = 0; s_run_eq = 0; }
   __syncthreads();
   for (int p0 = 0; p0 < n; p0 += NT) {
@@ -425,13 +487,13 @@ __global__ void __launch_bounds__(256) sample_kernel(SampleGeom g, int32_t* __re
 
 int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipStream_t s) {
   if (d.mode == SBP_RANDOM_MASK || d.mode == SBP_TEMPORAL) {
-    VariantGeom v;
+    VariantGeom v{};
     v.B = d.B; v.P = d.P; v.H = d.H; v.W = d.W; v.k = d.k; v.cell = d.cell; v.per_sample = d.per_sample;
     v.N = d.P + d.H * d.W;
     v.base = absorb(absorb(0, d.seed), d.stream_id);
     if (d.mode == SBP_RANDOM_MASK) {
       v.n_keep = random_keep(d); v.tail_keep = 0;
-      v.win_lo = v.win_hi = 0;
+      v.win_lo = v.win_hi = 0; v.mask_chunks = 0;
       if (d.H * d.W > 2048) {
         // window of +-(6 standard deviations + 16) ranks around the expected key n_keep / n * 2^64
         const double n = (double)d.H * d.W, q = v.n_keep / n;
@@ -441,7 +503,18 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
         v.win_lo = (uint64_t)(lo * two64);
         v.win_hi = hi >= 1.0 ? ~0ull : (uint64_t)(hi * two64);
         if (std::getenv("SBP_SAMPLER_NO_WINDOW")) v.win_lo = v.win_hi = 0;   // debugging aid: an empty window, i.e. the full select
-        SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<1024, true>), dim3(d.B), dim3(1024), 0, s, v, idx, inv);
+        // keep bits and chunk prefixes of the ordered write-out: 24 bytes per 64 positions, next to 34 KB of static LDS
+        const int64_t chunks = ceil_div((int64_t)d.H * d.W, 64);
+        size_t lds = (size_t)chunks * 24;
+        static bool big_lds_ok = false, big_lds_asked = false;
+        if (lds > 28 * 1024 && !big_lds_asked) {        // more than 64 KB in all: granted per kernel, asked for once
+          big_lds_asked = true;
+          big_lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_random_kernel<1024, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024) == hipSuccess;
+        }
+        v.mask_chunks = (int)chunks;
+        if (lds > 120 * 1024 || (lds > 28 * 1024 && !big_lds_ok) || std::getenv("SBP_SAMPLER_NO_MASKS")) { v.mask_chunks = 0; lds = 0; }
+        SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<1024, true>), dim3(d.B), dim3(1024), lds, s, v, idx, inv);
       } else {
         SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<256, false>), dim3(d.B), dim3(256), 0, s, v, idx, inv);
       }

@@ -58,15 +58,20 @@ def test_random_mask_sampler_bit_exact(geom, k):
     assert np.array_equal(one.cpu().numpy(), oracle.sample_indices_random(B, P, H, W, k, 11, 12, per_sample=False))
 
 
-@pytest.mark.parametrize("window", [True, False])
-def test_random_mask_sampler_large_maps_window_and_full_select(window):
+@pytest.mark.parametrize("window,masks", [(True, True), (False, True), (True, False)])
+def test_random_mask_sampler_large_maps_window_and_full_select(window, masks):
     # maps above 2048 positions: the select over a window of keys around the expected threshold, and (window switched
-    # off) the full select that stands behind it; several seeds, all keep ratios, the detection-size map among them
+    # off) the full select that stands behind it; the ordered write-out from keep masks in LDS (also beyond 64 KB of
+    # LDS: the 300 x 400 map) and (masks switched off) the chunked loop that stands behind it; several seeds, all keep
+    # ratios, the detection-size map among them
     import os
     if not window:
         os.environ["SBP_SAMPLER_NO_WINDOW"] = "1"
+    if not masks:
+        os.environ["SBP_SAMPLER_NO_MASKS"] = "1"
     try:
-        for (B, P, H, W), seeds in (((2, 0, 200, 336), ((0, 1),)), ((3, 1, 50, 84), ((5, 6), (2**64 - 1, 7), (123, 2**40)))):
+        for (B, P, H, W), seeds in (((2, 0, 200, 336), ((0, 1),)), ((3, 1, 50, 84), ((5, 6), (2**64 - 1, 7), (123, 2**40))),
+                                    ((1, 2, 300, 400), ((3, 4),))):
             for k in (1, 2, 3, 4):
                 for seed, stream in seeds:
                     ref = oracle.sample_indices_random(B, P, H, W, k, seed, stream)
@@ -76,6 +81,7 @@ def test_random_mask_sampler_large_maps_window_and_full_select(window):
                     assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(ref, B * (P + H * W)))
     finally:
         os.environ.pop("SBP_SAMPLER_NO_WINDOW", None)
+        os.environ.pop("SBP_SAMPLER_NO_MASKS", None)
 
 
 @pytest.mark.parametrize("c,k", [(2, 1), (2, 2), (3, 2), (4, 1), (4, 3)])
