@@ -3,6 +3,7 @@
 // HBM: every thread moves 16-byte pieces, several in flight, rows laid out so that a
 // wavefront reads and writes whole contiguous row segments.
 #include <algorithm>
+#include <cstdlib>
 
 #include "sbp_internal.h"
 
@@ -132,11 +133,94 @@ __global__ void __launch_bounds__(256) scatter_patches_kernel(const U* __restric
   }
 }
 
+// The same two kernels with 32-bit unit numbers and multiply-shift divisions, for tensors of fewer than 2^32 units
+// (the plain versions above spend more time on their eight integer divisions per unit than on the memory accesses).
+struct PatchGeomFast {
+  FastDiv seg, W, H, p, per_row, Wo, HoWo;
+  int Ho_;
+};
+
+template <typename U>
+__global__ void __launch_bounds__(256) gather_patches_fast_kernel(const U* __restrict__ X, const int32_t* __restrict__ idx,
+                                                                  uint32_t total, PatchGeomFast g, U* __restrict__ Xk) {
+  const uint32_t stride = gridDim.x * 256u;
+  for (uint32_t t = blockIdx.x * 256u + threadIdx.x; t < total; t += stride) {
+    uint32_t j, rem, s, c, dy, dx, b, r, yo, xo;
+    g.per_row.divmod(t, j, rem);
+    g.seg.divmod(rem, s, c);
+    g.p.divmod(s, dy, dx);
+    g.HoWo.divmod((uint32_t)idx[j], b, r);
+    g.Wo.divmod(r, yo, xo);
+    const long long pix = ((long long)b * g.H.d + g.p.d * yo + dy) * g.W.d + g.p.d * xo + dx;
+    Xk[t] = X[pix * g.seg.d + c];
+    if (stride > ~t) return;
+  }
+}
+
+// Three dependent loads stand behind every unit (inverse map, keep list, patch row): UNROLL units per thread, each
+// kind of load issued for all of them before the next kind, keep enough of them in flight.
+template <typename U, int UNROLL>
+__global__ void __launch_bounds__(256) scatter_patches_fast_kernel(const U* __restrict__ dXp, const int32_t* __restrict__ idx,
+                                                                   const int32_t* __restrict__ inv, int K, uint32_t total,
+                                                                   PatchGeomFast g, U* __restrict__ dX) {
+  const uint32_t stride = gridDim.x * 256u;
+  U zero;
+  __builtin_memset(&zero, 0, sizeof(U));
+  for (uint32_t t0 = blockIdx.x * 256u + threadIdx.x; t0 < total; t0 += UNROLL * stride) {
+    int f[UNROLL], j[UNROLL];
+    uint32_t off[UNROLL];
+    bool live[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const uint32_t t = t0 + u * stride;
+      live[u] = t >= t0 && t < total;                     // t >= t0: no wrap-around
+      uint32_t pix, c, by, x, b, y, yo, yi, xo, xi;
+      g.seg.divmod(live[u] ? t : 0u, pix, c);
+      g.W.divmod(pix, by, x);
+      g.H.divmod(by, b, y);
+      g.p.divmod(y, yo, yi);
+      g.p.divmod(x, xo, xi);
+      f[u] = (int)((b * (uint32_t)g.Ho_ + yo) * g.Wo.d + xo);
+      off[u] = (yi * g.p.d + xi) * g.seg.d + c;
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) j[u] = inv[f[u]];
+    int back[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      back[u] = (unsigned)j[u] < (unsigned)K ? idx[j[u]] : -1;   // (no load where nothing is kept: idx may be empty)
+    }
+    U v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const bool kept = back[u] == f[u];
+      v[u] = kept ? dXp[(long long)j[u] * g.per_row.d + off[u]] : zero;
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u)
+      if (live[u]) dX[t0 + u * stride] = v[u];
+    if (UNROLL * stride > ~t0) return;
+  }
+}
+
 template <typename U>
 static void launch_patches_t(bool scatter, const void* src, const int32_t* idx, const int32_t* inv, int64_t K, long long npix,
                              PatchGeom g, void* dst, hipStream_t s) {
   const long long total = scatter ? npix * g.seg : K * (long long)g.p * g.p * g.seg;
   const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(total, 256), 256 * 32));
+  if (total < (1ll << 32) && !std::getenv("SBP_PATCH_WIDE")) {   // (debugging aid: the 64-bit kernels on any size)
+    PatchGeomFast f;
+    f.seg = FastDiv((uint32_t)g.seg); f.W = FastDiv((uint32_t)g.W); f.H = FastDiv((uint32_t)g.H); f.p = FastDiv((uint32_t)g.p);
+    f.per_row = FastDiv((uint32_t)(g.p * g.p * g.seg)); f.Wo = FastDiv((uint32_t)g.Wo); f.HoWo = FastDiv((uint32_t)(g.Ho * g.Wo));
+    f.Ho_ = g.Ho;
+    if (scatter)
+      SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (scatter_patches_fast_kernel<U, 4>), dim3(std::max(1u, blocks / 4)), dim3(256), 0, s, (const U*)src, idx, inv,
+                 (int)K, (uint32_t)total, f, (U*)dst);
+    else
+      SBP_LAUNCH(SBP_PROF_GATHER, s, (gather_patches_fast_kernel<U>), dim3(blocks), dim3(256), 0, s, (const U*)src, idx,
+                 (uint32_t)total, f, (U*)dst);
+    return;
+  }
   if (scatter)
     SBP_LAUNCH(SBP_PROF_ZERO_ROWS, s, (scatter_patches_kernel<U>), dim3(blocks), dim3(256), 0, s, (const U*)src, idx, inv, (int)K,
                npix, g, (U*)dst);
