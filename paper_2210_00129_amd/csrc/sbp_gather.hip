@@ -56,13 +56,13 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
   const bool vec = row_bytes % 16 == 0 && ((uintptr_t)X % 16 == 0) && ((uintptr_t)Xk % 16 == 0);
   if (vec) {
     const int ppr = (int)(row_bytes / 16);
-    constexpr int U = 4;
+    constexpr int U = 1;   // pieces per thread and pass: one, in many blocks (16 wavefronts per SIMD), ran ahead of 2 or 4 in flight
     const int64_t rows_per_launch = std::max<int64_t>(1, 0xFFFFFFFFll / ppr);   // piece numbers of a launch fit 32 bits
     for (int64_t j0 = 0; j0 < K; j0 += rows_per_launch) {
       const int64_t rows = std::min(rows_per_launch, K - j0);
       const uint32_t total = (uint32_t)(rows * ppr);
       long long blocks = ceil_div(total, 256LL * U);
-      if (blocks > 256 * 16) blocks = 256 * 16;
+      if (blocks > 256 * 64) blocks = 256 * 64;
       if (blocks < 1) blocks = 1;
       SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_vec16<U>, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)X, idx + j0,
                  total, FastDiv((uint32_t)ppr), (uint4*)Xk + j0 * ppr);
