@@ -130,7 +130,7 @@ template <typename T>
 static void launch_act_t(const T* dH, const T* Z, long long n, bool backward, T* out, hipStream_t s) {
   const bool vec = n % 8 == 0 && (uintptr_t)Z % 16 == 0 && (uintptr_t)out % 16 == 0 && (!backward || (uintptr_t)dH % 16 == 0);
   const long long work = vec ? n / 8 : n;
-  const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(work, 2 * PW_THREADS), 256 * 16));
+  const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(work, PW_THREADS), 256 * 64));
   if (vec) {
     if (backward) SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, true, true>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
     else SBP_LAUNCH(SBP_PROF_OTHER, s, (act_rows_kernel<T, false, true>), dim3(blocks), dim3(PW_THREADS), 0, s, dH, Z, n, out);
