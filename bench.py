@@ -243,6 +243,12 @@ def cpu_baseline(wl, r, seconds, si):
                       f"(fp64 numpy oracle incl. its python sampler), {dt:.1f} s"}
 
 
+def attainable_tflops(flops, algorithmic_bytes):
+    """Ceiling of a whole step by the two published peaks: the matrix cores, or the step's intensity (flop per
+    algorithmic byte, gathers and zero-filled rows included) times the HBM rate, whichever is lower."""
+    return min(PEAK_BF16_TFLOPS, flops / algorithmic_bytes * PEAK_HBM_GBS / 1e3)
+
+
 def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3):
     wl = si.WORKLOADS[name]
     job = Job(wl, torch, sbp, si)
@@ -251,8 +257,11 @@ def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3):
         job.set_ratio(rr)
         ms, _ = job.time_steps(steps, warmup)
         tag = f"r{rr:g}"
-        out[tag] = {"ms_per_step": round(ms, 4), "tflops": round(job.flops_per_step() / ms / 1e9, 2),
-                    "algorithmic_gbs": round(job.algorithmic_bytes_per_step() / ms / 1e6, 1)}
+        tf = job.flops_per_step() / ms / 1e9
+        ceiling = attainable_tflops(job.flops_per_step(), job.algorithmic_bytes_per_step())
+        out[tag] = {"ms_per_step": round(ms, 4), "tflops": round(tf, 2),
+                    "algorithmic_gbs": round(job.algorithmic_bytes_per_step() / ms / 1e6, 1),
+                    "attainable_tflops": round(ceiling, 1), "frac_of_attainable": round(tf / ceiling, 4)}
     out["speedup_vs_r1"] = round(out["r1"]["ms_per_step"] / out[f"r{r:g}"]["ms_per_step"], 3)
     del job
     torch.cuda.empty_cache()
@@ -518,6 +527,15 @@ def main():
                     if (wl.name == "vit_base" and args.ratio == 0.5 and engines == ["mfma_large"]) else None,
                     "avg_launch_us": round(avg_ms * 1e3, 2),
                     "flops_per_launch": fl}
+        # layers whose intensity lies under the ridge of the two peaks are priced against HBM instead
+        s_b = 2 if wl.dtype == "bf16" else 4
+        by = sum(s_b * (K_r * s.Cout + K_r * s.Cin + s.Cout * s.Cin + wl.M * s.Cin) + 4 * s.Cout * s.Cin + 4 * s.Cout + 4 * K_r
+                 for s in wl.linears) / len(wl.linears)
+        if fused and fl / by < PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS:
+            gbs = by / avg_ms / 1e6
+            roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                             "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": by,
+                             "mfma_tflops": round(achieved, 2)})
     breakdown = {c: {"ms_per_step": round(v[0] / max(2, min(args.steps, 5)), 4), "launches": v[1]}
                  for c, v in prof.items() if v[1]}
 
@@ -541,6 +559,8 @@ def main():
         "host_wall_ms_per_step": round(wall_ms, 4),
         "frac_of_bf16_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "algorithmic_gbs": round(bytes_step / ms / 1e6, 1),
+        "attainable_tflops": round(attainable_tflops(flops, bytes_step), 1),
+        "frac_of_attainable": round(value / attainable_tflops(flops, bytes_step), 4),
         "activation_memory_saving": round(1.0 - cached / full, 4),
         "kernel_breakdown": breakdown,
         "roofline": roofline,
