@@ -65,6 +65,7 @@ extern "C" {
 #define SBP_FLAG_DY_COMPACT     1u  /* dY is already compact: [K, Cout], row j belongs to idx[j] */
 #define SBP_FLAG_DX_COMPACT     2u  /* write dX compact: [K, Cin], no scatter, no zero rows */
 #define SBP_FLAG_ACCUMULATE_DW  4u  /* dW += and db += instead of overwrite */
+#define SBP_FLAG_DW_OUT_BF16    8u  /* sbp_backward_linear: dW is bf16 [Cout, Cin]: the fp32 sum rounded once */
 
 /*
  * One draw of a grid-wise keep-set (paper, "How to sample the gradient keep mask?": a
@@ -155,7 +156,10 @@ int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Co
  *                       is built in the workspace by one more small kernel.  Only used to zero-fill dX.
  *   X_k    device, in,  [K, Cin] rows cached by sbp_forward_cache (may be NULL if dW is NULL)
  *   W      device, in,  [Cout, Cin]                       (may be NULL if dX is NULL)
- *   dW, db, dX   device, out; each may be NULL to skip that output
+ *   dW, db, dX   device, out; each may be NULL to skip that output.  dW is fp32, or bf16 with
+ *                SBP_FLAG_DW_OUT_BF16 (the same fp32 sum, rounded to nearest even once; together with
+ *                SBP_FLAG_ACCUMULATE_DW the old bf16 values are added in fp32 and the sum rounded again);
+ *                db is fp32 either way
  *   workspace    device, 256-byte aligned, at least sbp_backward_linear_workspace(...) bytes;
  *                contents on entry are irrelevant, contents on exit are unspecified
  * Channel counts that are multiples of 8 take the MFMA path for SBP_BF16; any other shape
@@ -164,7 +168,7 @@ int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Co
 int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* inv, const void* X_k,
                             const void* W,
                             int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
-                            float* dW, float* db, void* dX,
+                            void* dW, float* db, void* dX,
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /* Host only.  Bytes of workspace sbp_backward_dwconv needs (0 on invalid sizes). */

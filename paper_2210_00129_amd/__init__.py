@@ -20,7 +20,7 @@ from ._lib import SampleDesc, SbpError  # noqa: F401
 
 F32, BF16 = 0, 1
 GRID_PER_CELL, GRID_SHARED, RANDOM_MASK, TEMPORAL = 0, 1, 2, 3
-FLAG_DY_COMPACT, FLAG_DX_COMPACT, FLAG_ACCUMULATE_DW = 1, 2, 4
+FLAG_DY_COMPACT, FLAG_DX_COMPACT, FLAG_ACCUMULATE_DW, FLAG_DW_OUT_BF16 = 1, 2, 4, 8
 
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
 
@@ -109,7 +109,7 @@ def backward_linear_engine(M, K, Cin, Cout, dtype_code, flags=0):
 
 def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), dW=None, db=None, dX=None,
                     workspace=None, inv=None):
-    """SBP backward of Y = X W^T + b on the kept rows.  Returns (dW fp32, db fp32, dX)."""
+    """SBP backward of Y = X W^T + b on the kept rows.  Returns (dW fp32 - bf16 with FLAG_DW_OUT_BF16 -, db fp32, dX)."""
     Cout, Cin = W.shape
     K = idx.numel() if idx is not None else dY.shape[0]
     if M is None:
@@ -119,7 +119,9 @@ def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), d
     code = _dtype_code(W)
     dev = W.device
     if "dW" in want and dW is None:
-        dW = torch.empty((Cout, Cin), dtype=torch.float32, device=dev)
+        dW = torch.empty((Cout, Cin), dtype=torch.bfloat16 if flags & FLAG_DW_OUT_BF16 else torch.float32, device=dev)
+    if dW is not None and dW.dtype != (torch.bfloat16 if flags & FLAG_DW_OUT_BF16 else torch.float32):
+        raise ValueError("dW must be bfloat16 with FLAG_DW_OUT_BF16 and float32 without")
     if "db" in want and db is None:
         db = torch.empty((Cout,), dtype=torch.float32, device=dev)
     if "dX" in want and dX is None:

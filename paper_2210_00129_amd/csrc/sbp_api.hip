@@ -130,7 +130,7 @@ int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t 
 
 static int32_t validate_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags) {
   if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
-  if (flags & ~(SBP_FLAG_DY_COMPACT | SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW))
+  if (flags & ~(SBP_FLAG_DY_COMPACT | SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16))
     return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);
   if (M < 1 || M > INT32_MAX || Cin < 1 || Cout < 1)
     return fail(SBP_ERR_SHAPE, "bad shape M=%lld Cin=%d Cout=%d", (long long)M, Cin, Cout);
@@ -155,7 +155,7 @@ int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Co
 
 int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* inv, const void* Xk, const void* W,
                             int64_t M,
-                            int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, float* dW, float* db,
+                            int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, void* dW, float* db,
                             void* dX, void* ws, size_t ws_bytes, uint32_t flags, void* stream) {
   int32_t st = validate_linear(M, K, Cin, Cout, dtype, flags);
   if (st != SBP_OK) return st;

@@ -68,7 +68,7 @@ struct LinearPlan {
 LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags);
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv,
                                const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
-                               int32_t dtype, float* dW, float* db, void* dX, void* ws, uint32_t flags,
+                               int32_t dtype, void* dW, float* db, void* dX, void* ws, uint32_t flags,
                                hipStream_t s);
 
 // inv[idx[j]] = j (no clearing needed: row m is kept iff 0 <= inv[m] < K and idx[inv[m]] == m), and +0 into

@@ -214,9 +214,23 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
 // adds a contiguous run of the splits (four loads in flight) and the G sums are added in lane order, so the order
 // depends on G and the split count only.  G > 1 is for small weight matrices cut into many splits, where one thread
 // per output would leave most CUs idle behind a long chain of dependent loads.
-template <int G>
+// dW in memory: fp32, or bf16 (BF16OUT: the fp32 sum rounded to nearest even; an old value is widened first)
+template <bool BF16OUT>
+__device__ __forceinline__ float4 load_dw4(const void* dW, long long e) {
+  if (!BF16OUT) return reinterpret_cast<const float4*>(dW)[e];
+  const uint2 w = reinterpret_cast<const uint2*>(dW)[e];
+  return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                     __uint_as_float(w.y & 0xffff0000u));
+}
+template <bool BF16OUT>
+__device__ __forceinline__ void store_dw4(void* dW, long long e, const float4& v) {
+  if (!BF16OUT) reinterpret_cast<float4*>(dW)[e] = v;
+  else reinterpret_cast<uint2*>(dW)[e] = make_uint2(bf16_pack(v.x, v.y), bf16_pack(v.z, v.w));
+}
+
+template <int G, bool BF16OUT>
 __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __restrict__ partial, int nsplit_w,
-                                                                  long long nW, float* __restrict__ dW,
+                                                                  long long nW, void* __restrict__ dW,
                                                                   const float* __restrict__ dbp, int nsplit_b, int Cout,
                                                                   float* __restrict__ db, int accumulate) {
   const long long nW4 = dW ? nW / 4 : 0;
@@ -245,10 +259,10 @@ __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __
       }
       if (g == 0) {
         if (accumulate) {
-          const float4 old = reinterpret_cast<const float4*>(dW)[e];
+          const float4 old = load_dw4<BF16OUT>(dW, e);
           t.x = old.x + t.x; t.y = old.y + t.y; t.z = old.z + t.z; t.w = old.w + t.w;
         }
-        reinterpret_cast<float4*>(dW)[e] = t;
+        store_dw4<BF16OUT>(dW, e, t);
       }
     } else {
       const long long o = e - nW4;
@@ -270,8 +284,9 @@ __global__ void __launch_bounds__(NTHREADS) reduce_splits_kernel(const float* __
 }
 
 // same, element by element, for weight matrices whose size is not a multiple of 4
+template <bool BF16OUT>
 __global__ void __launch_bounds__(NTHREADS) reduce_splits_scalar_kernel(const float* __restrict__ partial, int nsplit,
-                                                                         long long nW, float* __restrict__ dW,
+                                                                         long long nW, void* __restrict__ dW,
                                                                          const float* __restrict__ dbp, int Cout,
                                                                          float* __restrict__ db, int accumulate) {
   const long long nWe = dW ? nW : 0;
@@ -279,9 +294,16 @@ __global__ void __launch_bounds__(NTHREADS) reduce_splits_scalar_kernel(const fl
   for (long long e = blockIdx.x * (long long)blockDim.x + threadIdx.x; e < total;
        e += (long long)gridDim.x * blockDim.x) {
     if (e < nWe) {
-      float a = accumulate ? dW[e] : 0.f;
+      float a = 0.f;
       for (int s = 0; s < nsplit; ++s) a += partial[(long long)s * nW + e];
-      dW[e] = a;
+      if (BF16OUT) {
+        uint16_t* w = reinterpret_cast<uint16_t*>(dW);
+        if (accumulate) a = __uint_as_float((uint32_t)w[e] << 16) + a;
+        w[e] = (uint16_t)(bf16_pack(a, 0.f) & 0xffffu);
+      } else {
+        float* w = reinterpret_cast<float*>(dW);
+        w[e] = accumulate ? w[e] + a : a;
+      }
     } else {
       const long long o = e - nWe;
       float a = accumulate ? db[o] : 0.f;
@@ -746,11 +768,12 @@ static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool
 
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv_in,
                                const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
-                               int32_t dtype, float* dW, float* db, void* dX, void* ws, uint32_t flags,
+                               int32_t dtype, void* dW, float* db, void* dX, void* ws, uint32_t flags,
                                hipStream_t s) {
   const int eb = dtype == SBP_F32 ? 4 : 2;
   const bool dy_compact = flags & SBP_FLAG_DY_COMPACT, dx_compact = flags & SBP_FLAG_DX_COMPACT;
   const int accumulate = (flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
+  const bool dw_bf16 = flags & SBP_FLAG_DW_OUT_BF16;
   const int32_t* idx_in = dy_compact ? nullptr : idx;
   const int32_t* idx_out = dx_compact ? nullptr : idx;
   float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + p.off_partial);
@@ -760,9 +783,14 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   const long long nW = (long long)Cin * Cout;
 
   if (K == 0) {  // nothing kept: gradients are zero
-    if (!accumulate) {
-      if (dW) SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(256), dim3(NTHREADS), 0, s, (uint32_t*)dW, nW);
-      if (db) SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(1), dim3(NTHREADS), 0, s, (uint32_t*)db, (long long)Cout);
+    if (!accumulate) {   // a sum over no splits, written in dW's type
+      const unsigned blocks = (unsigned)std::min<long long>(ceil_div(nW + Cout, NTHREADS), 4096);
+      if (dw_bf16)
+        SBP_LAUNCH(SBP_PROF_OTHER, s, reduce_splits_scalar_kernel<true>, dim3(blocks), dim3(NTHREADS), 0, s, nullptr, 0, nW, dW,
+                   nullptr, Cout, db, 0);
+      else
+        SBP_LAUNCH(SBP_PROF_OTHER, s, reduce_splits_scalar_kernel<false>, dim3(blocks), dim3(NTHREADS), 0, s, nullptr, 0, nW, dW,
+                   nullptr, Cout, db, 0);
     }
     if (dX && !dx_compact)
       SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(1024), dim3(NTHREADS), 0, s, (uint32_t*)dX,
@@ -817,14 +845,19 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
       const int deepest = std::max(dW ? p.splits : 0, db ? nsplit_b : 0);
       const int G = total <= 20000 && deepest >= 16 ? 8 : (total <= 40000 && deepest >= 8 ? 4 : 1);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total * G, NTHREADS), 4096);
-      auto kernel = G == 8 ? reduce_splits_kernel<8> : (G == 4 ? reduce_splits_kernel<4> : reduce_splits_kernel<1>);
+      auto kernel = dw_bf16 ? (G == 8 ? reduce_splits_kernel<8, true> : (G == 4 ? reduce_splits_kernel<4, true> : reduce_splits_kernel<1, true>))
+                            : (G == 8 ? reduce_splits_kernel<8, false> : (G == 4 ? reduce_splits_kernel<4, false> : reduce_splits_kernel<1, false>));
       SBP_LAUNCH(SBP_PROF_REDUCE, s, kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW, dbp, nsplit_b, Cout, db,
                  accumulate);
     } else {
       const long long total = (dW ? nW : 0) + (db ? Cout : 0);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total, NTHREADS), 4096);
-      SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_scalar_kernel, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW, dW,
-                         dbp, Cout, db, accumulate);   // plain path only: db partials follow the dW splits
+      if (dw_bf16)   // plain path only: db partials follow the dW splits
+        SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_scalar_kernel<true>, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW,
+                   dW, dbp, Cout, db, accumulate);
+      else
+        SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_splits_scalar_kernel<false>, dim3(blocks), dim3(NTHREADS), 0, s, part, p.splits, nW,
+                   dW, dbp, Cout, db, accumulate);
     }
   }
 

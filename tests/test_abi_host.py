@@ -158,6 +158,10 @@ def test_backward_linear_engine_report_and_plan():
     assert sbp.backward_linear_engine(4200, 500, 512, 512, sbp.BF16)[0] == "mfma"       # too few kept rows
     with pytest.raises(ValueError):
         sbp.backward_linear_engine(100, 500, 64, 128, sbp.BF16)
+    # the bf16 weight gradient is a property of the last step only: same plan, same workspace
+    assert sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16, sbp.FLAG_DW_OUT_BF16) == \
+        sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16)
+    assert sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16, 16) == 0      # unknown flag
     # rows of dY that byte offsets of 32 bits cannot reach: the general engine takes the shape
     assert sbp.backward_linear_engine(1 << 20, 1 << 19, 4096, 4096, sbp.BF16)[0] == "mfma"
 

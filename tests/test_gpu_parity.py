@@ -347,6 +347,38 @@ def test_linear_accumulate_flag():
     assert nerr(f64(dW), rW + 2.0) <= TOL_F32 and nerr(f64(db), rb - 1.0) <= TOL_F32
 
 
+@pytest.mark.parametrize("case", ["large_tile", "general", "general_many_splits", "plain_f32", "plain_odd"])
+def test_linear_bf16_weight_gradient(case):
+    # FLAG_DW_OUT_BF16: dW leaves as bf16 = the fp32 sum rounded to nearest even once, on every engine and through
+    # every form of the split reduction; db and dX are untouched by the flag.  With FLAG_ACCUMULATE_DW the old bf16
+    # values are added in fp32 and the sum is rounded again.
+    B, Cin, Cout, dtype, env = {"large_tile": (16, 320, 288, "bf16", dict(SBP_TILE="big", SBP_SPLITS=3)),
+                                "general": (6, 200, 136, "bf16", dict(SBP_TILE="128x128x4x64")),
+                                "general_many_splits": (24, 64, 128, "bf16", {}),
+                                "plain_f32": (3, 24, 40, "f32", {}),
+                                "plain_odd": (3, 7, 5, "bf16", {})}[case]
+    X, W, dY, idx = _grid_case(B, 1, 14, 14, Cin, Cout, 2, dtype, 97)
+    M = X.shape[0]
+    idxd = torch.from_numpy(idx).cuda()
+    Xk = sbp.forward_cache(X.cuda(), idxd)
+    with _env(**env):
+        dW32, db32, dX32 = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda())
+        dW16, db16, dX16 = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda(), flags=sbp.FLAG_DW_OUT_BF16)
+        assert dW16.dtype == torch.bfloat16
+        assert np.array_equal(bits(dW16), bits(dW32.to(torch.bfloat16)))          # one rounding of the same sum
+        assert np.array_equal(bits(db16), bits(db32)) and np.array_equal(bits(dX16), bits(dX32))
+        rW, _, _ = oracle.backward_linear(si.to_f64(dY), idx, si.to_f64(X)[idx], si.to_f64(W), M)
+        assert nerr(f64(dW16), rW) <= TOL_BF16_TIGHT
+        old = torch.full((Cout, Cin), 0.5, dtype=torch.bfloat16, device="cuda")
+        acc, _, _ = sbp.backward_linear(dY.cuda(), idxd, Xk, W.cuda(), flags=sbp.FLAG_DW_OUT_BF16 | sbp.FLAG_ACCUMULATE_DW,
+                                        dW=old, want=("dW",))
+        assert np.array_equal(bits(acc), bits((dW32 + 0.5).to(torch.bfloat16)))
+    # nothing kept: zeros of the right type
+    empty = torch.empty(0, dtype=torch.int32, device="cuda")
+    z, _, _ = sbp.backward_linear(dY.cuda(), empty, Xk[:0], W.cuda(), flags=sbp.FLAG_DW_OUT_BF16, want=("dW", "db"))
+    assert z.dtype == torch.bfloat16 and np.all(bits(z) == 0)
+
+
 def test_linear_is_deterministic():
     X, W, dY, idx = _grid_case(8, 1, 14, 14, 256, 256, 2, "bf16", 95)
     idxd = torch.from_numpy(idx).cuda()
