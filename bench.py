@@ -436,6 +436,48 @@ def measure_attention(torch, sbp, si, iters=30, warmup=6):
     return out
 
 
+def measure_ceilings(torch, sbp, si, iters=10):
+    """What this library's own kernels reach on this machine where nothing of SBP is in the way: the row gather with
+    every row kept, in order (a plain copy of 512 MB), and the linear backward with every row kept on compact
+    operands of a large square layer (two plain dense bf16 GEMMs, 16384 x 4096 x 4096)."""
+    out = {}
+    M, C = 65536, 4096
+    X = torch.empty((M, C), dtype=torch.bfloat16, device="cuda").normal_()
+    Y = torch.empty_like(X)
+    idx = torch.arange(M, dtype=torch.int32, device="cuda")
+    def timed(fn, n):
+        for _ in range(3): fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n): fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    ms = timed(lambda: sbp.forward_cache(X, idx, out=Y), iters)
+    out["stream_copy"] = {"kernel": "gather_rows_vec16, identity keep list", "mb": round(2 * M * C * 2 / 1e6, 1),
+                          "us": round(ms * 1e3, 1), "gbs": round(2 * M * C * 2 / ms / 1e6, 1),
+                          "frac_of_hbm_peak": round(2 * M * C * 2 / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    del X, Y
+    K, Cin, Cout = 16384, 4096, 4096
+    dY = torch.empty((K, Cout), dtype=torch.bfloat16, device="cuda").normal_()
+    Xk = torch.empty((K, Cin), dtype=torch.bfloat16, device="cuda").normal_()
+    W = torch.empty((Cout, Cin), dtype=torch.bfloat16, device="cuda").normal_(0, 0.02)
+    flags = sbp.FLAG_DY_COMPACT | sbp.FLAG_DX_COMPACT
+    dW = torch.empty((Cout, Cin), dtype=torch.float32, device="cuda")
+    dX = torch.empty((K, Cin), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(sbp.backward_linear_workspace(K, K, Cin, Cout, sbp.BF16, flags), dtype=torch.uint8, device="cuda")
+    idx = idx[:K].contiguous()
+    ms = timed(lambda: sbp.backward_linear(dY, idx, Xk, W, M=K, flags=flags, want=("dW", "dX"), dW=dW, dX=dX, workspace=ws), iters)
+    tf = 4.0 * K * Cin * Cout / ms / 1e9
+    out["dense_gemm_pair"] = {"kernel": "sbp_backward_linear, r = 1, compact operands, 16384 x 4096 x 4096",
+                              "us": round(ms * 1e3, 1), "tflops": round(tf, 1),
+                              "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    del dY, Xk, W, dW, dX, ws
+    torch.cuda.empty_cache()
+    return out
+
+
 def measure_samplers(torch, sbp, si):
     """One draw (keep list + inverse map) of every sampler mode on the ViT-Base batch and on a detection map."""
     out = {}
@@ -577,6 +619,8 @@ def main():
         result["downsample_layer"] = measure_downsample(torch, sbp, si, args.ratio)
         result["sampler_modes"] = measure_samplers(torch, sbp, si)
         result["attention_drop_qkv"] = measure_attention(torch, sbp, si)
+        result["measured_ceilings"] = measure_ceilings(torch, sbp, si)
+        result["frac_of_own_dense_gemm"] = round(value / result["measured_ceilings"]["dense_gemm_pair"]["tflops"], 4)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, args.ratio, args.cpu_seconds, si)
     print(json.dumps(result))
