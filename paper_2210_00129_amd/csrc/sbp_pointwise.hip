@@ -164,10 +164,35 @@ __global__ void __launch_bounds__(PW_THREADS) ln_bwd_rows_kernel(const T* __rest
                                                                   const float* __restrict__ gamma, float eps,
                                                                   const int32_t* __restrict__ idx_out, int K, int C,
                                                                   int rows_per_block, T* __restrict__ dX,
-                                                                  float* __restrict__ partial) {
+                                                                  float* __restrict__ partial, int row_blocks,
+                                                                  const int32_t* __restrict__ inv, int M) {
   extern __shared__ float red[];                       // [4][C]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ngroups = C / 8;
+  if ((int)blockIdx.x >= row_blocks) {
+    // The blocks behind the row blocks write +0 to the rows of dX [M, C] that are not kept (scattered output
+    // only): a wavefront looks 64 rows up at once (row m is kept iff idx[inv[m]] == m) and all lanes together
+    // write each dropped row.
+    constexpr int PPG = 8 * sizeof(T) / 16;            // 16-byte pieces per group of 8 values
+    const int nz = gridDim.x - row_blocks, gw = ((int)blockIdx.x - row_blocks) * 4 + wave;
+    uint4* out = reinterpret_cast<uint4*>(dX);
+    for (int base = gw * 64; base < M; base += nz * 4 * 64) {
+      const int m = base + lane;
+      bool dropped = false;
+      if (m < M) {
+        const int j = inv[m];
+        dropped = !((unsigned)j < (unsigned)K && idx_out[j] == m);
+      }
+      unsigned long long mask = __ballot(dropped);
+      while (mask) {
+        const int b = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        uint4* row = out + (long long)(base + b) * (ngroups * PPG);
+        for (int q = lane; q < ngroups * PPG; q += 64) row[q] = make_uint4(0, 0, 0, 0);
+      }
+    }
+    return;
+  }
   const int r0 = blockIdx.x * rows_per_block, r1 = min(K, r0 + rows_per_block);
   float gam[NV][8], sg[NV][8], sb[NV][8];
 #pragma unroll
@@ -364,25 +389,30 @@ LnPlan plan_layernorm(int64_t M, int64_t K, int32_t C, int32_t, uint32_t flags) 
 
 template <typename T, int NV>
 static void launch_ln_fast(const LnPlan& p, const T* dU, const T* Xk, const float* gamma, float eps,
-                           const int32_t* idx_out, int K, int C, int rpb, T* dX, float* partial, hipStream_t s) {
+                           const int32_t* idx_out, int K, int C, int rpb, T* dX, float* partial, const int32_t* inv, int M,
+                           hipStream_t s) {
   const size_t lds = (size_t)4 * C * sizeof(float);   // at most 64 KB (C <= 4096)
-  SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_rows_kernel<T, NV>), dim3(p.nblocks), dim3(PW_THREADS), lds, s, dU, Xk, gamma, eps,
-             idx_out, K, C, rpb, dX, partial);
+  // scattered output: zero-fill blocks ride in the same launch
+  const int nz = (dX && idx_out && inv) ? (int)std::min<int64_t>(128, std::max<int64_t>(8, ceil_div(M, 256))) : 0;
+  SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_rows_kernel<T, NV>), dim3(p.nblocks + nz), dim3(PW_THREADS), lds, s, dU, Xk, gamma, eps,
+             idx_out, K, C, rpb, dX, partial, p.nblocks, inv, M);
 }
 
+// returns true if the launch also zero-filled the dropped rows of a scattered dX
 template <typename T>
-static void launch_ln_t(const LnPlan& p, const T* dU, const T* Xk, const float* gamma, float eps, const int32_t* idx_out,
-                        int K, int C, T* dX, float* partial, float* stats, hipStream_t s) {
+static bool launch_ln_t(const LnPlan& p, const T* dU, const T* Xk, const float* gamma, float eps, const int32_t* idx_out,
+                        int K, int C, T* dX, float* partial, float* stats, const int32_t* inv, int M, hipStream_t s) {
   const int rpb = (int)ceil_div(K, p.nblocks);
   const bool aligned = (uintptr_t)dU % 16 == 0 && (uintptr_t)Xk % 16 == 0 && (uintptr_t)dX % 16 == 0;
   if (p.fast && aligned) {
     const int nv = (int)ceil_div(C / 8, 64);
     switch (nv) {
-      case 1: launch_ln_fast<T, 1>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
-      case 2: launch_ln_fast<T, 2>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
-      case 3: case 4: launch_ln_fast<T, 4>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
-      default: launch_ln_fast<T, 8>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, s); break;
+      case 1: launch_ln_fast<T, 1>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, inv, M, s); break;
+      case 2: launch_ln_fast<T, 2>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, inv, M, s); break;
+      case 3: case 4: launch_ln_fast<T, 4>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, inv, M, s); break;
+      default: launch_ln_fast<T, 8>(p, dU, Xk, gamma, eps, idx_out, K, C, rpb, dX, partial, inv, M, s); break;
     }
+    return dX && idx_out && inv;
   } else {
     const unsigned rows_grid = (unsigned)std::min<int64_t>(K, 8192);
     SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_plain_rows_kernel<T>), dim3(rows_grid), dim3(64), 0, s, dU, Xk, gamma, eps, idx_out, K,
@@ -391,6 +421,7 @@ static void launch_ln_t(const LnPlan& p, const T* dU, const T* Xk, const float* 
       SBP_LAUNCH(SBP_PROF_OTHER, s, (ln_bwd_plain_cols_kernel<T>), dim3((unsigned)ceil_div(C, PW_THREADS), p.nblocks),
                  dim3(PW_THREADS), 0, s, dU, Xk, stats, K, C, rpb, partial);
   }
+  return false;
 }
 
 int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* Xk, const float* gamma, float eps,
@@ -405,6 +436,13 @@ int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* X
   int32_t* inv_ws = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + p.off_inv);
   const bool want_params = dgamma || dbeta;
 
+  // the inverse map for the zero fill of a scattered dX (built here unless the caller brought the sampler's)
+  const int32_t* inv = inv_in;
+  if (dX && !dx_compact && !inv) {
+    launch_build_inverse(idx, K, inv_ws, s);
+    inv = inv_ws;
+  }
+  bool zero_filled = false;
   if (K == 0) {   // nothing kept: gradients are zero
     if (!accumulate && want_params) {
       if (dgamma) SBP_LAUNCH(SBP_PROF_OTHER, s, ln_fill_zero_kernel, dim3((unsigned)ceil_div(C, PW_THREADS)), dim3(PW_THREADS), 0, s, dgamma, C);
@@ -413,23 +451,16 @@ int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* X
   } else {
     const int32_t* idx_out = dx_compact ? nullptr : idx;
     if (dtype == SBP_F32)
-      launch_ln_t<float>(p, (const float*)dU, (const float*)Xk, gamma, eps, idx_out, (int)K, C, (float*)dX,
-                         want_params ? partial : nullptr, stats, s);
+      zero_filled = launch_ln_t<float>(p, (const float*)dU, (const float*)Xk, gamma, eps, idx_out, (int)K, C, (float*)dX,
+                                       want_params ? partial : nullptr, stats, inv, (int)M, s);
     else
-      launch_ln_t<uint16_t>(p, (const uint16_t*)dU, (const uint16_t*)Xk, gamma, eps, idx_out, (int)K, C, (uint16_t*)dX,
-                            want_params ? partial : nullptr, stats, s);
+      zero_filled = launch_ln_t<uint16_t>(p, (const uint16_t*)dU, (const uint16_t*)Xk, gamma, eps, idx_out, (int)K, C,
+                                          (uint16_t*)dX, want_params ? partial : nullptr, stats, inv, (int)M, s);
     if (want_params)
       SBP_LAUNCH(SBP_PROF_REDUCE, s, ln_reduce_kernel, dim3((unsigned)ceil_div(16 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
                  partial, p.nblocks, C, dgamma, dbeta, accumulate);
   }
-  if (dX && !dx_compact) {
-    const int32_t* inv = inv_in;
-    if (!inv) {
-      launch_build_inverse(idx, K, inv_ws, s);
-      inv = inv_ws;
-    }
-    launch_zero_dropped_rows(idx, inv, K, M, (int64_t)C * eb, dX, s);
-  }
+  if (dX && !dx_compact && !zero_filled) launch_zero_dropped_rows(idx, inv, K, M, (int64_t)C * eb, dX, s);
   return check_launch("backward_layernorm");
 }
 
