@@ -268,13 +268,12 @@ def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3):
     return out
 
 
-def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5):
-    """Backward of one ViT-Base MLP branch (LayerNorm -> fc1 -> GELU -> fc2, one keep-set) on compact rows with a
+def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5, model="vit_base", C=768, Hd=3072, row_wise=True):
+    """Backward of one ViT MLP branch (LayerNorm -> fc1 -> GELU -> fc2, one keep-set) on compact rows with a
     single final scatter, against the same kernels scattering to full size after every linear layer; plus the
     row-wise kernels on their own against the HBM roofline."""
-    wl = si.WORKLOADS["vit_base"]
+    wl = si.WORKLOADS[model]
     M = wl.B * (wl.P + wl.H * wl.W)
-    C, Hd = 768, 3072
     k = sbp.k_from_ratio(r)
     idx, inv = sbp.sample_indices(wl.B, wl.P, wl.H, wl.W, k, 0, 1, want_inv=True)
     K = idx.numel()
@@ -330,7 +329,7 @@ def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5):
     flops = 2 * 4.0 * K * C * Hd
     ms_c, ms_s = timed(compact), timed(scattered)
     kern = {}
-    for name, fn, nbytes in (
+    for name, fn, nbytes in () if not row_wise else (
             ("act_forward_rows", lambda b: sbp.act_forward_rows(b["Zk"], out=b["Hk"]), 2 * K * Hd * 2),
             ("act_backward_rows", lambda b: sbp.act_backward_rows(b["dHk"], b["Zk"], out=b["dHk"]), 3 * K * Hd * 2),
             ("backward_layernorm", lambda b: sbp.backward_layernorm(b["dUk"], b["Xk"], b["gamma"], 1e-6, idx, M, inv=inv,
@@ -342,9 +341,12 @@ def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5):
         ms = timed(fn, 50)
         kern[name] = {"us": round(ms * 1e3, 2), "algorithmic_mb": round(nbytes / 1e6, 2),
                       "gbs": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / 8000.0, 4)}
-    return {"workload": f"vit_base MLP branch backward (LayerNorm, fc1 768->3072, GELU, fc2 3072->768), K={K} of M={M}",
-            "compact_ms": round(ms_c, 4), "scatter_every_layer_ms": round(ms_s, 4), "speedup": round(ms_s / ms_c, 3),
-            "tflops_compact": round(flops / ms_c / 1e9, 1), "row_wise_kernels": kern}
+    out = {"workload": f"{model} MLP branch backward (LayerNorm, fc1 {C}->{Hd}, GELU, fc2 {Hd}->{C}), K={K} of M={M}",
+           "compact_ms": round(ms_c, 4), "scatter_every_layer_ms": round(ms_s, 4), "speedup": round(ms_s / ms_c, 3),
+           "tflops_compact": round(flops / ms_c / 1e9, 1)}
+    if row_wise:
+        out["row_wise_kernels"] = kern
+    return out
 
 
 def measure_downsample(torch, sbp, si, r, iters=20, warmup=5):
@@ -616,6 +618,8 @@ def main():
                 extras.append(measure_extra(name, args.ratio, torch, sbp, si))
         result["other_workloads"] = extras
         result["mlp_branch_compact"] = measure_mlp_branch(torch, sbp, si, args.ratio)
+        result["mlp_branch_compact_vit_tiny"] = measure_mlp_branch(torch, sbp, si, args.ratio, model="vit_tiny_mlp", C=192, Hd=768,
+                                                                   row_wise=False)
         result["downsample_layer"] = measure_downsample(torch, sbp, si, args.ratio)
         result["sampler_modes"] = measure_samplers(torch, sbp, si)
         result["attention_drop_qkv"] = measure_attention(torch, sbp, si)
