@@ -58,7 +58,8 @@ struct LinearPlan {
   int    nw_w;          // wavefronts per block (4 or 8)
   int    kb;            // contraction elements per LDS stage (64: two stages, 32: four stages)
   bool   big;           // 256 x 256 tiles, one workgroup per CU (sbp_mfma_big.h)
-  int    dx_bm;         // big engine: rows of a dX tile (256, or 128 where 256-row tiles are too few)
+  int    dx_bm;         // rows of a dX tile: big engine 256, or 128 where 256-row tiles are too few; general engine 128, or
+                        // 64 (in a ring of three stages) for small layers
   int    db_slices;     // partial sums of db (row slices of the column-sum blocks)
   int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]

@@ -94,7 +94,8 @@ __device__ __forceinline__ void zero_rows_block(const LinArgs& a, int blk) {
   }
 }
 
-template <int BM, int BN, int NW, int KB, int NSTAGE>
+// BMX, NSX: rows and ring depth of the dX tiles (the dW units use BM and NSTAGE)
+template <int BM, int BN, int NW, int KB, int NSTAGE, int BMX, int NSX>
 __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_kernel(const LinArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   int wg = blockIdx.x;
@@ -122,11 +123,11 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
   }
   const int tiles_n = (a.Cin + BN - 1) / BN;
   if (kind == 0) {
-    const int ntiles = ((a.K + BM - 1) / BM) * tiles_n;
+    const int ntiles = ((a.K + BMX - 1) / BMX) * tiles_n;
     const int L = xcd_chunked_id(wg, ntiles);
     if (L >= ntiles) return;
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-    dx_tile<BM, BN, NW, KB, NSTAGE>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * BM, tile_n * BN);
+    dx_tile<BMX, BN, NW, KB, NSX>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * BMX, tile_n * BN);
     return;
   }
   const int tiles_m = (a.Cout + BM - 1) / BM;
@@ -628,6 +629,13 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
       int64_t max_by_len = std::max<int64_t>(1, K / (4 * 64));
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(want, max_by_len), 64));
       splits = (int)std::max<int64_t>(splits, ceil_div(K, kMaxRowsPerSplit));   // the split's row ids sit in LDS
+      // Small layers, whose workgroups (nearly) all find a slot at once (two per CU): the launch then lasts as long as
+      // its longest workgroup, a dX tile walking the whole of Cout with one stage in flight.  Tiles of 64 rows in a
+      // ring of three keep two stages in flight in the same LDS (ViT-Tiny MLP: 52.9 -> 50.3 us per step); where the
+      // tiles queue for slots the 128-row tiles move fewer bytes and win (detection shapes).
+      p.dx_bm = 128;
+      if (p.bm_w == 128 && p.kb == 64 && ceil_div(K, 128) * ceil_div(Cin, 128) + tiles * splits + 64 <= 700) p.dx_bm = 64;   // (measured: still ahead at 650 workgroups, behind at 770)
+      if (const char* e = std::getenv("SBP_DXROWS")) p.dx_bm = std::atoi(e) == 64 && p.bm_w == 128 && p.kb == 64 ? 64 : 128;   // debugging aid
     } else {
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(K, 512), 64));
     }
@@ -688,17 +696,18 @@ static void allow_big_lds(KernelT kernel, size_t lds) {
   }
 }
 
-template <int BM, int BN, int NW, int KB, int NSTAGE>
+template <int BM, int BN, int NW, int KB, int NSTAGE, int BMX = BM, int NSX = NSTAGE>
 static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero,
                               hipStream_t s) {
-  // stage ring + the row-id table of a dW split (rows_per_split rounded up to the stage length)
-  const size_t lds = (size_t)NSTAGE * (BM + BN) * KB * 2 + (size_t)(p.rows_per_split + KB) * sizeof(int);
-  allow_big_lds(linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>, lds);
+  // stage ring + the row-id table of a dW split (rows_per_split rounded up to the stage length), or the dX tiles' ring
+  const size_t lds = std::max((size_t)NSTAGE * (BM + BN) * KB * 2 + (size_t)(p.rows_per_split + KB) * sizeof(int),
+                              (size_t)NSX * (BMX + BN) * KB * 2);
+  allow_big_lds(linear_bwd_kernel<BM, BN, NW, KB, NSTAGE, BMX, NSX>, lds);
   const long long tiles_n = ceil_div(a.Cin, BN);
   a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M, 64 * NW))) : 0;
   const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
   a.n_helper = (int)(8 * ceil_div(a.n_zero + n_db, 8));
-  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, BM) * tiles_n, 8)) : 0;
+  a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, BMX) * tiles_n, 8)) : 0;
   a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, BM) * tiles_n * p.splits, 8)) : 0;
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
   if (grid == 0) return;
@@ -716,7 +725,7 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
         (1 << v[0] | 1 << v[1] | 1 << v[2]) == 7)
       for (int q = 0; q < 3; ++q) a.seg_order[q] = v[q];
   }
-  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE>), dim3(grid), dim3(64 * NW), lds, s, a);
+  SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE, BMX, NSX>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 
 // Writes +0 to the rows of out[M][row_bytes] that are not in idx (inv: inverse map, see mark_rows_kernel).
@@ -828,6 +837,8 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
       launch_linear_bwd<256, 256, 4, 64, 2>(p, a, want_dx, want_dw, scatter, s);
     else if (p.kb == 32)
       launch_linear_bwd<128, 128, 4, 32, 4>(p, a, want_dx, want_dw, scatter, s);
+    else if (p.dx_bm == 64)
+      launch_linear_bwd<128, 128, 4, 64, 2, 64, 3>(p, a, want_dx, want_dw, scatter, s);
     else
       launch_linear_bwd<128, 128, 4, 64, 2>(p, a, want_dx, want_dw, scatter, s);
   } else if (dtype == SBP_F32) {

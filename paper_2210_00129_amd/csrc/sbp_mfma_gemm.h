@@ -233,7 +233,7 @@ __device__ __forceinline__ void zero_acc(f32x16_t (&acc)[FM][FN]) {
 // ------------------------------------------------------------------------------------------------
 template <int NSTAGE, int KB, int A_BYTES, int STAGE, class LA, class LB, class Compute>
 __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, int kend, int nk, Compute&& compute) {
-  static_assert(NSTAGE == 2 || NSTAGE == 4, "ring of 2 or 4 stages");
+  static_assert(NSTAGE >= 2 && NSTAGE <= 4, "ring of 2 to 4 stages");
   constexpr int C = LA::NI + LB::NI;               // copies per wavefront and stage
   if (nk <= 0) return;
   const int t = threadIdx.x;
@@ -255,8 +255,8 @@ __device__ __forceinline__ void stage_loop(char* smem, LA& la, LB& lb, int k0, i
   for (int kt = 0; kt < nk; ++kt) {
     char* cur = smem + (kt % NSTAGE) * STAGE;
     const int ahead = min(NSTAGE - 2, nk - 1 - kt);    // stages issued after stage kt
-    if (NSTAGE == 4 && ahead == 2) wait_async_copies<2 * C>();
-    else if (NSTAGE == 4 && ahead == 1) wait_async_copies<C>();
+    if (NSTAGE >= 4 && ahead == 2) wait_async_copies<2 * C>();
+    else if (NSTAGE >= 3 && ahead == 1) wait_async_copies<C>();
     else wait_async_copies<0>();
     lds_barrier();
     if (tail && kt == nk - 1) {

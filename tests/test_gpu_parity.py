@@ -213,6 +213,18 @@ def test_linear_general_engine_every_segment_order(order):
         check_linear(X, W, dY, idx, "bf16", flags=sbp.FLAG_DX_COMPACT)
 
 
+@pytest.mark.parametrize("k", [1, 2, 4])
+@pytest.mark.parametrize("shape", [(192, 768), (768, 192), (72, 200), (8, 8), (264, 136)])
+def test_linear_general_engine_short_dx_tiles(shape, k):
+    # dX tiles of 64 rows in a ring of three stages (what small layers get by themselves), forced on ragged shapes
+    # with one to many stages of the contraction
+    Cin, Cout = shape
+    X, W, dY, idx = _grid_case(6, 1, 14, 14, Cin, Cout, k, "bf16", 50 + k)
+    with _env(SBP_TILE="128x128x4x64", SBP_DXROWS=64):
+        check_linear(X, W, dY, idx, "bf16")
+        check_linear(X, W, dY, idx, "bf16", flags=sbp.FLAG_DX_COMPACT | sbp.FLAG_DY_COMPACT)
+
+
 def test_linear_engines_agree_bit_for_bit_on_integers():
     # exact arithmetic: whichever engine, tile height or split count runs, the results are the same bits
     B, P, H, W_, Cin, Cout = 8, 1, 14, 14, 320, 288
@@ -222,7 +234,8 @@ def test_linear_engines_agree_bit_for_bit_on_integers():
     idx = torch.from_numpy(oracle.sample_indices(B, P, H, W_, 2, 5, 9)).cuda()
     Xk = sbp.forward_cache(X.cuda(), idx)
     outs = []
-    for env in (dict(SBP_TILE="128x128x4x64"), dict(SBP_TILE="big", SBP_DXBM=256, SBP_SPLITS=1),
+    for env in (dict(SBP_TILE="128x128x4x64"), dict(SBP_TILE="128x128x4x64", SBP_DXROWS=64),
+                dict(SBP_TILE="big", SBP_DXBM=256, SBP_SPLITS=1),
                 dict(SBP_TILE="big", SBP_DXBM=128, SBP_SPLITS=4)):
         with _env(**env):
             outs.append([bits(t) if t.dtype == torch.bfloat16 else f64(t) for t in sbp.backward_linear(dY.cuda(), idx, Xk, Wt.cuda())])
