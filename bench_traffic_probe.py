@@ -7,6 +7,7 @@ Run it twice under rocprofv3, once per counter (the two do not fit one pass):
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d prof_out/pmc_write -- python3 bench_traffic_probe.py
     python3 bench_traffic_probe.py --summarize prof_out/pmc_fetch prof_out/pmc_write
 
+(`--workload NAME` after the script name takes another workload of synth_inputs.WORKLOADS than ViT-Base.)
 The workload: a plain device-to-device copy of known size (the calibration: what the counter reads
 for a known number of bytes), then one SBP linear backward per ViT-Base layer shape at r = 0.5 and one
 forward-cache gather, on fresh buffers larger than the last-level cache between launches.
@@ -26,13 +27,13 @@ sys.path.insert(0, ROOT)
 COPY_BYTES = 256 * 1024 * 1024           # read 256 MiB, write 256 MiB per copy launch
 
 
-def workload():
+def workload(name="vit_base"):
     import torch
     import paper_2210_00129_amd as sbp
     import synth_inputs as si
 
     torch.cuda.set_device(0)
-    wl = si.WORKLOADS["vit_base"]
+    wl = si.WORKLOADS[name]
     src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
     dst = torch.empty_like(src)
     flush = torch.empty(768 * 1024 * 1024, dtype=torch.uint8, device="cuda")
@@ -78,5 +79,7 @@ def summarize(dirs):
 if __name__ == "__main__":
     if len(sys.argv) > 1 and sys.argv[1] == "--summarize":
         summarize(sys.argv[2:])
+    elif len(sys.argv) > 2 and sys.argv[1] == "--workload":     # e.g. --workload convnext_det_s1
+        workload(sys.argv[2])
     else:
         workload()
