@@ -201,17 +201,17 @@ __device__ __forceinline__ float dw_dot2(uint32_t a, uint32_t b, float acc) {
 // paired along x, and added to the KS output rows it reaches, whose DW_TX x 2 running sums each stay in registers
 // (slot j holds output row yy - PAD + j; after gradient row yy slot 0 is complete, is stored, and the slots
 // move up).  Products are exact (bf16 x bf16 in fp32), sums fp32.
+// (strip: number of the strip chunk; the channel pair comes from blockIdx.y and threadIdx.x)
 template <int KS>
-__global__ void __launch_bounds__(DW_THREADS) dw_dx_strip_kernel(const uint32_t* __restrict__ dY, const int32_t* __restrict__ inv,
-                                                                 const uint32_t* __restrict__ Wd, int H, int W, int C2,
-                                                                 uint32_t* __restrict__ dX, int tiles_x, int chunks,
-                                                                 int rows_per_chunk) {
+__device__ __forceinline__ void dw_dx_strip_body(int strip, const uint32_t* __restrict__ dY, const int32_t* __restrict__ inv,
+                                                 const uint32_t* __restrict__ Wd, int H, int W, int C2,
+                                                 uint32_t* __restrict__ dX, int tiles_x, int chunks, int rows_per_chunk) {
   constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1, NP = (KS + 1) / 2, NG = WIN / 2;
   static_assert(WIN % 2 == 0, "pairs along the window row");
   const int cp_raw = blockIdx.y * blockDim.x + threadIdx.x;
   const bool active = cp_raw < C2;
   const int cp = active ? cp_raw : C2 - 1;
-  const DwStrip t = dw_strip(blockIdx.x, tiles_x, chunks, rows_per_chunk, H);
+  const DwStrip t = dw_strip(strip, tiles_x, chunks, rows_per_chunk, H);
   // weight pairs of tap row u: (w[u][KS-1-2m], w[u][KS-2-2m]) meet the gradients of columns (ox + 2m, ox + 2m + 1)
   uint32_t wp[KS][NP][2];
 #pragma unroll
@@ -280,16 +280,23 @@ __global__ void __launch_bounds__(DW_THREADS) dw_dx_strip_kernel(const uint32_t*
   }
 }
 
+template <int KS>
+__global__ void __launch_bounds__(DW_THREADS) dw_dx_strip_kernel(const uint32_t* __restrict__ dY, const int32_t* __restrict__ inv,
+                                                                 const uint32_t* __restrict__ Wd, int H, int W, int C2,
+                                                                 uint32_t* __restrict__ dX, int tiles_x, int chunks,
+                                                                 int rows_per_chunk) {
+  dw_dx_strip_body<KS>(blockIdx.x, dY, inv, Wd, H, W, C2, dX, tiles_x, chunks, rows_per_chunk);
+}
+
 // dWd, db: blockDim = (channel pairs, GROUPS); every group walks strips with the window of X in registers and
 // KS*KS + 1 running sums per channel.  Groups are added through LDS in a fixed order, one partial per block.
+// (blk of nblk: this block among those that share the strips; the whole workgroup calls this together)
 template <int KS, int GROUPS>
-__global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_strip_kernel(const uint32_t* __restrict__ dY,
-                                                                          const int32_t* __restrict__ inv,
-                                                                          const uint32_t* __restrict__ X, int H, int W,
-                                                                          int C2, int tiles_x, int chunks, int rows_per_chunk,
-                                                                          int nstrips, float* __restrict__ part) {
-  constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1, NT = KS * KS + 1;
-  extern __shared__ float red[];             // [GROUPS - 1][CHUNK][blockDim.x][2]
+__device__ __forceinline__ void dw_dw_strip_body(int blk, int nblk, float* red, const uint32_t* __restrict__ dY,
+                                                 const int32_t* __restrict__ inv, const uint32_t* __restrict__ X, int H, int W,
+                                                 int C2, int tiles_x, int chunks, int rows_per_chunk, int nstrips,
+                                                 float* __restrict__ part) {
+  constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1, NT = KS * KS + 1;   // red: [GROUPS - 1][CHUNK][blockDim.x][2] in LDS
   const int cp_raw = blockIdx.y * blockDim.x + threadIdx.x;
   const bool active = cp_raw < C2;
   const int cp = active ? cp_raw : C2 - 1;
@@ -299,7 +306,7 @@ __global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_strip_kernel(const 
 #pragma unroll
   for (int tp = 0; tp < NT; ++tp) { s0[tp] = 0.f; s1[tp] = 0.f; }
 
-  for (int strip = blockIdx.x * GROUPS + grp; strip < nstrips; strip += gridDim.x * GROUPS) {
+  for (int strip = blk * GROUPS + grp; strip < nstrips; strip += nblk * GROUPS) {
     const DwStrip t = dw_strip(strip, tiles_x, chunks, rows_per_chunk, H);
     unsigned colmask = 0;                     // window columns inside the map
 #pragma unroll
@@ -367,7 +374,7 @@ __global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_strip_kernel(const 
   // add the groups (fixed order 0, 1, 2, ...) through LDS, CHUNK taps at a time
   constexpr int CHUNK = 10;
   const int ct = blockDim.x;
-  float* out = part + ((long long)blockIdx.x * NT) * (2 * C2);
+  float* out = part + ((long long)blk * NT) * (2 * C2);
 #pragma unroll
   for (int c0 = 0; c0 < NT; c0 += CHUNK) {
     if (grp > 0) {
@@ -393,6 +400,38 @@ __global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_strip_kernel(const 
         }
     }
     __syncthreads();
+  }
+}
+
+template <int KS, int GROUPS>
+__global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_dw_strip_kernel(const uint32_t* __restrict__ dY,
+                                                                          const int32_t* __restrict__ inv,
+                                                                          const uint32_t* __restrict__ X, int H, int W,
+                                                                          int C2, int tiles_x, int chunks, int rows_per_chunk,
+                                                                          int nstrips, float* __restrict__ part) {
+  extern __shared__ float red[];
+  dw_dw_strip_body<KS, GROUPS>(blockIdx.x, gridDim.x, red, dY, inv, X, H, W, C2, tiles_x, chunks, rows_per_chunk, nstrips, part);
+}
+
+// Both in one launch, for callers that want dX and the weight gradient (the usual case): on a small map each of the
+// two kernels alone leaves the SIMDs with one wavefront, and neither can hide its latencies; side by side they
+// share the CUs.  The first n_dw workgroups walk strips for dWd / db, the others take GROUPS dX strips each.
+struct DwBothArgs {
+  const uint32_t* dY; const int32_t* inv; const uint32_t* X; const uint32_t* Wd;
+  int H, W, C2, tiles_x;
+  int chunks_w, rows_w, nstrips_w, n_dw;     // weight-gradient role
+  int chunks_x, rows_x, nstrips_x;           // dX role
+  float* part; uint32_t* dX;
+};
+template <int KS, int GROUPS>
+__global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_both_strip_kernel(const DwBothArgs a) {
+  extern __shared__ float red[];
+  if ((int)blockIdx.x < a.n_dw) {
+    dw_dw_strip_body<KS, GROUPS>(blockIdx.x, a.n_dw, red, a.dY, a.inv, a.X, a.H, a.W, a.C2, a.tiles_x, a.chunks_w, a.rows_w,
+                                 a.nstrips_w, a.part);
+  } else {
+    const int strip = ((int)blockIdx.x - a.n_dw) * GROUPS + (int)threadIdx.y;
+    if (strip < a.nstrips_x) dw_dx_strip_body<KS>(strip, a.dY, a.inv, a.Wd, a.H, a.W, a.C2, a.dX, a.tiles_x, a.chunks_x, a.rows_x);
   }
 }
 
@@ -472,6 +511,27 @@ int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* i
     int rows = pick_rows(256);
     int chunks = (int)ceil_div(H, rows);
     int nstrips = tiles_x * chunks * B;
+    if (dX && (dWd || db) && !std::getenv("SBP_DW_SEPARATE")) {   // (debugging aid: the two kernels one after the other)
+      // one launch for both; strip heights chosen so that everything finds a CU at once where the map allows
+      DwBothArgs a{};
+      a.dY = (const uint32_t*)dY; a.inv = inv; a.X = (const uint32_t*)X; a.Wd = (const uint32_t*)Wd;
+      a.H = H; a.W = W; a.C2 = C2; a.tiles_x = tiles_x;
+      a.rows_x = rows; a.chunks_x = chunks; a.nstrips_x = nstrips;
+      const int n_dx = (int)ceil_div(nstrips, DW_GROUPS);
+      a.rows_w = pick_rows(288);
+      a.chunks_w = (int)ceil_div(H, a.rows_w);
+      a.nstrips_w = tiles_x * a.chunks_w * B;
+      a.n_dw = (int)std::min<int64_t>(p.nparts, ceil_div(a.nstrips_w, DW_GROUPS));
+      a.part = part; a.dX = (uint32_t*)dX;
+      dim3 grid((unsigned)(a.n_dw + n_dx), (unsigned)cblocks);
+      const size_t lds = (size_t)(DW_GROUPS - 1) * 10 * ct * 2 * sizeof(float);
+      if (ks == 7) SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_both_strip_kernel<7, DW_GROUPS>), grid, dim3(ct, DW_GROUPS), lds, s, a);
+      else SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_both_strip_kernel<3, DW_GROUPS>), grid, dim3(ct, DW_GROUPS), lds, s, a);
+      const int n = (ks * ks + 1) * C;
+      SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, dw_reduce_kernel, dim3((unsigned)ceil_div(n, 32)), dim3(DW_THREADS), 0,
+                 s, part, a.n_dw, ks * ks, C, dWd, db);
+      return check_launch("backward_dwconv");
+    }
     if (dX) {
       dim3 grid((unsigned)nstrips, (unsigned)cblocks);
       if (ks == 7)

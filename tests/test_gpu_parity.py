@@ -456,6 +456,26 @@ def test_dwconv_convnext_stage3_full_size(k):
     _check_dw(2, 50, 84, 512, 7, k, "bf16", 131, use_inv=True)
 
 
+@pytest.mark.parametrize("geom", [(2, 50, 84, 512, 7), (1, 7, 9, 24, 7), (2, 5, 5, 8, 3)])
+def test_dwconv_one_launch_two_launches_and_single_outputs_agree(geom):
+    # dX and the weight gradient normally share one launch; the two kernels on their own (switch, or a caller that
+    # wants only one of the outputs) give the same dX bit for bit and the same sums up to their order
+    B, H, W, C, ks = geom
+    X, Wd, dY = si.dwconv_case(B, H, W, C, ks, 151, "bf16")
+    idx_np = oracle.sample_indices(B, 0, H, W, 2, 151, 78)
+    idx = torch.from_numpy(idx_np).cuda()
+    inv = torch.from_numpy(oracle.inverse_map(idx_np, B * H * W)).cuda()
+    both = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+    with _env(SBP_DW_SEPARATE=1):
+        two = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+    only_dx = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dX",))
+    only_w = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dWd", "db"))
+    assert np.array_equal(bits(both[2]), bits(two[2])) and np.array_equal(bits(both[2]), bits(only_dx[2]))
+    rWd, rb, _ = oracle.backward_dwconv(si.to_f64(dY), idx_np, si.to_f64(X), si.to_f64(Wd), ks // 2)
+    for got in (both, two, only_w):
+        assert nerr(f64(got[0]), rWd) <= TOL_F32 and nerr(f64(got[1]), rb) <= TOL_F32
+
+
 def test_dwconv_single_kept_position_stamps_kernel():
     B, H, W, C, ks = 1, 9, 11, 64, 7
     X, Wd, dY = si.dwconv_case(B, H, W, C, ks, 141, "f32")
