@@ -131,9 +131,6 @@ __global__ void __launch_bounds__(DW_THREADS) dw_reduce_kernel(const float* __re
 // ------------------------------------------------------------------------------------------------
 static constexpr int DW_TX = 8;
 
-__device__ __forceinline__ float dw_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float dw_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
 // Strip kernels: a workgroup (dX) or a group of a workgroup (dWd, db) walks down a strip of DW_TX columns over a
 // chunk of rows: each row of the map is fetched once per strip instead of KS times, the weights once per chunk,
 // the next row's loads (and its inverse-map lookups) are in flight while the current row is computed, and the
@@ -338,26 +335,38 @@ __device__ __forceinline__ void dw_dw_strip_body(int blk, int nblk, float* red, 
         dw_load_row<KS>(X, t.b, y + 1 + PAD, t.x0, H, W, C2, cp, nxt);
         lookn = load_g(y + 1, gn);
       }
-      float g0[DW_TX], g1[DW_TX];
+      // pairs along x of one channel: gradients (g[2k], g[2k+1]) against window pairs (x[2k+v], x[2k+v+1]); one
+      // v_dot2 adds two exact products to the fp32 sum of tap (u, v); the bias sum pairs the gradients with (1, 1)
+      static_assert(DW_TX % 2 == 0, "gradient pairs");
+      constexpr uint32_t kOnes = 0x3f803f80u;
 #pragma unroll
-      for (int ox = 0; ox < DW_TX; ++ox) {
-        g0[ox] = dw_lo(g[ox]);
-        g1[ox] = dw_hi(g[ox]);
-        s0[KS * KS] += g0[ox]; s1[KS * KS] += g1[ox];
-      }
+      for (int c = 0; c < 2; ++c) {
+        uint32_t gp[DW_TX / 2];
 #pragma unroll
-      for (int u = 0; u < KS; ++u)
-#pragma unroll
-        for (int col = 0; col < WIN; ++col) {
-          const float xa = dw_lo(win[u][col]), xb = dw_hi(win[u][col]);
-#pragma unroll
-          for (int ox = 0; ox < DW_TX; ++ox) {
-            const int v = col - ox;
-            if (v < 0 || v >= KS) continue;            // compile time
-            s0[u * KS + v] = fmaf(g0[ox], xa, s0[u * KS + v]);
-            s1[u * KS + v] = fmaf(g1[ox], xb, s1[u * KS + v]);
-          }
+        for (int k = 0; k < DW_TX / 2; ++k) {
+          gp[k] = c == 0 ? dw_pair_lo(g[2 * k], g[2 * k + 1]) : dw_pair_hi(g[2 * k], g[2 * k + 1]);
+          if (c == 0) s0[KS * KS] = dw_dot2(gp[k], kOnes, s0[KS * KS]);
+          else s1[KS * KS] = dw_dot2(gp[k], kOnes, s1[KS * KS]);
         }
+#pragma unroll
+        for (int u = 0; u < KS; ++u) {
+          uint32_t xe[WIN / 2], xo[WIN / 2];       // (x[2m], x[2m+1]) and (x[2m+1], x[2m+2])
+#pragma unroll
+          for (int m = 0; m < WIN / 2; ++m) {
+            xe[m] = c == 0 ? dw_pair_lo(win[u][2 * m], win[u][2 * m + 1]) : dw_pair_hi(win[u][2 * m], win[u][2 * m + 1]);
+            xo[m] = 2 * m + 2 < WIN ? (c == 0 ? dw_pair_lo(win[u][2 * m + 1], win[u][2 * m + 2]) : dw_pair_hi(win[u][2 * m + 1], win[u][2 * m + 2])) : 0u;
+          }
+#pragma unroll
+          for (int v = 0; v < KS; ++v)
+#pragma unroll
+            for (int k = 0; k < DW_TX / 2; ++k) {
+              const int m = 2 * k + v;                 // first window column of the pair (compile time)
+              const uint32_t xp = (m & 1) ? xo[(m - 1) / 2] : xe[m / 2];
+              if (c == 0) s0[u * KS + v] = dw_dot2(gp[k], xp, s0[u * KS + v]);
+              else s1[u * KS + v] = dw_dot2(gp[k], xp, s1[u * KS + v]);
+            }
+        }
+      }
 #pragma unroll
       for (int r = 0; r + 1 < KS; ++r)
 #pragma unroll
