@@ -158,13 +158,24 @@ __device__ __forceinline__ DwStrip dw_strip(int strip, int tiles_x, int chunks, 
 
 // one window row of a [B, H, W, C2] tensor of channel pairs: columns x0 - PAD .. x0 + DW_TX + PAD - 1 of row yy,
 // addresses clamped into the map (values outside are never used)
+// (the element offsets of the window's columns inside a row are the same for every row of a strip: computed once,
+// wave-uniform, so that a row costs one 64-bit row address and an add per column instead of a clamp and a 64-bit
+// multiply per column - with one or two wavefronts per SIMD every scalar instruction takes an issue slot too)
 template <int KS>
-__device__ __forceinline__ void dw_load_row(const uint32_t* __restrict__ src, int b, int yy, int x0, int H, int W, int C2, int cp,
-                                            uint32_t (&dst)[DW_TX + KS - 1]) {
-  constexpr int PAD = KS / 2, WIN = DW_TX + KS - 1;
-  const long long prow = ((long long)b * H + min(max(yy, 0), H - 1)) * W;
+struct DwCols {
+  int off[DW_TX + KS - 1];
+  __device__ __forceinline__ void init(int x0, int W, int C2) {
 #pragma unroll
-  for (int col = 0; col < WIN; ++col) dst[col] = src[(prow + min(max(x0 + col - PAD, 0), W - 1)) * C2 + cp];
+    for (int col = 0; col < DW_TX + KS - 1; ++col) off[col] = min(max(x0 + col - KS / 2, 0), W - 1) * C2;
+  }
+};
+template <int KS>
+__device__ __forceinline__ void dw_load_row(const uint32_t* __restrict__ src, int b, int yy, const DwCols<KS>& cols, int H, int W,
+                                            int C2, int cp, uint32_t (&dst)[DW_TX + KS - 1]) {
+  constexpr int WIN = DW_TX + KS - 1;
+  const uint32_t* rowp = src + ((long long)b * H + min(max(yy, 0), H - 1)) * W * C2 + cp;
+#pragma unroll
+  for (int col = 0; col < WIN; ++col) dst[col] = rowp[cols.off[col]];
 }
 // dst[col] &= all-ones where bit col of `bits` is set, zero elsewhere (the mask is wave-uniform: scalar operands)
 template <int N>
@@ -226,12 +237,14 @@ __device__ __forceinline__ void dw_dx_strip_body(int strip, const uint32_t* __re
 #pragma unroll
     for (int ox = 0; ox < DW_TX; ++ox) acc[j][ox][0] = acc[j][ox][1] = 0.f;
   uint32_t raw[WIN], nxt[WIN];
-  dw_load_row<KS>(dY, t.b, t.y0 - PAD, t.x0, H, W, C2, cp, raw);
+  DwCols<KS> cols;
+  cols.init(t.x0, W, C2);
+  dw_load_row<KS>(dY, t.b, t.y0 - PAD, cols, H, W, C2, cp, raw);
   int look = dw_row_lookup<KS>(inv, t.b, t.y0 - PAD, t.x0, H, W);
   for (int yy = t.y0 - PAD; yy < t.y1 + PAD; ++yy) {
     int lookn = -1;
     if (yy + 1 < t.y1 + PAD) {                 // the next gradient row: in flight during this one
-      dw_load_row<KS>(dY, t.b, yy + 1, t.x0, H, W, C2, cp, nxt);
+      dw_load_row<KS>(dY, t.b, yy + 1, cols, H, W, C2, cp, nxt);
       lookn = dw_row_lookup<KS>(inv, t.b, yy + 1, t.x0, H, W);
     }
     dw_mask_words<WIN>(raw, (unsigned)__ballot(look >= 0));    // dropped and outside positions: zero
@@ -311,19 +324,22 @@ __device__ __forceinline__ void dw_dw_strip_body(int blk, int nblk, float* red, 
       if (t.x0 + col - PAD >= 0 && t.x0 + col - PAD < W) colmask |= 1u << col;
     // window rows of X: positions outside the map are zeroed as a row enters the window (zero padding), the
     // gradients of dropped positions are zeroed too, and the row loop has no branches
+    DwCols<KS> cols;
+    cols.init(t.x0, W, C2);
     uint32_t win[KS][WIN], nxt[WIN], g[DW_TX], gn[DW_TX];
 #pragma unroll
     for (int r = 0; r < KS; ++r) {
       const int yy = t.y0 + r - PAD;
-      dw_load_row<KS>(X, t.b, yy, t.x0, H, W, C2, cp, win[r]);
+      dw_load_row<KS>(X, t.b, yy, cols, H, W, C2, cp, win[r]);
       dw_mask_words<WIN>(win[r], (yy >= 0 && yy < H) ? colmask : 0u);
     }
     // gradients of row y and, per lane, the inverse-map entry of position x0 + lane (-1: outside or dropped);
     // the ballot that makes the kept mask is taken when the values are needed, a row later
     auto load_g = [&](int y, uint32_t (&dst)[DW_TX]) -> int {
       const long long prow = ((long long)t.b * H + y) * W;
+      const uint32_t* rowp = dY + prow * C2 + cp;
 #pragma unroll
-      for (int ox = 0; ox < DW_TX; ++ox) dst[ox] = dY[(prow + min(t.x0 + ox, W - 1)) * C2 + cp];
+      for (int ox = 0; ox < DW_TX; ++ox) dst[ox] = rowp[cols.off[ox + PAD]];    // window column ox + PAD is map column x0 + ox
       const int v = inv[prow + min(t.x0 + lane, W - 1)];                 // unconditional: no branch, no wait here
       return (lane < DW_TX && t.x0 + lane < W) ? v : -1;
     };
@@ -332,7 +348,7 @@ __device__ __forceinline__ void dw_dw_strip_body(int blk, int nblk, float* red, 
     for (int y = t.y0; y < t.y1; ++y) {
       int lookn = -1;
       if (y + 1 < t.y1) {
-        dw_load_row<KS>(X, t.b, y + 1 + PAD, t.x0, H, W, C2, cp, nxt);
+        dw_load_row<KS>(X, t.b, y + 1 + PAD, cols, H, W, C2, cp, nxt);
         lookn = load_g(y + 1, gn);
       }
       // pairs along x of one channel: gradients (g[2k], g[2k+1]) against window pairs (x[2k+v], x[2k+v+1]); one
