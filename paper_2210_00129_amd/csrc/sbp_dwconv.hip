@@ -173,9 +173,12 @@ template <int KS>
 __device__ __forceinline__ void dw_load_row(const uint32_t* __restrict__ src, int b, int yy, const DwCols<KS>& cols, int H, int W,
                                             int C2, int cp, uint32_t (&dst)[DW_TX + KS - 1]) {
   constexpr int WIN = DW_TX + KS - 1;
-  const uint32_t* rowp = src + ((long long)b * H + min(max(yy, 0), H - 1)) * W * C2 + cp;
+  // wave-uniform column address + the lane's channel pair as an unsigned 32-bit offset: scalar base and vector offset
+  // of one load instruction, no 64-bit vector arithmetic
+  const uint32_t* rowp = src + ((long long)b * H + min(max(yy, 0), H - 1)) * W * C2;
+  const uint32_t lane_off = (uint32_t)cp;
 #pragma unroll
-  for (int col = 0; col < WIN; ++col) dst[col] = rowp[cols.off[col]];
+  for (int col = 0; col < WIN; ++col) dst[col] = (rowp + cols.off[col])[lane_off];
 }
 // dst[col] &= all-ones where bit col of `bits` is set, zero elsewhere (the mask is wave-uniform: scalar operands)
 template <int N>
@@ -337,9 +340,9 @@ __device__ __forceinline__ void dw_dw_strip_body(int blk, int nblk, float* red, 
     // the ballot that makes the kept mask is taken when the values are needed, a row later
     auto load_g = [&](int y, uint32_t (&dst)[DW_TX]) -> int {
       const long long prow = ((long long)t.b * H + y) * W;
-      const uint32_t* rowp = dY + prow * C2 + cp;
+      const uint32_t* rowp = dY + prow * C2;
 #pragma unroll
-      for (int ox = 0; ox < DW_TX; ++ox) dst[ox] = rowp[cols.off[ox + PAD]];    // window column ox + PAD is map column x0 + ox
+      for (int ox = 0; ox < DW_TX; ++ox) dst[ox] = (rowp + cols.off[ox + PAD])[(uint32_t)cp];   // window column ox + PAD is map column x0 + ox
       const int v = inv[prow + min(t.x0 + lane, W - 1)];                 // unconditional: no branch, no wait here
       return (lane < DW_TX && t.x0 + lane < W) ? v : -1;
     };
