@@ -190,7 +190,9 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
   const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
   if (kind == 0) {
     const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-    if (a.dx_bm == 128)
+    if (a.dx_bm == 64)
+      big::dx_tile<64>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 64, tile_n * big::BT);
+    else if (a.dx_bm == 128)
       big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT);
     else
       big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT);
@@ -462,6 +464,7 @@ static constexpr int kBigMaxRowsPerSplit = 4096;   // row ids of a split in LDS 
 // dW unit stores 256 KB of partial sums).
 static constexpr int64_t kNsStage256 = 750, kNsFixedDx256 = 6500;     // 256 x 256 dX tile
 static constexpr int64_t kNsStage128 = 450, kNsFixedDx128 = 8000;     // 128 x 256 dX tile
+static constexpr int64_t kNsStage64 = 365, kNsFixedDx64 = 8000;       // 64 x 256 dX tile
 static constexpr int64_t kNsStageDw = 667, kNsFixedDw = 10000;        // 256 x 256 dW unit
 static constexpr int64_t kNsFixedHelper = 1800;                       // zero-fill and column-sum blocks: fixed part
 static constexpr int64_t kHelperBytesPerNs = 50;                      //   and the rate at which one CU streams
@@ -523,9 +526,10 @@ static BigChoice choose_big(int64_t M, int64_t K, int32_t Cin, int32_t Cout) {
   double best_cost = 0;
   auto l_dw = [](int64_t rows) { return kNsFixedDw + kNsStageDw * ceil_div(rows, big::KB); };
   static const int small_rows[] = {0, 256, 384, 512, 768, 1024, 1536};
-  for (int bm : {256, 128}) {
+  for (int bm : {256, 128, 64}) {
     const int64_t n_dx = ceil_div(K, bm) * tiles_n;
-    const int64_t l_dx = bm == 256 ? kNsFixedDx256 + kNsStage256 * nk_x : kNsFixedDx128 + kNsStage128 * nk_x;
+    const int64_t l_dx = bm == 256 ? kNsFixedDx256 + kNsStage256 * nk_x
+                                   : (bm == 128 ? kNsFixedDx128 + kNsStage128 * nk_x : kNsFixedDx64 + kNsStage64 * nk_x);
     for (int64_t a : small_rows) {
       for (int64_t ns = (a ? 1 : 0); ns <= (a ? 4 : 0); ++ns) {
         if (ns * a >= K) break;
@@ -596,7 +600,7 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
     p.rows_per_split = c.rps; p.n_big = c.n_big; p.rows_small = c.rows_small;
     for (int q = 0; q < 3; ++q) p.seg_order[q] = c.seg_order[q];
     two_sizes = true;
-    if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : 256;   // debugging aids
+    if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : (std::atoi(e) == 64 ? 64 : 256);   // debugging aids
     char plan_var[48];
     std::snprintf(plan_var, sizeof plan_var, "SBP_PLAN_%dx%d", Cin, Cout);   // a schedule by hand for one layer shape ...
     const char* plan_env = std::getenv(plan_var);
@@ -605,7 +609,7 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
       int bm = 256, A = 0, nb = 1, a = 0;
       if (std::sscanf(e, "%d,%d,%d,%d", &bm, &A, &nb, &a) == 4 && A >= 64 && A % 64 == 0 && A <= kBigMaxRowsPerSplit &&
           nb >= 1 && a % 64 == 0 && a >= 0 && a <= A && (int64_t)nb * A < K + A && (a > 0 || (int64_t)nb * A >= K)) {
-        p.dx_bm = bm == 128 ? 128 : 256;
+        p.dx_bm = bm == 128 ? 128 : (bm == 64 ? 64 : 256);
         p.rows_per_split = A; p.n_big = (int)std::min<int64_t>(nb, ceil_div(K, A)); p.rows_small = a;
         const int64_t rest = K - std::min<int64_t>(K, (int64_t)p.n_big * A);
         if (rest <= 0) p.rows_small = 0;

@@ -34,7 +34,7 @@ static constexpr int KB = 32;                   // contraction elements per stag
 static constexpr int NS = 4;                    // ring depth
 static constexpr int TILE_BYTES = BT * KB * 2;  // a 256-wide operand tile of a stage
 static constexpr int RING = NS * 2 * TILE_BYTES;   // the largest ring (two 256-wide operands): 128 KB
-// A tile is BMX x 256 with BMX = 256 (dW, dX) or 128 (dX where too few 256-row tiles exist to fill the
+// A tile is BMX x 256 with BMX = 256 (dW, dX), 128 or 64 (dX where too few taller tiles exist to fill the
 // chip): FM = BMX / 64 accumulator block rows per wavefront, FM + 4 copies per wavefront and stage.
 
 template <int CPS>
@@ -152,7 +152,8 @@ __device__ __forceinline__ void step_slots() {
 }
 template <int NM, int NREAD, int NCOPY>
 __device__ __forceinline__ void interleave_step() {
-  step_slots<NM, NREAD, NCOPY, 0>();
+  // (a step of the 64-row dX tile has 4 MFMAs for 9 reads: no room for this pattern, the compiler's own order stands)
+  if constexpr ((NREAD + 1) / 2 < NM || ((NREAD + 1) / 2 == NM && NCOPY == 0)) step_slots<NM, NREAD, NCOPY, 0>();
 }
 
 // ---- the stage ring ------------------------------------------------------------------------------
@@ -297,18 +298,20 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
   zero_acc<FM, 4>(acc);
   ring_loop(smem, pb, Cout / KB, false, KB, acc);
 
-  // epilogue: round to bf16, stage 128 rows at a time through LDS, write whole 16-byte pieces of the
+  // epilogue: round to bf16, stage up to 128 rows at a time through LDS, write whole 16-byte pieces of the
   // (scattered) rows.  Register v of lane l of block (i, j) is
   // C[row wm + 32 i + (l & 31)][column wn + 32 j + 8 (v >> 2) + 4 (l >> 5) + (v & 3)].
   constexpr int PITCH = BT * 2 + 16;
+  constexpr int BPP = FM >= 2 ? 2 : 1;             // accumulator block rows per wavefront and pass
+  constexpr int HALF = 32 * BPP;                   // staged rows per half (wavefront row) and pass
   const int pc = t & 31, pr = t >> 5;
   const bool col_ok = n0 + 8 * pc < Cin;
 #pragma unroll
-  for (int pass = 0; pass < FM / 2; ++pass) {
+  for (int pass = 0; pass < FM / BPP; ++pass) {
 #pragma unroll
-    for (int ii = 0; ii < 2; ++ii) {
-      const int i = 2 * pass + ii;
-      char* row = smem + ((wave >> 1) * 64 + ii * 32 + (lane & 31)) * PITCH + (wn + 4 * (lane >> 5)) * 2;
+    for (int ii = 0; ii < BPP; ++ii) {
+      const int i = BPP * pass + ii;
+      char* row = smem + ((wave >> 1) * HALF + ii * 32 + (lane & 31)) * PITCH + (wn + 4 * (lane >> 5)) * 2;
 #pragma unroll
       for (int jn = 0; jn < 4; ++jn)
 #pragma unroll
@@ -321,9 +324,9 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
     }
     __syncthreads();
 #pragma unroll
-    for (int p = 0; p < 16; ++p) {
-      const int r = pr + 8 * p;                   // staged row: half (r >> 6), block (r >> 5) & 1, row (r & 31)
-      const int o = orow[(r >> 6) * (BMX / 2) + 32 * (2 * pass + ((r >> 5) & 1)) + (r & 31)];
+    for (int p = 0; p < 2 * HALF / 8; ++p) {
+      const int r = pr + 8 * p;                   // staged row: half r / HALF, block (r % HALF) / 32, row r & 31
+      const int o = orow[(r / HALF) * (BMX / 2) + 32 * (BPP * pass + (r % HALF) / 32) + (r & 31)];
       if (o >= 0 && col_ok)
         *reinterpret_cast<uint4*>(dX + (long long)o * Cin + n0 + 8 * pc) =
             *reinterpret_cast<const uint4*>(smem + r * PITCH + pc * 16);

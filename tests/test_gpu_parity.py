@@ -169,7 +169,7 @@ class _env:
                 os.environ[k] = v
 
 
-@pytest.mark.parametrize("dx_rows", [256, 128])
+@pytest.mark.parametrize("dx_rows", [256, 128, 64])
 @pytest.mark.parametrize("k", [1, 2, 3, 4])
 @pytest.mark.parametrize("shape", [(192, 768), (768, 192), (512, 128), (72, 224), (8, 32), (264, 160)])
 def test_linear_large_tile_engine_forced_on_ragged_shapes(shape, k, dx_rows):
@@ -200,6 +200,8 @@ def test_linear_large_tile_engine_short_contractions(K):
     with _env(SBP_TILE="big"):
         check_linear(X, W, dY, idx, "bf16")
     with _env(SBP_TILE="big", SBP_DXBM=128):
+        check_linear(X, W, dY, idx, "bf16")
+    with _env(SBP_TILE="big", SBP_DXBM=64):
         check_linear(X, W, dY, idx, "bf16")
 
 
@@ -236,7 +238,7 @@ def test_linear_engines_agree_bit_for_bit_on_integers():
     outs = []
     for env in (dict(SBP_TILE="128x128x4x64"), dict(SBP_TILE="128x128x4x64", SBP_DXROWS=64),
                 dict(SBP_TILE="big", SBP_DXBM=256, SBP_SPLITS=1),
-                dict(SBP_TILE="big", SBP_DXBM=128, SBP_SPLITS=4)):
+                dict(SBP_TILE="big", SBP_DXBM=128, SBP_SPLITS=4), dict(SBP_TILE="big", SBP_DXBM=64, SBP_SPLITS=2)):
         with _env(**env):
             outs.append([bits(t) if t.dtype == torch.bfloat16 else f64(t) for t in sbp.backward_linear(dY.cuda(), idx, Xk, Wt.cuda())])
     for o in outs[1:]:
