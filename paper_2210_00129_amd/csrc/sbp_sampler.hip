@@ -447,14 +447,22 @@ __global__ void __launch_bounds__(256) sample_cells_kernel(CellGeom g, int32_t* 
     // p = floor(h * n! / 2^64); factorial-base digits most significant first
     uint64_t fact = 1;
     for (int i = 2; i <= n; ++i) fact *= (uint64_t)i;
-    uint64_t p = __umul64hi(h, fact);
+    const uint64_t p = __umul64hi(h, fact);
+    // The factorial-base digits of p, least significant first: the digit of weight (i - 1)! is the remainder of
+    // the i-th division by i.  The divisors are compile-time constants here (multiply-and-shift code), where taking
+    // the digits from the top costs two 64-bit divisions by run-time values per digit.  Four bits per digit.
+    uint64_t q = p, digits = 0;
+#pragma unroll
+    for (int i = 2; i <= 16; ++i)
+      if (i <= n) {
+        const uint64_t qq = q / (uint64_t)i;
+        digits |= (q - qq * (uint64_t)i) << (4 * (i - 1));
+        q = qq;
+      }
     uint32_t freem = (1u << n) - 1u, keepm = 0;
     int taken = 0;
-    uint64_t f = fact;
     for (int r = 0; r < n && taken < kc; ++r) {       // slots by increasing rank, until kc valid ones are kept
-      f /= (uint64_t)(n - r);                          // (n - 1 - r)!
-      const uint32_t d = (uint32_t)(p / f);
-      p -= (uint64_t)d * f;
+      const uint32_t d = (uint32_t)(digits >> (4 * (n - 1 - r))) & 15u;   // digit of weight (n - 1 - r)!
       uint32_t m = freem;                              // the d-th set bit of freem
       for (uint32_t q = 0; q < d; ++q) m &= m - 1u;
       const uint32_t slot = (uint32_t)__ffs((int)m) - 1u;
