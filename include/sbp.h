@@ -115,7 +115,8 @@ int32_t sbp_sample_indices(const sbp_sample_desc* desc, int32_t* idx, int64_t id
                            int32_t* inv, void* stream);
 
 /*
- * Step "forward cache" (paper: SBP "only caches a subset of the feature maps"):
+ * Step "forward cache" (paper, section "Calculation of Linear Layers": of the layer input only the kept
+ * rows are retained for the backward pass):
  * X_k[j, :] = X[idx[j], :] for j in [0, K).
  *   X      device, in,  [M, C] of `dtype`
  *   idx    device, in,  [K] row ids in [0, M), unique (caller's contract; any unique list is legal)
@@ -151,9 +152,11 @@ int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Co
  * The result is deterministic (no floating-point atomics).
  *   dY     device, in,  [M, Cout] (only rows in idx are read) or [K, Cout] with SBP_FLAG_DY_COMPACT
  *   idx    device, in,  [K] unique row ids in [0, M)
- *   inv    device, in,  [M] inverse of idx as written by sbp_sample_indices (inv[idx[j]] = j; other
- *                       entries may hold anything that is not a position of that row), or NULL: then it
- *                       is built in the workspace by one more small kernel.  Only used to zero-fill dX.
+ *   inv    device, in,  [M] inverse map of idx, or NULL: then it is built in the workspace by one more
+ *                       small kernel.  Only used to zero-fill dX.  ONE contract for every call of this
+ *                       library that takes an inverse map (this one, sbp_backward_dwconv,
+ *                       sbp_backward_layernorm, sbp_scatter_patches): inv[idx[j]] = j for the kept rows
+ *                       and -1 for every dropped row, i.e. what sbp_sample_indices writes.
  *   X_k    device, in,  [K, Cin] rows cached by sbp_forward_cache (may be NULL if dW is NULL)
  *   W      device, in,  [Cout, Cin]                       (may be NULL if dX is NULL)
  *   dW, db, dX   device, out; each may be NULL to skip that output.  dW is fp32, or bf16 with
@@ -185,8 +188,10 @@ size_t sbp_backward_dwconv_workspace(int32_t B, int32_t H, int32_t W, int32_t C,
  *   dX[b,y,x,c]= sum_{u,v} [ (b,y-u+pad,x-v+pad) kept ] dY[..] * Wd[u,v,c]    `dtype`, dense
  *   dY   device, in, [B,H,W,C]; only kept positions are read
  *   idx  device, in, [K] kept flat positions b*H*W + y*W + x, unique
- *   inv  device, in, [B*H*W] inverse of idx (-1 = dropped) or NULL (then built in the workspace)
- *   X    device, in, [B,H,W,C] FULL input of the layer (a k>1 conv needs the neighbours)
+ *   inv  device, in, [B*H*W] inverse map of idx (position in idx, -1 = dropped: the contract stated at
+ *        sbp_backward_linear) or NULL (then built in the workspace)
+ *   X    device, in, [B,H,W,C] FULL input of the layer (a k>1 conv needs the neighbours); required
+ *        whenever dWd or db is requested (SBP_ERR_NULL otherwise)
  *   Wd   device, in, [ks,ks,C]
  *   dWd, db, dX  device, out; each may be NULL
  * ks must be odd and <= 7, pad = ks/2.

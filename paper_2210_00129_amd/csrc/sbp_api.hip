@@ -347,7 +347,7 @@ int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* i
   if (!dY) return fail(SBP_ERR_NULL, "dY is NULL");
   if ((dWd || db) && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL but dWd / db is requested");
   if (dX && !idx && !inv && K > 0) return fail(SBP_ERR_NULL, "idx and inv are both NULL");
-  if (dWd && !X) return fail(SBP_ERR_NULL, "X is NULL but dWd is requested");
+  if ((dWd || db) && !X) return fail(SBP_ERR_NULL, "X is NULL but dWd / db is requested");
   if (dX && !Wd) return fail(SBP_ERR_NULL, "Wd is NULL but dX is requested");
   DwPlan p = plan_dwconv(B, H, W, C, ks, K, dtype);
   if (!ws) return fail(SBP_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", p.bytes);

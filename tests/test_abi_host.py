@@ -274,6 +274,7 @@ def test_backward_dwconv_argument_errors():
     assert call(dY=None) == -1
     assert call(idx=None) == -1
     assert call(X=None) == -1
+    assert call(X=None, dWd=None) == -1                 # db alone also reads X's positions: rejected on the host
     assert call(Wd=None) == -1
     assert call(ks=4) == -2
     assert call(ks=9, pad=4) == -2

@@ -304,6 +304,17 @@ def test_linear_convnext_detection_full_size(geom):
     check_linear(X, Wt, dY, idx, "bf16", check_cache=False)
 
 
+@pytest.mark.parametrize("k", [1, 2, 4])
+@pytest.mark.parametrize("shape", [(512, 2048), (2048, 512)])
+def test_linear_convnext_stage3_pointwise_full_size(shape, k):
+    # the two pointwise convs of the stage-3 block: B = 2, 50 x 84 map, 512 -> 2048 -> 512, r = 0.25 / 0.5 / 1
+    # (eq:backward_fc_sbp), with whatever engine and splits the library picks for these sizes
+    Cin, Cout = shape
+    X, Wt, dY, idx = _grid_case(2, 0, 50, 84, Cin, Cout, k, "bf16", 70 + k)
+    assert idx.size == {1: 2100, 2: 4200, 4: 8400}[k]
+    check_linear(X, Wt, dY, idx, "bf16", check_cache=(k == 2))
+
+
 def test_linear_integer_inputs_are_bit_exact():
     # small integers: every product and partial sum is exact in fp32, so any summation order must
     # reproduce the oracle bit for bit, and the kept / dropped halves must add up to full backprop
@@ -426,6 +437,39 @@ def test_two_layer_chain_same_mask_compact():
     assert nerr(f64(dX0), rX0) <= TOL_BF16_TIGHT
     dropped = np.setdiff1d(np.arange(M), idx)
     assert np.all(bits(dX0)[dropped] == 0)
+
+
+def test_two_layer_chain_different_masks_is_the_intersection():
+    # eq:keep_indices_intersect / eq:backward_fc2_sbp_different_drop_loc: layer 2 (later in the forward) drops with
+    # mask Z2 and hands a full-size, zero-filled gradient to layer 1, which drops with its own mask Z1.  Layer 1's
+    # weight gradient and input gradient then come from the rows in both sets only: one oracle run on the
+    # intersection, fed with the exact gradient rows, must agree.
+    B, P, H, W, C0, C1, C2 = 6, 1, 14, 14, 128, 256, 192
+    M = B * (P + H * W)
+    X0, W0, _ = si.linear_case(M, C0, C1, 201, "bf16")
+    X1, W1, dY2 = si.linear_case(M, C1, C2, 202, "bf16")
+    z1 = oracle.sample_indices(B, P, H, W, 2, 5, 11)
+    z2 = oracle.sample_indices(B, P, H, W, 3, 5, 12)
+    both = np.intersect1d(z1, z2).astype(np.int32)
+    assert 0 < both.size < min(z1.size, z2.size)
+    z1d, z2d = torch.from_numpy(z1).cuda(), torch.from_numpy(z2).cuda()
+    X0k, X1k = sbp.forward_cache(X0.cuda(), z1d), sbp.forward_cache(X1.cuda(), z2d)
+    _, _, g = sbp.backward_linear(dY2.cuda(), z2d, X1k, W1.cuda())            # [M, C1], zero off Z2
+    dW0, db0, dX0 = sbp.backward_linear(g, z1d, X0k, W0.cuda())                 # Z1 applied to that gradient
+    torch.cuda.synchronize()
+    # oracle: layer 2 on Z2 (exact rows), then layer 1 on the intersection alone
+    _, _, rg = oracle.backward_linear(si.to_f64(dY2), z2, si.to_f64(X1)[z2], si.to_f64(W1), M)
+    assert nerr(f64(g), rg) <= TOL_BF16_TIGHT
+    g_gpu = f64(g)                                                           # the rounded gradient layer 1 really saw
+    rW0, rb0, rX0 = oracle.backward_linear(g_gpu, both, si.to_f64(X0)[both], si.to_f64(W0), M)
+    assert nerr(f64(dW0), rW0) <= TOL_F32 and nerr(f64(db0), rb0) <= TOL_F32
+    assert nerr(f64(dX0), rX0) <= TOL_BF16_TIGHT
+    off = np.setdiff1d(np.arange(M), both)
+    assert np.all(f64(dX0)[off] == 0), "rows outside the intersection carry no gradient"
+    assert np.all(bits(dX0)[np.setdiff1d(np.arange(M), z1)] == 0)
+    # and against the oracle's own two-mask chain from the unrounded gradient (bf16 bar: g was rounded once)
+    qW0, _, qX0 = oracle.backward_linear(rg, z1, si.to_f64(X0)[z1], si.to_f64(W0), M)
+    assert nerr(f64(dW0), qW0) <= TOL_BF16_TIGHT and nerr(f64(dX0), qX0) <= 2 * TOL_BF16_TIGHT
 
 
 # ------------------------------------------------------------------ depthwise backward

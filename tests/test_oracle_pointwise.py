@@ -1,6 +1,6 @@
 """Pins of the oracle's row-wise steps (GELU, LayerNorm on the kept rows): closed forms, finite
 differences of the forward definitions, and reverse-mode differentiation by torch (CPU, fp64) of the
-paper's own wrapper (Alg. alg:sbp_impl: kept rows through f with gradient, dropped rows without) -- none
+effect of the paper's wrapper (Alg. alg:sbp_impl: gradient flows through the kept rows of f only) -- none
 of which share a formula with the oracle's backward code."""
 import math
 
@@ -12,13 +12,14 @@ import oracle
 
 
 def _sbp_f(f, inputs, keep, drop, out_cols):
-    # the wrapper of Alg. alg:sbp_impl, written from its description
-    outputs = torch.zeros((inputs.shape[0], out_cols), dtype=inputs.dtype)
-    with torch.enable_grad():
-        outputs[keep] = f(inputs[keep])
-    with torch.no_grad():
-        outputs[drop] = f(inputs[drop])
-    return outputs
+    # What Alg. alg:sbp_impl achieves, expressed differently: the full forward result everywhere, with the
+    # gradient path cut under the dropped rows (a row mask picks between f(x) and its detached copy).
+    full = f(inputs)
+    assert full.shape[1] == out_cols
+    kept = torch.zeros(inputs.shape[0], dtype=torch.bool)
+    kept[keep] = True
+    assert not kept[drop].any()
+    return torch.where(kept[:, None], full, full.detach())
 
 
 def _case(M, C, K, seed):
