@@ -325,6 +325,26 @@ int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* g
                                void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
 /*
+ * Explicit overrides for tests and parameter sweeps (not a step of the method).  The library reads no
+ * environment variable; by default every choice below is automatic.  name = NULL restores all defaults;
+ * value = NULL clears one override.  Process-wide, thread-safe (calls in flight use the snapshot they took);
+ * results never depend on these beyond the summation order of dW / db.  Returns SBP_ERR_FLAGS for an unknown
+ * name or a value that is not valid for it (nothing changes then).
+ *   "tile"      "big" (large-tile engine wherever its limits allow) | "128x128x4x64" | "128x128x4x32" |
+ *               "256x256x8x64" | "256x256x8x32" | "256x256x4x64" | "256x256x4x32" (general engine: rows x
+ *               columns x wavefronts x stage length)
+ *   "dxbm"      64 | 128 | 256: rows of a dX tile of the large-tile engine;  "dxrows"  64 | 128: general engine
+ *   "splits"    number of equal dW splits of the large-tile engine
+ *   "plan", "plan_<Cin>x<Cout>"   "bm,rows_long,n_long,rows_short": a whole schedule of the large-tile engine
+ *               for every shape / one shape (ignored where it does not fit the kept-row count)
+ *   "order"     "a,b,c", a permutation of 0,1,2: dispatch order of the kinds of workgroups
+ *   "dw_rows"   rows per strip of the depthwise kernels;  "dw_separate"  "1": dX and dWd as two launches
+ *   "attn"      "plain": attention backward without the matrix cores
+ *   "sampler_no_window", "sampler_no_masks", "patch_wide", "debug_plan"   "1" | "0"
+ */
+int32_t sbp_set_option(const char* name, const char* value);
+
+/*
  * Measurement aid (not a step of the method; for benchmarks only).  While enabled, every kernel
  * launch of the library is bracketed by a pair of HIP events on the caller's stream; this is the
  * one place where the library creates HIP objects (the events, destroyed again by the read call).

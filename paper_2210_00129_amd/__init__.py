@@ -280,6 +280,27 @@ def backward_attention(qkv_k, A_k, dA_k, lse_k, B, h, d, scale, out=None):
     return out
 
 
+def set_option(name=None, value=None) -> None:
+    """Explicit override for tests and sweeps (see sbp_set_option in include/sbp.h); name=None restores the defaults."""
+    _lib.check(_lib.lib().sbp_set_option(None if name is None else str(name).encode(),
+                                         None if value is None else str(value).encode()))
+
+
+class options:
+    """Context manager: sets overrides for the duration of a block, then restores the defaults for those names."""
+    def __init__(self, **kv):
+        self.kv = kv
+
+    def __enter__(self):
+        for k, v in self.kv.items():
+            set_option(k, v)
+        return self
+
+    def __exit__(self, *exc):
+        for k in self.kv:
+            set_option(k, None)
+
+
 PROF_CLASSES = ("sample", "gather", "dw_gemm", "dx_gemm", "reduce", "colsum", "zero_rows", "dwconv_dx",
                 "dwconv_dw", "other", "attention")
 

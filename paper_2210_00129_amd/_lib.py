@@ -48,6 +48,7 @@ PROTOTYPES = {
     "sbp_backward_dwconv_workspace": (c_sz, [c_i32, c_i32, c_i32, c_i32, c_i32, c_i64, c_i32, c_u32]),
     "sbp_backward_dwconv": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32,
                                     c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),
+    "sbp_set_option": (c_i32, [ctypes.c_char_p, ctypes.c_char_p]),
     "sbp_profile_enable": (c_i32, [c_i32]),
     "sbp_profile_read": (c_i32, [c_i32, ctypes.POINTER(c_dbl), ctypes.POINTER(c_i64)]),
 }

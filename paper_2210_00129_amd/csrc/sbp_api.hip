@@ -2,8 +2,12 @@
 // before the first HIP call so that error paths need no device.
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
 #include <cmath>
+#include <mutex>
 #include <vector>
+
+#include <string>
 
 #include "sbp_internal.h"
 
@@ -23,6 +27,81 @@ int32_t check_launch(const char* what) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(SBP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
   return SBP_OK;
+}
+
+// ---- explicit overrides -------------------------------------------------------------------------
+static std::mutex g_opt_mutex;
+static Options g_opt;
+Options options() {
+  std::lock_guard<std::mutex> lock(g_opt_mutex);
+  return g_opt;
+}
+
+static bool parse_flag(const char* v, bool* out) {
+  if (!v || !std::strcmp(v, "0") || !std::strcmp(v, "")) { *out = false; return true; }
+  if (!std::strcmp(v, "1")) { *out = true; return true; }
+  return false;
+}
+
+// Applies one override to `o`; false if the name is unknown or the value is not valid for it.
+static bool apply_option(Options& o, const char* name, const char* v) {
+  const std::string n(name);
+  if (n == "tile") {
+    if (!v) { o.tile_mode = 0; return true; }
+    if (!std::strcmp(v, "big")) { o.tile_mode = 2; return true; }
+    int a = 0, b = 0, w = 4, k = 64;
+    if (std::sscanf(v, "%dx%dx%dx%d", &a, &b, &w, &k) < 2) return false;
+    const bool ok = ((a == 256 && b == 256 && (w == 8 || w == 4)) || (a == 128 && b == 128 && w == 4)) && (k == 32 || k == 64);
+    if (!ok) return false;
+    o.tile_mode = 1; o.tile_bm = a; o.tile_bn = b; o.tile_nw = w; o.tile_kb = k;
+    return true;
+  }
+  if (n == "dxbm" || n == "dxrows" || n == "splits" || n == "dw_rows") {
+    int x = v ? std::atoi(v) : 0;
+    if (v && x <= 0) return false;
+    if (n == "dxbm") { if (x && x != 64 && x != 128 && x != 256) return false; o.dxbm = x; }
+    else if (n == "dxrows") { if (x && x != 64 && x != 128) return false; o.dxrows = x; }
+    else if (n == "splits") { if (x > 4096) return false; o.splits = x; }
+    else { if (x > 4096) return false; o.dw_rows = x; }
+    return true;
+  }
+  if (n == "order") {
+    if (!v) { o.order_set = false; return true; }
+    int q[3];
+    if (std::sscanf(v, "%d,%d,%d", &q[0], &q[1], &q[2]) != 3) return false;
+    for (int i = 0; i < 3; ++i) if ((unsigned)q[i] > 2u) return false;
+    if ((1 << q[0] | 1 << q[1] | 1 << q[2]) != 7) return false;          // a permutation of 0, 1, 2
+    o.order_set = true;
+    for (int i = 0; i < 3; ++i) o.order[i] = q[i];
+    return true;
+  }
+  if (n.rfind("plan", 0) == 0) {                                        // "plan" or "plan_<Cin>x<Cout>"
+    int cin = 0, cout = 0;
+    if (n != "plan" && (std::sscanf(name, "plan_%dx%d", &cin, &cout) != 2 || cin < 1 || cout < 1)) return false;
+    int slot = -1;
+    for (int i = 0; i < o.nplans; ++i) if (o.plans[i].cin == cin && o.plans[i].cout == cout) slot = i;
+    if (!v) {
+      if (slot >= 0) o.plans[slot] = o.plans[--o.nplans];
+      return true;
+    }
+    int bm = 0, A = 0, nb = 0, a = 0;
+    if (std::sscanf(v, "%d,%d,%d,%d", &bm, &A, &nb, &a) != 4) return false;
+    if ((bm != 64 && bm != 128 && bm != 256) || A < 64 || A % 64 || nb < 1 || a < 0 || a % 64 || a > A) return false;
+    if (slot < 0) { if (o.nplans == 8) return false; slot = o.nplans++; }
+    o.plans[slot] = ShapePlan{cin, cout, bm, A, nb, a};
+    return true;
+  }
+  if (n == "attn") {
+    if (!v) { o.attn_plain = false; return true; }
+    if (std::strcmp(v, "plain")) return false;
+    o.attn_plain = true;
+    return true;
+  }
+  bool* flag = n == "debug_plan" ? &o.debug_plan : n == "dw_separate" ? &o.dw_separate
+             : n == "sampler_no_window" ? &o.sampler_no_window : n == "sampler_no_masks" ? &o.sampler_no_masks
+             : n == "patch_wide" ? &o.patch_wide : nullptr;
+  if (!flag) return false;
+  return parse_flag(v, flag);
 }
 
 // ---- measurement aid --------------------------------------------------------------------------
@@ -139,6 +218,25 @@ static int32_t validate_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, 
   return SBP_OK;
 }
 
+}  // extern "C"
+
+namespace sbp {
+// Host-side argument checks shared by the entry points of the linear backward (sizes, flags, required pointers).
+int32_t check_linear_args(const void* dY, const int32_t* idx, const void* Xk, const void* W, int64_t M, int64_t K,
+                          int32_t Cin, int32_t Cout, int32_t dtype, const void* dW, const void* dX, uint32_t flags) {
+  int32_t st = validate_linear(M, K, Cin, Cout, dtype, flags);
+  if (st != SBP_OK) return st;
+  if (!dY) return fail(SBP_ERR_NULL, "dY is NULL");
+  bool need_idx = !((flags & SBP_FLAG_DY_COMPACT) && ((flags & SBP_FLAG_DX_COMPACT) || !dX));
+  if (need_idx && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL");
+  if (dW && !Xk && K > 0) return fail(SBP_ERR_NULL, "X_k is NULL but dW is requested");
+  if (dX && !W) return fail(SBP_ERR_NULL, "W is NULL but dX is requested");
+  return SBP_OK;
+}
+}  // namespace sbp
+
+extern "C" {
+
 size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
                                      uint32_t flags) {
   if (validate_linear(M, K, Cin, Cout, dtype, flags) != SBP_OK) return 0;
@@ -157,13 +255,8 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
                             int64_t M,
                             int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, void* dW, float* db,
                             void* dX, void* ws, size_t ws_bytes, uint32_t flags, void* stream) {
-  int32_t st = validate_linear(M, K, Cin, Cout, dtype, flags);
+  int32_t st = check_linear_args(dY, idx, Xk, W, M, K, Cin, Cout, dtype, dW, dX, flags);
   if (st != SBP_OK) return st;
-  if (!dY) return fail(SBP_ERR_NULL, "dY is NULL");
-  bool need_idx = !((flags & SBP_FLAG_DY_COMPACT) && ((flags & SBP_FLAG_DX_COMPACT) || !dX));
-  if (need_idx && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL");
-  if (dW && !Xk && K > 0) return fail(SBP_ERR_NULL, "X_k is NULL but dW is requested");
-  if (dX && !W) return fail(SBP_ERR_NULL, "W is NULL but dX is requested");
   LinearPlan p = plan_linear(M, K, Cin, Cout, dtype, flags);
   if (p.bytes) {
     if (!ws) return fail(SBP_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", p.bytes);
@@ -356,6 +449,19 @@ int32_t sbp_backward_dwconv(const void* dY, const int32_t* idx, const int32_t* i
   if (!dWd && !db && !dX) return SBP_OK;
   return launch_backward_dwconv(p, dY, idx, inv, X, Wd, B, H, W, C, ks, pad, K, dtype, dWd, db, dX, ws,
                                 (hipStream_t)stream);
+}
+
+int32_t sbp_set_option(const char* name, const char* value) {
+  std::lock_guard<std::mutex> lock(g_opt_mutex);
+  if (!name) {                 // back to the defaults
+    g_opt = Options{};
+    return SBP_OK;
+  }
+  Options o = g_opt;
+  if (!apply_option(o, name, value))
+    return fail(SBP_ERR_FLAGS, "unknown option or invalid value: %s = %s", name, value ? value : "(unset)");
+  g_opt = o;
+  return SBP_OK;
 }
 
 int32_t sbp_profile_enable(int32_t on) {

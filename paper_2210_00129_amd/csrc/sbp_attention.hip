@@ -418,9 +418,7 @@ static size_t attn_lds_bytes(int n_k, int d) {
 int attention_engine(int32_t n_k, int32_t d, int32_t dtype) {
   if (dtype != SBP_BF16) return 0;
   if (d != 32 && d != 64 && d != 128) return 0;
-  if (const char* e = std::getenv("SBP_ATTN")) {            // debugging aid: "plain" forces the plain kernel
-    if (std::strcmp(e, "plain") == 0) return 0;
-  }
+  if (options().attn_plain) return 0;                       // explicit override (sbp_set_option "attn" = "plain")
   return attn_lds_bytes(n_k, d) <= kAttnMaxLds ? 1 : 0;
 }
 

@@ -530,16 +530,16 @@ int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* i
     // rows per strip chunk: a chunk pays for KS - 1 halo rows on top of its own, a short chunk for its start-up;
     // about one workgroup per CU for dX, somewhat more for the weight gradient (measured on the 50 x 84 x 512 map)
     const int64_t row_tiles = (int64_t)tiles_x * B * H * cblocks;
-    const char* env_rows = std::getenv("SBP_DW_ROWS");                         // debugging aid for sweeps
+    const Options opt = options();                                             // explicit overrides for sweeps and tests
     auto pick_rows = [&](int64_t per) {
       int r = (int)std::min<int64_t>(16, std::max<int64_t>(3, ceil_div(row_tiles, per)));
-      if (env_rows) r = std::max(1, std::atoi(env_rows));
+      if (opt.dw_rows) r = opt.dw_rows;
       return std::min(r, H);
     };
     int rows = pick_rows(256);
     int chunks = (int)ceil_div(H, rows);
     int nstrips = tiles_x * chunks * B;
-    if (dX && (dWd || db) && !std::getenv("SBP_DW_SEPARATE")) {   // (debugging aid: the two kernels one after the other)
+    if (dX && (dWd || db) && !opt.dw_separate) {   // (override "dw_separate": the two kernels one after the other)
       // one launch for both; strip heights chosen so that everything finds a CU at once where the map allows
       DwBothArgs a{};
       a.dY = (const uint32_t*)dY; a.inv = inv; a.X = (const uint32_t*)X; a.Wd = (const uint32_t*)Wd;

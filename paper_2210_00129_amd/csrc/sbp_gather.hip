@@ -208,7 +208,7 @@ static void launch_patches_t(bool scatter, const void* src, const int32_t* idx, 
                              PatchGeom g, void* dst, hipStream_t s) {
   const long long total = scatter ? npix * g.seg : K * (long long)g.p * g.p * g.seg;
   const unsigned blocks = (unsigned)std::max<long long>(1, std::min<long long>(ceil_div(total, 256), 256 * 32));
-  if (total < (1ll << 32) && !std::getenv("SBP_PATCH_WIDE")) {   // (debugging aid: the 64-bit kernels on any size)
+  if (total < (1ll << 32) && !options().patch_wide) {   // (override "patch_wide": the 64-bit kernels on any size)
     PatchGeomFast f;
     f.seg = FastDiv((uint32_t)g.seg); f.W = FastDiv((uint32_t)g.W); f.H = FastDiv((uint32_t)g.H); f.p = FastDiv((uint32_t)g.p);
     f.per_row = FastDiv((uint32_t)(g.p * g.p * g.seg)); f.Wo = FastDiv((uint32_t)g.Wo); f.HoWo = FastDiv((uint32_t)(g.Ho * g.Wo));

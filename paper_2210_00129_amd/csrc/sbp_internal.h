@@ -31,6 +31,22 @@ struct ProfScope {
     hipLaunchKernelGGL(__VA_ARGS__);              \
   } while (0)
 
+// ---- explicit overrides (sbp_set_option): for tests and sweeps; defaults = everything automatic -------------
+struct ShapePlan { int cin, cout, bm, rows_long, n_long, rows_short; };   // cin = 0: every shape
+struct Options {
+  int  tile_mode = 0;                 // 0 automatic, 1 a tile shape of the general engine, 2 the large-tile engine
+  int  tile_bm = 128, tile_bn = 128, tile_nw = 4, tile_kb = 64;
+  int  dxbm = 0, splits = 0, dxrows = 0;   // 0 = automatic
+  bool order_set = false;
+  int  order[3] = {0, 1, 2};
+  int  nplans = 0;
+  ShapePlan plans[8] = {};
+  bool debug_plan = false;
+  int  dw_rows = 0;
+  bool dw_separate = false, attn_plain = false, sampler_no_window = false, sampler_no_masks = false, patch_wide = false;
+};
+Options options();                    // a snapshot (taken under a lock; safe against a concurrent sbp_set_option)
+
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -66,6 +82,8 @@ struct LinearPlan {
   size_t off_inv;       // int32 [M]
   size_t bytes;
 };
+int32_t check_linear_args(const void* dY, const int32_t* idx, const void* Xk, const void* W, int64_t M, int64_t K,
+                          int32_t Cin, int32_t Cout, int32_t dtype, const void* dW, const void* dX, uint32_t flags);
 LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags);
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv,
                                const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,

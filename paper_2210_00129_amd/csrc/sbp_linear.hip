@@ -15,6 +15,7 @@
 
 #include <algorithm>
 #include <functional>
+#include <mutex>
 #include <queue>
 #include <string>
 #include <vector>
@@ -440,20 +441,6 @@ __global__ void __launch_bounds__(NTHREADS) plain_db_kernel(const T* __restrict_
 // ------------------------------------------------------------------------------------------------
 static constexpr int kNumCU = 256;
 
-// Debug aid: SBP_TILE = "128x128x4x64" | "128x128x4x32" | "256x256x8x64" | "256x256x8x32" | "256x256x4x64" |
-// "256x256x4x32" forces a tile shape of the general engine (rows x columns x wavefronts x stage length; stage
-// length 32 runs a 4-deep ring, 64 a 2-deep one); "big" forces the large-tile engine (see plan_linear).
-static bool env_tile(const char* name, int* bm, int* bn, int* nw, int* kb) {
-  const char* v = std::getenv(name);
-  if (!v) return false;
-  int a = 0, b = 0, w = 4, k = 64;
-  if (std::sscanf(v, "%dx%dx%dx%d", &a, &b, &w, &k) < 2) return false;
-  const bool ok = ((a == 256 && b == 256 && (w == 8 || w == 4)) || (a == 128 && b == 128 && w == 4)) && (k == 32 || k == 64);
-  if (!ok) return false;
-  *bm = a; *bn = b; *nw = w; *kb = k;
-  return true;
-}
-
 // ---- large-tile engine: tile height of dX and the dW splits ----------------------------------------
 // Workgroup i of the grid goes to XCD i % 8, every XCD hands its workgroups in order to its 32 CUs, one per CU:
 // list scheduling per XCD.  The host simulates it from unit costs and takes the cheapest schedule.
@@ -564,7 +551,7 @@ static BigChoice choose_big(int64_t M, int64_t K, int32_t Cin, int32_t Cout) {
       }
     }
   }
-  if (std::getenv("SBP_DEBUG_PLAN"))
+  if (options().debug_plan)
     std::fprintf(stderr, "sbp plan M=%lld K=%lld %d->%d: dx rows %d, %d long splits of %d rows, short splits of %d rows (%d splits), order %d%d%d, fill %.2f, cost %.1f us\n",
                  (long long)M, (long long)K, Cin, Cout, best.dx_bm, best.n_big, best.rps, best.rows_small, best.splits, best.seg_order[0],
                  best.seg_order[1], best.seg_order[2], best.fill, best_cost / 1e3);
@@ -580,15 +567,14 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   p.nw_w = 4;
   p.kb = 64;
   int splits = 1;
+  const Options opt = options();   // explicit overrides (sbp_set_option); every field is validated when it is set
   if (K > 0 && p.mfma) {
-    // SBP_TILE=big forces the large-tile engine wherever its limits allow (debugging aid, like the shapes below)
-    const char* env = std::getenv("SBP_TILE");
-    const bool forced = env && std::string(env) == "big";
-    const bool fits = Cout % big::KB == 0 && (uint64_t)M * (uint64_t)std::max(Cin, Cout) * 2u < (1ull << 32);
+    const bool fits = Cout % big::KB == 0 && (uint64_t)M * (uint64_t)std::max(Cin, Cout) * 2u < (1ull << 32) &&
+                      ceil_div(K, kBigMaxRowsPerSplit) <= 64;
     // it pays where whole 256-wide tiles exist and the simulated schedule keeps the CUs reasonably busy
-    const bool pays = !env && Cin >= big::BT && Cout >= big::BT && K >= 1024 &&
+    const bool pays = opt.tile_mode == 0 && Cin >= big::BT && Cout >= big::BT && K >= 1024 &&
                       choose_big(M, K, Cin, Cout).fill >= 0.45;
-    p.big = fits && (forced || pays);
+    p.big = fits && (opt.tile_mode == 2 || pays);
   }
   bool two_sizes = false;
   if (p.big) {
@@ -600,32 +586,40 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
     p.rows_per_split = c.rps; p.n_big = c.n_big; p.rows_small = c.rows_small;
     for (int q = 0; q < 3; ++q) p.seg_order[q] = c.seg_order[q];
     two_sizes = true;
-    if (const char* e = std::getenv("SBP_DXBM")) p.dx_bm = std::atoi(e) == 128 ? 128 : (std::atoi(e) == 64 ? 64 : 256);   // debugging aids
-    char plan_var[48];
-    std::snprintf(plan_var, sizeof plan_var, "SBP_PLAN_%dx%d", Cin, Cout);   // a schedule by hand for one layer shape ...
-    const char* plan_env = std::getenv(plan_var);
-    if (!plan_env) plan_env = std::getenv("SBP_PLAN");                         // ... or for all: "bm,rows_big,n_big,rows_small"
-    if (const char* e = plan_env) {
-      int bm = 256, A = 0, nb = 1, a = 0;
-      if (std::sscanf(e, "%d,%d,%d,%d", &bm, &A, &nb, &a) == 4 && A >= 64 && A % 64 == 0 && A <= kBigMaxRowsPerSplit &&
-          nb >= 1 && a % 64 == 0 && a >= 0 && a <= A && (int64_t)nb * A < K + A && (a > 0 || (int64_t)nb * A >= K)) {
-        p.dx_bm = bm == 128 ? 128 : (bm == 64 ? 64 : 256);
+    if (c.splits == 0) {       // no simulated schedule fits (forced engine on an odd size): equal splits of the largest legal length
+      splits = (int)ceil_div(K, kBigMaxRowsPerSplit);
+      two_sizes = false;
+      p.dx_bm = 256;
+      p.seg_order[0] = 1; p.seg_order[1] = 0; p.seg_order[2] = 2;
+    }
+    if (opt.dxbm) p.dx_bm = opt.dxbm;
+    const ShapePlan* sp = nullptr;                               // a schedule by hand: for this shape, else for all
+    for (int i = 0; i < opt.nplans; ++i)
+      if (opt.plans[i].cin == Cin && opt.plans[i].cout == Cout) sp = &opt.plans[i];
+    if (!sp)
+      for (int i = 0; i < opt.nplans; ++i)
+        if (opt.plans[i].cin == 0) sp = &opt.plans[i];
+    if (sp) {
+      const int A = sp->rows_long, nb = sp->n_long, a = sp->rows_short;
+      if (A <= kBigMaxRowsPerSplit && (int64_t)nb * A < K + A && (a > 0 || (int64_t)nb * A >= K)) {   // else: infeasible here, ignored
+        p.dx_bm = sp->bm;
         p.rows_per_split = A; p.n_big = (int)std::min<int64_t>(nb, ceil_div(K, A)); p.rows_small = a;
         const int64_t rest = K - std::min<int64_t>(K, (int64_t)p.n_big * A);
         if (rest <= 0) p.rows_small = 0;
         splits = p.n_big + (p.rows_small ? (int)ceil_div(rest, p.rows_small) : 0);
+        two_sizes = true;
         p.seg_order[0] = 1; p.seg_order[1] = 0; p.seg_order[2] = 2;
-        if (const char* o = std::getenv("SBP_ORDER")) std::sscanf(o, "%d,%d,%d", &p.seg_order[0], &p.seg_order[1], &p.seg_order[2]);
+        if (opt.order_set) for (int q = 0; q < 3; ++q) p.seg_order[q] = opt.order[q];
       }
     }
-    if (const char* e = std::getenv("SBP_SPLITS")) {            // equal splits, dW units first
-      splits = std::max<int>(std::atoi(e), (int)ceil_div(K, kBigMaxRowsPerSplit));
+    if (opt.splits) {                                          // equal splits, dW units first
+      splits = std::max<int>(opt.splits, (int)ceil_div(K, kBigMaxRowsPerSplit));
       two_sizes = false;
       p.seg_order[0] = 1; p.seg_order[1] = 0; p.seg_order[2] = 2;
     }
   } else if (K > 0) {
     if (p.mfma) {
-      env_tile("SBP_TILE", &p.bm_w, &p.bn_w, &p.nw_w, &p.kb);
+      if (opt.tile_mode == 1) { p.bm_w = opt.tile_bm; p.bn_w = opt.tile_bn; p.nw_w = opt.tile_nw; p.kb = opt.tile_kb; }
       // enough blocks to fill the chip's block slots once, each split at least 4 stages long
       const int64_t tiles = ceil_div(Cout, p.bm_w) * ceil_div(Cin, p.bn_w);
       const int64_t slots = (p.bm_w + p.bn_w <= 256) ? 2 * kNumCU : kNumCU;
@@ -639,7 +633,7 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
       // tiles queue for slots the 128-row tiles move fewer bytes and win (detection shapes).
       p.dx_bm = 128;
       if (p.bm_w == 128 && p.kb == 64 && ceil_div(K, 128) * ceil_div(Cin, 128) + tiles * splits + 64 <= 700) p.dx_bm = 64;   // (measured: still ahead at 650 workgroups, behind at 770)
-      if (const char* e = std::getenv("SBP_DXROWS")) p.dx_bm = std::atoi(e) == 64 && p.bm_w == 128 && p.kb == 64 ? 64 : 128;   // debugging aid
+      if (opt.dxrows) p.dx_bm = opt.dxrows == 64 && p.bm_w == 128 && p.kb == 64 ? 64 : 128;
     } else {
       splits = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div(K, 512), 64));
     }
@@ -691,8 +685,10 @@ static int32_t launch_plain(const LinearPlan& p, const T* dY, const int32_t* idx
 // Dynamic LDS beyond 64 KB has to be granted per kernel; asked for once per kernel and size (one device per process).
 template <typename KernelT>
 static void allow_big_lds(KernelT kernel, size_t lds) {
-  static size_t granted = 0;                    // one instance per kernel type
+  static std::mutex m;                          // one instance of these per kernel type
+  static size_t granted = 0;
   static KernelT granted_for = nullptr;
+  std::lock_guard<std::mutex> lock(m);
   if (lds <= 64 * 1024 || (granted_for == kernel && lds <= granted)) return;
   if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess) {
     granted = lds;
@@ -723,12 +719,9 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
       1800 + std::max<int64_t>(a.n_zero ? (int64_t)(a.M - a.K) * a.Cin * 2 / a.n_zero : 0, n_db ? (int64_t)a.db_slice_rows * 512 : 0) / 40};
   for (int q = 0; q < 3; ++q) a.seg_order[q] = q;
   std::sort(a.seg_order, a.seg_order + 3, [&](int x, int y) { return len[x] != len[y] ? len[x] > len[y] : x < y; });
-  if (const char* o = std::getenv("SBP_ORDER")) {   // debugging aid: the order by hand
-    int v[3];
-    if (std::sscanf(o, "%d,%d,%d", &v[0], &v[1], &v[2]) == 3 && (unsigned)v[0] < 3 && (unsigned)v[1] < 3 && (unsigned)v[2] < 3 &&
-        (1 << v[0] | 1 << v[1] | 1 << v[2]) == 7)
-      for (int q = 0; q < 3; ++q) a.seg_order[q] = v[q];
-  }
+  const Options opt = options();
+  if (opt.order_set)                                // the order by hand (a permutation, checked when it was set)
+    for (int q = 0; q < 3; ++q) a.seg_order[q] = opt.order[q];
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE, BMX, NSX>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 

@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 
 #include "sbp_internal.h"
 
@@ -444,7 +445,7 @@ __global__ void __launch_bounds__(256) sample_cells_kernel(CellGeom g, int32_t* 
     const int off = g.P + (full_h ? cy * g.row_full : g.fh * g.row_full) + cx * (full_h ? g.k : g.k_ef);
     uint64_t h = absorb(g.base, g.per_sample ? (uint64_t)b : 0ull);
     h = absorb(h, g.shared ? 0ull : (uint64_t)ci);
-    // p = floor(h * n! / 2^64); factorial-base digits most significant first
+    // p = floor(h * n! / 2^64), the index of the cell's slot permutation
     uint64_t fact = 1;
     for (int i = 2; i <= n; ++i) fact *= (uint64_t)i;
     const uint64_t p = __umul64hi(h, fact);
@@ -510,18 +511,20 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
         const double lo = std::max(0.0, q - half), hi = q + half;
         v.win_lo = (uint64_t)(lo * two64);
         v.win_hi = hi >= 1.0 ? ~0ull : (uint64_t)(hi * two64);
-        if (std::getenv("SBP_SAMPLER_NO_WINDOW")) v.win_lo = v.win_hi = 0;   // debugging aid: an empty window, i.e. the full select
+        const Options opt = options();
+        if (opt.sampler_no_window) v.win_lo = v.win_hi = 0;   // override: an empty window, i.e. the full select
         // keep bits and chunk prefixes of the ordered write-out: 24 bytes per 64 positions, next to 34 KB of static LDS
         const int64_t chunks = ceil_div((int64_t)d.H * d.W, 64);
         size_t lds = (size_t)chunks * 24;
-        static bool big_lds_ok = false, big_lds_asked = false;
-        if (lds > 28 * 1024 && !big_lds_asked) {        // more than 64 KB in all: granted per kernel, asked for once
-          big_lds_asked = true;
-          big_lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_random_kernel<1024, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024) == hipSuccess;
-        }
+        static std::once_flag big_lds_once;             // more than 64 KB in all: granted per kernel, asked for once
+        static bool big_lds_ok = false;
+        if (lds > 28 * 1024)
+          std::call_once(big_lds_once, [] {
+            big_lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_random_kernel<1024, true>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024) == hipSuccess;
+          });
         v.mask_chunks = (int)chunks;
-        if (lds > 120 * 1024 || (lds > 28 * 1024 && !big_lds_ok) || std::getenv("SBP_SAMPLER_NO_MASKS")) { v.mask_chunks = 0; lds = 0; }
+        if (lds > 120 * 1024 || (lds > 28 * 1024 && !big_lds_ok) || opt.sampler_no_masks) { v.mask_chunks = 0; lds = 0; }
         SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<1024, true>), dim3(d.B), dim3(1024), lds, s, v, idx, inv);
       } else {
         SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<256, false>), dim3(d.B), dim3(256), 0, s, v, idx, inv);

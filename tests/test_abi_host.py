@@ -21,7 +21,7 @@ def _declared_symbols():
 
 def test_library_exports_every_declared_symbol():
     names = _declared_symbols()
-    assert len(names) == 24
+    assert len(names) == 25
     handle = ctypes.CDLL(_lib.LIB_PATH)
     for n in names:
         assert hasattr(handle, n), n
@@ -285,6 +285,47 @@ def test_backward_dwconv_argument_errors():
     assert call(wsp=None) == -6
     assert call(wsb=16) == -6
     assert call(dWd=None, db=None, dX=None) == 0
+
+
+def test_set_option_validates_names_and_values_and_changes_the_plan():
+    L = _lib.lib()
+    try:
+        assert L.sbp_set_option(b"no_such_option", b"1") == -8
+        assert L.sbp_set_option(b"tile", b"96x96") == -8
+        assert L.sbp_set_option(b"dxbm", b"100") == -8
+        # the dispatch order must be a permutation of 0, 1, 2: repeated or out-of-range kinds are refused here, on
+        # the host, and never reach a kernel
+        for bad in (b"0,0,0", b"0,1,3", b"1,2", b"-1,0,1", b"2,2,1"):
+            assert L.sbp_set_option(b"order", bad) == -8
+        assert L.sbp_set_option(b"order", b"2,0,1") == 0
+        assert L.sbp_set_option(b"plan", b"128,100,1,0") == -8           # rows not a multiple of 64
+        assert L.sbp_set_option(b"plan_768x2304", b"128,2112,3,0") == 0
+        # the engine report follows an override and returns to the automatic choice when it is cleared
+        auto = sbp.backward_linear_engine(4 * 197, 4 * 99, 64, 128, sbp.BF16)
+        assert auto[0] == "mfma"
+        sbp.set_option("tile", "big")
+        sbp.set_option("splits", 3)
+        assert sbp.backward_linear_engine(4 * 197, 4 * 99, 64, 128, sbp.BF16) == ("mfma_large", 3)
+        sbp.set_option("splits", None)
+        # a forced engine on a size its schedule search cannot serve falls back to equal legal splits (never a
+        # split length of zero): 70000 kept rows need at least 18 splits of 4096
+        eng, n = sbp.backward_linear_engine(140000, 70000, 64, 128, sbp.BF16)
+        assert eng == "mfma_large" and n >= 18
+        sbp.set_option("tile", None)
+        assert sbp.backward_linear_engine(4 * 197, 4 * 99, 64, 128, sbp.BF16) == auto
+        ws_auto = sbp.backward_linear_workspace(12608, 6336, 768, 2304, sbp.BF16)
+        sbp.set_option("plan_768x2304", "128,1088,6,0")
+        assert sbp.backward_linear_engine(12608, 6336, 768, 2304, sbp.BF16) == ("mfma_large", 6)
+        assert sbp.backward_linear_workspace(12608, 6336, 768, 2304, sbp.BF16) != ws_auto
+    finally:
+        assert L.sbp_set_option(None, None) == 0
+    assert sbp.backward_linear_workspace(12608, 6336, 768, 2304, sbp.BF16) == ws_auto
+
+
+def test_library_reads_no_environment_variable():
+    src = os.path.join(ROOT, "paper_2210_00129_amd", "csrc")
+    for name in os.listdir(src):
+        assert "getenv" not in open(os.path.join(src, name)).read(), name
 
 
 def test_binding_refuses_cpu_tensors():

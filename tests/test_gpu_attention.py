@@ -72,12 +72,10 @@ def test_engine_choice():
 
 
 def test_plain_kernel_on_bf16_matches_oracle():
-    os.environ["SBP_ATTN"] = "plain"
-    try:
+    with sbp.options(attn="plain"):
         assert sbp.backward_attention_engine(99, 64, sbp.BF16) == "plain"
         errs = _run(2, 197, 3, 64, _keep_sets(2, 197, 99, 7), "bf16", 9)
-    finally:
-        del os.environ["SBP_ATTN"]
+    assert sbp.backward_attention_engine(99, 64, sbp.BF16) == "mfma"
     assert max(errs) <= TOL_BF16, errs
 
 

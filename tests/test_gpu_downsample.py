@@ -19,10 +19,16 @@ def _keep(B, Ho, Wo, k, seed):
 @pytest.mark.parametrize("wide", [False, True])
 @pytest.mark.parametrize("dtype,C", [("bf16", 128), ("bf16", 8), ("bf16", 3), ("f32", 5), ("f32", 64)])
 @pytest.mark.parametrize("p", [2, 4, 1])
-def test_patch_gather_and_scatter_are_bit_exact(p, dtype, C, wide, monkeypatch):
+def test_patch_gather_and_scatter_are_bit_exact(p, dtype, C, wide):
     # wide: the kernels with 64-bit unit numbers, which otherwise only tensors of 2^32 units and more would reach
-    if wide:
-        monkeypatch.setenv("SBP_PATCH_WIDE", "1")
+    sbp.set_option("patch_wide", int(wide))
+    try:
+        _patch_gather_and_scatter(p, dtype, C)
+    finally:
+        sbp.set_option("patch_wide", None)
+
+
+def _patch_gather_and_scatter(p, dtype, C):
     B, Ho, Wo = 3, 6, 10
     H, W = p * Ho, p * Wo
     X = si.normal((B, H, W, C), 1.0, 7, dtype)

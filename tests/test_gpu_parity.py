@@ -64,12 +64,7 @@ def test_random_mask_sampler_large_maps_window_and_full_select(window, masks):
     # off) the full select that stands behind it; the ordered write-out from keep masks in LDS (also beyond 64 KB of
     # LDS: the 300 x 400 map) and (masks switched off) the chunked loop that stands behind it; several seeds, all keep
     # ratios, the detection-size map among them
-    import os
-    if not window:
-        os.environ["SBP_SAMPLER_NO_WINDOW"] = "1"
-    if not masks:
-        os.environ["SBP_SAMPLER_NO_MASKS"] = "1"
-    try:
+    with sbp.options(sampler_no_window=int(not window), sampler_no_masks=int(not masks)):
         for (B, P, H, W), seeds in (((2, 0, 200, 336), ((0, 1),)), ((3, 1, 50, 84), ((5, 6), (2**64 - 1, 7), (123, 2**40))),
                                     ((1, 2, 300, 400), ((3, 4),))):
             for k in (1, 2, 3, 4):
@@ -79,9 +74,6 @@ def test_random_mask_sampler_large_maps_window_and_full_select(window, masks):
                     torch.cuda.synchronize()
                     assert np.array_equal(idx.cpu().numpy(), ref)
                     assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(ref, B * (P + H * W)))
-    finally:
-        os.environ.pop("SBP_SAMPLER_NO_WINDOW", None)
-        os.environ.pop("SBP_SAMPLER_NO_MASKS", None)
 
 
 @pytest.mark.parametrize("c,k", [(2, 1), (2, 2), (3, 2), (4, 1), (4, 3)])
@@ -151,22 +143,11 @@ def test_linear_bf16_mfma_tiles_and_ragged_tails(shape, k):
     check_linear(X, W, dY, idx, "bf16")
 
 
-class _env:
-    """Sets debugging variables the library reads at every call, for the duration of a test."""
-    def __init__(self, **kv):
-        self.kv = kv
-    def __enter__(self):
-        import os
-        self.old = {k: os.environ.get(k) for k in self.kv}
-        for k, v in self.kv.items():
-            os.environ[k] = str(v)
-    def __exit__(self, *exc):
-        import os
-        for k, v in self.old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
+def _env(**kv):
+    """Explicit overrides of the library's choices (sbp_set_option) for the duration of a block."""
+    names = {"SBP_TILE": "tile", "SBP_DXBM": "dxbm", "SBP_SPLITS": "splits", "SBP_DXROWS": "dxrows", "SBP_ORDER": "order",
+             "SBP_DW_SEPARATE": "dw_separate"}
+    return sbp.options(**{names[k]: v for k, v in kv.items()})
 
 
 @pytest.mark.parametrize("dx_rows", [256, 128, 64])
