@@ -174,6 +174,27 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
                             void* dW, float* db, void* dX,
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
+/*
+ * sbp_backward_linear for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as sbp_backward_linear without `workspace` / `workspace_bytes`: the partial sums of the dW splits, the
+ * db slices and the inverse row map live in a fixed array of SBP_STATIC_SCRATCH_BYTES in device memory that
+ * belongs to the library (one per GPU, held from the library's first use on that GPU until the process ends;
+ * its address is looked up once per device, on the first call with that device current).  The call allocates
+ * and frees nothing.  Sizes that need more scratch than that (sbp_backward_linear_workspace(...) >
+ * SBP_STATIC_SCRATCH_BYTES) are refused with SBP_ERR_CAPACITY before anything is enqueued; every layer of the
+ * ViT / ConvNeXt workloads this library is measured on fits.  All calls on one GPU share the array: two calls
+ * that may overlap in time on that GPU (different streams, or graph branches) race; calls on one stream are
+ * ordered and safe.  Nothing in the array has to be cleared between calls (every element read was written by
+ * the same call first).  sbp_static_scratch_bytes() returns SBP_STATIC_SCRATCH_BYTES (host only).
+ */
+#define SBP_STATIC_SCRATCH_BYTES (48u << 20)
+size_t sbp_static_scratch_bytes(void);
+int32_t sbp_backward_linear_static(const void* dY, const int32_t* idx, const int32_t* inv, const void* X_k,
+                                   const void* W,
+                                   int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
+                                   void* dW, float* db, void* dX, uint32_t flags, void* stream);
+
 /* Host only.  Bytes of workspace sbp_backward_dwconv needs (0 on invalid sizes). */
 size_t sbp_backward_dwconv_workspace(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks,
                                      int64_t K, int32_t dtype, uint32_t flags);

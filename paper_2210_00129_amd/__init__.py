@@ -137,6 +137,21 @@ def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), d
     return dW, db, dX
 
 
+def static_scratch_bytes() -> int:
+    return int(_lib.lib().sbp_static_scratch_bytes())
+
+
+def backward_linear_static(dY, idx, X_k, W, dW, db, dX, M, flags=0, inv=None):
+    """sbp_backward_linear_static: the caller passes inputs and (preallocated) outputs only; the workspace is the
+    library's own fixed device array.  Any of dW, db, dX may be None."""
+    Cout, Cin = W.shape
+    K = idx.numel() if idx is not None else dY.shape[0]
+    _lib.check(_lib.lib().sbp_backward_linear_static(
+        _dev(dY, "dY"), _dev(idx, "idx"), _dev(inv, "inv"), _dev(X_k, "X_k"), _dev(W, "W"), M, K, Cin, Cout,
+        _dtype_code(W), _dev(dW, "dW"), _dev(db, "db"), _dev(dX, "dX"), flags, _stream(W.device)))
+    return dW, db, dX
+
+
 def forward_cache_patches(X, idx, p, out=None):
     """Rows [K, p*p*C]: the p x p input patch of X [B, H, W, C] under every kept output position."""
     B, H, W, C = X.shape

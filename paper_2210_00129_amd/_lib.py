@@ -45,6 +45,9 @@ PROTOTYPES = {
     "sbp_backward_linear_engine": (c_i32, [c_i64, c_i64, c_i32, c_i32, c_i32, c_u32, ctypes.POINTER(c_i32)]),
     "sbp_backward_linear": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_i32,
                                     c_vp, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),
+    "sbp_static_scratch_bytes": (c_sz, []),
+    "sbp_backward_linear_static": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_i32,
+                                           c_vp, c_vp, c_vp, c_u32, c_vp]),
     "sbp_backward_dwconv_workspace": (c_sz, [c_i32, c_i32, c_i32, c_i32, c_i32, c_i64, c_i32, c_u32]),
     "sbp_backward_dwconv": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32,
                                     c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),

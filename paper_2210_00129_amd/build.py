@@ -14,7 +14,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["sbp_api.hip", "sbp_sampler.hip", "sbp_gather.hip", "sbp_linear.hip", "sbp_dwconv.hip", "sbp_pointwise.hip", "sbp_attention.hip"]
+SOURCES = ["sbp_api.hip", "sbp_sampler.hip", "sbp_gather.hip", "sbp_linear.hip", "sbp_dwconv.hip", "sbp_pointwise.hip", "sbp_attention.hip", "sbp_static.hip"]
 LIB = os.path.join(HERE, "libsbp.so")
 
 HIPCC_FLAGS = [
