@@ -39,6 +39,16 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the side measurements of the other workloads")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--per-layer", action="store_true",
+                    help="one cache call and one backward call per layer instead of one batched call per block")
+    ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
+                    help="an explicit override of the library's choices (sbp_set_option), for sweeps")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="workload for rocprofv3 --pmc runs: a calibration copy of known size, then one cold pass of a block")
+    ap.add_argument("--summarize-pmc", nargs="+", metavar="DIR",
+                    help="print per-kernel means of the counters in rocprofv3 output directories and exit (no GPU needed)")
+    ap.add_argument("--timeline", action="store_true",
+                    help="per-workgroup time stamps of the last batched backward launch of a step, summarised per kind of unit")
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed region at the chosen ratio (for profiler runs: no r=1 leg, no event pass)")
     ap.add_argument("--attention-only", action="store_true",
@@ -76,9 +86,10 @@ class LinearLayer:
 class Job:
     """All buffers of a workload and a step() that enqueues one pass of the path."""
 
-    def __init__(self, wl, torch, sbp, si):
+    def __init__(self, wl, torch, sbp, si, batched=True):
         from paper_2210_00129_amd import _lib
         self.wl, self.torch, self.sbp = wl, torch, sbp
+        self.batched = batched
         self.L = _lib.lib()
         self.check = _lib.check
         self.stream = torch.cuda.current_stream().cuda_stream
@@ -122,11 +133,30 @@ class Job:
                            torch.empty((wl.B, wl.H, wl.W, C), dtype=tdt, device="cuda"))
         self.desc = sbp.make_desc(wl.B, wl.P, wl.H, wl.W, 2, 0, 0)
         self.step_no = 0
+        # batched calls: per block one array of layer descriptors (backward order) and one of gather items,
+        # marshalled once; set_ratio fills in K
+        self.batch_args = []
+        for blk in self.blocks:
+            lays = (_lib.LinearLayer * len(blk))(*[
+                _lib.LinearLayer(l.dY.data_ptr(), self.idx.data_ptr(), self.inv.data_ptr(), l.Xk.data_ptr(), l.W.data_ptr(), M, 0,
+                                 l.Cin, l.Cout, l.dW.data_ptr(), l.db.data_ptr(), l.dX.data_ptr(), 0, 0) for l in reversed(blk)])
+            items = (_lib.GatherItem * len(blk))(*[
+                _lib.GatherItem(l.X.data_ptr(), self.idx.data_ptr(), l.Xk.data_ptr(), M, 0, l.Cin, 0) for l in blk])
+            self.batch_args.append((lays, items))
+        self.ws_batch = None
 
     def set_ratio(self, r):
         self.k = self.sbp.k_from_ratio(r)
         self.desc.k = self.k
         self.K = self.sbp.keep_count(self.wl.B, self.wl.P, self.wl.H, self.wl.W, self.k)
+        need = 256
+        for lays, items in self.batch_args:
+            for i in range(len(lays)):
+                lays[i].K = self.K
+                items[i].K = self.K
+            need = max(need, int(self.L.sbp_backward_linear_batch_workspace(lays, len(lays), self.code)))
+        if self.ws_batch is None or self.ws_batch.numel() < need:
+            self.ws_batch = self.torch.empty(need, dtype=self.torch.uint8, device="cuda")
 
     def flops_per_step(self):
         f = sum(4.0 * self.K * s.Cin * s.Cout for s in self.wl.linears)
@@ -142,10 +172,16 @@ class Job:
         for b, blk in enumerate(self.blocks):
             self.desc.stream_id = self.step_no * 1000 + b          # fresh mask for every block and step
             check(L.sbp_sample_indices(ctypes.byref(self.desc), idx_ptr, self.M, inv_ptr, self.stream))
-            for lay in blk:                                         # forward side: keep only the kept rows
-                check(lay.cache(idx_ptr, K))
-            for lay in reversed(blk):                               # backward side
-                check(lay.backward(idx_ptr, inv_ptr, K))
+            if self.batched:
+                lays, items = self.batch_args[b]
+                check(L.sbp_forward_cache_batch(items, len(items), self.code, self.stream))   # forward side: the kept rows
+                check(L.sbp_backward_linear_batch(lays, len(lays), self.code, self.ws_batch.data_ptr(),
+                                                  self.ws_batch.numel(), self.stream))          # backward side
+            else:
+                for lay in blk:                                     # forward side: keep only the kept rows
+                    check(lay.cache(idx_ptr, K))
+                for lay in reversed(blk):                           # backward side
+                    check(lay.backward(idx_ptr, inv_ptr, K))
             if self.wl.dw_channels:
                 X, Wd, dY = self.dw_in[b]
                 dWd, db, dX = self.dw_out
@@ -193,6 +229,114 @@ class Job:
             C = self.wl.dw_channels
             total += s_ * (K * C + 2 * M * C) + 49 * C * (s_ + 4)
         return total * self.wl.blocks
+
+
+def timeline_report(job, torch, sbp, wl):
+    """Device-clock time stamps of every workgroup of one linear_multi_kernel launch inside a step (the last block's):
+    per layer and kind of unit the start times and durations, the shader clock the long units ran at, and how busy
+    the 256 CUs were."""
+    import numpy as np
+    for _ in range(3):
+        job.step()
+    torch.cuda.synchronize()
+    rec = torch.zeros((8192, 8), dtype=torch.int64, device="cuda")
+    sbp.profile_timeline(rec)
+    job.step()
+    torch.cuda.synchronize()
+    sbp.profile_timeline(None)
+    t = rec.cpu().numpy()
+    used = t[:, 0] > 0
+    n = int(used.sum())
+    t = t[:np.nonzero(used)[0].max() + 1]
+    base = t[used[:len(t)], 0].min()
+    kind, layer = t[:, 4] & 0xff, (t[:, 4] >> 8) & 0xff
+    s = (t[:, 0] - base) / 100.0
+    tiles = t[:, 1] > 0
+    e = np.where(tiles, (t[:, 1] - base) / 100.0, s)
+    d = e - s
+    names = [x.name for x in reversed(wl.linears)]
+    kn = {0: "dX tile", 1: "dW unit", 2: "dW unit (short)", 3: "zero fill", 4: "column sums"}
+    out = {"workgroups": n, "span_us": round(float(e.max()), 1), "segments": []}
+    xcd, ran_on = t[:, 5] & 0xff, (t[:, 5] >> 8) & 0xff      # queue the unit was planned on, XCD that ran it
+    keys = sorted({(int(layer[i]), int(kind[i])) for i in range(len(t)) if used[i]}, key=lambda lk: float(np.min(s[(layer == lk[0]) & (kind == lk[1]) & used[:len(t)]])))
+    for lay, kd in keys:
+        sl = (layer == lay) & (kind == kd) & used[:len(t)]
+        seg = {"layer": names[lay] if lay < len(names) else lay, "kind": kn[kd], "workgroups": int(sl.sum()),
+               "xcds": sorted(int(v) for v in set(xcd[sl])), "run_elsewhere": int((xcd[sl] != ran_on[sl]).sum()),
+               "start_us": [round(float(f(s[sl])), 1) for f in (np.min, np.median, np.max)]}
+        if True:
+            seg["duration_us"] = [round(float(f(d[sl])), 1) for f in (np.min, np.median, np.max)]
+            seg["end_max_us"] = round(float(e[sl].max()), 1)
+            cyc = (t[sl, 3] - t[sl, 2]).astype(np.float64)
+            seg["shader_mhz_median"] = round(float(np.median(cyc / np.maximum(d[sl], 1e-3))), 0)
+        out["segments"].append(seg)
+    out["cu_busy_frac"] = round(float(d[tiles].sum() / (256.0 * e.max())), 3)
+    out["cu_busy_frac_tiles_only"] = round(float(d[tiles & (kind <= 2)].sum() / (256.0 * e.max())), 3)
+    out["per_xcd_last_end_us"] = [round(float(e[(ran_on == x) & used[:len(t)]].max()), 1) for x in range(8)]
+    return out
+
+
+COPY_BYTES = 256 * 1024 * 1024           # the calibration copy reads 256 MiB and writes 256 MiB
+
+
+def traffic_probe(wl, ratio, torch, sbp, si):
+    """Workload of the counter runs (rocprofv3 --pmc <counters> -- python3 bench.py --traffic-probe): a plain device
+    copy of known size (what FETCH_SIZE / WRITE_SIZE read for a known number of bytes), then, on buffers pushed out of
+    the last-level cache before every call, one block of the workload through the batched calls, the same layers
+    through the per-layer calls, and the depthwise backward where the workload has one."""
+    src = torch.empty(COPY_BYTES, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    flush = torch.empty(768 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        dst.copy_(src)
+    k = sbp.k_from_ratio(ratio)
+    idx, inv = sbp.sample_indices(wl.B, wl.P, wl.H, wl.W, k, 0, 1, want_inv=True)
+    layers = []
+    for i, s in enumerate(wl.linears):
+        X, W, dY = (t.cuda() for t in si.linear_case(wl.M, s.Cin, s.Cout, 100 + i, wl.dtype))
+        layers.append(dict(X=X, W=W, dY=dY))
+    for rep in range(2):                                   # the second pass is the one to read (code and plans warm)
+        flush.fill_(0)
+        Xks = sbp.forward_cache_batch([l["X"] for l in layers], [idx] * len(layers))
+        flush.fill_(0)
+        sbp.backward_linear_batch([dict(dY=l["dY"], idx=idx, inv=inv, X_k=xk, W=l["W"], M=wl.M) for l, xk in zip(layers, Xks)])
+        for l, xk in zip(layers, Xks):
+            flush.fill_(0)
+            sbp.forward_cache(l["X"], idx, out=xk)
+            flush.fill_(0)
+            sbp.backward_linear(l["dY"], idx, xk, l["W"], inv=inv)
+        if wl.dw_channels:
+            X, Wd, dY = (t.cuda() for t in si.dwconv_case(wl.B, wl.H, wl.W, wl.dw_channels, 7, 200, wl.dtype))
+            flush.fill_(0)
+            sbp.backward_dwconv(dY, idx, X, Wd, inv=inv)
+    torch.cuda.synchronize()
+    print(json.dumps({"traffic_probe": wl.name, "keep_ratio": ratio, "K": idx.numel()}))
+
+
+def summarize_pmc(dirs):
+    """Per kernel and counter: dispatches, mean and last value over the *counter_collection.csv files under `dirs`;
+    FETCH_SIZE / WRITE_SIZE (KiB) are also scaled by what the same counter read for the calibration copy."""
+    import csv
+    import glob
+    vals = {}
+    for d in dirs:
+        for f in glob.glob(os.path.join(d, "**", "*counter_collection.csv"), recursive=True):
+            for row in csv.DictReader(open(f)):
+                vals.setdefault((row["Counter_Name"], row["Kernel_Name"][:72]), []).append(float(row["Counter_Value"]))
+    factor = {}
+    for counter in ("FETCH_SIZE", "WRITE_SIZE"):
+        cands = [(max(v), k) for (c, k), v in vals.items() if c == counter and "copy" in k.lower()]
+        if cands:
+            reading, k = max(cands)
+            factor[counter] = COPY_BYTES / (reading * 1024.0)
+            print(f"calibration {counter}: copy kernel '{k[:50]}' reads {reading:.0f} KiB for {COPY_BYTES} bytes -> factor {factor[counter]:.4f}")
+    for (counter, kernel), v in sorted(vals.items(), key=lambda kv: (kv[0][1], kv[0][0])):
+        if not any(t in kernel for t in ("sbp::", "copy")):
+            continue
+        line = f"{kernel:72s} {counter:32s} n={len(v):4d} mean={sum(v) / len(v):16.1f} last={v[-1]:16.1f}"
+        if counter in factor:
+            line += f"  calibrated last = {v[-1] * 1024 * factor[counter] / 1e6:9.2f} MB"
+        print(line)
 
 
 def measured_traffic(name):
@@ -515,6 +659,9 @@ def measure_samplers(torch, sbp, si):
 
 def main():
     args = parse()
+    if args.summarize_pmc:
+        summarize_pmc(args.summarize_pmc)
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py measures one GPU: this path has no multi-GPU leg (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
@@ -526,13 +673,22 @@ def main():
         print("bench.py needs a GPU: the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     torch.cuda.set_device(0)
+    for kv in args.set:
+        name, _, value = kv.partition("=")
+        sbp.set_option(name, value)
     if args.attention_only:
         print(json.dumps({"attention_drop_qkv": measure_attention(torch, sbp, si)}))
         return
     wl = si.WORKLOADS[args.workload]
-    job = Job(wl, torch, sbp, si)
+    if args.traffic_probe:
+        traffic_probe(wl, args.ratio, torch, sbp, si)
+        return
+    job = Job(wl, torch, sbp, si, batched=not args.per_layer)
 
     job.set_ratio(args.ratio)
+    if args.timeline:
+        print(json.dumps(timeline_report(job, torch, sbp, wl)))
+        return
     ms, wall_ms = job.time_steps(args.steps, args.warmup)
     flops = job.flops_per_step()
     value = flops / ms / 1e9                       # TFLOP/s
@@ -551,10 +707,11 @@ def main():
     fused = prof["dx_gemm"][1] == 0
     gemm_flops = {"dw_gemm": 4.0 if fused else 2.0, "dx_gemm": 2.0}
     per_launch = {}
+    layers_per_launch = len(wl.linears) if job.batched else 1        # a batched call serves a whole block in one launch
     for cls in ("dw_gemm", "dx_gemm"):
         tot_ms, n = prof[cls]
         if n:
-            fl = sum(gemm_flops[cls] * K_r * s.Cin * s.Cout for s in wl.linears) / len(wl.linears)
+            fl = sum(gemm_flops[cls] * K_r * s.Cin * s.Cout for s in wl.linears) / len(wl.linears) * layers_per_launch
             per_launch[cls] = (tot_ms / n, fl)
     dom = max(per_launch, key=lambda c: prof[c][0]) if per_launch else None
     roofline = None
@@ -565,16 +722,19 @@ def main():
         engines = sorted({sbp.backward_linear_engine(job.M, K_r, s.Cin, s.Cout, job.code)[0] for s in wl.linears})
         kname = {"mfma_large": "linear_big_kernel", "mfma": "linear_bwd_kernel", "plain": "plain_dw_kernel"}
         kernel = " / ".join(kname[e] for e in engines) + (" (dW + dX tiles, zero fill, db sums: one launch per layer)" if fused else "")
+        if job.batched and engines == ["mfma_large"]:
+            kernel = f"linear_multi_kernel (dX tiles, dW units, zero fill, db sums of the {len(wl.linears)} layers of a block: one launch per block)"
+        profile_file = "linear_multi_kernel_vit_base_r0.5.md" if job.batched else "linear_big_kernel_vit_base_r0.5.md"
         roofline = {"bound": "mfma", "kernel": kernel if fused else dom, "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": measured_traffic("linear_big_kernel_vit_base_r0.5.md")
+                    "traffic": measured_traffic(profile_file)
                     if (wl.name == "vit_base" and args.ratio == 0.5 and engines == ["mfma_large"]) else None,
                     "avg_launch_us": round(avg_ms * 1e3, 2),
                     "flops_per_launch": fl}
         # layers whose intensity lies under the ridge of the two peaks are priced against HBM instead
         s_b = 2 if wl.dtype == "bf16" else 4
         by = sum(s_b * (K_r * s.Cout + K_r * s.Cin + s.Cout * s.Cin + wl.M * s.Cin) + 4 * s.Cout * s.Cin + 4 * s.Cout + 4 * K_r
-                 for s in wl.linears) / len(wl.linears)
+                 for s in wl.linears) / len(wl.linears) * layers_per_launch
         if fused and fl / by < PEAK_BF16_TFLOPS * 1e3 / PEAK_HBM_GBS:
             gbs = by / avg_ms / 1e6
             roofline.update({"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -587,6 +747,13 @@ def main():
     job.set_ratio(1.0)
     ms_full, _ = job.time_steps(max(3, args.steps // 2), 2)
     job.set_ratio(args.ratio)
+    # the same step with one cache call and one backward call per layer (the four-call ABI of the method) / batched
+    job.batched = not job.batched
+    ms_other, _ = job.time_steps(max(3, args.steps // 2), 2)
+    other_mode = {"calls": "one sbp_forward_cache_batch + one sbp_backward_linear_batch per block" if job.batched
+                  else "one sbp_forward_cache + one sbp_backward_linear per layer",
+                  "ms_per_step": round(ms_other, 4), "tflops": round(flops / ms_other / 1e9, 2)}
+    job.batched = not job.batched
     s_ = 2 if wl.dtype == "bf16" else 4
     cached = sum(K_r * s.Cin * s_ + 4 * K_r for s in wl.linears)
     full = sum(wl.M * s.Cin * s_ for s in wl.linears)
@@ -606,6 +773,9 @@ def main():
         "attainable_tflops": round(attainable_tflops(flops, bytes_step), 1),
         "frac_of_attainable": round(value / attainable_tflops(flops, bytes_step), 4),
         "activation_memory_saving": round(1.0 - cached / full, 4),
+        "calls": "one sbp_forward_cache_batch + one sbp_backward_linear_batch per block" if job.batched
+                 else "one sbp_forward_cache + one sbp_backward_linear per layer",
+        "other_call_pattern": other_mode,
         "kernel_breakdown": breakdown,
         "roofline": roofline,
     }

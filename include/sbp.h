@@ -61,6 +61,8 @@ extern "C" {
  * round-half-up(k*c'/cell) (>= 1).  idx order: sample-major, prefix rows, kept frames ascending. */
 #define SBP_TEMPORAL      3
 
+#define SBP_MAX_BATCH_LAYERS 8   /* most layers / tensors one batched call takes */
+
 /* flags of sbp_backward_linear */
 #define SBP_FLAG_DY_COMPACT     1u  /* dY is already compact: [K, Cout], row j belongs to idx[j] */
 #define SBP_FLAG_DX_COMPACT     2u  /* write dX compact: [K, Cin], no scatter, no zero rows */
@@ -125,6 +127,21 @@ int32_t sbp_sample_indices(const sbp_sample_desc* desc, int32_t* idx, int64_t id
 int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t K, int32_t C,
                           int32_t dtype, void* X_k, void* stream);
 
+/*
+ * Step "forward cache" for several tensors in one call (the inputs of all linear layers of a block): item i is
+ * sbp_forward_cache(X, idx, M, K, C, dtype, X_k).  Rows whose byte length is a multiple of 16 (16-byte aligned
+ * tensors) are served by ONE launch; otherwise the items run one after the other.  1 <= n <= SBP_MAX_BATCH_LAYERS.
+ */
+typedef struct sbp_gather_item {
+  const void*    X;       /* [M, C] */
+  const int32_t* idx;     /* [K] */
+  void*          X_k;     /* [K, C] out */
+  int64_t        M, K;
+  int32_t        C;
+  int32_t        reserved;/* 0 */
+} sbp_gather_item;
+int32_t sbp_forward_cache_batch(const sbp_gather_item* items, int32_t n, int32_t dtype, void* stream);
+
 /* Host only.  Bytes of workspace sbp_backward_linear needs for these sizes (0 on invalid sizes). */
 size_t sbp_backward_linear_workspace(int64_t M, int64_t K, int32_t Cin, int32_t Cout,
                                      int32_t dtype, uint32_t flags);
@@ -173,6 +190,41 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
                             int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype,
                             void* dW, float* db, void* dX,
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
+/*
+ * Several linear layers in one call (paper, eq:backward_fc_sbp per layer; the benchmark configuration asks for
+ * the "per-block backward of all four linears" of a transformer block).  Every layer is described as in
+ * sbp_backward_linear (same argument meaning, flags and outputs); all layers share `dtype`.  The layers must be
+ * independent: no layer's dY may be another's dX or alias any output of the call (a chain of dependent layers
+ * still profits: the weight gradients of a block need only each layer's dY and X_k, so a caller can run the
+ * dX of the critical path layer by layer and hand all dW / db of the block to one call, with dX = NULL).
+ * bf16 layers within the large-tile engine's limits (Cin % 8 == 0, Cout % 32 == 0, M * max(Cin, Cout) < 2^31,
+ * K >= 1, 16-byte aligned tensors) run as ONE grid whose units - dX tiles, dW units, zero-fill and column-sum
+ * blocks of all layers - are dispatched longest first, plus one reduction launch for all split sums; a batch
+ * with any other layer runs layer by layer, exactly as n calls of sbp_backward_linear would.  A layer whose dW
+ * needs a single split writes dW directly (no partial sums, no reduction).  Results per layer equal those of
+ * sbp_backward_linear up to the summation order of dW / db (bit-identical on exactly representable inputs).
+ *   layers     host array of n descriptors, 1 <= n <= SBP_MAX_BATCH_LAYERS; read during the call only
+ *   workspace  device, 256-byte aligned, sbp_backward_linear_batch_workspace(layers, n, dtype) bytes (the
+ *              query looks at sizes, flags and at which of inv / dW / db / dX are NULL, not at the addresses)
+ */
+typedef struct sbp_linear_layer {
+  const void*    dY;      /* [M, Cout], or [K, Cout] with SBP_FLAG_DY_COMPACT */
+  const int32_t* idx;     /* [K] */
+  const int32_t* inv;     /* [M] or NULL */
+  const void*    X_k;     /* [K, Cin] */
+  const void*    W;       /* [Cout, Cin] */
+  int64_t        M, K;
+  int32_t        Cin, Cout;
+  void*          dW;      /* [Cout, Cin] fp32 (bf16 with SBP_FLAG_DW_OUT_BF16) or NULL */
+  float*         db;      /* [Cout] or NULL */
+  void*          dX;      /* [M, Cin] ([K, Cin] with SBP_FLAG_DX_COMPACT) or NULL */
+  uint32_t       flags;   /* SBP_FLAG_* as for sbp_backward_linear */
+  uint32_t       reserved;/* 0 */
+} sbp_linear_layer;
+size_t sbp_backward_linear_batch_workspace(const sbp_linear_layer* layers, int32_t n, int32_t dtype);
+int32_t sbp_backward_linear_batch(const sbp_linear_layer* layers, int32_t n, int32_t dtype,
+                                  void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * sbp_backward_linear for callers that cannot allocate device memory and have no workspace to pass: code
@@ -387,6 +439,16 @@ int32_t sbp_set_option(const char* name, const char* value);
 #define SBP_PROF_NCLASSES   11
 #define SBP_PROF_RESET     (-1)
 int32_t sbp_profile_enable(int32_t on);
+/*
+ * Measurement aid: per-workgroup time stamps of the batched linear backward.  While `records` (device memory,
+ * 8 x uint64 per unit of work, capacity_records units; NULL switches it off) is set, every unit of
+ * sbp_backward_linear_batch's common grid with a number below the capacity writes
+ *   [0] start and [1] end on the 100 MHz constant clock, [2] start and [3] end on the shader clock,
+ *   [4] kind | layer << 8 | unit << 16   (kind 0 dX tile, 1 dW unit, 3 zero-fill block, 4 column-sum block)
+ *   [5] queue (XCD) the unit was planned on | XCD that ran it << 8 | workgroup << 16
+ * The caller owns the buffer and zeroes it.  Not thread-safe.
+ */
+int32_t sbp_profile_timeline(void* records, int64_t capacity_records);
 int32_t sbp_profile_read(int32_t which, double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus

@@ -16,7 +16,7 @@ from __future__ import annotations
 import torch
 
 from . import _lib
-from ._lib import SampleDesc, SbpError  # noqa: F401
+from ._lib import GatherItem, LinearLayer, SampleDesc, SbpError  # noqa: F401
 
 F32, BF16 = 0, 1
 GRID_PER_CELL, GRID_SHARED, RANDOM_MASK, TEMPORAL = 0, 1, 2, 3
@@ -90,6 +90,17 @@ def forward_cache(X: torch.Tensor, idx: torch.Tensor, out=None) -> torch.Tensor:
     return Xk
 
 
+def forward_cache_batch(Xs, idxs, outs=None):
+    """X_k = X[idx] for several tensors in one call (one launch where every row is a multiple of 16 bytes)."""
+    n = len(Xs)
+    if outs is None:
+        outs = [torch.empty((i.numel(), X.shape[1]), dtype=X.dtype, device=X.device) for X, i in zip(Xs, idxs)]
+    items = (GatherItem * n)(*[GatherItem(_dev(X, "X"), _dev(i, "idx"), _dev(o, "X_k"), X.shape[0], i.numel(), X.shape[1], 0)
+                               for X, i, o in zip(Xs, idxs, outs)])
+    _lib.check(_lib.lib().sbp_forward_cache_batch(items, n, _dtype_code(Xs[0]), _stream(Xs[0].device)))
+    return outs
+
+
 def backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags=0) -> int:
     return int(_lib.lib().sbp_backward_linear_workspace(M, K, Cin, Cout, dtype_code, flags))
 
@@ -135,6 +146,52 @@ def backward_linear(dY, idx, X_k, W, M=None, flags=0, want=("dW", "db", "dX"), d
         _dev(dW, "dW"), _dev(db, "db"), _dev(dX, "dX"), _dev(workspace, "workspace"), workspace.numel(),
         flags, _stream(dev)))
     return dW, db, dX
+
+
+def make_layer(dY, idx, X_k, W, M, dW=None, db=None, dX=None, flags=0, inv=None) -> LinearLayer:
+    """One sbp_linear_layer descriptor from tensors (outputs preallocated by the caller; None skips one)."""
+    Cout, Cin = W.shape
+    K = idx.numel() if idx is not None else dY.shape[0]
+    return LinearLayer(_dev(dY, "dY"), _dev(idx, "idx"), _dev(inv, "inv"), _dev(X_k, "X_k"), _dev(W, "W"), int(M), int(K),
+                       int(Cin), int(Cout), _dev(dW, "dW"), _dev(db, "db"), _dev(dX, "dX"), int(flags), 0)
+
+
+def backward_linear_batch_workspace(descs, dtype_code) -> int:
+    arr = (LinearLayer * len(descs))(*descs)
+    return int(_lib.lib().sbp_backward_linear_batch_workspace(arr, len(descs), dtype_code))
+
+
+def backward_linear_batch(layers, workspace=None, want=("dW", "db", "dX")):
+    """SBP backward of several independent layers in one call.  layers: dicts with dY, idx, X_k, W, M and
+    optionally flags, inv, dW, db, dX (preallocated outputs); outputs named in `want` are allocated when absent.
+    Returns a list of (dW, db, dX)."""
+    descs, outs = [], []
+    code = None
+    for l in layers:
+        W = l["W"]
+        Cout, Cin = W.shape
+        flags = l.get("flags", 0)
+        idx = l["idx"]
+        K = idx.numel()
+        M = l["M"]
+        dev = W.device
+        code = _dtype_code(W)
+        dW, db, dX = l.get("dW"), l.get("db"), l.get("dX")
+        if "dW" in want and dW is None:
+            dW = torch.empty((Cout, Cin), dtype=torch.bfloat16 if flags & FLAG_DW_OUT_BF16 else torch.float32, device=dev)
+        if "db" in want and db is None:
+            db = torch.empty((Cout,), dtype=torch.float32, device=dev)
+        if "dX" in want and dX is None:
+            dX = torch.empty((K if flags & FLAG_DX_COMPACT else M, Cin), dtype=W.dtype, device=dev)
+        descs.append(make_layer(l["dY"], idx, l["X_k"], W, M, dW, db, dX, flags, l.get("inv")))
+        outs.append((dW, db, dX))
+    arr = (LinearLayer * len(descs))(*descs)
+    need = int(_lib.lib().sbp_backward_linear_batch_workspace(arr, len(descs), code))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=layers[0]["W"].device)
+    _lib.check(_lib.lib().sbp_backward_linear_batch(arr, len(descs), code, _dev(workspace, "workspace"), workspace.numel(),
+                                                    _stream(layers[0]["W"].device)))
+    return outs
 
 
 def static_scratch_bytes() -> int:
@@ -323,6 +380,15 @@ PROF_CLASSES = ("sample", "gather", "dw_gemm", "dx_gemm", "reduce", "colsum", "z
 def profile_enable(on: bool) -> None:
     """Benchmark aid: bracket every kernel launch of the library with HIP events."""
     _lib.check(_lib.lib().sbp_profile_enable(1 if on else 0))
+
+
+def profile_timeline(records=None) -> None:
+    """Benchmark aid: per-workgroup time stamps of the batched linear backward into `records` (int64 tensor
+    [n, 8] on the GPU, zeroed by the caller); None switches it off."""
+    if records is None:
+        _lib.check(_lib.lib().sbp_profile_timeline(None, 0))
+    else:
+        _lib.check(_lib.lib().sbp_profile_timeline(_dev(records, "records"), records.shape[0]))
 
 
 def profile_read(reset: bool = True) -> dict:

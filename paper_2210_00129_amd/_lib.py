@@ -21,6 +21,18 @@ class SampleDesc(ctypes.Structure):
                 ("mode", c_i32), ("per_sample", c_i32), ("seed", c_u64), ("stream_id", c_u64)]
 
 
+class LinearLayer(ctypes.Structure):
+    """Mirror of sbp_linear_layer in include/sbp.h."""
+    _fields_ = [("dY", c_vp), ("idx", c_vp), ("inv", c_vp), ("X_k", c_vp), ("W", c_vp), ("M", c_i64), ("K", c_i64),
+                ("Cin", c_i32), ("Cout", c_i32), ("dW", c_vp), ("db", c_vp), ("dX", c_vp), ("flags", c_u32),
+                ("reserved", c_u32)]
+
+
+class GatherItem(ctypes.Structure):
+    """Mirror of sbp_gather_item in include/sbp.h."""
+    _fields_ = [("X", c_vp), ("idx", c_vp), ("X_k", c_vp), ("M", c_i64), ("K", c_i64), ("C", c_i32), ("reserved", c_i32)]
+
+
 # name -> (restype, argtypes); every symbol include/sbp.h declares
 PROTOTYPES = {
     "sbp_status_string": (ctypes.c_char_p, [c_i32]),
@@ -29,6 +41,7 @@ PROTOTYPES = {
     "sbp_keep_count": (c_i64, [ctypes.POINTER(SampleDesc)]),
     "sbp_sample_indices": (c_i32, [ctypes.POINTER(SampleDesc), c_vp, c_i64, c_vp, c_vp]),
     "sbp_forward_cache": (c_i32, [c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_vp, c_vp]),
+    "sbp_forward_cache_batch": (c_i32, [ctypes.POINTER(GatherItem), c_i32, c_i32, c_vp]),
     "sbp_backward_linear_workspace": (c_sz, [c_i64, c_i64, c_i32, c_i32, c_i32, c_u32]),
     "sbp_forward_cache_patches": (c_i32, [c_vp, c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i64, c_i32, c_vp, c_vp]),
     "sbp_scatter_patches_workspace": (c_sz, [c_i32, c_i32, c_i32, c_i32]),
@@ -45,6 +58,8 @@ PROTOTYPES = {
     "sbp_backward_linear_engine": (c_i32, [c_i64, c_i64, c_i32, c_i32, c_i32, c_u32, ctypes.POINTER(c_i32)]),
     "sbp_backward_linear": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_i32,
                                     c_vp, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),
+    "sbp_backward_linear_batch_workspace": (c_sz, [ctypes.POINTER(LinearLayer), c_i32, c_i32]),
+    "sbp_backward_linear_batch": (c_i32, [ctypes.POINTER(LinearLayer), c_i32, c_i32, c_vp, c_sz, c_vp]),
     "sbp_static_scratch_bytes": (c_sz, []),
     "sbp_backward_linear_static": (c_i32, [c_vp, c_vp, c_vp, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_i32,
                                            c_vp, c_vp, c_vp, c_u32, c_vp]),
@@ -53,6 +68,7 @@ PROTOTYPES = {
                                     c_i64, c_i32, c_vp, c_vp, c_vp, c_vp, c_sz, c_u32, c_vp]),
     "sbp_set_option": (c_i32, [ctypes.c_char_p, ctypes.c_char_p]),
     "sbp_profile_enable": (c_i32, [c_i32]),
+    "sbp_profile_timeline": (c_i32, [c_vp, c_i64]),
     "sbp_profile_read": (c_i32, [c_i32, ctypes.POINTER(c_dbl), ctypes.POINTER(c_i64)]),
 }
 

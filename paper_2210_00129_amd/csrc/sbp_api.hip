@@ -99,7 +99,8 @@ static bool apply_option(Options& o, const char* name, const char* v) {
   }
   bool* flag = n == "debug_plan" ? &o.debug_plan : n == "dw_separate" ? &o.dw_separate
              : n == "sampler_no_window" ? &o.sampler_no_window : n == "sampler_no_masks" ? &o.sampler_no_masks
-             : n == "patch_wide" ? &o.patch_wide : nullptr;
+             : n == "patch_wide" ? &o.patch_wide : n == "batch_dynamic" ? &o.batch_dynamic
+             : n == "batch_spread" ? &o.batch_spread : nullptr;
   if (!flag) return false;
   return parse_flag(v, flag);
 }
@@ -121,6 +122,13 @@ ProfScope::ProfScope(int cls, hipStream_t s) : cls_(cls), s_(s), rec_(nullptr) {
 ProfScope::~ProfScope() {
   if (!rec_) return;
   (void)hipEventRecord((*g_prof)[reinterpret_cast<size_t>(rec_) - 1].b, s_);
+}
+
+static unsigned long long* g_timeline = nullptr;
+static int g_timeline_cap = 0;
+void timeline_target(unsigned long long** buf, int* capacity_records) {
+  *buf = g_timeline;
+  *capacity_records = g_timeline_cap;
 }
 
 static int32_t validate_desc(const sbp_sample_desc* d) {
@@ -218,6 +226,21 @@ static int32_t validate_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, 
   return SBP_OK;
 }
 
+int32_t sbp_forward_cache_batch(const sbp_gather_item* items, int32_t n, int32_t dtype, void* stream) {
+  int eb = elem_bytes(dtype);
+  if (!eb) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
+  if (!items) return fail(SBP_ERR_NULL, "items is NULL");
+  if (n < 1 || n > SBP_MAX_BATCH_LAYERS) return fail(SBP_ERR_SHAPE, "need 1 <= n <= %d items, got %d", SBP_MAX_BATCH_LAYERS, n);
+  for (int i = 0; i < n; ++i) {
+    const sbp_gather_item& g = items[i];
+    if (g.reserved) return fail(SBP_ERR_FLAGS, "item %d: reserved field must be 0", i);
+    if (g.M < 1 || g.M > INT32_MAX || g.C < 1) return fail(SBP_ERR_SHAPE, "item %d: bad shape M=%lld C=%d", i, (long long)g.M, g.C);
+    if (g.K < 0 || g.K > g.M) return fail(SBP_ERR_SHAPE, "item %d: need 0 <= K <= M, got K=%lld M=%lld", i, (long long)g.K, (long long)g.M);
+    if (g.K > 0 && (!g.X || !g.idx || !g.X_k)) return fail(SBP_ERR_NULL, "item %d: X, idx and X_k must be non-NULL", i);
+  }
+  return launch_gather_rows_batch(items, n, eb, (hipStream_t)stream);
+}
+
 }  // extern "C"
 
 namespace sbp {
@@ -266,6 +289,38 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
   if (!dW && !db && !dX) return SBP_OK;
   return launch_backward_linear(p, dY, idx, inv, Xk, W, M, K, Cin, Cout, dtype, dW, db, dX, ws, flags,
                                 (hipStream_t)stream);
+}
+
+static int32_t check_batch(const sbp_linear_layer* layers, int32_t n, int32_t dtype) {
+  if (!layers) return fail(SBP_ERR_NULL, "layers is NULL");
+  if (n < 1 || n > SBP_MAX_BATCH_LAYERS) return fail(SBP_ERR_SHAPE, "need 1 <= n <= %d layers, got %d", SBP_MAX_BATCH_LAYERS, n);
+  for (int i = 0; i < n; ++i) {
+    const sbp_linear_layer& l = layers[i];
+    if (l.reserved) return fail(SBP_ERR_FLAGS, "layer %d: reserved field must be 0", i);
+    int32_t st = check_linear_args(l.dY, l.idx, l.X_k, l.W, l.M, l.K, l.Cin, l.Cout, dtype, l.dW, l.dX, l.flags);
+    if (st != SBP_OK) return st;
+  }
+  return SBP_OK;
+}
+
+size_t sbp_backward_linear_batch_workspace(const sbp_linear_layer* layers, int32_t n, int32_t dtype) {
+  if (!layers || n < 1 || n > SBP_MAX_BATCH_LAYERS || !elem_bytes(dtype)) return 0;
+  for (int i = 0; i < n; ++i)
+    if (validate_linear(layers[i].M, layers[i].K, layers[i].Cin, layers[i].Cout, dtype, layers[i].flags) != SBP_OK) return 0;
+  return plan_linear_batch(layers, n, dtype).bytes;
+}
+
+int32_t sbp_backward_linear_batch(const sbp_linear_layer* layers, int32_t n, int32_t dtype, void* ws, size_t ws_bytes,
+                                  void* stream) {
+  int32_t st = check_batch(layers, n, dtype);
+  if (st != SBP_OK) return st;
+  const BatchPlan p = plan_linear_batch(layers, n, dtype);
+  if (p.bytes) {
+    if (!ws) return fail(SBP_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", p.bytes);
+    if (ws_bytes < p.bytes) return fail(SBP_ERR_WORKSPACE, "workspace %zu bytes < %zu needed", ws_bytes, p.bytes);
+    if ((uintptr_t)ws % 256) return fail(SBP_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  }
+  return launch_backward_linear_batch(p, layers, dtype, ws, (hipStream_t)stream);
 }
 
 static int32_t validate_dw(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int32_t pad, int64_t K,
@@ -466,6 +521,14 @@ int32_t sbp_set_option(const char* name, const char* value) {
 
 int32_t sbp_profile_enable(int32_t on) {
   g_prof_on = on != 0;
+  return SBP_OK;
+}
+
+int32_t sbp_profile_timeline(void* records, int64_t capacity_records) {
+  if (capacity_records < 0 || capacity_records > INT32_MAX) return fail(SBP_ERR_SHAPE, "bad record capacity");
+  if (records && ((uintptr_t)records & 7)) return fail(SBP_ERR_SHAPE, "records must be 8-byte aligned");
+  g_timeline = records && capacity_records ? static_cast<unsigned long long*>(records) : nullptr;
+  g_timeline_cap = g_timeline ? (int)capacity_records : 0;
   return SBP_OK;
 }
 

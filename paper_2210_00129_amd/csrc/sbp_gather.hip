@@ -81,6 +81,63 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
   return check_launch("gather_rows");
 }
 
+// ---- several row gathers in one launch (the forward-side caches of all layers of a block) ----------------
+static constexpr int kMaxGatherBatch = SBP_MAX_BATCH_LAYERS;
+struct GatherItem {
+  const uint4* X; const int32_t* idx; uint4* Xk;
+  uint32_t total;            // 16-byte pieces of the item
+  FastDiv ppr;               // pieces per row
+  int blk_start, nblk;       // its blocks in the grid
+};
+struct GatherBatchArgs { int n; GatherItem it[kMaxGatherBatch]; };
+
+__global__ void __launch_bounds__(256) gather_rows_batch_kernel(const GatherBatchArgs a) {
+  int q = 0;
+  for (int i = 1; i < a.n; ++i)
+    if ((int)blockIdx.x >= a.it[i].blk_start) q = i;
+  const GatherItem& g = a.it[q];
+  const uint32_t stride = (uint32_t)g.nblk * 256u;
+  const uint32_t ppr = g.ppr.d;
+  for (uint32_t t = ((uint32_t)blockIdx.x - (uint32_t)g.blk_start) * 256u + threadIdx.x; t < g.total; t += stride) {
+    uint32_t j, c;
+    g.ppr.divmod(t, j, c);
+    g.Xk[t] = g.X[(long long)g.idx[j] * ppr + c];
+    if (stride > ~t) return;                                // the next step would wrap
+  }
+}
+
+int32_t launch_gather_rows_batch(const sbp_gather_item* items, int32_t n, int32_t elem_bytes, hipStream_t s) {
+  bool fused = n > 1 && n <= kMaxGatherBatch;
+  for (int i = 0; i < n && fused; ++i) {
+    const long long row_bytes = (long long)items[i].C * elem_bytes;
+    fused = items[i].K > 0 && row_bytes % 16 == 0 && ((uintptr_t)items[i].X % 16 == 0) && ((uintptr_t)items[i].X_k % 16 == 0) &&
+            items[i].K * (row_bytes / 16) < 0xFFFFFFFFll;
+  }
+  if (!fused) {
+    for (int i = 0; i < n; ++i) {
+      if (items[i].K == 0) continue;
+      const int32_t st = launch_gather_rows(items[i].X, items[i].idx, items[i].K, items[i].C, elem_bytes, items[i].X_k, s);
+      if (st != SBP_OK) return st;
+    }
+    return SBP_OK;
+  }
+  GatherBatchArgs a{};
+  a.n = n;
+  int blk = 0;
+  for (int i = 0; i < n; ++i) {
+    const uint32_t ppr = (uint32_t)((long long)items[i].C * elem_bytes / 16);
+    GatherItem& g = a.it[i];
+    g.X = static_cast<const uint4*>(items[i].X); g.idx = items[i].idx; g.Xk = static_cast<uint4*>(items[i].X_k);
+    g.total = (uint32_t)(items[i].K * ppr);
+    g.ppr = FastDiv(ppr);
+    g.blk_start = blk;
+    g.nblk = (int)std::min<long long>(ceil_div(g.total, 256), 256 * 64);
+    blk += g.nblk;
+  }
+  SBP_LAUNCH(SBP_PROF_GATHER, s, gather_rows_batch_kernel, dim3((unsigned)blk), dim3(256), 0, s, a);
+  return check_launch("gather_rows_batch");
+}
+
 // ------------------------------------------------------------------------------------------------
 // Down-sampling layers (convolution with kernel p x p and stride p: the paper's case s >= k, where
 // every output position owns its own patch of inputs and the layer behaves like a point-wise one).

@@ -25,6 +25,9 @@ struct ProfScope {
   void* rec_;
 };
 
+// Measurement aid: where the kernels that support it write per-workgroup time stamps (NULL, 0: nowhere).
+void timeline_target(unsigned long long** buf, int* capacity_records);
+
 #define SBP_LAUNCH(cls, stream, ...)             \
   do {                                            \
     ::sbp::ProfScope _prof_scope((cls), (stream)); \
@@ -43,6 +46,8 @@ struct Options {
   ShapePlan plans[8] = {};
   bool debug_plan = false;
   int  dw_rows = 0;
+  bool batch_spread = false;          // batched linear backward: units dealt to the XCDs in turn instead of in runs
+  bool batch_dynamic = false;         // batched linear backward: units taken from the XCD queues with atomic counters
   bool dw_separate = false, attn_plain = false, sampler_no_window = false, sampler_no_masks = false, patch_wide = false;
 };
 Options options();                    // a snapshot (taken under a lock; safe against a concurrent sbp_set_option)
@@ -57,6 +62,8 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
 // ---- row gather --------------------------------------------------------------------------
 int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t C, int32_t elem_bytes,
                            void* Xk, hipStream_t s);
+
+int32_t launch_gather_rows_batch(const sbp_gather_item* items, int32_t n, int32_t elem_bytes, hipStream_t s);
 
 // patches of a p x p, stride p down-sampling layer: gather [K, p*p*C] rows / scatter them back with zero fill
 int32_t launch_patches(bool scatter, const void* src, const int32_t* idx, const int32_t* inv, int32_t B, int32_t H, int32_t W,
@@ -89,6 +96,23 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
                                const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
                                int32_t dtype, void* dW, float* db, void* dX, void* ws, uint32_t flags,
                                hipStream_t s);
+
+// several independent layers in one launch
+struct BatchLayer {
+  int    dx_bm, splits, rows_per_split, db_slices, db_slice_rows;
+  bool   direct;        // a single split: the dW unit writes dW itself, nothing to reduce
+  size_t off, off_dbp, off_inv;   // workspace: split partials (layer-by-layer mode: the layer's whole workspace), db slices, inverse map
+};
+struct BatchPlan {
+  int    n;
+  bool   fused;         // one grid for all layers (else layer by layer)
+  BatchLayer lay[SBP_MAX_BATCH_LAYERS];
+  size_t off_counters;  // the eight queue counters of the common grid
+  size_t bytes;
+};
+BatchPlan plan_linear_batch(const sbp_linear_layer* layers, int32_t n, int32_t dtype);
+int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer* layers, int32_t dtype, void* ws,
+                                     hipStream_t s);
 
 // inv[idx[j]] = j (no clearing needed: row m is kept iff 0 <= inv[m] < K and idx[inv[m]] == m), and +0 into
 // the rows of out[M][row_bytes] that are not kept (row_bytes a multiple of 2)

@@ -157,6 +157,34 @@ __device__ __forceinline__ int segment_unit(int wg_global, int s, int n) {
   return before + congruent_below(x, wg_global) - congruent_below(x, s);
 }
 
+// One unit of the large-tile engine: kind 0 = dX tile number L, kind 1 / 2 = dW unit number L among the long /
+// short splits (a tile of dW over the kept rows of one split, written as an fp32 partial sum).
+__device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind, int L) {
+  const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
+  if (kind == 0) {
+    const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
+    if (a.dx_bm == 64)
+      big::dx_tile<64>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 64, tile_n * big::BT);
+    else if (a.dx_bm == 128)
+      big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT);
+    else
+      big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT);
+    return;
+  }
+  // the first n_big splits have rows_per_split rows each, the others rows_small
+  const int tiles_w = ((a.Cout + big::BT - 1) / big::BT) * tiles_n;
+  const int covered = min(a.K, a.n_big * a.rows_per_split);
+  const int sl = L / tiles_w;                                  // split within its kind
+  const int rem = L - sl * tiles_w;
+  const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
+  const int j0 = kind == 1 ? sl * a.rows_per_split : covered + sl * a.rows_small;
+  const int j1 = min(a.K, j0 + (kind == 1 ? a.rows_per_split : a.rows_small));
+  const int split = kind == 1 ? sl : a.n_big + sl;
+  float* part = a.part + (long long)split * a.Cout * a.Cin;
+  if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+  else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+}
+
 // The same work with 256 x 256 tiles (sbp_mfma_big.h): one workgroup per CU, so the order of the grid
 // is the order in which the CUs of an XCD pick work up: the longer kind of tile first, the shorter kind next,
 // the streaming helpers (zero fill, column sums) last, where they fill the CUs that run out of tiles.
@@ -187,31 +215,90 @@ __global__ void __launch_bounds__(256, 1) linear_big_kernel(const LinArgs a) {
     if (wg < seg_start + seg_n) break;
     seg_start += seg_n;
   }
-  const int L = segment_unit(wg, seg_start, seg_n);
-  const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
-  if (kind == 0) {
-    const int tile_m = L / tiles_n, tile_n = L - tile_m * tiles_n;
-    if (a.dx_bm == 64)
-      big::dx_tile<64>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 64, tile_n * big::BT);
-    else if (a.dx_bm == 128)
-      big::dx_tile<128>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 128, tile_n * big::BT);
-    else
-      big::dx_tile<256>(smem, a.dY, a.idx_in, a.idx_out, a.W, a.K, a.Cin, a.Cout, a.dX, tile_m * 256, tile_n * big::BT);
+  big_unit(smem, a, kind, segment_unit(wg, seg_start, seg_n));
+}
+
+// ---- several layers in one launch ----------------------------------------------------------------------
+// The backward of up to kMaxBatch independent layers as ONE grid: the units of all layers (dX tiles, dW units,
+// zero-fill and column-sum blocks) lie in the grid as segments, longest kind of unit first whatever its layer,
+// each segment spread over the eight XCD queues in contiguous runs (segment_unit).  A ViT block's four layers
+// are about 1000 units: the CUs stay busy until the short helper blocks at the end of the grid even out the
+// finish, where four separate launches each end with their longest unit and start with an empty chip.
+static constexpr int kMaxBatch = 8;
+static constexpr int kMaxEnt = 24;                  // entries of one XCD's queue
+// Workgroup i of a grid runs on XCD i % 8, and every XCD hands its workgroups to its 32 CUs in order.  The host
+// therefore writes one queue per XCD: entry = a run of consecutive units of one kind of one layer (kind 0 dX tiles,
+// 1 dW units, 3 zero-fill blocks, 4 column-sum blocks), entries in the order they are to start.  A layer's tiles
+// are kept on as few XCDs as the balance of work allows, as runs of neighbouring tiles: the operand panels they
+// share are then fetched into one L2 instead of eight.
+struct XcdEntry { int first_q, unit0; short layer; signed char kind, stride; };   // positions first_q .. next entry's first_q - 1 of the
+                                                                                  // queue are units unit0, unit0 + stride, ...
+struct MultiArgs {
+  int nent[kNumXCD], nq[kNumXCD];     // entries and units of every queue
+  int* counters;                      // [kNumXCD] in the workspace, zero at launch: next position of every queue
+  int timeline_cap, pad_;
+  unsigned long long* timeline;       // measurement aid (sbp_profile_timeline): 8 words per unit, or NULL
+  XcdEntry ent[kNumXCD][kMaxEnt];
+  LinArgs lay[kMaxBatch];
+};
+static_assert(sizeof(MultiArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
+// Grid = 8 x the longest queue; workgroup i serves position i / 8 of queue i % 8 (`dynamic` = 0), or (`dynamic` = 1)
+// takes the next position of its XCD's queue from an atomic counter and, when that queue is empty, of the other
+// queues, nearest first: XCDs that run out of their own units then help the others.  Workgroups that find nothing
+// leave at once.
+__global__ void __launch_bounds__(256, 1) linear_multi_kernel(const MultiArgs a, int dynamic) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int wg = blockIdx.x;
+  const int home = wg & (kNumXCD - 1);
+  int x = home, q = wg >> 3;
+  if (dynamic) {
+    int* ticket = reinterpret_cast<int*>(smem);
+    if (threadIdx.x == 0) {
+      int got = -1;
+      for (int t = 0; t < kNumXCD && got < 0; ++t) {
+        const int v = (home + t) & (kNumXCD - 1);
+        const int p = __hip_atomic_fetch_add(a.counters + v, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (p < a.nq[v]) got = (v << 24) | p;
+      }
+      *ticket = got;
+    }
+    __syncthreads();
+    const int got = __builtin_amdgcn_readfirstlane(*ticket);
+    __syncthreads();                               // the unit may now overwrite the ticket's place in LDS
+    if (got < 0) return;
+    x = got >> 24; q = got & 0xffffff;
+  } else if (q >= a.nq[x]) {
     return;
   }
-  // dW unit: a tile over the kept rows of one split; the first n_big splits have rows_per_split rows each, the
-  // others rows_small
-  const int tiles_w = ((a.Cout + big::BT - 1) / big::BT) * tiles_n;
-  const int covered = min(a.K, a.n_big * a.rows_per_split);
-  const int sl = L / tiles_w;                                  // split within its kind
-  const int rem = L - sl * tiles_w;
-  const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
-  const int j0 = kind == 1 ? sl * a.rows_per_split : covered + sl * a.rows_small;
-  const int j1 = min(a.K, j0 + (kind == 1 ? a.rows_per_split : a.rows_small));
-  const int split = kind == 1 ? sl : a.n_big + sl;
-  float* part = a.part + (long long)split * a.Cout * a.Cin;
-  if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
-  else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+  int e = 0;
+  for (int i = 1; i < a.nent[x]; ++i)
+    if (q >= a.ent[x][i].first_q) e = i;
+  const int kind = a.ent[x][e].kind, layer = a.ent[x][e].layer;
+  const int L = a.ent[x][e].unit0 + (q - a.ent[x][e].first_q) * a.ent[x][e].stride;
+  const LinArgs& la = a.lay[layer];
+  // measurement aid: the 100 MHz wall clock and the shader clock at the start and at the end of every unit
+  int slot = q;
+  for (int i = 0; i < x; ++i) slot += a.nq[i];
+  const bool stamp = a.timeline != nullptr && slot < a.timeline_cap;
+  unsigned long long t0 = 0, c0 = 0;
+  if (stamp) { t0 = wall_clock64(); c0 = clock64(); }
+  if (kind <= 2) {
+    big_unit(smem, la, kind, L);
+  } else if (kind == 3) {
+    zero_rows_block(la, L);                        // la.n_zero = number of these blocks
+  } else {
+    const int nslice = (la.K + la.db_slice_rows - 1) / la.db_slice_rows;
+    const int slice = L % nslice, chunk = L / nslice;
+    const int j0 = slice * la.db_slice_rows, j1 = min(la.K, j0 + la.db_slice_rows);
+    colsum_block<16>(smem, la.dY, la.idx_in, la.Cout, j0, j1, chunk * 256, la.dbp + (long long)slice * la.Cout);
+  }
+  if (stamp && threadIdx.x == 0) {
+    unsigned long long* rec = a.timeline + 8ll * slot;
+    rec[0] = t0; rec[1] = wall_clock64(); rec[2] = c0; rec[3] = clock64();
+    rec[4] = (unsigned long long)kind | ((unsigned long long)layer << 8) | ((unsigned long long)L << 16);
+    rec[5] = (unsigned long long)x | ((unsigned long long)home << 8) | ((unsigned long long)wg << 16);
+  }
 }
 
 // dW = sum_s partial[s] (+ dW), db = sum_s dbp[s] (+ db): fixed summation order.  G lanes share an output: lane g
@@ -872,6 +959,429 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   if (scatter && !use_mfma)   // the MFMA launch zero-fills by itself
     launch_zero_dropped_rows(idx, inv, K, M, (int64_t)Cin * eb, dX, s);
   return check_launch("backward_linear");
+}
+
+// ------------------------------------------------------------------------------------------------
+// Several independent layers in one launch (linear_multi_kernel) + one reduction launch.
+// ------------------------------------------------------------------------------------------------
+struct RedLayer {
+  const float* part; const float* dbp; void* dW; float* db;
+  long long nW;
+  int nsplit_w, nsplit_b, Cout, accumulate, bf16out, blk_start, nblk;
+};
+struct RedMultiArgs { int n; RedLayer lay[kMaxBatch]; };
+
+// the split reduction of every layer of a batch: blocks [blk_start, blk_start + nblk) serve layer i; per output the
+// partial sums are added in split order (fixed order, as in reduce_splits_kernel with one lane per output)
+__global__ void __launch_bounds__(NTHREADS) reduce_multi_kernel(const RedMultiArgs a) {
+  int li = 0;
+  for (int i = 1; i < a.n; ++i)
+    if ((int)blockIdx.x >= a.lay[i].blk_start) li = i;
+  const RedLayer& r = a.lay[li];
+  const long long nW4 = r.dW ? r.nW / 4 : 0;
+  const long long total = nW4 + (r.db ? r.Cout : 0);
+  const long long first = ((long long)blockIdx.x - r.blk_start) * NTHREADS + threadIdx.x;
+  for (long long e = first; e < total; e += (long long)r.nblk * NTHREADS) {
+    if (e < nW4) {
+      float4 acc = make_float4(0, 0, 0, 0);
+      for (int s0 = 0; s0 < r.nsplit_w; s0 += 4) {
+        float4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          p[u] = s0 + u < r.nsplit_w ? reinterpret_cast<const float4*>(r.part + (long long)(s0 + u) * r.nW)[e]
+                                     : make_float4(0, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { acc.x += p[u].x; acc.y += p[u].y; acc.z += p[u].z; acc.w += p[u].w; }
+      }
+      if (r.bf16out) {
+        if (r.accumulate) {
+          const float4 old = load_dw4<true>(r.dW, e);
+          acc.x = old.x + acc.x; acc.y = old.y + acc.y; acc.z = old.z + acc.z; acc.w = old.w + acc.w;
+        }
+        store_dw4<true>(r.dW, e, acc);
+      } else {
+        if (r.accumulate) {
+          const float4 old = load_dw4<false>(r.dW, e);
+          acc.x = old.x + acc.x; acc.y = old.y + acc.y; acc.z = old.z + acc.z; acc.w = old.w + acc.w;
+        }
+        store_dw4<false>(r.dW, e, acc);
+      }
+    } else {
+      const long long o = e - nW4;
+      float acc = 0.f;
+      for (int s0 = 0; s0 < r.nsplit_b; s0 += 8) {
+        float p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = s0 + u < r.nsplit_b ? r.dbp[(long long)(s0 + u) * r.Cout + o] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += p[u];
+      }
+      r.db[o] = r.accumulate ? r.db[o] + acc : acc;
+    }
+  }
+}
+
+// Is this layer one the multi-layer launch can take?  (bf16 on the matrix cores, the large-tile engine's limits,
+// something kept, 16-byte aligned tensors; everything else runs layer by layer.)
+static bool batch_layer_fits(const sbp_linear_layer& l, int32_t dtype) {
+  if (dtype != SBP_BF16 || l.K < 1) return false;
+  if (l.Cin % 8 || l.Cout % big::KB) return false;
+  if ((uint64_t)l.M * (uint64_t)std::max(l.Cin, l.Cout) * 2u >= (1ull << 32)) return false;
+  if (ceil_div(l.K, kBigMaxRowsPerSplit) > 64) return false;
+  if (((uintptr_t)l.dY | (uintptr_t)l.X_k | (uintptr_t)l.W | (uintptr_t)l.dX) & 15) return false;
+  if (l.dW && (l.flags & SBP_FLAG_DW_OUT_BF16) == 0 && ((uintptr_t)l.dW & 15)) return false;
+  return true;
+}
+
+// Unit costs inside a batched launch, read from the per-unit time stamps of the ViT-Base block (sbp_profile_timeline) with
+// the per-XCD queues in place: every CU is in matrix-core code for the whole launch and the chip then runs at 1.6-1.7 GHz
+// (1.3 GHz before the queues cut the traffic between the L2s and memory by a third); dW units of 99 / 66 stages took
+// 95 / 63 us, dX tiles of 96 / 72 / 24 stages 89 / 67 / 29 us.  The shorter dX tiles are scaled as in the single-layer costs.
+static constexpr int64_t kNsFixedBatchDw = 3000, kNsStageBatchDw = 930, kNsFixedBatch = 9000, kNsStageBatch256 = 830,
+                         kNsStageBatch128 = 500, kNsStageBatch64 = 400;
+struct BatchLayerChoice { int dx_bm, splits; };
+static int64_t split_rows(int64_t K, int64_t splits) { return ceil_div(ceil_div(K, splits), 64) * 64; }   // rows of each equal split
+
+// The jobs of a batch for given per-layer choices: {units, unit length, layer, kind}.
+struct Job { int64_t n, len; int layer, kind; };
+static constexpr int kMaxJobs = 4 * kMaxBatch;
+static int batch_jobs(const sbp_linear_layer* L, int n, const BatchLayerChoice* c, Job* out, double* reduce_ns) {
+  int nj = 0;
+  double red = 0;
+  for (int i = 0; i < n; ++i) {
+    const sbp_linear_layer& l = L[i];
+    const int64_t tiles_n = ceil_div(l.Cin, big::BT), tiles_w = ceil_div(l.Cout, big::BT) * tiles_n, nk_x = l.Cout / big::KB;
+    if (l.dX) {
+      const int bm = c[i].dx_bm;
+      const int64_t len = kNsFixedBatch + (bm == 256 ? kNsStageBatch256 : (bm == 128 ? kNsStageBatch128 : kNsStageBatch64)) * nk_x;
+      out[nj++] = Job{ceil_div(l.K, bm) * tiles_n, len, i, 0};
+      if (!(l.flags & SBP_FLAG_DX_COMPACT) && l.M > l.K) {
+        const int64_t nz = big_zero_blocks(l.M);
+        out[nj++] = Job{nz, kNsFixedHelper + (l.M - l.K) * l.Cin * 2 / nz / kHelperBytesPerNs, i, 3};
+      }
+    }
+    if (l.dW) {
+      const int64_t rps = split_rows(l.K, c[i].splits);
+      const int64_t nsp = ceil_div(l.K, rps);
+      out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + kNsStageBatchDw * ceil_div(std::min<int64_t>(rps, l.K), big::KB), i, 1};
+      const bool direct = nsp == 1 && !(l.flags & (SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16));
+      if (!direct) red += (double)(nsp + 1) * l.Cout * l.Cin * 4.0 / kReduceBytesPerNs;
+    }
+    if (l.db) {
+      const int64_t slice_rows = db_slice_rows_for(l.K, true);
+      out[nj++] = Job{ceil_div(l.Cout, 256) * ceil_div(l.K, slice_rows), kNsFixedHelper + slice_rows * 512 / kHelperBytesPerNs, i, 4};
+    }
+  }
+  *reduce_ns = red;
+  return nj;
+}
+
+// The eight queues, by simulated list scheduling: units in the order longest kind first (helpers last), each to the
+// XCD whose next CU frees first - but the XCD that took the previous unit keeps taking units while one of its CUs is
+// (nearly) as early: consecutive units of a job, which share operand panels, land in one L2 in runs of a round of 32
+// or more, a job lies on as few XCDs as an even finish allows, and short units fill what the long ones leave.  The
+// queues list the units of an XCD in the order of their simulated starts.  Returns the simulated finish time in ns,
+// or -1 if a queue would need more than kMaxEnt entries.
+struct XcdQueues {
+  int nent[kNumXCD], nq[kNumXCD];
+  XcdEntry ent[kNumXCD][kMaxEnt];
+  int64_t len[kNumXCD][kMaxEnt];
+  int cnt[kNumXCD][kMaxEnt];
+};
+static int64_t partition_xcd(const Job* jobs, int nj, XcdQueues* out) {
+  XcdQueues& Q = *out;
+  const bool spread = options().batch_spread;     // override: no affinity, consecutive units on consecutive XCDs
+  int order[kMaxJobs];
+  for (int j = 0; j < nj; ++j) order[j] = j;
+  std::stable_sort(order, order + nj, [&](int u, int v) {
+    const bool hu = jobs[u].kind > 2, hv = jobs[v].kind > 2;
+    return hu != hv ? hv : jobs[u].len > jobs[v].len;
+  });
+  using MinHeap = std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>>;
+  MinHeap cu[kNumXCD];
+  for (int x = 0; x < kNumXCD; ++x) {
+    Q.nent[x] = Q.nq[x] = 0;
+    for (int i = 0; i < kNumCU / kNumXCD; ++i) cu[x].push(0);
+  }
+  int64_t end = 0;
+  int cur = 0;
+  for (int t = 0; t < nj; ++t) {
+    const Job& jb = jobs[order[t]];
+    const int64_t slack = spread ? 0 : jb.len / 4;
+    for (int64_t u = 0; u < jb.n; ++u) {
+      if (spread) cur = (cur + 1) & (kNumXCD - 1);
+      int best = cur;
+      for (int x = 0; x < kNumXCD; ++x)
+        if (cu[x].top() + (x == cur ? 0 : slack) < cu[best].top() + (best == cur ? 0 : slack)) best = x;
+      const int64_t fin = cu[best].top() + jb.len;
+      cu[best].pop();
+      cu[best].push(fin);
+      end = std::max(end, fin);
+      cur = best;
+      int& ne = Q.nent[best];
+      XcdEntry* last = ne > 0 ? &Q.ent[best][ne - 1] : nullptr;
+      const bool same_job = last && last->layer == jb.layer && last->kind == jb.kind;
+      if (same_job && Q.cnt[best][ne - 1] == 1 && u > last->unit0 && u - last->unit0 < 128) {
+        last->stride = (signed char)(u - last->unit0);          // the second unit of a run fixes its stride
+        ++Q.cnt[best][ne - 1];
+      } else if (same_job && Q.cnt[best][ne - 1] > 1 && last->unit0 + (int64_t)Q.cnt[best][ne - 1] * last->stride == u) {
+        ++Q.cnt[best][ne - 1];
+      } else {
+        if (ne == kMaxEnt) return -1;
+        Q.ent[best][ne] = XcdEntry{Q.nq[best], (int)u, (short)jb.layer, (signed char)jb.kind, 1};
+        Q.len[best][ne] = jb.len;
+        Q.cnt[best][ne] = 1;
+        ++ne;
+      }
+      ++Q.nq[best];
+    }
+  }
+  return end;
+}
+
+static double batch_cost(const sbp_linear_layer* L, int n, const BatchLayerChoice* c) {
+  Job jobs[kMaxJobs];
+  double red = 0;
+  const int nj = batch_jobs(L, n, c, jobs, &red);
+  XcdQueues Q;
+  const int64_t end = partition_xcd(jobs, nj, &Q);
+  if (end < 0) return 1e30;
+  return (double)end + (red > 0 ? 3000.0 + red : 0.0);
+}
+
+// Per-layer tile height and split count of a batch: coordinate descent on the simulated finish time of the whole
+// grid plus the reduction's time, from tall tiles and two splits; cached per batch signature.
+static void choose_batch(const sbp_linear_layer* L, int n, BatchLayerChoice* c) {
+  struct Key { int64_t M, K; int32_t Cin, Cout; uint32_t flags; int want; };
+  struct Entry { int n; Key k[kMaxBatch]; BatchLayerChoice c[kMaxBatch]; };
+  thread_local Entry cache[8] = {};
+  thread_local int next = 0;
+  Key key[kMaxBatch];
+  for (int i = 0; i < n; ++i)
+    key[i] = Key{L[i].M, L[i].K, L[i].Cin, L[i].Cout, L[i].flags, (L[i].dW ? 1 : 0) | (L[i].db ? 2 : 0) | (L[i].dX ? 4 : 0)};
+  const Options opt = options();
+  int min_splits[kMaxBatch];
+  for (int i = 0; i < n; ++i) min_splits[i] = (int)ceil_div(L[i].K, kBigMaxRowsPerSplit);
+  auto overrides = [&]() {                        // explicit overrides (tests, sweeps) on top of the automatic choice
+    for (int i = 0; i < n; ++i) {
+      if (opt.dxbm) c[i].dx_bm = opt.dxbm;
+      if (opt.splits) c[i].splits = std::max(opt.splits, min_splits[i]);
+    }
+  };
+  for (const Entry& e : cache) {
+    if (e.n != n) continue;
+    bool same = true;
+    for (int i = 0; i < n && same; ++i)
+      same = e.k[i].M == key[i].M && e.k[i].K == key[i].K && e.k[i].Cin == key[i].Cin && e.k[i].Cout == key[i].Cout &&
+             e.k[i].flags == key[i].flags && e.k[i].want == key[i].want;
+    if (same) { for (int i = 0; i < n; ++i) c[i] = e.c[i]; overrides(); return; }
+  }
+  for (int i = 0; i < n; ++i) c[i] = BatchLayerChoice{256, std::max(min_splits[i], L[i].K >= 2048 ? 2 : 1)};
+  double best = batch_cost(L, n, c);
+  for (int pass = 0; pass < 2; ++pass)
+    for (int i = 0; i < n; ++i) {
+      const BatchLayerChoice start = c[i];
+      BatchLayerChoice arg = start;
+      for (int bm : {256, 128, 64}) {
+        if (!L[i].dX && bm != 256) continue;
+        for (int sp = min_splits[i]; sp < min_splits[i] + 8; ++sp) {
+          if (!L[i].dW && sp != min_splits[i]) continue;
+          if (sp > 1 && ceil_div(L[i].K, sp) < 512) break;        // splits shorter than 16 stages do not pay
+          c[i] = BatchLayerChoice{bm, sp};
+          const double cost = batch_cost(L, n, c);
+          if (cost < best) { best = cost; arg = c[i]; }
+        }
+      }
+      c[i] = arg;
+    }
+  if (opt.debug_plan) {
+    std::fprintf(stderr, "sbp batch plan (%d layers, simulated %.1f us):", n, best / 1e3);
+    for (int i = 0; i < n; ++i) std::fprintf(stderr, " [%d->%d K=%lld: dx rows %d, %d splits]", L[i].Cin, L[i].Cout, (long long)L[i].K, c[i].dx_bm, c[i].splits);
+    std::fprintf(stderr, "\n");
+  }
+  Entry& e = cache[next];
+  next = (next + 1) % 8;
+  e.n = n;
+  for (int i = 0; i < n; ++i) { e.k[i] = key[i]; e.c[i] = c[i]; }
+  overrides();
+}
+
+BatchPlan plan_linear_batch(const sbp_linear_layer* L, int32_t n, int32_t dtype) {
+  BatchPlan p{};
+  p.n = n;
+  p.fused = n >= 1 && n <= kMaxBatch;
+  for (int i = 0; i < n && p.fused; ++i) p.fused = batch_layer_fits(L[i], dtype);
+  // layer by layer: every layer gets its own piece of the workspace.  The size returned covers both modes, so that
+  // a size query made with other (e.g. differently aligned) addresses than the call still holds.
+  size_t off = 0, seq_bytes = 0;
+  for (int i = 0; i < n; ++i) {
+    if (!p.fused) p.lay[i].off = seq_bytes;
+    seq_bytes += align_up(plan_linear(L[i].M, L[i].K, L[i].Cin, L[i].Cout, dtype, L[i].flags).bytes, 256);
+  }
+  p.bytes = seq_bytes;
+  if (!p.fused) return p;
+  BatchLayerChoice c[kMaxBatch];
+  choose_batch(L, n, c);
+  for (int i = 0; i < n; ++i) {
+    const sbp_linear_layer& l = L[i];
+    BatchLayer& b = p.lay[i];
+    b.dx_bm = c[i].dx_bm;
+    // (fewer splits than asked for may cover K once their length is rounded up: iterate to the fixed point, so that
+    // the unit tables, which are rebuilt from `splits` at every launch, agree with these numbers)
+    b.splits = c[i].splits;
+    for (;;) {
+      b.rows_per_split = (int)split_rows(l.K, b.splits);
+      const int covered = (int)ceil_div(l.K, b.rows_per_split);
+      if (covered == b.splits) break;
+      b.splits = covered;
+    }
+    b.direct = l.dW && b.splits == 1 && !(l.flags & (SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16));
+    b.db_slice_rows = db_slice_rows_for(l.K, true);
+    b.db_slices = (int)ceil_div(l.K, b.db_slice_rows);
+    b.off = off;
+    if (l.dW && !b.direct) off += align_up((size_t)b.splits * l.Cout * l.Cin * sizeof(float), 256);
+    b.off_dbp = off;
+    if (l.db) off += align_up((size_t)b.db_slices * l.Cout * sizeof(float), 256);
+    b.off_inv = off;
+    if (l.dX && !(l.flags & SBP_FLAG_DX_COMPACT) && !l.inv) off += align_up((size_t)l.M * sizeof(int32_t), 256);
+  }
+  p.off_counters = off;
+  off += 256;
+  p.bytes = std::max(off, seq_bytes);
+  if (options().debug_plan) {
+    Job jobs[kMaxJobs];
+    double red = 0;
+    const int nj = batch_jobs(L, n, c, jobs, &red);
+    XcdQueues Q;
+    const int64_t end = partition_xcd(jobs, nj, &Q);
+    std::fprintf(stderr, "sbp batch queues: simulated end %.1f us, reduction %.1f us\n", end / 1e3, red / 1e3);
+    for (int x = 0; x < kNumXCD && end >= 0; ++x) {
+      std::fprintf(stderr, "  xcd %d (%d workgroups):", x, Q.nq[x]);
+      for (int e = 0; e < Q.nent[x]; ++e)
+        std::fprintf(stderr, " L%d.k%d[%d +%dx%d) %.0fus", Q.ent[x][e].layer, Q.ent[x][e].kind, Q.ent[x][e].unit0, Q.cnt[x][e], Q.ent[x][e].stride, Q.len[x][e] / 1e3);
+      std::fprintf(stderr, "\n");
+    }
+  }
+  return p;
+}
+
+int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer* L, int32_t dtype, void* ws, hipStream_t s) {
+  char* wsb = static_cast<char*>(ws);
+  if (!p.fused) {
+    for (int i = 0; i < p.n; ++i) {
+      const sbp_linear_layer& l = L[i];
+      if (!l.dW && !l.db && !l.dX) continue;
+      const LinearPlan lp = plan_linear(l.M, l.K, l.Cin, l.Cout, dtype, l.flags);
+      const int32_t st = launch_backward_linear(lp, l.dY, l.idx, l.inv, l.X_k, l.W, l.M, l.K, l.Cin, l.Cout, dtype, l.dW,
+                                                l.db, l.dX, wsb + p.lay[i].off, l.flags, s);
+      if (st != SBP_OK) return st;
+    }
+    return SBP_OK;
+  }
+  MultiArgs a{};
+  RedMultiArgs r{};
+  BatchLayerChoice c[kMaxBatch];
+  size_t lds = 0;
+  bool any = false, any_reduce = false;
+  for (int i = 0; i < p.n; ++i) {
+    const sbp_linear_layer& l = L[i];
+    const BatchLayer& b = p.lay[i];
+    c[i] = BatchLayerChoice{b.dx_bm, b.splits};
+    const bool dy_compact = l.flags & SBP_FLAG_DY_COMPACT, dx_compact = l.flags & SBP_FLAG_DX_COMPACT;
+    const bool scatter = l.dX && !dx_compact;
+    const int32_t* inv = l.inv;
+    if (scatter && !inv && l.M > l.K) {
+      int32_t* inv_ws = reinterpret_cast<int32_t*>(wsb + b.off_inv);
+      launch_build_inverse(l.idx, l.K, inv_ws, s);
+      inv = inv_ws;
+    }
+    LinArgs& la = a.lay[i];
+    la.dY = static_cast<const uint16_t*>(l.dY);
+    la.idx_in = dy_compact ? nullptr : l.idx;
+    la.idx_out = dx_compact ? nullptr : l.idx;
+    la.idx = l.idx; la.inv = inv;
+    la.Xk = static_cast<const uint16_t*>(l.X_k); la.W = static_cast<const uint16_t*>(l.W);
+    la.dX = static_cast<uint16_t*>(l.dX);
+    la.part = b.direct ? static_cast<float*>(l.dW) : reinterpret_cast<float*>(wsb + b.off);
+    la.dbp = l.db ? reinterpret_cast<float*>(wsb + b.off_dbp) : nullptr;
+    la.K = (int)l.K; la.M = (int)l.M; la.Cin = l.Cin; la.Cout = l.Cout;
+    la.rows_per_split = b.rows_per_split; la.db_slice_rows = b.db_slice_rows;
+    la.n_big = b.splits; la.rows_small = 0; la.dx_bm = b.dx_bm;
+    la.n_zero = scatter && l.M > l.K ? big_zero_blocks(l.M) : 0;
+    lds = std::max(lds, (size_t)big::RING + std::max<size_t>((size_t)(b.rows_per_split + 2 * big::KB), big::BT) * sizeof(int));
+    lds = std::max<size_t>(lds, 16 * 1024);     // the column-sum blocks' staging
+    any = any || l.dW || l.db || l.dX;
+    RedLayer& rl = r.lay[i];
+    rl.part = la.part; rl.dbp = la.dbp;
+    rl.dW = b.direct ? nullptr : l.dW; rl.db = l.db;
+    rl.nW = (long long)l.Cin * l.Cout;
+    rl.nsplit_w = b.splits; rl.nsplit_b = b.db_slices; rl.Cout = l.Cout;
+    rl.accumulate = (l.flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
+    rl.bf16out = (l.flags & SBP_FLAG_DW_OUT_BF16) ? 1 : 0;
+    any_reduce = any_reduce || rl.dW || rl.db;
+  }
+  if (!any) return SBP_OK;
+  Job jobs[kMaxJobs];
+  double red_ns = 0;
+  const int nj = batch_jobs(L, p.n, c, jobs, &red_ns);
+  // the unit counts must describe exactly the work the per-layer arguments imply: checked here, on the host
+  for (int j = 0; j < nj; ++j) {
+    const LinArgs& la = a.lay[jobs[j].layer];
+    const int64_t tiles_n = ceil_div(la.Cin, big::BT), tiles_w = ceil_div(la.Cout, big::BT) * tiles_n;
+    const int64_t expect = jobs[j].kind == 0 ? ceil_div(la.K, la.dx_bm) * tiles_n
+                         : jobs[j].kind == 1 ? tiles_w * la.n_big
+                         : jobs[j].kind == 3 ? la.n_zero
+                         : jobs[j].kind == 4 ? ceil_div(la.Cout, 256) * ceil_div(la.K, la.db_slice_rows) : -1;
+    if (jobs[j].n != expect || (int64_t)la.n_big * la.rows_per_split < la.K || jobs[j].n <= 0)
+      return fail(SBP_ERR_SHAPE, "backward_linear_batch: inconsistent unit table (layer %d, kind %d)", jobs[j].layer, jobs[j].kind);
+  }
+  XcdQueues Q;
+  if (partition_xcd(jobs, nj, &Q) < 0) return fail(SBP_ERR_SHAPE, "backward_linear_batch: queue table overflow");
+  int longest = 0;
+  int64_t covered[kMaxJobs] = {};
+  for (int x = 0; x < kNumXCD; ++x) {
+    a.nent[x] = Q.nent[x]; a.nq[x] = Q.nq[x];
+    longest = std::max(longest, Q.nq[x]);
+    for (int e = 0; e < Q.nent[x]; ++e) {
+      a.ent[x][e] = Q.ent[x][e];
+      for (int j = 0; j < nj; ++j)      // every entry must lie inside its job's unit range
+        if (jobs[j].layer == Q.ent[x][e].layer && jobs[j].kind == Q.ent[x][e].kind) {
+          if (Q.ent[x][e].unit0 < 0 || Q.ent[x][e].stride < 1 ||
+              Q.ent[x][e].unit0 + (int64_t)(Q.cnt[x][e] - 1) * Q.ent[x][e].stride >= jobs[j].n)
+            return fail(SBP_ERR_SHAPE, "backward_linear_batch: queue entry outside its job");
+          covered[j] += Q.cnt[x][e];
+        }
+    }
+  }
+  for (int j = 0; j < nj; ++j)
+    if (covered[j] != jobs[j].n) return fail(SBP_ERR_SHAPE, "backward_linear_batch: queues do not cover job %d", j);
+  timeline_target(&a.timeline, &a.timeline_cap);
+  if (longest > 0) {
+    a.counters = reinterpret_cast<int*>(wsb + p.off_counters);
+    const int dynamic = options().batch_dynamic ? 1 : 0;
+    int grid = kNumXCD * longest;
+    if (dynamic) {          // the same number of workgroups on every XCD, a quarter more than an even share of the units
+      int total = 0;
+      for (int x = 0; x < kNumXCD; ++x) total += Q.nq[x];
+      grid = kNumXCD * (int)ceil_div((int64_t)total * 5, 4 * kNumXCD);
+      SBP_LAUNCH(SBP_PROF_OTHER, s, fill_zero_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(a.counters), (long long)kNumXCD);
+    }
+    allow_big_lds(linear_multi_kernel, lds);
+    SBP_LAUNCH(SBP_PROF_DW_GEMM, s, linear_multi_kernel, dim3((unsigned)grid), dim3(256), lds, s, a, dynamic);
+  }
+  if (any_reduce) {
+    r.n = p.n;
+    int blk = 0;
+    for (int i = 0; i < p.n; ++i) {
+      RedLayer& rl = r.lay[i];
+      const long long total = (rl.dW ? rl.nW / 4 : 0) + (rl.db ? rl.Cout : 0);
+      rl.blk_start = blk;
+      rl.nblk = (int)std::min<long long>(ceil_div(total, NTHREADS), 2048);
+      blk += rl.nblk;
+    }
+    if (blk > 0) SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_multi_kernel, dim3((unsigned)blk), dim3(NTHREADS), 0, s, r);
+  }
+  return check_launch("backward_linear_batch");
 }
 
 }  // namespace sbp

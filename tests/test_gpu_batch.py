@@ -1,0 +1,164 @@
+"""GPU parity of sbp_backward_linear_batch: several independent layers in one call (one grid for all their units
+plus one reduction launch) against the CPU oracle layer by layer, and bit for bit against sbp_backward_linear on
+exactly representable inputs."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2210_00129_amd as sbp
+import synth_inputs as si
+from gpu_util import TOL_BF16_TIGHT, TOL_F32, bits, f64, nerr
+
+pytestmark = pytest.mark.gpu
+
+
+def _layer(B, P, H, W, Cin, Cout, k, seed, flags=0, dtype="bf16", ints=False):
+    M = B * (P + H * W)
+    if ints:
+        X = si.small_ints((M, Cin), -2, 2, seed, dtype); Wt = si.small_ints((Cout, Cin), -2, 2, seed + 1, dtype)
+        dY = si.small_ints((M, Cout), -2, 2, seed + 2, dtype)
+    else:
+        X, Wt, dY = si.linear_case(M, Cin, Cout, seed, dtype)
+    idx = oracle.sample_indices(B, P, H, W, k, seed, 500 + seed)
+    return dict(M=M, X=X, W=Wt, dY=dY, idx=idx, flags=flags)
+
+
+def _to_device(c, with_inv):
+    idx = torch.from_numpy(c["idx"]).cuda()
+    Xk = sbp.forward_cache(c["X"].cuda(), idx)
+    dY = c["dY"].cuda()
+    if c["flags"] & sbp.FLAG_DY_COMPACT:
+        dY = dY[idx.long()].contiguous()
+    d = dict(dY=dY, idx=idx, X_k=Xk, W=c["W"].cuda(), M=c["M"], flags=c["flags"])
+    if with_inv:
+        d["inv"] = torch.from_numpy(oracle.inverse_map(c["idx"], c["M"])).cuda()
+    return d
+
+
+def _check_against_oracle(c, out, dtype="bf16"):
+    dW, db, dX = out
+    idx, M = c["idx"], c["M"]
+    rW, rb, rX = oracle.backward_linear(si.to_f64(c["dY"]), idx, si.to_f64(c["X"])[idx], si.to_f64(c["W"]), M)
+    tol = TOL_F32 if dtype == "f32" else TOL_BF16_TIGHT
+    if dW is not None:
+        assert nerr(f64(dW), rW) <= (TOL_BF16_TIGHT if dW.dtype == torch.bfloat16 else TOL_F32)
+    if db is not None:
+        assert nerr(f64(db), rb) <= TOL_F32
+    if dX is not None:
+        if c["flags"] & sbp.FLAG_DX_COMPACT:
+            assert nerr(f64(dX), rX[idx]) <= tol
+        else:
+            assert nerr(f64(dX), rX) <= tol
+            assert np.all(bits(dX)[np.setdiff1d(np.arange(M), idx)] == 0)
+
+
+def _run(cases, with_inv=True, want=("dW", "db", "dX"), dtype="bf16"):
+    outs = sbp.backward_linear_batch([_to_device(c, with_inv) for c in cases], want=want)
+    torch.cuda.synchronize()
+    for c, o in zip(cases, outs):
+        _check_against_oracle(c, o, dtype)
+    return outs
+
+
+@pytest.mark.parametrize("with_inv", [True, False])
+def test_batch_of_ragged_layers_with_every_flag_combination(with_inv):
+    # four layers of different shapes, keep ratios and flags in one grid: partial tiles in every dimension, partial
+    # last stages, scattered and compact rows side by side
+    CF, CY = sbp.FLAG_DX_COMPACT, sbp.FLAG_DY_COMPACT
+    cases = [_layer(6, 1, 14, 14, 192, 768, 2, 11), _layer(6, 1, 14, 14, 264, 160, 1, 12, flags=CF),
+             _layer(5, 0, 10, 12, 72, 224, 3, 13, flags=CY), _layer(6, 1, 14, 14, 320, 288, 4, 14, flags=CF | CY)]
+    _run(cases, with_inv)
+
+
+@pytest.mark.parametrize("opts", [dict(), dict(dxbm=64), dict(dxbm=128, splits=3), dict(dxbm=256, splits=1), dict(splits=7)])
+def test_batch_tile_heights_and_split_counts(opts):
+    cases = [_layer(16, 1, 14, 14, 320, 288, 3, 21), _layer(16, 1, 14, 14, 288, 320, 2, 22)]
+    with sbp.options(**opts):
+        _run(cases)
+
+
+def test_batch_single_layer_and_single_outputs():
+    c = _layer(8, 1, 14, 14, 256, 512, 2, 31)
+    full = _run([c])[0]
+    for i, name in enumerate(("dW", "db", "dX")):
+        one = sbp.backward_linear_batch([_to_device(c, True)], want=(name,))[0]
+        assert [o is not None for o in one] == [j == i for j in range(3)]
+        _check_against_oracle(c, one)
+    # weight gradients of several layers only (the deferred-dW use of a dependent chain): no dX anywhere
+    cases = [_layer(8, 1, 14, 14, 256, 512, 2, 32), _layer(8, 1, 14, 14, 512, 256, 2, 33)]
+    outs = _run(cases, want=("dW", "db"))
+    assert all(o[2] is None for o in outs)
+    assert full[0] is not None
+
+
+def test_batch_equals_single_layer_calls_bit_for_bit_on_integers():
+    cases = [_layer(8, 1, 14, 14, 320, 288, 2, 41, ints=True), _layer(8, 1, 14, 14, 64, 96, 3, 44, ints=True)]
+    dev = [_to_device(c, True) for c in cases]
+    outs = sbp.backward_linear_batch(dev)
+    for d, o in zip(dev, outs):
+        ref = sbp.backward_linear(d["dY"], d["idx"], d["X_k"], d["W"], M=d["M"], inv=d["inv"])
+        for a, b in zip(o, ref):
+            assert np.array_equal(bits(a), bits(b))
+
+
+def test_batch_accumulate_and_bf16_weight_gradient():
+    c0 = _layer(8, 1, 14, 14, 128, 256, 2, 51, flags=sbp.FLAG_ACCUMULATE_DW)
+    c1 = _layer(8, 1, 14, 14, 256, 128, 2, 52, flags=sbp.FLAG_DW_OUT_BF16)
+    d0, d1 = _to_device(c0, True), _to_device(c1, True)
+    d0["dW"] = torch.full((256, 128), 2.0, dtype=torch.float32, device="cuda")
+    d0["db"] = torch.full((256,), -1.0, dtype=torch.float32, device="cuda")
+    with sbp.options(splits=1):          # a single split may not take the direct-write path with these flags
+        (dW0, db0, _), (dW1, db1, _) = sbp.backward_linear_batch([d0, d1])
+        plain = sbp.backward_linear_batch([dict(d1, flags=0)])[0]          # same single split, written directly as fp32
+    rW0, rb0, _ = oracle.backward_linear(si.to_f64(c0["dY"]), c0["idx"], si.to_f64(c0["X"])[c0["idx"]], si.to_f64(c0["W"]), c0["M"])
+    assert nerr(f64(dW0), rW0 + 2.0) <= TOL_F32 and nerr(f64(db0), rb0 - 1.0) <= TOL_F32
+    assert dW1.dtype == torch.bfloat16 and np.array_equal(bits(dW1), bits(plain[0].to(torch.bfloat16)))
+    _check_against_oracle(c1, (dW1, db1, None))
+
+
+def test_batch_with_a_layer_outside_the_fused_path_runs_layer_by_layer():
+    # fp32, odd channel counts and an empty keep list cannot join the common grid: the call still serves them
+    cases = [_layer(3, 1, 6, 6, 20, 36, 2, 61, dtype="f32"), _layer(3, 1, 6, 6, 64, 30, 2, 62, dtype="f32")]
+    _run(cases, dtype="f32")
+    odd = [_layer(4, 1, 14, 14, 128, 256, 2, 63), _layer(3, 1, 6, 6, 7, 5, 2, 64)]
+    _run(odd)
+    c = _layer(4, 1, 14, 14, 128, 256, 2, 65)
+    d = _to_device(c, True)
+    e = dict(d, idx=torch.empty(0, dtype=torch.int32, device="cuda"), X_k=d["X_k"][:0].contiguous())
+    outs = sbp.backward_linear_batch([d, e])
+    _check_against_oracle(c, outs[0])
+    assert all(np.all(bits(t) == 0) for t in outs[1])
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4])
+def test_batch_vit_base_block_full_size(k):
+    # the four linear layers of a ViT-Base block (B = 64, 197 tokens), fresh mask per layer, one call
+    shapes = [(768, 2304), (768, 768), (768, 3072), (3072, 768)]
+    cases = [_layer(64, 1, 14, 14, ci, co, k, 70 + 10 * k + i) for i, (ci, co) in enumerate(shapes)]
+    _run(cases)
+
+
+@pytest.mark.parametrize("k", [1, 2, 4])
+def test_batch_convnext_shapes_full_size(k):
+    _run([_layer(2, 0, 50, 84, 512, 2048, k, 90 + k), _layer(2, 0, 50, 84, 2048, 512, k, 95 + k)])
+    if k == 2:
+        _run([_layer(2, 0, 100, 168, 256, 1024, k, 97), _layer(2, 0, 100, 168, 1024, 256, k, 98)])
+        _run([_layer(2, 0, 200, 336, 128, 512, k, 99), _layer(2, 0, 200, 336, 512, 128, k, 100)])
+        _run([_layer(64, 1, 14, 14, 192, 768, k, 101), _layer(64, 1, 14, 14, 768, 192, k, 102)])
+
+
+def test_forward_cache_batch_is_bit_exact():
+    B, P, H, W = 6, 1, 14, 14
+    M = B * (P + H * W)
+    for Cs, dtype in (((192, 768, 64, 3072), "bf16"), ((64, 20), "f32"), ((768, 20), "bf16"), ((128,), "bf16")):
+        Xs = [si.normal((M, C), 1.0, 5 + i, dtype) for i, C in enumerate(Cs)]
+        idxs = [oracle.sample_indices(B, P, H, W, 1 + i % 4, 3, 40 + i) for i in range(len(Cs))]
+        outs = sbp.forward_cache_batch([X.cuda() for X in Xs], [torch.from_numpy(i).cuda() for i in idxs])
+        for X, i, o in zip(Xs, idxs, outs):
+            assert np.array_equal(bits(o), oracle.forward_cache(bits(X), i))
+    # an empty keep list among the items
+    X = si.normal((M, 64), 1.0, 9, "bf16").cuda()
+    full = torch.arange(M, dtype=torch.int32, device="cuda")
+    outs = sbp.forward_cache_batch([X, X], [full, full[:0]])
+    assert np.array_equal(bits(outs[0]), bits(X)) and outs[1].shape == (0, 64)
