@@ -67,6 +67,8 @@ struct LinArgs {
   int seg_order[3];                   // dispatch order: large-tile kernel 0 = dX tiles, 1 = long dW, 2 = short dW units;
                                       // general kernel 0 = dX tiles, 1 = dW units, 2 = zero-fill and column-sum blocks
   int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
+  int db_in_dw;                       // large-tile kernel: the dW units of the first tile column also produce db (one
+                                      // partial per split in dbp); no column-sum blocks then
 };
 
 // Zero fill of the dropped rows.  A wavefront takes 64 consecutive rows: every lane looks one row up
@@ -181,6 +183,12 @@ __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind,
   const int j1 = min(a.K, j0 + (kind == 1 ? a.rows_per_split : a.rows_small));
   const int split = kind == 1 ? sl : a.n_big + sl;
   float* part = a.part + (long long)split * a.Cout * a.Cin;
+  if (a.db_in_dw && tile_n == 0) {
+    float* dbp = a.dbp + (long long)split * a.Cout;
+    if (a.idx_in) big::dw_tile<true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
+    else big::dw_tile<false, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
+    return;
+  }
   if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
   else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
 }
@@ -1067,7 +1075,7 @@ static int batch_jobs(const sbp_linear_layer* L, int n, const BatchLayerChoice* 
       const bool direct = nsp == 1 && !(l.flags & (SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16));
       if (!direct) red += (double)(nsp + 1) * l.Cout * l.Cin * 4.0 / kReduceBytesPerNs;
     }
-    if (l.db) {
+    if (l.db && !l.dW) {               // (with dW the column sums come out of the dW units)
       const int64_t slice_rows = db_slice_rows_for(l.K, true);
       out[nj++] = Job{ceil_div(l.Cout, 256) * ceil_div(l.K, slice_rows), kNsFixedHelper + slice_rows * 512 / kHelperBytesPerNs, i, 4};
     }
@@ -1241,7 +1249,7 @@ BatchPlan plan_linear_batch(const sbp_linear_layer* L, int32_t n, int32_t dtype)
     b.off = off;
     if (l.dW && !b.direct) off += align_up((size_t)b.splits * l.Cout * l.Cin * sizeof(float), 256);
     b.off_dbp = off;
-    if (l.db) off += align_up((size_t)b.db_slices * l.Cout * sizeof(float), 256);
+    if (l.db) off += align_up((size_t)std::max(b.db_slices, b.splits) * l.Cout * sizeof(float), 256);
     b.off_inv = off;
     if (l.dX && !(l.flags & SBP_FLAG_DX_COMPACT) && !l.inv) off += align_up((size_t)l.M * sizeof(int32_t), 256);
   }
@@ -1308,6 +1316,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     la.rows_per_split = b.rows_per_split; la.db_slice_rows = b.db_slice_rows;
     la.n_big = b.splits; la.rows_small = 0; la.dx_bm = b.dx_bm;
     la.n_zero = scatter && l.M > l.K ? big_zero_blocks(l.M) : 0;
+    la.db_in_dw = l.db && l.dW ? 1 : 0;
     lds = std::max(lds, (size_t)big::RING + std::max<size_t>((size_t)(b.rows_per_split + 2 * big::KB), big::BT) * sizeof(int));
     lds = std::max<size_t>(lds, 16 * 1024);     // the column-sum blocks' staging
     any = any || l.dW || l.db || l.dX;
@@ -1315,7 +1324,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     rl.part = la.part; rl.dbp = la.dbp;
     rl.dW = b.direct ? nullptr : l.dW; rl.db = l.db;
     rl.nW = (long long)l.Cin * l.Cout;
-    rl.nsplit_w = b.splits; rl.nsplit_b = b.db_slices; rl.Cout = l.Cout;
+    rl.nsplit_w = b.splits; rl.nsplit_b = la.db_in_dw ? b.splits : b.db_slices; rl.Cout = l.Cout;
     rl.accumulate = (l.flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
     rl.bf16out = (l.flags & SBP_FLAG_DW_OUT_BF16) ? 1 : 0;
     any_reduce = any_reduce || rl.dW || rl.db;

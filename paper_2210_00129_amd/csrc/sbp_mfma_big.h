@@ -176,7 +176,7 @@ __device__ __forceinline__ void wait_stage_runtime(bool next2, bool next3a) {   
 template <class P>
 __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, int kvalid_last,
                                           f32x16_t (&acc)[P::FM][4]) {
-  constexpr int STAGE = P::STAGE, CPS = P::CPA + P::CPB, FM = P::FM, NM = 4 * P::FM;
+  constexpr int STAGE = P::STAGE, CPS = P::CPA + P::CPB, FM = P::FM, NM = 4 * P::FM + P::NEXTRA;
   static_assert(NS == 4, "buffer arithmetic below assumes a ring of four");
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
@@ -204,12 +204,14 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     pb.read(cur, 1, qa, qb);
     pb.issue_a(s + 3, dst, false);
     mfma_step<P::SWAP, FM>(acc, pa, pbf);
+    pb.extra(pa);
     interleave_step<NM, P::NREAD + P::NPRE, P::CPA>();
     wait_async_copies<CPS + P::CPA>();          // stage s + 1 has landed (s + 2 and half of s + 3 may be in flight)
     lds_barrier();
     pb.read(nxt, 0, pa, pbf);
     pb.issue_b(s + 3, dst, false);
     mfma_step<P::SWAP, FM>(acc, qa, qb);
+    pb.extra(qa);
     interleave_step<NM, P::NREAD, P::CPB>();
   }
   // drain: the same steps with the end of the operand in view
@@ -222,6 +224,7 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     pb.read(cur, 1, qa, qb);
     if (more) pb.issue_a(s + 3, dst, last_partial);
     mfma_step<P::SWAP, FM>(acc, pa, pbf);
+    pb.extra(pa);
     interleave_step<NM, P::NREAD, 0>();
     if (s + 1 < nk) wait_stage_runtime<P, CPS>(s + 2 < nk, more);
     lds_barrier();
@@ -232,6 +235,7 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     pb.read(nxt, 0, pa, pbf);                   // past the last stage: reads a stale buffer, never used
     if (more) pb.issue_b(s + 3, dst, last_partial);
     mfma_step<P::SWAP, FM>(acc, qa, qb);
+    pb.extra(qa);
     interleave_step<NM, P::NREAD, 0>();
   }
   lds_barrier();
@@ -241,7 +245,8 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
 template <int BMX>
 struct DxProb {
   static constexpr bool SWAP = true;            // lane ends with 4 consecutive input channels of one row
-  static constexpr int FM = BMX / 64, CPA = FM, CPB = 4, NREAD = FM + 8, NPRE = 0;
+  static constexpr int FM = BMX / 64, CPA = FM, CPB = 4, NREAD = FM + 8, NPRE = 0, NEXTRA = 0;
+  __device__ __forceinline__ void extra(const bf16x8_t (&)[FM]) {}
   static constexpr int A_BYTES = BMX * KB * 2, STAGE = A_BYTES + TILE_BYTES;
   RowCopy<FM> ca;
   SlowCopy cb;
@@ -336,11 +341,40 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 }
 
 // ---- dW partial = dY_k[j0:j1]^T X_k[j0:j1] -----------------------------------------------------------
-template <bool GATHER>
+// DB: the unit also sums the columns of its dY panel over its rows (the layer's bias gradient: db[o] = sum_j dY[j][o]), from
+// the dY fragments that are in registers anyway: lane l of fragment i holds 8 consecutive j of column 32 i + l % 32 (j group
+// l / 32), added with four v_dot2_f32_bf16 against (1, 1) into one fp32 sum per fragment row on the vector ALU, which is
+// otherwise idle here.  (Summing on the matrix cores - a fifth product with an operand of ones - needs accumulator
+// registers beyond the 256 the tile already fills, and the compiler then shuffles accumulators every step.)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+template <bool GATHER, bool DB>
 struct DwProb {
   static constexpr bool SWAP = false;
-  static constexpr int FM = 4, CPA = 4, CPB = 4, STAGE = 2 * TILE_BYTES;
+  static constexpr int FM = 4, CPA = 4, CPB = 4, STAGE = 2 * TILE_BYTES, NEXTRA = 0;
   static constexpr int NREAD = 16, NPRE = GATHER ? 2 : 0;   // the 4 id reads pair up into 2 instructions
+  float accdb[DB ? 4 : 1];
+  __device__ __forceinline__ void init_db(int) {
+    if constexpr (DB) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) accdb[i] = 0.f;
+    }
+  }
+  __device__ __forceinline__ void extra(const bf16x8_t (&a)[4]) {
+    if constexpr (DB) {
+      const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const u32x4_t w = __builtin_bit_cast(u32x4_t, a[i]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          unsigned wq = w[q];
+          asm("" : "+v"(wq));       // (without this the four words of a fragment were folded into its first one)
+          accdb[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, wq), ones, accdb[i], false);
+        }
+      }
+    }
+  }
   SlowCopy ca, cb;
   const char* a_src;      // dY (GATHER) or dY + j0 rows
   const char* b_src;      // X_k + j0 rows
@@ -383,17 +417,18 @@ struct DwProb {
   }
 };
 
-template <bool GATHER>
+template <bool GATHER, bool DB = false>
 __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                                         const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
-                                        float* __restrict__ part, int m0, int n0) {
+                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp = nullptr) {
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
   const int nrows = j1 - j0;
   const int nk = (nrows + KB - 1) / KB;
 
-  DwProb<GATHER> pb;
+  DwProb<GATHER, DB> pb;
+  pb.init_db(lane);
   pb.wave = wave;
   pb.nrows = nrows;
   pb.a_ld = (uint32_t)Cout * 2u;
@@ -422,6 +457,16 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   const bool tail = (nrows % KB) != 0;
   ring_loop(smem, pb, nk, tail, nrows - (nk - 1) * KB, acc);
 
+  if constexpr (DB) {
+    // lanes l and l + 32 hold the two j groups of column 32 i + l % 32; the two wavefronts that own different rows of the
+    // tile (wn = 0) write the sums
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float both = pb.accdb[i] + __shfl_xor(pb.accdb[i], 32);
+      const int o = m0 + wm + 32 * i + (lane & 31);
+      if (wn == 0 && lane < 32 && o < Cout) dbp[o] = both;
+    }
+  }
   // register v of lane l of block (i, j) is C[row wm + 32 i + 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col wn + 32 j + (l & 31)]
   if (m0 + BT <= Cout && n0 + BT <= Cin) {
 #pragma unroll

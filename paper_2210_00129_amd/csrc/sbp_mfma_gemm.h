@@ -28,7 +28,9 @@ namespace sbp {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
 #define SBP_LDS __attribute__((address_space(3)))
 #define SBP_GLB __attribute__((address_space(1)))
 
