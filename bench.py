@@ -135,14 +135,23 @@ class Job:
         self.step_no = 0
         # batched calls: per block one array of layer descriptors (backward order) and one of gather items,
         # marshalled once; set_ratio fills in K
+        # (every block has its own keep list there: the masks of a whole step are drawn by one call at its start)
         self.batch_args = []
-        for blk in self.blocks:
+        nb = len(self.blocks)
+        self.idx_b = [torch.empty(M, dtype=torch.int32, device="cuda") for _ in range(nb)]
+        self.inv_b = [torch.empty(M, dtype=torch.int32, device="cuda") for _ in range(nb)]
+        for b, blk in enumerate(self.blocks):
+            ip, vp = self.idx_b[b].data_ptr(), self.inv_b[b].data_ptr()
             lays = (_lib.LinearLayer * len(blk))(*[
-                _lib.LinearLayer(l.dY.data_ptr(), self.idx.data_ptr(), self.inv.data_ptr(), l.Xk.data_ptr(), l.W.data_ptr(), M, 0,
+                _lib.LinearLayer(l.dY.data_ptr(), ip, vp, l.Xk.data_ptr(), l.W.data_ptr(), M, 0,
                                  l.Cin, l.Cout, l.dW.data_ptr(), l.db.data_ptr(), l.dX.data_ptr(), 0, 0) for l in reversed(blk)])
             items = (_lib.GatherItem * len(blk))(*[
-                _lib.GatherItem(l.X.data_ptr(), self.idx.data_ptr(), l.Xk.data_ptr(), M, 0, l.Cin, 0) for l in blk])
+                _lib.GatherItem(l.X.data_ptr(), ip, l.Xk.data_ptr(), M, 0, l.Cin, 0) for l in blk])
             self.batch_args.append((lays, items))
+        self.descs = (_lib.SampleDesc * nb)(*[sbp.make_desc(wl.B, wl.P, wl.H, wl.W, 2, 0, 0) for _ in range(nb)])
+        self.idx_ptrs = (ctypes.c_void_p * nb)(*[t.data_ptr() for t in self.idx_b])
+        self.inv_ptrs = (ctypes.c_void_p * nb)(*[t.data_ptr() for t in self.inv_b])
+        self.idx_caps = (ctypes.c_int64 * nb)(*[M] * nb)
         self.ws_batch = None
 
     def set_ratio(self, r):
@@ -169,9 +178,17 @@ class Job:
         idx_ptr, K = self.idx.data_ptr(), self.K
         inv_ptr = self.inv.data_ptr() if self.inv is not None else None
         self.step_no += 1
+        if self.batched:                                            # fresh masks for every block and step, drawn at once
+            for b in range(len(self.blocks)):
+                self.descs[b].k = self.k
+                self.descs[b].stream_id = self.step_no * 1000 + b
+            check(L.sbp_sample_indices_batch(self.descs, len(self.blocks), self.idx_ptrs, self.idx_caps, self.inv_ptrs, self.stream))
         for b, blk in enumerate(self.blocks):
-            self.desc.stream_id = self.step_no * 1000 + b          # fresh mask for every block and step
-            check(L.sbp_sample_indices(ctypes.byref(self.desc), idx_ptr, self.M, inv_ptr, self.stream))
+            if self.batched:
+                idx_ptr, inv_ptr = self.idx_b[b].data_ptr(), self.inv_b[b].data_ptr()
+            else:
+                self.desc.stream_id = self.step_no * 1000 + b      # fresh mask for every block and step
+                check(L.sbp_sample_indices(ctypes.byref(self.desc), idx_ptr, self.M, inv_ptr, self.stream))
             if self.batched:
                 lays, items = self.batch_args[b]
                 check(L.sbp_forward_cache_batch(items, len(items), self.code, self.stream))   # forward side: the kept rows
@@ -773,7 +790,7 @@ def main():
         "attainable_tflops": round(attainable_tflops(flops, bytes_step), 1),
         "frac_of_attainable": round(value / attainable_tflops(flops, bytes_step), 4),
         "activation_memory_saving": round(1.0 - cached / full, 4),
-        "calls": "one sbp_forward_cache_batch + one sbp_backward_linear_batch per block" if job.batched
+        "calls": "one sbp_sample_indices_batch per step, one sbp_forward_cache_batch + one sbp_backward_linear_batch per block" if job.batched
                  else "one sbp_forward_cache + one sbp_backward_linear per layer",
         "other_call_pattern": other_mode,
         "kernel_breakdown": breakdown,

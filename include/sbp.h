@@ -117,6 +117,15 @@ int32_t sbp_sample_indices(const sbp_sample_desc* desc, int32_t* idx, int64_t id
                            int32_t* inv, void* stream);
 
 /*
+ * Several draws in one call (a training step draws the keep-sets of all its blocks or layers at once): draw i is
+ * sbp_sample_indices(&descs[i], idx[i], idx_capacity[i], inv ? inv[i] : NULL).  Draws of the 2 x 2 grid sampler
+ * share launches (16 draws each); the other modes run one by one.  descs, idx, idx_capacity, inv are HOST arrays of n
+ * entries (idx[i], inv[i] device pointers; inv or single inv[i] may be NULL); 1 <= n <= 4096.
+ */
+int32_t sbp_sample_indices_batch(const sbp_sample_desc* descs, int32_t n, int32_t* const* idx,
+                                 const int64_t* idx_capacity, int32_t* const* inv, void* stream);
+
+/*
  * Step "forward cache" (paper, section "Calculation of Linear Layers": of the layer input only the kept
  * rows are retained for the backward pass):
  * X_k[j, :] = X[idx[j], :] for j in [0, K).

@@ -78,6 +78,21 @@ def sample_indices(B, P, H, W, k, seed, stream_id, mode=GRID_PER_CELL, per_sampl
     return idx, inv
 
 
+def sample_indices_batch(descs, idx_list, inv_list=None):
+    """Several draws in one call: descs = SampleDesc objects (make_desc), idx_list / inv_list = preallocated int32
+    tensors on the GPU (inv_list or single entries may be None)."""
+    import ctypes
+    n = len(descs)
+    arr = (SampleDesc * n)(*descs)
+    idx_p = (ctypes.c_void_p * n)(*[_dev(t, "idx") for t in idx_list])
+    cap = (ctypes.c_int64 * n)(*[t.numel() for t in idx_list])
+    inv_p = None
+    if inv_list is not None:
+        inv_p = (ctypes.c_void_p * n)(*[_dev(t, "inv") for t in inv_list])
+    _lib.check(_lib.lib().sbp_sample_indices_batch(arr, n, idx_p, cap, inv_p, _stream(idx_list[0].device)))
+    return idx_list, inv_list
+
+
 def forward_cache(X: torch.Tensor, idx: torch.Tensor, out=None) -> torch.Tensor:
     """X_k = X[idx] (rows), the only part of the layer input kept for the backward pass."""
     if X.dim() != 2:

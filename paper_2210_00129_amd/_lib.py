@@ -40,6 +40,8 @@ PROTOTYPES = {
     "sbp_k_from_ratio": (c_i32, [c_dbl, c_i32]),
     "sbp_keep_count": (c_i64, [ctypes.POINTER(SampleDesc)]),
     "sbp_sample_indices": (c_i32, [ctypes.POINTER(SampleDesc), c_vp, c_i64, c_vp, c_vp]),
+    "sbp_sample_indices_batch": (c_i32, [ctypes.POINTER(SampleDesc), c_i32, ctypes.POINTER(c_vp), ctypes.POINTER(c_i64),
+                                         ctypes.POINTER(c_vp), c_vp]),
     "sbp_forward_cache": (c_i32, [c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_vp, c_vp]),
     "sbp_forward_cache_batch": (c_i32, [ctypes.POINTER(GatherItem), c_i32, c_i32, c_vp]),
     "sbp_backward_linear_workspace": (c_sz, [c_i64, c_i64, c_i32, c_i32, c_i32, c_u32]),

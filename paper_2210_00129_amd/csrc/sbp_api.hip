@@ -204,6 +204,21 @@ int32_t sbp_sample_indices(const sbp_sample_desc* d, int32_t* idx, int64_t idx_c
   return launch_sample(*d, idx, inv, (hipStream_t)stream);
 }
 
+int32_t sbp_sample_indices_batch(const sbp_sample_desc* descs, int32_t n, int32_t* const* idx, const int64_t* idx_capacity,
+                                 int32_t* const* inv, void* stream) {
+  if (!descs || !idx || !idx_capacity) return fail(SBP_ERR_NULL, "descs, idx or idx_capacity is NULL");
+  if (n < 1 || n > 4096) return fail(SBP_ERR_SHAPE, "need 1 <= n <= 4096 draws, got %d", n);
+  for (int i = 0; i < n; ++i) {
+    int32_t st = validate_desc(&descs[i]);
+    if (st != SBP_OK) return st;
+    if (!idx[i]) return fail(SBP_ERR_NULL, "idx[%d] is NULL", i);
+    const int64_t K = keep_count_host(descs[i]);
+    if (idx_capacity[i] < K)
+      return fail(SBP_ERR_CAPACITY, "idx[%d] capacity %lld < K=%lld", i, (long long)idx_capacity[i], (long long)K);
+  }
+  return launch_sample_batch(descs, n, idx, inv, (hipStream_t)stream);
+}
+
 int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t K, int32_t C, int32_t dtype,
                           void* Xk, void* stream) {
   int eb = elem_bytes(dtype);

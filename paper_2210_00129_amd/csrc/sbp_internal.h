@@ -58,6 +58,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // ---- sampler -----------------------------------------------------------------------------
 int64_t keep_count_host(const sbp_sample_desc& d);
 int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipStream_t s);
+int32_t launch_sample_batch(const sbp_sample_desc* d, int32_t n, int32_t* const* idx, int32_t* const* inv, hipStream_t s);
 
 // ---- row gather --------------------------------------------------------------------------
 int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t C, int32_t elem_bytes,

@@ -1184,17 +1184,28 @@ static void choose_batch(const sbp_linear_layer* L, int n, BatchLayerChoice* c) 
              e.k[i].flags == key[i].flags && e.k[i].want == key[i].want;
     if (same) { for (int i = 0; i < n; ++i) c[i] = e.c[i]; overrides(); return; }
   }
-  for (int i = 0; i < n; ++i) c[i] = BatchLayerChoice{256, std::max(min_splits[i], L[i].K >= 2048 ? 2 : 1)};
+  // start from what every layer would get on its own (a search over one layer at a time cannot leave a start in which
+  // every layer has a few long units: the finish is the longest unit's, and shortening one layer's does not move it)
+  for (int i = 0; i < n; ++i) {
+    const BigChoice own = choose_big(L[i].M, L[i].K, L[i].Cin, L[i].Cout);
+    c[i] = BatchLayerChoice{own.splits > 0 ? own.dx_bm : 256, std::max(min_splits[i], own.splits > 0 ? own.splits : 1)};
+  }
   double best = batch_cost(L, n, c);
   for (int pass = 0; pass < 2; ++pass)
     for (int i = 0; i < n; ++i) {
-      const BatchLayerChoice start = c[i];
-      BatchLayerChoice arg = start;
+      BatchLayerChoice arg = c[i];
+      int cand[24], nc = 0;
+      for (int sp = 1; sp <= 8; ++sp) cand[nc++] = std::max(sp, min_splits[i]);
+      for (int m : {5, 6, 8, 10, 12, 16, 20, 24, 32}) cand[nc++] = std::max(min_splits[i] * m / 4, min_splits[i]);
+      for (int d = -2; d <= 2; ++d) cand[nc++] = std::max(c[i].splits + d, min_splits[i]);
+      std::sort(cand, cand + nc);
+      nc = (int)(std::unique(cand, cand + nc) - cand);
       for (int bm : {256, 128, 64}) {
         if (!L[i].dX && bm != 256) continue;
-        for (int sp = min_splits[i]; sp < min_splits[i] + 8; ++sp) {
-          if (!L[i].dW && sp != min_splits[i]) continue;
-          if (sp > 1 && ceil_div(L[i].K, sp) < 512) break;        // splits shorter than 16 stages do not pay
+        for (int q = 0; q < nc; ++q) {
+          const int sp = cand[q];
+          if (!L[i].dW && q > 0) break;
+          if (sp > min_splits[i] && sp > 1 && ceil_div(L[i].K, sp) < 512) break;   // splits shorter than 16 stages do not pay
           c[i] = BatchLayerChoice{bm, sp};
           const double cost = batch_cost(L, n, c);
           if (cost < best) { best = cost; arg = c[i]; }
@@ -1217,8 +1228,13 @@ static void choose_batch(const sbp_linear_layer* L, int n, BatchLayerChoice* c) 
 BatchPlan plan_linear_batch(const sbp_linear_layer* L, int32_t n, int32_t dtype) {
   BatchPlan p{};
   p.n = n;
+  // one grid for all layers: where every layer is within the large-tile engine's limits and wide enough for its 256-wide
+  // tiles to pay (narrower layers are better off with the 128-tile engine, layer by layer); override "tile" = "big"
+  // takes the common grid wherever the limits allow
+  const bool forced = options().tile_mode == 2;
   p.fused = n >= 1 && n <= kMaxBatch;
-  for (int i = 0; i < n && p.fused; ++i) p.fused = batch_layer_fits(L[i], dtype);
+  for (int i = 0; i < n && p.fused; ++i)
+    p.fused = batch_layer_fits(L[i], dtype) && (forced || (L[i].Cin >= big::BT && L[i].Cout >= big::BT && L[i].K >= 1024));
   // layer by layer: every layer gets its own piece of the workspace.  The size returned covers both modes, so that
   // a size query made with other (e.g. differently aligned) addresses than the call still holds.
   size_t off = 0, seq_bytes = 0;

@@ -494,6 +494,47 @@ __global__ void __launch_bounds__(256) sample_kernel(SampleGeom g, int32_t* __re
     sample_unit(g, t, idx, inv);
 }
 
+// several draws of the 2 x 2 grid sampler in one launch: blockIdx.y = draw
+static constexpr int kMaxDrawsPerLaunch = 16;
+struct SampleBatchArgs {
+  SampleGeom g[kMaxDrawsPerLaunch];
+  int32_t* idx[kMaxDrawsPerLaunch];
+  int32_t* inv[kMaxDrawsPerLaunch];
+};
+__global__ void __launch_bounds__(256) sample_batch_kernel(const SampleBatchArgs a) {
+  const SampleGeom& g = a.g[blockIdx.y];
+  const long long total = (long long)g.B * (g.P + g.ch * g.cw);
+  for (long long t = blockIdx.x * (long long)blockDim.x + threadIdx.x; t < total;
+       t += (long long)gridDim.x * blockDim.x)
+    sample_unit(g, t, a.idx[blockIdx.y], a.inv[blockIdx.y]);
+}
+
+int32_t launch_sample_batch(const sbp_sample_desc* d, int32_t n, int32_t* const* idx, int32_t* const* inv, hipStream_t s) {
+  int i = 0;
+  while (i < n) {
+    const bool grid2 = (d[i].mode == SBP_GRID_PER_CELL || d[i].mode == SBP_GRID_SHARED) && d[i].cell == 2;
+    if (!grid2) {                      // the other samplers: one launch per draw
+      const int32_t st = launch_sample(d[i], idx[i], inv ? inv[i] : nullptr, s);
+      if (st != SBP_OK) return st;
+      ++i;
+      continue;
+    }
+    SampleBatchArgs a{};
+    int m = 0;
+    long long most = 1;
+    while (i < n && m < kMaxDrawsPerLaunch && (d[i].mode == SBP_GRID_PER_CELL || d[i].mode == SBP_GRID_SHARED) && d[i].cell == 2) {
+      a.g[m] = make_geom(d[i]);
+      a.idx[m] = idx[i];
+      a.inv[m] = inv ? inv[i] : nullptr;
+      most = std::max(most, (long long)a.g[m].B * (a.g[m].P + a.g[m].ch * a.g[m].cw));
+      ++m; ++i;
+    }
+    const unsigned blocks = (unsigned)std::min<long long>((most + 255) / 256, 65535);
+    SBP_LAUNCH(SBP_PROF_SAMPLE, s, sample_batch_kernel, dim3(blocks, (unsigned)m), dim3(256), 0, s, a);
+  }
+  return check_launch("sample_batch_kernel");
+}
+
 int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipStream_t s) {
   if (d.mode == SBP_RANDOM_MASK || d.mode == SBP_TEMPORAL) {
     VariantGeom v{};

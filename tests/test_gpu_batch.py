@@ -53,8 +53,10 @@ def _check_against_oracle(c, out, dtype="bf16"):
             assert np.all(bits(dX)[np.setdiff1d(np.arange(M), idx)] == 0)
 
 
-def _run(cases, with_inv=True, want=("dW", "db", "dX"), dtype="bf16"):
-    outs = sbp.backward_linear_batch([_to_device(c, with_inv) for c in cases], want=want)
+def _run(cases, with_inv=True, want=("dW", "db", "dX"), dtype="bf16", forced=True):
+    # forced: the common grid also for layers narrower than it would be chosen for (ragged tiles in every dimension)
+    with sbp.options(**({"tile": "big"} if forced else {})):
+        outs = sbp.backward_linear_batch([_to_device(c, with_inv) for c in cases], want=want)
     torch.cuda.synchronize()
     for c, o in zip(cases, outs):
         _check_against_oracle(c, o, dtype)
@@ -76,6 +78,7 @@ def test_batch_tile_heights_and_split_counts(opts):
     cases = [_layer(16, 1, 14, 14, 320, 288, 3, 21), _layer(16, 1, 14, 14, 288, 320, 2, 22)]
     with sbp.options(**opts):
         _run(cases)
+        _run(cases, forced=False)
 
 
 def test_batch_single_layer_and_single_outputs():
@@ -95,7 +98,8 @@ def test_batch_single_layer_and_single_outputs():
 def test_batch_equals_single_layer_calls_bit_for_bit_on_integers():
     cases = [_layer(8, 1, 14, 14, 320, 288, 2, 41, ints=True), _layer(8, 1, 14, 14, 64, 96, 3, 44, ints=True)]
     dev = [_to_device(c, True) for c in cases]
-    outs = sbp.backward_linear_batch(dev)
+    with sbp.options(tile="big"):
+        outs = sbp.backward_linear_batch(dev)
     for d, o in zip(dev, outs):
         ref = sbp.backward_linear(d["dY"], d["idx"], d["X_k"], d["W"], M=d["M"], inv=d["inv"])
         for a, b in zip(o, ref):
@@ -108,7 +112,7 @@ def test_batch_accumulate_and_bf16_weight_gradient():
     d0, d1 = _to_device(c0, True), _to_device(c1, True)
     d0["dW"] = torch.full((256, 128), 2.0, dtype=torch.float32, device="cuda")
     d0["db"] = torch.full((256,), -1.0, dtype=torch.float32, device="cuda")
-    with sbp.options(splits=1):          # a single split may not take the direct-write path with these flags
+    with sbp.options(splits=1, tile="big"):          # a single split may not take the direct-write path with these flags
         (dW0, db0, _), (dW1, db1, _) = sbp.backward_linear_batch([d0, d1])
         plain = sbp.backward_linear_batch([dict(d1, flags=0)])[0]          # same single split, written directly as fp32
     rW0, rb0, _ = oracle.backward_linear(si.to_f64(c0["dY"]), c0["idx"], si.to_f64(c0["X"])[c0["idx"]], si.to_f64(c0["W"]), c0["M"])
@@ -136,16 +140,18 @@ def test_batch_vit_base_block_full_size(k):
     # the four linear layers of a ViT-Base block (B = 64, 197 tokens), fresh mask per layer, one call
     shapes = [(768, 2304), (768, 768), (768, 3072), (3072, 768)]
     cases = [_layer(64, 1, 14, 14, ci, co, k, 70 + 10 * k + i) for i, (ci, co) in enumerate(shapes)]
-    _run(cases)
+    _run(cases, forced=False)
 
 
 @pytest.mark.parametrize("k", [1, 2, 4])
 def test_batch_convnext_shapes_full_size(k):
-    _run([_layer(2, 0, 50, 84, 512, 2048, k, 90 + k), _layer(2, 0, 50, 84, 2048, 512, k, 95 + k)])
-    if k == 2:
-        _run([_layer(2, 0, 100, 168, 256, 1024, k, 97), _layer(2, 0, 100, 168, 1024, 256, k, 98)])
-        _run([_layer(2, 0, 200, 336, 128, 512, k, 99), _layer(2, 0, 200, 336, 512, 128, k, 100)])
-        _run([_layer(64, 1, 14, 14, 192, 768, k, 101), _layer(64, 1, 14, 14, 768, 192, k, 102)])
+    # whatever the library picks for these sizes (common grid or layer by layer), and the common grid forced
+    for forced in (False, True):
+        _run([_layer(2, 0, 50, 84, 512, 2048, k, 90 + k), _layer(2, 0, 50, 84, 2048, 512, k, 95 + k)], forced=forced)
+        if k == 2:
+            _run([_layer(2, 0, 100, 168, 256, 1024, k, 97), _layer(2, 0, 100, 168, 1024, 256, k, 98)], forced=forced)
+            _run([_layer(2, 0, 200, 336, 128, 512, k, 99), _layer(2, 0, 200, 336, 512, 128, k, 100)], forced=forced)
+            _run([_layer(64, 1, 14, 14, 192, 768, k, 101), _layer(64, 1, 14, 14, 768, 192, k, 102)], forced=forced)
 
 
 def test_forward_cache_batch_is_bit_exact():
@@ -162,3 +168,31 @@ def test_forward_cache_batch_is_bit_exact():
     full = torch.arange(M, dtype=torch.int32, device="cuda")
     outs = sbp.forward_cache_batch([X, X], [full, full[:0]])
     assert np.array_equal(bits(outs[0]), bits(X)) and outs[1].shape == (0, 64)
+
+
+def test_sample_indices_batch_is_bit_exact():
+    # 20 draws (more than one launch holds) of different geometries, keep ratios and modes, the other samplers among them
+    geoms = [(64, 1, 14, 14), (2, 0, 50, 84), (3, 1, 5, 7), (1, 0, 1, 1), (2, 0, 100, 168)]
+    descs, refs = [], []
+    for i in range(20):
+        B, P, H, W = geoms[i % len(geoms)]
+        k = 1 + i % 4
+        if i == 7:
+            descs.append(sbp.make_desc(B, P, H, W, k, 5, 100 + i, mode=sbp.RANDOM_MASK))
+            refs.append(oracle.sample_indices_random(B, P, H, W, k, 5, 100 + i))
+        elif i == 11:
+            descs.append(sbp.make_desc(B, P, H, W, 5, 5, 100 + i, cell=3))
+            refs.append(oracle.sample_indices_cells(B, P, H, W, 5, 3, 5, 100 + i))
+        else:
+            mode = sbp.GRID_SHARED if i % 5 == 4 else sbp.GRID_PER_CELL
+            descs.append(sbp.make_desc(B, P, H, W, k, 5, 100 + i, mode=mode, per_sample=(i % 3 != 2)))
+            refs.append(oracle.sample_indices(B, P, H, W, k, 5, 100 + i, mode=mode, per_sample=(i % 3 != 2)))
+    idxs = [torch.empty(r.size, dtype=torch.int32, device="cuda") for r in refs]
+    invs = [torch.empty(d.B * (d.P + d.H * d.W), dtype=torch.int32, device="cuda") if i % 2 == 0 else None
+            for i, d in enumerate(descs)]
+    sbp.sample_indices_batch(descs, idxs, invs)
+    torch.cuda.synchronize()
+    for d, r, got, inv in zip(descs, refs, idxs, invs):
+        assert np.array_equal(got.cpu().numpy(), r)
+        if inv is not None:
+            assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(r, d.B * (d.P + d.H * d.W)))
