@@ -7,6 +7,7 @@
 // for the whole wavefront and dropped taps are skipped by a scalar branch.  bf16 or fp32 storage,
 // fp32 arithmetic on the vector ALUs (a depthwise conv is no dense contraction: no MFMA).
 #include <cstdlib>
+#include <mutex>
 
 #include "sbp_internal.h"
 
@@ -463,8 +464,302 @@ __global__ void __launch_bounds__(DW_THREADS * GROUPS) dw_both_strip_kernel(cons
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// bf16, channel counts that are multiples of 8: LDS-tiled kernel.  A workgroup takes a tile of R rows x TS strips of 8
+// columns and a slab of 32 channels, stages the gradient tile WITH its halo of KS - 1 rows and columns (dropped and
+// outside positions as zeros: no mask is looked at afterwards) and the X tile (no halo) in LDS once, and computes from
+// them both the dX of the tile and the tile's share of dWd and db:
+//   dX[y][x]   = sum_{i,t} g[y - PAD + i][x - PAD + t] w[KS-1-i][KS-1-t]
+//   dWd[u][v] += sum_{(y,x) in tile} X[y][x] g[y - u + PAD][x - v + PAD]      (summed over X positions: every pair of an
+//                                                                              X and a gradient position lies in one tile)
+// LDS lines are [row][channel][column]: 2-byte elements, columns contiguous, so a 4-byte word is two neighbouring
+// columns of ONE channel - the operand shape of v_dot2_f32_bf16 (two exact products added to an fp32 sum).  A lane owns
+// one channel and, per work item, one row of one strip: per gradient row it reads 8 words (two 16-byte reads), makes the
+// 7 odd-aligned pairs with v_alignbit, and feeds 8 x 4 dot2 (dX) and 4 x KS dot2 (dWd) from them.  The two halves of a
+// wavefront work on different strips; the 8 half-wavefronts of a workgroup are added through LDS at the end, one
+// partial per workgroup (fixed order), and dw_reduce_kernel adds the workgroups' partials.
+// ------------------------------------------------------------------------------------------------
+static constexpr int DWF_SLAB = 32;      // channels per workgroup
+static constexpr int DWF_THREADS = 256;  // two workgroups per CU (512 threads each were slower: the kernel is bound by its instruction count)
+static constexpr int DWF_SLOTS = DWF_THREADS / DWF_SLAB;   // half-wavefronts = strips in flight
+static constexpr int DWF_RED = DWF_SLOTS < 8 ? DWF_SLOTS : 8;        // slots of the LDS buffer the half-wavefronts' sums are added through
+
+struct DwFusedArgs {
+  const uint16_t* dY; const int32_t* inv; const uint16_t* X; const uint16_t* Wd;
+  uint16_t* dX; float* part;   // part[workgroup x][KS*KS + 1][C]
+  int B, H, W, C;
+  int R, TS;                   // output rows and 8-column strips per tile
+  int tiles_y, tiles_x, ntiles;
+  int pitch;                   // bytes of one (row, channel) line of the LDS tiles
+  int want_dx, want_dw;
+};
+
+__device__ __forceinline__ uint32_t dwf_alignbit(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_alignbit(hi, lo, 16); }   // (lo.hi, hi.lo)
+
+// the words (A.k, B.k) of 8 channels of two neighbouring positions into the 8 channel lines starting at dst
+__device__ __forceinline__ void dwf_store_pairs(char* dst, int pitch, const uint4& A, const uint4& Bv) {
+  *reinterpret_cast<uint32_t*>(dst + 0 * pitch) = dw_pair_lo(A.x, Bv.x);
+  *reinterpret_cast<uint32_t*>(dst + 1 * pitch) = dw_pair_hi(A.x, Bv.x);
+  *reinterpret_cast<uint32_t*>(dst + 2 * pitch) = dw_pair_lo(A.y, Bv.y);
+  *reinterpret_cast<uint32_t*>(dst + 3 * pitch) = dw_pair_hi(A.y, Bv.y);
+  *reinterpret_cast<uint32_t*>(dst + 4 * pitch) = dw_pair_lo(A.z, Bv.z);
+  *reinterpret_cast<uint32_t*>(dst + 5 * pitch) = dw_pair_hi(A.z, Bv.z);
+  *reinterpret_cast<uint32_t*>(dst + 6 * pitch) = dw_pair_lo(A.w, Bv.w);
+  *reinterpret_cast<uint32_t*>(dst + 7 * pitch) = dw_pair_hi(A.w, Bv.w);
+}
+
+template <int KS>
+__global__ void __launch_bounds__(DWF_THREADS, 2) dw_fused_kernel(const DwFusedArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  constexpr int PAD = KS / 2, NP = (KS + 1) / 2, NT = KS * KS + 1;
+  const int tid = threadIdx.x;
+  const int slot = tid >> 5, ch = tid & 31;
+  const int slab0 = blockIdx.y * DWF_SLAB;
+  const int c = slab0 + ch;
+  const bool active = c < a.C;
+  const int cc = active ? c : a.C - 1;
+  const int GR = a.R + KS - 1;                         // gradient rows of a tile
+  const int ncw = a.pitch >> 2;                        // words per line
+  char* gt = lds;                                      // [GR][32][pitch]
+  char* xt = lds + (size_t)GR * DWF_SLAB * a.pitch;    // [R][32][pitch]
+  unsigned char* mask = reinterpret_cast<unsigned char*>(xt + (size_t)a.R * DWF_SLAB * a.pitch);   // [GR][2 ncw] kept / dropped
+
+  // flipped weight pairs of this lane's channel: pair m of gradient row i holds taps (KS-1-2m, KS-2-2m) of row KS-1-i
+  uint32_t wp[KS][NP];
+  if (a.want_dx) {
+#pragma unroll
+    for (int i = 0; i < KS; ++i)
+#pragma unroll
+      for (int m = 0; m < NP; ++m) {
+        const int u = KS - 1 - i, v0 = KS - 1 - 2 * m, v1 = KS - 2 - 2 * m;
+        const uint32_t lo = a.Wd[(u * KS + v0) * a.C + cc];
+        const uint32_t hi = v1 >= 0 ? a.Wd[(u * KS + v1) * a.C + cc] : 0u;
+        wp[i][m] = lo | (hi << 16);
+      }
+  }
+  float accw[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) accw[t] = 0.f;
+
+  for (int tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+    const int tx = tile % a.tiles_x, rest = tile / a.tiles_x;
+    const int ty = rest % a.tiles_y, b = rest / a.tiles_y;
+    const int y0 = ty * a.R, x0 = tx * a.TS * 8;
+    __syncthreads();                                   // the previous tile's readers are done
+    // ---- stage the gradient tile (halo, zeros where dropped or outside) and the X tile -----------------------------
+    {
+      // Order of the global loads (latency is what staging costs: every load here misses the caches of the CU):
+      //   1. the inverse-map entries of the halo tile's positions (kept / dropped; up to 4 per thread),
+      //   2. the thread's X rows (2 rows in flight; they depend on nothing),
+      //   3. kept / dropped bytes into LDS (waits for 1 only: loads complete in order), barrier,
+      //   4. the thread's gradient rows, kept positions only (3 rows in flight: more spill registers),
+      //   5. X rows into LDS, gradient rows into LDS; further chunks of rows, if any, the same way.
+      const int ncols = 2 * ncw;
+      const int npos = GR * ncols;
+      int mv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int p = tid + u * DWF_THREADS;
+        mv[u] = -1;
+        if (p < npos) {
+          const int row = p / ncols, j = p - row * ncols;
+          const int y = y0 - PAD + row, x = x0 - PAD + j;
+          if (y >= 0 && y < a.H && x >= 0 && x < a.W) mv[u] = a.inv[((long long)b * a.H + y) * a.W + x];
+        }
+      }
+      // thread <-> (8-channel group, word of the line, row phase): no divisions per item, rows advance by a fixed step
+      const int per_row = ncw * 4, rstep = DWF_THREADS / per_row;     // (host: per_row <= DWF_THREADS)
+      const int g8 = tid & 3, wj = (tid >> 2) % ncw, r0 = (tid >> 2) / ncw;
+      const int c8 = min(slab0 + 8 * g8, a.C - 8);                     // (slabs beyond C: clamped, their lanes store nothing)
+      const bool stager = r0 < rstep;
+      const bool xstager = stager && a.want_dw && wj < a.TS * 4;
+      const int x = x0 - PAD + 2 * wj, xx = x0 + 2 * wj;
+      auto load_x = [&](int rb, uint4 (&A)[2], uint4 (&Bv)[2]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int row = rb + u * rstep, y = y0 + row;
+          A[u] = make_uint4(0, 0, 0, 0); Bv[u] = make_uint4(0, 0, 0, 0);
+          if (row < a.R && y < a.H) {
+            const long long prow = ((long long)b * a.H + y) * a.W;
+            if (xx < a.W) A[u] = *reinterpret_cast<const uint4*>(a.X + (prow + xx) * a.C + c8);
+            if (xx + 1 < a.W) Bv[u] = *reinterpret_cast<const uint4*>(a.X + (prow + xx + 1) * a.C + c8);
+          }
+        }
+      };
+      auto store_x = [&](int rb, const uint4 (&A)[2], const uint4 (&Bv)[2]) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const int row = rb + u * rstep;
+          if (row < a.R) dwf_store_pairs(xt + ((size_t)(row * DWF_SLAB + 8 * g8)) * a.pitch + wj * 4, a.pitch, A[u], Bv[u]);
+        }
+      };
+      uint4 XA[2], XB[2];
+      if (xstager) load_x(r0, XA, XB);
+      for (int u = 0; u < 4; ++u) {
+        const int p = tid + u * DWF_THREADS;
+        if (p < npos) mask[p] = mv[u] >= 0 ? 1 : 0;
+      }
+      for (int p = tid + 4 * DWF_THREADS; p < npos; p += DWF_THREADS) {      // (tiles of more than 1024 positions)
+        const int row = p / ncols, j = p - row * ncols;
+        const int y = y0 - PAD + row, xq = x0 - PAD + j;
+        bool kept = false;
+        if (y >= 0 && y < a.H && xq >= 0 && xq < a.W) kept = a.inv[((long long)b * a.H + y) * a.W + xq] >= 0;
+        mask[p] = kept ? 1 : 0;
+      }
+      __syncthreads();
+      if (stager) {
+        for (int rb = r0; rb < GR; rb += 3 * rstep) {
+          uint4 A[3], Bv[3];
+#pragma unroll
+          for (int u = 0; u < 3; ++u) {
+            const int row = rb + u * rstep;
+            A[u] = make_uint4(0, 0, 0, 0); Bv[u] = make_uint4(0, 0, 0, 0);
+            if (row < GR) {
+              const unsigned m = *reinterpret_cast<const unsigned short*>(mask + row * ncols + 2 * wj);
+              const long long prow = ((long long)b * a.H + (y0 - PAD + row)) * a.W;
+              if (m & 0xffu) A[u] = *reinterpret_cast<const uint4*>(a.dY + (prow + x) * a.C + c8);
+              if (m >> 8) Bv[u] = *reinterpret_cast<const uint4*>(a.dY + (prow + x + 1) * a.C + c8);
+            }
+          }
+          if (rb == r0 && xstager) store_x(r0, XA, XB);          // (arrived long ago)
+#pragma unroll
+          for (int u = 0; u < 3; ++u) {
+            const int row = rb + u * rstep;
+            if (row < GR) dwf_store_pairs(gt + ((size_t)(row * DWF_SLAB + 8 * g8)) * a.pitch + wj * 4, a.pitch, A[u], Bv[u]);
+          }
+        }
+        if (xstager)
+          for (int rb = r0 + 2 * rstep; rb < a.R; rb += 2 * rstep) {
+            load_x(rb, XA, XB);
+            store_x(rb, XA, XB);
+          }
+      }
+    }
+    __syncthreads();
+    // ---- work items: (row, strip) pairs, dealt to the 8 half-wavefronts -------------------------------------------
+    for (int it = slot; it < a.R * a.TS; it += DWF_SLOTS) {
+      const int row = it / a.TS, st = it - row * a.TS;
+      const int y = y0 + row;
+      if (y >= a.H) continue;
+      float acc[8];
+#pragma unroll
+      for (int ox = 0; ox < 8; ++ox) acc[ox] = 0.f;
+      uint32_t xw[4] = {0, 0, 0, 0};
+      if (a.want_dw) {
+        const uint4 v = *reinterpret_cast<const uint4*>(xt + ((size_t)(row * DWF_SLAB + ch)) * a.pitch + st * 16);
+        xw[0] = v.x; xw[1] = v.y; xw[2] = v.z; xw[3] = v.w;
+      }
+#pragma unroll
+      for (int i = 0; i < KS; ++i) {
+        const char* line = gt + ((size_t)((row + i) * DWF_SLAB + ch)) * a.pitch + st * 16;
+        const uint4 lo4 = *reinterpret_cast<const uint4*>(line), hi4 = *reinterpret_cast<const uint4*>(line + 16);
+        const uint32_t Wv[8] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};   // elements (2k, 2k+1) from tile column 8 st
+        uint32_t Ov[7];                                                                    // elements (2k+1, 2k+2)
+#pragma unroll
+        for (int k = 0; k < 7; ++k) Ov[k] = dwf_alignbit(Wv[k + 1], Wv[k]);
+        // (loop orders: consecutive instructions add to different sums)
+        if (a.want_dx) {
+#pragma unroll
+          for (int m = 0; m < NP; ++m)
+#pragma unroll
+            for (int ox = 0; ox < 8; ++ox) {
+              const uint32_t src = (ox & 1) ? Ov[(ox - 1) / 2 + m] : Wv[ox / 2 + m];
+              acc[ox] = dw_dot2(src, wp[i][m], acc[ox]);
+            }
+        }
+        if (a.want_dw) {
+#pragma unroll
+          for (int p = 0; p < 4; ++p)
+#pragma unroll
+            for (int t = 0; t < KS; ++t) {
+              const uint32_t src = (t & 1) ? Ov[p + (t - 1) / 2] : Wv[p + t / 2];
+              accw[(KS - 1 - i) * KS + (KS - 1 - t)] = dw_dot2(xw[p], src, accw[(KS - 1 - i) * KS + (KS - 1 - t)]);
+            }
+          if (i == PAD) {               // the gradients at the strip's own positions: the bias sum
+            constexpr uint32_t kOnes = 0x3f803f80u;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+              const uint32_t src = (PAD & 1) ? Ov[p + (PAD - 1) / 2] : Wv[p + PAD / 2];
+              accw[KS * KS] = dw_dot2(src, kOnes, accw[KS * KS]);
+            }
+          }
+        }
+      }
+      if (a.want_dx && active) {
+        uint16_t* orow = a.dX + (((long long)b * a.H + y) * a.W + x0 + st * 8) * a.C + c;
+#pragma unroll
+        for (int ox = 0; ox < 8; ++ox)
+          if (x0 + st * 8 + ox < a.W) orow[(long long)ox * a.C] = (uint16_t)(dw_pack(acc[ox], 0.f) & 0xffffu);
+      }
+    }
+  }
+  // ---- the workgroup's partial sums of dWd / db: the upper half-wavefronts hand theirs to the lower ones through LDS,
+  // then the DWF_RED sums are added in slot order (a fixed order)
+  if (a.want_dw) {
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(lds);          // [DWF_RED][tap][32]
+    if constexpr (DWF_SLOTS > DWF_RED) {
+      if (slot >= DWF_RED) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) red[((slot - DWF_RED) * NT + t) * DWF_SLAB + ch] = accw[t];
+      }
+      __syncthreads();
+      if (slot < DWF_RED) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) red[(slot * NT + t) * DWF_SLAB + ch] += accw[t];
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) red[(slot * NT + t) * DWF_SLAB + ch] = accw[t];
+    }
+    __syncthreads();
+    for (int o = tid; o < NT * DWF_SLAB; o += DWF_THREADS) {
+      float sum = 0.f;
+#pragma unroll
+      for (int sl = 0; sl < DWF_RED; ++sl) sum += red[sl * NT * DWF_SLAB + o];
+      const int t = o / DWF_SLAB, cl = o - t * DWF_SLAB;
+      if (slab0 + cl < a.C) a.part[((long long)blockIdx.x * NT + t) * a.C + slab0 + cl] = sum;
+    }
+  }
+}
+
 static constexpr int DW_GROUPS = 2;
 static constexpr int DW_MAX_PARTS = 256;
+
+// Tile shape of the LDS-tiled kernel: TS strips of 8 columns wide (line pitch 16 (TS + 1) bytes, rounded up to an odd
+// number of 16-byte units so that the 16-byte reads of neighbouring channels fall into different banks), R rows high,
+// at most 80 KB of LDS so that two workgroups share a CU; chosen for the fewest rounds of 2 x 256 workgroups, then
+// for the least halo.
+struct DwFusedShape { int R, TS, pitch, tiles_y, tiles_x, nwg_x; size_t lds; };
+static DwFusedShape dw_fused_shape(int B, int H, int W, int C, int ks) {
+  DwFusedShape best{};
+  double best_cost = 0;
+  const int nstrips = (int)ceil_div(W, 8), slabs = (int)ceil_div(C, DWF_SLAB);
+  for (int TS = 1; TS <= 6; ++TS) {
+    int units = TS + 1;
+    if (units % 2 == 0) ++units;
+    const int pitch = 16 * units;
+    const int tiles_x = (int)ceil_div(nstrips, TS);
+    const int ts_eff = (int)ceil_div(nstrips, tiles_x);           // strips really used per tile
+    if (ts_eff < TS) continue;                                    // a narrower tile covers the row as well
+    for (int R = 2; R <= 16; ++R) {
+      const size_t lds = std::max((size_t)(2 * R + ks - 1) * DWF_SLAB * pitch + align_up((size_t)(R + ks - 1) * (pitch / 2), 16),
+                                  (size_t)DWF_RED * (ks * ks + 1) * DWF_SLAB * sizeof(float));
+      if (lds > 80 * 1024) break;
+      const int tiles_y = (int)ceil_div(H, R);
+      const int64_t nwg = (int64_t)B * tiles_y * tiles_x * slabs;
+      const double rounds = (double)ceil_div(nwg, 2 * 256);
+      // time of a round ~ items per workgroup (each with ks gradient rows) + the staging of the halo tile
+      const double cost = rounds * ((double)R * TS * ks + 0.15 * (R + ks - 1) * (TS + 1) * 4);
+      if (best.R == 0 || cost < best_cost) {
+        best_cost = cost;
+        best = DwFusedShape{R, TS, pitch, tiles_y, tiles_x, 0, lds};
+      }
+    }
+  }
+  best.nwg_x = (int)std::min<int64_t>((int64_t)B * best.tiles_y * best.tiles_x, DW_MAX_PARTS);
+  return best;
+}
 
 DwPlan plan_dwconv(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int64_t K, int32_t dtype) {
   DwPlan p{};
@@ -474,6 +769,7 @@ DwPlan plan_dwconv(int32_t B, int32_t H, int32_t W, int32_t C, int32_t ks, int64
   // (its parallelism does not depend on K), the plain path slices the kept list.
   const int64_t row_tiles = (int64_t)B * H * ceil_div(W, DW_TX);
   p.nparts = (int)std::max<int64_t>(1, std::min<int64_t>(DW_MAX_PARTS, std::max<int64_t>(ceil_div(row_tiles, 2 * DW_GROUPS), 1)));
+  if (ks == 7 || ks == 3) p.nparts = std::max(p.nparts, dw_fused_shape(B, H, W, C, ks).nwg_x);   // the LDS-tiled kernel's workgroups
   size_t off = 0;
   p.off_inv = off;
   off += align_up((size_t)B * H * W * sizeof(int32_t), 256);
@@ -520,6 +816,33 @@ int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* i
                          inv_ws);
     inv = inv_ws;
   }
+  const Options opt = options();                                             // explicit overrides for sweeps and tests
+  const bool tiled = dtype == SBP_BF16 && C % 8 == 0 && (ks == 7 || ks == 3) && !opt.dw_strips &&
+                     (((uintptr_t)dY | (uintptr_t)X | (uintptr_t)dX) % 16 == 0) && (int64_t)B * H * W * C < (1ll << 40);
+  if (tiled) {
+    const DwFusedShape f = dw_fused_shape(B, H, W, C, ks);
+    DwFusedArgs a{};
+    a.dY = (const uint16_t*)dY; a.inv = inv; a.X = (const uint16_t*)X; a.Wd = (const uint16_t*)Wd;
+    a.dX = (uint16_t*)dX; a.part = part;
+    a.B = B; a.H = H; a.W = W; a.C = C;
+    a.R = f.R; a.TS = f.TS; a.tiles_y = f.tiles_y; a.tiles_x = f.tiles_x; a.ntiles = B * f.tiles_y * f.tiles_x;
+    a.pitch = f.pitch;
+    a.want_dx = dX != nullptr; a.want_dw = (dWd || db) ? 1 : 0;
+    const dim3 grid((unsigned)f.nwg_x, (unsigned)ceil_div(C, DWF_SLAB));
+    static std::once_flag once7, once3;
+    if (f.lds > 64 * 1024) {
+      if (ks == 7) std::call_once(once7, [] { (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dw_fused_kernel<7>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024); });
+      else std::call_once(once3, [] { (void)hipFuncSetAttribute(reinterpret_cast<const void*>(dw_fused_kernel<3>), hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024); });
+    }
+    if (ks == 7) SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_fused_kernel<7>), grid, dim3(DWF_THREADS), f.lds, s, a);
+    else SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, (dw_fused_kernel<3>), grid, dim3(DWF_THREADS), f.lds, s, a);
+    if (a.want_dw) {
+      const int n = (ks * ks + 1) * C;
+      SBP_LAUNCH(SBP_PROF_DWCONV_DW, s, dw_reduce_kernel, dim3((unsigned)ceil_div(n, 32)), dim3(DW_THREADS), 0, s, part, f.nwg_x,
+                 ks * ks, C, dWd, db);
+    }
+    return check_launch("backward_dwconv");
+  }
   const bool fast = dtype == SBP_BF16 && C % 2 == 0 && (ks == 7 || ks == 3) && ((uintptr_t)dY % 4 == 0) &&
                     ((uintptr_t)X % 4 == 0) && ((uintptr_t)Wd % 4 == 0) && ((uintptr_t)dX % 4 == 0);
   if (fast) {
@@ -530,7 +853,6 @@ int32_t launch_backward_dwconv(const DwPlan& p, const void* dY, const int32_t* i
     // rows per strip chunk: a chunk pays for KS - 1 halo rows on top of its own, a short chunk for its start-up;
     // about one workgroup per CU for dX, somewhat more for the weight gradient (measured on the 50 x 84 x 512 map)
     const int64_t row_tiles = (int64_t)tiles_x * B * H * cblocks;
-    const Options opt = options();                                             // explicit overrides for sweeps and tests
     auto pick_rows = [&](int64_t per) {
       int r = (int)std::min<int64_t>(16, std::max<int64_t>(3, ceil_div(row_tiles, per)));
       if (opt.dw_rows) r = opt.dw_rows;

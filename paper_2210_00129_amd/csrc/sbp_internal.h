@@ -46,6 +46,7 @@ struct Options {
   ShapePlan plans[8] = {};
   bool debug_plan = false;
   int  dw_rows = 0;
+  bool dw_strips = false;             // depthwise backward: the register-strip kernels instead of the LDS-tiled one
   bool batch_spread = false;          // batched linear backward: units dealt to the XCDs in turn instead of in runs
   bool batch_dynamic = false;         // batched linear backward: units taken from the XCD queues with atomic counters
   bool dw_separate = false, attn_plain = false, sampler_no_window = false, sampler_no_masks = false, patch_wide = false;

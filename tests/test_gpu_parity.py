@@ -485,22 +485,53 @@ def test_dwconv_convnext_stage3_full_size(k):
 
 @pytest.mark.parametrize("geom", [(2, 50, 84, 512, 7), (1, 7, 9, 24, 7), (2, 5, 5, 8, 3)])
 def test_dwconv_one_launch_two_launches_and_single_outputs_agree(geom):
-    # dX and the weight gradient normally share one launch; the two kernels on their own (switch, or a caller that
-    # wants only one of the outputs) give the same dX bit for bit and the same sums up to their order
+    # the register-strip kernels (what channel counts that are not multiples of 8 get; forced here): dX and the weight
+    # gradient normally share one launch; the two kernels on their own (switch, or a caller that wants only one of the
+    # outputs) give the same dX bit for bit and the same sums up to their order
     B, H, W, C, ks = geom
     X, Wd, dY = si.dwconv_case(B, H, W, C, ks, 151, "bf16")
     idx_np = oracle.sample_indices(B, 0, H, W, 2, 151, 78)
     idx = torch.from_numpy(idx_np).cuda()
     inv = torch.from_numpy(oracle.inverse_map(idx_np, B * H * W)).cuda()
-    both = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
-    with _env(SBP_DW_SEPARATE=1):
-        two = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
-    only_dx = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dX",))
-    only_w = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dWd", "db"))
+    with sbp.options(dw_strips=1):
+        both = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+        with _env(SBP_DW_SEPARATE=1):
+            two = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+        only_dx = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dX",))
+        only_w = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dWd", "db"))
     assert np.array_equal(bits(both[2]), bits(two[2])) and np.array_equal(bits(both[2]), bits(only_dx[2]))
-    rWd, rb, _ = oracle.backward_dwconv(si.to_f64(dY), idx_np, si.to_f64(X), si.to_f64(Wd), ks // 2)
+    rWd, rb, rX = oracle.backward_dwconv(si.to_f64(dY), idx_np, si.to_f64(X), si.to_f64(Wd), ks // 2)
     for got in (both, two, only_w):
         assert nerr(f64(got[0]), rWd) <= TOL_F32 and nerr(f64(got[1]), rb) <= TOL_F32
+    assert nerr(f64(both[2]), rX) <= TOL_BF16_TIGHT
+
+
+@pytest.mark.parametrize("geom", [(2, 50, 84, 512, 7), (1, 7, 9, 24, 7), (2, 5, 5, 8, 3), (1, 33, 70, 40, 7), (3, 4, 100, 72, 3),
+                                  (1, 1, 1, 8, 7), (2, 19, 9, 264, 7)])
+@pytest.mark.parametrize("k", [1, 2, 4])
+def test_dwconv_lds_tiled_kernel_and_single_outputs(geom, k):
+    # the LDS-tiled kernel (bf16, channel counts that are multiples of 8): ragged tiles in rows, columns and channel
+    # slabs, maps smaller than a tile, every keep ratio; a caller that wants only dX or only the weight gradient gets
+    # the same values bit for bit
+    B, H, W, C, ks = geom
+    X, Wd, dY = si.dwconv_case(B, H, W, C, ks, 161, "bf16")
+    idx_np = oracle.sample_indices(B, 0, H, W, k, 161, 79)
+    idx = torch.from_numpy(idx_np).cuda()
+    inv = torch.from_numpy(oracle.inverse_map(idx_np, B * H * W)).cuda()
+    full = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+    rWd, rb, rX = oracle.backward_dwconv(si.to_f64(dY), idx_np, si.to_f64(X), si.to_f64(Wd), ks // 2)
+    assert nerr(f64(full[0]), rWd) <= TOL_F32 and nerr(f64(full[1]), rb) <= TOL_F32
+    assert nerr(f64(full[2]), rX) <= TOL_BF16_TIGHT
+    only_dx = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), inv=inv, want=("dX",))
+    only_w = sbp.backward_dwconv(dY.cuda(), idx, X.cuda(), Wd.cuda(), want=("dWd", "db"))        # inverse map built inside
+    assert np.array_equal(bits(only_dx[2]), bits(full[2]))
+    assert np.array_equal(f64(only_w[0]), f64(full[0])) and np.array_equal(f64(only_w[1]), f64(full[1]))
+    # dropped gradient values are never used
+    dY2 = dY.clone().view(-1, C)
+    dY2[torch.from_numpy(np.setdiff1d(np.arange(B * H * W), idx_np))] = float("nan")
+    again = sbp.backward_dwconv(dY2.view(B, H, W, C).cuda(), idx, X.cuda(), Wd.cuda(), inv=inv)
+    for u, v in zip(again, full):
+        assert np.array_equal(bits(u), bits(v))
 
 
 def test_dwconv_single_kept_position_stamps_kernel():
