@@ -212,15 +212,18 @@ class Job:
         for _ in range(warmup):
             self.step()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        e0.record()
-        for _ in range(steps):
+        ev[0].record()
+        for i in range(steps):
             self.step()
-        e1.record()
+            ev[i + 1].record()
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3 / steps
-        return max(e0.elapsed_time(e1) / steps, 0.0), wall
+        per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+        self.last_stats = {"mean_ms": round(ev[0].elapsed_time(ev[steps]) / steps, 4), "median_ms": round(per[steps // 2], 4),
+                           "min_ms": round(per[0], 4), "max_ms": round(per[-1], 4)}
+        return max(ev[0].elapsed_time(ev[steps]) / steps, 0.0), wall
 
     def kernel_breakdown(self, steps):
         """Second pass with every launch bracketed by HIP events: per-class average durations."""
@@ -410,22 +413,77 @@ def attainable_tflops(flops, algorithmic_bytes):
     return min(PEAK_BF16_TFLOPS, flops / algorithmic_bytes * PEAK_HBM_GBS / 1e3)
 
 
-def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3):
+def ratio_entry(job, ms):
+    tf = job.flops_per_step() / ms / 1e9
+    ceiling = attainable_tflops(job.flops_per_step(), job.algorithmic_bytes_per_step())
+    return {"K": job.K, "ms_per_step": round(ms, 4), "median_ms": job.last_stats["median_ms"], "min_ms": job.last_stats["min_ms"],
+            "tflops": round(tf, 2), "algorithmic_gbs": round(job.algorithmic_bytes_per_step() / ms / 1e6, 1),
+            "attainable_tflops": round(ceiling, 1), "frac_of_attainable": round(tf / ceiling, 4)}
+
+
+def measure_extra(name, r, torch, sbp, si, steps=10, warmup=3, ratios=None):
+    """A workload's step at several keep ratios (the batched calls; buffers of a step exceed the last-level cache only
+    for the larger workloads: every block has its own tensors, see Job)."""
     wl = si.WORKLOADS[name]
     job = Job(wl, torch, sbp, si)
     out = {"workload": name}
-    for rr in (r, 1.0):
+    for rr in (ratios or (r, 1.0)):
         job.set_ratio(rr)
         ms, _ = job.time_steps(steps, warmup)
-        tag = f"r{rr:g}"
-        tf = job.flops_per_step() / ms / 1e9
-        ceiling = attainable_tflops(job.flops_per_step(), job.algorithmic_bytes_per_step())
-        out[tag] = {"ms_per_step": round(ms, 4), "tflops": round(tf, 2),
-                    "algorithmic_gbs": round(job.algorithmic_bytes_per_step() / ms / 1e6, 1),
-                    "attainable_tflops": round(ceiling, 1), "frac_of_attainable": round(tf / ceiling, 4)}
+        out[f"r{rr:g}"] = ratio_entry(job, ms)
     out["speedup_vs_r1"] = round(out["r1"]["ms_per_step"] / out[f"r{r:g}"]["ms_per_step"], 3)
+    out["ideal_flop_ratio_vs_r1"] = round(out["r1"]["K"] / out[f"r{r:g}"]["K"], 3)
     del job
     torch.cuda.empty_cache()
+    return out
+
+
+PEAK_VALU_TFLOPS = 78.6        # fp32 vector ALU without packed instructions: 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+
+
+def measure_dwconv(torch, sbp, si, iters=40, warmup=5):
+    """The depthwise 7 x 7 backward on kept outputs alone (ConvNeXt stage 3: 2 x 50 x 84 x 512) at r = 0.25 / 0.5 / 1:
+    eight rotating tensor sets (8 x 26 MB: the last-level cache holds them - the map is small - so these are
+    cache-resident numbers); algorithmic bytes s (K C + 2 M C) + 49 C (s + 4), flops 4 * 49 K C."""
+    B, H, W, C = 2, 50, 84, 512
+    M = B * H * W
+    out = {"workload": f"depthwise 7x7 backward, map {B}x{H}x{W}x{C} (cache-resident: 8 rotating sets of 26 MB)", "ratios": {}}
+    sets = []
+    for i in range(8):
+        X, Wd, dY = (t.cuda() for t in si.dwconv_case(B, H, W, C, 7, 300 + i, "bf16"))
+        sets.append((X, Wd, dY, torch.empty_like(X), torch.empty((7, 7, C), device="cuda"), torch.empty(C, device="cuda")))
+    from paper_2210_00129_amd import _lib
+    L = _lib.lib()
+    stream = torch.cuda.current_stream().cuda_stream
+    for r in (0.25, 0.5, 1.0):
+        k = sbp.k_from_ratio(r)
+        idx, inv = sbp.sample_indices(B, 0, H, W, k, 0, 1, want_inv=True)
+        K = idx.numel()
+        ws = torch.empty(sbp.backward_dwconv_workspace(B, H, W, C, 7, K, sbp.BF16), dtype=torch.uint8, device="cuda")
+
+        def run(i):
+            X, Wd, dY, dX, dWd, db = sets[i % 8]
+            _lib.check(L.sbp_backward_dwconv(dY.data_ptr(), idx.data_ptr(), inv.data_ptr(), X.data_ptr(), Wd.data_ptr(), B, H, W, C,
+                                             7, 3, K, sbp.BF16, dWd.data_ptr(), db.data_ptr(), dX.data_ptr(), ws.data_ptr(),
+                                             ws.numel(), 0, stream))
+        for i in range(warmup):
+            run(i)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record()
+        for i in range(iters):
+            run(i)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        per = sorted(ev[i].elapsed_time(ev[i + 1]) * 1e3 for i in range(iters))
+        us = ev[0].elapsed_time(ev[iters]) * 1e3 / iters
+        nbytes = 2 * (K * C + 2 * M * C) + 49 * C * 6
+        flops = 4.0 * 49 * K * C
+        out["ratios"][f"r{r:g}"] = {"K": K, "us": round(us, 2), "median_us": round(per[iters // 2], 2), "min_us": round(per[0], 2),
+                                    "algorithmic_mb": round(nbytes / 1e6, 2), "gbs": round(nbytes / us / 1e3, 1),
+                                    "frac_of_hbm_peak": round(nbytes / us / 1e3 / PEAK_HBM_GBS, 4),
+                                    "tflops": round(flops / us / 1e6, 2),
+                                    "frac_of_fp32_valu_peak": round(flops / us / 1e6 / PEAK_VALU_TFLOPS, 4)}
     return out
 
 
@@ -621,6 +679,10 @@ def measure_ceilings(torch, sbp, si, iters=10):
     out["stream_copy"] = {"kernel": "gather_rows_vec16, identity keep list", "mb": round(2 * M * C * 2 / 1e6, 1),
                           "us": round(ms * 1e3, 1), "gbs": round(2 * M * C * 2 / ms / 1e6, 1),
                           "frac_of_hbm_peak": round(2 * M * C * 2 / ms / 1e6 / PEAK_HBM_GBS, 4)}
+    ms = timed(lambda: Y.copy_(X), iters)                 # the runtime's own device-to-device copy of the same 512 MiB
+    out["device_copy"] = {"kernel": "hipMemcpy device to device (torch copy_)", "mb": round(2 * M * C * 2 / 1e6, 1),
+                          "us": round(ms * 1e3, 1), "gbs": round(2 * M * C * 2 / ms / 1e6, 1),
+                          "frac_of_hbm_peak": round(2 * M * C * 2 / ms / 1e6 / PEAK_HBM_GBS, 4)}
     del X, Y
     K, Cin, Cout = 16384, 4096, 4096
     dY = torch.empty((K, Cout), dtype=torch.bfloat16, device="cuda").normal_()
@@ -707,6 +769,7 @@ def main():
         print(json.dumps(timeline_report(job, torch, sbp, wl)))
         return
     ms, wall_ms = job.time_steps(args.steps, args.warmup)
+    main_stats = dict(job.last_stats)
     flops = job.flops_per_step()
     value = flops / ms / 1e9                       # TFLOP/s
     bytes_step = job.algorithmic_bytes_per_step()
@@ -760,10 +823,22 @@ def main():
     breakdown = {c: {"ms_per_step": round(v[0] / max(2, min(args.steps, 5)), 4), "launches": v[1]}
                  for c, v in prof.items() if v[1]}
 
-    # same kernels at r = 1
+    # same kernels at r = 1, and the other keep ratios of the workload's configuration
+    sweep = {f"r{args.ratio:g}": None}
     job.set_ratio(1.0)
     ms_full, _ = job.time_steps(max(3, args.steps // 2), 2)
+    sweep["r1"] = ratio_entry(job, ms_full)
+    for rr in (0.25, 0.75):
+        if rr != args.ratio:
+            job.set_ratio(rr)
+            ms_r, _ = job.time_steps(max(3, args.steps // 2), 2)
+            sweep[f"r{rr:g}"] = ratio_entry(job, ms_r)
     job.set_ratio(args.ratio)
+    job.last_stats = main_stats
+    sweep[f"r{args.ratio:g}"] = ratio_entry(job, ms)
+    for v in sweep.values():
+        v["speedup_vs_r1"] = round(ms_full / v["ms_per_step"], 3)
+        v["ideal_flop_ratio_vs_r1"] = round(wl.M / v["K"], 3)
     # the same step with one cache call and one backward call per layer (the four-call ABI of the method) / batched
     job.batched = not job.batched
     ms_other, _ = job.time_steps(max(3, args.steps // 2), 2)
@@ -777,7 +852,8 @@ def main():
 
     result = {
         "metric": METRIC, "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "median_ms_per_step": main_stats["median_ms"],
+        "min_ms_per_step": main_stats["min_ms"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B}, {wl.N} tokens, {wl.blocks} blocks x "
                                f"{[(s.name, s.Cin, s.Cout) for s in wl.linears]}, grid-wise 2x2 keep r={args.ratio}",
@@ -793,6 +869,7 @@ def main():
         "calls": "one sbp_sample_indices_batch per step, one sbp_forward_cache_batch + one sbp_backward_linear_batch per block" if job.batched
                  else "one sbp_forward_cache + one sbp_backward_linear per layer",
         "other_call_pattern": other_mode,
+        "keep_ratio_sweep": sweep,
         "kernel_breakdown": breakdown,
         "roofline": roofline,
     }
@@ -802,8 +879,10 @@ def main():
         extras = []
         for name in ("vit_tiny_mlp", "convnext_det_s1", "convnext_det_s2", "convnext_s3_block"):
             if name != wl.name:
-                extras.append(measure_extra(name, args.ratio, torch, sbp, si))
+                extras.append(measure_extra(name, args.ratio, torch, sbp, si,
+                                            ratios=(0.25, 0.5, 1.0) if name == "convnext_s3_block" else None))
         result["other_workloads"] = extras
+        result["dwconv_backward"] = measure_dwconv(torch, sbp, si)
         result["mlp_branch_compact"] = measure_mlp_branch(torch, sbp, si, args.ratio)
         result["mlp_branch_compact_vit_tiny"] = measure_mlp_branch(torch, sbp, si, args.ratio, model="vit_tiny_mlp", C=192, Hd=768,
                                                                    row_wise=False)
