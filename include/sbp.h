@@ -208,9 +208,10 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
  * still profits: the weight gradients of a block need only each layer's dY and X_k, so a caller can run the
  * dX of the critical path layer by layer and hand all dW / db of the block to one call, with dX = NULL).
  * bf16 layers within the large-tile engine's limits (Cin % 8 == 0, Cout % 32 == 0, M * max(Cin, Cout) < 2^31,
- * K >= 1, 16-byte aligned tensors) run as ONE grid whose units - dX tiles, dW units, zero-fill and column-sum
- * blocks of all layers - are dispatched longest first, plus one reduction launch for all split sums; a batch
- * with any other layer runs layer by layer, exactly as n calls of sbp_backward_linear would.  A layer whose dW
+ * K >= 1, 16-byte aligned tensors) that are at least 256 channels wide with K >= 1024 run as ONE grid whose
+ * units - dX tiles, dW units (which also sum db), zero-fill blocks of all layers - are laid out in one queue
+ * per XCD, longest first, plus one reduction launch for all split sums; a batch with any other layer runs
+ * layer by layer, exactly as n calls of sbp_backward_linear would.  A layer whose dW
  * needs a single split writes dW directly (no partial sums, no reduction).  Results per layer equal those of
  * sbp_backward_linear up to the summation order of dW / db (bit-identical on exactly representable inputs).
  *   layers     host array of n descriptors, 1 <= n <= SBP_MAX_BATCH_LAYERS; read during the call only
@@ -423,6 +424,9 @@ int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* g
  *   "dw_rows"   rows per strip of the depthwise kernels;  "dw_separate"  "1": dX and dWd as two launches
  *   "attn"      "plain": attention backward without the matrix cores
  *   "sampler_no_window", "sampler_no_masks", "patch_wide", "debug_plan"   "1" | "0"
+ *   "batch_spread"  "1": batched linear call deals its units to the XCDs in turn (no neighbour affinity)
+ *   "batch_dynamic" "1": batched linear call fetches units through one counter per XCD instead of static queues
+ *   "dw_strips"     "1": depthwise backward with the register-strip kernels instead of the LDS-tiled one
  */
 int32_t sbp_set_option(const char* name, const char* value);
 
