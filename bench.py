@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--per-layer", action="store_true",
                     help="one cache call and one backward call per layer instead of one batched call per block")
+    ap.add_argument("--xk-layout", choices=["rows", "kmajor"], default="rows",
+                    help="layout of the cached rows X_k in the batched call pattern: [K, C] or groups of 8 rows [K/8, C, 8]")
     ap.add_argument("--set", action="append", default=[], metavar="NAME=VALUE",
                     help="an explicit override of the library's choices (sbp_set_option), for sweeps")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -63,7 +65,7 @@ class LinearLayer:
         self.Cin, self.Cout = shape.Cin, shape.Cout
         X, W, dY = src
         self.X, self.W, self.dY = X.clone(), W.clone(), dY.clone()     # own memory per block
-        self.Xk = torch.empty((Kmax, self.Cin), dtype=X.dtype, device="cuda")
+        self.Xk = torch.empty((Kmax + 8, self.Cin), dtype=X.dtype, device="cuda")   # (+ 8: room for a padded last row group)
         self.code = sbp.BF16 if dtype == "bf16" else sbp.F32
         self.M = M
         self.L = L
@@ -86,10 +88,11 @@ class LinearLayer:
 class Job:
     """All buffers of a workload and a step() that enqueues one pass of the path."""
 
-    def __init__(self, wl, torch, sbp, si, batched=True):
+    def __init__(self, wl, torch, sbp, si, batched=True, kmajor=False):
         from paper_2210_00129_amd import _lib
         self.wl, self.torch, self.sbp = wl, torch, sbp
         self.batched = batched
+        self.kmajor = bool(kmajor and batched and wl.dtype == "bf16" and all(s.Cin % 8 == 0 for s in wl.linears))
         self.L = _lib.lib()
         self.check = _lib.check
         self.stream = torch.cuda.current_stream().cuda_stream
@@ -144,9 +147,10 @@ class Job:
             ip, vp = self.idx_b[b].data_ptr(), self.inv_b[b].data_ptr()
             lays = (_lib.LinearLayer * len(blk))(*[
                 _lib.LinearLayer(l.dY.data_ptr(), ip, vp, l.Xk.data_ptr(), l.W.data_ptr(), M, 0,
-                                 l.Cin, l.Cout, l.dW.data_ptr(), l.db.data_ptr(), l.dX.data_ptr(), 0, 0) for l in reversed(blk)])
+                                 l.Cin, l.Cout, l.dW.data_ptr(), l.db.data_ptr(), l.dX.data_ptr(), sbp.FLAG_XK_KMAJOR if self.kmajor else 0, 0)
+                for l in reversed(blk)])
             items = (_lib.GatherItem * len(blk))(*[
-                _lib.GatherItem(l.X.data_ptr(), ip, l.Xk.data_ptr(), M, 0, l.Cin, 0) for l in blk])
+                _lib.GatherItem(l.X.data_ptr(), ip, l.Xk.data_ptr(), M, 0, l.Cin, sbp.LAYOUT_KMAJOR if self.kmajor else 0) for l in blk])
             self.batch_args.append((lays, items))
         self.descs = (_lib.SampleDesc * nb)(*[sbp.make_desc(wl.B, wl.P, wl.H, wl.W, 2, 0, 0) for _ in range(nb)])
         self.idx_ptrs = (ctypes.c_void_p * nb)(*[t.data_ptr() for t in self.idx_b])
@@ -275,7 +279,7 @@ def timeline_report(job, torch, sbp, wl):
     e = np.where(tiles, (t[:, 1] - base) / 100.0, s)
     d = e - s
     names = [x.name for x in reversed(wl.linears)]
-    kn = {0: "dX tile", 1: "dW unit", 2: "dW unit (short)", 3: "zero fill", 4: "column sums"}
+    kn = {0: "dX tile", 1: "dW unit", 2: "dW unit (short)", 3: "zero fill", 4: "column sums", 5: "dW unit + db"}
     out = {"workgroups": n, "span_us": round(float(e.max()), 1), "segments": []}
     xcd, ran_on = t[:, 5] & 0xff, (t[:, 5] >> 8) & 0xff      # queue the unit was planned on, XCD that ran it
     keys = sorted({(int(layer[i]), int(kind[i])) for i in range(len(t)) if used[i]}, key=lambda lk: float(np.min(s[(layer == lk[0]) & (kind == lk[1]) & used[:len(t)]])))
@@ -291,7 +295,7 @@ def timeline_report(job, torch, sbp, wl):
             seg["shader_mhz_median"] = round(float(np.median(cyc / np.maximum(d[sl], 1e-3))), 0)
         out["segments"].append(seg)
     out["cu_busy_frac"] = round(float(d[tiles].sum() / (256.0 * e.max())), 3)
-    out["cu_busy_frac_tiles_only"] = round(float(d[tiles & (kind <= 2)].sum() / (256.0 * e.max())), 3)
+    out["cu_busy_frac_tiles_only"] = round(float(d[tiles & ((kind <= 2) | (kind == 5))].sum() / (256.0 * e.max())), 3)
     out["per_xcd_last_end_us"] = [round(float(e[(ran_on == x) & used[:len(t)]].max()), 1) for x in range(8)]
     return out
 
@@ -299,7 +303,7 @@ def timeline_report(job, torch, sbp, wl):
 COPY_BYTES = 256 * 1024 * 1024           # the calibration copy reads 256 MiB and writes 256 MiB
 
 
-def traffic_probe(wl, ratio, torch, sbp, si):
+def traffic_probe(wl, ratio, torch, sbp, si, kmajor=False):
     """Workload of the counter runs (rocprofv3 --pmc <counters> -- python3 bench.py --traffic-probe): a plain device
     copy of known size (what FETCH_SIZE / WRITE_SIZE read for a known number of bytes), then, on buffers pushed out of
     the last-level cache before every call, one block of the workload through the batched calls, the same layers
@@ -317,6 +321,12 @@ def traffic_probe(wl, ratio, torch, sbp, si):
         layers.append(dict(X=X, W=W, dY=dY))
     for rep in range(2):                                   # the second pass is the one to read (code and plans warm)
         flush.fill_(0)
+        if kmajor:                                         # the cached rows in groups of 8 rows, as the batched call can read them
+            Xkt = sbp.forward_cache_batch([l["X"] for l in layers], [idx] * len(layers), layout=sbp.LAYOUT_KMAJOR)
+            flush.fill_(0)
+            sbp.backward_linear_batch([dict(dY=l["dY"], idx=idx, inv=inv, X_k=xk, W=l["W"], M=wl.M, flags=sbp.FLAG_XK_KMAJOR)
+                                       for l, xk in zip(layers, Xkt)])
+            flush.fill_(0)
         Xks = sbp.forward_cache_batch([l["X"] for l in layers], [idx] * len(layers))
         flush.fill_(0)
         sbp.backward_linear_batch([dict(dY=l["dY"], idx=idx, inv=inv, X_k=xk, W=l["W"], M=wl.M) for l, xk in zip(layers, Xks)])
@@ -760,9 +770,9 @@ def main():
         return
     wl = si.WORKLOADS[args.workload]
     if args.traffic_probe:
-        traffic_probe(wl, args.ratio, torch, sbp, si)
+        traffic_probe(wl, args.ratio, torch, sbp, si, kmajor=args.xk_layout == "kmajor")
         return
-    job = Job(wl, torch, sbp, si, batched=not args.per_layer)
+    job = Job(wl, torch, sbp, si, batched=not args.per_layer, kmajor=args.xk_layout == "kmajor")
 
     job.set_ratio(args.ratio)
     if args.timeline:

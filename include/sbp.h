@@ -68,6 +68,18 @@ extern "C" {
 #define SBP_FLAG_DX_COMPACT     2u  /* write dX compact: [K, Cin], no scatter, no zero rows */
 #define SBP_FLAG_ACCUMULATE_DW  4u  /* dW += and db += instead of overwrite */
 #define SBP_FLAG_DW_OUT_BF16    8u  /* sbp_backward_linear: dW is bf16 [Cout, Cin]: the fp32 sum rounded once */
+#define SBP_FLAG_XK_KMAJOR     16u  /* sbp_backward_linear: X_k is in the row-group layout SBP_LAYOUT_KMAJOR (bf16 only) */
+
+/* Layouts of a cached tensor X_k (the kept rows of a layer input, written by sbp_forward_cache_batch, read by the
+ * linear backward for dW = dY_k^T X_k, whose contraction runs over the kept rows):
+ *   SBP_LAYOUT_ROWS    [K, C] row-major: X_k[j][c] at element j * C + c
+ *   SBP_LAYOUT_KMAJOR  [ceil(K / 8), C, 8]: X_k[j][c] at element ((j / 8) * C + c) * 8 + j % 8, i.e. the 8 rows of a
+ *                      group side by side for every channel (one 16-byte piece per channel and group of rows), rows
+ *                      K .. 8 ceil(K / 8) - 1 stored as +0.  8 ceil(K / 8) * C elements.  bf16 with C % 8 == 0 only.
+ *                      The contraction index is then contiguous in memory, as the matrix cores want their operands:
+ *                      the dW units read X_k from LDS with plain 16-byte reads instead of transposing reads. */
+#define SBP_LAYOUT_ROWS   0
+#define SBP_LAYOUT_KMAJOR 1
 
 /*
  * One draw of a grid-wise keep-set (paper, "How to sample the gradient keep mask?": a
@@ -140,14 +152,16 @@ int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t 
  * Step "forward cache" for several tensors in one call (the inputs of all linear layers of a block): item i is
  * sbp_forward_cache(X, idx, M, K, C, dtype, X_k).  Rows whose byte length is a multiple of 16 (16-byte aligned
  * tensors) are served by ONE launch; otherwise the items run one after the other.  1 <= n <= SBP_MAX_BATCH_LAYERS.
+ * layout = SBP_LAYOUT_KMAJOR writes X_k in the row-group layout (bf16, C % 8 == 0, 16-byte aligned tensors; else
+ * SBP_ERR_FLAGS); items of one call that share a layout share a launch.
  */
 typedef struct sbp_gather_item {
   const void*    X;       /* [M, C] */
   const int32_t* idx;     /* [K] */
-  void*          X_k;     /* [K, C] out */
+  void*          X_k;     /* [K, C] out ([ceil(K / 8), C, 8] with SBP_LAYOUT_KMAJOR) */
   int64_t        M, K;
   int32_t        C;
-  int32_t        reserved;/* 0 */
+  int32_t        layout;  /* SBP_LAYOUT_ROWS (0) or SBP_LAYOUT_KMAJOR */
 } sbp_gather_item;
 int32_t sbp_forward_cache_batch(const sbp_gather_item* items, int32_t n, int32_t dtype, void* stream);
 
@@ -183,7 +197,10 @@ int32_t sbp_backward_linear_engine(int64_t M, int64_t K, int32_t Cin, int32_t Co
  *                       library that takes an inverse map (this one, sbp_backward_dwconv,
  *                       sbp_backward_layernorm, sbp_scatter_patches): inv[idx[j]] = j for the kept rows
  *                       and -1 for every dropped row, i.e. what sbp_sample_indices writes.
- *   X_k    device, in,  [K, Cin] rows cached by sbp_forward_cache (may be NULL if dW is NULL)
+ *   X_k    device, in,  [K, Cin] rows cached by sbp_forward_cache (may be NULL if dW is NULL); with
+ *                       SBP_FLAG_XK_KMAJOR in the row-group layout written by sbp_forward_cache_batch (bf16, Cin % 8
+ *                       == 0 and a 16-byte aligned X_k, else SBP_ERR_FLAGS): the large-tile engine reads it as it
+ *                       is, every other engine first copies it back to rows in the workspace
  *   W      device, in,  [Cout, Cin]                       (may be NULL if dX is NULL)
  *   dW, db, dX   device, out; each may be NULL to skip that output.  dW is fp32, or bf16 with
  *                SBP_FLAG_DW_OUT_BF16 (the same fp32 sum, rounded to nearest even once; together with

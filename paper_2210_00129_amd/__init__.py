@@ -20,7 +20,8 @@ from ._lib import GatherItem, LinearLayer, SampleDesc, SbpError  # noqa: F401
 
 F32, BF16 = 0, 1
 GRID_PER_CELL, GRID_SHARED, RANDOM_MASK, TEMPORAL = 0, 1, 2, 3
-FLAG_DY_COMPACT, FLAG_DX_COMPACT, FLAG_ACCUMULATE_DW, FLAG_DW_OUT_BF16 = 1, 2, 4, 8
+FLAG_DY_COMPACT, FLAG_DX_COMPACT, FLAG_ACCUMULATE_DW, FLAG_DW_OUT_BF16, FLAG_XK_KMAJOR = 1, 2, 4, 8, 16
+LAYOUT_ROWS, LAYOUT_KMAJOR = 0, 1
 
 _DTYPES = {torch.float32: F32, torch.bfloat16: BF16}
 
@@ -105,12 +106,16 @@ def forward_cache(X: torch.Tensor, idx: torch.Tensor, out=None) -> torch.Tensor:
     return Xk
 
 
-def forward_cache_batch(Xs, idxs, outs=None):
-    """X_k = X[idx] for several tensors in one call (one launch where every row is a multiple of 16 bytes)."""
+def forward_cache_batch(Xs, idxs, outs=None, layout=LAYOUT_ROWS):
+    """X_k = X[idx] for several tensors in one call (one launch where every row is a multiple of 16 bytes).
+    layout = LAYOUT_KMAJOR writes [ceil(K / 8), C, 8] (groups of 8 kept rows side by side per channel, zero padded)."""
     n = len(Xs)
     if outs is None:
-        outs = [torch.empty((i.numel(), X.shape[1]), dtype=X.dtype, device=X.device) for X, i in zip(Xs, idxs)]
-    items = (GatherItem * n)(*[GatherItem(_dev(X, "X"), _dev(i, "idx"), _dev(o, "X_k"), X.shape[0], i.numel(), X.shape[1], 0)
+        if layout == LAYOUT_KMAJOR:
+            outs = [torch.empty(((i.numel() + 7) // 8, X.shape[1], 8), dtype=X.dtype, device=X.device) for X, i in zip(Xs, idxs)]
+        else:
+            outs = [torch.empty((i.numel(), X.shape[1]), dtype=X.dtype, device=X.device) for X, i in zip(Xs, idxs)]
+    items = (GatherItem * n)(*[GatherItem(_dev(X, "X"), _dev(i, "idx"), _dev(o, "X_k"), X.shape[0], i.numel(), X.shape[1], layout)
                                for X, i, o in zip(Xs, idxs, outs)])
     _lib.check(_lib.lib().sbp_forward_cache_batch(items, n, _dtype_code(Xs[0]), _stream(Xs[0].device)))
     return outs

@@ -30,7 +30,7 @@ class LinearLayer(ctypes.Structure):
 
 class GatherItem(ctypes.Structure):
     """Mirror of sbp_gather_item in include/sbp.h."""
-    _fields_ = [("X", c_vp), ("idx", c_vp), ("X_k", c_vp), ("M", c_i64), ("K", c_i64), ("C", c_i32), ("reserved", c_i32)]
+    _fields_ = [("X", c_vp), ("idx", c_vp), ("X_k", c_vp), ("M", c_i64), ("K", c_i64), ("C", c_i32), ("layout", c_i32)]
 
 
 # name -> (restype, argtypes); every symbol include/sbp.h declares

@@ -232,8 +232,10 @@ int32_t sbp_forward_cache(const void* X, const int32_t* idx, int64_t M, int64_t 
 
 static int32_t validate_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t dtype, uint32_t flags) {
   if (!elem_bytes(dtype)) return fail(SBP_ERR_DTYPE, "unknown dtype %d", dtype);
-  if (flags & ~(SBP_FLAG_DY_COMPACT | SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16))
+  if (flags & ~(SBP_FLAG_DY_COMPACT | SBP_FLAG_DX_COMPACT | SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16 | SBP_FLAG_XK_KMAJOR))
     return fail(SBP_ERR_FLAGS, "unknown flags 0x%x", flags);
+  if ((flags & SBP_FLAG_XK_KMAJOR) && (dtype != SBP_BF16 || Cin % 8 != 0))
+    return fail(SBP_ERR_FLAGS, "SBP_FLAG_XK_KMAJOR needs bf16 and Cin %% 8 == 0 (dtype %d, Cin %d)", dtype, Cin);
   if (M < 1 || M > INT32_MAX || Cin < 1 || Cout < 1)
     return fail(SBP_ERR_SHAPE, "bad shape M=%lld Cin=%d Cout=%d", (long long)M, Cin, Cout);
   if (K < 0 || K > M) return fail(SBP_ERR_SHAPE, "need 0 <= K <= M, got K=%lld M=%lld", (long long)K, (long long)M);
@@ -248,7 +250,9 @@ int32_t sbp_forward_cache_batch(const sbp_gather_item* items, int32_t n, int32_t
   if (n < 1 || n > SBP_MAX_BATCH_LAYERS) return fail(SBP_ERR_SHAPE, "need 1 <= n <= %d items, got %d", SBP_MAX_BATCH_LAYERS, n);
   for (int i = 0; i < n; ++i) {
     const sbp_gather_item& g = items[i];
-    if (g.reserved) return fail(SBP_ERR_FLAGS, "item %d: reserved field must be 0", i);
+    if (g.layout != SBP_LAYOUT_ROWS && g.layout != SBP_LAYOUT_KMAJOR) return fail(SBP_ERR_FLAGS, "item %d: unknown layout %d", i, g.layout);
+    if (g.layout == SBP_LAYOUT_KMAJOR && (dtype != SBP_BF16 || g.C % 8 != 0 || (uintptr_t)g.X % 16 || (uintptr_t)g.X_k % 16))
+      return fail(SBP_ERR_FLAGS, "item %d: SBP_LAYOUT_KMAJOR needs bf16, C %% 8 == 0 and 16-byte aligned tensors", i);
     if (g.M < 1 || g.M > INT32_MAX || g.C < 1) return fail(SBP_ERR_SHAPE, "item %d: bad shape M=%lld C=%d", i, (long long)g.M, g.C);
     if (g.K < 0 || g.K > g.M) return fail(SBP_ERR_SHAPE, "item %d: need 0 <= K <= M, got K=%lld M=%lld", i, (long long)g.K, (long long)g.M);
     if (g.K > 0 && (!g.X || !g.idx || !g.X_k)) return fail(SBP_ERR_NULL, "item %d: X, idx and X_k must be non-NULL", i);
@@ -269,6 +273,7 @@ int32_t check_linear_args(const void* dY, const int32_t* idx, const void* Xk, co
   if (need_idx && !idx && K > 0) return fail(SBP_ERR_NULL, "idx is NULL");
   if (dW && !Xk && K > 0) return fail(SBP_ERR_NULL, "X_k is NULL but dW is requested");
   if (dX && !W) return fail(SBP_ERR_NULL, "W is NULL but dX is requested");
+  if ((flags & SBP_FLAG_XK_KMAJOR) && ((uintptr_t)Xk % 16)) return fail(SBP_ERR_FLAGS, "SBP_FLAG_XK_KMAJOR needs a 16-byte aligned X_k");
   return SBP_OK;
 }
 }  // namespace sbp

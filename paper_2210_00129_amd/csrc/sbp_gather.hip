@@ -106,7 +106,108 @@ __global__ void __launch_bounds__(256) gather_rows_batch_kernel(const GatherBatc
   }
 }
 
+// ---- row-group layout [ceil(K / 8)][C][8] (bf16): the 8 kept rows of a group side by side for every channel ----
+// A thread owns 8 rows x 2 channels: eight 4-byte loads along the rows (a wavefront reads 256 contiguous bytes of every
+// row), one byte permute per output word, two 16-byte stores (32 contiguous bytes per thread, 2 KB per wavefront).
+struct KmajorItem {
+  const uint32_t* X; const int32_t* idx; uint32_t* Xk;
+  uint32_t total;            // threads of the item: groups of 8 rows x pairs of channels
+  FastDiv c2;                // pairs of channels per row
+  int K;
+  int blk_start, nblk;
+};
+struct KmajorBatchArgs { int n; KmajorItem it[kMaxGatherBatch]; };
+
+// TO_ROWS = false: X_k(row groups) from X[idx[.]];  true: rows [K][C] back from row groups (idx unused)
+template <bool TO_ROWS>
+__global__ void __launch_bounds__(256) kmajor_batch_kernel(const KmajorBatchArgs a) {
+  int qi = 0;
+  for (int i = 1; i < a.n; ++i)
+    if ((int)blockIdx.x >= a.it[i].blk_start) qi = i;
+  const KmajorItem& g = a.it[qi];
+  const uint32_t stride = (uint32_t)g.nblk * 256u;
+  const uint32_t c2n = g.c2.d;
+  for (uint32_t t = ((uint32_t)blockIdx.x - (uint32_t)g.blk_start) * 256u + threadIdx.x; t < g.total; t += stride) {
+    uint32_t kg, c2;
+    g.c2.divmod(t, kg, c2);
+    uint32_t v[8];
+    if (!TO_ROWS) {
+      int row[8];           // (all eight row ids first, then all eight loads: nothing waits in between)
+#pragma unroll
+      for (int r = 0; r < 8; ++r) row[r] = g.idx[min((int)(8 * kg) + r, g.K - 1)];
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v[r] = g.X[(long long)row[r] * c2n + c2];
+#pragma unroll
+      for (int r = 0; r < 8; ++r)
+        if ((int)(8 * kg) + r >= g.K) v[r] = 0;
+      uint4 lo, hi;     // the 8 rows of the even / odd channel of the pair
+      lo.x = __builtin_amdgcn_perm(v[1], v[0], 0x05040100u); hi.x = __builtin_amdgcn_perm(v[1], v[0], 0x07060302u);
+      lo.y = __builtin_amdgcn_perm(v[3], v[2], 0x05040100u); hi.y = __builtin_amdgcn_perm(v[3], v[2], 0x07060302u);
+      lo.z = __builtin_amdgcn_perm(v[5], v[4], 0x05040100u); hi.z = __builtin_amdgcn_perm(v[5], v[4], 0x07060302u);
+      lo.w = __builtin_amdgcn_perm(v[7], v[6], 0x05040100u); hi.w = __builtin_amdgcn_perm(v[7], v[6], 0x07060302u);
+      uint4* dst = reinterpret_cast<uint4*>(g.Xk) + ((long long)kg * c2n + c2) * 2;
+      dst[0] = lo;
+      dst[1] = hi;
+    } else {
+      const uint4* src = reinterpret_cast<const uint4*>(g.X) + ((long long)kg * c2n + c2) * 2;
+      const uint4 lo = src[0], hi = src[1];
+      const uint32_t l[4] = {lo.x, lo.y, lo.z, lo.w}, h[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {     // word q: rows 2q, 2q + 1 of one channel
+        v[2 * q] = __builtin_amdgcn_perm(h[q], l[q], 0x05040100u);
+        v[2 * q + 1] = __builtin_amdgcn_perm(h[q], l[q], 0x07060302u);
+      }
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int j = (int)(8 * kg) + r;
+        if (j < g.K) g.Xk[(long long)j * c2n + c2] = v[r];
+      }
+    }
+    if (stride > ~t) return;
+  }
+}
+
+static int32_t launch_kmajor(bool to_rows, const sbp_gather_item* items, int32_t n, hipStream_t s) {
+  KmajorBatchArgs a{};
+  int blk = 0, m = 0;
+  for (int i = 0; i < n; ++i) {
+    if (items[i].K == 0) continue;
+    const long long total = ceil_div(items[i].K, 8) * (long long)(items[i].C / 2);
+    if (total >= 0xFFFFFFFFll || items[i].K > INT32_MAX) return fail(SBP_ERR_SHAPE, "tensor too large for the row-group layout");
+    KmajorItem& g = a.it[m++];
+    g.X = static_cast<const uint32_t*>(items[i].X); g.idx = items[i].idx; g.Xk = static_cast<uint32_t*>(items[i].X_k);
+    g.total = (uint32_t)total;
+    g.c2 = FastDiv((uint32_t)(items[i].C / 2));
+    g.K = (int)items[i].K;
+    g.blk_start = blk;
+    g.nblk = (int)std::min<long long>(ceil_div(total, 256), 256 * 64);
+    blk += g.nblk;
+  }
+  a.n = m;
+  if (m == 0) return SBP_OK;
+  if (to_rows) SBP_LAUNCH(SBP_PROF_GATHER, s, kmajor_batch_kernel<true>, dim3((unsigned)blk), dim3(256), 0, s, a);
+  else SBP_LAUNCH(SBP_PROF_GATHER, s, kmajor_batch_kernel<false>, dim3((unsigned)blk), dim3(256), 0, s, a);
+  return check_launch("kmajor_batch");
+}
+
+// rows [K][C] (bf16, C % 8 == 0, 16-byte aligned) back from the row-group layout: for the engines that read X_k by rows
+int32_t launch_kmajor_to_rows(const void* Xt, int64_t K, int32_t C, void* Xrows, hipStream_t s) {
+  sbp_gather_item it{};
+  it.X = Xt; it.idx = nullptr; it.X_k = Xrows; it.M = K; it.K = K; it.C = C; it.layout = SBP_LAYOUT_KMAJOR;
+  return launch_kmajor(true, &it, 1, s);
+}
+
 int32_t launch_gather_rows_batch(const sbp_gather_item* items, int32_t n, int32_t elem_bytes, hipStream_t s) {
+  {  // items in the row-group layout share one launch of their own; the others go on below
+    sbp_gather_item km[kMaxGatherBatch], rows[kMaxGatherBatch];
+    int nk = 0, nr = 0;
+    for (int i = 0; i < n; ++i) (items[i].layout == SBP_LAYOUT_KMAJOR ? km[nk++] : rows[nr++]) = items[i];
+    if (nk > 0) {
+      const int32_t st = launch_kmajor(false, km, nk, s);
+      if (st != SBP_OK || nr == 0) return st;
+      return launch_gather_rows_batch(rows, nr, elem_bytes, s);
+    }
+  }
   bool fused = n > 1 && n <= kMaxGatherBatch;
   for (int i = 0; i < n && fused; ++i) {
     const long long row_bytes = (long long)items[i].C * elem_bytes;

@@ -66,6 +66,7 @@ int32_t launch_gather_rows(const void* X, const int32_t* idx, int64_t K, int32_t
                            void* Xk, hipStream_t s);
 
 int32_t launch_gather_rows_batch(const sbp_gather_item* items, int32_t n, int32_t elem_bytes, hipStream_t s);
+int32_t launch_kmajor_to_rows(const void* Xt, int64_t K, int32_t C, void* Xrows, hipStream_t s);
 
 // patches of a p x p, stride p down-sampling layer: gather [K, p*p*C] rows / scatter them back with zero fill
 int32_t launch_patches(bool scatter, const void* src, const int32_t* idx, const int32_t* inv, int32_t B, int32_t H, int32_t W,
@@ -89,6 +90,7 @@ struct LinearPlan {
   int    db_slice_rows; // kept rows per db slice
   size_t off_partial;   // fp32 [splits, Cout, Cin]
   size_t off_inv;       // int32 [M]
+  size_t off_xrows;     // bf16 [K, Cin]: X_k by rows when it came in the row-group layout and the engine reads rows
   size_t bytes;
 };
 int32_t check_linear_args(const void* dY, const int32_t* idx, const void* Xk, const void* W, int64_t M, int64_t K,

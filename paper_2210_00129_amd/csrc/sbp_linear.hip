@@ -69,6 +69,7 @@ struct LinArgs {
   int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
   int db_in_dw;                       // large-tile kernel: the dW units of the first tile column also produce db (one
                                       // partial per split in dbp); no column-sum blocks then
+  int xk_kmajor;                      // large-tile kernel: Xk is in the row-group layout [K / 8][Cin][8]
 };
 
 // Zero fill of the dropped rows.  A wavefront takes 64 consecutive rows: every lane looks one row up
@@ -160,6 +161,7 @@ __device__ __forceinline__ int segment_unit(int wg_global, int s, int n) {
 }
 
 // One unit of the large-tile engine: kind 0 = dX tile number L, kind 1 / 2 = dW unit number L among the long /
+// (with db_in_dw: kind 5 = dW unit number L among those of the first tile column, kind 1 among the others)
 // short splits (a tile of dW over the kept rows of one split, written as an fp32 partial sum).
 __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind, int L) {
   const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
@@ -174,15 +176,39 @@ __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind,
     return;
   }
   // the first n_big splits have rows_per_split rows each, the others rows_small
-  const int tiles_w = ((a.Cout + big::BT - 1) / big::BT) * tiles_n;
+  const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
   const int covered = min(a.K, a.n_big * a.rows_per_split);
-  const int sl = L / tiles_w;                                  // split within its kind
-  const int rem = L - sl * tiles_w;
-  const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
+  int sl, tile_m, tile_n;                                      // sl: split within its kind
+  if (!a.db_in_dw) {
+    const int tiles_w = tiles_m * tiles_n;
+    sl = L / tiles_w;
+    const int rem = L - sl * tiles_w;
+    tile_m = rem / tiles_n; tile_n = rem - tile_m * tiles_n;
+  } else if (kind == 5) {                                      // the units of the first tile column, which also sum db
+    sl = L / tiles_m;
+    tile_m = L - sl * tiles_m; tile_n = 0;
+    kind = 1;
+  } else {                                                     // ... and the other tile columns
+    const int tn1 = tiles_n - 1, tiles_w = tiles_m * tn1;
+    sl = L / tiles_w;
+    const int rem = L - sl * tiles_w;
+    tile_m = rem / tn1; tile_n = rem - tile_m * tn1 + 1;
+  }
   const int j0 = kind == 1 ? sl * a.rows_per_split : covered + sl * a.rows_small;
   const int j1 = min(a.K, j0 + (kind == 1 ? a.rows_per_split : a.rows_small));
   const int split = kind == 1 ? sl : a.n_big + sl;
   float* part = a.part + (long long)split * a.Cout * a.Cin;
+  if (a.xk_kmajor) {
+    if (a.db_in_dw && tile_n == 0) {
+      float* dbp = a.dbp + (long long)split * a.Cout;
+      if (a.idx_in) big::dw_tile<true, true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
+      else big::dw_tile<false, true, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
+      return;
+    }
+    if (a.idx_in) big::dw_tile<true, false, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+    else big::dw_tile<false, false, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+    return;
+  }
   if (a.db_in_dw && tile_n == 0) {
     float* dbp = a.dbp + (long long)split * a.Cout;
     if (a.idx_in) big::dw_tile<true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
@@ -291,7 +317,7 @@ __global__ void __launch_bounds__(256, 1) linear_multi_kernel(const MultiArgs a,
   const bool stamp = a.timeline != nullptr && slot < a.timeline_cap;
   unsigned long long t0 = 0, c0 = 0;
   if (stamp) { t0 = wall_clock64(); c0 = clock64(); }
-  if (kind <= 2) {
+  if (kind <= 2 || kind == 5) {
     big_unit(smem, la, kind, L);
   } else if (kind == 3) {
     zero_rows_block(la, L);                        // la.n_zero = number of these blocks
@@ -749,6 +775,8 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   off += align_up(((size_t)splits * Cout * Cin + (size_t)std::max(p.db_slices, splits) * Cout) * sizeof(float), 256);
   p.off_inv = off;
   if (!(flags & SBP_FLAG_DX_COMPACT)) off += align_up((size_t)M * sizeof(int32_t), 256);
+  p.off_xrows = off;      // X_k copied back to rows, for the engines that do not read the row-group layout
+  if (flags & SBP_FLAG_XK_KMAJOR) off += align_up((size_t)K * Cin * 2, 256);
   p.bytes = off;
   return p;
 }
@@ -908,6 +936,14 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   const bool aligned = ((uintptr_t)dY % 16 == 0) && ((uintptr_t)Xk % 16 == 0) && ((uintptr_t)W % 16 == 0) &&
                        ((uintptr_t)dX % 16 == 0);
   const bool use_mfma = p.mfma && aligned;
+  bool kmajor = (flags & SBP_FLAG_XK_KMAJOR) && dW && Xk;
+  if (kmajor && !(use_mfma && p.big && p.rows_per_split % 8 == 0 && p.rows_small % 8 == 0)) {
+    void* rows = static_cast<char*>(ws) + p.off_xrows;
+    const int32_t st = launch_kmajor_to_rows(Xk, K, Cin, rows, s);
+    if (st != SBP_OK) return st;
+    Xk = rows;
+    kmajor = false;
+  }
   if (use_mfma) {
     const uint16_t* dYh = static_cast<const uint16_t*>(dY);
     LinArgs a{};
@@ -916,6 +952,7 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
     a.dX = static_cast<uint16_t*>(dX); a.part = part; a.dbp = db ? dbp : nullptr;
     a.K = (int)K; a.M = (int)M; a.Cin = Cin; a.Cout = Cout;
     a.rows_per_split = p.rows_per_split; a.db_slice_rows = p.db_slice_rows;
+    a.xk_kmajor = kmajor ? 1 : 0;
     const bool want_dx = dX != nullptr, want_dw = dW != nullptr;
     if (p.big)
       launch_linear_big(p, a, want_dx, want_dw, scatter, s);
@@ -1045,6 +1082,7 @@ static bool batch_layer_fits(const sbp_linear_layer& l, int32_t dtype) {
 // the per-XCD queues in place: every CU is in matrix-core code for the whole launch and the chip then runs at 1.6-1.7 GHz
 // (1.3 GHz before the queues cut the traffic between the L2s and memory by a third); dW units of 99 / 66 stages took
 // 95 / 63 us, dX tiles of 96 / 72 / 24 stages 89 / 67 / 29 us.  The shorter dX tiles are scaled as in the single-layer costs.
+static constexpr int64_t kNsStageBatchDwDb = 1040;      // dW units that also sum db
 static constexpr int64_t kNsFixedBatchDw = 3000, kNsStageBatchDw = 930, kNsFixedBatch = 9000, kNsStageBatch256 = 830,
                          kNsStageBatch128 = 500, kNsStageBatch64 = 400;
 struct BatchLayerChoice { int dx_bm, splits; };
@@ -1071,7 +1109,13 @@ static int batch_jobs(const sbp_linear_layer* L, int n, const BatchLayerChoice* 
     if (l.dW) {
       const int64_t rps = split_rows(l.K, c[i].splits);
       const int64_t nsp = ceil_div(l.K, rps);
-      out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + kNsStageBatchDw * ceil_div(std::min<int64_t>(rps, l.K), big::KB), i, 1};
+      const int64_t stages = ceil_div(std::min<int64_t>(rps, l.K), big::KB), tiles_m = ceil_div(l.Cout, big::BT);
+      if (l.db) {          // the units of the first tile column also sum db and take longer: a kind of their own, dispatched first
+        out[nj++] = Job{tiles_m * nsp, kNsFixedBatchDw + kNsStageBatchDwDb * stages, i, 5};
+        if (tiles_n > 1) out[nj++] = Job{tiles_m * (tiles_n - 1) * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages, i, 1};
+      } else {
+        out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages, i, 1};
+      }
       const bool direct = nsp == 1 && !(l.flags & (SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16));
       if (!direct) red += (double)(nsp + 1) * l.Cout * l.Cin * 4.0 / kReduceBytesPerNs;
     }
@@ -1102,7 +1146,7 @@ static int64_t partition_xcd(const Job* jobs, int nj, XcdQueues* out) {
   int order[kMaxJobs];
   for (int j = 0; j < nj; ++j) order[j] = j;
   std::stable_sort(order, order + nj, [&](int u, int v) {
-    const bool hu = jobs[u].kind > 2, hv = jobs[v].kind > 2;
+    const bool hu = jobs[u].kind == 3 || jobs[u].kind == 4, hv = jobs[v].kind == 3 || jobs[v].kind == 4;
     return hu != hv ? hv : jobs[u].len > jobs[v].len;
   });
   using MinHeap = std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>>;
@@ -1333,6 +1377,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     la.n_big = b.splits; la.rows_small = 0; la.dx_bm = b.dx_bm;
     la.n_zero = scatter && l.M > l.K ? big_zero_blocks(l.M) : 0;
     la.db_in_dw = l.db && l.dW ? 1 : 0;
+    la.xk_kmajor = (l.flags & SBP_FLAG_XK_KMAJOR) ? 1 : 0;     // (equal splits of a multiple of 64 rows: every split starts on a row group)
     lds = std::max(lds, (size_t)big::RING + std::max<size_t>((size_t)(b.rows_per_split + 2 * big::KB), big::BT) * sizeof(int));
     lds = std::max<size_t>(lds, 16 * 1024);     // the column-sum blocks' staging
     any = any || l.dW || l.db || l.dX;
@@ -1354,7 +1399,8 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     const LinArgs& la = a.lay[jobs[j].layer];
     const int64_t tiles_n = ceil_div(la.Cin, big::BT), tiles_w = ceil_div(la.Cout, big::BT) * tiles_n;
     const int64_t expect = jobs[j].kind == 0 ? ceil_div(la.K, la.dx_bm) * tiles_n
-                         : jobs[j].kind == 1 ? tiles_w * la.n_big
+                         : jobs[j].kind == 1 ? (la.db_in_dw ? tiles_w - ceil_div(la.Cout, big::BT) : tiles_w) * la.n_big
+                         : jobs[j].kind == 5 ? (la.db_in_dw ? ceil_div(la.Cout, big::BT) * la.n_big : -1)
                          : jobs[j].kind == 3 ? la.n_zero
                          : jobs[j].kind == 4 ? ceil_div(la.Cout, 256) * ceil_div(la.K, la.db_slice_rows) : -1;
     if (jobs[j].n != expect || (int64_t)la.n_big * la.rows_per_split < la.K || jobs[j].n <= 0)

@@ -348,24 +348,51 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 // registers beyond the 256 the tile already fills, and the compiler then shuffles accumulators every step.)
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-template <bool GATHER, bool DB>
+// XT: X_k lies in memory in groups of 8 rows, [row group][channel][8 rows] (one 16-byte piece per channel and group): the
+// contraction index is contiguous, a stage is 4 groups x 256 pieces that are copied as they lie (a copy instruction takes
+// 64 consecutive pieces of one group) and a fragment is one 16-byte LDS read per lane (lane l: group l / 32 of the step,
+// channel l % 32) instead of two transposing reads.
+struct GroupCopy {
+  uint32_t voff[4];       // this lane's piece of group n of a stage, in bytes from the stage's first group
+  __device__ __forceinline__ void init(uint32_t Cin, int col0, int lane, int wave) {
+    const uint32_t c = (uint32_t)min(col0 + 64 * wave + lane, (int)Cin - 1);
+#pragma unroll
+    for (int n = 0; n < 4; ++n) voff[n] = ((uint32_t)n * Cin + c) * 16u;
+  }
+  // groups g0 .. g0 + 3 of the operand
+  __device__ __forceinline__ void issue(const char* src, uint32_t Cin, int g0, char* tile, int wave) const {
+    const char* base = src + (size_t)g0 * Cin * 16u;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) async_copy16(base + voff[n], tile + (n * 256 + 64 * wave) * 16);
+  }
+  // the same, groups clamped to last_group (partial last stage)
+  __device__ __forceinline__ void issue_clamped(const char* src, uint32_t Cin, int g0, int last_group, char* tile, int wave) const {
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+      async_copy16(src + (size_t)min(g0 + n, last_group) * Cin * 16u + voff[0], tile + (n * 256 + 64 * wave) * 16);
+  }
+};
+
+template <bool GATHER, bool DB, bool XT = false, int DBH = 0>
 struct DwProb {
   static constexpr bool SWAP = false;
   static constexpr int FM = 4, CPA = 4, CPB = 4, STAGE = 2 * TILE_BYTES, NEXTRA = 0;
-  static constexpr int NREAD = 16, NPRE = GATHER ? 2 : 0;   // the 4 id reads pair up into 2 instructions
-  float accdb[DB ? 4 : 1];
+  static constexpr int NREAD = XT ? 12 : 16, NPRE = GATHER ? 2 : 0;   // the 4 id reads pair up into 2 instructions
+  // The two wavefronts that own the same rows of the tile (and so hold the same dY fragments) share the sums: DBH = 0
+  // adds up fragments 0 and 1, DBH = 1 fragments 2 and 3.
+  float accdb[DB ? 2 : 1];
   __device__ __forceinline__ void init_db(int) {
     if constexpr (DB) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) accdb[i] = 0.f;
+      for (int i = 0; i < 2; ++i) accdb[i] = 0.f;
     }
   }
   __device__ __forceinline__ void extra(const bf16x8_t (&a)[4]) {
     if constexpr (DB) {
       const bf16x2_t ones = __builtin_bit_cast(bf16x2_t, 0x3f803f80u);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u32x4_t w = __builtin_bit_cast(u32x4_t, a[i]);
+      for (int i = 0; i < 2; ++i) {
+        const u32x4_t w = __builtin_bit_cast(u32x4_t, a[2 * DBH + i]);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           unsigned wq = w[q];
@@ -376,8 +403,11 @@ struct DwProb {
     }
   }
   SlowCopy ca, cb;
+  GroupCopy cg;           // XT: copies of X_k
+  int last_group;         // XT: last row group of the split, counted from b_src
+  uint32_t cin;
   const char* a_src;      // dY (GATHER) or dY + j0 rows
-  const char* b_src;      // X_k + j0 rows
+  const char* b_src;      // X_k + j0 rows (XT: + j0 / 8 row groups)
   const int* rows;        // LDS table: row of dY for kept row j0 + i
   uint32_t a_ld, b_ld, rid[4], rid_next[4];
   int wave, nrows, a_off[4], b_off[4];   // nrows = j1 - j0
@@ -400,42 +430,62 @@ struct DwProb {
     }
   }
   __device__ __forceinline__ void issue_b(int s, char* buf, bool partial) {
-    if (!partial) cb.issue(b_src + (size_t)s * KB * b_ld, buf + TILE_BYTES, wave);
-    else cb.issue_clamped(b_src, b_ld, s * KB, nrows - 1, buf + TILE_BYTES, wave);
+    if constexpr (XT) {
+      if (!partial) cg.issue(b_src, cin, s * (KB / 8), buf + TILE_BYTES, wave);
+      else cg.issue_clamped(b_src, cin, s * (KB / 8), last_group, buf + TILE_BYTES, wave);
+    } else {
+      if (!partial) cb.issue(b_src + (size_t)s * KB * b_ld, buf + TILE_BYTES, wave);
+      else cb.issue_clamped(b_src, b_ld, s * KB, nrows - 1, buf + TILE_BYTES, wave);
+    }
+  }
+  __device__ __forceinline__ bf16x8_t read_b(const char* buf, int ks, int f) const {
+    if constexpr (XT) return *reinterpret_cast<const bf16x8_t*>(buf + TILE_BYTES + b_off[f] + ks * (2 * 256 * 16));
+    else return read_slow1(buf + TILE_BYTES, b_off[f], ks);
   }
   __device__ __forceinline__ void read(const char* buf, int ks, bf16x8_t (&a)[4], bf16x8_t (&b)[4]) const {
-    b[0] = read_slow1(buf + TILE_BYTES, b_off[0], ks);
+    b[0] = read_b(buf, ks, 0);
     a[0] = read_slow1(buf, a_off[0], ks);
 #pragma unroll
-    for (int f = 1; f < 4; ++f) b[f] = read_slow1(buf + TILE_BYTES, b_off[f], ks);
+    for (int f = 1; f < 4; ++f) b[f] = read_b(buf, ks, f);
 #pragma unroll
     for (int f = 1; f < 4; ++f) a[f] = read_slow1(buf, a_off[f], ks);
   }
+  // rows kvalid .. 31 of the last stage: the dY tile is zeroed, so whatever X_k holds there adds nothing (XT: the rows of a
+  // partly filled group come from memory, where rows past K are stored as zeros and rows of the next split are finite
+  // values of X_k that meet zeros of dY; whole groups past the split are copies of its last group)
   __device__ __forceinline__ void zero_tail(char* buf, int kvalid) const {
     zero_slow_tail(buf, kvalid, threadIdx.x);
-    zero_slow_tail(buf + TILE_BYTES, kvalid, threadIdx.x);
+    if constexpr (!XT) zero_slow_tail(buf + TILE_BYTES, kvalid, threadIdx.x);
   }
 };
 
-template <bool GATHER, bool DB = false>
-__device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
+template <bool GATHER, bool DB, bool XT, int DBH>
+__device__ __forceinline__ void dw_tile_impl(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                                         const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
-                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp = nullptr) {
+                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp) {
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
   const int nrows = j1 - j0;
   const int nk = (nrows + KB - 1) / KB;
 
-  DwProb<GATHER, DB> pb;
+  DwProb<GATHER, DB, XT, DBH> pb;
   pb.init_db(lane);
   pb.wave = wave;
   pb.nrows = nrows;
   pb.a_ld = (uint32_t)Cout * 2u;
   pb.b_ld = (uint32_t)Cin * 2u;
   pb.ca.init(pb.a_ld, m0, Cout, lane, wave);
-  pb.cb.init(pb.b_ld, n0, Cin, lane, wave);
-  pb.b_src = reinterpret_cast<const char*>(Xk) + (size_t)j0 * pb.b_ld;
+  pb.cin = (uint32_t)Cin;
+  pb.last_group = 0;
+  if constexpr (XT) {       // j0 is a multiple of 8 (host)
+    pb.cg.init((uint32_t)Cin, n0, lane, wave);
+    pb.b_src = reinterpret_cast<const char*>(Xk) + (size_t)(j0 >> 3) * Cin * 16u;
+    pb.last_group = ((nrows + 7) >> 3) - 1;
+  } else {
+    pb.cb.init(pb.b_ld, n0, Cin, lane, wave);
+    pb.b_src = reinterpret_cast<const char*>(Xk) + (size_t)j0 * pb.b_ld;
+  }
   pb.rows = nullptr;
   if (GATHER) {
     int* rows = reinterpret_cast<int*>(smem + RING);        // one stage more than the split has: ids are read ahead
@@ -450,7 +500,12 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
     pb.a_src = reinterpret_cast<const char*>(dY) + (size_t)j0 * pb.a_ld;
   }
   slow_tile_lane_offs<BT, 4>(wm, lane, pb.a_off);
-  slow_tile_lane_offs<BT, 4>(wn, lane, pb.b_off);
+  if constexpr (XT) {
+#pragma unroll
+    for (int f = 0; f < 4; ++f) pb.b_off[f] = ((lane >> 5) * 256 + wn + 32 * f + (lane & 31)) * 16;
+  } else {
+    slow_tile_lane_offs<BT, 4>(wn, lane, pb.b_off);
+  }
 
   f32x16_t acc[4][4];
   zero_acc<4, 4>(acc);
@@ -458,13 +513,12 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
   ring_loop(smem, pb, nk, tail, nrows - (nk - 1) * KB, acc);
 
   if constexpr (DB) {
-    // lanes l and l + 32 hold the two j groups of column 32 i + l % 32; the two wavefronts that own different rows of the
-    // tile (wn = 0) write the sums
+    // lanes l and l + 32 hold the two j groups of column 32 i + l % 32; every wavefront writes the sums of its two fragments
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 2; ++i) {
       const float both = pb.accdb[i] + __shfl_xor(pb.accdb[i], 32);
-      const int o = m0 + wm + 32 * i + (lane & 31);
-      if (wn == 0 && lane < 32 && o < Cout) dbp[o] = both;
+      const int o = m0 + wm + 32 * (2 * DBH + i) + (lane & 31);
+      if (lane < 32 && o < Cout) dbp[o] = both;
     }
   }
   // register v of lane l of block (i, j) is C[row wm + 32 i + 8 (v >> 2) + 4 (l >> 5) + (v & 3)][col wn + 32 j + (l & 31)]
@@ -490,6 +544,21 @@ __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__
           if (o < Cout && col < Cin) part[(long long)o * Cin + col] = acc[i][jn][v];
         }
       }
+  }
+}
+
+template <bool GATHER, bool DB = false, bool XT = false>
+__device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
+                                        const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
+                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp = nullptr) {
+  if constexpr (DB) {
+    // (wave-uniform: both versions run the same barriers in the same order)
+    if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 1)
+      dw_tile_impl<GATHER, true, XT, 1>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp);
+    else
+      dw_tile_impl<GATHER, true, XT, 0>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp);
+  } else {
+    dw_tile_impl<GATHER, false, XT, 0>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp);
   }
 }
 

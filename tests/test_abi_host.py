@@ -135,6 +135,11 @@ def test_backward_linear_argument_errors():
     assert call(M=0) == -2
     assert call(Cin=0) == -2
     assert call(flags=64) == -8
+    # the row-group layout of X_k exists for bf16 with Cin % 8 == 0 and a 16-byte aligned X_k only
+    assert call(flags=16, dtype=0) == -8
+    assert call(flags=16, Cin=60) == -8
+    assert call(flags=16, Xk=p + 8) == -8
+    assert L.sbp_backward_linear_workspace(100, 50, 64, 128, 1, 16) >= ws + 50 * 64 * 2   # room to copy X_k back to rows
     assert call(ws=None) == -6
     assert call(ws_bytes=ws - 1) == -6
     assert call(ws=p * 4 + 8) == -6
@@ -161,7 +166,7 @@ def test_backward_linear_engine_report_and_plan():
     # the bf16 weight gradient is a property of the last step only: same plan, same workspace
     assert sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16, sbp.FLAG_DW_OUT_BF16) == \
         sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16)
-    assert sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16, 16) == 0      # unknown flag
+    assert sbp.backward_linear_workspace(12608, 6336, 768, 768, sbp.BF16, 32) == 0      # unknown flag
     # rows of dY that byte offsets of 32 bits cannot reach: the general engine takes the shape
     assert sbp.backward_linear_engine(1 << 20, 1 << 19, 4096, 4096, sbp.BF16)[0] == "mfma"
 
@@ -346,3 +351,17 @@ def test_fast_division_of_the_streaming_kernels_is_exact(tmp_path):
                     os.path.join(here, "fastdiv_check.cpp"), "-o", exe], check=True)
     out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
     assert out.startswith("ok "), out
+
+
+def test_forward_cache_batch_rejects_bad_layouts():
+    L = _lib.lib()
+    p = 4096
+
+    def call(layout, dtype=1, C=64, X=p, Xk=p):
+        items = (_lib.GatherItem * 1)(_lib.GatherItem(X, p, Xk, 100, 50, C, layout))
+        return L.sbp_forward_cache_batch(items, 1, dtype, None)
+
+    assert call(2) == -8 and call(-1) == -8
+    assert call(1, dtype=0) == -8            # row groups: bf16 only
+    assert call(1, C=60) == -8
+    assert call(1, X=p + 8) == -8 and call(1, Xk=p + 2) == -8
