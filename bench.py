@@ -635,9 +635,9 @@ def measure_attention(torch, sbp, si, iters=30, warmup=6):
     197 tokens kept (r = 0.5) and all 197 (r = 1).  Six rotating input sets; algorithmic bytes = kept rows of qkv,
     A, dA read once, lse read, dqkv written; flops = the five products of the backward (10 n_k^2 d per head)."""
     import math
-    B, h, d = 64, 12, 64
-    out = {"workload": f"vit_base attention core backward, B={B}, {h} heads of {d}", "sizes": {}}
-    for tag, n_k in (("r0.5", 99), ("r1", 197)):
+    B0, h, d = 64, 12, 64
+    out = {"workload": f"vit_base attention core backward, B={B0}, {h} heads of {d} (long: B=8, 1024 kept tokens)", "sizes": {}}
+    for tag, n_k, B in (("r0.5", 99, B0), ("r1", 197, B0), ("long", 1024, 8)):
         K = B * n_k
         sets = []
         for i in range(6):

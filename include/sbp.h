@@ -391,8 +391,10 @@ int32_t sbp_backward_layerscale(const void* dU_k, const void* Y_k, const float* 
  *   d       head dimension: 16, 32, 64 or 128.   scale: usually 1/sqrt(d).
  * All pointers 16-byte aligned.  fp32 arithmetic and accumulation; in bf16 the probabilities S and dM are
  * rounded to bf16 before the second products (matrix cores), outputs rounded once.  Deterministic.
- * sbp_backward_attention_engine (host only) reports which kernel serves a size: 1 = matrix-core kernel
- * (bf16, d in {32, 64, 128}, the kept tokens of one head fit LDS: n_k <= 256 at d = 64), 0 = plain kernel.
+ * sbp_backward_attention_engine (host only) reports which kernel serves a size: 1 = matrix-core kernel with one
+ * workgroup per (sample, head) (bf16, d in {32, 64, 128}, the kept tokens of one head fit LDS: n_k <= 256 at
+ * d = 64), 2 = matrix-core kernel tiled over chunks of 128 tokens (bf16, d in {32, 64, 128}, any n_k),
+ * 0 = plain kernel (fp32, d = 16).
  */
 int32_t sbp_backward_attention_engine(int32_t n_k, int32_t d, int32_t dtype);
 int32_t sbp_backward_attention(const void* qkv_k, const void* A_k, const void* dA_k, const float* lse_k,
@@ -439,7 +441,8 @@ int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* g
  *               for every shape / one shape (ignored where it does not fit the kept-row count)
  *   "order"     "a,b,c", a permutation of 0,1,2: dispatch order of the kinds of workgroups
  *   "dw_rows"   rows per strip of the depthwise kernels;  "dw_separate"  "1": dX and dWd as two launches
- *   "attn"      "plain": attention backward without the matrix cores
+ *   "attn"      "plain": attention backward without the matrix cores | "whole": one workgroup per (sample, head)
+ *               where its tokens fit LDS | "tiled": chunks of 128 tokens per workgroup, at any size
  *   "sampler_no_window", "sampler_no_masks", "patch_wide", "debug_plan"   "1" | "0"
  *   "batch_spread"  "1": batched linear call deals its units to the XCDs in turn (no neighbour affinity)
  *   "batch_dynamic" "1": batched linear call fetches units through one counter per XCD instead of static queues

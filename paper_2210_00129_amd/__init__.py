@@ -350,11 +350,12 @@ def backward_dwconv(dY, idx, X, Wd, inv=None, want=("dWd", "db", "dX"), dWd=None
 
 
 def backward_attention_engine(n_k, d, dtype_code) -> str:
-    """Which kernel serves an attention backward of n_k kept tokens per sample: 'mfma' or 'plain'."""
+    """Which kernel serves an attention backward of n_k kept tokens per sample: 'mfma' (one workgroup per head),
+    'mfma_tiled' (chunks of 128 tokens) or 'plain'."""
     e = int(_lib.lib().sbp_backward_attention_engine(n_k, d, dtype_code))
     if e < 0:
         raise ValueError(_lib.lib().sbp_last_error().decode())
-    return "mfma" if e == 1 else "plain"
+    return {1: "mfma", 2: "mfma_tiled"}.get(e, "plain")
 
 
 def backward_attention(qkv_k, A_k, dA_k, lse_k, B, h, d, scale, out=None):

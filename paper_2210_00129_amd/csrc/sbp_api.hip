@@ -92,9 +92,10 @@ static bool apply_option(Options& o, const char* name, const char* v) {
     return true;
   }
   if (n == "attn") {
-    if (!v) { o.attn_plain = false; return true; }
-    if (std::strcmp(v, "plain")) return false;
-    o.attn_plain = true;
+    if (!v) { o.attn_mode = 0; return true; }
+    const int m = !std::strcmp(v, "plain") ? 1 : !std::strcmp(v, "whole") ? 2 : !std::strcmp(v, "tiled") ? 3 : -1;
+    if (m < 0) return false;
+    o.attn_mode = m;
     return true;
   }
   bool* flag = n == "debug_plan" ? &o.debug_plan : n == "dw_separate" ? &o.dw_separate

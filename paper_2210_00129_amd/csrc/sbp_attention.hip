@@ -10,6 +10,7 @@
 // LDS) and a plain fp32-arithmetic kernel for fp32 tensors and for sizes beyond the LDS budget.
 #include <cstdlib>
 #include <cstring>
+#include <type_traits>
 
 #include "sbp_internal.h"
 #include "sbp_mfma_gemm.h"
@@ -245,138 +246,218 @@ struct AttnPieces {
   }
 };
 
-// dK and dV of the 32 keys of block jb (one wavefront)
+// dK and dV of 32 keys (one wavefront): the keys' fragments live in registers, the queries come block by block from
+// LDS tiles (tq, tg: rows of q and dA; lse_s, delta_s: their tables), any number of tiles one after the other.
+template <int D>
+struct AttnKeyAcc {
+  static constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32;
+  f32x16_t dv[DB], dk[DB];
+  bf16x8_t kf[KS], vf[KS];
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int x = 0; x < DB; ++x)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dv[x][e] = dk[x][e] = 0.f;
+  }
+  // fragments of the keys from LDS tiles (rows row0 .. row0 + 31)
+  __device__ __forceinline__ void keys_from_lds(const char* tk, const char* tv, int row0, int lane) {
+    const int foff = (row0 + (lane & 31)) * PITCH + 16 * (lane >> 5);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = *reinterpret_cast<const bf16x8_t*>(tk + foff + ks * 32);
+      vf[ks] = *reinterpret_cast<const bf16x8_t*>(tv + foff + ks * 32);
+    }
+  }
+  // ... or straight from memory: k and v of token `tok` (zeros if valid is false), row pointers of the head's columns
+  __device__ __forceinline__ void keys_from_memory(const uint16_t* krow, const uint16_t* vrow, bool valid, int lane) {
+    const int u = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 a = make_uint4(0, 0, 0, 0), b = a;
+      if (valid) {
+        a = *reinterpret_cast<const uint4*>(krow + 16 * ks + 8 * u);
+        b = *reinterpret_cast<const uint4*>(vrow + 16 * ks + 8 * u);
+      }
+      kf[ks] = __builtin_bit_cast(bf16x8_t, a);
+      vf[ks] = __builtin_bit_cast(bf16x8_t, b);
+    }
+  }
+  __device__ __forceinline__ void run(const char* tq, const char* tg, const float* lse_s, const float* delta_s, int nblk,
+                                      float scale, int lane) {
+    const int u = lane >> 5, lrow = lane & 31;
+    const int foff = lrow * PITCH + 16 * u;              // 16-byte operand read of row (lane & 31), k chunk 8u
+    const float c2 = scale * kLog2e;
+    for (int ib = 0; ib < nblk; ++ib) {
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(tq + ib * 32 * PITCH + foff + ks * 32);
+        const bf16x8_t gf = *reinterpret_cast<const bf16x8_t*>(tg + ib * 32 * PITCH + foff + ks * 32);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], s, 0, 0, 0);      // rows i, columns j
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float4 l4 = *reinterpret_cast<const float4*>(lse_s + ib * 32 + 8 * q4 + 4 * u);
+        const float4 d4 = *reinterpret_cast<const float4*>(delta_s + ib * 32 + 8 * q4 + 4 * u);
+        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float p = __builtin_amdgcn_exp2f(s[4 * q4 + e] * c2 - lv[e]);
+          s[4 * q4 + e] = p;
+          dp[4 * q4 + e] = p * (dp[4 * q4 + e] - dl[e]);
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8_t pf = pack8(s, ks), dsf = pack8(dp, ks);
+#pragma unroll
+        for (int x = 0; x < DB; ++x) {
+          const bf16x8_t gt = read_tr_tokens<PITCH>(tg, ib * 32 + 16 * ks, 32 * x, lane);
+          const bf16x8_t qt = read_tr_tokens<PITCH>(tq, ib * 32 + 16 * ks, 32 * x, lane);
+          dv[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf, dv[x], 0, 0, 0);   // rows head dim, columns j
+          dk[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[x], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // key j = first key of the block + (lane & 31); out: row 0 of the head's columns in dqkv
+  __device__ __forceinline__ void store(uint16_t* __restrict__ out, int j, int n_k, int h, float scale, int lane) const {
+    const int u = lane >> 5;
+    if (j < n_k) {
+      uint16_t* o = out + (long long)j * (3LL * h * D);
+#pragma unroll
+      for (int x = 0; x < DB; ++x)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int dcol = 32 * x + 8 * q4 + 4 * u;
+          uint2 w;
+          w.x = bf16_pack(dk[x][4 * q4] * scale, dk[x][4 * q4 + 1] * scale);
+          w.y = bf16_pack(dk[x][4 * q4 + 2] * scale, dk[x][4 * q4 + 3] * scale);
+          *reinterpret_cast<uint2*>(o + (long long)h * D + dcol) = w;
+          w.x = bf16_pack(dv[x][4 * q4], dv[x][4 * q4 + 1]);
+          w.y = bf16_pack(dv[x][4 * q4 + 2], dv[x][4 * q4 + 3]);
+          *reinterpret_cast<uint2*>(o + 2LL * h * D + dcol) = w;
+        }
+    }
+  }
+};
+
+// dQ of 32 queries (one wavefront): the queries' fragments, lse and delta live in registers, the keys come block by
+// block from LDS tiles (tk, tv).
+template <int D>
+struct AttnQueryAcc {
+  static constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32;
+  f32x16_t dq[DB];
+  bf16x8_t qf[KS], gf[KS];
+  float l, dl;                   // lse * log2(e) and delta of query (lane & 31)
+  __device__ __forceinline__ void zero() {
+#pragma unroll
+    for (int x = 0; x < DB; ++x)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) dq[x][e] = 0.f;
+  }
+  __device__ __forceinline__ void queries_from_lds(const char* tq, const char* tg, const float* lse_s, const float* delta_s,
+                                                   int row0, int lane) {
+    const int foff = (row0 + (lane & 31)) * PITCH + 16 * (lane >> 5);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[ks] = *reinterpret_cast<const bf16x8_t*>(tq + foff + ks * 32);
+      gf[ks] = *reinterpret_cast<const bf16x8_t*>(tg + foff + ks * 32);
+    }
+    l = lse_s[row0 + (lane & 31)];
+    dl = delta_s[row0 + (lane & 31)];
+  }
+  // straight from memory: q, dA, A rows of the token (head's columns) and its lse; zeros if valid is false
+  __device__ __forceinline__ void queries_from_memory(const uint16_t* qrow, const uint16_t* grow, const uint16_t* arow,
+                                                      const float* lse_tok, bool valid, int lane) {
+    const int u = lane >> 5;
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 a = make_uint4(0, 0, 0, 0), b = a, c = a;
+      if (valid) {
+        a = *reinterpret_cast<const uint4*>(qrow + 16 * ks + 8 * u);
+        b = *reinterpret_cast<const uint4*>(grow + 16 * ks + 8 * u);
+        c = *reinterpret_cast<const uint4*>(arow + 16 * ks + 8 * u);
+      }
+      qf[ks] = __builtin_bit_cast(bf16x8_t, a);
+      gf[ks] = __builtin_bit_cast(bf16x8_t, b);
+      const uint32_t gw[4] = {b.x, b.y, b.z, b.w}, aw[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) part += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
+    }
+    dl = part + __shfl_xor(part, 32);          // the two halves of every 16 columns lie 32 lanes apart
+    l = valid ? *lse_tok * kLog2e : 0.f;
+  }
+  __device__ __forceinline__ void run(const char* tk, const char* tv, int nblk, float scale, int lane) {
+    const int u = lane >> 5, lrow = lane & 31;
+    const int foff = lrow * PITCH + 16 * u;
+    const float c2 = scale * kLog2e;
+    for (int jb = 0; jb < nblk; ++jb) {
+      f32x16_t s, dp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(tk + jb * 32 * PITCH + foff + ks * 32);
+        const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(tv + jb * 32 * PITCH + foff + ks * 32);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);      // rows j, columns i
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks], dp, 0, 0, 0);
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float p = __builtin_amdgcn_exp2f(s[e] * c2 - l);
+        dp[e] = p * (dp[e] - dl);
+      }
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        const bf16x8_t dsf = pack8(dp, ks);
+#pragma unroll
+        for (int x = 0; x < DB; ++x) {
+          const bf16x8_t kt = read_tr_tokens<PITCH>(tk, jb * 32 + 16 * ks, 32 * x, lane);
+          dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dq[x], 0, 0, 0);   // rows head dim, columns i
+        }
+      }
+    }
+  }
+  __device__ __forceinline__ void store(uint16_t* __restrict__ out, int i, int n_k, int h, float scale, int lane) const {
+    const int u = lane >> 5;
+    if (i < n_k) {
+      uint16_t* o = out + (long long)i * (3LL * h * D);
+#pragma unroll
+      for (int x = 0; x < DB; ++x)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          uint2 w;
+          w.x = bf16_pack(dq[x][4 * q4] * scale, dq[x][4 * q4 + 1] * scale);
+          w.y = bf16_pack(dq[x][4 * q4 + 2] * scale, dq[x][4 * q4 + 3] * scale);
+          *reinterpret_cast<uint2*>(o + 32 * x + 8 * q4 + 4 * u) = w;
+        }
+    }
+  }
+};
+
 template <int D>
 __device__ __forceinline__ void attn_key_block(const AttnTiles<D>& T, int jb, int nblk, int n_k, int h, float scale,
                                                uint16_t* __restrict__ out, int lane) {
-  constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32;
-  const int u = lane >> 5, lrow = lane & 31;
-  const int foff = lrow * PITCH + 16 * u;              // 16-byte operand read of row (lane & 31), k chunk 8u
-  const float c2 = scale * kLog2e;
-  f32x16_t dv[DB], dk[DB];
-#pragma unroll
-  for (int x = 0; x < DB; ++x)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) dv[x][e] = dk[x][e] = 0.f;
-  bf16x8_t kf[KS], vf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    kf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tk + jb * 32 * PITCH + foff + ks * 32);
-    vf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tv + jb * 32 * PITCH + foff + ks * 32);
-  }
-  for (int ib = 0; ib < nblk; ++ib) {
-    f32x16_t s, dp;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8_t qf = *reinterpret_cast<const bf16x8_t*>(T.tq + ib * 32 * PITCH + foff + ks * 32);
-      const bf16x8_t gf = *reinterpret_cast<const bf16x8_t*>(T.tg + ib * 32 * PITCH + foff + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks], s, 0, 0, 0);      // rows i, columns j
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks], dp, 0, 0, 0);
-    }
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) {
-      const float4 l4 = *reinterpret_cast<const float4*>(T.lse_s + ib * 32 + 8 * q4 + 4 * u);
-      const float4 d4 = *reinterpret_cast<const float4*>(T.delta_s + ib * 32 + 8 * q4 + 4 * u);
-      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float p = __builtin_amdgcn_exp2f(s[4 * q4 + e] * c2 - lv[e]);
-        s[4 * q4 + e] = p;
-        dp[4 * q4 + e] = p * (dp[4 * q4 + e] - dl[e]);
-      }
-    }
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const bf16x8_t pf = pack8(s, ks), dsf = pack8(dp, ks);
-#pragma unroll
-      for (int x = 0; x < DB; ++x) {
-        const bf16x8_t gt = read_tr_tokens<PITCH>(T.tg, ib * 32 + 16 * ks, 32 * x, lane);
-        const bf16x8_t qt = read_tr_tokens<PITCH>(T.tq, ib * 32 + 16 * ks, 32 * x, lane);
-        dv[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf, dv[x], 0, 0, 0);   // rows head dim, columns j
-        dk[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt, dsf, dk[x], 0, 0, 0);
-      }
-    }
-  }
-  const int j = jb * 32 + lrow;
-  if (j < n_k) {
-    uint16_t* o = out + (long long)j * (3LL * h * D);
-#pragma unroll
-    for (int x = 0; x < DB; ++x)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int dcol = 32 * x + 8 * q4 + 4 * u;
-        uint2 w;
-        w.x = bf16_pack(dk[x][4 * q4] * scale, dk[x][4 * q4 + 1] * scale);
-        w.y = bf16_pack(dk[x][4 * q4 + 2] * scale, dk[x][4 * q4 + 3] * scale);
-        *reinterpret_cast<uint2*>(o + (long long)h * D + dcol) = w;
-        w.x = bf16_pack(dv[x][4 * q4], dv[x][4 * q4 + 1]);
-        w.y = bf16_pack(dv[x][4 * q4 + 2], dv[x][4 * q4 + 3]);
-        *reinterpret_cast<uint2*>(o + 2LL * h * D + dcol) = w;
-      }
-  }
+  AttnKeyAcc<D> acc;
+  acc.zero();
+  acc.keys_from_lds(T.tk, T.tv, jb * 32, lane);
+  acc.run(T.tq, T.tg, T.lse_s, T.delta_s, nblk, scale, lane);
+  acc.store(out, jb * 32 + (lane & 31), n_k, h, scale, lane);
 }
 
-// dQ of the 32 queries of block ib (one wavefront)
 template <int D>
 __device__ __forceinline__ void attn_query_block(const AttnTiles<D>& T, int ib, int nblk, int n_k, int h, float scale,
                                                  uint16_t* __restrict__ out, int lane) {
-  constexpr int PITCH = AttnLds<D>::PITCH, KS = D / 16, DB = D / 32;
-  const int u = lane >> 5, lrow = lane & 31;
-  const int foff = lrow * PITCH + 16 * u;
-  const float c2 = scale * kLog2e;
-  f32x16_t dq[DB];
-#pragma unroll
-  for (int x = 0; x < DB; ++x)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) dq[x][e] = 0.f;
-  bf16x8_t qf[KS], gf[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    qf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tq + ib * 32 * PITCH + foff + ks * 32);
-    gf[ks] = *reinterpret_cast<const bf16x8_t*>(T.tg + ib * 32 * PITCH + foff + ks * 32);
-  }
-  const float l = T.lse_s[ib * 32 + lrow], dl = T.delta_s[ib * 32 + lrow];
-  for (int jb = 0; jb < nblk; ++jb) {
-    f32x16_t s, dp;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) s[e] = dp[e] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(T.tk + jb * 32 * PITCH + foff + ks * 32);
-      const bf16x8_t vf = *reinterpret_cast<const bf16x8_t*>(T.tv + jb * 32 * PITCH + foff + ks * 32);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);      // rows j, columns i
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks], dp, 0, 0, 0);
-    }
-#pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const float p = __builtin_amdgcn_exp2f(s[e] * c2 - l);
-      dp[e] = p * (dp[e] - dl);
-    }
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const bf16x8_t dsf = pack8(dp, ks);
-#pragma unroll
-      for (int x = 0; x < DB; ++x) {
-        const bf16x8_t kt = read_tr_tokens<PITCH>(T.tk, jb * 32 + 16 * ks, 32 * x, lane);
-        dq[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt, dsf, dq[x], 0, 0, 0);   // rows head dim, columns i
-      }
-    }
-  }
-  const int i = ib * 32 + lrow;
-  if (i < n_k) {
-    uint16_t* o = out + (long long)i * (3LL * h * D);
-#pragma unroll
-    for (int x = 0; x < DB; ++x)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        uint2 w;
-        w.x = bf16_pack(dq[x][4 * q4] * scale, dq[x][4 * q4 + 1] * scale);
-        w.y = bf16_pack(dq[x][4 * q4 + 2] * scale, dq[x][4 * q4 + 3] * scale);
-        *reinterpret_cast<uint2*>(o + 32 * x + 8 * q4 + 4 * u) = w;
-      }
-  }
+  AttnQueryAcc<D> acc;
+  acc.zero();
+  acc.queries_from_lds(T.tq, T.tg, T.lse_s, T.delta_s, ib * 32, lane);
+  acc.run(T.tk, T.tv, nblk, scale, lane);
+  acc.store(out, ib * 32 + (lane & 31), n_k, h, scale, lane);
 }
 
 // One (sample, head) per workgroup of 4 wavefronts: load, then the key blocks, then the query blocks.  Any
@@ -405,6 +486,87 @@ __global__ void __launch_bounds__(256, D == 128 ? 1 : 2) attn_bwd_mfma_kernel(co
 }
 
 // ------------------------------------------------------------------------------------------------
+// Tiled MFMA kernel: any number of kept tokens.  A workgroup owns a chunk of 128 tokens of one (sample, head) in one of
+// two roles: as keys (dK, dV of the chunk: every wavefront holds the k and v fragments of its 32 keys in registers and
+// the queries - rows of q and dA, lse, delta - stream through LDS in tiles of 128) or as queries (dQ of the chunk: q,
+// dA fragments, lse and delta in registers, the keys - rows of k and v - stream through LDS).  The chunk itself never
+// touches LDS, a tile is two [128][D] images (37 KB at D = 64): three workgroups per CU.  Every output element is
+// written by exactly one wavefront, sums run in token order: deterministic, no atomics.
+// ------------------------------------------------------------------------------------------------
+static constexpr int kAttnChunk = 128;
+
+template <int D, bool KEY>
+__device__ __forceinline__ void attn_tiled_body(char* smem, const AttnItem& it, int chunk, int n_k, int h, float scale) {
+  constexpr int CH = D / 8, PITCH = AttnLds<D>::PITCH, R = kAttnChunk * CH / 256;   // 16-byte pieces per thread, tensor and tile
+  char* t1 = smem;                                   // rows of q (key role) or k (query role)
+  char* t2 = t1 + kAttnChunk * PITCH;                // rows of dA or v
+  float* lse_s = reinterpret_cast<float*>(t2 + kAttnChunk * PITCH);
+  float* delta_s = lse_s + kAttnChunk;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const long long ldq = 3LL * h * D, lda = (long long)h * D;
+  const int own = chunk * kAttnChunk + wave * 32 + (lane & 31);     // this lane's token of the chunk
+  const bool own_ok = own < n_k;
+  const int own_c = min(own, n_k - 1);
+  typename std::conditional<KEY, AttnKeyAcc<D>, AttnQueryAcc<D>>::type acc;
+  acc.zero();
+  if constexpr (KEY) acc.keys_from_memory(it.q + own_c * ldq + (long long)h * D, it.q + own_c * ldq + 2LL * h * D, own_ok, lane);
+  else acc.queries_from_memory(it.q + own_c * ldq, it.g + own_c * lda, it.a + own_c * lda, it.lse + (long long)own_c * h, own_ok, lane);
+  const int npad = (n_k + 31) & ~31;
+  for (int t0 = 0; t0 < npad; t0 += kAttnChunk) {
+    const int rows = min(kAttnChunk, npad - t0);            // rows of this tile (a multiple of 32); rows past n_k are zeros
+    uint4 x1[R], x2[R], x3[KEY ? R : 1];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int p = t + 256 * r, tok = t0 + p / CH, ch = p % CH;
+      x1[r] = x2[r] = make_uint4(0, 0, 0, 0);
+      if constexpr (KEY) x3[r] = make_uint4(0, 0, 0, 0);
+      if (tok < n_k) {
+        if constexpr (KEY) {
+          x1[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + 8 * ch);
+          x2[r] = *reinterpret_cast<const uint4*>(it.g + tok * lda + 8 * ch);
+          x3[r] = *reinterpret_cast<const uint4*>(it.a + tok * lda + 8 * ch);
+        } else {
+          x1[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + (long long)h * D + 8 * ch);
+          x2[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + 2LL * h * D + 8 * ch);
+        }
+      }
+    }
+    float lv = 0.f;
+    if (KEY && t < kAttnChunk && t0 + t < n_k) lv = it.lse[(long long)(t0 + t) * h] * kLog2e;
+    __syncthreads();                                        // the previous tile has been consumed
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int p = t + 256 * r, tok = p / CH, ch = p % CH;
+      *reinterpret_cast<uint4*>(t1 + tok * PITCH + ch * 16) = x1[r];
+      *reinterpret_cast<uint4*>(t2 + tok * PITCH + ch * 16) = x2[r];
+      if constexpr (KEY) {
+        const uint32_t gw[4] = {x2[r].x, x2[r].y, x2[r].z, x2[r].w}, aw[4] = {x3[r].x, x3[r].y, x3[r].z, x3[r].w};
+        float sacc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sacc += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
+        for (int m = 1; m < CH; m <<= 1) sacc += __shfl_xor(sacc, m);
+        if (ch == 0) delta_s[tok] = sacc;
+      }
+    }
+    if (KEY && t < kAttnChunk) lse_s[t] = lv;
+    __syncthreads();
+    if constexpr (KEY) acc.run(t1, t2, lse_s, delta_s, rows >> 5, scale, lane);
+    else acc.run(t1, t2, rows >> 5, scale, lane);
+  }
+  acc.store(it.o, own, n_k, h, scale, lane);
+}
+
+template <int D>
+__global__ void __launch_bounds__(256, D == 128 ? 1 : 3) attn_bwd_tiled_kernel(const uint16_t* __restrict__ qkv, const uint16_t* __restrict__ A,
+                                                              const uint16_t* __restrict__ dA, const float* __restrict__ lse,
+                                                              int n_k, int h, float scale, int nchunks, uint16_t* __restrict__ dqkv) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const AttnItem it = attn_item(qkv, A, dA, lse, dqkv, blockIdx.z, blockIdx.y, n_k, h, D);
+  if ((int)blockIdx.x < nchunks) attn_tiled_body<D, true>(smem, it, blockIdx.x, n_k, h, scale);
+  else attn_tiled_body<D, false>(smem, it, blockIdx.x - nchunks, n_k, h, scale);
+}
+
+// ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
 static constexpr size_t kAttnMaxLds = 160 * 1024;
@@ -414,12 +576,15 @@ static size_t attn_lds_bytes(int n_k, int d) {
   return d == 32 ? AttnLds<32>::bytes(npad) : d == 64 ? AttnLds<64>::bytes(npad) : AttnLds<128>::bytes(npad);
 }
 
-// 1: MFMA kernel, 0: plain kernel
+// 2: tiled MFMA kernel, 1: MFMA kernel with one workgroup per (sample, head), 0: plain kernel
 int attention_engine(int32_t n_k, int32_t d, int32_t dtype) {
   if (dtype != SBP_BF16) return 0;
   if (d != 32 && d != 64 && d != 128) return 0;
-  if (options().attn_plain) return 0;                       // explicit override (sbp_set_option "attn" = "plain")
-  return attn_lds_bytes(n_k, d) <= kAttnMaxLds ? 1 : 0;
+  const Options opt = options();
+  if (opt.attn_mode == 1) return 0;                         // explicit overrides (sbp_set_option "attn" = "plain" | "whole" | "tiled")
+  if (opt.attn_mode == 3) return 2;
+  const bool fits = attn_lds_bytes(n_k, d) <= kAttnMaxLds;
+  return fits ? 1 : 2;
 }
 
 template <int D>
@@ -431,6 +596,18 @@ static void launch_attn_mfma(const uint16_t* qkv, const uint16_t* A, const uint1
                               (int)kAttnMaxLds);
   SBP_LAUNCH(SBP_PROF_ATTENTION, s, (attn_bwd_mfma_kernel<D>), dim3(h, B), dim3(256), image, s, qkv, A, dA, lse, n_k, h, scale,
              dqkv);
+}
+
+template <int D>
+static void launch_attn_tiled(const uint16_t* qkv, const uint16_t* A, const uint16_t* dA, const float* lse, int B, int n_k,
+                              int h, float scale, uint16_t* dqkv, hipStream_t s) {
+  const size_t lds = (size_t)2 * kAttnChunk * AttnLds<D>::PITCH + (size_t)2 * kAttnChunk * sizeof(float);
+  if (lds > 64 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bwd_tiled_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+  const int nchunks = (n_k + kAttnChunk - 1) / kAttnChunk;
+  SBP_LAUNCH(SBP_PROF_ATTENTION, s, (attn_bwd_tiled_kernel<D>), dim3(2 * nchunks, h, B), dim3(256), lds, s, qkv, A, dA, lse, n_k, h,
+             scale, nchunks, dqkv);
 }
 
 template <typename T>
@@ -447,11 +624,19 @@ static void launch_attn_plain(const T* qkv, const T* A, const T* dA, const float
 
 int32_t launch_backward_attention(const void* qkv, const void* A, const void* dA, const float* lse, int32_t B, int32_t n_k,
                                   int32_t h, int32_t d, float scale, int32_t dtype, void* dqkv, hipStream_t s) {
-  if (attention_engine(n_k, d, dtype)) {
+  const int engine = attention_engine(n_k, d, dtype);
+  if (engine) {
     const uint16_t* q = (const uint16_t*)qkv; const uint16_t* a = (const uint16_t*)A; const uint16_t* g = (const uint16_t*)dA;
-    if (d == 32) launch_attn_mfma<32>(q, a, g, lse, B, n_k, h, scale, (uint16_t*)dqkv, s);
-    else if (d == 64) launch_attn_mfma<64>(q, a, g, lse, B, n_k, h, scale, (uint16_t*)dqkv, s);
-    else launch_attn_mfma<128>(q, a, g, lse, B, n_k, h, scale, (uint16_t*)dqkv, s);
+    uint16_t* o = (uint16_t*)dqkv;
+    if (engine == 2) {
+      if (d == 32) launch_attn_tiled<32>(q, a, g, lse, B, n_k, h, scale, o, s);
+      else if (d == 64) launch_attn_tiled<64>(q, a, g, lse, B, n_k, h, scale, o, s);
+      else launch_attn_tiled<128>(q, a, g, lse, B, n_k, h, scale, o, s);
+    } else {
+      if (d == 32) launch_attn_mfma<32>(q, a, g, lse, B, n_k, h, scale, o, s);
+      else if (d == 64) launch_attn_mfma<64>(q, a, g, lse, B, n_k, h, scale, o, s);
+      else launch_attn_mfma<128>(q, a, g, lse, B, n_k, h, scale, o, s);
+    }
   } else if (dtype == SBP_BF16) {
     launch_attn_plain<uint16_t>((const uint16_t*)qkv, (const uint16_t*)A, (const uint16_t*)dA, lse, B, n_k, h, d, scale,
                                 (uint16_t*)dqkv, s);

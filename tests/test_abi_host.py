@@ -243,8 +243,8 @@ def test_backward_attention_argument_errors_and_engine():
     assert call(q=None) == -1 and call(l=None) == -1 and call(o=None) == -1
     assert call(a=ctypes.c_void_p(260)) == -2                                # alignment
     assert L.sbp_backward_attention_engine(99, 64, 1) == 1                   # bf16: matrix-core kernel
-    assert L.sbp_backward_attention_engine(256, 64, 1) == 1 and L.sbp_backward_attention_engine(257, 64, 1) == 0
-    assert L.sbp_backward_attention_engine(128, 128, 1) == 1 and L.sbp_backward_attention_engine(129, 128, 1) == 0
+    assert L.sbp_backward_attention_engine(256, 64, 1) == 1 and L.sbp_backward_attention_engine(257, 64, 1) == 2   # beyond one LDS image: tiled
+    assert L.sbp_backward_attention_engine(128, 128, 1) == 1 and L.sbp_backward_attention_engine(129, 128, 1) == 2
     assert L.sbp_backward_attention_engine(99, 64, 0) == 0 and L.sbp_backward_attention_engine(99, 16, 1) == 0
     assert L.sbp_backward_attention_engine(99, 48, 1) == -1
 

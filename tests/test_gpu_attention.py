@@ -48,7 +48,11 @@ CASES = [  # B, n, h, d, n_k
     (2, 70, 2, 64, 32),       # exactly one block
     (1, 70, 1, 64, 33),
     (1, 300, 1, 64, 256),     # the largest size of the matrix-core kernel at d = 64
-    (1, 300, 1, 64, 257),     # one more: plain kernel
+    (1, 300, 1, 64, 257),     # one more: tiled over chunks of 128 tokens (three chunks, the last with one token)
+    (1, 600, 2, 64, 512),     # four full chunks
+    (1, 1100, 1, 64, 1024),
+    (1, 400, 1, 32, 390),
+    (1, 300, 1, 128, 161),
     (2, 120, 3, 32, 100),
     (1, 140, 2, 128, 100),
     (2, 40, 2, 16, 21),       # d = 16: plain kernel
@@ -66,7 +70,8 @@ def test_attention_backward_matches_oracle(B, n, h, d, n_k, dtype):
 def test_engine_choice():
     assert sbp.backward_attention_engine(99, 64, sbp.BF16) == "mfma"
     assert sbp.backward_attention_engine(256, 64, sbp.BF16) == "mfma"
-    assert sbp.backward_attention_engine(257, 64, sbp.BF16) == "plain"
+    assert sbp.backward_attention_engine(257, 64, sbp.BF16) == "mfma_tiled"
+    assert sbp.backward_attention_engine(4096, 128, sbp.BF16) == "mfma_tiled"
     assert sbp.backward_attention_engine(99, 64, sbp.F32) == "plain"
     assert sbp.backward_attention_engine(99, 16, sbp.BF16) == "plain"
 
@@ -128,3 +133,19 @@ def test_empty_and_errors():
     q = torch.zeros((4, 3 * 2 * 24), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(Exception):
         sbp.backward_attention(q, q[:, :48], q[:, :48], torch.zeros((4, 2), device="cuda"), 1, 2, 24, 0.2)   # d = 24
+
+
+@pytest.mark.parametrize("B,n,h,d,n_k", [(2, 197, 3, 64, 99), (1, 197, 2, 64, 197), (2, 50, 2, 64, 1), (1, 70, 1, 64, 33),
+                                         (1, 300, 1, 64, 256), (2, 120, 3, 32, 100), (1, 140, 2, 128, 100)])
+def test_tiled_kernel_at_sizes_the_single_workgroup_kernel_also_serves(B, n, h, d, n_k):
+    # the two matrix-core kernels do the same products on the same rounded probabilities: both within the bar, and
+    # close to each other
+    keep = _keep_sets(B, n, n_k, 11)
+    with sbp.options(attn="tiled"):
+        assert sbp.backward_attention_engine(n_k, d, sbp.BF16) == "mfma_tiled"
+        errs = _run(B, n, h, d, keep, "bf16", 13)
+    assert max(errs) <= TOL_BF16, errs
+    with sbp.options(attn="whole"):
+        assert sbp.backward_attention_engine(n_k, d, sbp.BF16) == "mfma"
+        errs_w = _run(B, n, h, d, keep, "bf16", 13)
+    assert max(errs_w) <= TOL_BF16, errs_w
