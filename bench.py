@@ -53,6 +53,8 @@ def parse():
                     help="per-workgroup time stamps of the last batched backward launch of a step, summarised per kind of unit")
     ap.add_argument("--main-only", action="store_true",
                     help="only the timed region at the chosen ratio (for profiler runs: no r=1 leg, no event pass)")
+    ap.add_argument("--rowwise-only", action="store_true",
+                    help="only the side measurements of the row-wise steps, the down-sampling layer and the samplers")
     ap.add_argument("--attention-only", action="store_true",
                     help="only the attention-backward side measurement (for profiler runs)")
     return ap.parse_args()
@@ -497,6 +499,23 @@ def measure_dwconv(torch, sbp, si, iters=40, warmup=5):
     return out
 
 
+def copy_same_size_us(torch, nbytes, iters=50, warmup=6):
+    """A plain device copy that moves `nbytes` in total (half read, half written), timed like the kernels it is compared
+    with: what the box gives a streaming kernel of this size (small tensors do not reach the rate of a 1 GB copy)."""
+    n = max(int(nbytes) // 2, 256)
+    bufs = [(torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1), torch.empty(n, dtype=torch.uint8, device="cuda")) for _ in range(6)]
+    for i in range(warmup):
+        bufs[i % 6][1].copy_(bufs[i % 6][0])
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        bufs[i % 6][1].copy_(bufs[i % 6][0])
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters * 1e3
+
+
 def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5, model="vit_base", C=768, Hd=3072, row_wise=True):
     """Backward of one ViT MLP branch (LayerNorm -> fc1 -> GELU -> fc2, one keep-set) on compact rows with a
     single final scatter, against the same kernels scattering to full size after every linear layer; plus the
@@ -568,8 +587,10 @@ def measure_mlp_branch(torch, sbp, si, r, iters=20, warmup=5, model="vit_base", 
                                                                       workspace=ws),
              3 * K * C * 2 + 2 * C * 4)):
         ms = timed(fn, 50)
+        cp = copy_same_size_us(torch, nbytes)
         kern[name] = {"us": round(ms * 1e3, 2), "algorithmic_mb": round(nbytes / 1e6, 2),
-                      "gbs": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / 8000.0, 4)}
+                      "gbs": round(nbytes / ms / 1e6, 1), "frac_of_hbm_peak": round(nbytes / ms / 1e6 / 8000.0, 4),
+                      "copy_same_size_us": round(cp, 2), "frac_of_copy_same_size": round(cp / (ms * 1e3), 3)}
     out = {"workload": f"{model} MLP branch backward (LayerNorm, fc1 {C}->{Hd}, GELU, fc2 {Hd}->{C}), K={K} of M={M}",
            "compact_ms": round(ms_c, 4), "scatter_every_layer_ms": round(ms_s, 4), "speedup": round(ms_s / ms_c, 3),
            "tflops_compact": round(flops / ms_c / 1e9, 1)}
@@ -625,8 +646,10 @@ def measure_downsample(torch, sbp, si, r, iters=20, warmup=5):
         m = timed(fn, 50)
         out["kernels"][name] = {"us": round(m * 1e3, 2)}
         if nbytes:
+            cp = copy_same_size_us(torch, nbytes)
             out["kernels"][name].update({"algorithmic_mb": round(nbytes / 1e6, 2), "gbs": round(nbytes / m / 1e6, 1),
-                                         "frac_of_hbm_peak": round(nbytes / m / 1e6 / 8000.0, 4)})
+                                         "frac_of_hbm_peak": round(nbytes / m / 1e6 / 8000.0, 4),
+                                         "copy_same_size_us": round(cp, 2), "frac_of_copy_same_size": round(cp / (m * 1e3), 3)})
     return out
 
 
@@ -767,6 +790,11 @@ def main():
         sbp.set_option(name, value)
     if args.attention_only:
         print(json.dumps({"attention_drop_qkv": measure_attention(torch, sbp, si)}))
+        return
+    if args.rowwise_only:
+        print(json.dumps({"mlp_branch_compact": measure_mlp_branch(torch, sbp, si, args.ratio),
+                          "downsample_layer": measure_downsample(torch, sbp, si, args.ratio),
+                          "sampler_modes": measure_samplers(torch, sbp, si)}))
         return
     wl = si.WORKLOADS[args.workload]
     if args.traffic_probe:

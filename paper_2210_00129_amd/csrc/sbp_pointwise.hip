@@ -61,11 +61,14 @@ template <> struct Gelu<uint16_t> {
 // 8 values per thread and access.  T = uint16_t (bf16) or float.
 template <typename T> struct Vec8;
 template <> struct Vec8<uint16_t> {
-  static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) {
-    const uint4 w = *reinterpret_cast<const uint4*>(p);
+  typedef uint4 Raw;                                   // 8 values as they lie in memory
+  static __device__ __forceinline__ Raw load_raw(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+  static __device__ __forceinline__ Raw zero_raw() { return make_uint4(0, 0, 0, 0); }
+  static __device__ __forceinline__ void unpack(const Raw& w, float (&v)[8]) {
     v[0] = pw_lo(w.x); v[1] = pw_hi(w.x); v[2] = pw_lo(w.y); v[3] = pw_hi(w.y);
     v[4] = pw_lo(w.z); v[5] = pw_hi(w.z); v[6] = pw_lo(w.w); v[7] = pw_hi(w.w);
   }
+  static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) { unpack(load_raw(p), v); }
   static __device__ __forceinline__ void store(uint16_t* p, const float (&v)[8]) {
     uint4 w;
     w.x = pw_pack(v[0], v[1]); w.y = pw_pack(v[2], v[3]); w.z = pw_pack(v[4], v[5]); w.w = pw_pack(v[6], v[7]);
@@ -75,10 +78,15 @@ template <> struct Vec8<uint16_t> {
   static __device__ __forceinline__ void store1(uint16_t* p, float v) { *p = (uint16_t)(pw_pack(v, 0.f) & 0xffffu); }
 };
 template <> struct Vec8<float> {
-  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
-    const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  struct Raw { float4 a, b; };
+  static __device__ __forceinline__ Raw load_raw(const float* p) {
+    return Raw{reinterpret_cast<const float4*>(p)[0], reinterpret_cast<const float4*>(p)[1]};
   }
+  static __device__ __forceinline__ Raw zero_raw() { return Raw{make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)}; }
+  static __device__ __forceinline__ void unpack(const Raw& r, float (&v)[8]) {
+    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+  }
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) { unpack(load_raw(p), v); }
   static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
     reinterpret_cast<float4*>(p)[0] = make_float4(v[0], v[1], v[2], v[3]);
     reinterpret_cast<float4*>(p)[1] = make_float4(v[4], v[5], v[6], v[7]);
@@ -149,10 +157,25 @@ int32_t launch_act_rows(const void* dH, const void* Z, int64_t n, int32_t dtype,
 }
 
 // ---- LayerNorm backward ----------------------------------------------------------------------------
-__device__ __forceinline__ float wave_sum(float v) {   // all lanes get the sum; fixed butterfly order
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+// Sum over the 64 lanes, every lane gets it, fixed order.  Inside a row of 16 lanes the partners come through the
+// data-parallel-primitive lane selects of the vector ALU (neighbour, pair, mirrored half row, mirrored row: four adds,
+// no LDS crossbar - a 64-lane butterfly of cross-lane reads through LDS took six dependent round trips of about 100
+// cycles each, four times per LayerNorm row); the four row sums are then read as scalars and added in row order.
+template <int CTRL>
+__device__ __forceinline__ float dpp_lane(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_lane<0xB1>(v);      // quad_perm [1, 0, 3, 2]
+  v += dpp_lane<0x4E>(v);      // quad_perm [2, 3, 0, 1]
+  v += dpp_lane<0x141>(v);     // row_half_mirror
+  v += dpp_lane<0x140>(v);     // row_mirror
+  const int iv = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48));
+  return ((r0 + r1) + r2) + r3;
 }
 
 // Fast path: C a multiple of 8, C <= 64 * 8 * NV.  A wavefront owns a row: lane l holds the 8-value groups
@@ -199,67 +222,107 @@ __global__ void __launch_bounds__(PW_THREADS) ln_bwd_rows_kernel(const T* __rest
   for (int v = 0; v < NV; ++v) {
     const int grp = lane + 64 * v;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      gam[v][i] = grp < ngroups ? gamma[8 * grp + i] : 0.f;
-      sg[v][i] = 0.f;
-      sb[v][i] = 0.f;
+    for (int i = 0; i < 8; ++i) { gam[v][i] = 0.f; sg[v][i] = 0.f; sb[v][i] = 0.f; }
+    if (grp < ngroups) {
+      const float4 ga = reinterpret_cast<const float4*>(gamma + 8 * grp)[0], gb = reinterpret_cast<const float4*>(gamma + 8 * grp)[1];
+      gam[v][0] = ga.x; gam[v][1] = ga.y; gam[v][2] = ga.z; gam[v][3] = ga.w;
+      gam[v][4] = gb.x; gam[v][5] = gb.y; gam[v][6] = gb.z; gam[v][7] = gb.w;
     }
   }
   const float invC = 1.0f / (float)C;
-  for (int j = r0 + wave; j < r1; j += 4) {
-    float x[NV][8], du[NV][8];
-    float s1 = 0.f;
+  // U rows of the wavefront side by side: their loads go out together and their reduction chains interleave
+  constexpr int U = NV <= 2 ? 2 : 1;
+  // ... and the rows of the next round are requested before this round's arithmetic starts
+  typename Vec8<T>::Raw xr[U][NV], dr[U][NV];
+  auto request = [&](int jb) {
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const int grp = lane + 64 * v;
-      if (grp < ngroups) {
-        Vec8<T>::load(Xk + (long long)j * C + 8 * grp, x[v]);
-        Vec8<T>::load(dU + (long long)j * C + 8 * grp, du[v]);
-      } else {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) { x[v][i] = 0.f; du[v][i] = 0.f; }
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) s1 += x[v][i];
-    }
-    const float mean = wave_sum(s1) * invC;
-    float s2 = 0.f;
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      const bool ok = lane + 64 * v < ngroups;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float d = ok ? x[v][i] - mean : 0.f;
-        x[v][i] = d;
-        s2 += d * d;
-      }
-    }
-    const float rstd = rsqrtf(wave_sum(s2) * invC + eps);
-    float m1 = 0.f, m2 = 0.f;
-#pragma unroll
-    for (int v = 0; v < NV; ++v)
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float xh = x[v][i] * rstd;
-        const float g = du[v][i] * gam[v][i];
-        x[v][i] = xh;
-        m1 += g;
-        m2 += g * xh;
-        sg[v][i] += du[v][i] * xh;
-        sb[v][i] += du[v][i];
-      }
-    m1 = wave_sum(m1) * invC;
-    m2 = wave_sum(m2) * invC;
-    if (dX) {
-      const long long orow = idx_out ? (long long)idx_out[j] : (long long)j;
+    for (int u = 0; u < U; ++u) {
+      const int j = jb + 4 * u;
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
         const int grp = lane + 64 * v;
-        if (grp < ngroups) {
-          float o[8];
+        if (grp < ngroups && j < r1) {
+          xr[u][v] = Vec8<T>::load_raw(Xk + (long long)j * C + 8 * grp);
+          dr[u][v] = Vec8<T>::load_raw(dU + (long long)j * C + 8 * grp);
+        } else {
+          xr[u][v] = Vec8<T>::zero_raw();
+          dr[u][v] = Vec8<T>::zero_raw();
+        }
+      }
+    }
+  };
+  request(r0 + wave);
+  for (int jb = r0 + wave; jb < r1; jb += 4 * U) {
+    float x[U][NV][8], du[U][NV][8];
+    float s1[U];
 #pragma unroll
-          for (int i = 0; i < 8; ++i) o[i] = (du[v][i] * gam[v][i] - m1 - x[v][i] * m2) * rstd;
-          Vec8<T>::store(dX + orow * C + 8 * grp, o);
+    for (int u = 0; u < U; ++u) {
+      s1[u] = 0.f;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        Vec8<T>::unpack(xr[u][v], x[u][v]);
+        Vec8<T>::unpack(dr[u][v], du[u][v]);
+      }
+    }
+    if (jb + 4 * U < r1) request(jb + 4 * U);
+    float mean[U], rstd[U], m1[U], m2[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s1[u] += x[u][v][i];
+      mean[u] = wave_sum(s1[u]) * invC;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float s2 = 0.f;
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        const bool ok = lane + 64 * v < ngroups;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float d = ok ? x[u][v][i] - mean[u] : 0.f;
+          x[u][v][i] = d;
+          s2 += d * d;
+        }
+      }
+      rstd[u] = rsqrtf(wave_sum(s2) * invC + eps);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+      for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float xh = x[u][v][i] * rstd[u];
+          const float g = du[u][v][i] * gam[v][i];
+          x[u][v][i] = xh;
+          a1 += g;
+          a2 += g * xh;
+          sg[v][i] += du[u][v][i] * xh;
+          sb[v][i] += du[u][v][i];
+        }
+      m1[u] = wave_sum(a1) * invC;
+      m2[u] = wave_sum(a2) * invC;
+    }
+    if (dX) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int j = jb + 4 * u;
+        if (j < r1) {
+          const long long orow = idx_out ? (long long)idx_out[j] : (long long)j;
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            const int grp = lane + 64 * v;
+            if (grp < ngroups) {
+              float o[8];
+#pragma unroll
+              for (int i = 0; i < 8; ++i) o[i] = (du[u][v][i] * gam[v][i] - m1[u] - x[u][v][i] * m2[u]) * rstd[u];
+              Vec8<T>::store(dX + orow * C + 8 * grp, o);
+            }
+          }
         }
       }
     }
@@ -337,30 +400,34 @@ __global__ void __launch_bounds__(PW_THREADS) ln_bwd_plain_cols_kernel(const T* 
   partial[((long long)blockIdx.y * 2 + 1) * C + c] = sb;
 }
 
-// dgamma / dbeta = sum over the blocks' partials.  Eight lanes per output: lane q adds the partials
-// q, q + 8, ... in order (four loads in flight), then the eight sums are added in lane order.
-__global__ void __launch_bounds__(PW_THREADS) ln_reduce_kernel(const float* __restrict__ partial, int nblocks, int C,
-                                                                float* __restrict__ dgamma, float* __restrict__ dbeta,
-                                                                int accumulate) {
+// out[o] = sum over the blocks b of partial[b * n_out + o] (o < split goes to out0[o], the rest to out1[o - split]).
+// 32 lanes per output: lane q adds the partials q, q + 32, ... in order (eight loads in flight), then the 32 sums are
+// added in a fixed order (inside 16 lanes by lane selects of the vector ALU, then the two halves).  Few lanes per
+// output left most CUs without work: 768 outputs x 8 lanes were 24 workgroups walking 100 dependent loads each.
+__global__ void __launch_bounds__(PW_THREADS) partials_reduce_kernel(const float* __restrict__ partial, int nblocks, int n_out,
+                                                                      int split, float* __restrict__ out0, float* __restrict__ out1,
+                                                                      int accumulate) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  const int o = t >> 3, q = t & 7;
-  const bool live = o < 2 * C;
-  const int which = live ? o / C : 0, c = live ? o - which * C : 0;
+  const int o = t >> 5, q = t & 31;
+  const bool live = o < n_out;
   float a = 0.f;
   if (live) {
-    for (int b0 = q; b0 < nblocks; b0 += 128) {       // sixteen loads in flight, added in block order
-      float p[16];
+    for (int b0 = q; b0 < nblocks; b0 += 256) {
+      float p[8];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) p[u] = b0 + 8 * u < nblocks ? partial[((long long)(b0 + 8 * u) * 2 + which) * C + c] : 0.f;
+      for (int u = 0; u < 8; ++u) p[u] = b0 + 32 * u < nblocks ? partial[(long long)(b0 + 32 * u) * n_out + o] : 0.f;
 #pragma unroll
-      for (int u = 0; u < 16; ++u) a += p[u];
+      for (int u = 0; u < 8; ++u) a += p[u];
     }
   }
-  float tot = 0.f;
-#pragma unroll
-  for (int l = 0; l < 8; ++l) tot += __shfl(a, (threadIdx.x & 56) + l, 64);     // every lane takes part
-  float* out = which == 0 ? dgamma : dbeta;
-  if (live && q == 0 && out) out[c] = (accumulate ? out[c] : 0.f) + tot;
+  a += dpp_lane<0xB1>(a);
+  a += dpp_lane<0x4E>(a);
+  a += dpp_lane<0x141>(a);
+  a += dpp_lane<0x140>(a);
+  a += __shfl_xor(a, 16, 64);
+  float* out = o < split ? out0 : out1;
+  const int c = o < split ? o : o - split;
+  if (live && q == 0 && out) out[c] = (accumulate ? out[c] : 0.f) + a;
 }
 
 __global__ void __launch_bounds__(PW_THREADS) ln_fill_zero_kernel(float* __restrict__ p, int n) {
@@ -403,7 +470,7 @@ template <typename T>
 static bool launch_ln_t(const LnPlan& p, const T* dU, const T* Xk, const float* gamma, float eps, const int32_t* idx_out,
                         int K, int C, T* dX, float* partial, float* stats, const int32_t* inv, int M, hipStream_t s) {
   const int rpb = (int)ceil_div(K, p.nblocks);
-  const bool aligned = (uintptr_t)dU % 16 == 0 && (uintptr_t)Xk % 16 == 0 && (uintptr_t)dX % 16 == 0;
+  const bool aligned = (uintptr_t)dU % 16 == 0 && (uintptr_t)Xk % 16 == 0 && (uintptr_t)dX % 16 == 0 && (uintptr_t)gamma % 16 == 0;
   if (p.fast && aligned) {
     const int nv = (int)ceil_div(C / 8, 64);
     switch (nv) {
@@ -457,101 +524,103 @@ int32_t launch_backward_layernorm(const LnPlan& p, const void* dU, const void* X
       zero_filled = launch_ln_t<uint16_t>(p, (const uint16_t*)dU, (const uint16_t*)Xk, gamma, eps, idx_out, (int)K, C,
                                           (uint16_t*)dX, want_params ? partial : nullptr, stats, inv, (int)M, s);
     if (want_params)
-      SBP_LAUNCH(SBP_PROF_REDUCE, s, ln_reduce_kernel, dim3((unsigned)ceil_div(16 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
-                 partial, p.nblocks, C, dgamma, dbeta, accumulate);
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, partials_reduce_kernel, dim3((unsigned)ceil_div(32 * 2 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+                 partial, p.nblocks, 2 * C, C, dgamma, dbeta, accumulate);
   }
   if (dX && !dx_compact && !zero_filled) launch_zero_dropped_rows(idx, inv, K, M, (int64_t)C * eb, dX, s);
   return check_launch("backward_layernorm");
 }
 
 // ---- per-channel layer scale U = gamma * Y on the kept rows ---------------------------------------------
-// dY_k = dU_k * gamma, dgamma = sum_j dU_k[j] * Y_k[j].  A thread owns VEC (8 or 1) adjacent channels and walks
-// the rows of its block's slab, four rows in flight; the block writes one partial of dgamma, a second launch adds
-// the partials in block order (deterministic).
-static constexpr int kLsMaxBlocks = 512;
+// dY_k = dU_k * gamma, dgamma = sum_j dU_k[j] * Y_k[j].  A thread owns VEC (8 or 1) adjacent channels; the G threads
+// that cover a row form a row lane, a block has RL row lanes (G * RL <= 256 threads) that walk the rows of the block's
+// slab in turn, four rows in flight each; the lanes' sums are added through LDS in lane order, the block writes one
+// partial of dgamma, a second launch adds the partials in block order (deterministic).
+static constexpr int kLsMaxBlocks = 1024;
 
 template <typename T, int VEC>
 __global__ void __launch_bounds__(PW_THREADS) layerscale_bwd_kernel(const T* __restrict__ dU, const T* __restrict__ Y,
                                                                     const float* __restrict__ gamma, int K, int C,
-                                                                    int rows_per_block, T* __restrict__ dY,
+                                                                    int rows_per_block, int G, int RL, T* __restrict__ dY,
                                                                     float* __restrict__ partial) {
-  const int g = blockIdx.y * blockDim.x + threadIdx.x;           // channel group
-  const int c0 = g * VEC;
-  if (c0 >= C) return;
+  extern __shared__ float ls_red[];                              // [RL][G * VEC] (RL > 1 only)
+  const int rr = threadIdx.x / G, gl = threadIdx.x - rr * G;
+  const int c0 = (blockIdx.y * G + gl) * VEC;                   // first channel of this thread
+  const bool live = c0 < C;
   const int r0 = blockIdx.x * rows_per_block, r1 = min(K, r0 + rows_per_block);
   float gam[VEC], acc[VEC];
 #pragma unroll
-  for (int e = 0; e < VEC; ++e) { gam[e] = gamma[c0 + e]; acc[e] = 0.f; }
-  for (int r = r0; r < r1; r += 4) {
-    float u[4][VEC], y[4][VEC];
+  for (int e = 0; e < VEC; ++e) { gam[e] = live ? gamma[c0 + e] : 0.f; acc[e] = 0.f; }
+  if (live)
+    for (int r = r0 + 4 * rr; r < r1; r += 4 * RL) {
+      float u[4][VEC], y[4][VEC];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const long long o = (long long)min(r + q, r1 - 1) * C + c0;
-      if (VEC == 8) { Vec8<T>::load(dU + o, reinterpret_cast<float(&)[8]>(u[q])); Vec8<T>::load(Y + o, reinterpret_cast<float(&)[8]>(y[q])); }
-      else { u[q][0] = Vec8<T>::load1(dU + o); y[q][0] = Vec8<T>::load1(Y + o); }
+      for (int q = 0; q < 4; ++q) {
+        const long long o = (long long)min(r + q, r1 - 1) * C + c0;
+        if (VEC == 8) { Vec8<T>::load(dU + o, reinterpret_cast<float(&)[8]>(u[q])); Vec8<T>::load(Y + o, reinterpret_cast<float(&)[8]>(y[q])); }
+        else { u[q][0] = Vec8<T>::load1(dU + o); y[q][0] = Vec8<T>::load1(Y + o); }
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (r + q >= r1) break;
+        float o8[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) { acc[e] = fmaf(u[q][e], y[q][e], acc[e]); o8[e] = u[q][e] * gam[e]; }
+        if (dY) {
+          const long long o = (long long)(r + q) * C + c0;
+          if (VEC == 8) Vec8<T>::store(dY + o, reinterpret_cast<float(&)[8]>(o8));
+          else Vec8<T>::store1(dY + o, o8[0]);
+        }
+      }
     }
+  if (!partial) return;
+  if (RL > 1) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (r + q >= r1) break;
-      float o8[VEC];
+    for (int e = 0; e < VEC; ++e) ls_red[(rr * G + gl) * VEC + e] = acc[e];
+    __syncthreads();
+    if (rr == 0) {
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) { acc[e] = fmaf(u[q][e], y[q][e], acc[e]); o8[e] = u[q][e] * gam[e]; }
-      if (dY) {
-        const long long o = (long long)(r + q) * C + c0;
-        if (VEC == 8) Vec8<T>::store(dY + o, reinterpret_cast<float(&)[8]>(o8));
-        else Vec8<T>::store1(dY + o, o8[0]);
+      for (int e = 0; e < VEC; ++e) {
+        float a = acc[e];
+        for (int l = 1; l < RL; ++l) a += ls_red[(l * G + gl) * VEC + e];
+        acc[e] = a;
       }
     }
   }
-  if (partial) {
+  if (rr == 0 && live) {
 #pragma unroll
     for (int e = 0; e < VEC; ++e) partial[(long long)blockIdx.x * C + c0 + e] = acc[e];
   }
 }
 
-__global__ void __launch_bounds__(PW_THREADS) cols_reduce_kernel(const float* __restrict__ partial, int nblocks, int C,
-                                                                 float* __restrict__ out, int accumulate) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  const int c = t >> 3, q = t & 7;                                // eight lanes per channel
-  float a = 0.f;
-  if (c < C)
-    for (int b0 = q; b0 < nblocks; b0 += 128) {       // sixteen loads in flight, added in block order
-      float p[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) p[u] = b0 + 8 * u < nblocks ? partial[(long long)(b0 + 8 * u) * C + c] : 0.f;
-#pragma unroll
-      for (int u = 0; u < 16; ++u) a += p[u];
-    }
-  a += __shfl_xor(a, 1); a += __shfl_xor(a, 2); a += __shfl_xor(a, 4);
-  if (c < C && q == 0) out[c] = accumulate ? out[c] + a : a;
-}
-
-int ls_blocks(int64_t K) { return (int)std::max<int64_t>(1, std::min<int64_t>(kLsMaxBlocks, ceil_div(K, 16))); }
+int ls_blocks(int64_t K) { return (int)std::max<int64_t>(1, std::min<int64_t>(kLsMaxBlocks, ceil_div(K, 8))); }
 
 int32_t launch_backward_layerscale(const void* dU, const void* Y, const float* gamma, int64_t K, int32_t C, int32_t dtype,
                                    float* dgamma, void* dY, float* partial, uint32_t flags, hipStream_t s) {
   const int accumulate = (flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
   if (K == 0) {
     if (dgamma)   // no partials: writes zeros (or leaves dgamma as it is when accumulating)
-      SBP_LAUNCH(SBP_PROF_REDUCE, s, cols_reduce_kernel, dim3((unsigned)ceil_div(8 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
-                 partial, 0, C, dgamma, accumulate);
+      SBP_LAUNCH(SBP_PROF_REDUCE, s, partials_reduce_kernel, dim3((unsigned)ceil_div(32 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+                 partial, 0, C, C, dgamma, (float*)nullptr, accumulate);
     return check_launch("backward_layerscale (K = 0)");
   }
-  const int nblocks = ls_blocks(K), rpb = (int)ceil_div(K, nblocks);
   const int eb = dtype == SBP_F32 ? 4 : 2;
   const bool vec = C % 8 == 0 && (uintptr_t)dU % 16 == 0 && (uintptr_t)Y % 16 == 0 && (uintptr_t)dY % 16 == 0 && ((size_t)C * eb) % 16 == 0;
   const int groups = vec ? C / 8 : C;
-  const int ct = (int)std::min<int64_t>(PW_THREADS, ceil_div(groups, 64) * 64);
-  const dim3 grid((unsigned)nblocks, (unsigned)ceil_div(groups, ct));
+  const int G = std::min(groups, PW_THREADS);                    // threads along a row
+  const int RL = std::max(1, PW_THREADS / G);                    // row lanes of a block
+  const int nblocks = ls_blocks(K), rpb = (int)ceil_div(K, nblocks);
+  const dim3 grid((unsigned)nblocks, (unsigned)ceil_div(groups, G));
+  const size_t lds = RL > 1 ? (size_t)RL * G * (vec ? 8 : 1) * sizeof(float) : 0;
   float* part = dgamma ? partial : nullptr;
-#define SBP_LS(T, V) SBP_LAUNCH(SBP_PROF_OTHER, s, (layerscale_bwd_kernel<T, V>), grid, dim3(ct), 0, s, (const T*)dU, (const T*)Y, gamma, \
-                                (int)K, C, rpb, (T*)dY, part)
+#define SBP_LS(T, V) SBP_LAUNCH(SBP_PROF_OTHER, s, (layerscale_bwd_kernel<T, V>), grid, dim3(G * RL), lds, s, (const T*)dU, (const T*)Y, gamma, \
+                                (int)K, C, rpb, G, RL, (T*)dY, part)
   if (dtype == SBP_F32) { if (vec) SBP_LS(float, 8); else SBP_LS(float, 1); }
   else { if (vec) SBP_LS(uint16_t, 8); else SBP_LS(uint16_t, 1); }
 #undef SBP_LS
   if (dgamma)
-    SBP_LAUNCH(SBP_PROF_REDUCE, s, cols_reduce_kernel, dim3((unsigned)ceil_div(8 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
-               partial, nblocks, C, dgamma, accumulate);
+    SBP_LAUNCH(SBP_PROF_REDUCE, s, partials_reduce_kernel, dim3((unsigned)ceil_div(32 * (int64_t)C, PW_THREADS)), dim3(PW_THREADS), 0, s,
+               partial, nblocks, C, C, dgamma, (float*)nullptr, accumulate);
   return check_launch("backward_layerscale");
 }
 
