@@ -14,6 +14,7 @@
 #include <cstdlib>
 
 #include <algorithm>
+#include <cstddef>
 #include <functional>
 #include <mutex>
 #include <queue>
@@ -100,9 +101,7 @@ __device__ __forceinline__ void zero_rows_block(const LinArgs& a, int blk) {
 
 // BMX, NSX: rows and ring depth of the dX tiles (the dW units use BM and NSTAGE)
 template <int BM, int BN, int NW, int KB, int NSTAGE, int BMX, int NSX>
-__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_kernel(const LinArgs a) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  int wg = blockIdx.x;
+__device__ __forceinline__ void linear_bwd_body(char* smem, const LinArgs& a, int wg) {
   int kind = 0;
 #pragma unroll
   for (int q = 0; q < 3; ++q) {
@@ -145,6 +144,38 @@ __global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_
   const int j0 = split * a.rows_per_split, j1 = min(a.K, j0 + a.rows_per_split);
   dw_tile<BM, BN, NW, KB, NSTAGE>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, a.part + (long long)split * a.Cout * a.Cin,
                       tile_m * BM, tile_n * BN);
+}
+
+template <int BM, int BN, int NW, int KB, int NSTAGE, int BMX, int NSX>
+__global__ void __launch_bounds__(64 * NW, (BM + BN) <= 256 ? 2 : 1) linear_bwd_kernel(const LinArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  linear_bwd_body<BM, BN, NW, KB, NSTAGE, BMX, NSX>(smem, a, blockIdx.x);
+}
+
+// Several small layers in one launch of the general engine (128 x 128 tiles, stages of 64): the grids of the layers
+// one behind the other, every layer with its own order of segments.  A ViT-Tiny-class layer is a few hundred
+// workgroups that all find a slot at once; two such layers side by side fill the chip better than one after the other
+// and save a launch.
+struct SmallMultiArgs { int n; int start[SBP_MAX_BATCH_LAYERS + 1]; LinArgs lay[SBP_MAX_BATCH_LAYERS]; };
+static_assert(sizeof(SmallMultiArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
+__global__ void __launch_bounds__(256, 2) linear_bwd_multi_kernel(const SmallMultiArgs m) {
+#if defined(__HIP_DEVICE_COMPILE__)      // (address-space casts below: the host pass only needs the symbol)
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  int li = 0, first = 0;
+#pragma unroll
+  for (int i = 1; i < SBP_MAX_BATCH_LAYERS; ++i)
+    if (i < m.n && (int)blockIdx.x >= m.start[i]) { li = i; first = m.start[i]; }
+  // the layer's arguments through the kernel-argument segment itself (constant address space, uniform index: scalar
+  // loads into scalar registers); indexing the by-value struct made the compiler copy all of it to scratch memory
+  typedef const __attribute__((address_space(4))) LinArgs* ConstLinArgsPtr;
+  const __attribute__((address_space(4))) char* kargs =
+      (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
+  const LinArgs a = *reinterpret_cast<ConstLinArgsPtr>(kargs + offsetof(SmallMultiArgs, lay) + (size_t)li * sizeof(LinArgs));
+  const int wg = (int)blockIdx.x - first;
+  if (a.dx_bm == 64) linear_bwd_body<128, 128, 4, 64, 2, 64, 3>(smem, a, wg);
+  else linear_bwd_body<128, 128, 4, 64, 2, 128, 2>(smem, a, wg);
+#endif
 }
 
 // Workgroups go to the 8 XCDs round robin by their index in the grid, and every XCD queues its own: a
@@ -819,13 +850,12 @@ static void allow_big_lds(KernelT kernel, size_t lds) {
   }
 }
 
+// fills in the segment sizes and their order; returns the number of workgroups, *lds_out the LDS bytes a workgroup needs
 template <int BM, int BN, int NW, int KB, int NSTAGE, int BMX = BM, int NSX = NSTAGE>
-static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero,
-                              hipStream_t s) {
+static unsigned prepare_linear_bwd(const LinearPlan& p, LinArgs& a, bool want_dx, bool want_dw, bool want_zero, size_t* lds_out) {
   // stage ring + the row-id table of a dW split (rows_per_split rounded up to the stage length), or the dX tiles' ring
-  const size_t lds = std::max((size_t)NSTAGE * (BM + BN) * KB * 2 + (size_t)(p.rows_per_split + KB) * sizeof(int),
-                              (size_t)NSX * (BMX + BN) * KB * 2);
-  allow_big_lds(linear_bwd_kernel<BM, BN, NW, KB, NSTAGE, BMX, NSX>, lds);
+  *lds_out = std::max((size_t)NSTAGE * (BM + BN) * KB * 2 + (size_t)(p.rows_per_split + KB) * sizeof(int),
+                      (size_t)NSX * (BMX + BN) * KB * 2);
   const long long tiles_n = ceil_div(a.Cin, BN);
   a.n_zero = want_zero ? (int)std::min<long long>(128, std::max<long long>(8, ceil_div((long long)a.M, 64 * NW))) : 0;
   const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
@@ -833,7 +863,7 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   a.n_dx = want_dx ? (int)(8 * ceil_div(ceil_div(a.K, BMX) * tiles_n, 8)) : 0;
   a.n_dw = want_dw ? (int)(8 * ceil_div(ceil_div(a.Cout, BM) * tiles_n * p.splits, 8)) : 0;
   const unsigned grid = (unsigned)(a.n_helper + a.n_dx + a.n_dw);
-  if (grid == 0) return;
+  if (grid == 0) return 0;
   // Longest kind first.  Lengths in nanoseconds, read from the device clock on the detection and ViT-Tiny shapes: a
   // tile costs about 3 us plus 1 us per stage of 64 (two stages in flight do not hide the memory latency), a
   // streaming block 1.8 us plus its bytes at what one CU gets while the others stream too.
@@ -845,6 +875,16 @@ static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool
   const Options opt = options();
   if (opt.order_set)                                // the order by hand (a permutation, checked when it was set)
     for (int q = 0; q < 3; ++q) a.seg_order[q] = opt.order[q];
+  return grid;
+}
+
+template <int BM, int BN, int NW, int KB, int NSTAGE, int BMX = BM, int NSX = NSTAGE>
+static void launch_linear_bwd(const LinearPlan& p, LinArgs a, bool want_dx, bool want_dw, bool want_zero,
+                              hipStream_t s) {
+  size_t lds = 0;
+  const unsigned grid = prepare_linear_bwd<BM, BN, NW, KB, NSTAGE, BMX, NSX>(p, a, want_dx, want_dw, want_zero, &lds);
+  if (grid == 0) return;
+  allow_big_lds(linear_bwd_kernel<BM, BN, NW, KB, NSTAGE, BMX, NSX>, lds);
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, (linear_bwd_kernel<BM, BN, NW, KB, NSTAGE, BMX, NSX>), dim3(grid), dim3(64 * NW), lds, s, a);
 }
 
@@ -894,6 +934,9 @@ static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool
   if (grid == 0) return;
   SBP_LAUNCH(SBP_PROF_DW_GEMM, s, linear_big_kernel, dim3(grid), dim3(256), lds, s, a);
 }
+
+// lanes per output of the split reductions: small weight matrices cut into many splits get several
+static int reduce_lanes(long long total, int deepest) { return total <= 20000 && deepest >= 16 ? 8 : (total <= 40000 && deepest >= 8 ? 4 : 1); }
 
 int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_t* idx, const int32_t* inv_in,
                                const void* Xk, const void* W, int64_t M, int64_t K, int32_t Cin, int32_t Cout,
@@ -983,7 +1026,7 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
       const long long total = (dW ? nW / 4 : 0) + (db ? Cout : 0);
       const int nsplit_b = use_mfma ? p.db_slices : p.splits;
       const int deepest = std::max(dW ? p.splits : 0, db ? nsplit_b : 0);
-      const int G = total <= 20000 && deepest >= 16 ? 8 : (total <= 40000 && deepest >= 8 ? 4 : 1);
+      const int G = reduce_lanes(total, deepest);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total * G, NTHREADS), 4096);
       auto kernel = dw_bf16 ? (G == 8 ? reduce_splits_kernel<8, true> : (G == 4 ? reduce_splits_kernel<4, true> : reduce_splits_kernel<1, true>))
                             : (G == 8 ? reduce_splits_kernel<8, false> : (G == 4 ? reduce_splits_kernel<4, false> : reduce_splits_kernel<1, false>));
@@ -1013,55 +1056,72 @@ struct RedLayer {
   const float* part; const float* dbp; void* dW; float* db;
   long long nW;
   int nsplit_w, nsplit_b, Cout, accumulate, bf16out, blk_start, nblk;
+  int G;       // lanes per output (1, 4 or 8): lane g adds a contiguous run of the splits, the G sums are added in lane order
 };
 struct RedMultiArgs { int n; RedLayer lay[kMaxBatch]; };
 
 // the split reduction of every layer of a batch: blocks [blk_start, blk_start + nblk) serve layer i; per output the
-// partial sums are added in split order (fixed order, as in reduce_splits_kernel with one lane per output)
+// partial sums are added in a fixed order (as in reduce_splits_kernel)
 __global__ void __launch_bounds__(NTHREADS) reduce_multi_kernel(const RedMultiArgs a) {
   int li = 0;
   for (int i = 1; i < a.n; ++i)
     if ((int)blockIdx.x >= a.lay[i].blk_start) li = i;
   const RedLayer& r = a.lay[li];
+  const int G = r.G, g = threadIdx.x & (G - 1), lane = threadIdx.x & 63;
   const long long nW4 = r.dW ? r.nW / 4 : 0;
   const long long total = nW4 + (r.db ? r.Cout : 0);
-  const long long first = ((long long)blockIdx.x - r.blk_start) * NTHREADS + threadIdx.x;
-  for (long long e = first; e < total; e += (long long)r.nblk * NTHREADS) {
+  const long long first = (((long long)blockIdx.x - r.blk_start) * NTHREADS + threadIdx.x) / G;
+  for (long long e = first; e < total; e += (long long)r.nblk * NTHREADS / G) {
     if (e < nW4) {
+      const int chunk = (r.nsplit_w + G - 1) / G, s_begin = g * chunk, s_end = min(r.nsplit_w, s_begin + chunk);
       float4 acc = make_float4(0, 0, 0, 0);
-      for (int s0 = 0; s0 < r.nsplit_w; s0 += 4) {
+      for (int s0 = s_begin; s0 < s_end; s0 += 4) {
         float4 p[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u)
-          p[u] = s0 + u < r.nsplit_w ? reinterpret_cast<const float4*>(r.part + (long long)(s0 + u) * r.nW)[e]
-                                     : make_float4(0, 0, 0, 0);
+          p[u] = s0 + u < s_end ? reinterpret_cast<const float4*>(r.part + (long long)(s0 + u) * r.nW)[e]
+                                : make_float4(0, 0, 0, 0);
 #pragma unroll
         for (int u = 0; u < 4; ++u) { acc.x += p[u].x; acc.y += p[u].y; acc.z += p[u].z; acc.w += p[u].w; }
       }
-      if (r.bf16out) {
-        if (r.accumulate) {
-          const float4 old = load_dw4<true>(r.dW, e);
-          acc.x = old.x + acc.x; acc.y = old.y + acc.y; acc.z = old.z + acc.z; acc.w = old.w + acc.w;
+      if (G > 1) {
+        const float4 own = acc;
+        for (int k = 1; k < G; ++k) {
+          const int src = (lane & ~(G - 1)) + k;
+          acc.x += __shfl(own.x, src); acc.y += __shfl(own.y, src); acc.z += __shfl(own.z, src); acc.w += __shfl(own.w, src);
         }
-        store_dw4<true>(r.dW, e, acc);
-      } else {
-        if (r.accumulate) {
-          const float4 old = load_dw4<false>(r.dW, e);
-          acc.x = old.x + acc.x; acc.y = old.y + acc.y; acc.z = old.z + acc.z; acc.w = old.w + acc.w;
+      }
+      if (g == 0) {
+        if (r.bf16out) {
+          if (r.accumulate) {
+            const float4 old = load_dw4<true>(r.dW, e);
+            acc.x = old.x + acc.x; acc.y = old.y + acc.y; acc.z = old.z + acc.z; acc.w = old.w + acc.w;
+          }
+          store_dw4<true>(r.dW, e, acc);
+        } else {
+          if (r.accumulate) {
+            const float4 old = load_dw4<false>(r.dW, e);
+            acc.x = old.x + acc.x; acc.y = old.y + acc.y; acc.z = old.z + acc.z; acc.w = old.w + acc.w;
+          }
+          store_dw4<false>(r.dW, e, acc);
         }
-        store_dw4<false>(r.dW, e, acc);
       }
     } else {
       const long long o = e - nW4;
+      const int chunk = (r.nsplit_b + G - 1) / G, s_begin = g * chunk, s_end = min(r.nsplit_b, s_begin + chunk);
       float acc = 0.f;
-      for (int s0 = 0; s0 < r.nsplit_b; s0 += 8) {
+      for (int s0 = s_begin; s0 < s_end; s0 += 8) {
         float p[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) p[u] = s0 + u < r.nsplit_b ? r.dbp[(long long)(s0 + u) * r.Cout + o] : 0.f;
+        for (int u = 0; u < 8; ++u) p[u] = s0 + u < s_end ? r.dbp[(long long)(s0 + u) * r.Cout + o] : 0.f;
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += p[u];
       }
-      r.db[o] = r.accumulate ? r.db[o] + acc : acc;
+      if (G > 1) {
+        const float own = acc;
+        for (int k = 1; k < G; ++k) acc += __shfl(own, (lane & ~(G - 1)) + k);
+      }
+      if (g == 0) r.db[o] = r.accumulate ? r.db[o] + acc : acc;
     }
   }
 }
@@ -1333,9 +1393,103 @@ BatchPlan plan_linear_batch(const sbp_linear_layer* L, int32_t n, int32_t dtype)
   return p;
 }
 
+// A batch that does not take the large-tile grid but whose layers all take the general engine in its default shape
+// (bf16, 128 x 128 tiles, stages of 64): one launch of linear_bwd_multi_kernel + one reduction launch.  Every layer uses
+// its own piece of the workspace exactly as a single call would.  Returns false if the batch is not of that kind.
+static bool launch_small_batch(const BatchPlan& p, const sbp_linear_layer* L, int32_t dtype, char* wsb, hipStream_t s, int32_t* status) {
+  if (p.n < 2 || dtype != SBP_BF16 || options().tile_mode != 0) return false;
+  LinearPlan lp[kMaxBatch];
+  for (int i = 0; i < p.n; ++i) {
+    const sbp_linear_layer& l = L[i];
+    lp[i] = plan_linear(l.M, l.K, l.Cin, l.Cout, dtype, l.flags);
+    if (!lp[i].mfma || lp[i].big || lp[i].bm_w != 128 || lp[i].nw_w != 4 || lp[i].kb != 64 || l.K < 1) return false;
+    if (l.flags & SBP_FLAG_XK_KMAJOR) return false;
+    if (!l.dW && !l.db && !l.dX) return false;
+    if (((uintptr_t)l.dY | (uintptr_t)l.X_k | (uintptr_t)l.W | (uintptr_t)l.dX) & 15) return false;
+    if (l.dW && ((uintptr_t)l.dW & 15)) return false;
+  }
+  // the layers fill the chip together: each needs only its share of the dW splits a launch of its own would take (fewer
+  // partial sums to write and to add); the workspace was sized for the larger number
+  for (int i = 0; i < p.n; ++i) {
+    const int64_t K = L[i].K;
+    int splits = (int)std::max<int64_t>(ceil_div(lp[i].splits, p.n), ceil_div(K, kMaxRowsPerSplit));
+    const int64_t rps = ceil_div(ceil_div(K, splits), 64) * 64;
+    splits = (int)ceil_div(K, rps);
+    if (splits < lp[i].splits) {
+      lp[i].splits = splits;
+      lp[i].rows_per_split = (int)rps;
+    }
+  }
+  SmallMultiArgs m{};
+  RedMultiArgs r{};
+  m.n = r.n = p.n;
+  size_t lds = 0;
+  int blk = 0;
+  bool any_reduce = false;
+  for (int i = 0; i < p.n; ++i) {
+    const sbp_linear_layer& l = L[i];
+    char* w = wsb + p.lay[i].off;
+    float* part = reinterpret_cast<float*>(w + lp[i].off_partial);
+    float* dbp = part + (size_t)lp[i].splits * l.Cout * l.Cin;
+    const bool dy_compact = l.flags & SBP_FLAG_DY_COMPACT, dx_compact = l.flags & SBP_FLAG_DX_COMPACT;
+    const bool scatter = l.dX && !dx_compact;
+    const int32_t* inv = l.inv;
+    if (scatter && !inv) {
+      int32_t* inv_ws = reinterpret_cast<int32_t*>(w + lp[i].off_inv);
+      launch_build_inverse(l.idx, l.K, inv_ws, s);
+      inv = inv_ws;
+    }
+    LinArgs& a = m.lay[i];
+    a.dY = static_cast<const uint16_t*>(l.dY);
+    a.idx_in = dy_compact ? nullptr : l.idx;
+    a.idx_out = dx_compact ? nullptr : l.idx;
+    a.idx = l.idx; a.inv = inv;
+    a.Xk = static_cast<const uint16_t*>(l.X_k); a.W = static_cast<const uint16_t*>(l.W);
+    a.dX = static_cast<uint16_t*>(l.dX); a.part = part; a.dbp = l.db ? dbp : nullptr;
+    a.K = (int)l.K; a.M = (int)l.M; a.Cin = l.Cin; a.Cout = l.Cout;
+    a.rows_per_split = lp[i].rows_per_split; a.db_slice_rows = lp[i].db_slice_rows;
+    a.dx_bm = lp[i].dx_bm;
+    size_t need = 0;
+    const unsigned grid = lp[i].dx_bm == 64
+        ? prepare_linear_bwd<128, 128, 4, 64, 2, 64, 3>(lp[i], a, l.dX != nullptr, l.dW != nullptr, scatter, &need)
+        : prepare_linear_bwd<128, 128, 4, 64, 2>(lp[i], a, l.dX != nullptr, l.dW != nullptr, scatter, &need);
+    lds = std::max(lds, need);
+    m.start[i] = blk;
+    blk += (int)grid;
+    RedLayer& rl = r.lay[i];
+    rl.part = part; rl.dbp = dbp; rl.dW = l.dW; rl.db = l.db;
+    rl.nW = (long long)l.Cin * l.Cout;
+    rl.nsplit_w = lp[i].splits; rl.nsplit_b = lp[i].db_slices; rl.Cout = l.Cout;
+    rl.accumulate = (l.flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
+    rl.bf16out = (l.flags & SBP_FLAG_DW_OUT_BF16) ? 1 : 0;
+    rl.G = reduce_lanes((rl.dW ? rl.nW / 4 : 0) + (rl.db ? rl.Cout : 0), std::max(rl.dW ? rl.nsplit_w : 0, rl.db ? rl.nsplit_b : 0));
+    any_reduce = any_reduce || rl.dW || rl.db;
+  }
+  m.start[p.n] = blk;
+  if (blk > 0) {
+    allow_big_lds(linear_bwd_multi_kernel, lds);
+    SBP_LAUNCH(SBP_PROF_DW_GEMM, s, linear_bwd_multi_kernel, dim3((unsigned)blk), dim3(256), lds, s, m);
+  }
+  if (any_reduce) {
+    int rb = 0;
+    for (int i = 0; i < p.n; ++i) {
+      RedLayer& rl = r.lay[i];
+      const long long total = (rl.dW ? rl.nW / 4 : 0) + (rl.db ? rl.Cout : 0);
+      rl.blk_start = rb;
+      rl.nblk = (int)std::min<long long>(ceil_div(total * rl.G, NTHREADS), 2048);
+      rb += rl.nblk;
+    }
+    if (rb > 0) SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_multi_kernel, dim3((unsigned)rb), dim3(NTHREADS), 0, s, r);
+  }
+  *status = check_launch("backward_linear_batch (general engine)");
+  return true;
+}
+
 int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer* L, int32_t dtype, void* ws, hipStream_t s) {
   char* wsb = static_cast<char*>(ws);
   if (!p.fused) {
+    int32_t st = SBP_OK;
+    if (launch_small_batch(p, L, dtype, wsb, s, &st)) return st;
     for (int i = 0; i < p.n; ++i) {
       const sbp_linear_layer& l = L[i];
       if (!l.dW && !l.db && !l.dX) continue;
@@ -1388,6 +1542,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     rl.nsplit_w = b.splits; rl.nsplit_b = la.db_in_dw ? b.splits : b.db_slices; rl.Cout = l.Cout;
     rl.accumulate = (l.flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
     rl.bf16out = (l.flags & SBP_FLAG_DW_OUT_BF16) ? 1 : 0;
+    rl.G = 1;
     any_reduce = any_reduce || rl.dW || rl.db;
   }
   if (!any) return SBP_OK;

@@ -196,3 +196,34 @@ def test_sample_indices_batch_is_bit_exact():
         assert np.array_equal(got.cpu().numpy(), r)
         if inv is not None:
             assert np.array_equal(inv.cpu().numpy(), oracle.inverse_map(r, d.B * (d.P + d.H * d.W)))
+
+
+@pytest.mark.parametrize("with_inv", [True, False])
+def test_batch_of_small_layers_shares_one_launch_of_the_general_engine(with_inv):
+    # layers narrower than the 256-wide tiles (ViT-Tiny class): one grid of 128-wide tiles for all of them; every flag,
+    # ragged channel counts, dX tiles of 64 and of 128 rows side by side, and the same results as single calls
+    CF, CY = sbp.FLAG_DX_COMPACT, sbp.FLAG_DY_COMPACT
+    cases = [_layer(16, 1, 14, 14, 192, 768, 2, 111), _layer(16, 1, 14, 14, 768, 192, 2, 112, flags=CF),
+             _layer(5, 0, 10, 12, 72, 224, 3, 113, flags=CY), _layer(64, 1, 14, 14, 200, 136, 4, 114, flags=CF | CY)]
+    outs = _run(cases, with_inv, forced=False)
+    assert all(o[0] is not None for o in outs)
+    ints = [_layer(16, 1, 14, 14, 192, 768, 2, 121, ints=True), _layer(16, 1, 14, 14, 768, 192, 1, 122, ints=True, flags=CF)]
+    dev = [_to_device(c, with_inv) for c in ints]
+    got = sbp.backward_linear_batch(dev)
+    for d, o in zip(dev, got):
+        ref = sbp.backward_linear(d["dY"], d["idx"], d["X_k"], d["W"], M=d["M"], inv=d.get("inv"), flags=d["flags"])
+        for a, b in zip(o, ref):
+            assert np.array_equal(bits(a), bits(b))
+
+
+def test_batch_of_small_layers_accumulates_and_rounds_the_weight_gradient():
+    c0 = _layer(16, 1, 14, 14, 192, 768, 2, 131, flags=sbp.FLAG_ACCUMULATE_DW)
+    c1 = _layer(16, 1, 14, 14, 768, 192, 2, 132, flags=sbp.FLAG_DW_OUT_BF16)
+    d0, d1 = _to_device(c0, True), _to_device(c1, True)
+    d0["dW"] = torch.full((768, 192), 2.0, dtype=torch.float32, device="cuda")
+    d0["db"] = torch.full((768,), -1.0, dtype=torch.float32, device="cuda")
+    (dW0, db0, _), (dW1, db1, _) = sbp.backward_linear_batch([d0, d1])
+    rW0, rb0, _ = oracle.backward_linear(si.to_f64(c0["dY"]), c0["idx"], si.to_f64(c0["X"])[c0["idx"]], si.to_f64(c0["W"]), c0["M"])
+    assert nerr(f64(dW0), rW0 + 2.0) <= TOL_F32 and nerr(f64(db0), rb0 - 1.0) <= TOL_F32
+    assert dW1.dtype == torch.bfloat16
+    _check_against_oracle(c1, (dW1, db1, None))
