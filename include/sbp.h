@@ -446,6 +446,7 @@ int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* g
  *   "sampler_no_window", "sampler_no_masks", "patch_wide", "debug_plan"   "1" | "0"
  *   "batch_spread"  "1": batched linear call deals its units to the XCDs in turn (no neighbour affinity)
  *   "batch_dynamic" "1": batched linear call fetches units through one counter per XCD instead of static queues
+ *   "batch_db_merged" "1": batched linear call schedules the dW units that also sum db like the other dW units
  *   "dw_strips"     "1": depthwise backward with the register-strip kernels instead of the LDS-tiled one
  */
 int32_t sbp_set_option(const char* name, const char* value);

@@ -101,7 +101,8 @@ static bool apply_option(Options& o, const char* name, const char* v) {
   bool* flag = n == "debug_plan" ? &o.debug_plan : n == "dw_separate" ? &o.dw_separate
              : n == "sampler_no_window" ? &o.sampler_no_window : n == "sampler_no_masks" ? &o.sampler_no_masks
              : n == "patch_wide" ? &o.patch_wide : n == "batch_dynamic" ? &o.batch_dynamic
-             : n == "batch_spread" ? &o.batch_spread : n == "dw_strips" ? &o.dw_strips : nullptr;
+             : n == "batch_spread" ? &o.batch_spread : n == "dw_strips" ? &o.dw_strips
+             : n == "batch_db_merged" ? &o.batch_db_merged : nullptr;
   if (!flag) return false;
   return parse_flag(v, flag);
 }

@@ -210,7 +210,7 @@ __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind,
   const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
   const int covered = min(a.K, a.n_big * a.rows_per_split);
   int sl, tile_m, tile_n;                                      // sl: split within its kind
-  if (!a.db_in_dw) {
+  if (a.db_in_dw != 1) {                                       // one numbering for all dW units of a split
     const int tiles_w = tiles_m * tiles_n;
     sl = L / tiles_w;
     const int rem = L - sl * tiles_w;
@@ -1070,8 +1070,9 @@ __global__ void __launch_bounds__(NTHREADS) reduce_multi_kernel(const RedMultiAr
   const int G = r.G, g = threadIdx.x & (G - 1), lane = threadIdx.x & 63;
   const long long nW4 = r.dW ? r.nW / 4 : 0;
   const long long total = nW4 + (r.db ? r.Cout : 0);
-  const long long first = (((long long)blockIdx.x - r.blk_start) * NTHREADS + threadIdx.x) / G;
-  for (long long e = first; e < total; e += (long long)r.nblk * NTHREADS / G) {
+  const int lg = G == 8 ? 3 : (G == 4 ? 2 : 0);          // G is 1, 4 or 8
+  const long long first = (((long long)blockIdx.x - r.blk_start) * NTHREADS + threadIdx.x) >> lg;
+  for (long long e = first; e < total; e += ((long long)r.nblk * NTHREADS) >> lg) {
     if (e < nW4) {
       const int chunk = (r.nsplit_w + G - 1) / G, s_begin = g * chunk, s_end = min(r.nsplit_w, s_begin + chunk);
       float4 acc = make_float4(0, 0, 0, 0);
@@ -1170,7 +1171,9 @@ static int batch_jobs(const sbp_linear_layer* L, int n, const BatchLayerChoice* 
       const int64_t rps = split_rows(l.K, c[i].splits);
       const int64_t nsp = ceil_div(l.K, rps);
       const int64_t stages = ceil_div(std::min<int64_t>(rps, l.K), big::KB), tiles_m = ceil_div(l.Cout, big::BT);
-      if (l.db) {          // the units of the first tile column also sum db and take longer: a kind of their own, dispatched first
+      if (l.db && options().batch_db_merged) {   // override: one kind for all dW units (those of the first tile column still sum db)
+        out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + (kNsStageBatchDw * (tiles_n - 1) + kNsStageBatchDwDb) / tiles_n * stages, i, 1};
+      } else if (l.db) {   // the units of the first tile column also sum db and take longer: a kind of their own, dispatched first
         out[nj++] = Job{tiles_m * nsp, kNsFixedBatchDw + kNsStageBatchDwDb * stages, i, 5};
         if (tiles_n > 1) out[nj++] = Job{tiles_m * (tiles_n - 1) * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages, i, 1};
       } else {
@@ -1530,7 +1533,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     la.rows_per_split = b.rows_per_split; la.db_slice_rows = b.db_slice_rows;
     la.n_big = b.splits; la.rows_small = 0; la.dx_bm = b.dx_bm;
     la.n_zero = scatter && l.M > l.K ? big_zero_blocks(l.M) : 0;
-    la.db_in_dw = l.db && l.dW ? 1 : 0;
+    la.db_in_dw = l.db && l.dW ? (options().batch_db_merged ? 2 : 1) : 0;
     la.xk_kmajor = (l.flags & SBP_FLAG_XK_KMAJOR) ? 1 : 0;     // (equal splits of a multiple of 64 rows: every split starts on a row group)
     lds = std::max(lds, (size_t)big::RING + std::max<size_t>((size_t)(b.rows_per_split + 2 * big::KB), big::BT) * sizeof(int));
     lds = std::max<size_t>(lds, 16 * 1024);     // the column-sum blocks' staging
@@ -1554,8 +1557,8 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     const LinArgs& la = a.lay[jobs[j].layer];
     const int64_t tiles_n = ceil_div(la.Cin, big::BT), tiles_w = ceil_div(la.Cout, big::BT) * tiles_n;
     const int64_t expect = jobs[j].kind == 0 ? ceil_div(la.K, la.dx_bm) * tiles_n
-                         : jobs[j].kind == 1 ? (la.db_in_dw ? tiles_w - ceil_div(la.Cout, big::BT) : tiles_w) * la.n_big
-                         : jobs[j].kind == 5 ? (la.db_in_dw ? ceil_div(la.Cout, big::BT) * la.n_big : -1)
+                         : jobs[j].kind == 1 ? (la.db_in_dw == 1 ? tiles_w - ceil_div(la.Cout, big::BT) : tiles_w) * la.n_big
+                         : jobs[j].kind == 5 ? (la.db_in_dw == 1 ? ceil_div(la.Cout, big::BT) * la.n_big : -1)
                          : jobs[j].kind == 3 ? la.n_zero
                          : jobs[j].kind == 4 ? ceil_div(la.Cout, 256) * ceil_div(la.K, la.db_slice_rows) : -1;
     if (jobs[j].n != expect || (int64_t)la.n_big * la.rows_per_split < la.K || jobs[j].n <= 0)
