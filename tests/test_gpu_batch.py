@@ -269,3 +269,59 @@ def test_chosen_batch_plan_is_close_to_the_best_forced_plan(name, shapes, geom):
             forced[tuple(sorted(opts.items()))] = _time_batch(dev, ws)
     best = min(forced.values())
     assert chosen <= 1.10 * best, (name, chosen, forced)
+
+
+def test_batched_step_replays_from_a_hip_graph():
+    # a block's three calls (draws, row gathers, backward of two layers) captured once and replayed: the library
+    # allocates nothing and records no memory-set nodes, so every replay must equal the eager result bit for bit,
+    # also with the program's own eager work and synchronisations between the replays
+    B, P, H, W, k = 16, 1, 14, 14, 2
+    M = B * (P + H * W)
+    shapes = [(320, 288), (288, 320)]
+    ins = [si.linear_case(M, ci, co, 150 + i, "bf16") for i, (ci, co) in enumerate(shapes)]
+    Xs = [x[0].cuda() for x in ins]; Ws = [x[1].cuda() for x in ins]; dYs = [x[2].cuda() for x in ins]
+    K = sbp.keep_count(B, P, H, W, k)
+    descs = [sbp.make_desc(B, P, H, W, k, 3, 40 + i) for i in range(2)]
+    idxs = [torch.empty(K, dtype=torch.int32, device="cuda") for _ in range(2)]
+    invs = [torch.empty(M, dtype=torch.int32, device="cuda") for _ in range(2)]
+    Xks = [torch.empty((K, ci), dtype=torch.bfloat16, device="cuda") for ci, _ in shapes]
+    outs = [(torch.empty((co, ci), dtype=torch.float32, device="cuda"), torch.empty((co,), dtype=torch.float32, device="cuda"),
+             torch.empty((M, ci), dtype=torch.bfloat16, device="cuda")) for ci, co in shapes]
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+
+    def step():
+        sbp.sample_indices_batch(descs, idxs, invs)
+        sbp.forward_cache_batch(Xs, idxs, outs=Xks)
+        sbp.backward_linear_batch([dict(dY=dYs[i], idx=idxs[i], inv=invs[i], X_k=Xks[i], W=Ws[i], M=M, dW=outs[i][0], db=outs[i][1],
+                                        dX=outs[i][2]) for i in range(2)], workspace=ws)
+
+    with sbp.options(tile="big"):
+        step()                                             # eager: the reference, and the once-only kernel attributes
+        torch.cuda.synchronize()
+        want = [[t.clone() for t in o] for o in outs]
+        want_idx = [t.clone() for t in idxs]
+        for i in range(2):
+            assert np.array_equal(want_idx[i].cpu().numpy(), oracle.sample_indices(B, P, H, W, k, 3, 40 + i))
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()                                         # warm-up on the capturing stream
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for o in outs:
+                for t in o:
+                    t.fill_(float("nan"))
+            for t in idxs:
+                t.fill_(-7)
+            junk = torch.randn(1 << 20, device="cuda").sum()      # eager work of the program between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert float(junk) == float(junk)
+            for i in range(2):
+                assert np.array_equal(idxs[i].cpu().numpy(), want_idx[i].cpu().numpy()), rep
+                for a, b in zip(outs[i], want[i]):
+                    assert np.array_equal(bits(a), bits(b)), (rep, i)
