@@ -192,8 +192,9 @@ __device__ __forceinline__ int segment_unit(int wg_global, int s, int n) {
 }
 
 // One unit of the large-tile engine: kind 0 = dX tile number L, kind 1 / 2 = dW unit number L among the long /
-// (with db_in_dw: kind 5 = dW unit number L among those of the first tile column, kind 1 among the others)
-// short splits (a tile of dW over the kept rows of one split, written as an fp32 partial sum).
+// short splits (a tile of dW over the kept rows of one split, written as an fp32 partial sum).  With db_in_dw = 1
+// the dW units of the first tile column (which also sum db) are numbered apart: kind 5 = unit number L among
+// them, kind 1 among the others; with db_in_dw = 2 they sum db too but all dW units share one numbering.
 __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind, int L) {
   const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
   if (kind == 0) {
@@ -921,7 +922,10 @@ static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool
   allow_big_lds(linear_big_kernel, lds);
   const long long tiles_n = ceil_div(a.Cin, big::BT);
   a.n_zero = want_zero ? big_zero_blocks(a.M) : 0;
-  const int n_db = a.dbp ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
+  // with dW wanted, db comes out of the dW units of the first tile column (one slice per split); column-sum blocks
+  // that read dY_k once more only where db is wanted alone
+  a.db_in_dw = a.dbp && want_dw ? 2 : 0;
+  const int n_db = a.dbp && !a.db_in_dw ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
   a.n_helper = a.n_zero + n_db;
   a.dx_bm = p.dx_bm;
   a.n_dx = want_dx ? (int)(ceil_div(a.K, p.dx_bm) * tiles_n) : 0;
@@ -1024,7 +1028,7 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   if (dW || db) {
     if (nW % 4 == 0) {
       const long long total = (dW ? nW / 4 : 0) + (db ? Cout : 0);
-      const int nsplit_b = use_mfma ? p.db_slices : p.splits;
+      const int nsplit_b = use_mfma && !(p.big && dW) ? p.db_slices : p.splits;   // (large tiles with dW: db slices come from the dW units, one per split)
       const int deepest = std::max(dW ? p.splits : 0, db ? nsplit_b : 0);
       const int G = reduce_lanes(total, deepest);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total * G, NTHREADS), 4096);
