@@ -1483,7 +1483,7 @@ static bool launch_small_batch(const BatchPlan& p, const sbp_linear_layer* L, in
       RedLayer& rl = r.lay[i];
       const long long total = (rl.dW ? rl.nW / 4 : 0) + (rl.db ? rl.Cout : 0);
       rl.blk_start = rb;
-      rl.nblk = (int)std::min<long long>(ceil_div(total * rl.G, NTHREADS), 2048);
+      rl.nblk = (int)std::min<long long>(ceil_div(total * rl.G, NTHREADS), 16384);
       rb += rl.nblk;
     }
     if (rb > 0) SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_multi_kernel, dim3((unsigned)rb), dim3(NTHREADS), 0, s, r);
@@ -1609,7 +1609,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
       RedLayer& rl = r.lay[i];
       const long long total = (rl.dW ? rl.nW / 4 : 0) + (rl.db ? rl.Cout : 0);
       rl.blk_start = blk;
-      rl.nblk = (int)std::min<long long>(ceil_div(total, NTHREADS), 2048);
+      rl.nblk = (int)std::min<long long>(ceil_div(total, NTHREADS), 16384);   // (one output per thread up to 4 M of them: the partials of an output are all in flight at once)
       blk += rl.nblk;
     }
     if (blk > 0) SBP_LAUNCH(SBP_PROF_REDUCE, s, reduce_multi_kernel, dim3((unsigned)blk), dim3(NTHREADS), 0, s, r);
