@@ -81,6 +81,12 @@ class LinearLayer:
         return self.L.sbp_forward_cache(self.X.data_ptr(), idx_ptr, self.M, K, self.Cin, self.code,
                                         self.Xk.data_ptr(), self.stream)
 
+    def backward_dx(self, idx_ptr, inv_ptr, K):
+        """only the input gradient (the critical path of a chain of dependent layers)"""
+        return self.L.sbp_backward_linear(self.dY.data_ptr(), idx_ptr, inv_ptr, None, self.W.data_ptr(), self.M,
+                                          K, self.Cin, self.Cout, self.code, None, None,
+                                          self.dX.data_ptr(), self.ws.data_ptr(), self.ws.numel(), 0, self.stream)
+
     def backward(self, idx_ptr, inv_ptr, K):
         return self.L.sbp_backward_linear(self.dY.data_ptr(), idx_ptr, inv_ptr, self.Xk.data_ptr(), self.W.data_ptr(), self.M,
                                           K, self.Cin, self.Cout, self.code, self.dW.data_ptr(), self.db.data_ptr(),
@@ -142,6 +148,8 @@ class Job:
         # marshalled once; set_ratio fills in K
         # (every block has its own keep list there: the masks of a whole step are drawn by one call at its start)
         self.batch_args = []
+        self.batch_args_w = []
+        self.chained = False
         nb = len(self.blocks)
         self.idx_b = [torch.empty(M, dtype=torch.int32, device="cuda") for _ in range(nb)]
         self.inv_b = [torch.empty(M, dtype=torch.int32, device="cuda") for _ in range(nb)]
@@ -153,7 +161,13 @@ class Job:
                 for l in reversed(blk)])
             items = (_lib.GatherItem * len(blk))(*[
                 _lib.GatherItem(l.X.data_ptr(), ip, l.Xk.data_ptr(), M, 0, l.Cin, sbp.LAYOUT_KMAJOR if self.kmajor else 0) for l in blk])
+            # chained pattern: the weight gradients of the block in one call, no dX
+            lays_w = (_lib.LinearLayer * len(blk))(*[
+                _lib.LinearLayer(l.dY.data_ptr(), ip, vp, l.Xk.data_ptr(), l.W.data_ptr(), M, 0,
+                                 l.Cin, l.Cout, l.dW.data_ptr(), l.db.data_ptr(), None, sbp.FLAG_XK_KMAJOR if self.kmajor else 0, 0)
+                for l in reversed(blk)])
             self.batch_args.append((lays, items))
+            self.batch_args_w.append(lays_w)
         self.descs = (_lib.SampleDesc * nb)(*[sbp.make_desc(wl.B, wl.P, wl.H, wl.W, 2, 0, 0) for _ in range(nb)])
         self.idx_ptrs = (ctypes.c_void_p * nb)(*[t.data_ptr() for t in self.idx_b])
         self.inv_ptrs = (ctypes.c_void_p * nb)(*[t.data_ptr() for t in self.inv_b])
@@ -169,6 +183,10 @@ class Job:
             for i in range(len(lays)):
                 lays[i].K = self.K
                 items[i].K = self.K
+            need = max(need, int(self.L.sbp_backward_linear_batch_workspace(lays, len(lays), self.code)))
+        for lays in self.batch_args_w:
+            for i in range(len(lays)):
+                lays[i].K = self.K
             need = max(need, int(self.L.sbp_backward_linear_batch_workspace(lays, len(lays), self.code)))
         if self.ws_batch is None or self.ws_batch.numel() < need:
             self.ws_batch = self.torch.empty(need, dtype=self.torch.uint8, device="cuda")
@@ -195,7 +213,15 @@ class Job:
             else:
                 self.desc.stream_id = self.step_no * 1000 + b      # fresh mask for every block and step
                 check(L.sbp_sample_indices(ctypes.byref(self.desc), idx_ptr, self.M, inv_ptr, self.stream))
-            if self.batched:
+            if self.batched and self.chained:
+                # a chain of dependent layers: dX layer by layer (the critical path), then all weight gradients of the block at once
+                lays, items = self.batch_args[b]
+                check(L.sbp_forward_cache_batch(items, len(items), self.code, self.stream))
+                for lay in reversed(blk):
+                    check(lay.backward_dx(idx_ptr, inv_ptr, K))
+                lw = self.batch_args_w[b]
+                check(L.sbp_backward_linear_batch(lw, len(lw), self.code, self.ws_batch.data_ptr(), self.ws_batch.numel(), self.stream))
+            elif self.batched:
                 lays, items = self.batch_args[b]
                 check(L.sbp_forward_cache_batch(items, len(items), self.code, self.stream))   # forward side: the kept rows
                 check(L.sbp_backward_linear_batch(lays, len(lays), self.code, self.ws_batch.data_ptr(),
@@ -731,6 +757,23 @@ def measure_ceilings(torch, sbp, si, iters=10):
     out["dense_gemm_pair"] = {"kernel": "sbp_backward_linear, r = 1, compact operands, 16384 x 4096 x 4096",
                               "us": round(ms * 1e3, 1), "tflops": round(tf, 1),
                               "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4)}
+    # for scale only (not part of the product, which calls no vendor GEMM): what the vendor's GEMM library reaches on this
+    # box for the same two dense products through torch.matmul, bf16 in, bf16 out
+    try:
+        dWv = torch.empty((Cout, Cin), dtype=torch.bfloat16, device="cuda")
+
+        def vendor():
+            torch.matmul(dY.t(), Xk, out=dWv)
+            torch.matmul(dY, W, out=dX)
+        msv = timed(vendor, iters)
+        tfv = 4.0 * K * Cin * Cout / msv / 1e9
+        out["vendor_gemm_pair"] = {"kernel": "torch.matmul (vendor GEMM library), the same two dense products, bf16 outputs",
+                                   "us": round(msv * 1e3, 1), "tflops": round(tfv, 1),
+                                   "frac_of_bf16_mfma_peak": round(tfv / PEAK_BF16_TFLOPS, 4)}
+        out["dense_gemm_pair"]["frac_of_vendor_gemm_pair"] = round(tf / tfv, 3)
+        del dWv
+    except Exception as e:   # the measurement is context, never a reason to fail the run
+        out["vendor_gemm_pair"] = {"error": str(e)[:200]}
     del dY, Xk, W, dW, dX, ws
     torch.cuda.empty_cache()
     return out
@@ -884,6 +927,16 @@ def main():
                   else "one sbp_forward_cache + one sbp_backward_linear per layer",
                   "ms_per_step": round(ms_other, 4), "tflops": round(flops / ms_other / 1e9, 2)}
     job.batched = not job.batched
+    chained_mode = None
+    if job.batched and not job.kmajor:
+        # a chain of dependent layers (a real training step): the input gradients layer by layer, the weight gradients
+        # of the block in one batched call
+        job.chained = True
+        ms_ch, _ = job.time_steps(max(3, args.steps // 2), 2)
+        job.chained = False
+        chained_mode = {"calls": "one sbp_forward_cache_batch per block, one sbp_backward_linear (dX only) per layer, "
+                                 "one sbp_backward_linear_batch (dW, db of the block) per block",
+                        "ms_per_step": round(ms_ch, 4), "tflops": round(flops / ms_ch / 1e9, 2)}
     s_ = 2 if wl.dtype == "bf16" else 4
     cached = sum(K_r * s.Cin * s_ + 4 * K_r for s in wl.linears)
     full = sum(wl.M * s.Cin * s_ for s in wl.linears)
@@ -907,6 +960,7 @@ def main():
         "calls": "one sbp_sample_indices_batch per step, one sbp_forward_cache_batch + one sbp_backward_linear_batch per block" if job.batched
                  else "one sbp_forward_cache + one sbp_backward_linear per layer",
         "other_call_pattern": other_mode,
+        "chained_call_pattern": chained_mode,
         "keep_ratio_sweep": sweep,
         "kernel_breakdown": breakdown,
         "roofline": roofline,

@@ -221,9 +221,10 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
  * Several linear layers in one call (paper, eq:backward_fc_sbp per layer; the benchmark configuration asks for
  * the "per-block backward of all four linears" of a transformer block).  Every layer is described as in
  * sbp_backward_linear (same argument meaning, flags and outputs); all layers share `dtype`.  The layers must be
- * independent: no layer's dY may be another's dX or alias any output of the call (a chain of dependent layers
- * still profits: the weight gradients of a block need only each layer's dY and X_k, so a caller can run the
- * dX of the critical path layer by layer and hand all dW / db of the block to one call, with dX = NULL).
+ * independent: no layer's dY may be another's dX or alias any output of the call.  (A chain of dependent layers
+ * can still hand the weight gradients of a block to one call with dX = NULL - they need only each layer's dY and
+ * X_k - after running the dX of the critical path layer by layer; on the ViT-Base block that was measured slower
+ * than one full sbp_backward_linear call per layer, whose launch overlaps a layer's dX tiles with its dW units.)
  * bf16 layers within the large-tile engine's limits (Cin % 8 == 0, Cout % 32 == 0, M * max(Cin, Cout) < 2^31,
  * K >= 1, 16-byte aligned tensors) that are at least 256 channels wide with K >= 1024 run as ONE grid whose
  * units - dX tiles, dW units (which also sum db), zero-fill blocks of all layers - are laid out in one queue
