@@ -495,9 +495,55 @@ __global__ void __launch_bounds__(256, D == 128 ? 1 : 2) attn_bwd_mfma_kernel(co
 // ------------------------------------------------------------------------------------------------
 static constexpr int kAttnChunk = 128;
 
+// Rows t0 .. t0 + 127 of one (sample, head) into two LDS images of 128 rows (rows past n_k as zeros).  KEY = true:
+// the queries' side (q -> t1, dA -> t2, lse * log2 e and delta = dA.A into the tables); false: the keys' side
+// (k -> t1, v -> t2).  The loads are issued before the barrier that retires the images' previous contents.
+template <int D, bool KEY>
+__device__ __forceinline__ void attn_load_tile(const AttnItem& it, int t0, int n_k, int h, char* t1, char* t2,
+                                               float* lse_s, float* delta_s) {
+  constexpr int CH = D / 8, PITCH = AttnLds<D>::PITCH, R = kAttnChunk * CH / 256;   // 16-byte pieces per thread, tensor and tile
+  const int t = threadIdx.x;
+  const long long ldq = 3LL * h * D, lda = (long long)h * D;
+  uint4 x1[R], x2[R], x3[KEY ? R : 1];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int p = t + 256 * r, tok = t0 + p / CH, ch = p % CH;
+    x1[r] = x2[r] = make_uint4(0, 0, 0, 0);
+    if constexpr (KEY) x3[r] = make_uint4(0, 0, 0, 0);
+    if (tok < n_k) {
+      if constexpr (KEY) {
+        x1[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + 8 * ch);
+        x2[r] = *reinterpret_cast<const uint4*>(it.g + tok * lda + 8 * ch);
+        x3[r] = *reinterpret_cast<const uint4*>(it.a + tok * lda + 8 * ch);
+      } else {
+        x1[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + (long long)h * D + 8 * ch);
+        x2[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + 2LL * h * D + 8 * ch);
+      }
+    }
+  }
+  float lv = 0.f;
+  if (KEY && t < kAttnChunk && t0 + t < n_k) lv = it.lse[(long long)(t0 + t) * h] * kLog2e;
+  __syncthreads();                                        // the previous contents have been consumed
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int p = t + 256 * r, tok = p / CH, ch = p % CH;
+    *reinterpret_cast<uint4*>(t1 + tok * PITCH + ch * 16) = x1[r];
+    *reinterpret_cast<uint4*>(t2 + tok * PITCH + ch * 16) = x2[r];
+    if constexpr (KEY) {
+      const uint32_t gw[4] = {x2[r].x, x2[r].y, x2[r].z, x2[r].w}, aw[4] = {x3[r].x, x3[r].y, x3[r].z, x3[r].w};
+      float sacc = 0.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) sacc += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
+      for (int m = 1; m < CH; m <<= 1) sacc += __shfl_xor(sacc, m);
+      if (ch == 0) delta_s[tok] = sacc;
+    }
+  }
+  if (KEY && t < kAttnChunk) lse_s[t] = lv;
+}
+
 template <int D, bool KEY>
 __device__ __forceinline__ void attn_tiled_body(char* smem, const AttnItem& it, int chunk, int n_k, int h, float scale) {
-  constexpr int CH = D / 8, PITCH = AttnLds<D>::PITCH, R = kAttnChunk * CH / 256;   // 16-byte pieces per thread, tensor and tile
+  constexpr int PITCH = AttnLds<D>::PITCH;
   char* t1 = smem;                                   // rows of q (key role) or k (query role)
   char* t2 = t1 + kAttnChunk * PITCH;                // rows of dA or v
   float* lse_s = reinterpret_cast<float*>(t2 + kAttnChunk * PITCH);
@@ -514,41 +560,7 @@ __device__ __forceinline__ void attn_tiled_body(char* smem, const AttnItem& it, 
   const int npad = (n_k + 31) & ~31;
   for (int t0 = 0; t0 < npad; t0 += kAttnChunk) {
     const int rows = min(kAttnChunk, npad - t0);            // rows of this tile (a multiple of 32); rows past n_k are zeros
-    uint4 x1[R], x2[R], x3[KEY ? R : 1];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int p = t + 256 * r, tok = t0 + p / CH, ch = p % CH;
-      x1[r] = x2[r] = make_uint4(0, 0, 0, 0);
-      if constexpr (KEY) x3[r] = make_uint4(0, 0, 0, 0);
-      if (tok < n_k) {
-        if constexpr (KEY) {
-          x1[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + 8 * ch);
-          x2[r] = *reinterpret_cast<const uint4*>(it.g + tok * lda + 8 * ch);
-          x3[r] = *reinterpret_cast<const uint4*>(it.a + tok * lda + 8 * ch);
-        } else {
-          x1[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + (long long)h * D + 8 * ch);
-          x2[r] = *reinterpret_cast<const uint4*>(it.q + tok * ldq + 2LL * h * D + 8 * ch);
-        }
-      }
-    }
-    float lv = 0.f;
-    if (KEY && t < kAttnChunk && t0 + t < n_k) lv = it.lse[(long long)(t0 + t) * h] * kLog2e;
-    __syncthreads();                                        // the previous tile has been consumed
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int p = t + 256 * r, tok = p / CH, ch = p % CH;
-      *reinterpret_cast<uint4*>(t1 + tok * PITCH + ch * 16) = x1[r];
-      *reinterpret_cast<uint4*>(t2 + tok * PITCH + ch * 16) = x2[r];
-      if constexpr (KEY) {
-        const uint32_t gw[4] = {x2[r].x, x2[r].y, x2[r].z, x2[r].w}, aw[4] = {x3[r].x, x3[r].y, x3[r].z, x3[r].w};
-        float sacc = 0.f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) sacc += bf16_lo(gw[e]) * bf16_lo(aw[e]) + bf16_hi(gw[e]) * bf16_hi(aw[e]);
-        for (int m = 1; m < CH; m <<= 1) sacc += __shfl_xor(sacc, m);
-        if (ch == 0) delta_s[tok] = sacc;
-      }
-    }
-    if (KEY && t < kAttnChunk) lse_s[t] = lv;
+    attn_load_tile<D, KEY>(it, t0, n_k, h, t1, t2, lse_s, delta_s);
     __syncthreads();
     if constexpr (KEY) acc.run(t1, t2, lse_s, delta_s, rows >> 5, scale, lane);
     else acc.run(t1, t2, rows >> 5, scale, lane);
