@@ -143,6 +143,7 @@ __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_
                                                            int32_t* __restrict__ inv) {
   constexpr int NWAVE = NT / 64, CAP = WINDOW ? 4096 : 1;
   __shared__ uint64_t cand[CAP];
+  __shared__ int cand_pos[CAP];                      // position of every collected key (large maps with keep bits in LDS)
   __shared__ int s_ncand, s_below;
   __shared__ int hist[256];
   __shared__ uint64_t s_prefix;
@@ -163,13 +164,36 @@ __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_
     if (t == 0) { s_ncand = 0; s_below = 0; }
     __syncthreads();
     int below = 0;
-    for (int p = t; p < n; p += NT) {
-      const uint64_t key = absorb(hb, (uint64_t)p);
-      if (key < g.win_lo) {
-        ++below;
-      } else if (key < g.win_hi) {
-        const int slot = atomicAdd(&s_ncand, 1);
-        if (slot < CAP) cand[slot] = key;
+    if (g.mask_chunks > 0) {
+      // chunk by chunk: the keys below the window are kept whatever the threshold turns out to be - their keep bits
+      // are written now, the collected keys remember their positions, and no second pass over the hash is needed
+      extern __shared__ __attribute__((aligned(16))) unsigned long long dyn0[];
+      unsigned long long* m_lt0 = dyn0;
+      unsigned long long* m_eq0 = dyn0 + g.mask_chunks;
+      for (int c = wave; c < g.mask_chunks; c += NWAVE) {
+        const int p = 64 * c + lane;
+        bool lt = false;
+        if (p < n) {
+          const uint64_t key = absorb(hb, (uint64_t)p);
+          lt = key < g.win_lo;
+          if (!lt && key < g.win_hi) {
+            const int slot = atomicAdd(&s_ncand, 1);
+            if (slot < CAP) { cand[slot] = key; cand_pos[slot] = p; }
+          }
+        }
+        const unsigned long long mlt = __ballot(lt);
+        if (lane == 0) { m_lt0[c] = mlt; m_eq0[c] = 0ull; }
+        below += lt ? 1 : 0;
+      }
+    } else {
+      for (int p = t; p < n; p += NT) {
+        const uint64_t key = absorb(hb, (uint64_t)p);
+        if (key < g.win_lo) {
+          ++below;
+        } else if (key < g.win_hi) {
+          const int slot = atomicAdd(&s_ncand, 1);
+          if (slot < CAP) cand[slot] = key;
+        }
       }
     }
 #pragma unroll
@@ -230,16 +254,27 @@ __global__ void __launch_bounds__(NT) sample_random_kernel(VariantGeom g, int32_
     int* pre_lt = reinterpret_cast<int*>(dyn + 2 * nchunks);
     int* pre_eq = pre_lt + nchunks;
     __syncthreads();                                // s_prefix / s_remaining read by everyone
-    for (int c = wave; c < nchunks; c += NWAVE) {
-      const int p = 64 * c + lane;
-      bool lt = false, eq = false;
-      if (p < n) {
-        const uint64_t key = absorb(hb, (uint64_t)p);
-        lt = key < thr;
-        eq = key == thr;
+    if (windowed) {
+      // the keys below the window already have their bits; of the collected keys those below the threshold get theirs
+      // now, those equal to it go to the "equal" mask (the write-out keeps the take_eq smallest positions of them)
+      for (int i = t; i < ncand; i += NT) {
+        const uint64_t key = cand[i];
+        const int p = cand_pos[i];
+        if (key < thr) atomicOr(&m_lt[p >> 6], 1ull << (p & 63));
+        else if (key == thr) atomicOr(&m_eq[p >> 6], 1ull << (p & 63));
       }
-      const unsigned long long mlt = __ballot(lt), meq = __ballot(eq);
-      if (lane == 0) { m_lt[c] = mlt; m_eq[c] = meq; }
+    } else {
+      for (int c = wave; c < nchunks; c += NWAVE) {
+        const int p = 64 * c + lane;
+        bool lt = false, eq = false;
+        if (p < n) {
+          const uint64_t key = absorb(hb, (uint64_t)p);
+          lt = key < thr;
+          eq = key == thr;
+        }
+        const unsigned long long mlt = __ballot(lt), meq = __ballot(eq);
+        if (lane == 0) { m_lt[c] = mlt; m_eq[c] = meq; }
+      }
     }
     __syncthreads();
     // exclusive scan of the chunk counts: a thread owns a contiguous run of chunks
@@ -554,18 +589,18 @@ int32_t launch_sample(const sbp_sample_desc& d, int32_t* idx, int32_t* inv, hipS
         v.win_hi = hi >= 1.0 ? ~0ull : (uint64_t)(hi * two64);
         const Options opt = options();
         if (opt.sampler_no_window) v.win_lo = v.win_hi = 0;   // override: an empty window, i.e. the full select
-        // keep bits and chunk prefixes of the ordered write-out: 24 bytes per 64 positions, next to 34 KB of static LDS
+        // keep bits and chunk prefixes of the ordered write-out: 24 bytes per 64 positions, next to 50 KB of static LDS
         const int64_t chunks = ceil_div((int64_t)d.H * d.W, 64);
         size_t lds = (size_t)chunks * 24;
         static std::once_flag big_lds_once;             // more than 64 KB in all: granted per kernel, asked for once
         static bool big_lds_ok = false;
-        if (lds > 28 * 1024)
+        if (lds > 12 * 1024)
           std::call_once(big_lds_once, [] {
             big_lds_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(sample_random_kernel<1024, true>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 120 * 1024) == hipSuccess;
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 104 * 1024) == hipSuccess;
           });
         v.mask_chunks = (int)chunks;
-        if (lds > 120 * 1024 || (lds > 28 * 1024 && !big_lds_ok) || opt.sampler_no_masks) { v.mask_chunks = 0; lds = 0; }
+        if (lds > 104 * 1024 || (lds > 12 * 1024 && !big_lds_ok) || opt.sampler_no_masks) { v.mask_chunks = 0; lds = 0; }
         SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<1024, true>), dim3(d.B), dim3(1024), lds, s, v, idx, inv);
       } else {
         SBP_LAUNCH(SBP_PROF_SAMPLE, s, (sample_random_kernel<256, false>), dim3(d.B), dim3(256), 0, s, v, idx, inv);
