@@ -307,7 +307,7 @@ def timeline_report(job, torch, sbp, wl):
     e = np.where(tiles, (t[:, 1] - base) / 100.0, s)
     d = e - s
     names = [x.name for x in reversed(wl.linears)]
-    kn = {0: "dX tile", 1: "dW unit", 2: "dW unit (short)", 3: "zero fill", 4: "column sums", 5: "dW unit + db"}
+    kn = {0: "dX tile", 1: "dW unit", 2: "dW unit (short)", 3: "zero fill", 4: "column sums"}
     out = {"workgroups": n, "span_us": round(float(e.max()), 1), "segments": []}
     xcd, ran_on = t[:, 5] & 0xff, (t[:, 5] >> 8) & 0xff      # queue the unit was planned on, XCD that ran it
     keys = sorted({(int(layer[i]), int(kind[i])) for i in range(len(t)) if used[i]}, key=lambda lk: float(np.min(s[(layer == lk[0]) & (kind == lk[1]) & used[:len(t)]])))
@@ -323,7 +323,7 @@ def timeline_report(job, torch, sbp, wl):
             seg["shader_mhz_median"] = round(float(np.median(cyc / np.maximum(d[sl], 1e-3))), 0)
         out["segments"].append(seg)
     out["cu_busy_frac"] = round(float(d[tiles].sum() / (256.0 * e.max())), 3)
-    out["cu_busy_frac_tiles_only"] = round(float(d[tiles & ((kind <= 2) | (kind == 5))].sum() / (256.0 * e.max())), 3)
+    out["cu_busy_frac_tiles_only"] = round(float(d[tiles & (kind <= 2)].sum() / (256.0 * e.max())), 3)
     out["per_xcd_last_end_us"] = [round(float(e[(ran_on == x) & used[:len(t)]].max()), 1) for x in range(8)]
     return out
 

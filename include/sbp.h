@@ -230,7 +230,8 @@ int32_t sbp_backward_linear(const void* dY, const int32_t* idx, const int32_t* i
  * units - dX tiles, dW units (which also sum db), zero-fill blocks of all layers - are laid out in one queue
  * per XCD, longest first, plus one reduction launch for all split sums; a batch with any other layer runs
  * layer by layer, exactly as n calls of sbp_backward_linear would.  A layer whose dW
- * needs a single split writes dW directly (no partial sums, no reduction).  Results per layer equal those of
+ * needs a single split (up to 7936 kept rows) writes dW directly (no partial sums; the reduction launch then
+ * adds only the db partials, one per tile column of dW).  Results per layer equal those of
  * sbp_backward_linear up to the summation order of dW / db (bit-identical on exactly representable inputs).
  *   layers     host array of n descriptors, 1 <= n <= SBP_MAX_BATCH_LAYERS; read during the call only
  *   workspace  device, 256-byte aligned, sbp_backward_linear_batch_workspace(layers, n, dtype) bytes (the
@@ -447,7 +448,6 @@ int32_t sbp_backward_layernorm(const void* dU_k, const void* X_k, const float* g
  *   "sampler_no_window", "sampler_no_masks", "patch_wide", "debug_plan"   "1" | "0"
  *   "batch_spread"  "1": batched linear call deals its units to the XCDs in turn (no neighbour affinity)
  *   "batch_dynamic" "1": batched linear call fetches units through one counter per XCD instead of static queues
- *   "batch_db_merged" "1": batched linear call schedules the dW units that also sum db like the other dW units
  *   "dw_strips"     "1": depthwise backward with the register-strip kernels instead of the LDS-tiled one
  */
 int32_t sbp_set_option(const char* name, const char* value);

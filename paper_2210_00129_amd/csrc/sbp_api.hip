@@ -102,7 +102,7 @@ static bool apply_option(Options& o, const char* name, const char* v) {
              : n == "sampler_no_window" ? &o.sampler_no_window : n == "sampler_no_masks" ? &o.sampler_no_masks
              : n == "patch_wide" ? &o.patch_wide : n == "batch_dynamic" ? &o.batch_dynamic
              : n == "batch_spread" ? &o.batch_spread : n == "dw_strips" ? &o.dw_strips
-             : n == "batch_db_merged" ? &o.batch_db_merged : nullptr;
+             : nullptr;
   if (!flag) return false;
   return parse_flag(v, flag);
 }

@@ -50,7 +50,6 @@ struct Options {
   bool batch_spread = false;          // batched linear backward: units dealt to the XCDs in turn instead of in runs
   bool batch_dynamic = false;         // batched linear backward: units taken from the XCD queues with atomic counters
   int attn_mode = 0;       // attention backward: 0 chosen by size, 1 plain kernel, 2 one workgroup per head where it fits, 3 tiled
-  bool batch_db_merged = false;   // batched linear call: the dW units that also sum db are not a unit kind of their own
   bool dw_separate = false, sampler_no_window = false, sampler_no_masks = false, patch_wide = false;
 };
 Options options();                    // a snapshot (taken under a lock; safe against a concurrent sbp_set_option)

@@ -68,8 +68,8 @@ struct LinArgs {
   int seg_order[3];                   // dispatch order: large-tile kernel 0 = dX tiles, 1 = long dW, 2 = short dW units;
                                       // general kernel 0 = dX tiles, 1 = dW units, 2 = zero-fill and column-sum blocks
   int dx_bm;                          // large-tile kernel: rows of a dX tile (256 or 128)
-  int db_in_dw;                       // large-tile kernel: the dW units of the first tile column also produce db (one
-                                      // partial per split in dbp); no column-sum blocks then
+  int db_in_dw;                       // large-tile kernel: the dW units also produce db, each from its share of the rows (one
+                                      // partial per split and tile column in dbp); no column-sum blocks then
   int xk_kmajor;                      // large-tile kernel: Xk is in the row-group layout [K / 8][Cin][8]
 };
 
@@ -192,9 +192,8 @@ __device__ __forceinline__ int segment_unit(int wg_global, int s, int n) {
 }
 
 // One unit of the large-tile engine: kind 0 = dX tile number L, kind 1 / 2 = dW unit number L among the long /
-// short splits (a tile of dW over the kept rows of one split, written as an fp32 partial sum).  With db_in_dw = 1
-// the dW units of the first tile column (which also sum db) are numbered apart: kind 5 = unit number L among
-// them, kind 1 among the others; with db_in_dw = 2 they sum db too but all dW units share one numbering.
+// short splits (a tile of dW over the kept rows of one split, written as an fp32 partial sum; with db_in_dw also a
+// partial of db: slice split * tiles_n + tile column of dbp).
 __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind, int L) {
   const int tiles_n = (a.Cin + big::BT - 1) / big::BT;
   if (kind == 0) {
@@ -208,47 +207,33 @@ __device__ __forceinline__ void big_unit(char* smem, const LinArgs& a, int kind,
     return;
   }
   // the first n_big splits have rows_per_split rows each, the others rows_small
-  const int tiles_m = (a.Cout + big::BT - 1) / big::BT;
+  const int tiles_m = (a.Cout + big::BT - 1) / big::BT, tiles_w = tiles_m * tiles_n;
   const int covered = min(a.K, a.n_big * a.rows_per_split);
-  int sl, tile_m, tile_n;                                      // sl: split within its kind
-  if (a.db_in_dw != 1) {                                       // one numbering for all dW units of a split
-    const int tiles_w = tiles_m * tiles_n;
-    sl = L / tiles_w;
-    const int rem = L - sl * tiles_w;
-    tile_m = rem / tiles_n; tile_n = rem - tile_m * tiles_n;
-  } else if (kind == 5) {                                      // the units of the first tile column, which also sum db
-    sl = L / tiles_m;
-    tile_m = L - sl * tiles_m; tile_n = 0;
-    kind = 1;
-  } else {                                                     // ... and the other tile columns
-    const int tn1 = tiles_n - 1, tiles_w = tiles_m * tn1;
-    sl = L / tiles_w;
-    const int rem = L - sl * tiles_w;
-    tile_m = rem / tn1; tile_n = rem - tile_m * tn1 + 1;
-  }
+  const int sl = L / tiles_w, rem = L - sl * tiles_w;          // sl: split within its kind
+  const int tile_m = rem / tiles_n, tile_n = rem - tile_m * tiles_n;
   const int j0 = kind == 1 ? sl * a.rows_per_split : covered + sl * a.rows_small;
   const int j1 = min(a.K, j0 + (kind == 1 ? a.rows_per_split : a.rows_small));
   const int split = kind == 1 ? sl : a.n_big + sl;
   float* part = a.part + (long long)split * a.Cout * a.Cin;
-  if (a.xk_kmajor) {
-    if (a.db_in_dw && tile_n == 0) {
-      float* dbp = a.dbp + (long long)split * a.Cout;
-      if (a.idx_in) big::dw_tile<true, true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
-      else big::dw_tile<false, true, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
-      return;
+  const int m0 = tile_m * big::BT, n0 = tile_n * big::BT;
+  if (a.db_in_dw) {        // every unit sums its share of the columns of its dY panel: one slice of dbp per split and tile column
+    float* dbp = a.dbp + ((long long)split * tiles_n + tile_n) * a.Cout;
+    if (a.xk_kmajor) {
+      if (a.idx_in) big::dw_tile<true, true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0, dbp, tile_n, tiles_n);
+      else big::dw_tile<false, true, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0, dbp, tile_n, tiles_n);
+    } else {
+      if (a.idx_in) big::dw_tile<true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0, dbp, tile_n, tiles_n);
+      else big::dw_tile<false, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0, dbp, tile_n, tiles_n);
     }
-    if (a.idx_in) big::dw_tile<true, false, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
-    else big::dw_tile<false, false, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
     return;
   }
-  if (a.db_in_dw && tile_n == 0) {
-    float* dbp = a.dbp + (long long)split * a.Cout;
-    if (a.idx_in) big::dw_tile<true, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
-    else big::dw_tile<false, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, 0, dbp);
+  if (a.xk_kmajor) {
+    if (a.idx_in) big::dw_tile<true, false, true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0);
+    else big::dw_tile<false, false, true>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0);
     return;
   }
-  if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
-  else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, tile_m * big::BT, tile_n * big::BT);
+  if (a.idx_in) big::dw_tile<true>(smem, a.dY, a.idx_in, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0);
+  else big::dw_tile<false>(smem, a.dY, nullptr, a.Xk, a.Cin, a.Cout, j0, j1, part, m0, n0);
 }
 
 // The same work with 256 x 256 tiles (sbp_mfma_big.h): one workgroup per CU, so the order of the grid
@@ -349,7 +334,7 @@ __global__ void __launch_bounds__(256, 1) linear_multi_kernel(const MultiArgs a,
   const bool stamp = a.timeline != nullptr && slot < a.timeline_cap;
   unsigned long long t0 = 0, c0 = 0;
   if (stamp) { t0 = wall_clock64(); c0 = clock64(); }
-  if (kind <= 2 || kind == 5) {
+  if (kind <= 2) {
     big_unit(smem, la, kind, L);
   } else if (kind == 3) {
     zero_rows_block(la, L);                        // la.n_zero = number of these blocks
@@ -597,7 +582,7 @@ static constexpr int kNumCU = 256;
 // ---- large-tile engine: tile height of dX and the dW splits ----------------------------------------
 // Workgroup i of the grid goes to XCD i % 8, every XCD hands its workgroups in order to its 32 CUs, one per CU:
 // list scheduling per XCD.  The host simulates it from unit costs and takes the cheapest schedule.
-static constexpr int kBigMaxRowsPerSplit = 4096;   // row ids of a split in LDS next to the 128 KB ring
+static constexpr int kBigMaxRowsPerSplit = 7936;   // row ids of a split in LDS next to the 128 KB ring (160 KB in all)
 // Unit costs in nanoseconds: durations of the workgroups read from the device clock inside a training-like
 // step (operands cold, all CUs busy) for the four ViT-Base layer shapes: a straight line through the units of
 // 20 to 96 stages of 32.  The fixed part is the first stages' latency, the index tables and the epilogue (a
@@ -804,7 +789,9 @@ LinearPlan plan_linear(int64_t M, int64_t K, int32_t Cin, int32_t Cout, int32_t 
   p.off_partial = off;
   p.db_slice_rows = db_slice_rows_for(K, p.big);
   p.db_slices = p.mfma ? (int)std::max<int64_t>(1, ceil_div(K, p.db_slice_rows)) : splits;
-  off += align_up(((size_t)splits * Cout * Cin + (size_t)std::max(p.db_slices, splits) * Cout) * sizeof(float), 256);
+  // db partials: one per slice of the column-sum blocks, or (large tiles, db out of the dW units) per split and tile column
+  const int64_t db_parts = std::max<int64_t>(p.db_slices, (int64_t)splits * (p.big ? ceil_div(Cin, big::BT) : 1));
+  off += align_up(((size_t)splits * Cout * Cin + (size_t)db_parts * Cout) * sizeof(float), 256);
   p.off_inv = off;
   if (!(flags & SBP_FLAG_DX_COMPACT)) off += align_up((size_t)M * sizeof(int32_t), 256);
   p.off_xrows = off;      // X_k copied back to rows, for the engines that do not read the row-group layout
@@ -924,7 +911,7 @@ static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool
   a.n_zero = want_zero ? big_zero_blocks(a.M) : 0;
   // with dW wanted, db comes out of the dW units of the first tile column (one slice per split); column-sum blocks
   // that read dY_k once more only where db is wanted alone
-  a.db_in_dw = a.dbp && want_dw ? 2 : 0;
+  a.db_in_dw = a.dbp && want_dw ? 1 : 0;
   const int n_db = a.dbp && !a.db_in_dw ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
   a.n_helper = a.n_zero + n_db;
   a.dx_bm = p.dx_bm;
@@ -1028,7 +1015,8 @@ int32_t launch_backward_linear(const LinearPlan& p, const void* dY, const int32_
   if (dW || db) {
     if (nW % 4 == 0) {
       const long long total = (dW ? nW / 4 : 0) + (db ? Cout : 0);
-      const int nsplit_b = use_mfma && !(p.big && dW) ? p.db_slices : p.splits;   // (large tiles with dW: db slices come from the dW units, one per split)
+      // (large tiles with dW: db partials come from the dW units, one per split and tile column)
+      const int nsplit_b = use_mfma && !(p.big && dW) ? p.db_slices : (p.big ? p.splits * (int)ceil_div(Cin, big::BT) : p.splits);
       const int deepest = std::max(dW ? p.splits : 0, db ? nsplit_b : 0);
       const int G = reduce_lanes(total, deepest);
       unsigned blocks = (unsigned)std::min<long long>(ceil_div(total * G, NTHREADS), 4096);
@@ -1147,7 +1135,7 @@ static bool batch_layer_fits(const sbp_linear_layer& l, int32_t dtype) {
 // the per-XCD queues in place: every CU is in matrix-core code for the whole launch and the chip then runs at 1.6-1.7 GHz
 // (1.3 GHz before the queues cut the traffic between the L2s and memory by a third); dW units of 99 / 66 stages took
 // 95 / 63 us, dX tiles of 96 / 72 / 24 stages 89 / 67 / 29 us.  The shorter dX tiles are scaled as in the single-layer costs.
-static constexpr int64_t kNsStageBatchDwDb = 1040;      // dW units that also sum db
+static constexpr int64_t kNsStageBatchDb = 110;         // extra per stage in which a dW unit sums db columns
 static constexpr int64_t kNsFixedBatchDw = 3000, kNsStageBatchDw = 930, kNsFixedBatch = 9000, kNsStageBatch256 = 830,
                          kNsStageBatch128 = 500, kNsStageBatch64 = 400;
 struct BatchLayerChoice { int dx_bm, splits; };
@@ -1175,14 +1163,9 @@ static int batch_jobs(const sbp_linear_layer* L, int n, const BatchLayerChoice* 
       const int64_t rps = split_rows(l.K, c[i].splits);
       const int64_t nsp = ceil_div(l.K, rps);
       const int64_t stages = ceil_div(std::min<int64_t>(rps, l.K), big::KB), tiles_m = ceil_div(l.Cout, big::BT);
-      if (l.db && options().batch_db_merged) {   // override: one kind for all dW units (those of the first tile column still sum db)
-        out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + (kNsStageBatchDw * (tiles_n - 1) + kNsStageBatchDwDb) / tiles_n * stages, i, 1};
-      } else if (l.db) {   // the units of the first tile column also sum db and take longer: a kind of their own, dispatched first
-        out[nj++] = Job{tiles_m * nsp, kNsFixedBatchDw + kNsStageBatchDwDb * stages, i, 5};
-        if (tiles_n > 1) out[nj++] = Job{tiles_m * (tiles_n - 1) * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages, i, 1};
-      } else {
-        out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages, i, 1};
-      }
+      // with db wanted every dW unit sums the db columns of its panel in its share (1 / tiles_n) of the stages
+      const int64_t db_stages = l.db ? ceil_div(stages, tiles_n) : 0;
+      out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages + kNsStageBatchDb * db_stages, i, 1};
       const bool direct = nsp == 1 && !(l.flags & (SBP_FLAG_ACCUMULATE_DW | SBP_FLAG_DW_OUT_BF16));
       if (!direct) red += (double)(nsp + 1) * l.Cout * l.Cin * 4.0 / kReduceBytesPerNs;
     }
@@ -1376,7 +1359,7 @@ BatchPlan plan_linear_batch(const sbp_linear_layer* L, int32_t n, int32_t dtype)
     b.off = off;
     if (l.dW && !b.direct) off += align_up((size_t)b.splits * l.Cout * l.Cin * sizeof(float), 256);
     b.off_dbp = off;
-    if (l.db) off += align_up((size_t)std::max(b.db_slices, b.splits) * l.Cout * sizeof(float), 256);
+    if (l.db) off += align_up((size_t)std::max<int64_t>(b.db_slices, b.splits * ceil_div(l.Cin, big::BT)) * l.Cout * sizeof(float), 256);
     b.off_inv = off;
     if (l.dX && !(l.flags & SBP_FLAG_DX_COMPACT) && !l.inv) off += align_up((size_t)l.M * sizeof(int32_t), 256);
   }
@@ -1537,7 +1520,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     la.rows_per_split = b.rows_per_split; la.db_slice_rows = b.db_slice_rows;
     la.n_big = b.splits; la.rows_small = 0; la.dx_bm = b.dx_bm;
     la.n_zero = scatter && l.M > l.K ? big_zero_blocks(l.M) : 0;
-    la.db_in_dw = l.db && l.dW ? (options().batch_db_merged ? 2 : 1) : 0;
+    la.db_in_dw = l.db && l.dW ? 1 : 0;
     la.xk_kmajor = (l.flags & SBP_FLAG_XK_KMAJOR) ? 1 : 0;     // (equal splits of a multiple of 64 rows: every split starts on a row group)
     lds = std::max(lds, (size_t)big::RING + std::max<size_t>((size_t)(b.rows_per_split + 2 * big::KB), big::BT) * sizeof(int));
     lds = std::max<size_t>(lds, 16 * 1024);     // the column-sum blocks' staging
@@ -1546,7 +1529,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     rl.part = la.part; rl.dbp = la.dbp;
     rl.dW = b.direct ? nullptr : l.dW; rl.db = l.db;
     rl.nW = (long long)l.Cin * l.Cout;
-    rl.nsplit_w = b.splits; rl.nsplit_b = la.db_in_dw ? b.splits : b.db_slices; rl.Cout = l.Cout;
+    rl.nsplit_w = b.splits; rl.nsplit_b = la.db_in_dw ? b.splits * (int)ceil_div(l.Cin, big::BT) : b.db_slices; rl.Cout = l.Cout;
     rl.accumulate = (l.flags & SBP_FLAG_ACCUMULATE_DW) ? 1 : 0;
     rl.bf16out = (l.flags & SBP_FLAG_DW_OUT_BF16) ? 1 : 0;
     rl.G = 1;
@@ -1561,8 +1544,7 @@ int32_t launch_backward_linear_batch(const BatchPlan& p, const sbp_linear_layer*
     const LinArgs& la = a.lay[jobs[j].layer];
     const int64_t tiles_n = ceil_div(la.Cin, big::BT), tiles_w = ceil_div(la.Cout, big::BT) * tiles_n;
     const int64_t expect = jobs[j].kind == 0 ? ceil_div(la.K, la.dx_bm) * tiles_n
-                         : jobs[j].kind == 1 ? (la.db_in_dw == 1 ? tiles_w - ceil_div(la.Cout, big::BT) : tiles_w) * la.n_big
-                         : jobs[j].kind == 5 ? (la.db_in_dw == 1 ? ceil_div(la.Cout, big::BT) * la.n_big : -1)
+                         : jobs[j].kind == 1 ? tiles_w * la.n_big
                          : jobs[j].kind == 3 ? la.n_zero
                          : jobs[j].kind == 4 ? ceil_div(la.Cout, 256) * ceil_div(la.K, la.db_slice_rows) : -1;
     if (jobs[j].n != expect || (int64_t)la.n_big * la.rows_per_split < la.K || jobs[j].n <= 0)

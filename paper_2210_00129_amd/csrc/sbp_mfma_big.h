@@ -173,6 +173,35 @@ __device__ __forceinline__ void wait_stage_runtime(bool next2, bool next3a) {   
   else wait_async_copies<0>();
 }
 
+// the steady state, stages s .. upto - 1: stage s + 3 exists and is not the last one.  EXTRA: with the problem's extra
+// work on the fragments of every step (DwProb: the column sums)
+template <class P, bool EXTRA>
+__device__ __forceinline__ void ring_steady(char* smem, P& pb, int& s, int upto, f32x16_t (&acc)[P::FM][4],
+                                            bf16x8_t (&pa)[P::FM], bf16x8_t (&pbf)[4], bf16x8_t (&qa)[P::FM],
+                                            bf16x8_t (&qb)[4]) {
+  constexpr int STAGE = P::STAGE, CPS = P::CPA + P::CPB, FM = P::FM, NM = 4 * P::FM + P::NEXTRA;
+  for (; s < upto; ++s) {
+    const char* cur = smem + (s & 3) * STAGE;
+    const char* nxt = smem + ((s + 1) & 3) * STAGE;
+    char* dst = smem + ((s + 3) & 3) * STAGE;
+    pb.prefetch(s + NS);
+    pb.read(cur, 1, qa, qb);
+    pb.issue_a(s + 3, dst, false);
+    mfma_step<P::SWAP, FM>(acc, pa, pbf);
+    if constexpr (EXTRA) pb.extra(pa);
+    interleave_step<NM, P::NREAD + P::NPRE, P::CPA>();
+    wait_async_copies<CPS + P::CPA>();          // stage s + 1 has landed (s + 2 and half of s + 3 may be in flight)
+    lds_barrier();
+    pb.read(nxt, 0, pa, pbf);
+    pb.issue_b(s + 3, dst, false);
+    mfma_step<P::SWAP, FM>(acc, qa, qb);
+    if constexpr (EXTRA) pb.extra(qa);
+    interleave_step<NM, P::NREAD, P::CPB>();
+  }
+}
+
+// P::PHASED: the extra work runs in the steady stages [pb.extra_begin, pb.extra_end) only (three copies of the steady
+// loop, the middle one with it), and in the last NS stages iff pb.extra_drain.
 template <class P>
 __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, int kvalid_last,
                                           f32x16_t (&acc)[P::FM][4]) {
@@ -195,24 +224,14 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
   pb.read(smem, 0, pa, pbf);
 
   int s = 0;
-  // steady state: stage s + 3 exists and is not the last one
-  for (; s + NS < nk; ++s) {
-    const char* cur = smem + (s & 3) * STAGE;
-    const char* nxt = smem + ((s + 1) & 3) * STAGE;
-    char* dst = smem + ((s + 3) & 3) * STAGE;
-    pb.prefetch(s + NS);
-    pb.read(cur, 1, qa, qb);
-    pb.issue_a(s + 3, dst, false);
-    mfma_step<P::SWAP, FM>(acc, pa, pbf);
-    pb.extra(pa);
-    interleave_step<NM, P::NREAD + P::NPRE, P::CPA>();
-    wait_async_copies<CPS + P::CPA>();          // stage s + 1 has landed (s + 2 and half of s + 3 may be in flight)
-    lds_barrier();
-    pb.read(nxt, 0, pa, pbf);
-    pb.issue_b(s + 3, dst, false);
-    mfma_step<P::SWAP, FM>(acc, qa, qb);
-    pb.extra(qa);
-    interleave_step<NM, P::NREAD, P::CPB>();
+  bool drain_extra = true;
+  if constexpr (P::PHASED) {
+    ring_steady<P, false>(smem, pb, s, min(pb.extra_begin, nk - NS), acc, pa, pbf, qa, qb);
+    ring_steady<P, true>(smem, pb, s, min(pb.extra_end, nk - NS), acc, pa, pbf, qa, qb);
+    ring_steady<P, false>(smem, pb, s, nk - NS, acc, pa, pbf, qa, qb);
+    drain_extra = pb.extra_drain;
+  } else {
+    ring_steady<P, true>(smem, pb, s, nk - NS, acc, pa, pbf, qa, qb);
   }
   // drain: the same steps with the end of the operand in view
   for (; s < nk; ++s) {
@@ -224,7 +243,7 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     pb.read(cur, 1, qa, qb);
     if (more) pb.issue_a(s + 3, dst, last_partial);
     mfma_step<P::SWAP, FM>(acc, pa, pbf);
-    pb.extra(pa);
+    if (drain_extra) pb.extra(pa);
     interleave_step<NM, P::NREAD, 0>();
     if (s + 1 < nk) wait_stage_runtime<P, CPS>(s + 2 < nk, more);
     lds_barrier();
@@ -235,7 +254,7 @@ __device__ __forceinline__ void ring_loop(char* smem, P& pb, int nk, bool tail, 
     pb.read(nxt, 0, pa, pbf);                   // past the last stage: reads a stale buffer, never used
     if (more) pb.issue_b(s + 3, dst, last_partial);
     mfma_step<P::SWAP, FM>(acc, qa, qb);
-    pb.extra(qa);
+    if (drain_extra) pb.extra(qa);
     interleave_step<NM, P::NREAD, 0>();
   }
   lds_barrier();
@@ -246,6 +265,7 @@ template <int BMX>
 struct DxProb {
   static constexpr bool SWAP = true;            // lane ends with 4 consecutive input channels of one row
   static constexpr int FM = BMX / 64, CPA = FM, CPB = 4, NREAD = FM + 8, NPRE = 0, NEXTRA = 0;
+  static constexpr bool PHASED = false;
   __device__ __forceinline__ void extra(const bf16x8_t (&)[FM]) {}
   static constexpr int A_BYTES = BMX * KB * 2, STAGE = A_BYTES + TILE_BYTES;
   RowCopy<FM> ca;
@@ -341,7 +361,11 @@ __device__ __forceinline__ void dx_tile(char* smem, const uint16_t* __restrict__
 }
 
 // ---- dW partial = dY_k[j0:j1]^T X_k[j0:j1] -----------------------------------------------------------
-// DB: the unit also sums the columns of its dY panel over its rows (the layer's bias gradient: db[o] = sum_j dY[j][o]), from
+// DB: the unit also sums the columns of its dY panel (the layer's bias gradient: db[o] = sum_j dY[j][o]) over a part of
+// its rows: the units of one tile row and split all hold the same dY panel and share the work, tile column c of n taking
+// the c-th of n equal runs of the steady stages and the last column the final stages as well (the sums cost vector
+// instructions between the matrix instructions, about a ninth of a stage: left to one tile column they made its units
+// the longest of the grid).  Every unit writes one partial per column of its panel.  The sums come from
 // the dY fragments that are in registers anyway: lane l of fragment i holds 8 consecutive j of column 32 i + l % 32 (j group
 // l / 32), added with four v_dot2_f32_bf16 against (1, 1) into one fp32 sum per fragment row on the vector ALU, which is
 // otherwise idle here.  (Summing on the matrix cores - a fifth product with an operand of ones - needs accumulator
@@ -378,9 +402,12 @@ struct DwProb {
   static constexpr bool SWAP = false;
   static constexpr int FM = 4, CPA = 4, CPB = 4, STAGE = 2 * TILE_BYTES, NEXTRA = 0;
   static constexpr int NREAD = XT ? 12 : 16, NPRE = GATHER ? 2 : 0;   // the 4 id reads pair up into 2 instructions
+  static constexpr bool PHASED = DB;
+  int extra_begin, extra_end;   // steady stages in which this unit sums columns
+  bool extra_drain;             // ... and whether it does in the final stages
   // The two wavefronts that own the same rows of the tile (and so hold the same dY fragments) share the sums: DBH = 0
   // adds up fragments 0 and 1, DBH = 1 fragments 2 and 3.
-  float accdb[DB ? 2 : 1];
+  float accdb[DB ? 2 : 1];         // (one running sum per word of a fragment - independent chains - measured 0.7 % slower)
   __device__ __forceinline__ void init_db(int) {
     if constexpr (DB) {
 #pragma unroll
@@ -462,7 +489,8 @@ struct DwProb {
 template <bool GATHER, bool DB, bool XT, int DBH>
 __device__ __forceinline__ void dw_tile_impl(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                                         const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
-                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp) {
+                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp, int db_part,
+                                        int db_parts) {
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
@@ -471,6 +499,12 @@ __device__ __forceinline__ void dw_tile_impl(char* smem, const uint16_t* __restr
 
   DwProb<GATHER, DB, XT, DBH> pb;
   pb.init_db(lane);
+  {
+    const int steady = max(nk - NS, 0);
+    pb.extra_begin = steady * db_part / db_parts;
+    pb.extra_end = steady * (db_part + 1) / db_parts;
+    pb.extra_drain = db_part == db_parts - 1;
+  }
   pb.wave = wave;
   pb.nrows = nrows;
   pb.a_ld = (uint32_t)Cout * 2u;
@@ -547,18 +581,20 @@ __device__ __forceinline__ void dw_tile_impl(char* smem, const uint16_t* __restr
   }
 }
 
+// db_part of db_parts: this unit's share of the column sums (DB)
 template <bool GATHER, bool DB = false, bool XT = false>
 __device__ __forceinline__ void dw_tile(char* smem, const uint16_t* __restrict__ dY, const int32_t* __restrict__ idx,
                                         const uint16_t* __restrict__ Xk, int Cin, int Cout, int j0, int j1,
-                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp = nullptr) {
+                                        float* __restrict__ part, int m0, int n0, float* __restrict__ dbp = nullptr,
+                                        int db_part = 0, int db_parts = 1) {
   if constexpr (DB) {
     // (wave-uniform: both versions run the same barriers in the same order)
     if (__builtin_amdgcn_readfirstlane(threadIdx.x >> 6) & 1)
-      dw_tile_impl<GATHER, true, XT, 1>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp);
+      dw_tile_impl<GATHER, true, XT, 1>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp, db_part, db_parts);
     else
-      dw_tile_impl<GATHER, true, XT, 0>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp);
+      dw_tile_impl<GATHER, true, XT, 0>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp, db_part, db_parts);
   } else {
-    dw_tile_impl<GATHER, false, XT, 0>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp);
+    dw_tile_impl<GATHER, false, XT, 0>(smem, dY, idx, Xk, Cin, Cout, j0, j1, part, m0, n0, dbp, 0, 1);
   }
 }
 
