@@ -313,9 +313,14 @@ def test_set_option_validates_names_and_values_and_changes_the_plan():
         assert sbp.backward_linear_engine(4 * 197, 4 * 99, 64, 128, sbp.BF16) == ("mfma_large", 3)
         sbp.set_option("splits", None)
         # a forced engine on a size its schedule search cannot serve falls back to equal legal splits (never a
-        # split length of zero): 70000 kept rows need at least 18 splits of 4096
+        # split length of zero): 70000 kept rows need at least 9 splits of at most 7936 rows
         eng, n = sbp.backward_linear_engine(140000, 70000, 64, 128, sbp.BF16)
-        assert eng == "mfma_large" and n >= 18
+        assert eng == "mfma_large" and n >= 9
+        # a split holds at most 7936 kept rows (their row ids sit in LDS): one more row forces a second split
+        sbp.set_option("splits", 1)
+        assert sbp.backward_linear_engine(9000, 7936, 256, 256, sbp.BF16) == ("mfma_large", 1)
+        assert sbp.backward_linear_engine(9000, 7937, 256, 256, sbp.BF16) == ("mfma_large", 2)
+        sbp.set_option("splits", None)
         sbp.set_option("tile", None)
         assert sbp.backward_linear_engine(4 * 197, 4 * 99, 64, 128, sbp.BF16) == auto
         ws_auto = sbp.backward_linear_workspace(12608, 6336, 768, 2304, sbp.BF16)

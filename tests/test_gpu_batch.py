@@ -325,3 +325,12 @@ def test_batched_step_replays_from_a_hip_graph():
                 assert np.array_equal(idxs[i].cpu().numpy(), want_idx[i].cpu().numpy()), rep
                 for a, b in zip(outs[i], want[i]):
                     assert np.array_equal(bits(a), bits(b)), (rep, i)
+
+
+def test_batch_longest_single_split():
+    # 7936 kept rows: the longest dW split (one unit per dW tile runs the whole contraction and writes dW itself); the db
+    # partials of the tile columns are the only thing left to the reduction launch
+    cases = [_layer(32, 0, 8, 62, 520, 264, 2, 151), _layer(32, 0, 8, 62, 264, 520, 2, 152, flags=sbp.FLAG_DY_COMPACT)]
+    assert all(c["idx"].size == 7936 for c in cases)
+    with sbp.options(splits=1):
+        _run(cases)

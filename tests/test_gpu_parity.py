@@ -186,6 +186,19 @@ def test_linear_large_tile_engine_short_contractions(K):
         check_linear(X, W, dY, idx, "bf16")
 
 
+@pytest.mark.parametrize("K", [7936, 7937, 7999])
+@pytest.mark.parametrize("flags", [0, sbp.FLAG_DY_COMPACT])
+def test_linear_large_tile_engine_longest_split(K, flags):
+    # 7936 kept rows are the longest single split (their row ids fill the LDS beside the ring); one more makes two splits
+    g = np.random.default_rng(K)
+    M, Cin, Cout = 9000, 264, 320
+    idx = np.sort(g.choice(M, size=K, replace=False)).astype(np.int32)
+    X = si.normal((M, Cin), 1.0, 15, "bf16"); W = si.normal((Cout, Cin), 0.05, 16, "bf16"); dY = si.normal((M, Cout), 1.0, 17, "bf16")
+    with _env(SBP_TILE="big", SBP_SPLITS=1):
+        assert sbp.backward_linear_engine(M, K, Cin, Cout, sbp.BF16) == ("mfma_large", 1 if K <= 7936 else 2)
+        check_linear(X, W, dY, idx, "bf16", flags=flags)
+
+
 @pytest.mark.parametrize("order", ["0,1,2", "0,2,1", "1,0,2", "1,2,0", "2,0,1", "2,1,0"])
 def test_linear_general_engine_every_segment_order(order):
     # the 128-tile engine lays its three kinds of workgroups (dX tiles, dW units, zero-fill / column-sum blocks) in
