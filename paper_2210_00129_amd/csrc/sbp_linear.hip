@@ -909,7 +909,7 @@ static void launch_linear_big(const LinearPlan& p, LinArgs a, bool want_dx, bool
   allow_big_lds(linear_big_kernel, lds);
   const long long tiles_n = ceil_div(a.Cin, big::BT);
   a.n_zero = want_zero ? big_zero_blocks(a.M) : 0;
-  // with dW wanted, db comes out of the dW units of the first tile column (one slice per split); column-sum blocks
+  // with dW wanted, db comes out of the dW units (one slice per split and tile column); column-sum blocks
   // that read dY_k once more only where db is wanted alone
   a.db_in_dw = a.dbp && want_dw ? 1 : 0;
   const int n_db = a.dbp && !a.db_in_dw ? (int)(ceil_div(a.Cout, 256) * p.db_slices) : 0;
