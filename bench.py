@@ -321,6 +321,10 @@ def timeline_report(job, torch, sbp, wl):
             seg["end_max_us"] = round(float(e[sl].max()), 1)
             cyc = (t[sl, 3] - t[sl, 2]).astype(np.float64)
             seg["shader_mhz_median"] = round(float(np.median(cyc / np.maximum(d[sl], 1e-3))), 0)
+            # the same per XCD that ran the units (every XCD has a clock of its own): [units, median us, median MHz]
+            seg["by_xcd"] = {int(x): [int((sl & (ran_on == x)).sum()), round(float(np.median(d[sl & (ran_on == x)])), 1),
+                                      round(float(np.median(cyc[ran_on[sl] == x] / np.maximum(d[sl & (ran_on == x)], 1e-3))), 0)]
+                             for x in sorted(int(v) for v in set(ran_on[sl]))}
         out["segments"].append(seg)
     out["cu_busy_frac"] = round(float(d[tiles].sum() / (256.0 * e.max())), 3)
     out["cu_busy_frac_tiles_only"] = round(float(d[tiles & (kind <= 2)].sum() / (256.0 * e.max())), 3)
