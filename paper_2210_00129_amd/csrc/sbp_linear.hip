@@ -1162,7 +1162,7 @@ static int batch_jobs(const sbp_linear_layer* L, int n, const BatchLayerChoice* 
     if (l.dW) {
       const int64_t rps = split_rows(l.K, c[i].splits);
       const int64_t nsp = ceil_div(l.K, rps);
-      const int64_t stages = ceil_div(std::min<int64_t>(rps, l.K), big::KB), tiles_m = ceil_div(l.Cout, big::BT);
+      const int64_t stages = ceil_div(std::min<int64_t>(rps, l.K), big::KB);
       // with db wanted every dW unit sums the db columns of its panel in its share (1 / tiles_n) of the stages
       const int64_t db_stages = l.db ? ceil_div(stages, tiles_n) : 0;
       out[nj++] = Job{tiles_w * nsp, kNsFixedBatchDw + kNsStageBatchDw * stages + kNsStageBatchDb * db_stages, i, 1};
